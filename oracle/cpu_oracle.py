@@ -1,0 +1,239 @@
+"""Python face of the CPU oracle (ctypes over oracle/libmorph_oracle.so, plus the
+few numpy-only pieces).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py.  The product package never imports this module and
+this module never imports the product package.
+
+Arrays are numpy, host memory.  fp16 data travels as numpy.float16 (bit pattern
+handed to C as uint16).  Packed words are numpy.uint32 (the GPU side declares
+them int32; the bits are the same).
+
+What is computed (paper Section 4.3, footnote: weight-only INT4; Section 5.2:
+"uniform INT4"; Appendix C: fp16 and W4 GEMMs side by side):
+  quantize_w4      O1  min/max per (group, column) -> fp16 scale (rounded up),
+                       uint4 zero, uint4 codes, 8 per word along N
+  unpack_w4        O2  nibble j of word c  <->  column 8c + j
+  dequant_w4       O3  (q - z) * s, exact in fp32; fp16 form is one RNE rounding
+  linear_w4a16     O4  fp64 sum over ascending k of x[m,k] * D32[k,n]
+  linear_fp16      O5  the same with fp16 weights
+  error_metric     O6  max |y - y_ref| / max |y_ref|
+  stack glue       O7  the elementwise/row-norm steps between the four linears
+                       of a synthetic decoder layer (fp64 numpy)
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmorph_oracle.so")
+_lib = None
+
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _b
+        _b.build(force=True)
+    _lib = ctypes.CDLL(_LIB_PATH)
+    _lib.oracle_quantize_w4.restype = ctypes.c_int
+    _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a, typ):
+    return a.ctypes.data_as(typ)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {a.dtype}")
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().oracle_set_num_threads(ctypes.c_int(int(n)))
+
+
+def fp32_to_fp16(f: np.ndarray) -> np.ndarray:
+    f = _c(f, np.float32)
+    h = np.empty(f.shape, np.uint16)
+    _load().oracle_fp32_to_fp16(_p(f, _f32p), _p(h, _u16p), ctypes.c_int64(f.size))
+    return h.view(np.float16)
+
+
+def fp16_to_fp32(h: np.ndarray) -> np.ndarray:
+    h = _c(h, np.float16)
+    f = np.empty(h.shape, np.float32)
+    _load().oracle_fp16_to_fp32(_p(h.view(np.uint16), _u16p), _p(f, _f32p), ctypes.c_int64(h.size))
+    return f
+
+
+def quantize_w4(W: np.ndarray, G: int = 128):
+    """O1.  W fp32 [K,N] -> (qweight uint32 [K,N/8], scales fp16 [ceil(K/G),N],
+    qzeros uint32 [ceil(K/G),N/8])."""
+    W = _c(W, np.float32)
+    K, N = W.shape
+    NG = (K + G - 1) // G
+    qw = np.empty((K, N // 8), np.uint32)
+    sc = np.empty((NG, N), np.uint16)
+    qz = np.empty((NG, N // 8), np.uint32)
+    rc = _load().oracle_quantize_w4(_p(W, _f32p), K, N, G, _p(qw, _u32p), _p(sc, _u16p), _p(qz, _u32p))
+    if rc != 0:
+        raise ValueError("oracle_quantize_w4: bad shape (need N % 8 == 0, K >= 1, G >= 1)")
+    return qw, sc.view(np.float16), qz
+
+
+def unpack_w4(packed: np.ndarray, N: int) -> np.ndarray:
+    """O2.  packed uint32 [R, N/8] -> codes uint8 [R, N]."""
+    packed = _c(packed, np.uint32)
+    R = packed.shape[0]
+    assert packed.shape[1] * 8 == N
+    out = np.empty((R, N), np.uint8)
+    _load().oracle_unpack_w4(_p(packed, _u32p), R, N, _p(out, _u8p))
+    return out
+
+
+def dequant_w4(qw, sc, qz, G: int = 128, dtype=np.float32) -> np.ndarray:
+    """O3.  -> D [K,N] as float32 (exact) or float16 (one RNE rounding of it)."""
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    K, N = qw.shape[0], qw.shape[1] * 8
+    if dtype == np.float32:
+        D = np.empty((K, N), np.float32)
+        _load().oracle_dequant_w4_f32(_p(qw, _u32p), _p(sc.view(np.uint16), _u16p), _p(qz, _u32p),
+                                      K, N, G, _p(D, _f32p))
+        return D
+    if dtype == np.float16:
+        D = np.empty((K, N), np.uint16)
+        _load().oracle_dequant_w4_f16(_p(qw, _u32p), _p(sc.view(np.uint16), _u16p), _p(qz, _u32p),
+                                      K, N, G, _p(D, _u16p))
+        return D.view(np.float16)
+    raise TypeError("dtype must be float32 or float16")
+
+
+def linear_w4a16(x, qw, sc, qz, G: int = 128) -> np.ndarray:
+    """O4.  x fp16 [M,K] -> y float64 [M,N]."""
+    x = _c(x, np.float16)
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    M, K = x.shape
+    N = qw.shape[1] * 8
+    assert qw.shape[0] == K and sc.shape == ((K + G - 1) // G, N) and qz.shape == (sc.shape[0], N // 8)
+    y = np.empty((M, N), np.float64)
+    _load().oracle_linear_w4a16(_p(x.view(np.uint16), _u16p), _p(qw, _u32p), _p(sc.view(np.uint16), _u16p),
+                                _p(qz, _u32p), M, K, N, G, _p(y, _f64p))
+    return y
+
+
+def linear_fp16(x, w) -> np.ndarray:
+    """O5.  x fp16 [M,K], w fp16 [K,N] -> y float64 [M,N]."""
+    x = _c(x, np.float16)
+    w = _c(w, np.float16)
+    M, K = x.shape
+    assert w.shape[0] == K
+    N = w.shape[1]
+    y = np.empty((M, N), np.float64)
+    _load().oracle_linear_fp16(_p(x.view(np.uint16), _u16p), _p(w.view(np.uint16), _u16p), M, K, N, _p(y, _f64p))
+    return y
+
+
+def linear_w4a16_at(x, qw, sc, qz, rows, cols, G: int = 128) -> np.ndarray:
+    """O4 at sampled output positions: out[p] = y[rows[p], cols[p]]."""
+    x = _c(x, np.float16)
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    rows = np.ascontiguousarray(rows, np.int32)
+    cols = np.ascontiguousarray(cols, np.int32)
+    M, K = x.shape
+    N = qw.shape[1] * 8
+    assert rows.shape == cols.shape and rows.min() >= 0 and rows.max() < M and cols.min() >= 0 and cols.max() < N
+    out = np.empty(rows.shape, np.float64)
+    _load().oracle_linear_w4a16_at(_p(x.view(np.uint16), _u16p), _p(qw, _u32p), _p(sc.view(np.uint16), _u16p),
+                                   _p(qz, _u32p), M, K, N, G, _p(rows, _i32p), _p(cols, _i32p),
+                                   ctypes.c_int64(rows.size), _p(out, _f64p))
+    return out
+
+
+def linear_fp16_at(x, w, rows, cols) -> np.ndarray:
+    """O5 at sampled output positions."""
+    x = _c(x, np.float16)
+    w = _c(w, np.float16)
+    rows = np.ascontiguousarray(rows, np.int32)
+    cols = np.ascontiguousarray(cols, np.int32)
+    M, K = x.shape
+    N = w.shape[1]
+    assert rows.shape == cols.shape and rows.min() >= 0 and rows.max() < M and cols.min() >= 0 and cols.max() < N
+    out = np.empty(rows.shape, np.float64)
+    _load().oracle_linear_fp16_at(_p(x.view(np.uint16), _u16p), _p(w.view(np.uint16), _u16p), M, K, N,
+                                  _p(rows, _i32p), _p(cols, _i32p), ctypes.c_int64(rows.size), _p(out, _f64p))
+    return out
+
+
+def error_metric(y, y_ref) -> dict:
+    """O6.  y: what the GPU produced (fp16, any shape); y_ref float64, not rounded.
+    err = max |y - y_ref| / max |y_ref| over the whole call."""
+    yd = np.asarray(y).astype(np.float64)
+    y_ref = np.asarray(y_ref, np.float64)
+    assert yd.shape == y_ref.shape
+    finite = bool(np.isfinite(yd).all())
+    diff = np.abs(yd - y_ref)
+    denom = float(np.abs(y_ref).max()) if y_ref.size else 0.0
+    if y_ref.size == 0:
+        return {"err": 0.0, "rms": 0.0, "finite": True, "argmax": None, "denom": 0.0}
+    worst = int(np.nanargmax(diff)) if finite else -1
+    err = float(diff.max() / denom) if denom > 0 else float(diff.max())
+    rms = float(np.sqrt(np.mean(diff ** 2)) / denom) if denom > 0 else 0.0
+    return {"err": err if finite else float("inf"), "rms": rms, "finite": finite,
+            "argmax": np.unravel_index(worst, y_ref.shape) if finite else None, "denom": denom}
+
+
+# ---- O7: glue between the four linears of the synthetic layer stack (fp64) ----
+# The stack has no attention; the steps below only keep every activation at unit
+# RMS so that 32 layers can be chained in fp16.  Inputs are what the GPU stored
+# (fp16); results are float64 and are compared with the GPU's fp16 at 2e-3.
+
+RMS_EPS = 1e-6
+
+
+def rms(v: np.ndarray) -> np.ndarray:
+    v = np.asarray(v, np.float64)
+    return v / np.sqrt(np.mean(v * v, axis=-1, keepdims=True) + RMS_EPS)
+
+
+def glue_qkv(qkv: np.ndarray) -> np.ndarray:
+    """[M,3H] -> rms(q + k + v), [M,H]."""
+    qkv = np.asarray(qkv, np.float64)
+    H = qkv.shape[1] // 3
+    return rms(qkv[:, :H] + qkv[:, H:2 * H] + qkv[:, 2 * H:])
+
+
+def glue_residual(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """rms(a + b)."""
+    return rms(np.asarray(a, np.float64) + np.asarray(b, np.float64))
+
+
+def glue_swiglu(gu: np.ndarray) -> np.ndarray:
+    """[M,2F] -> rms(silu(gate) * up), [M,F]."""
+    gu = np.asarray(gu, np.float64)
+    F = gu.shape[1] // 2
+    g, u = gu[:, :F], gu[:, F:]
+    return rms(g / (1.0 + np.exp(-g)) * u)

@@ -1,0 +1,393 @@
+"""Pins for the CPU oracle: every expectation below comes from the mathematics, the
+paper's printed values, exact rational arithmetic or a textbook library routine --
+never from the oracle itself and never from the GPU path.
+
+Pin names (used in the oracle's documentation):
+  P1 round trip within half a step      P2 on-grid exactness
+  P3 brute force with exact rationals   P4 closed forms (ones, one-hot)
+  P5 identity activations               P6 numpy float64 matmul
+  P7 the paper's layer sizes            P8 quantization-noise level (sanity)
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2506_02006_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------- independent helpers (written out here, not imported from oracle/) ----------
+
+def pack_nibbles(codes):
+    """codes: list of rows of ints in [0,15], len % 8 == 0 -> list of rows of python ints.
+    Column 8c + j sits in bits [4j+3 : 4j] of word c."""
+    out = []
+    for row in codes:
+        words = []
+        for c in range(len(row) // 8):
+            w = 0
+            for j in range(8):
+                assert 0 <= row[8 * c + j] <= 15
+                w |= row[8 * c + j] << (4 * j)
+            words.append(w)
+        out.append(words)
+    return out
+
+
+def half_to_fraction(h: np.float16) -> Fraction:
+    return Fraction(float(h))          # float(h) is exact; Fraction(float) is exact
+
+
+# ---------- fp16 conversions against numpy (library routine) ----------
+
+def test_fp16_to_fp32_all_patterns(oracle):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    h = bits.view(np.float16)
+    got = oracle.fp16_to_fp32(h)
+    want = h.astype(np.float32)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+
+
+def test_fp32_to_fp16_matches_numpy_rne(oracle):
+    rng = np.random.default_rng(11)
+    parts = [rng.standard_normal(200000, dtype=np.float32) * s for s in (1e-8, 1e-5, 1e-3, 1.0, 300.0, 7e4)]
+    # every fp16 value, every midpoint between neighbours (ties), and just off the midpoints
+    h = np.arange(0x7C00, dtype=np.uint16).view(np.float16).astype(np.float64)
+    mid = (h[:-1] + h[1:]) / 2
+    parts += [h.astype(np.float32), mid.astype(np.float32),
+              np.nextafter(mid.astype(np.float32), np.float32(np.inf)),
+              np.nextafter(mid.astype(np.float32), np.float32(-np.inf)),
+              np.array([65504.0, 65519.99, 65520.0, 65536.0, 1e9, np.inf, 0.0, -0.0, 2.0 ** -25,
+                        np.nextafter(np.float32(2.0 ** -25), np.float32(1)), 2.0 ** -24, 2.0 ** -14], np.float32)]
+    f = np.concatenate(parts)
+    f = np.concatenate([f, -f])
+    with np.errstate(over="ignore"):
+        want = f.astype(np.float16)
+    got = oracle.fp32_to_fp16(f)
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+
+
+# ---------- O2 unpack: nibble order ----------
+
+def test_unpack_nibble_order(oracle):
+    # word 0x76543210: nibble j holds j -> columns 0..7 read 0..7
+    packed = np.array([[0x76543210, 0xFEDCBA98]], np.uint32)
+    got = oracle.unpack_w4(packed, 16)
+    assert got.tolist() == [list(range(16))]
+    rng = np.random.default_rng(3)
+    codes = rng.integers(0, 16, size=(5, 24))
+    packed = np.array(pack_nibbles(codes.tolist()), np.uint32)
+    assert np.array_equal(oracle.unpack_w4(packed, 24), codes.astype(np.uint8))
+
+
+# ---------- P1 round trip ----------
+
+def _distributions(rng, K, N):
+    yield "gauss", (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    yield "student_t", (rng.standard_t(5.0, (K, N)) * 0.02).astype(np.float32)
+    yield "uniform", rng.uniform(-3, 5, (K, N)).astype(np.float32)
+    yield "positive", rng.uniform(0.5, 2.0, (K, N)).astype(np.float32)
+    yield "negative", (-rng.uniform(0.5, 2.0, (K, N))).astype(np.float32)
+    yield "constant", np.full((K, N), 0.37, np.float32)
+    yield "zero", np.zeros((K, N), np.float32)
+    w = (rng.standard_normal((K, N)) * 1e-7).astype(np.float32)        # below the scale floor
+    yield "tiny", w
+    w = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w[3, :] = 11.0                                                     # one outlier row per group
+    yield "outlier", w
+
+
+@pytest.mark.parametrize("G,K", [(128, 256), (128, 384), (32, 80), (8, 20)])
+def test_p1_round_trip_half_step(oracle, G, K):
+    rng = np.random.default_rng(100 + G + K)
+    N = 24
+    for name, W in _distributions(rng, K, N):
+        qw, sc, qz = oracle.quantize_w4(W, G)
+        q = oracle.unpack_w4(qw, N)
+        z = oracle.unpack_w4(qz, N)
+        assert q.max() <= 15 and z.max() <= 15
+        s = sc.astype(np.float64)
+        assert (s >= 2.0 ** -14).all(), name
+        D = oracle.dequant_w4(qw, sc, qz, G).astype(np.float64)
+        step = np.repeat(s, G, axis=0)[:K]
+        # half a step, with slack for the rounding of the fp32 division only
+        bound = 0.5 * step * (1 + 1e-5)
+        assert (np.abs(W.astype(np.float64) - D) <= bound).all(), name
+        # the scale is the range / 15 rounded UP to fp16: never below, less than one fp16 ulp above
+        for g in range(s.shape[0]):
+            blk = W[g * G:(g + 1) * G].astype(np.float64)
+            rngw = np.maximum(blk.max(0), 0) - np.minimum(blk.min(0), 0)
+            floor = np.maximum(rngw / 15, 2.0 ** -14)
+            assert (s[g] >= floor * (1 - 1e-7)).all(), name
+            assert (s[g] <= floor * (1 + 2.0 ** -10) + 1e-30).all(), name
+
+
+def test_p1_zero_group_is_exactly_zero(oracle):
+    W = np.zeros((128, 8), np.float32)
+    qw, sc, qz = oracle.quantize_w4(W)
+    assert not qw.any() and not qz.any()
+    assert (sc.view(np.uint16) == 0x0400).all()            # the 2^-14 floor
+    assert not oracle.dequant_w4(qw, sc, qz).any()
+
+
+# ---------- P2 on-grid exactness ----------
+
+@pytest.mark.parametrize("G,K,N", [(128, 256, 16), (16, 48, 8), (8, 20, 8)])
+def test_p2_on_grid_exact(oracle, G, K, N):
+    rng = np.random.default_rng(7 * G + K)
+    NG = (K + G - 1) // G
+    s0 = rng.uniform(2.0 ** -10, 4.0, (NG, N)).astype(np.float16)
+    z0 = rng.integers(0, 16, (NG, N))
+    q0 = rng.integers(0, 16, (K, N))
+    for g in range(NG):                                      # each group holds codes 0 and 15
+        k0 = g * G
+        k1 = min(k0 + G, K)
+        assert k1 - k0 >= 2
+        q0[k0] = 0
+        q0[k0 + 1] = 15
+    zz = np.repeat(z0, G, axis=0)[:K]
+    ss = np.repeat(s0.astype(np.float64), G, axis=0)[:K]
+    Wd = (q0 - zz) * ss                                      # exact in float64
+    W = Wd.astype(np.float32)
+    assert np.array_equal(W.astype(np.float64), Wd)          # and exact in float32
+    qw, sc, qz = oracle.quantize_w4(W, G)
+    assert np.array_equal(sc.view(np.uint16), s0.view(np.uint16))
+    assert np.array_equal(oracle.unpack_w4(qz, N), z0.astype(np.uint8))
+    assert np.array_equal(oracle.unpack_w4(qw, N), q0.astype(np.uint8))
+    D = oracle.dequant_w4(qw, sc, qz, G)
+    assert np.array_equal(D.view(np.uint32), W.view(np.uint32))
+    D16 = oracle.dequant_w4(qw, sc, qz, G, np.float16)
+    assert np.array_equal(D16.view(np.uint16), W.astype(np.float16).view(np.uint16))
+
+
+# ---------- P3 brute force with exact rationals ----------
+
+@pytest.mark.parametrize("K,G", [(8, 8), (16, 8), (32, 128), (64, 16), (64, 128), (40, 16)])
+@pytest.mark.parametrize("M", [1, 3, 4])
+def test_p3_brute_force_fractions(oracle, K, G, M):
+    rng = np.random.default_rng(1000 * K + 10 * G + M)
+    N = 16
+    NG = (K + G - 1) // G
+    q = rng.integers(0, 16, (K, N)).tolist()
+    z = rng.integers(0, 16, (NG, N)).tolist()
+    s = rng.uniform(0.001, 2.0, (NG, N)).astype(np.float16)
+    x = rng.integers(-6, 7, (M, K)).astype(np.float16) / np.float16(4)      # small dyadic values
+    qw = np.array(pack_nibbles(q), np.uint32)
+    qz = np.array(pack_nibbles(z), np.uint32)
+    y = oracle.linear_w4a16(x, qw, s, qz, G)
+    D = oracle.dequant_w4(qw, s, qz, G)
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(0)
+            for k in range(K):
+                g = k // G
+                d = (q[k][n] - z[g][n]) * half_to_fraction(s[g, n])
+                assert Fraction(float(D[k, n])) == d                       # O3 is exact
+                acc += half_to_fraction(x[m, k]) * d
+            # exact value is a dyadic rational well inside float64: must match to the last bit
+            assert Fraction(float(y[m, n])) == acc, (m, n)
+    # sampled form agrees with the full one
+    rows = rng.integers(0, M, 20)
+    cols = rng.integers(0, N, 20)
+    assert np.array_equal(oracle.linear_w4a16_at(x, qw, s, qz, rows, cols, G), y[rows, cols])
+
+
+def test_p3_fp16_linear_fractions(oracle):
+    rng = np.random.default_rng(5)
+    M, K, N = 3, 24, 5
+    x = (rng.integers(-8, 9, (M, K)) / 8).astype(np.float16)
+    w = (rng.integers(-64, 65, (K, N)) / 256).astype(np.float16)
+    y = oracle.linear_fp16(x, w)
+    for m in range(M):
+        for n in range(N):
+            acc = sum(half_to_fraction(x[m, k]) * half_to_fraction(w[k, n]) for k in range(K))
+            assert Fraction(float(y[m, n])) == acc
+    rows = np.array([0, 2, 1])
+    cols = np.array([4, 0, 3])
+    assert np.array_equal(oracle.linear_fp16_at(x, w, rows, cols), y[rows, cols])
+
+
+# ---------- P4 closed forms ----------
+
+def test_p4_ones_and_constant_codes(oracle):
+    G, NG, N = 128, 3, 8
+    K = G * NG
+    c = [[3, 9, 15, 0, 7, 7, 1, 12], [5, 5, 2, 15, 0, 8, 14, 3], [0, 15, 6, 6, 9, 1, 2, 11]]
+    z = [[1, 9, 4, 0, 8, 15, 0, 12], [5, 2, 2, 7, 0, 3, 15, 9], [0, 15, 1, 11, 6, 6, 13, 4]]
+    s = np.array([[0.5, 0.25, 1.0, 2.0, 0.125, 0.75, 1.5, 0.0625],
+                  [1.0, 0.5, 0.5, 0.25, 4.0, 0.375, 0.25, 1.0],
+                  [0.25, 2.0, 0.75, 0.5, 1.0, 1.0, 0.125, 3.0]], np.float16)
+    q = [c[k // G] for k in range(K)]
+    qw = np.array(pack_nibbles(q), np.uint32)
+    qz = np.array(pack_nibbles(z), np.uint32)
+    x = np.ones((2, K), np.float16)
+    y = oracle.linear_w4a16(x, qw, s, qz, G)
+    for n in range(N):
+        want = sum(128 * (c[g][n] - z[g][n]) * float(s[g, n]) for g in range(NG))
+        assert y[0, n] == want and y[1, n] == want
+
+
+def test_p4_one_hot_selects_row(oracle):
+    rng = np.random.default_rng(9)
+    K, N, G = 256, 24, 128
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    qw, sc, qz = oracle.quantize_w4(W, G)
+    D = oracle.dequant_w4(qw, sc, qz, G)
+    for k in (0, 1, 127, 128, 200, 255):
+        x = np.zeros((1, K), np.float16)
+        x[0, k] = 1.0
+        assert np.array_equal(oracle.linear_w4a16(x, qw, sc, qz, G)[0], D[k].astype(np.float64))
+    # and the fp16 product selects the fp16 row
+    w16 = W.astype(np.float16)
+    x = np.zeros((2, K), np.float16)
+    x[0, 5] = 2.0
+    x[1, 250] = -1.0
+    y = oracle.linear_fp16(x, w16)
+    assert np.array_equal(y[0], 2.0 * w16[5].astype(np.float64))
+    assert np.array_equal(y[1], -w16[250].astype(np.float64))
+
+
+# ---------- P5 identity activations: Y = D, through the product ----------
+
+def test_p5_identity_gives_dequantized_matrix(oracle):
+    rng = np.random.default_rng(21)
+    K, N = 256, 40
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    qw, sc, qz = oracle.quantize_w4(W)
+    x = np.eye(K, dtype=np.float16)
+    y = oracle.linear_w4a16(x, qw, sc, qz)
+    assert np.array_equal(y, oracle.dequant_w4(qw, sc, qz).astype(np.float64))
+
+
+# ---------- P6 numpy float64 matmul ----------
+
+@pytest.mark.parametrize("M,K,N", [(5, 384, 72), (1, 4096, 64), (33, 256, 264)])
+def test_p6_matches_numpy_matmul(oracle, M, K, N):
+    rng = np.random.default_rng(M * K + N)
+    x = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    w16 = W.astype(np.float16)
+    y = oracle.linear_fp16(x, w16)
+    want = x.astype(np.float64) @ w16.astype(np.float64)
+    assert np.abs(y - want).max() <= 1e-12 * np.abs(want).max()
+    # W4: independent dequantization in numpy from the unpacked codes
+    qw, sc, qz = oracle.quantize_w4(W)
+    q = ((qw[:, :, None] >> (4 * np.arange(8, dtype=np.uint32))) & 15).reshape(K, N).astype(np.int64)
+    z = ((qz[:, :, None] >> (4 * np.arange(8, dtype=np.uint32))) & 15).reshape(-1, N).astype(np.int64)
+    D = (q - np.repeat(z, 128, 0)) * np.repeat(sc.astype(np.float64), 128, 0)
+    y4 = oracle.linear_w4a16(x, qw, sc, qz)
+    want4 = x.astype(np.float64) @ D
+    assert np.abs(y4 - want4).max() <= 1e-12 * np.abs(want4).max()
+    assert np.array_equal(oracle.dequant_w4(qw, sc, qz).astype(np.float64), D)
+    assert np.array_equal(oracle.dequant_w4(qw, sc, qz, 128, np.float16).view(np.uint16),
+                          D.astype(np.float16).view(np.uint16))
+
+
+def test_thread_count_does_not_change_result(oracle):
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((3, 256)).astype(np.float16)
+    W = (rng.standard_normal((256, 1024)) * 0.02).astype(np.float32)
+    qw, sc, qz = oracle.quantize_w4(W)
+    n = oracle.num_threads()
+    y_all = oracle.linear_w4a16(x, qw, sc, qz)
+    oracle.set_num_threads(1)
+    y_one = oracle.linear_w4a16(x, qw, sc, qz)
+    oracle.set_num_threads(n)
+    assert np.array_equal(y_all, y_one)
+
+
+# ---------- P7 the paper's layer sizes ----------
+
+def test_p7_layer_bytes_match_paper():
+    vals = {}
+    with open(os.path.join(GOLDEN, "paper_layer_bytes.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                vals[k] = float(v)
+    shapes = synth.LAYER_SHAPES["llama7b"]
+    fp16 = sum(synth.fp16_bytes(K, N) for K, N in shapes.values())
+    w4 = sum(synth.w4_bytes(K, N) for K, N in shapes.values())
+    assert fp16 == 404_750_336 and w4 == 105_140_224
+    assert round(fp16 / 1e9, 1) == vals["fp16_layer_gb"]
+    assert round(w4 / 1e9, 1) == vals["int4_layer_gb"]
+    saving = 1 - w4 / fp16
+    assert 0.73 < saving <= vals["max_saving_fraction"]
+    # bytes of a record equal the sizes of the arrays the quantizer returns
+    K, N = 256, 64
+    assert synth.w4_bytes(K, N) == K * N // 8 * 4 + (K // 128) * N * 2 + (K // 128) * N // 8 * 4
+
+
+# ---------- P8 noise level (sanity, loose) ----------
+
+def test_p8_quantization_noise_level(oracle):
+    K, N = 1024, 256
+    Wg = synth.weights(90, K, N, dist="normal")
+    Wt = synth.weights(90, K, N, dist="student_t5")
+    out = {}
+    for name, W in (("g", Wg), ("t", Wt)):
+        qw, sc, qz = oracle.quantize_w4(W)
+        D = oracle.dequant_w4(qw, sc, qz)
+        out[name] = float(np.sqrt(np.mean((D - W) ** 2)) / W.std())
+    assert 0.075 < out["g"] < 0.125          # range ~5.2 sigma / 15 steps -> ~0.10 sigma
+    assert out["t"] > out["g"]               # heavy tails widen the groups' ranges
+
+
+# ---------- O6 metric and O7 glue ----------
+
+def test_o6_error_metric(oracle):
+    y_ref = np.array([[1.0, -4.0], [2.0, 0.5]])
+    y = np.array([[1.0, -4.0], [2.25, 0.5]], np.float16)
+    r = oracle.error_metric(y, y_ref)
+    assert r["err"] == 0.25 / 4.0 and r["argmax"] == (1, 0) and r["finite"]
+    y[0, 0] = np.inf
+    assert oracle.error_metric(y, y_ref)["err"] == float("inf")
+
+
+def test_o7_glue_closed_forms(oracle):
+    rng = np.random.default_rng(4)
+    v = rng.standard_normal((3, 64)) * 7
+    r = oracle.rms(v)
+    assert np.allclose(np.mean(r * r, axis=1), 1.0, rtol=1e-6)
+    assert np.allclose(r * np.sqrt(np.mean(v * v, axis=1, keepdims=True) + 1e-6), v)
+    qkv = rng.standard_normal((2, 12))
+    assert np.allclose(oracle.glue_qkv(qkv), oracle.rms(qkv[:, :4] + qkv[:, 4:8] + qkv[:, 8:]))
+    gu = np.array([[0.0, 2.0, 5.0, 3.0]])                       # gate = [0, 2], up = [5, 3]
+    want = np.array([[0.0, 2.0 / (1 + np.exp(-2.0)) * 3.0]])
+    assert np.allclose(oracle.glue_swiglu(gu), oracle.rms(want))
+    a = rng.standard_normal((2, 8))
+    assert np.allclose(oracle.glue_residual(a, -a), 0.0)
+
+
+# ---------- planted mistakes: each must be caught by a pin above ----------
+
+def test_pins_catch_planted_mistakes(oracle):
+    """A wrong nibble order, a dropped zero point, a wrong group index and a transposed
+    weight are each visible to the exact checks used above (run here on numpy mutants
+    of an independent dequantization, so no pin passes by accident)."""
+    rng = np.random.default_rng(77)
+    K, N, G = 256, 16, 128
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    qw, sc, qz = oracle.quantize_w4(W, G)
+    D = oracle.dequant_w4(qw, sc, qz, G).astype(np.float64)
+    sh = 4 * np.arange(8, dtype=np.uint32)
+    q = ((qw[:, :, None] >> sh) & 15).reshape(K, N).astype(np.int64)
+    z = ((qz[:, :, None] >> sh) & 15).reshape(-1, N).astype(np.int64)
+    s = sc.astype(np.float64)
+    good = (q - np.repeat(z, G, 0)) * np.repeat(s, G, 0)
+    assert np.array_equal(good, D)
+    q_rev = ((qw[:, :, None] >> sh[::-1]) & 15).reshape(K, N).astype(np.int64)
+    mutants = {
+        "reversed nibbles": (q_rev - np.repeat(z, G, 0)) * np.repeat(s, G, 0),
+        "zero point dropped": q * np.repeat(s, G, 0),
+        "zero point sign": (q + np.repeat(z, G, 0)) * np.repeat(s, G, 0),
+        "group index stuck at 0": (q - z[0]) * s[0],
+    }
+    for name, Dm in mutants.items():
+        assert not np.array_equal(Dm, D), name
+        assert np.abs(Dm - W).max() > 0.5 * s.max() * 1.01, name      # breaks P1
