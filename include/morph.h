@@ -1,0 +1,155 @@
+/*
+ * libmorph -- fp16 and weight-only 4-bit (W4A16) linear layers for MI355X (gfx950).
+ *
+ * The method served: a transformer whose decoder layers can be swapped at run time between a
+ * full-precision fp16 variant and a 4-bit weight-only variant written over the same device
+ * addresses, so that layers of both kinds coexist inside one forward pass and a layer's kind may
+ * change between two decode steps (paper Section 4.3 "Runtime Layer Swapping"; Appendix C
+ * "Implementation Details": FP16 / W8 / W4 variants, GEMM kernels precompiled, weights
+ * overwritten in place without pointer remapping).  This library is the compute under that
+ * mechanism: the four linear projections of a layer (QKV, O, gate/up, down) in either kind.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device unless marked "host".
+ *     The caller owns every buffer; the library never allocates, frees or keeps a pointer
+ *     between calls (a layer's weights may be overwritten in place at any time between calls).
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = default stream)
+ *     and never synchronise the host.
+ *   - Arguments are validated on the host before anything is launched; on a non-zero return
+ *     nothing was launched and the outputs are untouched.
+ *   - Matrices are row-major.  x, y, w must not overlap.  No bias term.
+ *   - fp16 = IEEE binary16.  Accumulation is fp32; outputs are rounded once to fp16.
+ *   - Built ahead of time for gfx950 only; nothing is compiled at run time.
+ *
+ * The 4-bit layer record (the "uniform INT4" weight-only flavour, paper Section 5.2
+ * "Effectiveness Across Quantization Algorithms"; footnote of Section 4.3: INT# = weights only):
+ *   qweight int32 [K, N/8]    bits [4j+3:4j] of word c in row k hold the code q of column 8c+j
+ *   scales  fp16  [K/128, N]  step size s of (group g = k/128, column n)
+ *   qzeros  int32 [K/128, N/8] zero points z, packed like qweight
+ *   weight value = (q - z) * s, q and z in 0..15.
+ */
+#ifndef MORPH_H
+#define MORPH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MORPH_OK = 0,
+    MORPH_ERR_NULL = 1,        /* a required pointer is NULL                                     */
+    MORPH_ERR_SHAPE = 2,       /* M < 1, K % 128 != 0, N % 8 != 0, group_size != 128, bad enum   */
+    MORPH_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned                               */
+    MORPH_ERR_WORKSPACE = 4,   /* workspace NULL or smaller than morph_workspace_bytes()         */
+    MORPH_ERR_UNSUPPORTED = 5, /* a size beyond what the kernels index (see each entry point)    */
+    MORPH_ERR_DEVICE = 6       /* the HIP runtime reported an error at launch                    */
+} morph_status;
+
+enum { MORPH_KIND_FP16 = 0, MORPH_KIND_W4A16 = 1 };
+enum { MORPH_DTYPE_F32 = 0, MORPH_DTYPE_F16 = 1 };
+enum { MORPH_GROUP_SIZE = 128 };
+
+/* ---- y = x * W with fp16 weights (the full-precision layer variant; Section 4.3, Appendix C) ----
+ * x [M,K] fp16, w [K,N] fp16, y [M,N] fp16.  K % 128 == 0, N % 8 == 0, M >= 1.
+ * M <= 64 takes the bandwidth-bound decode kernel (split along K; needs the workspace),
+ * larger M the LDS-tiled MFMA kernel (workspace unused).
+ * workspace: morph_workspace_bytes(MORPH_KIND_FP16, M, K, N) bytes prepared once with
+ * morph_workspace_init(); may be NULL when that size is 0.  One workspace must not be used by
+ * two calls that can run concurrently (different streams).
+ * Sizes: every array must be smaller than 4 GiB (32-bit byte offsets), else UNSUPPORTED. */
+int morph_linear_fp16(const void* x, const void* w, void* y, int M, int K, int N,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- y = x * dequant(W4) (the swapped-in 4-bit variant; Section 4.3, Appendix C) ----
+ * x [M,K] fp16; qweight/scales/qzeros as described above; y [M,N] fp16; group_size must be 128.
+ * The weights are unpacked and dequantized in registers (decode) or into LDS tiles (prefill)
+ * inside the GEMM kernel; no dequantized copy is ever written to memory.
+ * Same M dispatch, workspace and size rules as morph_linear_fp16 (kind MORPH_KIND_W4A16). */
+int morph_linear_w4a16(const void* x, const int32_t* qweight, const void* scales,
+                       const int32_t* qzeros, void* y, int M, int K, int N, int group_size,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- produce the 4-bit record of one weight matrix (the variant that gets swapped in) ----
+ * w [K,N] in w_dtype (MORPH_DTYPE_F32 or MORPH_DTYPE_F16).  Per (group g, column n):
+ *   lo = min(0, min w), hi = max(0, max w) over the group's 128 rows;
+ *   s  = (hi - lo) / 15 rounded UP to fp16, at least 2^-14;   z = clamp(rint(-lo / s), 0, 15);
+ *   q  = clamp(rint(w / s) + z, 0, 15)   (IEEE fp32 division, round half to even).
+ * Writes qweight, scales, qzeros (every word of them).  Deterministic: one exact result. */
+int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* scales,
+                         int32_t* qzeros, int K, int N, int group_size, void* stream);
+
+/* ---- verification export: the dequantized matrix itself ----
+ * out [K,N] = (q - z) * s, as fp32 (exact: at most 15 significant bits) or as fp16 (that value
+ * rounded once, to nearest even).  Not on the serving path. */
+int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_t* qzeros,
+                        void* out, int out_dtype, int K, int N, int group_size, void* stream);
+
+/* Bytes of workspace a linear call of this kind and shape needs (0 = none).  Host only. */
+size_t morph_workspace_bytes(int kind, int M, int K, int N);
+
+/* Zero-fill a workspace once after allocating it (fill kernel on `stream`).  Every linear call
+ * expects its arrival counters at zero and leaves them at zero. */
+int morph_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- elementwise + row-norm steps between the linears of the synthetic layer stack ----
+ * rms(v) = v / sqrt(mean_row(v^2) + 1e-6), computed in fp32, stored as fp16.
+ *   MORPH_GLUE_QKV      a [M,3H]           -> out [M,H] = rms(a[:, :H] + a[:, H:2H] + a[:, 2H:])
+ *   MORPH_GLUE_RESIDUAL a [M,H], b [M,H]   -> out [M,H] = rms(a + b)
+ *   MORPH_GLUE_SWIGLU   a [M,2H]           -> out [M,H] = rms(silu(a[:, :H]) * a[:, H:])
+ *   MORPH_GLUE_RMS      a [M,H]            -> out [M,H] = rms(a)
+ * These stand where attention and the MLP activation sit in a real layer; they only keep the
+ * activations at unit scale so that a 32-layer chain of linears can be driven in fp16.
+ * H % 8 == 0, H <= 65536.  b is ignored except for RESIDUAL.  out may not alias a or b. */
+enum { MORPH_GLUE_QKV = 0, MORPH_GLUE_RESIDUAL = 1, MORPH_GLUE_SWIGLU = 2, MORPH_GLUE_RMS = 3 };
+int morph_glue(int op, const void* a, const void* b, void* out, int M, int H, void* stream);
+
+/* ---- one decode step through a stack of layers of mixed kinds (Sections 3 and 4.1: quantized
+ * and full-precision layers coexist; Section 4.3: kernels of every precision are ready) ----
+ * Each layer: qkv = L_qkv(x); a = GLUE_QKV(qkv); o = L_o(a); r = GLUE_RESIDUAL(x, o);
+ *             gu = L_gate_up(r); m = GLUE_SWIGLU(gu); d = L_down(m); x' = GLUE_RESIDUAL(r, d).
+ * `layers` is a HOST array of n_layers records; each linear names its kind and device pointers
+ * (for MORPH_KIND_FP16 only `w` is used).  hidden = K of qkv; inter = K of down.
+ * x_io [M,hidden] fp16 is read as the input and overwritten with the output.
+ * scratch: device buffer of morph_stack_scratch_bytes() bytes (activations between steps).
+ * If tap_layer is in [0, n_layers) the inputs and outputs of that layer's four linears are also
+ * copied, in order (x, qkv, a, o, r, gu, m, d), to `tap` (device, morph_stack_tap_bytes() bytes),
+ * for checking each linear against a reference on its actual input. */
+typedef struct {
+    int         kind;     /* MORPH_KIND_FP16 or MORPH_KIND_W4A16 */
+    const void* w;        /* fp16 [K,N]  or  int32 qweight [K,N/8] */
+    const void* scales;   /* fp16 [K/128,N]   (W4A16 only) */
+    const void* qzeros;   /* int32 [K/128,N/8] (W4A16 only) */
+} morph_linear_desc;
+
+typedef struct {
+    morph_linear_desc qkv, o, gate_up, down;
+} morph_layer_desc;
+
+size_t morph_stack_scratch_bytes(int M, int hidden, int inter);
+size_t morph_stack_tap_bytes(int M, int hidden, int inter);
+int morph_stack_forward(const morph_layer_desc* layers /* host */, int n_layers, void* x_io,
+                        int M, int hidden, int inter, void* scratch, size_t scratch_bytes,
+                        void* workspace, size_t workspace_bytes, int tap_layer, void* tap,
+                        void* stream);
+
+/* Launch every kernel variant once on tiny internal dummies so that code objects are loaded
+ * before serving starts (Section 4.3: kernels are precompiled ahead of time; Appendix C: with
+ * dummy data).  `dummy` is a caller-provided device buffer of at least morph_warmup_bytes(). */
+size_t morph_warmup_bytes(void);
+int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
+
+/* Override a kernel-selection heuristic (0 restores the default).  For benchmarking sweeps only;
+ * defaults are chosen from the shape.  Keys: 0 = K-split factor of the decode kernels,
+ * 1 = target workgroup count of the decode kernels, 2 = prefill tile (1 = 256x256, 2 = 128x128).
+ * A change alters morph_workspace_bytes(); size the workspace after setting. */
+int morph_set_tuning(int key, int value);
+
+const char* morph_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MORPH_H */

@@ -1,0 +1,262 @@
+"""ctypes binding of libmorph.so (include/morph.h).  Argument marshalling only: every function
+takes torch tensors that already live on the GPU, checks dtype / contiguity / device, and hands
+raw device pointers and sizes to the C ABI on torch's current stream.  There is no CPU path: if
+the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmorph.so")
+
+KIND_FP16, KIND_W4A16 = 0, 1
+DTYPE_F32, DTYPE_F16 = 0, 1
+GROUP = 128
+GLUE_QKV, GLUE_RESIDUAL, GLUE_SWIGLU, GLUE_RMS = 0, 1, 2, 3
+TUNE_DECODE_SPLIT, TUNE_DECODE_WGS, TUNE_PREFILL_TILE = 0, 1, 2
+
+EXPORTS = [
+    "morph_linear_fp16", "morph_linear_w4a16", "morph_quantize_layer", "morph_dequantize_w4",
+    "morph_workspace_bytes", "morph_workspace_init", "morph_glue", "morph_stack_scratch_bytes",
+    "morph_stack_tap_bytes", "morph_stack_forward", "morph_warmup_bytes", "morph_warmup",
+    "morph_set_tuning", "morph_status_string",
+]
+
+
+class MorphError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+
+
+class LinearDesc(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("w", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("qzeros", ctypes.c_void_p)]
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [("qkv", LinearDesc), ("o", LinearDesc), ("gate_up", LinearDesc), ("down", LinearDesc)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libmorph.so (built by `python -m paper_2506_02006_amd.build`).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} not built; run `python -m paper_2506_02006_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.morph_linear_fp16.argtypes = [vp, vp, vp, i, i, i, vp, sz, vp]
+    L.morph_linear_w4a16.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.morph_quantize_layer.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
+    L.morph_dequantize_w4.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
+    L.morph_workspace_bytes.argtypes = [i, i, i, i]
+    L.morph_workspace_bytes.restype = sz
+    L.morph_workspace_init.argtypes = [vp, sz, vp]
+    L.morph_glue.argtypes = [i, vp, vp, vp, i, i, vp]
+    L.morph_stack_scratch_bytes.argtypes = [i, i, i]
+    L.morph_stack_scratch_bytes.restype = sz
+    L.morph_stack_tap_bytes.argtypes = [i, i, i]
+    L.morph_stack_tap_bytes.restype = sz
+    L.morph_stack_forward.argtypes = [ctypes.POINTER(LayerDesc), i, vp, i, i, i, vp, sz, vp, sz, i, vp, vp]
+    L.morph_warmup_bytes.argtypes = []
+    L.morph_warmup_bytes.restype = sz
+    L.morph_warmup.argtypes = [vp, sz, vp]
+    L.morph_set_tuning.argtypes = [i, i]
+    L.morph_status_string.argtypes = [i]
+    L.morph_status_string.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("morph_workspace_bytes", "morph_stack_scratch_bytes", "morph_stack_tap_bytes",
+                        "morph_warmup_bytes", "morph_status_string"):
+            getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().morph_status_string(int(status)).decode()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MorphError(rc, what)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def workspace_bytes(kind: int, M: int, K: int, N: int) -> int:
+    return int(lib().morph_workspace_bytes(kind, M, K, N))
+
+
+def new_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """Allocate and prepare a workspace of at least nbytes (uint8 tensor)."""
+    ws = torch.empty(max(int(nbytes), 4096), dtype=torch.uint8, device=device)
+    _check(lib().morph_workspace_init(ws.data_ptr(), ws.numel(), _stream()), "morph_workspace_init")
+    return ws
+
+
+def _ws_args(ws):
+    if ws is None:
+        return None, 0
+    return ws.data_ptr(), ws.numel()
+
+
+def linear_fp16(x: torch.Tensor, w: torch.Tensor, ws=None, out=None) -> torch.Tensor:
+    M, K = x.shape
+    K2, N = w.shape
+    assert K == K2
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    wp, wb = _ws_args(ws)
+    _check(lib().morph_linear_fp16(_dev(x, torch.float16, "x"), _dev(w, torch.float16, "w"),
+                                   _dev(y, torch.float16, "y"), M, K, N, wp, wb, _stream()), "morph_linear_fp16")
+    return y
+
+
+def linear_w4a16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:
+    M, K = x.shape
+    N = scales.shape[1]
+    assert qweight.shape == (K, N // 8), (qweight.shape, K, N)
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    wp, wb = _ws_args(ws)
+    _check(lib().morph_linear_w4a16(_dev(x, torch.float16, "x"), _dev(qweight, torch.int32, "qweight"),
+                                    _dev(scales, torch.float16, "scales"), _dev(qzeros, torch.int32, "qzeros"),
+                                    _dev(y, torch.float16, "y"), M, K, N, group_size, wp, wb, _stream()),
+           "morph_linear_w4a16")
+    return y
+
+
+def quantize_layer(w: torch.Tensor, group_size: int = GROUP):
+    """w [K,N] float32 or float16 on the GPU -> (qweight int32 [K,N/8], scales fp16 [K/128,N], qzeros int32 [K/128,N/8])."""
+    K, N = w.shape
+    if w.dtype == torch.float32:
+        dt = DTYPE_F32
+    elif w.dtype == torch.float16:
+        dt = DTYPE_F16
+    else:
+        raise TypeError("w must be float32 or float16")
+    qw = torch.empty((K, N // 8), dtype=torch.int32, device=w.device)
+    sc = torch.empty((K // GROUP, N), dtype=torch.float16, device=w.device)
+    qz = torch.empty((K // GROUP, N // 8), dtype=torch.int32, device=w.device)
+    _check(lib().morph_quantize_layer(_dev(w, w.dtype, "w"), dt, qw.data_ptr(), sc.data_ptr(), qz.data_ptr(),
+                                      K, N, group_size, _stream()), "morph_quantize_layer")
+    return qw, sc, qz
+
+
+def dequantize_w4(qweight, scales, qzeros, dtype=torch.float32, group_size: int = GROUP) -> torch.Tensor:
+    K = qweight.shape[0]
+    N = scales.shape[1]
+    out = torch.empty((K, N), dtype=dtype, device=qweight.device)
+    dt = DTYPE_F32 if dtype == torch.float32 else DTYPE_F16
+    _check(lib().morph_dequantize_w4(_dev(qweight, torch.int32, "qweight"), _dev(scales, torch.float16, "scales"),
+                                     _dev(qzeros, torch.int32, "qzeros"), _dev(out, dtype, "out"), dt, K, N,
+                                     group_size, _stream()), "morph_dequantize_w4")
+    return out
+
+
+def glue(op: int, a: torch.Tensor, b=None, H=None) -> torch.Tensor:
+    M = a.shape[0]
+    if H is None:
+        H = a.shape[1] // (3 if op == GLUE_QKV else 2 if op == GLUE_SWIGLU else 1)
+    out = torch.empty((M, H), dtype=torch.float16, device=a.device)
+    bp = _dev(b, torch.float16, "b") if b is not None else None
+    _check(lib().morph_glue(op, _dev(a, torch.float16, "a"), bp, out.data_ptr(), M, H, _stream()), "morph_glue")
+    return out
+
+
+def set_tuning(key: int, value: int):
+    _check(lib().morph_set_tuning(key, value), "morph_set_tuning")
+
+
+def warmup(device="cuda"):
+    n = int(lib().morph_warmup_bytes())
+    buf = torch.empty(n, dtype=torch.uint8, device=device)
+    _check(lib().morph_warmup(buf.data_ptr(), n, _stream()), "morph_warmup")
+    torch.cuda.synchronize()
+
+
+class LayerStack:
+    """Host-side record of a stack of layers of mixed kinds plus the buffers one decode step needs.
+    Holds references to the weight tensors so they outlive the raw pointers."""
+
+    def __init__(self, hidden: int, inter: int, M: int, device="cuda"):
+        self.hidden, self.inter, self.M = hidden, inter, M
+        self.device = device
+        self.layers = []      # list of dict name -> ("fp16", w) | ("w4", qw, sc, qz)
+        self._desc = None
+        self.scratch = torch.empty(int(lib().morph_stack_scratch_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
+        self.tap = torch.empty(int(lib().morph_stack_tap_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
+        self.ws = None
+
+    def add_layer(self, linears: dict):
+        self.layers.append(linears)
+        self._desc = None
+
+    def set_layer(self, idx: int, linears: dict):
+        self.layers[idx] = linears
+        self._desc = None
+
+    def _shapes(self):
+        h, i = self.hidden, self.inter
+        return {"qkv": (h, 3 * h), "o": (h, h), "gate_up": (h, 2 * i), "down": (i, h)}
+
+    def _build(self):
+        arr = (LayerDesc * len(self.layers))()
+        need = 0
+        for li, layer in enumerate(self.layers):
+            for name, (K, N) in self._shapes().items():
+                rec = layer[name]
+                d = getattr(arr[li], name)
+                if rec[0] == "fp16":
+                    assert rec[1].shape == (K, N)
+                    d.kind, d.w, d.scales, d.qzeros = KIND_FP16, _dev(rec[1], torch.float16, name), None, None
+                else:
+                    assert rec[1].shape == (K, N // 8)
+                    d.kind = KIND_W4A16
+                    d.w = _dev(rec[1], torch.int32, name)
+                    d.scales = _dev(rec[2], torch.float16, name)
+                    d.qzeros = _dev(rec[3], torch.int32, name)
+                need = max(need, workspace_bytes(d.kind, self.M, K, N))
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = new_workspace(need, self.device)
+        self._desc = arr
+
+    def forward(self, x_io: torch.Tensor, tap_layer: int = -1):
+        """One decode step in place on x_io [M,hidden] fp16."""
+        if self._desc is None:
+            self._build()
+        assert x_io.shape == (self.M, self.hidden)
+        _check(lib().morph_stack_forward(self._desc, len(self.layers), _dev(x_io, torch.float16, "x_io"), self.M,
+                                         self.hidden, self.inter, self.scratch.data_ptr(), self.scratch.numel(),
+                                         self.ws.data_ptr(), self.ws.numel(), tap_layer, self.tap.data_ptr(),
+                                         _stream()), "morph_stack_forward")
+        return x_io
+
+    def tapped(self):
+        """Views into the tap buffer: x, qkv, a, o, r, gu, m, d as fp16 tensors (valid after a forward with tap_layer set)."""
+        M, h, i = self.M, self.hidden, self.inter
+        sizes = [("x", h), ("qkv", 3 * h), ("a", h), ("o", h), ("r", h), ("gu", 2 * i), ("m", i), ("d", h)]
+        out, off = {}, 0
+        buf = self.tap
+        for name, cols in sizes:
+            nb = M * cols * 2
+            out[name] = buf[off:off + nb].view(torch.float16).view(M, cols)
+            off += (nb + 255) & ~255
+        return out

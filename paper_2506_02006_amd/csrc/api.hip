@@ -1,0 +1,338 @@
+// The C ABI of include/morph.h: argument validation on the host, kernel selection by shape,
+// launches on the caller's stream.  Nothing here allocates, synchronises or remembers a pointer.
+#include "../../include/morph.h"
+#include "kernels.h"
+
+#include <atomic>
+
+namespace morph {
+
+static std::atomic<int> g_tuning[TUNE_COUNT];
+
+int tuning_get(int key) { return (key >= 0 && key < TUNE_COUNT) ? g_tuning[key].load(std::memory_order_relaxed) : 0; }
+void tuning_set(int key, int value)
+{
+    if (key >= 0 && key < TUNE_COUNT) g_tuning[key].store(value, std::memory_order_relaxed);
+}
+
+namespace {
+
+constexpr int    kDecodeMaxM = 64;
+constexpr size_t k4G         = (size_t)1 << 32;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int M, int K, int N)
+{
+    if (M < 1 || K < MORPH_GROUP_SIZE || N < 8) return MORPH_ERR_SHAPE;
+    if (K % MORPH_GROUP_SIZE != 0 || N % 8 != 0) return MORPH_ERR_SHAPE;
+    return MORPH_OK;
+}
+
+// every array is indexed with 32-bit byte offsets
+int check_sizes(int kind, int M, int K, int N)
+{
+    const size_t m = (size_t)M, k = (size_t)K, n = (size_t)N;
+    if (m * k * 2 >= k4G || m * n * 2 >= k4G) return MORPH_ERR_UNSUPPORTED;
+    if (kind == MORPH_KIND_FP16) {
+        if (k * n * 2 >= k4G) return MORPH_ERR_UNSUPPORTED;
+    } else {
+        if (k * n / 2 >= k4G) return MORPH_ERR_UNSUPPORTED;
+    }
+    return MORPH_OK;
+}
+
+size_t workspace_need(int kind, int M, int K, int N)
+{
+    if (M > kDecodeMaxM) return 0;
+    const DecodePlan pl = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
+    return pl.S > 1 ? kCounterBytes + pl.partial_bytes : 0;
+}
+
+int run_linear(int kind, const void* x, const void* w, const void* scales, const void* qzeros, void* y,
+               int M, int K, int N, void* workspace, size_t workspace_bytes, hipStream_t st)
+{
+    hipError_t e;
+    if (M <= kDecodeMaxM) {
+        const DecodePlan pl = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
+        if (pl.tiles > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
+        DecodeArgs a;
+        a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
+        a.M = M; a.K = K; a.N = N; a.S = pl.S;
+        a.partial = nullptr; a.counters = nullptr;
+        if (pl.S > 1) {
+            if (!workspace || workspace_bytes < kCounterBytes + pl.partial_bytes) return MORPH_ERR_WORKSPACE;
+            if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
+            a.counters = reinterpret_cast<int*>(workspace);
+            a.partial  = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+        }
+        e = launch_decode(kind == MORPH_KIND_W4A16, a, st);
+    } else {
+        GemmArgs g;
+        g.x = x; g.w = w; g.scales = scales; g.qzeros = qzeros; g.y = y; g.M = M; g.K = K; g.N = N;
+        e = launch_prefill(kind == MORPH_KIND_W4A16, g, st);
+    }
+    return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+int validate_linear(int kind, const void* x, const void* w, const void* scales, const void* qzeros,
+                    const void* y, int M, int K, int N)
+{
+    if (!x || !w || !y) return MORPH_ERR_NULL;
+    if (kind == MORPH_KIND_W4A16 && (!scales || !qzeros)) return MORPH_ERR_NULL;
+    if (int rc = check_shape(M, K, N)) return rc;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MORPH_ERR_ALIGN;
+    if (kind == MORPH_KIND_W4A16 && (!aligned16(scales) || !aligned16(qzeros))) return MORPH_ERR_ALIGN;
+    return check_sizes(kind, M, K, N);
+}
+
+}  // namespace
+}  // namespace morph
+
+using namespace morph;
+
+extern "C" {
+
+int morph_linear_fp16(const void* x, const void* w, void* y, int M, int K, int N, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    if (int rc = validate_linear(MORPH_KIND_FP16, x, w, nullptr, nullptr, y, M, K, N)) return rc;
+    return run_linear(MORPH_KIND_FP16, x, w, nullptr, nullptr, y, M, K, N, workspace, workspace_bytes,
+                      (hipStream_t)stream);
+}
+
+int morph_linear_w4a16(const void* x, const int32_t* qweight, const void* scales, const int32_t* qzeros,
+                       void* y, int M, int K, int N, int group_size, void* workspace,
+                       size_t workspace_bytes, void* stream)
+{
+    if (group_size != MORPH_GROUP_SIZE) return (x && qweight && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
+    if (int rc = validate_linear(MORPH_KIND_W4A16, x, qweight, scales, qzeros, y, M, K, N)) return rc;
+    return run_linear(MORPH_KIND_W4A16, x, qweight, scales, qzeros, y, M, K, N, workspace, workspace_bytes,
+                      (hipStream_t)stream);
+}
+
+int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
+                         int K, int N, int group_size, void* stream)
+{
+    if (!w || !qweight || !scales || !qzeros) return MORPH_ERR_NULL;
+    if (group_size != MORPH_GROUP_SIZE) return MORPH_ERR_SHAPE;
+    if (w_dtype != MORPH_DTYPE_F32 && w_dtype != MORPH_DTYPE_F16) return MORPH_ERR_SHAPE;
+    if (int rc = check_shape(1, K, N)) return rc;
+    if (!aligned16(w) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros)) return MORPH_ERR_ALIGN;
+    if (K / MORPH_GROUP_SIZE > 65535) return MORPH_ERR_UNSUPPORTED;
+    hipError_t e = launch_quantize_w4(w, w_dtype == MORPH_DTYPE_F16, reinterpret_cast<uint32_t*>(qweight), scales,
+                                      reinterpret_cast<uint32_t*>(qzeros), K, N, (hipStream_t)stream);
+    return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_t* qzeros, void* out,
+                        int out_dtype, int K, int N, int group_size, void* stream)
+{
+    if (!qweight || !scales || !qzeros || !out) return MORPH_ERR_NULL;
+    if (group_size != MORPH_GROUP_SIZE) return MORPH_ERR_SHAPE;
+    if (out_dtype != MORPH_DTYPE_F32 && out_dtype != MORPH_DTYPE_F16) return MORPH_ERR_SHAPE;
+    if (int rc = check_shape(1, K, N)) return rc;
+    if (!aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(out)) return MORPH_ERR_ALIGN;
+    if (K > 65535) return MORPH_ERR_UNSUPPORTED;
+    hipError_t e = launch_dequantize_w4(reinterpret_cast<const uint32_t*>(qweight), scales,
+                                        reinterpret_cast<const uint32_t*>(qzeros), out,
+                                        out_dtype == MORPH_DTYPE_F16, K, N, (hipStream_t)stream);
+    return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+size_t morph_workspace_bytes(int kind, int M, int K, int N)
+{
+    if (kind != MORPH_KIND_FP16 && kind != MORPH_KIND_W4A16) return 0;
+    if (check_shape(M, K, N) != MORPH_OK) return 0;
+    return workspace_need(kind, M, K, N);
+}
+
+int morph_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (workspace_bytes == 0) return MORPH_OK;
+    if (!workspace) return MORPH_ERR_NULL;
+    if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
+    // only the arrival counters at the head need to start at zero
+    size_t bytes = workspace_bytes < kCounterBytes ? (workspace_bytes & ~(size_t)15) : kCounterBytes;
+    hipError_t e = launch_fill_zero(workspace, bytes, (hipStream_t)stream);
+    return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+int morph_glue(int op, const void* a, const void* b, void* out, int M, int H, void* stream)
+{
+    if (op < MORPH_GLUE_QKV || op > MORPH_GLUE_RMS) return MORPH_ERR_SHAPE;
+    if (!a || !out || (op == MORPH_GLUE_RESIDUAL && !b)) return MORPH_ERR_NULL;
+    if (M < 1 || H < 8 || H % 8 != 0 || H > 65536) return MORPH_ERR_SHAPE;
+    if (!aligned16(a) || !aligned16(out) || (op == MORPH_GLUE_RESIDUAL && !aligned16(b))) return MORPH_ERR_ALIGN;
+    hipError_t e = launch_glue(op, a, b, out, M, H, (hipStream_t)stream);
+    return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+// ---- layer stack ----
+// scratch layout (fp16, each piece rounded up to 256 bytes):
+//   qkv [M,3h] | a [M,h] | o [M,h] | r [M,h] | gu [M,2i] | m [M,i] | d [M,h] | xn [M,h]
+namespace {
+struct StackLayout {
+    size_t qkv, a, o, r, gu, m, d, xn, total;
+};
+inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+StackLayout stack_layout(int M, int h, int i)
+{
+    StackLayout L;
+    size_t off = 0, m = (size_t)M;
+    L.qkv = off; off += up256(m * 3 * h * 2);
+    L.a   = off; off += up256(m * h * 2);
+    L.o   = off; off += up256(m * h * 2);
+    L.r   = off; off += up256(m * h * 2);
+    L.gu  = off; off += up256(m * 2 * i * 2);
+    L.m   = off; off += up256(m * i * 2);
+    L.d   = off; off += up256(m * h * 2);
+    L.xn  = off; off += up256(m * h * 2);
+    L.total = off;
+    return L;
+}
+}  // namespace
+
+size_t morph_stack_scratch_bytes(int M, int hidden, int inter)
+{
+    if (M < 1 || hidden < 1 || inter < 1) return 0;
+    return stack_layout(M, hidden, inter).total;
+}
+
+size_t morph_stack_tap_bytes(int M, int hidden, int inter)
+{
+    if (M < 1 || hidden < 1 || inter < 1) return 0;
+    // x, qkv, a, o, r, gu, m, d  (xn of the layout is replaced by the layer input x at the front)
+    return stack_layout(M, hidden, inter).total;
+}
+
+int morph_stack_forward(const morph_layer_desc* layers, int n_layers, void* x_io, int M, int hidden,
+                        int inter, void* scratch, size_t scratch_bytes, void* workspace,
+                        size_t workspace_bytes, int tap_layer, void* tap, void* stream)
+{
+    if (!layers || !x_io || !scratch) return MORPH_ERR_NULL;
+    if (n_layers < 1 || M < 1 || M > kDecodeMaxM) return MORPH_ERR_SHAPE;
+    if (hidden % MORPH_GROUP_SIZE || inter % MORPH_GROUP_SIZE || hidden < MORPH_GROUP_SIZE || inter < MORPH_GROUP_SIZE)
+        return MORPH_ERR_SHAPE;
+    if (!aligned16(x_io) || !aligned16(scratch) || (tap && !aligned16(tap))) return MORPH_ERR_ALIGN;
+    const StackLayout L = stack_layout(M, hidden, inter);
+    if (scratch_bytes < L.total) return MORPH_ERR_WORKSPACE;
+    if (tap_layer >= 0 && tap_layer < n_layers && !tap) return MORPH_ERR_NULL;
+
+    struct Lin { const morph_linear_desc* d; int K, N; };
+    // validate every record and the workspace before the first launch
+    size_t need = 0;
+    for (int l = 0; l < n_layers; l++) {
+        const Lin lins[4] = {{&layers[l].qkv, hidden, 3 * hidden}, {&layers[l].o, hidden, hidden},
+                             {&layers[l].gate_up, hidden, 2 * inter}, {&layers[l].down, inter, hidden}};
+        for (const Lin& li : lins) {
+            if (li.d->kind != MORPH_KIND_FP16 && li.d->kind != MORPH_KIND_W4A16) return MORPH_ERR_SHAPE;
+            if (int rc = validate_linear(li.d->kind, x_io, li.d->w, li.d->scales, li.d->qzeros, scratch, M, li.K, li.N))
+                return rc;
+            size_t nb = workspace_need(li.d->kind, M, li.K, li.N);
+            need = nb > need ? nb : need;
+        }
+    }
+    if (need > 0 && (!workspace || workspace_bytes < need)) return MORPH_ERR_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    char* sc = reinterpret_cast<char*>(scratch);
+    char* tp = reinterpret_cast<char*>(tap);
+    void *qkv = sc + L.qkv, *a = sc + L.a, *o = sc + L.o, *r = sc + L.r, *gu = sc + L.gu, *m = sc + L.m,
+         *d = sc + L.d, *xn = sc + L.xn;
+    void* x = x_io;
+    auto lin = [&](const morph_linear_desc& ld, const void* in, void* out, int K, int N) {
+        return run_linear(ld.kind, in, ld.w, ld.scales, ld.qzeros, out, M, K, N, workspace, workspace_bytes, st);
+    };
+    auto glue = [&](int op, const void* p, const void* q, void* out, int H) {
+        return launch_glue(op, p, q, out, M, H, st) == hipSuccess ? (int)MORPH_OK : (int)MORPH_ERR_DEVICE;
+    };
+    for (int l = 0; l < n_layers; l++) {
+        const morph_layer_desc& ly = layers[l];
+        int rc;
+        if ((rc = lin(ly.qkv, x, qkv, hidden, 3 * hidden))) return rc;
+        if ((rc = glue(MORPH_GLUE_QKV, qkv, nullptr, a, hidden))) return rc;
+        if ((rc = lin(ly.o, a, o, hidden, hidden))) return rc;
+        if ((rc = glue(MORPH_GLUE_RESIDUAL, x, o, r, hidden))) return rc;
+        if ((rc = lin(ly.gate_up, r, gu, hidden, 2 * inter))) return rc;
+        if ((rc = glue(MORPH_GLUE_SWIGLU, gu, nullptr, m, inter))) return rc;
+        if ((rc = lin(ly.down, m, d, inter, hidden))) return rc;
+        if (l == tap_layer) {
+            // layer input first (same slot size as xn), then the seven intermediates
+            const size_t mh = (size_t)M * hidden * 2;
+            if (launch_copy(x, tp + 0, (mh + 15) & ~(size_t)15, st) != hipSuccess) return MORPH_ERR_DEVICE;
+            size_t off = up256(mh);
+            if (launch_copy(sc + L.qkv, tp + off, L.xn - L.qkv, st) != hipSuccess) return MORPH_ERR_DEVICE;
+        }
+        void* xout = (x == x_io) ? xn : x_io;               // ping-pong between x_io and xn
+        if ((rc = glue(MORPH_GLUE_RESIDUAL, r, d, xout, hidden))) return rc;
+        x = xout;
+    }
+    if (x != x_io) {
+        if (launch_copy(x, x_io, ((size_t)M * hidden * 2 + 15) & ~(size_t)15, st) != hipSuccess) return MORPH_ERR_DEVICE;
+    }
+    return MORPH_OK;
+}
+
+int morph_set_tuning(int key, int value)
+{
+    if (key < 0 || key >= TUNE_COUNT) return MORPH_ERR_SHAPE;
+    tuning_set(key, value);
+    return MORPH_OK;
+}
+
+// ---- warm-up: one launch of every kernel family on a tiny dummy problem ----
+// dummy layout: x [64,128] fp16 | w fp16 [128,256] | qweight [128,32] | scales [1,256] | qzeros [1,32] |
+//               y [80,256] fp16 | f32 [128,256] | workspace
+namespace {
+constexpr int    kWM = 80, kWK = 128, kWN = 256;
+constexpr size_t kWarmX = 0, kWarmW = kWarmX + 32768, kWarmQ = kWarmW + 65536, kWarmS = kWarmQ + 16384,
+                 kWarmZ = kWarmS + 512, kWarmY = kWarmZ + 256, kWarmF = kWarmY + 40960, kWarmWs = kWarmF + 131072,
+                 kWarmTotal = kWarmWs + 1048576;
+}  // namespace
+
+size_t morph_warmup_bytes(void) { return kWarmTotal; }
+
+int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
+{
+    if (!dummy) return MORPH_ERR_NULL;
+    if (!aligned16(dummy)) return MORPH_ERR_ALIGN;
+    if (dummy_bytes < kWarmTotal) return MORPH_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char* p = reinterpret_cast<char*>(dummy);
+    if (launch_fill_zero(p, kWarmTotal, st) != hipSuccess) return MORPH_ERR_DEVICE;
+    int rc;
+    int32_t* q = reinterpret_cast<int32_t*>(p + kWarmQ);
+    int32_t* z = reinterpret_cast<int32_t*>(p + kWarmZ);
+    void *x = p + kWarmX, *w = p + kWarmW, *s = p + kWarmS, *y = p + kWarmY, *f = p + kWarmF, *ws = p + kWarmWs;
+    const size_t wsb = kWarmTotal - kWarmWs;
+    if ((rc = morph_quantize_layer(f, MORPH_DTYPE_F32, q, s, z, kWK, kWN, 128, stream))) return rc;
+    if ((rc = morph_quantize_layer(w, MORPH_DTYPE_F16, q, s, z, kWK, kWN, 128, stream))) return rc;
+    if ((rc = morph_dequantize_w4(q, s, z, f, MORPH_DTYPE_F32, kWK, kWN, 128, stream))) return rc;
+    if ((rc = morph_dequantize_w4(q, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
+    const int ms[] = {1, 17, 33, 49, kWM};
+    for (int m : ms) {
+        if ((rc = morph_linear_fp16(x, w, y, m, kWK, kWN, ws, wsb, stream))) return rc;
+        if ((rc = morph_linear_w4a16(x, q, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
+    }
+    for (int op = MORPH_GLUE_QKV; op <= MORPH_GLUE_RMS; op++)
+        if ((rc = morph_glue(op, w, x, y, 2, 64, stream))) return rc;
+    if (launch_copy(x, y, 4096, st) != hipSuccess) return MORPH_ERR_DEVICE;
+    return MORPH_OK;
+}
+
+const char* morph_status_string(int status)
+{
+    switch (status) {
+        case MORPH_OK: return "ok";
+        case MORPH_ERR_NULL: return "a required pointer is NULL";
+        case MORPH_ERR_SHAPE: return "bad shape, group size or enum value";
+        case MORPH_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case MORPH_ERR_WORKSPACE: return "workspace missing or too small";
+        case MORPH_ERR_UNSUPPORTED: return "size beyond what the kernels index";
+        case MORPH_ERR_DEVICE: return "HIP runtime error at launch";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

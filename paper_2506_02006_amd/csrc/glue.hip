@@ -1,0 +1,126 @@
+// Small elementwise + row-norm kernels that sit between the linears of the synthetic layer
+// stack, and two utility kernels (zero fill, copy) used instead of runtime memset/memcpy so
+// that every step of a stack pass is an ordinary kernel node.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace morph {
+
+namespace {
+
+constexpr float kRmsEps = 1e-6f;
+
+// value vector (8 consecutive columns starting at column 8v of the output row)
+template <int OP>
+__device__ __forceinline__ void glue_values(const half_t* a, const half_t* b, int H, int v, float out[8])
+{
+    if constexpr (OP == 0) {            // q + k + v slices of one row of [3H]
+        half8_t x0 = *reinterpret_cast<const half8_t*>(a + 8 * v);
+        half8_t x1 = *reinterpret_cast<const half8_t*>(a + H + 8 * v);
+        half8_t x2 = *reinterpret_cast<const half8_t*>(a + 2 * H + 8 * v);
+#pragma unroll
+        for (int j = 0; j < 8; j++) out[j] = (float)x0[j] + (float)x1[j] + (float)x2[j];
+    } else if constexpr (OP == 1) {     // a + b
+        half8_t x0 = *reinterpret_cast<const half8_t*>(a + 8 * v);
+        half8_t x1 = *reinterpret_cast<const half8_t*>(b + 8 * v);
+#pragma unroll
+        for (int j = 0; j < 8; j++) out[j] = (float)x0[j] + (float)x1[j];
+    } else if constexpr (OP == 2) {     // silu(gate) * up, gate = a[:H], up = a[H:]
+        half8_t g = *reinterpret_cast<const half8_t*>(a + 8 * v);
+        half8_t u = *reinterpret_cast<const half8_t*>(a + H + 8 * v);
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            float gf = (float)g[j];
+            out[j]   = gf / (1.0f + __expf(-gf)) * (float)u[j];
+        }
+    } else {
+        half8_t x0 = *reinterpret_cast<const half8_t*>(a + 8 * v);
+#pragma unroll
+        for (int j = 0; j < 8; j++) out[j] = (float)x0[j];
+    }
+}
+
+// One workgroup per row.  Pass 1 sums squares, pass 2 recomputes the same fp32 values (inputs
+// are a few KB and still in cache) and scales them.
+template <int OP>
+__global__ __launch_bounds__(256) void glue_kernel(const half_t* __restrict__ a, const half_t* __restrict__ b,
+                                                   half_t* __restrict__ out, int H)
+{
+    __shared__ float wsum[4];
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const int in_cols = OP == 0 ? 3 * H : (OP == 2 ? 2 * H : H);
+    const half_t* ar = a + (size_t)row * in_cols;
+    const half_t* br = OP == 1 ? b + (size_t)row * H : nullptr;
+    float ss = 0.f;
+    for (int v = tid; v < H / 8; v += 256) {
+        float x[8];
+        glue_values<OP>(ar, br, H, v, x);
+#pragma unroll
+        for (int j = 0; j < 8; j++) ss += x[j] * x[j];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((tid & 63) == 0) wsum[tid >> 6] = ss;
+    __syncthreads();
+    const float total = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    const float inv   = 1.0f / sqrtf(total / (float)H + kRmsEps);
+    for (int v = tid; v < H / 8; v += 256) {
+        float x[8];
+        glue_values<OP>(ar, br, H, v, x);
+        half8_t h;
+#pragma unroll
+        for (int j = 0; j < 8; j++) h[j] = (half_t)(x[j] * inv);
+        *reinterpret_cast<half8_t*>(out + (size_t)row * H + 8 * v) = h;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* p, size_t n16)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = u32x4{0u, 0u, 0u, 0u};
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ s, u32x4* __restrict__ d, size_t n16)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        d[i] = s[i];
+}
+
+}  // namespace
+
+hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, hipStream_t st)
+{
+    const half_t* ha = (const half_t*)a;
+    const half_t* hb = (const half_t*)b;
+    half_t*       ho = (half_t*)out;
+    switch (op) {
+        case 0: hipLaunchKernelGGL(glue_kernel<0>, dim3(M), dim3(256), 0, st, ha, hb, ho, H); break;
+        case 1: hipLaunchKernelGGL(glue_kernel<1>, dim3(M), dim3(256), 0, st, ha, hb, ho, H); break;
+        case 2: hipLaunchKernelGGL(glue_kernel<2>, dim3(M), dim3(256), 0, st, ha, hb, ho, H); break;
+        default: hipLaunchKernelGGL(glue_kernel<3>, dim3(M), dim3(256), 0, st, ha, hb, ho, H); break;
+    }
+    return hipGetLastError();
+}
+
+// bytes must be a multiple of 16 and p 16-byte aligned (checked by the callers)
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    int blocks = (int)((n16 + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, (u32x4*)p, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    int blocks = (int)((n16 + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4*)src, (u32x4*)dst, n16);
+    return hipGetLastError();
+}
+
+}  // namespace morph

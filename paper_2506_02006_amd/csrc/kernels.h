@@ -1,0 +1,59 @@
+// Host-side launch functions of the kernels (internal to the library; the public face is
+// include/morph.h).  Each returns hipGetLastError() taken right after the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace morph {
+
+// ---- quantizer / verification dequantizer (quant.hip) ----
+hipError_t launch_quantize_w4(const void* w, int w_is_f16, uint32_t* qweight, void* scales,
+                              uint32_t* qzeros, int K, int N, hipStream_t st);
+hipError_t launch_dequantize_w4(const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
+                                void* out, int out_is_f16, int K, int N, hipStream_t st);
+
+// ---- decode, M <= 64 (decode.hip) ----
+struct DecodeArgs {
+    const void*     x;         // fp16 [M,K]
+    const void*     w;         // fp16 [K,N] or uint32 [K,N/8]
+    const void*     scales;    // fp16 [K/128,N]      (W4 only)
+    const void*     qzeros;    // uint32 [K/128,N/8]  (W4 only)
+    void*           y;         // fp16 [M,N]
+    float*          partial;   // [tiles][S][M][tile columns] fp32, used when S > 1
+    int*            counters;  // [tiles], zero on entry, zero on exit
+    int             M, K, N;
+    int             S;         // workgroups sharing one column tile (split along K)
+};
+struct DecodePlan {
+    int    tile_n;             // columns per workgroup
+    int    tiles;              // ceil(N / tile_n)
+    int    S;                  // split along K across workgroups
+    size_t partial_bytes;      // 0 when S == 1
+};
+constexpr size_t kCounterBytes = 4096;   // head of the workspace: arrival counters
+DecodePlan plan_decode(int is_w4, int M, int K, int N);
+hipError_t launch_decode(int is_w4, const DecodeArgs& a, hipStream_t st);
+
+// ---- prefill, M > 64 (prefill.hip) ----
+struct GemmArgs {
+    const void* x;
+    const void* w;
+    const void* scales;
+    const void* qzeros;
+    void*       y;
+    int         M, K, N;
+};
+hipError_t launch_prefill(int is_w4, const GemmArgs& a, hipStream_t st);
+
+// ---- glue (glue.hip) ----
+hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, hipStream_t st);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+
+// tuning knobs (morph_set_tuning)
+int  tuning_get(int key);
+void tuning_set(int key, int value);
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_COUNT = 8 };
+
+}  // namespace morph

@@ -1,0 +1,114 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before anything is launched (so this runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "morph.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2506_02006_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(morph_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(L):
+    from paper_2506_02006_amd import binding
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_status_strings(L):
+    for s in range(0, 8):
+        assert isinstance(L.morph_status_string(s), bytes) and L.morph_status_string(s)
+
+
+FAKE = 0x7F0000001000          # non-null, 16-byte aligned, never dereferenced on these paths
+
+
+def test_linear_w4a16_validation(L):
+    f = L.morph_linear_w4a16
+    ok = dict(M=4, K=256, N=64, g=128)
+    def call(x=FAKE, q=FAKE, s=FAKE, z=FAKE, y=FAKE, M=4, K=256, N=64, g=128, ws=None, wsb=0):
+        return f(x, q, s, z, y, M, K, N, g, ws, wsb, None)
+    assert call(x=None) == 1 and call(q=None) == 1 and call(s=None) == 1 and call(z=None) == 1 and call(y=None) == 1
+    assert call(M=0) == 2 and call(K=200) == 2 and call(N=60) == 2 and call(g=64) == 2 and call(K=0) == 2
+    assert call(x=FAKE + 8) == 3 and call(q=FAKE + 4) == 3 and call(s=FAKE + 2) == 3 and call(y=FAKE + 8) == 3
+    # decode shape that needs a workspace: none given
+    assert L.morph_workspace_bytes(1, 4, 4096, 4096) > 0
+    assert call(M=4, K=4096, N=4096) == 4
+    assert call(M=4, K=4096, N=4096, ws=FAKE, wsb=64) == 4
+    # 4 GiB limit on a single array
+    assert call(M=1, K=128 * 1024 * 64, N=1024) == 5
+
+
+def test_linear_fp16_validation(L):
+    f = L.morph_linear_fp16
+    assert f(None, FAKE, FAKE, 1, 128, 8, None, 0, None) == 1
+    assert f(FAKE, FAKE, FAKE, 1, 100, 8, None, 0, None) == 2
+    assert f(FAKE, FAKE + 2, FAKE, 1, 128, 8, None, 0, None) == 3
+    assert f(FAKE, FAKE, FAKE, 8, 4096, 4096, None, 0, None) == 4
+
+
+def test_quantize_dequantize_validation(L):
+    q, d = L.morph_quantize_layer, L.morph_dequantize_w4
+    assert q(None, 0, FAKE, FAKE, FAKE, 128, 8, 128, None) == 1
+    assert q(FAKE, 2, FAKE, FAKE, FAKE, 128, 8, 128, None) == 2
+    assert q(FAKE, 0, FAKE, FAKE, FAKE, 128, 12, 128, None) == 2
+    assert q(FAKE, 0, FAKE, FAKE, FAKE, 128, 8, 32, None) == 2
+    assert q(FAKE + 4, 0, FAKE, FAKE, FAKE, 128, 8, 128, None) == 3
+    assert d(FAKE, FAKE, None, FAKE, 0, 128, 8, 128, None) == 1
+    assert d(FAKE, FAKE, FAKE, FAKE, 3, 128, 8, 128, None) == 2
+    assert d(FAKE, FAKE, FAKE, FAKE + 8, 0, 128, 8, 128, None) == 3
+
+
+def test_workspace_bytes_rules(L):
+    wb = L.morph_workspace_bytes
+    assert wb(7, 1, 4096, 4096) == 0 and wb(1, 0, 4096, 4096) == 0 and wb(1, 1, 100, 4096) == 0
+    assert wb(1, 512, 4096, 4096) == 0                     # prefill needs none
+    small, large = wb(1, 1, 4096, 4096), wb(1, 64, 4096, 4096)
+    assert 0 < small < large < 64 * 1024 * 1024
+    assert L.morph_workspace_init(None, 0, None) == 0
+    assert L.morph_workspace_init(None, 4096, None) == 1
+    assert L.morph_workspace_init(FAKE + 1, 4096, None) == 3
+
+
+def test_glue_and_stack_validation(L):
+    from paper_2506_02006_amd.binding import LayerDesc
+    assert L.morph_glue(9, FAKE, None, FAKE, 1, 64, None) == 2
+    assert L.morph_glue(1, FAKE, None, FAKE, 1, 64, None) == 1
+    assert L.morph_glue(0, FAKE, None, FAKE, 1, 60, None) == 2
+    assert L.morph_stack_scratch_bytes(32, 4096, 11008) > 32 * (12288 + 22016) * 2
+    assert L.morph_stack_tap_bytes(32, 4096, 11008) == L.morph_stack_scratch_bytes(32, 4096, 11008)
+    arr = (LayerDesc * 1)()
+    for name in ("qkv", "o", "gate_up", "down"):
+        d = getattr(arr[0], name)
+        d.kind, d.w, d.scales, d.qzeros = 0, FAKE, None, None
+    sf = L.morph_stack_forward
+    big = 1 << 30
+    assert sf(arr, 1, None, 32, 256, 384, FAKE, big, FAKE, big, -1, None, None) == 1
+    assert sf(arr, 1, FAKE, 65, 256, 384, FAKE, big, FAKE, big, -1, None, None) == 2
+    assert sf(arr, 1, FAKE, 32, 200, 384, FAKE, big, FAKE, big, -1, None, None) == 2
+    assert sf(arr, 1, FAKE, 32, 256, 384, FAKE, 16, FAKE, big, -1, None, None) == 4
+    arr[0].o.kind = 5
+    assert sf(arr, 1, FAKE, 32, 256, 384, FAKE, big, FAKE, big, -1, None, None) == 2
+    arr[0].o.kind = 1                                      # W4 record without scales
+    assert sf(arr, 1, FAKE, 32, 256, 384, FAKE, big, FAKE, big, -1, None, None) == 1
+    assert L.morph_warmup(None, 0, None) == 1
+    assert L.morph_warmup(FAKE, 16, None) == 4
+    assert L.morph_set_tuning(99, 1) == 2

@@ -1,0 +1,333 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the
+same seeded host-generated inputs.
+
+Bars
+  * quantize, dequantize, identity-activation products: bit-exact.
+  * linears: max|y - y_ref| / max|y_ref| <= 5e-3 (fp16 output, fp32 accumulation), y_ref unrounded fp64.
+  * glue: 2e-3 on the same normalised metric.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2506_02006_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 5e-3
+GLUE_TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2506_02006_amd import binding
+    binding.lib()                       # raises if the HIP library is not built
+    binding.warmup()
+    return binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a: np.ndarray):
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t) -> np.ndarray:
+    return t.detach().cpu().numpy()
+
+
+def make_ws(B, kind, M, K, N):
+    return B.new_workspace(B.workspace_bytes(kind, M, K, N))
+
+
+def rand_w(seed, K, N, dist="normal"):
+    return synth.weights(77, K, N, layer_id=seed, dist=dist)
+
+
+# ---------------- quantizer and dequantizer: bit-exact ----------------
+
+@pytest.mark.parametrize("K,N,dist", [(128, 8, "normal"), (384, 264, "normal"), (1024, 4096, "student_t5"),
+                                      (256, 2056, "normal")])
+def test_quantize_bit_exact(B, oracle, K, N, dist):
+    say(f"quantize K={K} N={N} {dist}")
+    W = rand_w(1, K, N, dist)
+    if N >= 264:                        # special groups: one-signed, constant, zero, tiny, outlier
+        W[0:128, 0] = np.abs(W[0:128, 0]) + 0.1
+        W[0:128, 1] = -np.abs(W[0:128, 1]) - 0.1
+        W[0:128, 2] = 0.37
+        W[0:128, 3] = 0.0
+        W[0:128, 4] *= 1e-6
+        W[5, 5] = 9.0
+    qw, sc, qz = oracle.quantize_w4(W)
+    gq, gs, gz = B.quantize_layer(dev(W))
+    assert np.array_equal(host(gs).view(np.uint16), sc.view(np.uint16))
+    assert np.array_equal(host(gz).view(np.uint32), qz)
+    assert np.array_equal(host(gq).view(np.uint32), qw)
+    # fp16 master weights: same procedure on the widened values
+    W16 = W.astype(np.float16)
+    qw, sc, qz = oracle.quantize_w4(W16.astype(np.float32))
+    gq, gs, gz = B.quantize_layer(dev(W16))
+    assert np.array_equal(host(gs).view(np.uint16), sc.view(np.uint16))
+    assert np.array_equal(host(gz).view(np.uint32), qz)
+    assert np.array_equal(host(gq).view(np.uint32), qw)
+
+
+@pytest.mark.parametrize("K,N", [(128, 8), (384, 264), (1024, 4096)])
+def test_dequantize_bit_exact(B, oracle, K, N):
+    say(f"dequantize K={K} N={N}")
+    rng = np.random.default_rng(K + N)
+    # arbitrary records (not only ones a quantizer would emit): all code/zero combinations occur
+    qw = rng.integers(0, 2 ** 32, (K, N // 8), dtype=np.uint64).astype(np.uint32)
+    qz = rng.integers(0, 2 ** 32, (K // 128, N // 8), dtype=np.uint64).astype(np.uint32)
+    sc = rng.uniform(2.0 ** -14, 3.0, (K // 128, N)).astype(np.float16)
+    d32 = B.dequantize_w4(dev(qw), dev(sc), dev(qz), torch.float32)
+    d16 = B.dequantize_w4(dev(qw), dev(sc), dev(qz), torch.float16)
+    assert np.array_equal(host(d32).view(np.uint32), oracle.dequant_w4(qw, sc, qz).view(np.uint32))
+    assert np.array_equal(host(d16).view(np.uint16), oracle.dequant_w4(qw, sc, qz, 128, np.float16).view(np.uint16))
+
+
+# ---------------- linears ----------------
+
+DECODE_SHAPES = [
+    # M, K, N : several column tiles, ragged tails in M and N, K with 1..86 groups
+    (1, 128, 8), (1, 4096, 4096), (3, 384, 264), (4, 1024, 520), (8, 256, 2048), (16, 1024, 1032),
+    (17, 512, 1024), (32, 11008, 512), (33, 640, 776), (48, 384, 256), (49, 1280, 264), (64, 768, 1288),
+]
+PREFILL_SHAPES = [(65, 256, 264), (100, 384, 776), (128, 128, 128), (256, 1024, 512), (300, 512, 1288), (513, 256, 520)]
+
+
+def check_w4(B, oracle, M, K, N, dist="normal", seed=0):
+    W = rand_w(seed, K, N, dist)
+    x = synth.activations(77, M, K, layer_id=seed)
+    qw, sc, qz = oracle.quantize_w4(W)
+    ws = make_ws(B, B.KIND_W4A16, M, K, N)
+    y = B.linear_w4a16(dev(x), dev(qw), dev(sc), dev(qz), ws)
+    torch.cuda.synchronize()
+    r = oracle.error_metric(host(y), oracle.linear_w4a16(x, qw, sc, qz))
+    say(f"  w4   M={M} K={K} N={N}: err={r['err']:.3e} at {r['argmax']}")
+    assert r["finite"] and r["err"] <= TOL, r
+    return r
+
+
+def check_fp16(B, oracle, M, K, N, seed=0):
+    W16 = rand_w(seed, K, N).astype(np.float16)
+    x = synth.activations(77, M, K, layer_id=seed)
+    ws = make_ws(B, B.KIND_FP16, M, K, N)
+    y = B.linear_fp16(dev(x), dev(W16), ws)
+    torch.cuda.synchronize()
+    r = oracle.error_metric(host(y), oracle.linear_fp16(x, W16))
+    say(f"  fp16 M={M} K={K} N={N}: err={r['err']:.3e} at {r['argmax']}")
+    assert r["finite"] and r["err"] <= TOL, r
+    return r
+
+
+@pytest.mark.parametrize("M,K,N", DECODE_SHAPES)
+def test_decode_w4a16(B, oracle, M, K, N):
+    check_w4(B, oracle, M, K, N, "student_t5" if M % 2 else "normal", seed=M)
+
+
+@pytest.mark.parametrize("M,K,N", DECODE_SHAPES)
+def test_decode_fp16(B, oracle, M, K, N):
+    check_fp16(B, oracle, M, K, N, seed=M)
+
+
+@pytest.mark.parametrize("M,K,N", PREFILL_SHAPES)
+def test_prefill_w4a16(B, oracle, M, K, N):
+    check_w4(B, oracle, M, K, N, seed=M)
+
+
+@pytest.mark.parametrize("M,K,N", PREFILL_SHAPES)
+def test_prefill_fp16(B, oracle, M, K, N):
+    check_fp16(B, oracle, M, K, N, seed=M)
+
+
+@pytest.mark.parametrize("tile", [1, 2])
+def test_prefill_both_tiles(B, oracle, tile):
+    B.set_tuning(B.TUNE_PREFILL_TILE, tile)
+    try:
+        check_w4(B, oracle, 300, 512, 776, seed=tile)
+        check_fp16(B, oracle, 300, 512, 776, seed=tile)
+    finally:
+        B.set_tuning(B.TUNE_PREFILL_TILE, 0)
+
+
+@pytest.mark.parametrize("split", [1, 2, 3, 7])
+def test_decode_every_split(B, oracle, split):
+    """The K split across workgroups only changes the fp32 summation order."""
+    B.set_tuning(B.TUNE_DECODE_SPLIT, split)
+    try:
+        for M in (1, 16, 33, 64):
+            check_w4(B, oracle, M, 1792, 520, seed=split)
+            check_fp16(B, oracle, M, 1792, 264, seed=split)
+    finally:
+        B.set_tuning(B.TUNE_DECODE_SPLIT, 0)
+
+
+@pytest.mark.parametrize("M", [16, 32, 64, 128, 256])
+def test_identity_activations_reproduce_dequantized_weights(B, oracle, M):
+    """x = rows of the identity: every output is a single term, so y must equal the fp16-rounded
+    dequantized weight bit for bit.  Pins nibble order, group indexing and operand layout through
+    the real GEMM kernels (decode for M <= 64, prefill above)."""
+    K, N = 256, 520
+    W = rand_w(3, K, N)
+    qw, sc, qz = oracle.quantize_w4(W)
+    D16 = oracle.dequant_w4(qw, sc, qz, 128, np.float16)
+    ws = make_ws(B, B.KIND_W4A16, min(M, 64), K, N)
+    for start in range(0, K, M):
+        x = np.zeros((M, K), np.float16)
+        x[np.arange(M), start + np.arange(M)] = 1.0
+        y = host(B.linear_w4a16(dev(x), dev(qw), dev(sc), dev(qz), ws))
+        assert np.array_equal(y.view(np.uint16), D16[start:start + M].view(np.uint16)), (M, start)
+    # the fp16 layer under the same activations returns its weights
+    W16 = W.astype(np.float16)
+    ws = make_ws(B, B.KIND_FP16, min(M, 64), K, N)
+    x = np.zeros((M, K), np.float16)
+    x[np.arange(M), np.arange(M)] = 1.0
+    y = host(B.linear_fp16(dev(x), dev(W16), ws))
+    assert np.array_equal(y.view(np.uint16), W16[:M].view(np.uint16))
+
+
+def test_in_place_swap_of_a_layer_is_seen(B, oracle):
+    """A layer's weights are overwritten in place between two calls (fp16 -> W4 over the same
+    bytes, then other W4 data): each call must see the bytes that are there now."""
+    M, K, N = 8, 1024, 1024
+    x = synth.activations(77, M, K)
+    Wa, Wb = rand_w(10, K, N), rand_w(11, K, N)
+    slot = torch.empty(K * N * 2, dtype=torch.uint8, device="cuda")          # sized for the fp16 variant
+    ws = B.new_workspace(max(B.workspace_bytes(0, M, K, N), B.workspace_bytes(1, M, K, N)))
+    xd = dev(x)
+    w16 = slot.view(torch.float16).view(K, N)
+    w16.copy_(dev(Wa.astype(np.float16)))
+    y0 = host(B.linear_fp16(xd, w16, ws))
+    assert oracle.error_metric(y0, oracle.linear_fp16(x, Wa.astype(np.float16)))["err"] <= TOL
+    nq, ns, nz = K * N // 2, K // 128 * N * 2, K // 128 * N // 2
+    qv = slot[:nq].view(torch.int32).view(K, N // 8)
+    sv = slot[nq:nq + ns].view(torch.float16).view(K // 128, N)
+    zv = slot[nq + ns:nq + ns + nz].view(torch.int32).view(K // 128, N // 8)
+    for W in (Wa, Wb, Wa):
+        qw, sc, qz = oracle.quantize_w4(W)
+        qv.copy_(dev(qw)); sv.copy_(dev(sc)); zv.copy_(dev(qz))
+        y = host(B.linear_w4a16(xd, qv, sv, zv, ws))
+        assert oracle.error_metric(y, oracle.linear_w4a16(x, qw, sc, qz))["err"] <= TOL
+    w16.copy_(dev(Wa.astype(np.float16)))
+    y1 = host(B.linear_fp16(xd, w16, ws))
+    assert np.array_equal(y0.view(np.uint16), y1.view(np.uint16))           # same bytes in, same bytes out
+
+
+def test_repeat_calls_are_bitwise_reproducible(B, oracle):
+    M, K, N = 16, 4096, 4096
+    x = dev(synth.activations(77, M, K))
+    qw, sc, qz = (dev(a) for a in oracle.quantize_w4(rand_w(4, K, N)))
+    ws = make_ws(B, B.KIND_W4A16, M, K, N)
+    ys = [host(B.linear_w4a16(x, qw, sc, qz, ws)) for _ in range(5)]
+    for y in ys[1:]:
+        assert np.array_equal(y.view(np.uint16), ys[0].view(np.uint16))
+
+
+# ---------------- glue and the layer stack ----------------
+
+def test_glue_ops(B, oracle):
+    rng = np.random.default_rng(5)
+    M, H = 5, 1384
+    qkv = (rng.standard_normal((M, 3 * H)) * 2).astype(np.float16)
+    a = rng.standard_normal((M, H)).astype(np.float16)
+    b = (rng.standard_normal((M, H)) * 3).astype(np.float16)
+    gu = (rng.standard_normal((M, 2 * H)) * 2).astype(np.float16)
+    cases = [(B.GLUE_QKV, qkv, None, oracle.glue_qkv(qkv)), (B.GLUE_RESIDUAL, a, b, oracle.glue_residual(a, b)),
+             (B.GLUE_SWIGLU, gu, None, oracle.glue_swiglu(gu)), (B.GLUE_RMS, a, None, oracle.rms(a))]
+    for op, p, q, want in cases:
+        got = host(B.glue(op, dev(p), dev(q) if q is not None else None))
+        r = oracle.error_metric(got, want)
+        say(f"  glue op={op}: err={r['err']:.3e}")
+        assert r["err"] <= GLUE_TOL
+
+
+def build_stack(B, oracle, family_shapes, n_layers, swapped, M, config_id, keep=()):
+    """Generate layer by layer on the host, quantize swapped layers with the ORACLE's quantizer,
+    upload.  Host copies are kept only for the layers in `keep` (for the oracle's checks)."""
+    hidden = family_shapes["qkv"][0]
+    inter = family_shapes["down"][0]
+    st = B.LayerStack(hidden, inter, M)
+    kept = {}
+    for l in range(n_layers):
+        rec, hostrec = {}, {}
+        for name in synth.LINEAR_ORDER:
+            K, N = family_shapes[name]
+            W = synth.weights(config_id, K, N, layer_id=l, tensor_id=synth._TENSOR_ID[name])
+            if l in swapped:
+                qw, sc, qz = oracle.quantize_w4(W)
+                rec[name] = ("w4", dev(qw), dev(sc), dev(qz))
+                hostrec[name] = ("w4", qw, sc, qz)
+            else:
+                w16 = W.astype(np.float16)
+                rec[name] = ("fp16", dev(w16))
+                hostrec[name] = ("fp16", w16)
+        st.add_layer(rec)
+        if l in keep:
+            kept[l] = hostrec
+    return st, kept
+
+
+def oracle_linear(oracle, rec, x):
+    return oracle.linear_fp16(x, rec[1]) if rec[0] == "fp16" else oracle.linear_w4a16(x, rec[1], rec[2], rec[3])
+
+
+def test_small_stack_against_independent_oracle_chain(B, oracle):
+    """The oracle runs the whole chain on its own from x0 (its own fp16 rounding between steps);
+    the GPU output after 6 mixed layers must still agree to a few 1e-3."""
+    shapes = {"qkv": (256, 768), "o": (256, 256), "gate_up": (256, 768), "down": (384, 256)}
+    n_layers, M = 6, 32
+    swapped = {1, 2, 4}
+    st, kept = build_stack(B, oracle, shapes, n_layers, swapped, M, 95, keep=range(n_layers))
+    x0 = oracle.rms(synth.activations(95, M, 256).astype(np.float64)).astype(np.float16)
+    xg = dev(x0).clone()
+    st.forward(xg)
+    f16 = lambda v: np.asarray(v, np.float64).astype(np.float16)
+    x = x0
+    for l in range(n_layers):
+        L = kept[l]
+        qkv = f16(oracle_linear(oracle, L["qkv"], x))
+        a = f16(oracle.glue_qkv(qkv))
+        o = f16(oracle_linear(oracle, L["o"], a))
+        r = f16(oracle.glue_residual(x, o))
+        gu = f16(oracle_linear(oracle, L["gate_up"], r))
+        m = f16(oracle.glue_swiglu(gu))
+        d = f16(oracle_linear(oracle, L["down"], m))
+        x = f16(oracle.glue_residual(r, d))
+    r = oracle.error_metric(host(xg), x.astype(np.float64))
+    say(f"  6-layer chain: err={r['err']:.3e}")
+    assert r["err"] <= 2e-2        # fp16 re-rounding after each of 48 steps on both sides
+
+
+def check_tapped_layer(oracle, st, hostrec, label):
+    t = {k: host(v) for k, v in st.tapped().items()}
+    pairs = [("qkv", "x", "qkv"), ("o", "a", "o"), ("gate_up", "r", "gu"), ("down", "m", "d")]
+    for name, tin, tout in pairs:
+        r = oracle.error_metric(t[tout], oracle_linear(oracle, hostrec[name], t[tin]))
+        say(f"  {label} {name} ({hostrec[name][0]}): err={r['err']:.3e}")
+        assert r["finite"] and r["err"] <= TOL, (label, name, r)
+    for got, want in ((t["a"], oracle.glue_qkv(t["qkv"])), (t["r"], oracle.glue_residual(t["x"], t["o"])),
+                      (t["m"], oracle.glue_swiglu(t["gu"]))):
+        assert oracle.error_metric(got, want)["err"] <= GLUE_TOL
+
+
+def test_small_stack_every_layer_teacher_forced(B, oracle):
+    shapes = {"qkv": (256, 768), "o": (256, 256), "gate_up": (256, 768), "down": (384, 256)}
+    n_layers, M = 4, 32
+    st, kept = build_stack(B, oracle, shapes, n_layers, {0, 3}, M, 96, keep=range(n_layers))
+    x0 = dev(oracle.rms(synth.activations(96, M, 256).astype(np.float64)).astype(np.float16))
+    for l in range(n_layers):
+        x = x0.clone()
+        st.forward(x, tap_layer=l)
+        torch.cuda.synchronize()
+        check_tapped_layer(oracle, st, kept[l], f"layer {l}")
