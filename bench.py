@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the fp16 / W4A16 linear path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--quick]
+
+A step = the four linears (QKV, O, gate_up, down) of one Llama-7B-shaped decoder layer in W4A16 at
+each decode batch M in {1, 4, 16}: 12 kernel launches, recorded once per layer into a HIP graph and
+replayed.  Consecutive steps use different layers out of a pool larger than 1 GiB, so no step finds
+its weights in the 256 MB last-level cache.  Inputs are resident in HBM before the clock starts.
+
+value = algorithmic weight traffic (packed codes + fp16 scales, as the target is stated) of the K
+timed steps / elapsed time, in GB/s.  The JSON line also carries:
+  roofline      the W4A16 decode kernel against the 8 TB/s HBM peak, over the same timed region
+  cpu_baseline  the CPU oracle (as it stands) on a bounded sample of the same workload
+  detail        per-shape figures: fp16 for comparison, M up to 64 on the 8B-shaped layer, prefill
+                TFLOP/s on the 13B-shaped layer at M = 512 / 2048, the 32-layer mixed stack
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X datasheet
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--quick", action="store_true", help="headline only, skip the detail sections")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2506_02006_amd import binding as B
+    from paper_2506_02006_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    B.warmup()
+    dev = "cuda"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.BASE_SEED)
+
+    def rand_w(K, N):
+        return torch.randn((K, N), device=dev, dtype=torch.float32, generator=gen) * 0.02
+
+    def rand_x(M, K):
+        return torch.randn((M, K), device=dev, dtype=torch.float32, generator=gen).to(torch.float16)
+
+    def make_w4(K, N):
+        w = rand_w(K, N)
+        rec = B.quantize_layer(w)
+        del w
+        return rec
+
+    def make_fp16(K, N):
+        return rand_w(K, N).to(torch.float16)
+
+    def timed(fn, steps, warmup):
+        """fn(i) enqueues step i on the current stream.  Returns seconds for `steps` steps (HIP events)."""
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            fn(warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3
+
+    def graph_of(fn):
+        """Record fn() (kernel launches on the capture stream) into a HIP graph."""
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            fn()                                   # once eagerly: loads code objects, sizes buffers
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            fn()
+        return g
+
+    shapes7 = synth.LAYER_SHAPES["llama7b"]
+    order = synth.LINEAR_ORDER
+    Ms = (1, 4, 16)
+
+    # ------------- headline: config 2, W4A16 decode -------------
+    n_pool = 12                                     # 12 x 105 MB = 1.26 GB of distinct W4 layers
+    pool = [{name: make_w4(*shapes7[name]) for name in order} for _ in range(n_pool)]
+    xs = {(M, K): rand_x(M, K) for M in Ms for K in (4096, 11008)}
+    ys = {(M, name): torch.empty((M, shapes7[name][1]), device=dev, dtype=torch.float16) for M in Ms for name in order}
+    ws_bytes = max(B.workspace_bytes(B.KIND_W4A16, M, *shapes7[name]) for M in Ms for name in order)
+    ws = B.new_workspace(ws_bytes)
+
+    def step_fn(layer):
+        def run():
+            for M in Ms:
+                for name in order:
+                    K, N = shapes7[name]
+                    qw, sc, qz = layer[name]
+                    B.linear_w4a16(xs[(M, K)], qw, sc, qz, ws, out=ys[(M, name)])
+        return run
+
+    graphs = [graph_of(step_fn(layer)) for layer in pool]
+    launches_per_step = len(Ms) * len(order)
+    bytes_ws = sum(synth.w4_bytes(K, N, zeros=False) for K, N in shapes7.values())      # codes + scales
+    bytes_all = sum(synth.w4_bytes(K, N, zeros=True) for K, N in shapes7.values())
+    sec = timed(lambda i: graphs[i % n_pool].replay(), args.steps, args.warmup)
+    step_bytes = len(Ms) * bytes_ws
+    value = step_bytes * args.steps / sec / 1e9
+    avg_launch_s = sec / (args.steps * launches_per_step)
+    roofline = {
+        "bound": "hbm",
+        "kernel": "decode_kernel<W4> (M <= 16 variant), mean over the 12 launches of a step",
+        "achieved": round(value, 1),
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": round(value / HBM_PEAK_GBS, 4),
+        "traffic": None,
+        "bytes_per_launch": step_bytes / launches_per_step,
+        "avg_launch_us": round(avg_launch_s * 1e6, 3),
+    }
+    result = {
+        "metric": "w4a16_decode_linear_hbm_bandwidth",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(sec / args.steps * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "llama7b decoder-layer linears (qkv 4096x12288, o 4096x4096, gate_up 4096x22016, "
+                               "down 11008x4096), W4A16 group 128, decode M in {1,4,16}; 12 launches per step, "
+                               f"layer pool {n_pool} x {bytes_all / 1e6:.1f} MB",
+                   "bytes_counted": "packed codes + fp16 scales", "launch": "HIP graph replay"},
+        "roofline": roofline,
+    }
+
+    detail = {}
+    if not args.quick:
+        # ---- per linear and per M, one shape back to back over the pool (W4A16 and fp16) ----
+        def per_linear(kind, family, name, M, recs, reps=60):
+            K, N = synth.LAYER_SHAPES[family][name]
+            x = rand_x(M, K)
+            y = torch.empty((M, N), device=dev, dtype=torch.float16)
+            w = B.new_workspace(B.workspace_bytes(kind, M, K, N))
+            def run():
+                for r in recs:
+                    if kind == B.KIND_W4A16:
+                        B.linear_w4a16(x, r[0], r[1], r[2], w, out=y)
+                    else:
+                        B.linear_fp16(x, r, w, out=y)
+            g = graph_of(run)
+            s = timed(lambda i: g.replay(), max(2, reps // len(recs)), 2) / (max(2, reps // len(recs)) * len(recs))
+            nbytes = synth.w4_bytes(K, N, zeros=False) if kind == B.KIND_W4A16 else synth.fp16_bytes(K, N)
+            return {"us": round(s * 1e6, 2), "GBps": round(nbytes / s / 1e9, 1),
+                    "pct_hbm": round(nbytes / s / 1e9 / HBM_PEAK_GBS * 100, 1),
+                    "TFLOPs": round(2.0 * M * K * N / s / 1e12, 2)}
+
+        d7 = {}
+        for name in order:
+            recs = [layer[name] for layer in pool]
+            for M in (1, 4, 16):
+                d7[f"w4a16/{name}/M{M}"] = per_linear(B.KIND_W4A16, "llama7b", name, M, recs)
+        del graphs
+        # fp16 comparison: pool of 4 layers x 405 MB
+        pool16 = [{name: make_fp16(*shapes7[name]) for name in order} for _ in range(4)]
+        for name in order:
+            recs = [layer[name] for layer in pool16]
+            for M in (1, 4, 16):
+                d7[f"fp16/{name}/M{M}"] = per_linear(B.KIND_FP16, "llama7b", name, M, recs, reps=24)
+        detail["config2_llama7b"] = d7
+        del pool16
+
+        # ---- config 3: 8B GQA shapes, W4A16, M up to 64 ----
+        shapes8 = synth.LAYER_SHAPES["llama3_8b"]
+        pool8 = [{name: make_w4(*shapes8[name]) for name in order} for _ in range(10)]
+        d8 = {}
+        for name in order:
+            recs = [layer[name] for layer in pool8]
+            for M in (1, 8, 32, 64):
+                d8[f"w4a16/{name}/M{M}"] = per_linear(B.KIND_W4A16, "llama3_8b", name, M, recs)
+        detail["config3_llama3_8b"] = d8
+        del pool8
+
+        # ---- config 4: 13B prefill chunk ----
+        shapes13 = synth.LAYER_SHAPES["llama13b"]
+        d13 = {}
+        for name in order:
+            K, N = shapes13[name]
+            w4 = make_w4(K, N)
+            w16 = make_fp16(K, N)
+            for M in (512, 2048):
+                x = rand_x(M, K)
+                y = torch.empty((M, N), device=dev, dtype=torch.float16)
+                for label, fn in (("w4a16", lambda: B.linear_w4a16(x, w4[0], w4[1], w4[2], None, out=y)),
+                                  ("fp16", lambda: B.linear_fp16(x, w16, None, out=y))):
+                    s = timed(lambda i: fn(), 10, 2) / 10
+                    tf = 2.0 * M * K * N / s / 1e12
+                    d13[f"{label}/{name}/M{M}"] = {"us": round(s * 1e6, 1), "TFLOPs": round(tf, 1),
+                                                   "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1)}
+            del w4, w16
+        detail["config4_llama13b_prefill"] = d13
+
+        # ---- config 5: 32-layer mixed stack at M = 32 ----
+        M5, L5 = 32, 32
+        base16 = [{name: make_fp16(*shapes7[name]) for name in order} for _ in range(L5)]
+        base4 = [{name: B.quantize_layer(base16[l][name]) for name in order} for l in range(L5)]
+        d5 = {}
+        for k in (0, 8, 16, 32):
+            swapped = set(synth.swapped_layers(L5, k).tolist())
+            st = B.LayerStack(4096, 11008, M5)
+            for l in range(L5):
+                if l in swapped:
+                    st.add_layer({n: ("w4",) + tuple(base4[l][n]) for n in order})
+                else:
+                    st.add_layer({n: ("fp16", base16[l][n]) for n in order})
+            x5 = rand_x(M5, 4096)
+            g5 = graph_of(lambda: st.forward(x5))
+            s = timed(lambda i: g5.replay(), 10, 2) / 10
+            nbytes = sum((bytes_ws if l in swapped else sum(synth.fp16_bytes(*shapes7[n]) for n in order)) for l in range(L5))
+            d5[f"k{k}"] = {"ms": round(s * 1e3, 4), "GBps": round(nbytes / s / 1e9, 1),
+                           "pct_hbm": round(nbytes / s / 1e9 / HBM_PEAK_GBS * 100, 1), "weight_GB": round(nbytes / 1e9, 3)}
+            del g5, st
+        detail["config5_stack_M32"] = d5
+        del base16, base4
+        result["detail"] = detail
+
+    # ------------- CPU oracle baseline: bounded sample of the same workload -------------
+    if not args.no_cpu:
+        from oracle import build as ob
+        ob.build(force=False)
+        from oracle import cpu_oracle as O
+        Mc = 4
+        t_total, b_total = 0.0, 0
+        for name in order:
+            K, N = shapes7[name]
+            W = synth.weights(2, K, N, tensor_id=synth._TENSOR_ID[name])
+            qw, sc, qz = O.quantize_w4(W)
+            x = synth.activations(2, Mc, K)
+            t0 = time.perf_counter()
+            O.linear_w4a16(x, qw, sc, qz)
+            t_total += time.perf_counter() - t0
+            b_total += synth.w4_bytes(K, N, zeros=False)
+        result["cpu_baseline"] = {"value": round(b_total / t_total / 1e9, 4), "unit": "GB/s", "cores": O.num_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"one llama7b layer (4 linears) W4A16 at M={Mc}, fp64 oracle, {t_total:.2f} s"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

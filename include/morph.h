@@ -143,7 +143,8 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
 
 /* Override a kernel-selection heuristic (0 restores the default).  For benchmarking sweeps only;
  * defaults are chosen from the shape.  Keys: 0 = K-split factor of the decode kernels,
- * 1 = target workgroup count of the decode kernels, 2 = prefill tile (1 = 256x256, 2 = 128x128).
+ * 1 = target workgroup count of the decode kernels, 2 = prefill tile (1 = 256x256, 2 = 128x128),
+ * 3 = waves per decode workgroup (4 or 8).
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);
 

@@ -55,7 +55,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
     hipError_t e;
     if (M <= kDecodeMaxM) {
         const DecodePlan pl = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
-        if (pl.tiles > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
+        if (pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
         DecodeArgs a;
         a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
         a.M = M; a.K = K; a.N = N; a.S = pl.S;

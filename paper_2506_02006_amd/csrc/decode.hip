@@ -2,77 +2,118 @@
 // record, bound by the rate at which the weights stream out of HBM.
 //
 // Shape of the computation
-//   * Every weight is read from memory exactly once, in its stored row-major layout, with
-//     full 128-byte (W4: 16 lanes x 8 B) or 256-byte (fp16: 16 lanes x 16 B) runs per row.
-//   * The multiply-accumulate runs on the matrix cores even at M = 1 (rows of x beyond M read
-//     as zero): v_mfma_f32_16x16x32_f16 with x as the A operand and the weights as B.  The B
-//     operand wants, per lane, 8 consecutive k of ONE column, while a packed word holds 8
-//     consecutive columns of ONE k.  A lane therefore loads the same word position from 8
-//     consecutive rows and regroups bytes across those rows (v_perm_b32); MFMA number j of a
-//     word then produces the output columns 8c + j.  The vector ALU only unpacks.
-//   * int4 -> fp16 without conversions: OR the nibble into the mantissa of 1024.0 and subtract
-//     (1024 + z) exactly in packed fp16; the high nibble of a byte lands as 1024 + 16 q and is
-//     brought back with one exact fma (x/16 - (64 + z)).  The group scale is applied once per
-//     group of 128 rows to the fp32 accumulators (M <= 32) or per weight in fp16 (M > 32, where
-//     a second accumulator set would not fit in registers).
-//   * K is split over the waves of a workgroup and over S workgroups per column tile.  Waves
-//     combine through LDS in a fixed order; workgroups write fp32 partials and the last one to
-//     arrive (atomic counter) adds them in index order, so results do not depend on timing.
+//   * Every weight is read from memory once, in its stored row-major layout, in full 128-byte
+//     (W4) or 256-byte (fp16) runs per row, three k-steps (of 32 rows) ahead of its use: a ring of
+//     four register stages in a loop unrolled by four, so that every slot issues a fixed number of
+//     loads and the wait counts are exact.
+//   * The multiply-accumulate runs on the matrix cores even at M = 1 (rows of x beyond M read as
+//     zero): v_mfma_f32_16x16x32_f16 with x as the A operand and the weights as B.  The B operand
+//     wants, per lane, 8 consecutive k of ONE column, while a packed word holds 8 consecutive
+//     columns of ONE k.  A lane therefore loads the same word position from 8 consecutive rows and
+//     pairs bytes across rows (v_perm_b32); MFMA number j of a word produces output column 8c + j.
+//   * W4 codes enter the MFMA without any conversion: a 16-bit lane holding the byte
+//     (16 q_hi + q_lo) IS the fp16 subnormal (16 q_hi + q_lo) * 2^-24, which the matrix core
+//     multiplies exactly.  Per byte two MFMAs run: one on the whole byte, one on the byte masked
+//     to its high nibble; their difference is the low-nibble column.  A third operand of ones
+//     gives the per-group row sums of x.  The four unrolled slots are one quantization group
+//     (128 rows): its first MFMA starts from zero and after its last the fp32 group sums are folded
+//     into the running result,  y += s * (2^24 * acc - z * rowsum(x)),  which lives in LDS (one
+//     private, lane-interleaved region per wave) so that the kernel stays under 256 registers and
+//     two waves share each SIMD.  The vector ALU does one permute and one AND per four weights
+//     plus that fold.
+//   * K is split over the waves of a workgroup and over S workgroups per column tile.  Waves are
+//     summed out of LDS in a fixed order; workgroups write fp32 partials (written through to
+//     memory) and the last one to arrive, found with an atomic counter, adds them in index order,
+//     so results do not depend on timing.  Rows above 32 are handled by a second slice of the
+//     grid (blockIdx.y) running the same kernel on rows 32..63.
 #include "dev_common.h"
 #include "kernels.h"
 
 namespace morph {
 
+// Optional phase timestamps for tuning builds (-DMORPH_TIMING): thread 0 of every workgroup stores
+// the shader clock and the 100 MHz wall clock at a few points.  Compiled out of the product library.
+#ifdef MORPH_TIMING
+__device__ unsigned long long g_ticks[8192 * 16];
+#define MORPH_TICK(i)                                                                          \
+    do {                                                                                       \
+        if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < 8192) {                        \
+            g_ticks[blockIdx.x * 16 + 2 * (i)]     = __builtin_readcyclecounter();             \
+            g_ticks[blockIdx.x * 16 + 2 * (i) + 1] = wall_clock64();                           \
+        }                                                                                      \
+    } while (0)
+#else
+#define MORPH_TICK(i) do { } while (0)
+#endif
+
 namespace {
 
-constexpr int kWaves = 4;
+constexpr int NS     = 4;            // register stages: the k-step being computed and three in flight
 
-template <bool W4> struct Tile;
-template <> struct Tile<true>  { static constexpr int CPL = 16; static constexpr int TN = 256; };  // cols per lane / tile
-template <> struct Tile<false> { static constexpr int CPL = 8;  static constexpr int TN = 128; };
+// Columns per lane (CPL) and per wave (TN = 16 lanes x CPL).  W4 with one M tile reads two packed
+// words per lane and row (128-byte runs per wave); with two M tiles a wave takes one word per lane
+// and two waves of a workgroup sit side by side (WN = 2) on the same rows, covering the 128-byte
+// run together.  Workgroup tile = WN * TN columns; the other kWaves / WN waves split K.
+template <bool W4, int MT> struct Tile;
+template <> struct Tile<true, 1>  { static constexpr int WPL = 2, CPL = 16, TN = 256, WN = 1; };
+template <> struct Tile<true, 2>  { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 2; };
+template <> struct Tile<false, 1> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 1; };
+template <> struct Tile<false, 2> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 1; };
+
+template <int WPL>
+struct GroupRaw {                // scale / zero data of one group for this lane's 8 WPL columns
+    uint32_t zq[WPL];
+    u32x4    sc[WPL];
+};
 
 // One k-step (32 rows) of operands as they arrive from memory.
-template <bool W4, int MT>
+template <bool W4, int MT, int WPL>
 struct Stage {
-    u32x2   w4[W4 ? 8 : 1];      // W4:   row i -> 2 packed words (16 columns)
-    u32x4   wh[W4 ? 1 : 8];      // fp16: row i -> 8 halfs (8 columns)
-    half8_t a[MT];               // x rows (lane & 15) + 16 mt, 8 consecutive k
+    uint32_t w4[W4 ? 8 : 1][WPL];  // W4:   row i -> WPL packed words (8 WPL columns)
+    u32x4    wh[W4 ? 1 : 8];       // fp16: row i -> 8 halfs (8 columns)
+    half8_t  a[MT];                // x rows (lane & 15) + 16 mt, 8 consecutive k
 };
 
-struct GroupRaw {                // scale / zero data of one group for this lane's 16 columns
-    u32x2 zq;
-    u32x4 sc[2];
-};
-
-template <bool W4, int MT, bool GROUP_SCALE>
-__global__ __launch_bounds__(kWaves * 64) void decode_kernel(DecodeArgs p)
+template <bool W4, int MT, int kWaves>
+__global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kernel(DecodeArgs p)
 {
-    constexpr int CPL = Tile<W4>::CPL;
-    constexpr int TN  = Tile<W4>::TN;
-    constexpr int LDP = TN + 4;                          // LDS row pitch in floats
-    extern __shared__ __align__(16) float red[];         // [MT * 16][LDP]
-    __shared__ int s_last;
+    constexpr int WPL = Tile<W4, MT>::WPL;
+    constexpr int CPL = Tile<W4, MT>::CPL;
+    constexpr int TN  = Tile<W4, MT>::TN;
+    constexpr int WN  = Tile<W4, MT>::WN, WK = kWaves / WN;
+    constexpr int TNB = TN * WN;                         // columns of the workgroup tile
+    constexpr int NV  = MT * CPL;                        // f32x4 result vectors per lane
+    typedef Stage<W4, MT, WPL> StageT;
+    // Result vectors in LDS: [wave][v][lane] f32x4; vector v = mt * CPL + j holds rows
+    // 16 mt + 4 (lane >> 4) + r (r = 0..3) of column CPL (lane & 15) + j of the wave's columns.
+    extern __shared__ __align__(16) f32x4 yl[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // The wave index is the same in all 64 lanes: say so, so that everything derived from it (this
+    // wave's k range, the scalar offsets of its loads) lives in scalar registers.
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, b = lane >> 4;
     const int S = p.S;
     const int nt = blockIdx.x / S, sp = blockIdx.x - nt * S;
-    const int n0 = nt * TN;
-    const int M = p.M, K = p.K, N = p.N, NW = N >> 3;
+    const int n0 = nt * TNB;                             // first column of the workgroup tile
+    const int wn = wave % WN, wk = wave / WN;            // this wave's column part and k part
+    const int mbase = blockIdx.y * 32;                   // first row of this slice
+    const int M = (p.M - mbase) < MT * 16 ? (p.M - mbase) : MT * 16;   // rows of this slice
+    const int K = p.K, N = p.N, NW = N >> 3;
     const int T  = K >> 5;                               // k-steps of 32 rows
-    const int TW = S * kWaves;
-    const int gw = sp * kWaves + wave;
+    const int TW = S * WK;
+    const int gw = sp * WK + wk;
     const int ks0 = (int)(((long long)gw * T) / TW);
     const int ks1 = (int)(((long long)(gw + 1) * T) / TW);
 
     const uint32_t row_bytes = W4 ? (uint32_t)NW * 4u : (uint32_t)N * 2u;
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (uint32_t)K * row_bytes);
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (uint32_t)M * (uint32_t)K * 2u);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc((const half_t*)p.x + (size_t)mbase * K, (uint32_t)M * (uint32_t)K * 2u);
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.scales, W4 ? (uint32_t)(K / kGroup) * (uint32_t)N * 2u : 0u);
     const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.qzeros, W4 ? (uint32_t)(K / kGroup) * (uint32_t)NW * 4u : 0u);
 
     // This lane's first column; lanes that start beyond N read nothing (offset past the buffer).
-    const int  ncol   = n0 + CPL * c;
+    const int  ncol   = n0 + wn * TN + CPL * c;
     const bool col_ok = ncol < N;
     const uint32_t kOut = 0xFFFFFFF0u;
     // W4: column n sits at byte n/2 of its row (8 columns per 4-byte word); fp16: at byte 2n.
@@ -84,101 +125,97 @@ __global__ __launch_bounds__(kWaves * 64) void decode_kernel(DecodeArgs p)
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) voff_a[mt] = ((uint32_t)(mt * 16 + c) * (uint32_t)K + 8u * b) * 2u;
 
-    auto load_stage = [&](Stage<W4, MT>& st, int ks) {
-        const uint32_t so = (uint32_t)ks * 32u * row_bytes;
+    // Loads of k-step ks.  A step outside [ks0, ks1) is "dead": its offsets are pushed past the
+    // buffers, so the loads still issue (every slot issues the same number) but return zeros
+    // without touching memory.
+    auto load_stage = [&](StageT& st, int ks) {
+        const bool     dead = ks < ks0 || ks >= ks1;
+        const uint32_t dm   = dead ? kOut : 0u;
+        const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
+        const uint32_t vw   = voff_w | dm;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            if constexpr (W4) st.w4[i] = buf_load_u32x2(rw, voff_w, so + (uint32_t)i * row_bytes);
-            else              st.wh[i] = buf_load_u32x4(rw, voff_w, so + (uint32_t)i * row_bytes);
+            if constexpr (W4 && WPL == 2) {
+                const u32x2 v = buf_load_u32x2(rw, vw, so + (uint32_t)i * row_bytes);
+                st.w4[i][0] = v[0];
+                st.w4[i][WPL - 1] = v[1];
+            } else if constexpr (W4) {
+                st.w4[i][0] = buf_load_u32(rw, vw, so + (uint32_t)i * row_bytes);
+            } else {
+                st.wh[i] = buf_load_u32x4(rw, vw, so + (uint32_t)i * row_bytes);
+            }
         }
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
-            st.a[mt] = bit_cast<half8_t>(buf_load_u32x4(rx, voff_a[mt], (uint32_t)ks * 64u));
+            st.a[mt] = bit_cast<half8_t>(buf_load_u32x4(rx, voff_a[mt] | dm, dead ? 0u : (uint32_t)ks * 64u));
     };
-    auto load_group = [&](GroupRaw& gr, int g) {
-        gr.zq    = buf_load_u32x2(rz, voff_z, (uint32_t)g * (uint32_t)NW * 4u);
-        gr.sc[0] = buf_load_u32x4(rs, voff_s, (uint32_t)g * (uint32_t)N * 2u);
-        gr.sc[1] = buf_load_u32x4(rs, voff_s, (uint32_t)g * (uint32_t)N * 2u + 16u);
+    // Scales and zero points of group g (dead when the group lies outside this wave's k range).
+    auto load_group = [&](GroupRaw<WPL>& gr, int g) {
+        const bool     dead = 4 * g + 3 < ks0 || 4 * g >= ks1;
+        const uint32_t gm   = dead ? kOut : 0u;
+        const uint32_t gg   = dead ? 0u : (uint32_t)g;
+        if constexpr (WPL == 2) {
+            const u32x2 v = buf_load_u32x2(rz, voff_z | gm, gg * (uint32_t)NW * 4u);
+            gr.zq[0] = v[0];
+            gr.zq[WPL - 1] = v[1];
+        } else {
+            gr.zq[0] = buf_load_u32(rz, voff_z | gm, gg * (uint32_t)NW * 4u);
+        }
+#pragma unroll
+        for (int t = 0; t < WPL; t++)
+            gr.sc[t] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u + 16u * t);
     };
 
-    f32x4 yacc[MT][CPL];
-    f32x4 gacc[(W4 && GROUP_SCALE) ? MT : 1][(W4 && GROUP_SCALE) ? CPL : 1];
+    // Accumulators.  Lane (c, b) holds rows 16 mt + 4 b + r (r = 0..3) of column CPL c + j.
+    //   W4:   gacc[mt][t*8 + 2yb]     = sum x * byte        (byte = 16 q_hi + q_lo, times 2^-24)
+    //         gacc[mt][t*8 + 2yb + 1] = sum x * 16 q_hi     (times 2^-24)
+    //         xs[mt]                  = sum x               over the open group
+    //   fp16: gacc[mt][j] is the result itself.
+    f32x4 gacc[MT][CPL];
+    f32x4 xs[W4 ? MT : 1];
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int mt = 0; mt < MT; mt++)
 #pragma unroll
-        for (int j = 0; j < CPL; j++) yacc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if constexpr (W4 && GROUP_SCALE) {
+        for (int j = 0; j < CPL; j++) gacc[mt][j] = zero4;
+    if constexpr (W4) {
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++)
+        for (int mt = 0; mt < MT; mt++) xs[mt] = zero4;
+    }
+    f32x4* ymine = yl + (size_t)wave * NV * 64 + lane;    // vector v at ymine[v * 64]
+    if constexpr (W4) {
 #pragma unroll
-            for (int j = 0; j < CPL; j++) gacc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int v = 0; v < NV; v++) ymine[v * 64] = zero4;
     }
 
-    // Per-group constants for this lane's 16 columns (W4 only):
-    //   czl[t][y] = -(1024 + z) twice (column 8t + 2y),  czh[t][y] = -(64 + z) twice (column 8t + 2y + 1)
-    //   sc: the 16 scales, kept as fp16 pairs
-    half2_t czl[2][4], czh[2][4];
-    u32x4   sc_cur[2];
-    auto set_group = [&](const GroupRaw& gr) {
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-            const uint32_t zw = gr.zq[t];
-            uint32_t d;
-            d = pair_bytes<0>(zw, zw); czl[t][0] = bit_cast<half2_t>((d & 0x000F000Fu) | 0xE400E400u); czh[t][0] = bit_cast<half2_t>((d & 0x00F000F0u) | 0xD400D400u);
-            d = pair_bytes<1>(zw, zw); czl[t][1] = bit_cast<half2_t>((d & 0x000F000Fu) | 0xE400E400u); czh[t][1] = bit_cast<half2_t>((d & 0x00F000F0u) | 0xD400D400u);
-            d = pair_bytes<2>(zw, zw); czl[t][2] = bit_cast<half2_t>((d & 0x000F000Fu) | 0xE400E400u); czh[t][2] = bit_cast<half2_t>((d & 0x00F000F0u) | 0xD400D400u);
-            d = pair_bytes<3>(zw, zw); czl[t][3] = bit_cast<half2_t>((d & 0x000F000Fu) | 0xE400E400u); czh[t][3] = bit_cast<half2_t>((d & 0x00F000F0u) | 0xD400D400u);
-        }
-        sc_cur[0] = gr.sc[0];
-        sc_cur[1] = gr.sc[1];
-    };
-    auto scale_of = [&](int col) -> half_t {             // col in 0..15 of this lane
-        const uint32_t wbits = sc_cur[col >> 3][(col & 7) >> 1];
-        return bit_cast<half_t>((uint16_t)((col & 1) ? (wbits >> 16) : (wbits & 0xFFFFu)));
-    };
-
-    auto compute = [&](const Stage<W4, MT>& st) {
+    // One k-step.  `first` (known at compile time: slot 0 of the unrolled group) starts the group
+    // sums from zero instead of adding to them.
+    auto compute = [&](const StageT& st, bool first) {
         if constexpr (W4) {
-            const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
+            const half_t  one  = (half_t)1.0f;
+            const half8_t ones = {one, one, one, one, one, one, one, one};
 #pragma unroll
-            for (int t = 0; t < 2; t++) {
+            for (int mt = 0; mt < MT; mt++)
+                xs[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], ones, first ? zero4 : xs[mt], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < WPL; t++) {
 #pragma unroll
                 for (int yb = 0; yb < 4; yb++) {
-                    uint32_t pr[4];
+                    uint32_t pr[4], ph[4];
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
                         const uint32_t r0 = st.w4[2 * q][t], r1 = st.w4[2 * q + 1][t];
                         pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
                               : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                        ph[q] = pr[q] & 0x00F000F0u;
                     }
-                    half2_t lo[4], hi[4];
-#pragma unroll
-                    for (int q = 0; q < 4; q++) {
-                        lo[q] = nib_lo_1024(pr[q]) + czl[t][yb];                      // q - z, exact
-                        hi[q] = nib_hi_1024(pr[q]) * sixteenth + czh[t][yb];          // q - z, exact
-                    }
-                    if constexpr (!GROUP_SCALE) {
-                        const half_t s0 = scale_of(t * 8 + 2 * yb), s1 = scale_of(t * 8 + 2 * yb + 1);
-                        const half2_t s0p = {s0, s0}, s1p = {s1, s1};
-#pragma unroll
-                        for (int q = 0; q < 4; q++) { lo[q] = lo[q] * s0p; hi[q] = hi[q] * s1p; }
-                    }
-                    half8_t blo, bhi;
-#pragma unroll
-                    for (int q = 0; q < 4; q++) {
-                        blo[2 * q] = lo[q][0]; blo[2 * q + 1] = lo[q][1];
-                        bhi[2 * q] = hi[q][0]; bhi[2 * q + 1] = hi[q][1];
-                    }
+                    const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
+                    const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
                     const int j0 = t * 8 + 2 * yb;
 #pragma unroll
                     for (int mt = 0; mt < MT; mt++) {
-                        if constexpr (GROUP_SCALE) {
-                            gacc[mt][j0]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], blo, gacc[mt][j0], 0, 0, 0);
-                            gacc[mt][j0 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bhi, gacc[mt][j0 + 1], 0, 0, 0);
-                        } else {
-                            yacc[mt][j0]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], blo, yacc[mt][j0], 0, 0, 0);
-                            yacc[mt][j0 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bhi, yacc[mt][j0 + 1], 0, 0, 0);
-                        }
+                        gacc[mt][j0]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bbyte, first ? zero4 : gacc[mt][j0], 0, 0, 0);
+                        gacc[mt][j0 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bhigh, first ? zero4 : gacc[mt][j0 + 1], 0, 0, 0);
                     }
                 }
             }
@@ -196,164 +233,235 @@ __global__ __launch_bounds__(kWaves * 64) void decode_kernel(DecodeArgs p)
                 const half8_t bo = bit_cast<half8_t>(u32x4{o[0], o[1], o[2], o[3]});
 #pragma unroll
                 for (int mt = 0; mt < MT; mt++) {
-                    yacc[mt][2 * jj]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], be, yacc[mt][2 * jj], 0, 0, 0);
-                    yacc[mt][2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bo, yacc[mt][2 * jj + 1], 0, 0, 0);
-                }
-            }
-        }
-    };
-    auto flush_group = [&]() {
-        if constexpr (W4 && GROUP_SCALE) {
-#pragma unroll
-            for (int j = 0; j < CPL; j++) {
-                const float s = (float)scale_of(j);
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) {
-#pragma unroll
-                    for (int r = 0; r < 4; r++) yacc[mt][j][r] = __builtin_fmaf(s, gacc[mt][j][r], yacc[mt][j][r]);
-                    gacc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    gacc[mt][2 * jj]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], be, gacc[mt][2 * jj], 0, 0, 0);
+                    gacc[mt][2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bo, gacc[mt][2 * jj + 1], 0, 0, 0);
                 }
             }
         }
     };
 
-    // ---- main loop over this wave's k-steps, operands fetched one step ahead ----
-    Stage<W4, MT> cur, nxt;
-    GroupRaw      gnext;
-    if (ks0 < ks1) {
-        load_stage(cur, ks0);
-        if constexpr (W4) { load_group(gnext, ks0 >> 2); set_group(gnext); }
-    }
-    for (int ks = ks0; ks < ks1; ks++) {
-        const bool more      = ks + 1 < ks1;
-        const bool group_end = ((ks + 1) & 3) == 0;
-        if (more) {
-            load_stage(nxt, ks + 1);
-            if constexpr (W4) { if (group_end) load_group(gnext, (ks + 1) >> 2); }
-        }
-        compute(cur);
+    // Fold the group sums into the running result in LDS:
+    //   low-nibble column:  y += s * (2^24 (acc_byte - acc_high) - z_lo * xs)
+    //   high-nibble column: y += s * (2^20  acc_high             - z_hi * xs)
+    auto flush_group = [&](const GroupRaw<WPL>& gr) {
         if constexpr (W4) {
-            if (group_end || !more) flush_group();
-            if (group_end && more) set_group(gnext);
-        }
-        if (more) cur = nxt;
-    }
-
-    // ---- combine the waves of this workgroup in LDS, wave 0 first, then 1, 2, 3 ----
-    // Lane (c, b) holds rows 16 mt + 4 b + r and columns CPL c + j of the tile.
-    for (int wv = 0; wv < kWaves; wv++) {
-        if (wave == wv) {
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++)
+            for (int t = 0; t < WPL; t++) {
+                const uint32_t zw  = gr.zq[t];
+                const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = (zw >> 4) & 0x0F0F0F0Fu;
 #pragma unroll
-                for (int r = 0; r < 4; r++) {
-                    float* rowp = red + (mt * 16 + 4 * b + r) * LDP + CPL * c;
+                for (int yb = 0; yb < 4; yb++) {
+                    const uint32_t sw  = gr.sc[t][yb];       // scales of columns 8t + 2yb, 8t + 2yb + 1
+                    const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+                    const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+                    const float z_lo = (float)((zlo >> (8 * yb)) & 0xFFu);
+                    const float z_hi = (float)((zhi >> (8 * yb)) & 0xFFu);
+                    const float a_lo = s_lo * 16777216.0f, a_hi = s_hi * 1048576.0f;
+                    const float c_lo = -s_lo * z_lo, c_hi = -s_hi * z_hi;
+                    const int j0 = t * 8 + 2 * yb;
 #pragma unroll
-                    for (int j4 = 0; j4 < CPL / 4; j4++) {
-                        f32x4 v = {yacc[mt][4 * j4][r], yacc[mt][4 * j4 + 1][r], yacc[mt][4 * j4 + 2][r], yacc[mt][4 * j4 + 3][r]};
-                        f32x4* q = reinterpret_cast<f32x4*>(rowp + 4 * j4);
-                        if (wv > 0) v += *q;
-                        *q = v;
+                    for (int mt = 0; mt < MT; mt++) {
+                        f32x4 y0 = ymine[(mt * CPL + j0) * 64], y1 = ymine[(mt * CPL + j0 + 1) * 64];
+#pragma unroll
+                        for (int r = 0; r < 4; r++) {
+                            const float d = gacc[mt][j0][r] - gacc[mt][j0 + 1][r];
+                            y0[r] = __builtin_fmaf(c_lo, xs[mt][r], __builtin_fmaf(a_lo, d, y0[r]));
+                            y1[r] = __builtin_fmaf(c_hi, xs[mt][r], __builtin_fmaf(a_hi, gacc[mt][j0 + 1][r], y1[r]));
+                        }
+                        ymine[(mt * CPL + j0) * 64]     = y0;
+                        ymine[(mt * CPL + j0 + 1) * 64] = y1;
                     }
                 }
-        }
-        __syncthreads();
-    }
-
-    // ---- write out: fp16 result directly (S == 1) or an fp32 partial for the last arriver ----
-    constexpr int VPR = TN / 4;                          // float4 vectors per tile row
-    half_t* y = (half_t*)p.y;
-    if (S == 1) {
-        for (int v = tid; v < MT * 16 * VPR; v += kWaves * 64) {
-            const int row = v / VPR, cv = v - row * VPR, col = n0 + 4 * cv;
-            if (row < M && col < N) {
-                const f32x4 f = *reinterpret_cast<const f32x4*>(red + row * LDP + 4 * cv);
-                half4_t h = {(half_t)f[0], (half_t)f[1], (half_t)f[2], (half_t)f[3]};
-                *reinterpret_cast<half4_t*>(y + (size_t)row * N + col) = h;
             }
         }
+    };
+
+    // ---- main loop: groups of four k-steps, loads three steps ahead of compute ----
+    MORPH_TICK(0);
+    const int g0 = ks0 >> 2, g1 = (ks1 + 3) >> 2;        // groups touched by [ks0, ks1)
+    StageT        buf[NS];
+    GroupRaw<WPL> gcur, gnext;
+    if constexpr (W4) load_group(gnext, g0);
+#pragma unroll
+    for (int i = 0; i < NS - 1; i++) {
+        load_stage(buf[i], 4 * g0 + i);
+        __builtin_amdgcn_sched_barrier(0);               // keep the stages in issue order: the waits count on it
+    }
+    for (int g = g0; g < g1; g++) {
+        if constexpr (W4) gcur = gnext;
+#pragma unroll
+        for (int u = 0; u < NS; u++) {
+            const int k = 4 * g + u;                     // step computed in this slot
+            load_stage(buf[(u + NS - 1) % NS], k + NS - 1);
+            if constexpr (W4) {
+                if (u == 1) load_group(gnext, g + 1);    // arrives well before the next group opens
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // A dead step holds zeros in x and in the weights and adds nothing; computing it anyway
+            // keeps the slot free of branches.
+            compute(buf[u], u == 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (W4) flush_group(gcur);
+    }
+    MORPH_TICK(1);
+
+    // ---- sum the waves that share columns (in the order of their k parts) and write out ----
+    if constexpr (!W4) {
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int j = 0; j < CPL; j++) ymine[(mt * CPL + j) * 64] = gacc[mt][j];
+    }
+    __syncthreads();
+    MORPH_TICK(2);
+    constexpr int ITEMS = WN * NV * 64;                  // f32x4 vectors of the workgroup tile
+    half_t* y = (half_t*)p.y + (size_t)mbase * N;
+    auto item_sum = [&](int it) {
+        const int pn = it / (NV * 64), rem = it - pn * (NV * 64);    // column part, (v, lane)
+        f32x4 acc = yl[(size_t)pn * NV * 64 + rem];                  // wave with wk = 0
+#pragma unroll
+        for (int q = 1; q < WK; q++) acc += yl[(size_t)(q * WN + pn) * NV * 64 + rem];
+        return acc;
+    };
+    auto item_store_y = [&](int it, f32x4 acc) {
+        const int pn = it / (NV * 64), rem = it - pn * (NV * 64);
+        const int v = rem >> 6, ln = rem & 63;
+        const int mt = v / CPL, j = v - mt * CPL;
+        const int col = n0 + pn * TN + CPL * (ln & 15) + j;
+        const int row = 16 * mt + 4 * (ln >> 4);
+        if (col < N) {
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (row + r < M) y[(size_t)(row + r) * N + col] = (half_t)acc[r];
+        }
+    };
+    auto item_rows_live = [&](int it) {                  // does the vector hold any row below M?
+        const int rem = it % (NV * 64), v = rem >> 6, ln = rem & 63;
+        return 16 * (v / CPL) + 4 * (ln >> 4) < M;
+    };
+    if (S == 1) {
+        for (int it = tid; it < ITEMS; it += kWaves * 64)
+            if (item_rows_live(it)) item_store_y(it, item_sum(it));
         return;
     }
-    float* part = p.partial + ((size_t)nt * S + sp) * (size_t)M * TN;
-    for (int v = tid; v < M * VPR; v += kWaves * 64) {
-        const int row = v / VPR, cv = v - row * VPR;
-        *reinterpret_cast<f32x4*>(part + (size_t)row * TN + 4 * cv) =
-            *reinterpret_cast<const f32x4*>(red + row * LDP + 4 * cv);
-    }
-    __threadfence();
+    // Partials cross workgroups that may sit on different XCDs (separate L2s).  They are written
+    // through to memory and read past the caches (scope bits on the instructions), which is all the
+    // ordering needs: wait for the stores, count the arrival, and the last arriver reads.  No
+    // whole-cache write-back or invalidate is issued.  Layout: [tile][split][item] f32x4.
+    const int tile_id = blockIdx.y * (gridDim.x / S) + nt;           // slices keep separate counters and partials
+    constexpr uint32_t kPartBytes = (uint32_t)ITEMS * 16u;           // one workgroup's partial
+    const float* tile_base = p.partial + (size_t)tile_id * S * ITEMS * 4;
+    const __amdgpu_buffer_rsrc_t rp = make_rsrc(tile_base, (uint32_t)S * kPartBytes);
+    for (int it = tid; it < ITEMS; it += kWaves * 64)
+        if (item_rows_live(it)) buf_store_through(rp, (uint32_t)sp * kPartBytes + (uint32_t)it * 16u, item_sum(it));
+    wait_stores();
+    MORPH_TICK(3);
+    __syncthreads();                                     // every wave is done reading yl
+    int* flag = reinterpret_cast<int*>(yl);
+    if (tid == 0) *flag = (atomicAdd(p.counters + tile_id, 1) == S - 1) ? 1 : 0;
     __syncthreads();
-    if (tid == 0) s_last = (atomicAdd(p.counters + nt, 1) == S - 1) ? 1 : 0;
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    const float* base = p.partial + (size_t)nt * S * (size_t)M * TN;
-    for (int v = tid; v < M * VPR; v += kWaves * 64) {
-        const int row = v / VPR, cv = v - row * VPR, col = n0 + 4 * cv;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int s2 = 0; s2 < S; s2++)
-            acc += *reinterpret_cast<const f32x4*>(base + ((size_t)s2 * M + row) * TN + 4 * cv);
-        if (col < N) {
-            half4_t h = {(half_t)acc[0], (half_t)acc[1], (half_t)acc[2], (half_t)acc[3]};
-            *reinterpret_cast<half4_t*>(y + (size_t)row * N + col) = h;
-        }
+    MORPH_TICK(4);
+    if (!*flag) return;
+    // All loads of a thread's items are independent: they are issued together and summed in index
+    // order (split 0 first), so the result does not depend on which workgroup arrived last.
+    constexpr int IPT = ITEMS / (kWaves * 64);           // items per thread
+    f32x4 acc[IPT];
+#pragma unroll
+    for (int i = 0; i < IPT; i++) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s2 = 0; s2 < S; s2 += 4) {
+        f32x4 v[4][IPT];
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+#pragma unroll
+            for (int i = 0; i < IPT; i++) {
+                // splits beyond S read past the buffer and come back as zeros
+                v[q][i] = buf_load_through(rp, (uint32_t)(s2 + q) * kPartBytes + (uint32_t)(tid + i * kWaves * 64) * 16u);
+            }
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+#pragma unroll
+            for (int i = 0; i < IPT; i++) acc[i] += v[q][i];
     }
-    if (tid == 0) atomicExch(p.counters + nt, 0);
+#pragma unroll
+    for (int i = 0; i < IPT; i++) {
+        const int it = tid + i * kWaves * 64;
+        if (item_rows_live(it)) item_store_y(it, acc[i]);
+    }
+    if (tid == 0) atomicExch(p.counters + tile_id, 0);
+    MORPH_TICK(5);
 }
 
-template <bool W4, int MT, bool GS>
-hipError_t launch_one(const DecodeArgs& a, int tiles, hipStream_t st)
+inline int decode_waves() { return tuning_get(TUNE_DECODE_WAVES) == 8 ? 8 : 4; }
+
+template <bool W4, int MT, int kWaves>
+hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
 {
-    constexpr size_t lds = (size_t)MT * 16 * (Tile<W4>::TN + 4) * sizeof(float);
-    if (lds > 48 * 1024) {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<W4, MT, GS>),
+    constexpr int tnb = Tile<W4, MT>::TN * Tile<W4, MT>::WN;
+    constexpr size_t lds = (size_t)kWaves * MT * Tile<W4, MT>::CPL * 64 * sizeof(f32x4);
+    static_assert(lds <= 128 * 1024, "LDS of one compute unit");
+    if (lds > 64 * 1024) {
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<W4, MT, kWaves>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (attr != hipSuccess) return attr;
     }
-    hipLaunchKernelGGL((decode_kernel<W4, MT, GS>), dim3(tiles * a.S), dim3(kWaves * 64), lds, st, a);
+    const int tiles = (a.N + tnb - 1) / tnb;
+    hipLaunchKernelGGL((decode_kernel<W4, MT, kWaves>), dim3(tiles * a.S, slices), dim3(kWaves * 64), lds, st, a);
     return hipGetLastError();
+}
+
+template <bool W4, int MT>
+hipError_t launch_one(const DecodeArgs& a, int slices, hipStream_t st)
+{
+    return decode_waves() == 8 ? launch_waves<W4, MT, 8>(a, slices, st) : launch_waves<W4, MT, 4>(a, slices, st);
 }
 
 }  // namespace
 
+#ifdef MORPH_TIMING
+extern "C" int morph_debug_read_ticks(unsigned long long* host_out, int n)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_ticks), sizeof(unsigned long long) * n);
+}
+extern "C" int morph_debug_clear_ticks()
+{
+    static unsigned long long z[8192 * 16];
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_ticks), z, sizeof(z));
+}
+#endif
+
 DecodePlan plan_decode(int is_w4, int M, int K, int N)
 {
     DecodePlan pl;
-    pl.tile_n = is_w4 ? Tile<true>::TN : Tile<false>::TN;
+    pl.tile_n = !is_w4 ? Tile<false, 1>::TN : 256;      // workgroup tile (W4: 1 x 256 or 2 x 128 columns)
+    const int kWaves = decode_waves();
+    const int wk = (is_w4 && M > 16) ? kWaves / Tile<true, 2>::WN : kWaves;   // waves of a workgroup along K
     pl.tiles  = (N + pl.tile_n - 1) / pl.tile_n;
+    pl.slices = (M + 31) / 32;
     const int T = K / 32;
     int target = tuning_get(TUNE_DECODE_WGS);
-    if (target <= 0) target = 512;                       // about two workgroups per compute unit
-    int S = (target + pl.tiles / 2) / pl.tiles;
-    int smax = T / (kWaves * 2);                          // at least two k-steps per wave
+    if (target <= 0) target = 256;                       // one workgroup per compute unit
+    const int units = pl.tiles * pl.slices;
+    int S = target / units;                              // never more workgroups than are resident at once
+    int smax = T / (wk * 4);                              // at least one group of four k-steps per wave
     if (S > smax) S = smax;
     if (S > 64) S = 64;
     const int forced = tuning_get(TUNE_DECODE_SPLIT);
-    if (forced > 0) S = forced > T / kWaves ? T / kWaves : forced;
+    if (forced > 0) S = forced > T / wk ? T / wk : forced;
     if (S < 1) S = 1;
     pl.S = S;
-    pl.partial_bytes = S > 1 ? (size_t)pl.tiles * S * M * pl.tile_n * sizeof(float) : 0;
+    // items of one workgroup tile: 16 rows x MT x tile columns, as fp32
+    const size_t tile_floats = (size_t)(M <= 16 ? 16 : 32) * pl.tile_n;
+    pl.partial_bytes = S > 1 ? (size_t)units * S * tile_floats * sizeof(float) : 0;
     return pl;
 }
 
 hipError_t launch_decode(int is_w4, const DecodeArgs& a, hipStream_t st)
 {
-    const int tn    = is_w4 ? Tile<true>::TN : Tile<false>::TN;
-    const int tiles = (a.N + tn - 1) / tn;
-    const int mt    = (a.M + 15) / 16;
-    if (is_w4) {
-        switch (mt) {
-            case 1: return launch_one<true, 1, true>(a, tiles, st);
-            case 2: return launch_one<true, 2, true>(a, tiles, st);
-            case 3: return launch_one<true, 3, false>(a, tiles, st);
-            default: return launch_one<true, 4, false>(a, tiles, st);
-        }
-    }
-    switch (mt) {
-        case 1: return launch_one<false, 1, false>(a, tiles, st);
-        case 2: return launch_one<false, 2, false>(a, tiles, st);
-        case 3: return launch_one<false, 3, false>(a, tiles, st);
-        default: return launch_one<false, 4, false>(a, tiles, st);
-    }
+    const int slices = (a.M + 31) / 32;
+    const bool one   = a.M <= 16;                        // a single 16-row MFMA tile
+    if (is_w4) return one ? launch_one<true, 1>(a, slices, st) : launch_one<true, 2>(a, slices, st);
+    return one ? launch_one<false, 1>(a, slices, st) : launch_one<false, 2>(a, slices, st);
 }
 
 }  // namespace morph

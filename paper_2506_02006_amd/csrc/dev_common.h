@@ -64,6 +64,23 @@ __device__ __forceinline__ half2_t nib_hi_1024(uint32_t p)
     return bit_cast<half2_t>((p & 0x00F000F0u) | 0x64006400u);
 }
 
+// 16-byte store written through to memory / load served past the caches (system-scope bits sc0 sc1
+// on the instruction), for data handed between workgroups inside one kernel.  wait_stores() returns
+// once every store of this wave has been acknowledged.
+constexpr int kAuxSystemScope = 0x11;    // cache-policy operand of the buffer builtins: sc0 | sc1
+__device__ __forceinline__ void buf_store_through(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(bit_cast<u32x4>(v), r, byte_off, 0, kAuxSystemScope);
+}
+__device__ __forceinline__ f32x4 buf_load_through(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return bit_cast<f32x4>(__builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kAuxSystemScope));
+}
+__device__ __forceinline__ void wait_stores()
+{
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+}
+
 __device__ __forceinline__ float h2f_bits(uint32_t bits16)
 {
     return (float)bit_cast<half_t>((uint16_t)bits16);

@@ -20,14 +20,15 @@ struct DecodeArgs {
     const void*     scales;    // fp16 [K/128,N]      (W4 only)
     const void*     qzeros;    // uint32 [K/128,N/8]  (W4 only)
     void*           y;         // fp16 [M,N]
-    float*          partial;   // [tiles][S][M][tile columns] fp32, used when S > 1
-    int*            counters;  // [tiles], zero on entry, zero on exit
+    float*          partial;   // [slices * tiles][S][32][tile columns] fp32, used when S > 1
+    int*            counters;  // [slices * tiles], zero on entry, zero on exit
     int             M, K, N;
     int             S;         // workgroups sharing one column tile (split along K)
 };
 struct DecodePlan {
     int    tile_n;             // columns per workgroup
     int    tiles;              // ceil(N / tile_n)
+    int    slices;             // ceil(M / 32): row slices, each run by its own part of the grid
     int    S;                  // split along K across workgroups
     size_t partial_bytes;      // 0 when S == 1
 };
@@ -54,6 +55,6 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_COUNT = 8 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_COUNT = 8 };
 
 }  // namespace morph

@@ -1,0 +1,220 @@
+"""GPU parity at the full sizes of the five benchmark configurations, in the launch configuration
+bench.py times (default kernel selection, workspace from morph_workspace_bytes).
+
+Decode sizes are compared element by element with the full fp64 oracle product.  The prefill
+configuration is compared on sampled outputs (rows and columns on both sides of every tile
+boundary plus seeded random positions), each computed by the oracle as a single fp64 dot
+product; its error is normalised by the largest sampled |y_ref|.  The 32-layer stack is checked
+per linear on the layer's actual fp16 input (copied back from the GPU) for a seeded subset of
+layers, whose weights are generated and quantized on the host by the oracle; the other layers
+only produce activations and are generated on the device.
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2506_02006_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+GLUE_TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2506_02006_amd import binding
+    binding.lib()
+    binding.warmup()
+    return binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def run_w4(B, oracle, x, rec_dev, rec_host, label):
+    M, K = x.shape
+    N = rec_host[1].shape[1]
+    ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
+    y = host(B.linear_w4a16(dev(x), *rec_dev, ws))
+    r = oracle.error_metric(y, oracle.linear_w4a16(x, *rec_host))
+    say(f"  {label} w4a16 M={M} K={K} N={N}: err={r['err']:.3e}")
+    assert r["finite"] and r["err"] <= TOL, (label, r)
+
+
+def run_fp16(B, oracle, x, w_dev, w_host, label):
+    M, K = x.shape
+    N = w_host.shape[1]
+    ws = B.new_workspace(B.workspace_bytes(B.KIND_FP16, M, K, N))
+    y = host(B.linear_fp16(dev(x), w_dev, ws))
+    r = oracle.error_metric(y, oracle.linear_fp16(x, w_host))
+    say(f"  {label} fp16  M={M} K={K} N={N}: err={r['err']:.3e}")
+    assert r["finite"] and r["err"] <= TOL, (label, r)
+
+
+def test_config1_single_linear(B, oracle):
+    K = N = 4096
+    W = synth.weights(1, K, N)
+    x = synth.activations(1, 1, K)
+    qw, sc, qz = oracle.quantize_w4(W)
+    gq, gs, gz = B.quantize_layer(dev(W))
+    assert np.array_equal(host(gq).view(np.uint32), qw)
+    assert np.array_equal(host(gs).view(np.uint16), sc.view(np.uint16))
+    assert np.array_equal(host(gz).view(np.uint32), qz)
+    assert np.array_equal(host(B.dequantize_w4(gq, gs, gz)).view(np.uint32), oracle.dequant_w4(qw, sc, qz).view(np.uint32))
+    run_w4(B, oracle, x, (gq, gs, gz), (qw, sc, qz), "config1")
+
+
+@pytest.mark.parametrize("linear", synth.LINEAR_ORDER)
+def test_config2_llama7b_decode(B, oracle, linear):
+    K, N = synth.LAYER_SHAPES["llama7b"][linear]
+    W = synth.layer_weights(2, "llama7b", linear)
+    rec = oracle.quantize_w4(W)
+    rec_dev = tuple(dev(a) for a in rec)
+    w16 = W.astype(np.float16)
+    w16_dev = dev(w16)
+    del W
+    for M in (1, 4, 16):
+        x = synth.activations(2, M, K, tensor_id=M)
+        run_w4(B, oracle, x, rec_dev, rec, f"config2/{linear}")
+        run_fp16(B, oracle, x, w16_dev, w16, f"config2/{linear}")
+
+
+@pytest.mark.parametrize("linear", synth.LINEAR_ORDER)
+def test_config3_llama3_8b_heavy_tails(B, oracle, linear):
+    K, N = synth.LAYER_SHAPES["llama3_8b"][linear]
+    W = synth.layer_weights(3, "llama3_8b", linear, dist="student_t5")
+    rec = oracle.quantize_w4(W)
+    rec_dev = tuple(dev(a) for a in rec)
+    del W
+    for M in (1, 8, 32, 64):
+        x = synth.activations(3, M, K, tensor_id=M)
+        run_w4(B, oracle, x, rec_dev, rec, f"config3/{linear}")
+
+
+def sample_positions(rng, M, N):
+    """Rows / columns on both sides of tile boundaries of the kernels (multiples of 128; every one
+    along M, a seeded subset along N), the first and last ones, plus seeded random positions."""
+    def edges(L, limit):
+        bounds = np.arange(128, L, 128)
+        if len(bounds) > limit:
+            bounds = np.sort(rng.choice(bounds, limit, replace=False))
+        s = {0, 1, L - 2, L - 1}
+        for e in bounds.tolist():
+            s.update((e - 1, e))
+        return sorted(v for v in s if 0 <= v < L)
+    rows = np.array(edges(M, 16) + rng.integers(0, M, 24).tolist())
+    cols = np.array(edges(N, 48) + rng.integers(0, N, 96).tolist())
+    rr, cc = np.meshgrid(rows, cols, indexing="ij")
+    return rr.ravel(), cc.ravel()
+
+
+@pytest.mark.parametrize("linear", synth.LINEAR_ORDER)
+def test_config4_llama13b_prefill(B, oracle, linear):
+    K, N = synth.LAYER_SHAPES["llama13b"][linear]
+    W = synth.layer_weights(4, "llama13b", linear)
+    rec = oracle.quantize_w4(W)
+    rec_dev = tuple(dev(a) for a in rec)
+    w16 = W.astype(np.float16)
+    w16_dev = dev(w16)
+    del W
+    rng = np.random.default_rng([synth.BASE_SEED, 4, synth._TENSOR_ID[linear]])
+    for M in (512, 2048):
+        x = synth.activations(4, M, K, tensor_id=M)
+        xd = dev(x)
+        rows, cols = sample_positions(rng, M, N)
+        y4 = host(B.linear_w4a16(xd, *rec_dev, None))
+        y16 = host(B.linear_fp16(xd, w16_dev, None))
+        assert np.isfinite(y4).all() and np.isfinite(y16).all()
+        ref4 = oracle.linear_w4a16_at(x, *rec, rows, cols)
+        ref16 = oracle.linear_fp16_at(x, w16, rows, cols)
+        e4 = oracle.error_metric(y4[rows, cols], ref4)
+        e16 = oracle.error_metric(y16[rows, cols], ref16)
+        say(f"  config4/{linear} M={M}: {rows.size} sampled outputs, w4a16 err={e4['err']:.3e} fp16 err={e16['err']:.3e}")
+        assert e4["err"] <= TOL and e16["err"] <= TOL
+        # properties that hold for every output: the two weight sets differ by the quantization
+        # noise only, so the two results agree to a few percent of the output scale everywhere
+        scale = np.abs(y16.astype(np.float32)).max()
+        assert np.abs(y4.astype(np.float32) - y16.astype(np.float32)).max() <= 0.2 * scale
+
+
+def oracle_linear(oracle, rec, x):
+    return oracle.linear_fp16(x, rec[1]) if rec[0] == "fp16" else oracle.linear_w4a16(x, rec[1], rec[2], rec[3])
+
+
+def test_config5_mixed_stack(B, oracle):
+    shapes = synth.LAYER_SHAPES["llama7b"]
+    L, M, hidden, inter = 32, 32, 4096, 11008
+    check_layers = sorted(np.random.default_rng([synth.BASE_SEED, 5, 1]).choice(L, 4, replace=False).tolist())
+    say(f"  config5: oracle-checked layers {check_layers}")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 5)
+    fp16_dev, w4_dev, host_recs = [], [], {}
+    t0 = time.time()
+    for l in range(L):
+        f, q = {}, {}
+        if l in check_layers:
+            host_recs[l] = {}
+            for name in synth.LINEAR_ORDER:
+                W = synth.layer_weights(5, "llama7b", name, layer_id=l)
+                rec = oracle.quantize_w4(W)
+                w16 = W.astype(np.float16)
+                host_recs[l][name] = {"fp16": ("fp16", w16), "w4": ("w4",) + rec}
+                f[name] = dev(w16)
+                q[name] = tuple(dev(a) for a in rec)
+        else:
+            for name in synth.LINEAR_ORDER:
+                K, N = shapes[name]
+                w = torch.randn((K, N), device="cuda", dtype=torch.float32, generator=gen) * 0.02
+                f[name] = w.to(torch.float16)
+                q[name] = B.quantize_layer(w)
+                del w
+        fp16_dev.append(f)
+        w4_dev.append(q)
+    say(f"  config5: 32 layers built in {time.time() - t0:.1f} s")
+    x0 = oracle.rms(synth.activations(5, M, hidden).astype(np.float64)).astype(np.float16)
+    for ki, k in enumerate((0, 8, 16, 32)):
+        swapped = set(synth.swapped_layers(L, k).tolist())
+        st = B.LayerStack(hidden, inter, M)
+        for l in range(L):
+            if l in swapped:
+                st.add_layer({n: ("w4",) + tuple(w4_dev[l][n]) for n in synth.LINEAR_ORDER})
+            else:
+                st.add_layer({n: ("fp16", fp16_dev[l][n]) for n in synth.LINEAR_ORDER})
+        outs = []
+        for l in (check_layers[ki % 4], check_layers[(ki + 2) % 4]):
+            x = dev(x0).clone()
+            st.forward(x, tap_layer=l)
+            torch.cuda.synchronize()
+            outs.append(host(x))
+            kind = "w4" if l in swapped else "fp16"
+            t = {name: host(v) for name, v in st.tapped().items()}
+            for name, tin, tout in (("qkv", "x", "qkv"), ("o", "a", "o"), ("gate_up", "r", "gu"), ("down", "m", "d")):
+                r = oracle.error_metric(t[tout], oracle_linear(oracle, host_recs[l][name][kind], t[tin]))
+                say(f"  config5 k={k} layer {l} {name} ({kind}): err={r['err']:.3e}")
+                assert r["finite"] and r["err"] <= TOL, (k, l, name, r)
+            for got, want in ((t["a"], oracle.glue_qkv(t["qkv"])), (t["r"], oracle.glue_residual(t["x"], t["o"])),
+                              (t["m"], oracle.glue_swiglu(t["gu"]))):
+                assert oracle.error_metric(got, want)["err"] <= GLUE_TOL
+        # the step is deterministic: the two passes (different tap layers) end in the same bytes,
+        # and the output rows keep unit RMS
+        assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+        rmsv = np.sqrt((outs[0].astype(np.float64) ** 2).mean(axis=1))
+        assert np.all(np.abs(rmsv - 1.0) < 1e-2)
