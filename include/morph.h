@@ -148,6 +148,11 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);
 
+/* Plain device-to-device copy kernel (16-byte vectors; src, dst 16-byte aligned, bytes % 16 == 0).
+ * The stack driver uses it for its taps; it is exported so that hardware byte counters can be
+ * calibrated against a transfer of known size. */
+int morph_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 const char* morph_status_string(int status);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ EXPORTS = [
     "morph_linear_fp16", "morph_linear_w4a16", "morph_quantize_layer", "morph_dequantize_w4",
     "morph_workspace_bytes", "morph_workspace_init", "morph_glue", "morph_stack_scratch_bytes",
     "morph_stack_tap_bytes", "morph_stack_forward", "morph_warmup_bytes", "morph_warmup",
-    "morph_set_tuning", "morph_status_string",
+    "morph_set_tuning", "morph_copy", "morph_status_string",
 ]
 
 
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
     L.morph_warmup_bytes.restype = sz
     L.morph_warmup.argtypes = [vp, sz, vp]
     L.morph_set_tuning.argtypes = [i, i]
+    L.morph_copy.argtypes = [vp, vp, sz, vp]
     L.morph_status_string.argtypes = [i]
     L.morph_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -179,6 +180,14 @@ def glue(op: int, a: torch.Tensor, b=None, H=None) -> torch.Tensor:
     bp = _dev(b, torch.float16, "b") if b is not None else None
     _check(lib().morph_glue(op, _dev(a, torch.float16, "a"), bp, out.data_ptr(), M, H, _stream()), "morph_glue")
     return out
+
+
+def copy(src: torch.Tensor, dst: torch.Tensor):
+    """dst <- src with the library's copy kernel (same byte size, 16-byte multiples)."""
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size() and src.is_contiguous() and dst.is_contiguous()
+    _check(lib().morph_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream()), "morph_copy")
+    return dst
 
 
 def set_tuning(key: int, value: int):

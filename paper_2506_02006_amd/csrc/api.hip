@@ -274,6 +274,14 @@ int morph_stack_forward(const morph_layer_desc* layers, int n_layers, void* x_io
     return MORPH_OK;
 }
 
+int morph_copy(const void* src, void* dst, size_t bytes, void* stream)
+{
+    if (!src || !dst) return MORPH_ERR_NULL;
+    if (!aligned16(src) || !aligned16(dst)) return MORPH_ERR_ALIGN;
+    if (bytes % 16 != 0) return MORPH_ERR_SHAPE;
+    return launch_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
 int morph_set_tuning(int key, int value)
 {
     if (key < 0 || key >= TUNE_COUNT) return MORPH_ERR_SHAPE;
