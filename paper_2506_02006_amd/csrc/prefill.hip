@@ -2,7 +2,10 @@
 // the 4-bit record.  Bound by MFMA throughput, so the aim is to keep v_mfma_f32_32x32x16_f16
 // issuing back to back and to touch each weight as rarely as possible.
 //
-//   * A workgroup (4 waves, 2 x 2) owns a BM x BN tile of y and walks K in steps of 64.
+//   * A workgroup owns a BM x BN tile of y and walks K in steps of 64.  The big tile (256 x 256)
+//     runs 8 waves (4 along M x 2 along N, 64 x 128 each, 128 accumulator registers) so that two
+//     waves share every SIMD and one can issue MFMAs while the other waits on LDS or a barrier;
+//     the small tile (128 x 128) runs 4 waves of 64 x 64.
 //   * x tile and weight tile are staged in LDS, both with k contiguous (pitch 72 halfs, which
 //     makes every 16-byte fragment read and every staging write conflict-free).  The weight
 //     tile is transposed on its way in: a thread loads an 8(k) x 8(n) block (fp16: eight 16-byte
@@ -11,8 +14,13 @@
 //     ORed into the mantissa of 1024.0, (1024 + z) is subtracted exactly and the result is
 //     multiplied once by the fp16 scale, which gives exactly the fp16-rounded weight.  Each
 //     weight is therefore dequantized once per workgroup and reused by all BM rows.
-//   * Global loads for step t+1 are issued before the MFMAs of step t (register staging), LDS is
-//     double buffered, one barrier per step.
+//   * Staging is split by wave: the first half of the waves stages the weight tile, the second
+//     half the x tile (eight 16-byte pieces per thread either way), so each wave runs one
+//     straight-line loop body in which the LDS stores of tile t+1 and the global loads of tile t+2
+//     are interleaved with the MFMAs of tile t (scheduling groups), LDS double buffered, one
+//     barrier per step.
+//   * The finished tile goes through LDS once more so that y is written in 16-byte pieces along
+//     rows instead of 2-byte scalars.
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -23,21 +31,35 @@ namespace {
 constexpr int BK  = 64;
 constexpr int LDK = BK + 8;           // LDS pitch in halfs (144 bytes)
 
-template <bool W4, int BM, int BN>
-__global__ __launch_bounds__(256) void prefill_kernel(GemmArgs p, int tiles_m)
-{
-    constexpr int WM = BM / 2, WN = BN / 2;            // wave tile
-    constexpr int FM = WM / 32, FN = WN / 32;          // 32x32 MFMA blocks per wave tile
-    constexpr int A_CHUNKS = BM * (BK / 8) / 256;      // 16-byte pieces of the x tile per thread
-    constexpr int B_BLOCKS = (BK / 8) * (BN / 8);      // 8x8 blocks in the weight tile
-    static_assert(B_BLOCKS <= 256, "one block per thread at most");
+// scheduling-group masks of __builtin_amdgcn_sched_group_barrier
+constexpr int kSgValu = 0x2, kSgMfma = 0x8, kSgVmemRead = 0x20, kSgDsRead = 0x100, kSgDsWrite = 0x200;
 
-    extern __shared__ __align__(16) half_t lds[];      // [2][(BM + BN) * LDK]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <bool W4, int BM, int BN, int WVM, int WVN>
+__global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kernel(GemmArgs p, int tiles_m)
+{
+    constexpr int NT = WVM * WVN * 64;                 // threads
+    constexpr int NH = NT / 2;                         // threads per staging role
+    constexpr int WM = BM / WVM, WN = BN / WVN;        // wave tile
+    constexpr int FM = WM / 32, FN = WN / 32;          // 32x32 MFMA blocks per wave tile
+    constexpr int XP = BM * (BK / 8) / NH;             // 16-byte pieces of the x tile per x-role thread
+    constexpr int WB = (BK / 8) * (BN / 8) / NH;       // 8x8 weight blocks per weight-role thread
+    static_assert(XP * NH == BM * (BK / 8) && (XP == 8 || XP == 16), "x tile divides over its role");
+    static_assert(WB * NH == (BK / 8) * (BN / 8) && (WB == 1 || WB == 2), "weight tile divides over its role");
+    constexpr int NST = XP > (W4 ? 2 * WB : 8 * WB) ? XP : (W4 ? 2 * WB : 8 * WB);   // staging registers (x4)
+
+    // Two separate objects (not halves of one array), so that the compiler knows a store into one
+    // cannot alias a fragment read from the other and is free to interleave them.
+    __shared__ __align__(16) half_t lds0[(BM + BN) * LDK];
+    __shared__ __align__(16) half_t lds1[(BM + BN) * LDK];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool w_role = wave < (WVM * WVN) / 2;        // wave-uniform: this wave stages weights (else x)
+    const int rt = w_role ? tid : tid - NH;            // thread index within its role
     const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;   // neighbours share a weight tile
     const int m0 = tm * BM, n0 = tn * BN;
     const int M = p.M, K = p.K, N = p.N, NW = N >> 3;
-    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+    const int KT = K / BK;
+    const int wm0 = (wave / WVN) * WM, wn0 = (wave % WVN) * WN;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (uint32_t)M * (uint32_t)K * 2u);
     const uint32_t w_row = W4 ? (uint32_t)NW * 4u : (uint32_t)N * 2u;
@@ -46,68 +68,79 @@ __global__ __launch_bounds__(256) void prefill_kernel(GemmArgs p, int tiles_m)
     const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.qzeros, W4 ? (uint32_t)(K / kGroup) * (uint32_t)NW * 4u : 0u);
     const uint32_t kOut = 0xFFFFFFF0u;
 
-    // x tile: piece q = tid + 256 i -> row q / 8, 8 halfs starting at k = 8 (q % 8).  Rows >= M read 0.
-    uint32_t a_voff[A_CHUNKS];
-    int      a_lds[A_CHUNKS];
+    // x role: piece q = rt + NH i -> row q / 8, 8 halfs starting at k = 8 (q % 8).  Rows >= M read 0.
+    const uint32_t a_voff0 = ((uint32_t)(m0 + (rt >> 3)) * (uint32_t)K + 8u * (rt & 7)) * 2u;
+    const uint32_t a_vstep = (uint32_t)(NH / 8) * (uint32_t)K * 2u;          // NH / 8 rows further per piece
+    const int      a_lds0  = (rt >> 3) * LDK + 8 * (rt & 7);
+    // weight role: block b of this thread is number rt + NH b: kb = number % 8, nb = number / 8,
+    // rows 8 kb .. +7 of the tile, columns 8 nb .. +7.
+    uint32_t b_voff[WB], s_voff[WB], z_voff[WB];
+    int      b_lds[WB];
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; i++) {
-        const int q = tid + 256 * i, row = q >> 3, kc = q & 7;
-        a_voff[i] = ((uint32_t)(m0 + row) * (uint32_t)K + 8u * kc) * 2u;
-        a_lds[i]  = row * LDK + 8 * kc;
+    for (int bl = 0; bl < WB; bl++) {
+        const int  idx = rt + NH * bl, kb = idx & 7, nb = idx >> 3;
+        const int  bcol = n0 + 8 * nb;
+        const bool b_ok = bcol < N;
+        b_voff[bl] = b_ok ? (uint32_t)(8 * kb) * w_row + (W4 ? (uint32_t)(bcol >> 3) * 4u : (uint32_t)bcol * 2u) : kOut;
+        s_voff[bl] = b_ok ? (uint32_t)bcol * 2u : kOut;
+        z_voff[bl] = b_ok ? (uint32_t)(bcol >> 3) * 4u : kOut;
+        b_lds[bl]  = BM * LDK + (8 * nb) * LDK + 8 * kb;
     }
-    // weight tile: block (kb = tid % 8, nb = tid / 8): rows 8 kb .. +7, columns 8 nb .. +7
-    const bool b_active = tid < B_BLOCKS;
-    const int  kb = tid & 7, nb = tid >> 3;
-    const int  bcol = n0 + 8 * nb;
-    const bool b_ok = b_active && bcol < N;
-    const uint32_t b_voff = b_ok ? (uint32_t)(8 * kb) * w_row + (W4 ? (uint32_t)(bcol >> 3) * 4u : (uint32_t)bcol * 2u) : kOut;
-    const uint32_t s_voff = b_ok ? (uint32_t)bcol * 2u : kOut;
-    const uint32_t z_voff = b_ok ? (uint32_t)(bcol >> 3) * 4u : kOut;
-    const int      b_lds  = BM * LDK + (8 * nb) * LDK + 8 * kb;
 
-    u32x4    a_reg[A_CHUNKS];
-    u32x4    bh_reg[W4 ? 1 : 8];
-    uint32_t bq_reg[W4 ? 8 : 1];
-    u32x4    sc_reg;
-    uint32_t zq_reg;
+    // staging registers: x role: st[i] = piece i; weight role: fp16: st[8 b + i] = row i of block b
+    // (8 halfs), W4: word i of block b = st[2 b + i / 4][i % 4], plus scales and zero points per block
+    u32x4    st[NST];
+    u32x4    sc_reg[WB];
+    uint32_t zq_reg[WB];
 
-    auto load_global = [&](int kt) {
+    // Every staging function works on one half (h = 0, 1) of the thread's items, so that the loop can
+    // spread the work over the k-substeps of a tile.
+    auto load_x = [&](int kt, int h) {
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; i++) a_reg[i] = buf_load_u32x4(rx, a_voff[i], (uint32_t)kt * (BK * 2u));
+        for (int i = (XP / 2) * h; i < (XP / 2) * (h + 1); i++)
+            st[i] = buf_load_u32x4(rx, a_voff0 + (uint32_t)i * a_vstep, (uint32_t)kt * (BK * 2u));
+    };
+    auto load_w = [&](int kt, int h) {
         const uint32_t so = (uint32_t)kt * BK * w_row;
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            if constexpr (W4) bq_reg[i] = buf_load_u32(rw, b_voff, so + (uint32_t)i * w_row);
-            else              bh_reg[i] = buf_load_u32x4(rw, b_voff, so + (uint32_t)i * w_row);
-        }
-        if constexpr (W4) {
-            const uint32_t g = (uint32_t)(kt * BK) / kGroup;
-            sc_reg = buf_load_u32x4(rs, s_voff, g * (uint32_t)N * 2u);
-            zq_reg = buf_load_u32(rz, z_voff, g * (uint32_t)NW * 4u);
+        for (int r = 4 * WB * h; r < 4 * WB * (h + 1); r++) {
+            const int bl = r >> 3, i = r & 7;
+            if constexpr (W4) st[2 * bl + (i >> 2)][i & 3] = buf_load_u32(rw, b_voff[bl], so + (uint32_t)i * w_row);
+            else              st[8 * bl + i] = buf_load_u32x4(rw, b_voff[bl], so + (uint32_t)i * w_row);
+            if constexpr (W4) {
+                if (i == 0) {
+                    const uint32_t g = (uint32_t)(kt * BK) / kGroup;
+                    sc_reg[bl] = buf_load_u32x4(rs, s_voff[bl], g * (uint32_t)N * 2u);
+                    zq_reg[bl] = buf_load_u32(rz, z_voff[bl], g * (uint32_t)NW * 4u);
+                }
+            }
         }
     };
-
-    auto store_lds = [&](int buf) {
-        half_t* base = lds + buf * ((BM + BN) * LDK);
+    auto store_x = [&](half_t* dst, int h) {
+        half_t* base = dst + a_lds0;
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; i++) *reinterpret_cast<u32x4*>(base + a_lds[i]) = a_reg[i];
-        if (!b_active) return;
-        half_t* bb = base + b_lds;
-        if constexpr (W4) {
-            const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
+        for (int i = (XP / 2) * h; i < (XP / 2) * (h + 1); i++) *reinterpret_cast<u32x4*>(base + i * (NH / 8) * LDK) = st[i];
+    };
+    // unit u of the weight role = column pair (u % 4) of block (u / 4)
+    auto store_w = [&](half_t* dst, int h) {
 #pragma unroll
-            for (int yb = 0; yb < 4; yb++) {
-                const uint32_t zd = yb == 0 ? pair_bytes<0>(zq_reg, zq_reg) : yb == 1 ? pair_bytes<1>(zq_reg, zq_reg)
-                                  : yb == 2 ? pair_bytes<2>(zq_reg, zq_reg) : pair_bytes<3>(zq_reg, zq_reg);
+        for (int u = 2 * WB * h; u < 2 * WB * (h + 1); u++) {
+            const int bl = u >> 2, yb = u & 3;
+            half_t* bb = dst + b_lds[bl];
+            if constexpr (W4) {
+                const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
+                const uint32_t zq = zq_reg[bl];
+                const uint32_t zd = yb == 0 ? pair_bytes<0>(zq, zq) : yb == 1 ? pair_bytes<1>(zq, zq)
+                                  : yb == 2 ? pair_bytes<2>(zq, zq) : pair_bytes<3>(zq, zq);
                 const half2_t czl = bit_cast<half2_t>((zd & 0x000F000Fu) | 0xE400E400u);   // -(1024 + z)
                 const half2_t czh = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xD400D400u);   // -(64 + z)
-                const uint32_t sw = sc_reg[yb];                                            // scales of columns 2yb, 2yb+1
+                const uint32_t sw = sc_reg[bl][yb];                                        // scales of columns 2yb, 2yb+1
                 const half_t  s0 = bit_cast<half_t>((uint16_t)(sw & 0xFFFFu)), s1 = bit_cast<half_t>((uint16_t)(sw >> 16));
                 const half2_t s0p = {s0, s0}, s1p = {s1, s1};
                 half8_t lo8, hi8;
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
-                    const uint32_t r0 = bq_reg[2 * q], r1 = bq_reg[2 * q + 1];
+                    const uint32_t r0 = st[2 * bl + ((2 * q) >> 2)][(2 * q) & 3], r1 = st[2 * bl + ((2 * q + 1) >> 2)][(2 * q + 1) & 3];
                     const uint32_t pr = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
                                       : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
                     const half2_t lo = (nib_lo_1024(pr) + czl) * s0p;                      // (q - z) * s, one rounding
@@ -117,19 +150,16 @@ __global__ __launch_bounds__(256) void prefill_kernel(GemmArgs p, int tiles_m)
                 }
                 *reinterpret_cast<half8_t*>(bb + (2 * yb) * LDK)     = lo8;
                 *reinterpret_cast<half8_t*>(bb + (2 * yb + 1) * LDK) = hi8;
-            }
-        } else {
-#pragma unroll
-            for (int jj = 0; jj < 4; jj++) {
+            } else {
                 uint32_t e[4], o[4];
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
-                    const uint32_t r0 = bh_reg[2 * q][jj], r1 = bh_reg[2 * q + 1][jj];
+                    const uint32_t r0 = st[8 * bl + 2 * q][yb], r1 = st[8 * bl + 2 * q + 1][yb];
                     e[q] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);
                     o[q] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);
                 }
-                *reinterpret_cast<u32x4*>(bb + (2 * jj) * LDK)     = u32x4{e[0], e[1], e[2], e[3]};
-                *reinterpret_cast<u32x4*>(bb + (2 * jj + 1) * LDK) = u32x4{o[0], o[1], o[2], o[3]};
+                *reinterpret_cast<u32x4*>(bb + (2 * yb) * LDK)     = u32x4{e[0], e[1], e[2], e[3]};
+                *reinterpret_cast<u32x4*>(bb + (2 * yb + 1) * LDK) = u32x4{o[0], o[1], o[2], o[3]};
             }
         }
     };
@@ -143,60 +173,100 @@ __global__ __launch_bounds__(256) void prefill_kernel(GemmArgs p, int tiles_m)
             for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
     const int frow = lane & 31, fk = (lane >> 5) * 8;
-    auto compute = [&](int buf) {
-        const half_t* abase = lds + buf * ((BM + BN) * LDK) + (wm0 + frow) * LDK + fk;
-        const half_t* bbase = lds + buf * ((BM + BN) * LDK) + BM * LDK + (wn0 + frow) * LDK + fk;
+    // One loop step of a wave: multiply tile kt out of `cur` (four k-substeps of 16), park tile kt+1
+    // (already in registers) in `nxt`, fetch tile kt+2 into the freed registers.  Past the end the
+    // last tile is fetched and parked again, which is harmless and keeps the body free of branches.
+    // Order inside a substep: the fragment reads of the NEXT substep first (so that waiting for
+    // them later does not also wait for the stores issued after them: LDS operations retire in
+    // order), then the MFMAs with a piece of the staging work behind each.  Substeps 0 and 1 carry the
+    // LDS stores, substeps 2 and 3 the global loads.
+    auto step = [&](int kt, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn) {
+        const int ktl = kt + 2 < KT ? kt + 2 : KT - 1;
+        const half_t* abase = cur + (wm0 + frow) * LDK + fk;
+        const half_t* bbase = cur + BM * LDK + (wn0 + frow) * LDK + fk;
+        half8_t af[2][FM], bf[2][FN];
+        auto read_frags = [&](int set, int kk) {
+#pragma unroll
+            for (int i = 0; i < FM; i++) af[set][i] = *reinterpret_cast<const half8_t*>(abase + i * 32 * LDK + kk * 16);
+#pragma unroll
+            for (int j = 0; j < FN; j++) bf[set][j] = *reinterpret_cast<const half8_t*>(bbase + j * 32 * LDK + kk * 16);
+        };
+        read_frags(0, 0);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; kk++) {
-            half8_t af[FM], bf[FN];
-#pragma unroll
-            for (int i = 0; i < FM; i++) af[i] = *reinterpret_cast<const half8_t*>(abase + i * 32 * LDK + kk * 16);
-#pragma unroll
-            for (int j = 0; j < FN; j++) bf[j] = *reinterpret_cast<const half8_t*>(bbase + j * 32 * LDK + kk * 16);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk + 1 < BK / 16) read_frags((kk + 1) & 1, kk + 1);
+            if (kk < 2) store_fn(nxt, kk);               // buffer last read in step kt-1, behind a barrier
+            else        load_fn(ktl, kk - 2);
 #pragma unroll
             for (int i = 0; i < FM; i++)
 #pragma unroll
                 for (int j = 0; j < FN; j++)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[kk & 1][i], bf[kk & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(kSgDsRead, FM + FN, 0);
+#pragma unroll
+            for (int g = 0; g < FM * FN; g++) {
+                __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(kSgValu, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(kSgDsWrite, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(kSgVmemRead, 1, 0);
+            }
         }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int KT = K / BK;
-    load_global(0);
-    store_lds(0);
+    if (w_role) { load_w(0, 0); load_w(0, 1); store_w(lds0, 0); store_w(lds0, 1); load_w(KT > 1 ? 1 : 0, 0); load_w(KT > 1 ? 1 : 0, 1); }
+    else        { load_x(0, 0); load_x(0, 1); store_x(lds0, 0); store_x(lds0, 1); load_x(KT > 1 ? 1 : 0, 0); load_x(KT > 1 ? 1 : 0, 1); }
     __syncthreads();
-    for (int kt = 0; kt < KT; kt++) {
-        const bool more = kt + 1 < KT;
-        if (more) load_global(kt + 1);
-        compute(kt & 1);
-        if (more) store_lds((kt + 1) & 1);
-        __syncthreads();
+    // two steps per trip so that each step names its buffers statically (KT is even: K % 128 == 0)
+    if (w_role) {
+        for (int kt = 0; kt < KT; kt += 2) {
+            step(kt, lds0, lds1, store_w, load_w);
+            __syncthreads();
+            step(kt + 1, lds1, lds0, store_w, load_w);
+            __syncthreads();
+        }
+    } else {
+        for (int kt = 0; kt < KT; kt += 2) {
+            step(kt, lds0, lds1, store_x, load_x);
+            __syncthreads();
+            step(kt + 1, lds1, lds0, store_x, load_x);
+            __syncthreads();
+        }
     }
 
-    // epilogue: register r of a 32x32 block = row 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32
-    half_t* y = (half_t*)p.y;
+    // ---- epilogue: each wave parks its tile in LDS as fp16 (pitch WN + 8), then writes rows ----
+    // register r of a 32x32 block = row 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32
+    constexpr int EP = WN + 8;                         // halfs; (WN + 8) * 2 bytes is a multiple of 16
+    static_assert((size_t)WM * EP * (WVM * WVN / 2) <= (size_t)(BM + BN) * LDK, "epilogue fits in the staging LDS");
+    constexpr int HALF_WAVES = WVM * WVN / 2;          // the loop's last barrier freed the staging buffers
+    half_t* et = (wave < HALF_WAVES ? lds0 : lds1) + (size_t)(wave % HALF_WAVES) * WM * EP;
 #pragma unroll
     for (int i = 0; i < FM; i++)
 #pragma unroll
-        for (int j = 0; j < FN; j++) {
-            const int col = n0 + wn0 + 32 * j + (lane & 31);
+        for (int j = 0; j < FN; j++)
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                const int row = m0 + wm0 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < M && col < N) y[(size_t)row * N + col] = (half_t)acc[i][j][r];
+                const int row = 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                et[row * EP + 32 * j + (lane & 31)] = (half_t)acc[i][j][r];
             }
-        }
+    // (a wave reads back only what it wrote itself; LDS operations of one wave complete in order)
+    half_t* y = (half_t*)p.y;
+    constexpr int VPR = WN / 8;                        // 16-byte pieces per tile row
+#pragma unroll 4
+    for (int v = lane; v < WM * VPR; v += 64) {
+        const int row = v / VPR, cv = v - row * VPR;
+        const int grow = m0 + wm0 + row, gcol = n0 + wn0 + 8 * cv;
+        if (grow < M && gcol < N)
+            *reinterpret_cast<u32x4*>(y + (size_t)grow * N + gcol) = *reinterpret_cast<const u32x4*>(et + row * EP + 8 * cv);
+    }
 }
 
-template <bool W4, int BM, int BN>
+template <bool W4, int BM, int BN, int WVM, int WVN>
 hipError_t launch_tile(const GemmArgs& a, hipStream_t st)
 {
-    constexpr size_t lds = (size_t)2 * (BM + BN) * LDK * sizeof(half_t);
-    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<W4, BM, BN>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (attr != hipSuccess) return attr;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    hipLaunchKernelGGL((prefill_kernel<W4, BM, BN>), dim3(tiles_m * tiles_n), dim3(256), lds, st, a, tiles_m);
+    hipLaunchKernelGGL((prefill_kernel<W4, BM, BN, WVM, WVN>), dim3(tiles_m * tiles_n), dim3(WVM * WVN * 64), 0, st, a, tiles_m);
     return hipGetLastError();
 }
 
@@ -210,8 +280,12 @@ hipError_t launch_prefill(int is_w4, const GemmArgs& a, hipStream_t st)
         const long long t256 = (long long)((a.M + 255) / 256) * ((a.N + 255) / 256);
         big = t256 >= 256 ? 1 : 2;
     }
-    if (is_w4) return big == 1 ? launch_tile<true, 256, 256>(a, st) : launch_tile<true, 128, 128>(a, st);
-    return big == 1 ? launch_tile<false, 256, 256>(a, st) : launch_tile<false, 128, 128>(a, st);
+    switch (big) {
+        case 1: return is_w4 ? launch_tile<true, 256, 256, 4, 2>(a, st) : launch_tile<false, 256, 256, 4, 2>(a, st);
+        case 3: return is_w4 ? launch_tile<true, 256, 256, 2, 2>(a, st) : launch_tile<false, 256, 256, 2, 2>(a, st);
+        case 4: return is_w4 ? launch_tile<true, 256, 128, 2, 2>(a, st) : launch_tile<false, 256, 128, 2, 2>(a, st);
+        default: return is_w4 ? launch_tile<true, 128, 128, 2, 2>(a, st) : launch_tile<false, 128, 128, 2, 2>(a, st);
+    }
 }
 
 }  // namespace morph

@@ -151,7 +151,7 @@ def test_prefill_fp16(B, oracle, M, K, N):
     check_fp16(B, oracle, M, K, N, seed=M)
 
 
-@pytest.mark.parametrize("tile", [1, 2])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
 def test_prefill_both_tiles(B, oracle, tile):
     B.set_tuning(B.TUNE_PREFILL_TILE, tile)
     try:
