@@ -238,8 +238,9 @@ def main():
             for M in (512, 2048):
                 x = rand_x(M, K)
                 y = torch.empty((M, N), device=dev, dtype=torch.float16)
-                for label, fn in (("w4a16", lambda: B.linear_w4a16(x, w4[0], w4[1], w4[2], None, out=y)),
-                                  ("fp16", lambda: B.linear_fp16(x, w16, None, out=y))):
+                wsp = B.new_workspace(max(B.workspace_bytes(B.KIND_W4A16, M, K, N), B.workspace_bytes(B.KIND_FP16, M, K, N)))
+                for label, fn in (("w4a16", lambda: B.linear_w4a16(x, w4[0], w4[1], w4[2], wsp, out=y)),
+                                  ("fp16", lambda: B.linear_fp16(x, w16, wsp, out=y))):
                     s = timed(lambda i: fn(), 10, 2) / 10
                     tf = 2.0 * M * K * N / s / 1e12
                     d13[f"{label}/{name}/M{M}"] = {"us": round(s * 1e6, 1), "TFLOPs": round(tf, 1),

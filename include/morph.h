@@ -55,7 +55,8 @@ enum { MORPH_GROUP_SIZE = 128 };
 /* ---- y = x * W with fp16 weights (the full-precision layer variant; Section 4.3, Appendix C) ----
  * x [M,K] fp16, w [K,N] fp16, y [M,N] fp16.  K % 128 == 0, N % 8 == 0, M >= 1.
  * M <= 64 takes the bandwidth-bound decode kernel (split along K; needs the workspace),
- * larger M the LDS-tiled MFMA kernel (workspace unused).
+ * larger M the LDS-tiled MFMA kernel (k-tiles shared out evenly over the compute units; needs the
+ * workspace whenever a share is not made of whole output tiles).
  * workspace: morph_workspace_bytes(MORPH_KIND_FP16, M, K, N) bytes prepared once with
  * morph_workspace_init(); may be NULL when that size is 0.  One workspace must not be used by
  * two calls that can run concurrently (different streams).
@@ -143,8 +144,9 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
 
 /* Override a kernel-selection heuristic (0 restores the default).  For benchmarking sweeps only;
  * defaults are chosen from the shape.  Keys: 0 = K-split factor of the decode kernels,
- * 1 = target workgroup count of the decode kernels, 2 = prefill tile (1 = 256x256, 2 = 128x128),
- * 3 = waves per decode workgroup (4 or 8).
+ * 1 = target workgroup count of the decode kernels, 2 = prefill tile (1 = 256x256 with 8 waves,
+ * 2 = 128x128, 3 = 256x256 with 4 waves, 4 = 256x128), 3 = waves per decode workgroup (4 or 8),
+ * 4 = prefill: sharing the last partial round of tiles out along K (1 = never, 2 = always).
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);
 

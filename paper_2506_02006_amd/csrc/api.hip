@@ -44,7 +44,10 @@ int check_sizes(int kind, int M, int K, int N)
 
 size_t workspace_need(int kind, int M, int K, int N)
 {
-    if (M > kDecodeMaxM) return 0;
+    if (M > kDecodeMaxM) {
+        const PrefillPlan pp = plan_prefill(M, K, N);
+        return pp.partial_bytes ? pp.counter_bytes + pp.partial_bytes : 0;
+    }
     const DecodePlan pl = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
     return pl.S > 1 ? kCounterBytes + pl.partial_bytes : 0;
 }
@@ -68,8 +71,19 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         }
         e = launch_decode(kind == MORPH_KIND_W4A16, a, st);
     } else {
+        const PrefillPlan pp = plan_prefill(M, K, N);
         GemmArgs g;
         g.x = x; g.w = w; g.scales = scales; g.qzeros = qzeros; g.y = y; g.M = M; g.K = K; g.N = N;
+        g.config = pp.config; g.grid = pp.grid; g.split_tail = pp.split_tail;
+        g.partial = nullptr; g.counters = nullptr;
+        if (pp.counter_bytes > ((size_t)1 << 20)) return MORPH_ERR_UNSUPPORTED;   // more tiles than counters are zeroed for
+        if (pp.partial_bytes) {
+            if (!workspace || workspace_bytes < pp.counter_bytes + pp.partial_bytes) return MORPH_ERR_WORKSPACE;
+            if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
+            if ((size_t)2 * pp.grid * pp.bm * pp.bn * sizeof(float) >= k4G) return MORPH_ERR_UNSUPPORTED;
+            g.counters = reinterpret_cast<int*>(workspace);
+            g.partial  = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pp.counter_bytes);
+        }
         e = launch_prefill(kind == MORPH_KIND_W4A16, g, st);
     }
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
@@ -152,8 +166,10 @@ int morph_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
     if (workspace_bytes == 0) return MORPH_OK;
     if (!workspace) return MORPH_ERR_NULL;
     if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
-    // only the arrival counters at the head need to start at zero
-    size_t bytes = workspace_bytes < kCounterBytes ? (workspace_bytes & ~(size_t)15) : kCounterBytes;
+    // only the arrival counters at the head need to start at zero (decode: 4 KB; prefill: one word
+    // per output tile, well under 1 MB)
+    const size_t head = (size_t)1 << 20;
+    size_t bytes = workspace_bytes < head ? (workspace_bytes & ~(size_t)15) : head;
     hipError_t e = launch_fill_zero(workspace, bytes, (hipStream_t)stream);
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }

@@ -43,8 +43,19 @@ struct GemmArgs {
     const void* scales;
     const void* qzeros;
     void*       y;
+    float*      partial;   // [2 * grid][BM * BN] fp32 partial tiles (stream-K), may be null when unused
+    int*        counters;  // [tiles], zero on entry, zero on exit
     int         M, K, N;
+    int         config;    // tile configuration (PrefillPlan::config)
+    int         grid;      // workgroups (PrefillPlan::grid)
+    int         split_tail; // share the last partial round out along K (PrefillPlan::split_tail)
 };
+struct PrefillPlan {
+    int    config, bm, bn, tiles, grid, split_tail;
+    size_t counter_bytes;  // head of the workspace
+    size_t partial_bytes;  // 0 when every share is made of whole tiles
+};
+PrefillPlan plan_prefill(int M, int K, int N);
 hipError_t launch_prefill(int is_w4, const GemmArgs& a, hipStream_t st);
 
 // ---- glue (glue.hip) ----
@@ -55,6 +66,6 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_COUNT = 8 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_COUNT = 8 };
 
 }  // namespace morph

@@ -35,7 +35,7 @@ constexpr int LDK = BK + 8;           // LDS pitch in halfs (144 bytes)
 constexpr int kSgValu = 0x2, kSgMfma = 0x8, kSgVmemRead = 0x20, kSgDsRead = 0x100, kSgDsWrite = 0x200;
 
 template <bool W4, int BM, int BN, int WVM, int WVN>
-__global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kernel(GemmArgs p, int tiles_m)
+__global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kernel(GemmArgs p, int tiles_m, int tiles)
 {
     constexpr int NT = WVM * WVN * 64;                 // threads
     constexpr int NH = NT / 2;                         // threads per staging role
@@ -55,10 +55,9 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool w_role = wave < (WVM * WVN) / 2;        // wave-uniform: this wave stages weights (else x)
     const int rt = w_role ? tid : tid - NH;            // thread index within its role
-    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;   // neighbours share a weight tile
-    const int m0 = tm * BM, n0 = tn * BN;
     const int M = p.M, K = p.K, N = p.N, NW = N >> 3;
     const int KT = K / BK;
+    int m0 = 0, n0 = 0;                                // origin of the tile being worked on
     const int wm0 = (wave / WVN) * WM, wn0 = (wave % WVN) * WN;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (uint32_t)M * (uint32_t)K * 2u);
@@ -69,23 +68,33 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     const uint32_t kOut = 0xFFFFFFF0u;
 
     // x role: piece q = rt + NH i -> row q / 8, 8 halfs starting at k = 8 (q % 8).  Rows >= M read 0.
-    const uint32_t a_voff0 = ((uint32_t)(m0 + (rt >> 3)) * (uint32_t)K + 8u * (rt & 7)) * 2u;
-    const uint32_t a_vstep = (uint32_t)(NH / 8) * (uint32_t)K * 2u;          // NH / 8 rows further per piece
-    const int      a_lds0  = (rt >> 3) * LDK + 8 * (rt & 7);
     // weight role: block b of this thread is number rt + NH b: kb = number % 8, nb = number / 8,
     // rows 8 kb .. +7 of the tile, columns 8 nb .. +7.
+    uint32_t a_voff0 = 0;
+    const uint32_t a_vstep = (uint32_t)(NH / 8) * (uint32_t)K * 2u;          // NH / 8 rows further per piece
+    const int      a_lds0  = (rt >> 3) * LDK + 8 * (rt & 7);
     uint32_t b_voff[WB], s_voff[WB], z_voff[WB];
     int      b_lds[WB];
 #pragma unroll
     for (int bl = 0; bl < WB; bl++) {
-        const int  idx = rt + NH * bl, kb = idx & 7, nb = idx >> 3;
-        const int  bcol = n0 + 8 * nb;
-        const bool b_ok = bcol < N;
-        b_voff[bl] = b_ok ? (uint32_t)(8 * kb) * w_row + (W4 ? (uint32_t)(bcol >> 3) * 4u : (uint32_t)bcol * 2u) : kOut;
-        s_voff[bl] = b_ok ? (uint32_t)bcol * 2u : kOut;
-        z_voff[bl] = b_ok ? (uint32_t)(bcol >> 3) * 4u : kOut;
-        b_lds[bl]  = BM * LDK + (8 * nb) * LDK + 8 * kb;
+        const int idx = rt + NH * bl;
+        b_lds[bl] = BM * LDK + (8 * (idx >> 3)) * LDK + 8 * (idx & 7);
     }
+    auto set_tile = [&](int tile) {
+        const int tm = tile % tiles_m, tn = tile / tiles_m;                  // neighbours share a weight tile
+        m0 = tm * BM;
+        n0 = tn * BN;
+        a_voff0 = ((uint32_t)(m0 + (rt >> 3)) * (uint32_t)K + 8u * (rt & 7)) * 2u;
+#pragma unroll
+        for (int bl = 0; bl < WB; bl++) {
+            const int  idx = rt + NH * bl, kb = idx & 7, nb = idx >> 3;
+            const int  bcol = n0 + 8 * nb;
+            const bool b_ok = bcol < N;
+            b_voff[bl] = b_ok ? (uint32_t)(8 * kb) * w_row + (W4 ? (uint32_t)(bcol >> 3) * 4u : (uint32_t)bcol * 2u) : kOut;
+            s_voff[bl] = b_ok ? (uint32_t)bcol * 2u : kOut;
+            z_voff[bl] = b_ok ? (uint32_t)(bcol >> 3) * 4u : kOut;
+        }
+    };
 
     // staging registers: x role: st[i] = piece i; weight role: fp16: st[8 b + i] = row i of block b
     // (8 halfs), W4: word i of block b = st[2 b + i / 4][i % 4], plus scales and zero points per block
@@ -165,12 +174,6 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     };
 
     f32x16 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; i++)
-#pragma unroll
-        for (int j = 0; j < FN; j++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
     const int frow = lane & 31, fk = (lane >> 5) * 8;
     // One loop step of a wave: multiply tile kt out of `cur` (four k-substeps of 16), park tile kt+1
@@ -180,8 +183,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // them later does not also wait for the stores issued after them: LDS operations retire in
     // order), then the MFMAs with a piece of the staging work behind each.  Substeps 0 and 1 carry the
     // LDS stores, substeps 2 and 3 the global loads.
-    auto step = [&](int kt, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn) {
-        const int ktl = kt + 2 < KT ? kt + 2 : KT - 1;
+    auto step = [&](int kt, int kend, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn) {
+        const int ktl = kt + 2 < kend ? kt + 2 : kend - 1;
         const half_t* abase = cur + (wm0 + frow) * LDK + fk;
         const half_t* bbase = cur + BM * LDK + (wn0 + frow) * LDK + fk;
         half8_t af[2][FM], bf[2][FN];
@@ -215,50 +218,161 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    if (w_role) { load_w(0, 0); load_w(0, 1); store_w(lds0, 0); store_w(lds0, 1); load_w(KT > 1 ? 1 : 0, 0); load_w(KT > 1 ? 1 : 0, 1); }
-    else        { load_x(0, 0); load_x(0, 1); store_x(lds0, 0); store_x(lds0, 1); load_x(KT > 1 ? 1 : 0, 0); load_x(KT > 1 ? 1 : 0, 1); }
-    __syncthreads();
-    // two steps per trip so that each step names its buffers statically (KT is even: K % 128 == 0)
-    if (w_role) {
-        for (int kt = 0; kt < KT; kt += 2) {
-            step(kt, lds0, lds1, store_w, load_w);
+    // k-tiles [k0, k1) of the current tile: acc = x[m0.., k-range] * W[k-range, n0..]
+    auto run_range = [&](int k0, int k1, auto store_fn, auto load_fn) {
+#pragma unroll
+        for (int i = 0; i < FM; i++)
+#pragma unroll
+            for (int j = 0; j < FN; j++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+        const int ks = k0 + 1 < k1 ? k0 + 1 : k0;
+        load_fn(k0, 0); load_fn(k0, 1);
+        store_fn(lds0, 0); store_fn(lds0, 1);
+        load_fn(ks, 0); load_fn(ks, 1);
+        __syncthreads();
+        int kt = k0;
+        // two steps per trip so that each step names its buffers statically
+        for (; kt + 2 <= k1; kt += 2) {
+            step(kt, k1, lds0, lds1, store_fn, load_fn);
             __syncthreads();
-            step(kt + 1, lds1, lds0, store_w, load_w);
+            step(kt + 1, k1, lds1, lds0, store_fn, load_fn);
             __syncthreads();
         }
-    } else {
-        for (int kt = 0; kt < KT; kt += 2) {
-            step(kt, lds0, lds1, store_x, load_x);
-            __syncthreads();
-            step(kt + 1, lds1, lds0, store_x, load_x);
+        if (kt < k1) {                                   // odd count: one more step out of lds0
+            step(kt, k1, lds0, lds1, store_fn, load_fn);
             __syncthreads();
         }
-    }
+    };
 
-    // ---- epilogue: each wave parks its tile in LDS as fp16 (pitch WN + 8), then writes rows ----
+    // ---- write the finished tile: each wave parks its part in LDS as fp16 (pitch WN + 8), then
+    // stores rows in 16-byte pieces ----
     // register r of a 32x32 block = row 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32
     constexpr int EP = WN + 8;                         // halfs; (WN + 8) * 2 bytes is a multiple of 16
     static_assert((size_t)WM * EP * (WVM * WVN / 2) <= (size_t)(BM + BN) * LDK, "epilogue fits in the staging LDS");
-    constexpr int HALF_WAVES = WVM * WVN / 2;          // the loop's last barrier freed the staging buffers
-    half_t* et = (wave < HALF_WAVES ? lds0 : lds1) + (size_t)(wave % HALF_WAVES) * WM * EP;
-#pragma unroll
-    for (int i = 0; i < FM; i++)
-#pragma unroll
-        for (int j = 0; j < FN; j++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int row = 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                et[row * EP + 32 * j + (lane & 31)] = (half_t)acc[i][j][r];
-            }
-    // (a wave reads back only what it wrote itself; LDS operations of one wave complete in order)
+    constexpr int HALF_WAVES = WVM * WVN / 2;
     half_t* y = (half_t*)p.y;
-    constexpr int VPR = WN / 8;                        // 16-byte pieces per tile row
+    auto write_tile = [&]() {                            // the range's last barrier freed the staging buffers
+        half_t* et = (wave < HALF_WAVES ? lds0 : lds1) + (size_t)(wave % HALF_WAVES) * WM * EP;
+#pragma unroll
+        for (int i = 0; i < FM; i++)
+#pragma unroll
+            for (int j = 0; j < FN; j++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int row = 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    et[row * EP + 32 * j + (lane & 31)] = (half_t)acc[i][j][r];
+                }
+        // (a wave reads back only what it wrote itself; LDS operations of one wave complete in order)
+        constexpr int VPR = WN / 8;                    // 16-byte pieces per tile row
 #pragma unroll 4
-    for (int v = lane; v < WM * VPR; v += 64) {
-        const int row = v / VPR, cv = v - row * VPR;
-        const int grow = m0 + wm0 + row, gcol = n0 + wn0 + 8 * cv;
-        if (grow < M && gcol < N)
-            *reinterpret_cast<u32x4*>(y + (size_t)grow * N + gcol) = *reinterpret_cast<const u32x4*>(et + row * EP + 8 * cv);
+        for (int v = lane; v < WM * VPR; v += 64) {
+            const int row = v / VPR, cv = v - row * VPR;
+            const int grow = m0 + wm0 + row, gcol = n0 + wn0 + 8 * cv;
+            if (grow < M && gcol < N)
+                *reinterpret_cast<u32x4*>(y + (size_t)grow * N + gcol) = *reinterpret_cast<const u32x4*>(et + row * EP + 8 * cv);
+        }
+    };
+
+    // ---- work distribution.  The grid is one workgroup per compute unit (or fewer).  Full rounds:
+    // workgroup g takes tile r * G + g whole, all workgroups walking K in step, so that neighbours
+    // fetch the same x and weight k-tiles at the same time (one HBM read, the rest cache hits).
+    // The remaining tiles (fewer than G) are either taken whole by the first workgroups or, when
+    // that would leave most compute units idle, stream-K: their k-tiles form one sequence of
+    // `units`, cut into G equal contiguous shares; a share covers whole tiles (written directly) and,
+    // at its ends, parts of tiles: those are stored as fp32 partial sums (accumulator layout,
+    // written through to memory) and the last contributor to arrive at the tile's counter adds all
+    // parts in share order and writes the tile.
+    const int G = gridDim.x, g = blockIdx.x;
+    const int full_rounds = tiles / G;
+    for (int r = 0; r < full_rounds; r++) {
+        __syncthreads();                                 // LDS reuse after the previous tile's write-out
+        set_tile(r * G + g);
+        if (w_role) run_range(0, KT, store_w, load_w);
+        else        run_range(0, KT, store_x, load_x);
+        write_tile();
+    }
+    const int tail_first = full_rounds * G, tail_tiles = tiles - tail_first;
+    if (tail_tiles == 0) return;
+    if (!p.split_tail) {
+        if (g < tail_tiles) {
+            __syncthreads();
+            set_tile(tail_first + g);
+            if (w_role) run_range(0, KT, store_w, load_w);
+            else        run_range(0, KT, store_x, load_x);
+            write_tile();
+        }
+        return;
+    }
+    const long long units = (long long)tail_tiles * KT;
+    auto share_begin = [&](int gg) { return (long long)gg * units / G; };
+    constexpr int PART_VEC = FM * FN * 4;              // f32x4 vectors per lane of one partial
+    constexpr uint32_t kPartBytes = (uint32_t)BM * BN * 4u;
+    const __amdgpu_buffer_rsrc_t rp = make_rsrc(p.partial, (uint32_t)(2 * G) * kPartBytes);
+    const uint32_t lane_off = ((uint32_t)wave * 64u + lane) * (PART_VEC * 16u);
+
+    long long u = share_begin(g);
+    const long long u_end = share_begin(g + 1);
+    while (u < u_end) {
+        const int tile = (int)(u / KT);
+        const int k0 = (int)(u - (long long)tile * KT);
+        const int k1 = (u_end - u) < (KT - k0) ? k0 + (int)(u_end - u) : KT;
+        __syncthreads();                                 // LDS reuse after the previous tile's write-out
+        set_tile(tail_first + tile);
+        if (w_role) run_range(k0, k1, store_w, load_w);
+        else        run_range(k0, k1, store_x, load_x);
+        u += k1 - k0;
+        if (k0 == 0 && k1 == KT) {
+            write_tile();
+            continue;
+        }
+        // contributors of this tile: shares g_first .. g_last
+        const long long t_begin = (long long)tile * KT, t_end = t_begin + KT;
+        int g_first = g, g_last = g;
+        while (share_begin(g_first) > t_begin) g_first--;
+        while (g_last + 1 < G && share_begin(g_last + 1) < t_end) g_last++;
+        const int parts = g_last - g_first + 1;
+        // a share owns two partial slots: 0 for a part that starts where the share starts, 1 otherwise
+        const uint32_t my_slot = 2u * g + (share_begin(g) >= t_begin ? 0u : 1u);
+#pragma unroll
+        for (int i = 0; i < FM; i++)
+#pragma unroll
+            for (int j = 0; j < FN; j++)
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    buf_store_through(rp, my_slot * kPartBytes + lane_off + (uint32_t)((i * FN + j) * 4 + q) * 16u, v);
+                }
+        wait_stores();
+        __syncthreads();
+        int* flag = reinterpret_cast<int*>(lds0);
+        if (tid == 0) *flag = (atomicAdd(p.counters + tile, 1) == parts - 1) ? 1 : 0;   // tile: index within the tail
+        __syncthreads();
+        if (!*flag) continue;
+        // last to arrive: add all parts in share order (its own included, from memory, so that the
+        // result does not depend on which workgroup came last)
+#pragma unroll
+        for (int i = 0; i < FM; i++)
+#pragma unroll
+            for (int j = 0; j < FN; j++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+        for (int gg = g_first; gg <= g_last; gg++) {
+            const uint32_t slot = 2u * gg + (share_begin(gg) >= t_begin ? 0u : 1u);
+#pragma unroll
+            for (int i = 0; i < FM; i++)
+#pragma unroll
+                for (int j = 0; j < FN; j++)
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const f32x4 v = buf_load_through(rp, slot * kPartBytes + lane_off + (uint32_t)((i * FN + j) * 4 + q) * 16u);
+#pragma unroll
+                        for (int e = 0; e < 4; e++) acc[i][j][4 * q + e] += v[e];
+                    }
+        }
+        if (tid == 0) atomicExch(p.counters + tile, 0);
+        __syncthreads();                                 // the flag word is about to be overwritten
+        write_tile();
     }
 }
 
@@ -266,21 +380,61 @@ template <bool W4, int BM, int BN, int WVM, int WVN>
 hipError_t launch_tile(const GemmArgs& a, hipStream_t st)
 {
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    hipLaunchKernelGGL((prefill_kernel<W4, BM, BN, WVM, WVN>), dim3(tiles_m * tiles_n), dim3(WVM * WVN * 64), 0, st, a, tiles_m);
+    const int tiles = tiles_m * tiles_n;
+    hipLaunchKernelGGL((prefill_kernel<W4, BM, BN, WVM, WVN>), dim3(a.grid), dim3(WVM * WVN * 64), 0, st, a, tiles_m, tiles);
     return hipGetLastError();
 }
 
 }  // namespace
 
+int prefill_compute_units()
+{
+    static int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
+        return n;
+    }();
+    return cus;
+}
+
+// Tile choice: the 256 x 256 tile is the most efficient per workgroup; with stream-K every compute
+// unit gets an equal share of k-tiles whatever the tile count, so the big tile is used whenever the
+// problem has at least one compute unit's worth of them per ... otherwise the smaller ones.
+PrefillPlan plan_prefill(int M, int K, int N)
+{
+    PrefillPlan pl;
+    const int cus = prefill_compute_units();
+    const int kt = K / BK;
+    int cfg = tuning_get(TUNE_PREFILL_TILE);             // 0 = by shape, 1 = 256x256 (8 waves), 2 = 128x128, 3 = 256x256 (4 waves), 4 = 256x128
+    if (cfg == 0) {
+        // the 256 x 256 tile is the most efficient per workgroup; smaller tiles when it would leave
+        // more than half of the compute units without a tile
+        const long long t256 = (long long)((M + 255) / 256) * ((N + 255) / 256);
+        const long long t256x128 = (long long)((M + 255) / 256) * ((N + 127) / 128);
+        cfg = 2 * t256 >= cus ? 1 : (2 * t256x128 >= cus || kt >= 128 ? 4 : 2);
+    }
+    pl.config = cfg;
+    pl.bm = (cfg == 2) ? 128 : 256;
+    pl.bn = (cfg == 2 || cfg == 4) ? 128 : 256;
+    pl.tiles = ((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn);
+    pl.grid = pl.tiles < cus ? ((long long)pl.tiles * kt < cus ? pl.tiles * kt : cus) : cus;
+    const int tail = pl.tiles % pl.grid;
+    // Sharing the k-tiles of a partial round out over all compute units (stream-K) costs the
+    // lock-step in which neighbouring workgroups fetch the same operand tiles, and measured slower
+    // than leaving compute units idle except when there are few tiles with a long K.  Tuning key
+    // 4 overrides: 1 = never, 2 = always.
+    const int force = tuning_get(TUNE_PREFILL_SPLIT);
+    pl.split_tail = tail != 0 && (force == 2 || (force != 1 && pl.tiles < pl.grid && 2 * tail < pl.grid && kt >= 128));
+    // every share may end and begin inside a tile: two partial slots per workgroup, plus the counters
+    pl.counter_bytes = ((size_t)pl.grid * sizeof(int) + 255) & ~(size_t)255;
+    pl.partial_bytes = pl.split_tail ? (size_t)2 * pl.grid * pl.bm * pl.bn * sizeof(float) : 0;
+    return pl;
+}
+
 hipError_t launch_prefill(int is_w4, const GemmArgs& a, hipStream_t st)
 {
-    // Big tiles when they still give every compute unit work, else small ones.
-    int big = tuning_get(TUNE_PREFILL_TILE);             // 0 = by shape, 1 = 256x256, 2 = 128x128
-    if (big == 0) {
-        const long long t256 = (long long)((a.M + 255) / 256) * ((a.N + 255) / 256);
-        big = t256 >= 256 ? 1 : 2;
-    }
-    switch (big) {
+    switch (a.config) {
         case 1: return is_w4 ? launch_tile<true, 256, 256, 4, 2>(a, st) : launch_tile<false, 256, 256, 4, 2>(a, st);
         case 3: return is_w4 ? launch_tile<true, 256, 256, 2, 2>(a, st) : launch_tile<false, 256, 256, 2, 2>(a, st);
         case 4: return is_w4 ? launch_tile<true, 256, 128, 2, 2>(a, st) : launch_tile<false, 256, 128, 2, 2>(a, st);

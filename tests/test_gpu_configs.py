@@ -140,8 +140,9 @@ def test_config4_llama13b_prefill(B, oracle, linear):
         x = synth.activations(4, M, K, tensor_id=M)
         xd = dev(x)
         rows, cols = sample_positions(rng, M, N)
-        y4 = host(B.linear_w4a16(xd, *rec_dev, None))
-        y16 = host(B.linear_fp16(xd, w16_dev, None))
+        ws = B.new_workspace(max(B.workspace_bytes(B.KIND_W4A16, M, K, N), B.workspace_bytes(B.KIND_FP16, M, K, N)))
+        y4 = host(B.linear_w4a16(xd, *rec_dev, ws))
+        y16 = host(B.linear_fp16(xd, w16_dev, ws))
         assert np.isfinite(y4).all() and np.isfinite(y16).all()
         ref4 = oracle.linear_w4a16_at(x, *rec, rows, cols)
         ref16 = oracle.linear_fp16_at(x, w16, rows, cols)

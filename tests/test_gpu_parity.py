@@ -182,7 +182,7 @@ def test_identity_activations_reproduce_dequantized_weights(B, oracle, M):
     W = rand_w(3, K, N)
     qw, sc, qz = oracle.quantize_w4(W)
     D16 = oracle.dequant_w4(qw, sc, qz, 128, np.float16)
-    ws = make_ws(B, B.KIND_W4A16, min(M, 64), K, N)
+    ws = make_ws(B, B.KIND_W4A16, M, K, N)
     for start in range(0, K, M):
         x = np.zeros((M, K), np.float16)
         x[np.arange(M), start + np.arange(M)] = 1.0
@@ -190,7 +190,7 @@ def test_identity_activations_reproduce_dequantized_weights(B, oracle, M):
         assert np.array_equal(y.view(np.uint16), D16[start:start + M].view(np.uint16)), (M, start)
     # the fp16 layer under the same activations returns its weights
     W16 = W.astype(np.float16)
-    ws = make_ws(B, B.KIND_FP16, min(M, 64), K, N)
+    ws = make_ws(B, B.KIND_FP16, M, K, N)
     x = np.zeros((M, K), np.float16)
     x[np.arange(M), np.arange(M)] = 1.0
     y = host(B.linear_fp16(dev(x), dev(W16), ws))
