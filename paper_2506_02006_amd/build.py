@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmorph.so")
-SOURCES = ["api.hip", "quant.hip", "decode.hip", "prefill.hip", "glue.hip"]
+SOURCES = ["api.hip", "quant.hip", "decode.hip", "prefill.hip", "glue.hip", "stack.hip"]
 
 # -packed-fp32-ops off: keep the compiler from forming packed fp32 instructions.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -1,329 +1,42 @@
 // Decode-size linears (M <= 64): y[M,N] = x[M,K] * W[K,N] with W either fp16 or the 4-bit
-// record, bound by the rate at which the weights stream out of HBM.
-//
-// Shape of the computation
-//   * Every weight is read from memory once, in its stored row-major layout, in full 128-byte
-//     (W4) or 256-byte (fp16) runs per row, three k-steps (of 32 rows) ahead of its use: a ring of
-//     four register stages in a loop unrolled by four, so that every slot issues a fixed number of
-//     loads and the wait counts are exact.
-//   * The multiply-accumulate runs on the matrix cores even at M = 1 (rows of x beyond M read as
-//     zero): v_mfma_f32_16x16x32_f16 with x as the A operand and the weights as B.  The B operand
-//     wants, per lane, 8 consecutive k of ONE column, while a packed word holds 8 consecutive
-//     columns of ONE k.  A lane therefore loads the same word position from 8 consecutive rows and
-//     pairs bytes across rows (v_perm_b32); MFMA number j of a word produces output column 8c + j.
-//   * W4 codes enter the MFMA without any conversion: a 16-bit lane holding the byte
-//     (16 q_hi + q_lo) IS the fp16 subnormal (16 q_hi + q_lo) * 2^-24, which the matrix core
-//     multiplies exactly.  Per byte two MFMAs run: one on the whole byte, one on the byte masked
-//     to its high nibble; their difference is the low-nibble column.  A third operand of ones
-//     gives the per-group row sums of x.  The four unrolled slots are one quantization group
-//     (128 rows): its first MFMA starts from zero and after its last the fp32 group sums are folded
-//     into the running result,  y += s * (2^24 * acc - z * rowsum(x)),  which lives in LDS (one
-//     private, lane-interleaved region per wave) so that the kernel stays under 256 registers and
-//     two waves share each SIMD.  The vector ALU does one permute and one AND per four weights
-//     plus that fold.
+// record, bound by the rate at which the weights stream out of HBM.  The streaming multiply
+// itself is tile_partial() of decode_core.h; this file adds what one launch per linear needs:
 //   * K is split over the waves of a workgroup and over S workgroups per column tile.  Waves are
 //     summed out of LDS in a fixed order; workgroups write fp32 partials (written through to
 //     memory) and the last one to arrive, found with an atomic counter, adds them in index order,
 //     so results do not depend on timing.  Rows above 32 are handled by a second slice of the
 //     grid (blockIdx.y) running the same kernel on rows 32..63.
-#include "dev_common.h"
+#include "decode_core.h"
 #include "kernels.h"
 
 namespace morph {
 
-// Optional phase timestamps for tuning builds (-DMORPH_TIMING): thread 0 of every workgroup stores
-// the shader clock and the 100 MHz wall clock at a few points.  Compiled out of the product library.
-#ifdef MORPH_TIMING
-__device__ unsigned long long g_ticks[8192 * 16];
-#define MORPH_TICK(i)                                                                          \
-    do {                                                                                       \
-        if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < 8192) {                        \
-            g_ticks[blockIdx.x * 16 + 2 * (i)]     = __builtin_readcyclecounter();             \
-            g_ticks[blockIdx.x * 16 + 2 * (i) + 1] = wall_clock64();                           \
-        }                                                                                      \
-    } while (0)
-#else
-#define MORPH_TICK(i) do { } while (0)
-#endif
-
 namespace {
-
-constexpr int NS     = 4;            // register stages: the k-step being computed and three in flight
-
-// Columns per lane (CPL) and per wave (TN = 16 lanes x CPL).  W4 with one M tile reads two packed
-// words per lane and row (128-byte runs per wave); with two M tiles a wave takes one word per lane
-// and two waves of a workgroup sit side by side (WN = 2) on the same rows, covering the 128-byte
-// run together.  Workgroup tile = WN * TN columns; the other kWaves / WN waves split K.
-template <bool W4, int MT> struct Tile;
-template <> struct Tile<true, 1>  { static constexpr int WPL = 2, CPL = 16, TN = 256, WN = 1; };
-template <> struct Tile<true, 2>  { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 2; };
-template <> struct Tile<false, 1> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 1; };
-template <> struct Tile<false, 2> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 1; };
-
-template <int WPL>
-struct GroupRaw {                // scale / zero data of one group for this lane's 8 WPL columns
-    uint32_t zq[WPL];
-    u32x4    sc[WPL];
-};
-
-// One k-step (32 rows) of operands as they arrive from memory.
-template <bool W4, int MT, int WPL>
-struct Stage {
-    uint32_t w4[W4 ? 8 : 1][WPL];  // W4:   row i -> WPL packed words (8 WPL columns)
-    u32x4    wh[W4 ? 1 : 8];       // fp16: row i -> 8 halfs (8 columns)
-    half8_t  a[MT];                // x rows (lane & 15) + 16 mt, 8 consecutive k
-};
 
 template <bool W4, int MT, int kWaves>
 __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kernel(DecodeArgs p)
 {
-    constexpr int WPL = Tile<W4, MT>::WPL;
-    constexpr int CPL = Tile<W4, MT>::CPL;
-    constexpr int TN  = Tile<W4, MT>::TN;
-    constexpr int WN  = Tile<W4, MT>::WN, WK = kWaves / WN;
-    constexpr int TNB = TN * WN;                         // columns of the workgroup tile
-    constexpr int NV  = MT * CPL;                        // f32x4 result vectors per lane
-    typedef Stage<W4, MT, WPL> StageT;
-    // Result vectors in LDS: [wave][v][lane] f32x4; vector v = mt * CPL + j holds rows
-    // 16 mt + 4 (lane >> 4) + r (r = 0..3) of column CPL (lane & 15) + j of the wave's columns.
+    typedef TileGeom<W4, MT, kWaves> G;
+    constexpr int CPL = G::CPL, TN = G::TN, TNB = G::TNB, NV = G::NV, ITEMS = G::ITEMS;
     extern __shared__ __align__(16) f32x4 yl[];
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    // The wave index is the same in all 64 lanes: say so, so that everything derived from it (this
-    // wave's k range, the scalar offsets of its loads) lives in scalar registers.
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int c = lane & 15, b = lane >> 4;
+    const int tid = threadIdx.x;
     const int S = p.S;
     const int nt = blockIdx.x / S, sp = blockIdx.x - nt * S;
     const int n0 = nt * TNB;                             // first column of the workgroup tile
-    const int wn = wave % WN, wk = wave / WN;            // this wave's column part and k part
     const int mbase = blockIdx.y * 32;                   // first row of this slice
     const int M = (p.M - mbase) < MT * 16 ? (p.M - mbase) : MT * 16;   // rows of this slice
-    const int K = p.K, N = p.N, NW = N >> 3;
-    const int T  = K >> 5;                               // k-steps of 32 rows
-    const int TW = S * WK;
-    const int gw = sp * WK + wk;
-    const int ks0 = (int)(((long long)gw * T) / TW);
-    const int ks1 = (int)(((long long)(gw + 1) * T) / TW);
+    const int N = p.N;
 
-    const uint32_t row_bytes = W4 ? (uint32_t)NW * 4u : (uint32_t)N * 2u;
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (uint32_t)K * row_bytes);
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc((const half_t*)p.x + (size_t)mbase * K, (uint32_t)M * (uint32_t)K * 2u);
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.scales, W4 ? (uint32_t)(K / kGroup) * (uint32_t)N * 2u : 0u);
-    const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.qzeros, W4 ? (uint32_t)(K / kGroup) * (uint32_t)NW * 4u : 0u);
-
-    // This lane's first column; lanes that start beyond N read nothing (offset past the buffer).
-    const int  ncol   = n0 + wn * TN + CPL * c;
-    const bool col_ok = ncol < N;
-    const uint32_t kOut = 0xFFFFFFF0u;
-    // W4: column n sits at byte n/2 of its row (8 columns per 4-byte word); fp16: at byte 2n.
-    const uint32_t col_byte = W4 ? (uint32_t)ncol / 2u : (uint32_t)ncol * 2u;
-    const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + col_byte : kOut;
-    const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
-    const uint32_t voff_z = col_ok ? (uint32_t)(ncol >> 3) * 4u : kOut;
-    uint32_t voff_a[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) voff_a[mt] = ((uint32_t)(mt * 16 + c) * (uint32_t)K + 8u * b) * 2u;
-
-    // Loads of k-step ks.  A step outside [ks0, ks1) is "dead": its offsets are pushed past the
-    // buffers, so the loads still issue (every slot issues the same number) but return zeros
-    // without touching memory.
-    auto load_stage = [&](StageT& st, int ks) {
-        const bool     dead = ks < ks0 || ks >= ks1;
-        const uint32_t dm   = dead ? kOut : 0u;
-        const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
-        const uint32_t vw   = voff_w | dm;
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-            if constexpr (W4 && WPL == 2) {
-                const u32x2 v = buf_load_u32x2(rw, vw, so + (uint32_t)i * row_bytes);
-                st.w4[i][0] = v[0];
-                st.w4[i][WPL - 1] = v[1];
-            } else if constexpr (W4) {
-                st.w4[i][0] = buf_load_u32(rw, vw, so + (uint32_t)i * row_bytes);
-            } else {
-                st.wh[i] = buf_load_u32x4(rw, vw, so + (uint32_t)i * row_bytes);
-            }
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; mt++)
-            st.a[mt] = bit_cast<half8_t>(buf_load_u32x4(rx, voff_a[mt] | dm, dead ? 0u : (uint32_t)ks * 64u));
-    };
-    // Scales and zero points of group g (dead when the group lies outside this wave's k range).
-    auto load_group = [&](GroupRaw<WPL>& gr, int g) {
-        const bool     dead = 4 * g + 3 < ks0 || 4 * g >= ks1;
-        const uint32_t gm   = dead ? kOut : 0u;
-        const uint32_t gg   = dead ? 0u : (uint32_t)g;
-        if constexpr (WPL == 2) {
-            const u32x2 v = buf_load_u32x2(rz, voff_z | gm, gg * (uint32_t)NW * 4u);
-            gr.zq[0] = v[0];
-            gr.zq[WPL - 1] = v[1];
-        } else {
-            gr.zq[0] = buf_load_u32(rz, voff_z | gm, gg * (uint32_t)NW * 4u);
-        }
-#pragma unroll
-        for (int t = 0; t < WPL; t++)
-            gr.sc[t] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u + 16u * t);
-    };
-
-    // Accumulators.  Lane (c, b) holds rows 16 mt + 4 b + r (r = 0..3) of column CPL c + j.
-    //   W4:   gacc[mt][t*8 + 2yb]     = sum x * byte        (byte = 16 q_hi + q_lo, times 2^-24)
-    //         gacc[mt][t*8 + 2yb + 1] = sum x * 16 q_hi     (times 2^-24)
-    //         xs[mt]                  = sum x               over the open group
-    //   fp16: gacc[mt][j] is the result itself.
-    f32x4 gacc[MT][CPL];
-    f32x4 xs[W4 ? MT : 1];
-    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-        for (int j = 0; j < CPL; j++) gacc[mt][j] = zero4;
-    if constexpr (W4) {
-#pragma unroll
-        for (int mt = 0; mt < MT; mt++) xs[mt] = zero4;
-    }
-    f32x4* ymine = yl + (size_t)wave * NV * 64 + lane;    // vector v at ymine[v * 64]
-    if constexpr (W4) {
-#pragma unroll
-        for (int v = 0; v < NV; v++) ymine[v * 64] = zero4;
-    }
-
-    // One k-step.  `first` (known at compile time: slot 0 of the unrolled group) starts the group
-    // sums from zero instead of adding to them.
-    auto compute = [&](const StageT& st, bool first) {
-        if constexpr (W4) {
-            const half_t  one  = (half_t)1.0f;
-            const half8_t ones = {one, one, one, one, one, one, one, one};
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++)
-                xs[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], ones, first ? zero4 : xs[mt], 0, 0, 0);
-#pragma unroll
-            for (int t = 0; t < WPL; t++) {
-#pragma unroll
-                for (int yb = 0; yb < 4; yb++) {
-                    uint32_t pr[4], ph[4];
-#pragma unroll
-                    for (int q = 0; q < 4; q++) {
-                        const uint32_t r0 = st.w4[2 * q][t], r1 = st.w4[2 * q + 1][t];
-                        pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
-                              : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
-                        ph[q] = pr[q] & 0x00F000F0u;
-                    }
-                    const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
-                    const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
-                    const int j0 = t * 8 + 2 * yb;
-#pragma unroll
-                    for (int mt = 0; mt < MT; mt++) {
-                        gacc[mt][j0]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bbyte, first ? zero4 : gacc[mt][j0], 0, 0, 0);
-                        gacc[mt][j0 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bhigh, first ? zero4 : gacc[mt][j0 + 1], 0, 0, 0);
-                    }
-                }
-            }
-        } else {
-#pragma unroll
-            for (int jj = 0; jj < 4; jj++) {                 // register jj of a row: columns 2jj, 2jj+1
-                uint32_t e[4], o[4];
-#pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const uint32_t r0 = st.wh[2 * q][jj], r1 = st.wh[2 * q + 1][jj];
-                    e[q] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);   // (row 2q, row 2q+1) of column 2jj
-                    o[q] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // ... of column 2jj + 1
-                }
-                const half8_t be = bit_cast<half8_t>(u32x4{e[0], e[1], e[2], e[3]});
-                const half8_t bo = bit_cast<half8_t>(u32x4{o[0], o[1], o[2], o[3]});
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) {
-                    gacc[mt][2 * jj]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], be, gacc[mt][2 * jj], 0, 0, 0);
-                    gacc[mt][2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bo, gacc[mt][2 * jj + 1], 0, 0, 0);
-                }
-            }
-        }
-    };
-
-    // Fold the group sums into the running result in LDS:
-    //   low-nibble column:  y += s * (2^24 (acc_byte - acc_high) - z_lo * xs)
-    //   high-nibble column: y += s * (2^20  acc_high             - z_hi * xs)
-    auto flush_group = [&](const GroupRaw<WPL>& gr) {
-        if constexpr (W4) {
-#pragma unroll
-            for (int t = 0; t < WPL; t++) {
-                const uint32_t zw  = gr.zq[t];
-                const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = (zw >> 4) & 0x0F0F0F0Fu;
-#pragma unroll
-                for (int yb = 0; yb < 4; yb++) {
-                    const uint32_t sw  = gr.sc[t][yb];       // scales of columns 8t + 2yb, 8t + 2yb + 1
-                    const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
-                    const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
-                    const float z_lo = (float)((zlo >> (8 * yb)) & 0xFFu);
-                    const float z_hi = (float)((zhi >> (8 * yb)) & 0xFFu);
-                    const float a_lo = s_lo * 16777216.0f, a_hi = s_hi * 1048576.0f;
-                    const float c_lo = -s_lo * z_lo, c_hi = -s_hi * z_hi;
-                    const int j0 = t * 8 + 2 * yb;
-#pragma unroll
-                    for (int mt = 0; mt < MT; mt++) {
-                        f32x4 y0 = ymine[(mt * CPL + j0) * 64], y1 = ymine[(mt * CPL + j0 + 1) * 64];
-#pragma unroll
-                        for (int r = 0; r < 4; r++) {
-                            const float d = gacc[mt][j0][r] - gacc[mt][j0 + 1][r];
-                            y0[r] = __builtin_fmaf(c_lo, xs[mt][r], __builtin_fmaf(a_lo, d, y0[r]));
-                            y1[r] = __builtin_fmaf(c_hi, xs[mt][r], __builtin_fmaf(a_hi, gacc[mt][j0 + 1][r], y1[r]));
-                        }
-                        ymine[(mt * CPL + j0) * 64]     = y0;
-                        ymine[(mt * CPL + j0 + 1) * 64] = y1;
-                    }
-                }
-            }
-        }
-    };
-
-    // ---- main loop: groups of four k-steps, loads three steps ahead of compute ----
-    MORPH_TICK(0);
-    const int g0 = ks0 >> 2, g1 = (ks1 + 3) >> 2;        // groups touched by [ks0, ks1)
-    StageT        buf[NS];
-    GroupRaw<WPL> gcur, gnext;
-    if constexpr (W4) load_group(gnext, g0);
-#pragma unroll
-    for (int i = 0; i < NS - 1; i++) {
-        load_stage(buf[i], 4 * g0 + i);
-        __builtin_amdgcn_sched_barrier(0);               // keep the stages in issue order: the waits count on it
-    }
-    for (int g = g0; g < g1; g++) {
-        if constexpr (W4) gcur = gnext;
-#pragma unroll
-        for (int u = 0; u < NS; u++) {
-            const int k = 4 * g + u;                     // step computed in this slot
-            load_stage(buf[(u + NS - 1) % NS], k + NS - 1);
-            if constexpr (W4) {
-                if (u == 1) load_group(gnext, g + 1);    // arrives well before the next group opens
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            // A dead step holds zeros in x and in the weights and adds nothing; computing it anyway
-            // keeps the slot free of branches.
-            compute(buf[u], u == 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if constexpr (W4) flush_group(gcur);
-    }
-    MORPH_TICK(1);
+    TileJob job;
+    job.x = (const half_t*)p.x + (size_t)mbase * p.K;
+    job.w = p.w; job.scales = p.scales; job.qzeros = p.qzeros;
+    job.M = M; job.K = p.K; job.N = N; job.n0 = n0; job.S = S; job.sp = sp;
+    tile_partial<W4, MT, kWaves, false>(job, yl);
 
     // ---- sum the waves that share columns (in the order of their k parts) and write out ----
-    if constexpr (!W4) {
-#pragma unroll
-        for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-            for (int j = 0; j < CPL; j++) ymine[(mt * CPL + j) * 64] = gacc[mt][j];
-    }
-    __syncthreads();
-    MORPH_TICK(2);
-    constexpr int ITEMS = WN * NV * 64;                  // f32x4 vectors of the workgroup tile
     half_t* y = (half_t*)p.y + (size_t)mbase * N;
-    auto item_sum = [&](int it) {
-        const int pn = it / (NV * 64), rem = it - pn * (NV * 64);    // column part, (v, lane)
-        f32x4 acc = yl[(size_t)pn * NV * 64 + rem];                  // wave with wk = 0
-#pragma unroll
-        for (int q = 1; q < WK; q++) acc += yl[(size_t)(q * WN + pn) * NV * 64 + rem];
-        return acc;
-    };
+    auto item_sum = [&](int it) { return G::item_sum(yl, it); };
     auto item_store_y = [&](int it, f32x4 acc) {
         const int pn = it / (NV * 64), rem = it - pn * (NV * 64);
         const int v = rem >> 6, ln = rem & 63;
@@ -398,7 +111,7 @@ template <bool W4, int MT, int kWaves>
 hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
 {
     constexpr int tnb = Tile<W4, MT>::TN * Tile<W4, MT>::WN;
-    constexpr size_t lds = (size_t)kWaves * MT * Tile<W4, MT>::CPL * 64 * sizeof(f32x4);
+    constexpr size_t lds = TileGeom<W4, MT, kWaves>::kLdsBytes;
     static_assert(lds <= 128 * 1024, "LDS of one compute unit");
     if (lds > 64 * 1024) {
         static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<W4, MT, kWaves>),
