@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="headline only, skip the detail sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--sections", default="config2,config3,config4,config5",
+                    help="detail sections to run after the headline (comma separated; used by the profiling commands)")
     return ap.parse_args()
 
 
@@ -182,7 +184,8 @@ def main():
     del cal_src, cal_dst
 
     detail = {}
-    if not args.quick:
+    sections = set() if args.quick else set(args.sections.split(","))
+    if sections:
         # ---- per linear and per M, one shape back to back over the pool (W4A16 and fp16) ----
         def per_linear(kind, family, name, M, recs, reps=60):
             K, N = synth.LAYER_SHAPES[family][name]
@@ -203,35 +206,39 @@ def main():
                     "TFLOPs": round(2.0 * M * K * N / s / 1e12, 2)}
 
         d7 = {}
-        for name in order:
-            recs = [layer[name] for layer in pool]
-            for M in (1, 4, 16):
-                d7[f"w4a16/{name}/M{M}"] = per_linear(B.KIND_W4A16, "llama7b", name, M, recs)
+        if "config2" in sections:
+            for name in order:
+                recs = [layer[name] for layer in pool]
+                for M in (1, 4, 16):
+                    d7[f"w4a16/{name}/M{M}"] = per_linear(B.KIND_W4A16, "llama7b", name, M, recs)
         del graphs
-        # fp16 comparison: pool of 4 layers x 405 MB
-        pool16 = [{name: make_fp16(*shapes7[name]) for name in order} for _ in range(4)]
-        for name in order:
-            recs = [layer[name] for layer in pool16]
-            for M in (1, 4, 16):
-                d7[f"fp16/{name}/M{M}"] = per_linear(B.KIND_FP16, "llama7b", name, M, recs, reps=24)
-        detail["config2_llama7b"] = d7
-        del pool16
+        if "config2" in sections:
+            # fp16 comparison: pool of 4 layers x 405 MB
+            pool16 = [{name: make_fp16(*shapes7[name]) for name in order} for _ in range(4)]
+            for name in order:
+                recs = [layer[name] for layer in pool16]
+                for M in (1, 4, 16):
+                    d7[f"fp16/{name}/M{M}"] = per_linear(B.KIND_FP16, "llama7b", name, M, recs, reps=24)
+            detail["config2_llama7b"] = d7
+            del pool16
+        del pool
 
         # ---- config 3: 8B GQA shapes, W4A16, M up to 64 ----
-        shapes8 = synth.LAYER_SHAPES["llama3_8b"]
-        pool8 = [{name: make_w4(*shapes8[name]) for name in order} for _ in range(10)]
-        d8 = {}
-        for name in order:
-            recs = [layer[name] for layer in pool8]
-            for M in (1, 8, 32, 64):
-                d8[f"w4a16/{name}/M{M}"] = per_linear(B.KIND_W4A16, "llama3_8b", name, M, recs)
-        detail["config3_llama3_8b"] = d8
-        del pool8
+        if "config3" in sections:
+            shapes8 = synth.LAYER_SHAPES["llama3_8b"]
+            pool8 = [{name: make_w4(*shapes8[name]) for name in order} for _ in range(10)]
+            d8 = {}
+            for name in order:
+                recs = [layer[name] for layer in pool8]
+                for M in (1, 8, 32, 64):
+                    d8[f"w4a16/{name}/M{M}"] = per_linear(B.KIND_W4A16, "llama3_8b", name, M, recs)
+            detail["config3_llama3_8b"] = d8
+            del pool8
 
         # ---- config 4: 13B prefill chunk ----
         shapes13 = synth.LAYER_SHAPES["llama13b"]
         d13 = {}
-        for name in order:
+        for name in (order if "config4" in sections else ()):
             K, N = shapes13[name]
             w4 = make_w4(K, N)
             w16 = make_fp16(K, N)
@@ -246,14 +253,15 @@ def main():
                     d13[f"{label}/{name}/M{M}"] = {"us": round(s * 1e6, 1), "TFLOPs": round(tf, 1),
                                                    "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1)}
             del w4, w16
-        detail["config4_llama13b_prefill"] = d13
+        if d13:
+            detail["config4_llama13b_prefill"] = d13
 
         # ---- config 5: 32-layer mixed stack at M = 32 ----
-        M5, L5 = 32, 32
+        M5, L5 = 32, (32 if "config5" in sections else 0)
         base16 = [{name: make_fp16(*shapes7[name]) for name in order} for _ in range(L5)]
         base4 = [{name: B.quantize_layer(base16[l][name]) for name in order} for l in range(L5)]
         d5 = {}
-        for k in (0, 8, 16, 32):
+        for k in ((0, 8, 16, 32) if L5 else ()):
             swapped = set(synth.swapped_layers(L5, k).tolist())
             st = B.LayerStack(4096, 11008, M5)
             for l in range(L5):
@@ -267,8 +275,16 @@ def main():
             nbytes = sum((bytes_ws if l in swapped else sum(synth.fp16_bytes(*shapes7[n]) for n in order)) for l in range(L5))
             d5[f"k{k}"] = {"ms": round(s * 1e3, 4), "GBps": round(nbytes / s / 1e9, 1),
                            "pct_hbm": round(nbytes / s / 1e9 / HBM_PEAK_GBS * 100, 1), "weight_GB": round(nbytes / 1e9, 3)}
-            del g5, st
-        detail["config5_stack_M32"] = d5
+            # the same step as two persistent launches of 16 layers each
+            g5f = graph_of(lambda: st.forward_fused(x5))
+            sf = timed(lambda i: g5f.replay(), 10, 2) / 10
+            if st.fused_abandoned():
+                raise RuntimeError("persistent stack launch was abandoned at a barrier")
+            d5[f"k{k}"].update({"persistent_ms": round(sf * 1e3, 4), "persistent_GBps": round(nbytes / sf / 1e9, 1),
+                                "persistent_pct_hbm": round(nbytes / sf / 1e9 / HBM_PEAK_GBS * 100, 1)})
+            del g5, g5f, st
+        if d5:
+            detail["config5_stack_M32"] = d5
         del base16, base4
         result["detail"] = detail
 
@@ -277,20 +293,28 @@ def main():
         from oracle import build as ob
         ob.build(force=False)
         from oracle import cpu_oracle as O
-        Mc = 4
-        t_total, b_total = 0.0, 0
+        # the bench step itself (one layer's four linears at M = 1, 4, 16), repeated on one layer's
+        # weights until about ten seconds of oracle time have been spent
+        recs, xs_c = {}, {}
         for name in order:
             K, N = shapes7[name]
-            W = synth.weights(2, K, N, tensor_id=synth._TENSOR_ID[name])
-            qw, sc, qz = O.quantize_w4(W)
-            x = synth.activations(2, Mc, K)
-            t0 = time.perf_counter()
-            O.linear_w4a16(x, qw, sc, qz)
-            t_total += time.perf_counter() - t0
-            b_total += synth.w4_bytes(K, N, zeros=False)
+            recs[name] = O.quantize_w4(synth.weights(2, K, N, tensor_id=synth._TENSOR_ID[name]))
+            for Mc in Ms:
+                xs_c[(Mc, K)] = synth.activations(2, Mc, K, tensor_id=Mc)
+        t_total, b_total, reps = 0.0, 0, 0
+        while t_total < 10.0 and reps < 64:
+            for Mc in Ms:
+                for name in order:
+                    K, N = shapes7[name]
+                    t0 = time.perf_counter()
+                    O.linear_w4a16(xs_c[(Mc, K)], *recs[name])
+                    t_total += time.perf_counter() - t0
+                    b_total += synth.w4_bytes(K, N, zeros=False)
+            reps += 1
         result["cpu_baseline"] = {"value": round(b_total / t_total / 1e9, 4), "unit": "GB/s", "cores": O.num_threads(),
                                   "kind": "oracle",
-                                  "sample": f"one llama7b layer (4 linears) W4A16 at M={Mc}, fp64 oracle, {t_total:.2f} s"}
+                                  "sample": f"{reps} repetitions of the bench step (llama7b layer, 4 linears, W4A16, "
+                                            f"M in {{1,4,16}}) on one layer's weights, fp64 oracle, {t_total:.1f} s"}
     print(json.dumps(result))
 
 

@@ -82,17 +82,24 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     f32x4 acc[IPT];
 #pragma unroll
     for (int i = 0; i < IPT; i++) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int s2 = 0; s2 < S; s2 += 4) {
-        f32x4 v[4][IPT];
+    constexpr int CH = IPT <= 4 ? 8 : 4;                 // splits fetched together (registers are free here)
+    uint32_t item_off[IPT];
 #pragma unroll
-        for (int q = 0; q < 4; q++)
+    for (int i = 0; i < IPT; i++) {                      // vectors made of rows that do not exist are not fetched
+        const int it = tid + i * kWaves * 64;
+        item_off[i] = item_rows_live(it) ? (uint32_t)it * 16u : 0xFFFFFFF0u;
+    }
+    for (int s2 = 0; s2 < S; s2 += CH) {
+        f32x4 v[CH][IPT];
+#pragma unroll
+        for (int q = 0; q < CH; q++)
 #pragma unroll
             for (int i = 0; i < IPT; i++) {
                 // splits beyond S read past the buffer and come back as zeros
-                v[q][i] = buf_load_through(rp, (uint32_t)(s2 + q) * kPartBytes + (uint32_t)(tid + i * kWaves * 64) * 16u);
+                v[q][i] = bit_cast<f32x4>(__builtin_amdgcn_raw_buffer_load_b128(rp, item_off[i], (uint32_t)(s2 + q) * kPartBytes, kAuxSystemScope));
             }
 #pragma unroll
-        for (int q = 0; q < 4; q++)
+        for (int q = 0; q < CH; q++)
 #pragma unroll
             for (int i = 0; i < IPT; i++) acc[i] += v[q][i];
     }

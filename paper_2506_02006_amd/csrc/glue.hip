@@ -40,19 +40,32 @@ __device__ __forceinline__ void glue_values(const half_t* a, const half_t* b, in
     }
 }
 
-// One workgroup per row.  Pass 1 sums squares, pass 2 recomputes the same fp32 values (inputs
-// are a few KB and still in cache) and scales them.
+// One workgroup per row.  Every thread computes its fp32 values once and keeps up to kGlueCache
+// vectors of them in registers across the row-wide sum of squares (rows wider than
+// 8 * kGlueThreads * kGlueCache columns recompute the rest: their inputs are still in cache).
+constexpr int kGlueThreads = 512, kGlueCache = 4;
 template <int OP>
-__global__ __launch_bounds__(256) void glue_kernel(const half_t* __restrict__ a, const half_t* __restrict__ b,
-                                                   half_t* __restrict__ out, int H)
+__global__ __launch_bounds__(kGlueThreads) void glue_kernel(const half_t* __restrict__ a, const half_t* __restrict__ b,
+                                                            half_t* __restrict__ out, int H)
 {
-    __shared__ float wsum[4];
+    __shared__ float wsum[kGlueThreads / 64];
     const int row = blockIdx.x, tid = threadIdx.x;
     const int in_cols = OP == 0 ? 3 * H : (OP == 2 ? 2 * H : H);
     const half_t* ar = a + (size_t)row * in_cols;
     const half_t* br = OP == 1 ? b + (size_t)row * H : nullptr;
+    const int nv = H / 8;
+    float xc[kGlueCache][8];
     float ss = 0.f;
-    for (int v = tid; v < H / 8; v += 256) {
+#pragma unroll
+    for (int c = 0; c < kGlueCache; c++) {
+        const int v = tid + c * kGlueThreads;
+        if (v < nv) {
+            glue_values<OP>(ar, br, H, v, xc[c]);
+#pragma unroll
+            for (int j = 0; j < 8; j++) ss += xc[c][j] * xc[c][j];
+        }
+    }
+    for (int v = tid + kGlueCache * kGlueThreads; v < nv; v += kGlueThreads) {
         float x[8];
         glue_values<OP>(ar, br, H, v, x);
 #pragma unroll
@@ -62,9 +75,21 @@ __global__ __launch_bounds__(256) void glue_kernel(const half_t* __restrict__ a,
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
     if ((tid & 63) == 0) wsum[tid >> 6] = ss;
     __syncthreads();
-    const float total = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
-    const float inv   = 1.0f / sqrtf(total / (float)H + kRmsEps);
-    for (int v = tid; v < H / 8; v += 256) {
+    float total = 0.f;
+#pragma unroll
+    for (int w = 0; w < kGlueThreads / 64; w++) total += wsum[w];
+    const float inv = 1.0f / sqrtf(total / (float)H + kRmsEps);
+#pragma unroll
+    for (int c = 0; c < kGlueCache; c++) {
+        const int v = tid + c * kGlueThreads;
+        if (v < nv) {
+            half8_t h;
+#pragma unroll
+            for (int j = 0; j < 8; j++) h[j] = (half_t)(xc[c][j] * inv);
+            *reinterpret_cast<half8_t*>(out + (size_t)row * H + 8 * v) = h;
+        }
+    }
+    for (int v = tid + kGlueCache * kGlueThreads; v < nv; v += kGlueThreads) {
         float x[8];
         glue_values<OP>(ar, br, H, v, x);
         half8_t h;
@@ -94,10 +119,10 @@ hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, i
     const half_t* hb = (const half_t*)b;
     half_t*       ho = (half_t*)out;
     switch (op) {
-        case 0: hipLaunchKernelGGL(glue_kernel<0>, dim3(M), dim3(256), 0, st, ha, hb, ho, H); break;
-        case 1: hipLaunchKernelGGL(glue_kernel<1>, dim3(M), dim3(256), 0, st, ha, hb, ho, H); break;
-        case 2: hipLaunchKernelGGL(glue_kernel<2>, dim3(M), dim3(256), 0, st, ha, hb, ho, H); break;
-        default: hipLaunchKernelGGL(glue_kernel<3>, dim3(M), dim3(256), 0, st, ha, hb, ho, H); break;
+        case 0: hipLaunchKernelGGL(glue_kernel<0>, dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
+        case 1: hipLaunchKernelGGL(glue_kernel<1>, dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
+        case 2: hipLaunchKernelGGL(glue_kernel<2>, dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
+        default: hipLaunchKernelGGL(glue_kernel<3>, dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
     }
     return hipGetLastError();
 }

@@ -11,6 +11,10 @@ under profiles/.
 --fetch / --write : `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of the same command.
           The counters are scaled by what they read for the library's plain copy kernel, whose
           transfer size bench.py fixes (COPY_BYTES read and COPY_BYTES written per launch).
+--counters : any other `rocprofv3 --pmc ...` run of the same command; prints the mean of every
+          counter per (kernel, grid) for kernels matching --like, and, where the MFMA operation
+          counter is among them, TFLOP/s = 512 * SQ_INSTS_VALU_MFMA_MOPS_F16 / mean duration of
+          the same (kernel, grid) in --trace, against the dense fp16 peak.
 """
 import argparse
 import sqlite3
@@ -45,6 +49,8 @@ def main():
     ap.add_argument("--command", default="")
     ap.add_argument("--note", default="")
     ap.add_argument("--mean-of", default="", help="kernel name prefix: print its launch-weighted mean traffic and duration")
+    ap.add_argument("--counters", help="results db of a further --pmc run")
+    ap.add_argument("--like", default="prefill_kernel", help="kernel name substring for --counters")
     a = ap.parse_args()
     if a.command:
         print("command:")
@@ -82,6 +88,28 @@ def main():
             tot = sum(f[k][0] * (f[k][1] * f_scale + w[k][1] * w_scale) * 1024 for k in ks)
             print(f"\nlaunch-weighted mean over {a.mean_of} (rows with n >= 10):")
             print(f"traffic_bytes_per_launch_mean: {tot / n:.0f}")
+    if a.counters:
+        c = sqlite3.connect(a.counters)
+        q = ("select kernel_name, grid_size_x, grid_size_y, counter_name, count(*), avg(value) from counters_collection "
+             "where kernel_name like ? group by kernel_name, grid_size_x, grid_size_y, counter_name")
+        rows = c.execute(q, ("%" + a.like + "%",)).fetchall()
+        dur = {}
+        if a.trace:
+            dur = {(short(r[0]), r[1], r[2]): r[4] for r in trace_rows(a.trace)}
+        names = sorted({r[3] for r in rows})
+        print(f"\nhardware counters per launch (rocprofv3 --pmc {' '.join(names)}), mean over launches")
+        keys = sorted({(short(r[0]), r[1], r[2]) for r in rows})
+        for k in keys:
+            vals = {r[3]: (r[4], r[5]) for r in rows if (short(r[0]), r[1], r[2]) == k}
+            n = max(v[0] for v in vals.values())
+            print(f"{k[0][:70]}  grid {k[1]}x{k[2]}  launches {n}")
+            for cn in names:
+                if cn in vals:
+                    print(f"    {cn:34s} {vals[cn][1]:16.4e}")
+            mops = vals.get("SQ_INSTS_VALU_MFMA_MOPS_F16")
+            if mops and k in dur:
+                tf = 512.0 * mops[1] / (dur[k] * 1e-6) / 1e12
+                print(f"    -> {512.0 * mops[1]:.4e} MFMA flop in {dur[k]:.1f} us = {tf:.1f} TFLOP/s = {tf / 2500.0 * 100:.1f} % of 2.5 PFLOP/s dense fp16")
     if a.mean_of and a.trace:
         rows = [r for r in trace_rows(a.trace) if short(r[0]).startswith(a.mean_of) and r[3] >= 10]
         n = sum(r[3] for r in rows)
