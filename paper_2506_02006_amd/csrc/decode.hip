@@ -112,7 +112,14 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     MORPH_TICK(5);
 }
 
-inline int decode_waves() { return tuning_get(TUNE_DECODE_WAVES) == 8 ? 8 : 4; }
+// Waves per workgroup: two M tiles (M > 16) halve the bytes a wave keeps in flight, so eight waves per
+// compute unit in one workgroup do better there; one M tile runs best as two workgroups of four.
+inline int decode_waves(int M)
+{
+    const int t = tuning_get(TUNE_DECODE_WAVES);
+    if (t == 4 || t == 8) return t;
+    return M > 16 ? 8 : 4;
+}
 
 template <bool W4, int MT, int kWaves>
 hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
@@ -133,7 +140,7 @@ hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
 template <bool W4, int MT>
 hipError_t launch_one(const DecodeArgs& a, int slices, hipStream_t st)
 {
-    return decode_waves() == 8 ? launch_waves<W4, MT, 8>(a, slices, st) : launch_waves<W4, MT, 4>(a, slices, st);
+    return decode_waves(a.M) == 8 ? launch_waves<W4, MT, 8>(a, slices, st) : launch_waves<W4, MT, 4>(a, slices, st);
 }
 
 }  // namespace
@@ -154,7 +161,7 @@ DecodePlan plan_decode(int is_w4, int M, int K, int N)
 {
     DecodePlan pl;
     pl.tile_n = !is_w4 ? Tile<false, 1>::TN : 256;      // workgroup tile (W4: 1 x 256 or 2 x 128 columns)
-    const int kWaves = decode_waves();
+    const int kWaves = decode_waves(M);
     const int wk = (is_w4 && M > 16) ? kWaves / Tile<true, 2>::WN : kWaves;   // waves of a workgroup along K
     pl.tiles  = (N + pl.tile_n - 1) / pl.tile_n;
     pl.slices = (M + 31) / 32;

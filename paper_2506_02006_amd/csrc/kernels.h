@@ -49,6 +49,7 @@ struct GemmArgs {
     int         config;    // tile configuration (PrefillPlan::config)
     int         grid;      // workgroups (PrefillPlan::grid)
     int         split_tail; // share the last partial round out along K (PrefillPlan::split_tail)
+    int         map;        // schedule index -> tile: 1 = column-major over (row tile, column tile), 2 = blocks of 8 column tiles dealt out to 8 XCDs (set by launch_prefill)
 };
 struct PrefillPlan {
     int    config, bm, bn, tiles, grid, split_tail;
@@ -93,6 +94,6 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_COUNT = 8 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_COUNT = 8 };
 
 }  // namespace morph
