@@ -16,6 +16,7 @@ namespace {
 template <bool W4, int MT, int kWaves>
 __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kernel(DecodeArgs p)
 {
+    MORPH_TICK(6);                                       // kernel entry
     typedef TileGeom<W4, MT, kWaves> G;
     constexpr int CPL = G::CPL, TN = G::TN, TNB = G::TNB, NV = G::NV, ITEMS = G::ITEMS;
     extern __shared__ __align__(16) f32x4 yl[];

@@ -332,6 +332,7 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
         load_stage(buf[i], 4 * g0 + i);
         __builtin_amdgcn_sched_barrier(0);               // keep the stages in issue order: the waits count on it
     }
+    MORPH_TICK(7);                                       // prologue loads issued
     for (int g = g0; g < g1; g++) {
         if constexpr (W4) gcur = gnext;
 #pragma unroll

@@ -6,86 +6,130 @@
 
 namespace morph {
 
-// One thread owns one packed word: 8 consecutive columns of one 128-row group.  Neighbouring
-// threads own neighbouring words, so every row of the group is read as one contiguous run.
-// Pass 1 finds the range, pass 2 (served by L2: a workgroup's tile is re-read at once) codes.
+// One workgroup owns one 128-row group of kQC consecutive columns.  The tile is read from memory
+// once, in 256-byte (fp32) or 128-byte (fp16) runs per row, and parked in LDS as fp32; the
+// column ranges, the scales and zero points and finally the codes are all computed from there.
+constexpr int kQC = 64;                                   // columns per workgroup (34 KB of LDS: four workgroups per compute unit)
+constexpr int kQT = 256 / kQC;                            // threads per column in the range pass
+constexpr int kQP = kQC + 4;                              // LDS pitch in floats (keeps 16-byte alignment, skews the banks)
 template <typename WT>
 __global__ __launch_bounds__(256) void quantize_w4_kernel(const WT* __restrict__ w,
                                                           uint32_t* __restrict__ qweight,
                                                           half_t* __restrict__ scales,
                                                           uint32_t* __restrict__ qzeros, int K, int N)
 {
+    __shared__ __align__(16) float tile[kGroup * kQP];
+    __shared__ float part_lo[kQT][kQC], part_hi[kQT][kQC];
+    __shared__ float sfl[kQC];
+    __shared__ int   zl[kQC];
+    const int tid = threadIdx.x;
     const int NW = N >> 3;
-    const int c  = blockIdx.x * blockDim.x + threadIdx.x;   // word column
+    const int n0 = blockIdx.x * kQC;                        // first column
     const int g  = blockIdx.y;                              // group
-    if (c >= NW) return;
-    const WT* base = w + (size_t)g * kGroup * N + (size_t)c * 8;
+    const WT* base = w + (size_t)g * kGroup * N + n0;
 
-    float lo[8], hi[8];
+    // ---- the tile, once ----
+    if constexpr (sizeof(WT) == 4) {
+        constexpr int PPR = kQC / 4;                        // 16-byte pieces per row
+        f32x4 v[kGroup * PPR / 256];
 #pragma unroll
-    for (int j = 0; j < 8; j++) { lo[j] = 0.f; hi[j] = 0.f; }
-    for (int r = 0; r < kGroup; r++) {
-        float v[8];
-        if constexpr (sizeof(WT) == 4) {
-            const f32x4* p = reinterpret_cast<const f32x4*>(base + (size_t)r * N);
-            f32x4 a = p[0], b = p[1];
-#pragma unroll
-            for (int j = 0; j < 4; j++) { v[j] = a[j]; v[4 + j] = b[j]; }
-        } else {
-            half8_t h = *reinterpret_cast<const half8_t*>(base + (size_t)r * N);
-#pragma unroll
-            for (int j = 0; j < 8; j++) v[j] = (float)h[j];
+        for (int i = 0; i < kGroup * PPR / 256; i++) {
+            const int p = tid + 256 * i, row = p / PPR, pc = p - row * PPR;
+            v[i] = n0 + 4 * pc < N ? *reinterpret_cast<const f32x4*>(base + (size_t)row * N + 4 * pc) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            lo[j] = v[j] < lo[j] ? v[j] : lo[j];
-            hi[j] = v[j] > hi[j] ? v[j] : hi[j];
+        for (int i = 0; i < kGroup * PPR / 256; i++) {
+            const int p = tid + 256 * i, row = p / PPR, pc = p - row * PPR;
+            *reinterpret_cast<f32x4*>(tile + row * kQP + 4 * pc) = v[i];
+        }
+    } else {
+        constexpr int PPR = kQC / 8;
+        half8_t v[kGroup * PPR / 256];
+        const half8_t zero8 = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+#pragma unroll
+        for (int i = 0; i < kGroup * PPR / 256; i++) {
+            const int p = tid + 256 * i, row = p / PPR, pc = p - row * PPR;
+            v[i] = n0 + 8 * pc < N ? *reinterpret_cast<const half8_t*>(base + (size_t)row * N + 8 * pc) : zero8;
+        }
+#pragma unroll
+        for (int i = 0; i < kGroup * PPR / 256; i++) {
+            const int p = tid + 256 * i, row = p / PPR, pc = p - row * PPR;
+            const f32x4 a = {(float)v[i][0], (float)v[i][1], (float)v[i][2], (float)v[i][3]};
+            const f32x4 b = {(float)v[i][4], (float)v[i][5], (float)v[i][6], (float)v[i][7]};
+            *reinterpret_cast<f32x4*>(tile + row * kQP + 8 * pc)     = a;
+            *reinterpret_cast<f32x4*>(tile + row * kQP + 8 * pc + 4) = b;
         }
     }
+    __syncthreads();
 
-    float    sf[8];
-    int      z[8];
-    uint32_t zword = 0;
-    half8_t  sh;
+    // ---- range of every column (widened to contain 0), kQT threads per column ----
+    {
+        const int c = tid & (kQC - 1), h = tid / kQC;
+        float lo = 0.f, hi = 0.f;
+#pragma unroll 8
+        for (int r = 0; r < kGroup / kQT; r++) {
+            const float v = tile[(h * (kGroup / kQT) + r) * kQP + c];
+            lo = v < lo ? v : lo;
+            hi = v > hi ? v : hi;
+        }
+        part_lo[h][c] = lo;
+        part_hi[h][c] = hi;
+    }
+    __syncthreads();
+    if (tid < kQC) {
+        float lo = part_lo[0][tid], hi = part_hi[0][tid];
 #pragma unroll
-    for (int j = 0; j < 8; j++) {
-        float    s32  = __fdiv_rn(hi[j] - lo[j], 15.0f);
+        for (int h = 1; h < kQT; h++) {
+            lo = part_lo[h][tid] < lo ? part_lo[h][tid] : lo;
+            hi = part_hi[h][tid] > hi ? part_hi[h][tid] : hi;
+        }
+        const float s32 = __fdiv_rn(hi - lo, 15.0f);
         half_t   s    = (half_t)s32;                        // round to nearest even
         uint16_t bits = bit_cast<uint16_t>(s);
         if ((float)s < s32) bits = (uint16_t)(bits + 1);    // round the step size up
         if (bits < 0x0400u) bits = 0x0400u;                 // at least 2^-14 (stay normal)
         if (bits > 0x7BFFu) bits = 0x7BFFu;                 // at most 65504
-        s     = bit_cast<half_t>(bits);
-        sf[j] = (float)s;
-        int zz = (int)rintf(__fdiv_rn(-lo[j], sf[j]));
+        s = bit_cast<half_t>(bits);
+        const float sf = (float)s;
+        int zz = (int)rintf(__fdiv_rn(-lo, sf));
         zz     = zz < 0 ? 0 : (zz > 15 ? 15 : zz);
-        z[j]   = zz;
-        zword |= (uint32_t)zz << (4 * j);
-        sh[j] = s;
+        sfl[tid] = sf;
+        zl[tid]  = zz;
+        if (n0 + tid < N) scales[(size_t)g * N + n0 + tid] = s;
     }
-    qzeros[(size_t)g * NW + c] = zword;
-    *reinterpret_cast<half8_t*>(scales + (size_t)g * N + (size_t)c * 8) = sh;
+    __syncthreads();
+    if (tid < kQC / 8 && n0 + 8 * tid < N) {
+        uint32_t zword = 0;
+#pragma unroll
+        for (int j = 0; j < 8; j++) zword |= (uint32_t)zl[8 * tid + j] << (4 * j);
+        qzeros[(size_t)g * NW + (n0 >> 3) + tid] = zword;
+    }
 
-    for (int r = 0; r < kGroup; r++) {
-        float v[8];
-        if constexpr (sizeof(WT) == 4) {
-            const f32x4* p = reinterpret_cast<const f32x4*>(base + (size_t)r * N);
-            f32x4 a = p[0], b = p[1];
+    // ---- codes: a thread keeps one word column (its 8 scales and zero points) and walks the rows ----
+    {
+        constexpr int WPR = kQC / 8;                        // words per row of the tile
+        const int cw = tid & (WPR - 1);
+        float sf[8];
+        int   z[8];
 #pragma unroll
-            for (int j = 0; j < 4; j++) { v[j] = a[j]; v[4 + j] = b[j]; }
-        } else {
-            half8_t h = *reinterpret_cast<const half8_t*>(base + (size_t)r * N);
+        for (int j = 0; j < 8; j++) { sf[j] = sfl[8 * cw + j]; z[j] = zl[8 * cw + j]; }
+        if (n0 + 8 * cw < N) {
+#pragma unroll 4
+            for (int i = 0; i < kGroup * WPR / 256; i++) {
+                const int row = (tid + 256 * i) / WPR;
+                const f32x4 a = *reinterpret_cast<const f32x4*>(tile + row * kQP + 8 * cw);
+                const f32x4 b = *reinterpret_cast<const f32x4*>(tile + row * kQP + 8 * cw + 4);
+                const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+                uint32_t word = 0;
 #pragma unroll
-            for (int j = 0; j < 8; j++) v[j] = (float)h[j];
+                for (int j = 0; j < 8; j++) {
+                    int q = (int)rintf(__fdiv_rn(v[j], sf[j])) + z[j];
+                    q     = q < 0 ? 0 : (q > 15 ? 15 : q);
+                    word |= (uint32_t)q << (4 * j);
+                }
+                qweight[((size_t)g * kGroup + row) * NW + (n0 >> 3) + cw] = word;
+            }
         }
-        uint32_t word = 0;
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-            int q = (int)rintf(__fdiv_rn(v[j], sf[j])) + z[j];
-            q     = q < 0 ? 0 : (q > 15 ? 15 : q);
-            word |= (uint32_t)q << (4 * j);
-        }
-        qweight[((size_t)g * kGroup + r) * NW + c] = word;
     }
 }
 
@@ -126,7 +170,7 @@ __global__ __launch_bounds__(256) void dequantize_w4_kernel(const uint32_t* __re
 hipError_t launch_quantize_w4(const void* w, int w_is_f16, uint32_t* qweight, void* scales,
                               uint32_t* qzeros, int K, int N, hipStream_t st)
 {
-    dim3 grid((N / 8 + 255) / 256, K / kGroup), block(256);
+    dim3 grid((N + kQC - 1) / kQC, K / kGroup), block(256);
     if (w_is_f16)
         hipLaunchKernelGGL(quantize_w4_kernel<half_t>, grid, block, 0, st, (const half_t*)w, qweight,
                            (half_t*)scales, qzeros, K, N);

@@ -170,7 +170,7 @@ __device__ __forceinline__ LinGeom lin_geom(int li, int H, int I)
 constexpr int kPrefetchLoads = 4;                        // touches per thread and call
 struct Prefetch { uint32_t t[kPrefetchLoads]; };
 template <int MT>
-__device__ __forceinline__ Prefetch prefetch_issue(const StackArgs& p, int l, int li, int half, int G, int g)
+__device__ __forceinline__ Prefetch prefetch_issue(const StackArgs& p, const StackLinear (*lin)[4], int l, int li, int half, int G, int g)
 {
     Prefetch r;
 #pragma unroll
@@ -178,7 +178,7 @@ __device__ __forceinline__ Prefetch prefetch_issue(const StackArgs& p, int l, in
     int l2 = l, li2 = li + 1;
     if (li2 == 4) { l2 = l + 1; li2 = 0; }
     if (l2 >= p.n_layers) return r;
-    const StackLinear lw = p.lin[l2][li2];
+    const StackLinear lw = lin[l2][li2];
     const bool w4 = lw.scales != nullptr;
     const LinGeom q = lin_geom(li2, p.hidden, p.inter);
     const int tnb = w4 ? TileGeom<true, MT, kStackWaves>::TNB : TileGeom<false, MT, kStackWaves>::TNB;
@@ -367,6 +367,14 @@ __global__ __launch_bounds__(kStackWaves * 64, 1) void stack_kernel(StackArgs p)
     const int G = gridDim.x, g = blockIdx.x;
     const int M = p.M, H = p.hidden, I = p.inter;
 
+    // The layer table is read once, by all threads, into LDS: the kernel arguments sit in memory
+    // that is slow to reach (a scalar load from them costs about a microsecond per phase).
+    __shared__ StackLinear lds_lin[kStackMaxLayers][4];
+    {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&p.lin[0][0]);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&lds_lin[0][0]);
+        for (int i = tid; i < (int)(sizeof(lds_lin) / 4); i += kStackWaves * 64) dst[i] = src[i];
+    }
     // a launch that follows an abandoned one does nothing (the workspace must be prepared again)
     if (tid == 0) lds_flag = load_word_through(p.sync + 2);
     __syncthreads();
@@ -377,7 +385,7 @@ __global__ __launch_bounds__(kStackWaves * 64, 1) void stack_kernel(StackArgs p)
     for (int l = 0; l < p.n_layers; l++) {
         STACK_TICK_ON(l == p.n_layers - 1);
         for (int li = 0; li < 4; li++) {
-            const StackLinear lw = p.lin[l][li];
+            const StackLinear lw = lds_lin[l][li];
             const bool w4 = lw.scales != nullptr;
             const LinGeom q = lin_geom(li, H, I);
             const half_t* vin = (l == 0 && li == 0) ? p.x_io : act_buf(p, l, li);
@@ -389,7 +397,7 @@ __global__ __launch_bounds__(kStackWaves * 64, 1) void stack_kernel(StackArgs p)
             // the shares of the input's sums of squares were complete before this linear began:
             // fetch them while waiting for everybody's partial products
             const SsRegs ssr = ss_issue(ss_buf(p, l, li), (l == 0 && li == 0) ? 0 : M);
-            const Prefetch pf0 = prefetch_issue<MT>(p, l, li, 0, G, g);
+            const Prefetch pf0 = prefetch_issue<MT>(p, lds_lin, l, li, 0, G, g);
             if (!grid_wait(p.sync, nb, &lds_flag)) return;
             STACK_TICK(li * 8 + 2);
             if (li == 0)      phase_reduce<MT, 3>(p, l, li, w4, ssr, G, g, lds);
@@ -398,7 +406,7 @@ __global__ __launch_bounds__(kStackWaves * 64, 1) void stack_kernel(StackArgs p)
             prefetch_done(pf0);
             STACK_TICK(li * 8 + 3);
             grid_arrive(p.sync, ++nb, G);
-            const Prefetch pf1 = prefetch_issue<MT>(p, l, li, 1, G, g);
+            const Prefetch pf1 = prefetch_issue<MT>(p, lds_lin, l, li, 1, G, g);
             if (!grid_wait(p.sync, nb, &lds_flag)) return;
             prefetch_done(pf1);
             STACK_TICK(li * 8 + 4);

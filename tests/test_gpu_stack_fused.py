@@ -196,6 +196,32 @@ def test_fused_same_workspace_different_inputs(B, oracle):
         assert e["finite"] and e["err"] <= 1e-2
 
 
+def test_fused_abandoned_workspace_is_left_alone(B, oracle):
+    """The abort word is raised from the host (never by making a kernel wait): launches on that
+    workspace then return at once without touching x, until the workspace is prepared again."""
+    hidden, inter, M = 256, 384, 4
+    rec, hostrec = make_layer(oracle, shapes_of(hidden, inter), ALL_FP16, 93, 0)
+    st = B.LayerStack(hidden, inter, M)
+    st.add_layer(rec)
+    x0 = synth.activations(93, M, hidden).astype(np.float16)
+    x = dev(x0).clone()
+    st.forward_fused(x)
+    torch.cuda.synchronize()
+    good = host(x).copy()
+    st.fused_ws[8:12].view(torch.int32).fill_(1)
+    x = dev(x0).clone()
+    st.forward_fused(x)
+    torch.cuda.synchronize()
+    assert st.fused_abandoned()
+    assert np.array_equal(host(x).view(np.uint16), x0.view(np.uint16))
+    B.lib().morph_workspace_init(st.fused_ws.data_ptr(), st.fused_ws.numel(), None)
+    x = dev(x0).clone()
+    st.forward_fused(x)
+    torch.cuda.synchronize()
+    assert not st.fused_abandoned()
+    assert np.array_equal(host(x).view(np.uint16), good.view(np.uint16))
+
+
 def test_fused_rejects_what_it_cannot_run(B):
     from paper_2506_02006_amd.binding import MorphError
     st = B.LayerStack(256, 384, 33)
