@@ -176,6 +176,8 @@ DecodePlan plan_decode(int is_w4, int M, int K, int N)
     if (S > 64) S = 64;
     const int forced = tuning_get(TUNE_DECODE_SPLIT);
     if (forced > 0) S = forced > T / wk ? T / wk : forced;
+    const long long lim = ((1LL << 31) / T) - 1;          // the kernels form (part + 1) * T in 32 bits
+    if (S > lim) S = (int)lim;
     if (S < 1) S = 1;
     pl.S = S;
     // items of one workgroup tile: 16 rows x MT x tile columns, as fp32

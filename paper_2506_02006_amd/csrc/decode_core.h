@@ -145,7 +145,8 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     // The workgroup's steps [kb, ke) are shared out over its k parts in whole rounds of four steps
     // (one quantization group), so that no round is walked by two waves; with fewer rounds than
     // parts some waves stay empty.
-    const int kb = (int)(((long long)sp * T) / S), ke = (int)(((long long)(sp + 1) * T) / S);
+    // (sp + 1) * T < 2^32: T < 2^26 and at most 64 parts (32-bit division: the 64-bit one costs hundreds of cycles)
+    const int kb = (int)(((uint32_t)sp * (uint32_t)T) / (uint32_t)S), ke = (int)(((uint32_t)(sp + 1) * (uint32_t)T) / (uint32_t)S);
     const int gb = kb >> 2, ng = ((ke + 3) >> 2) - gb;
     const int ga = gb + (wk * ng) / WK, gz = gb + ((wk + 1) * ng) / WK;
     const int ks0 = ga == gz ? 4 * ga : (4 * ga > kb ? 4 * ga : kb);

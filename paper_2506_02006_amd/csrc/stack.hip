@@ -190,7 +190,7 @@ __device__ __forceinline__ Prefetch prefetch_issue(const StackArgs& p, const Sta
     const uint32_t row_bytes = w4 ? (uint32_t)(q.N >> 3) * 4u : (uint32_t)q.N * 2u;
     const uint32_t byte0 = w4 ? (uint32_t)(nt * tnb) / 2u : (uint32_t)(nt * tnb) * 2u;
     const int segs = w4 ? tnb / 128 : tnb / 32;                              // 64-byte pieces per row of the tile
-    const int r0 = (int)(((long long)sp * T) / S) * 32, r1 = (int)(((long long)(sp + 1) * T) / S) * 32;
+    const int r0 = (int)(((uint32_t)sp * (uint32_t)T) / (uint32_t)S) * 32, r1 = (int)(((uint32_t)(sp + 1) * (uint32_t)T) / (uint32_t)S) * 32;
     const int mid = r0 + (r1 - r0) / 2;
     const int ra = half == 0 ? r0 : mid, rb = half == 0 ? mid : r1;
     const int total = (rb - ra) * segs;
