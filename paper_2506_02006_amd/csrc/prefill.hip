@@ -26,6 +26,24 @@
 
 namespace morph {
 
+// Optional measurement for tuning builds (-DMORPH_TIMING): per wave of the first 256 workgroups, the
+// shader-clock cycles spent inside the k loop of its first tile and, of those, waiting at the
+// loop's barriers.  Compiled out of the product library.
+#ifdef MORPH_TIMING
+static __device__ unsigned long long p_ticks[256 * 8 * 2];
+static __device__ unsigned long long p_wall[256 * 8];    // per workgroup: wall clock (10 ns) at points of its first tile
+#define PF_WALL(i) do { if (threadIdx.x == 0 && blockIdx.x < 256 && p_wall[blockIdx.x * 8 + (i)] == 0) p_wall[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#define PF_BARRIER()                                                                   \
+    do {                                                                               \
+        const unsigned long long t0_ = __builtin_readcyclecounter();                   \
+        __syncthreads();                                                               \
+        pf_wait += __builtin_readcyclecounter() - t0_;                                 \
+    } while (0)
+#else
+#define PF_BARRIER() __syncthreads()
+#define PF_WALL(i) do { } while (0)
+#endif
+
 namespace {
 
 constexpr int BK  = 64;
@@ -88,20 +106,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // fewer distinct bytes (fp16 weights: 12 instead of 33 tiles' worth per k step; measured +3..5 %
     // for fp16, +0..3 % for W4).
     const int tiles_n = tiles / tiles_m;
-    auto set_tile = [&](int tile) {
-        int tm = tile % tiles_m, tn = tile / tiles_m;
-        if (p.map == 2) {
-            const int blk = 8 * tiles_m, full = (tiles_n / 8) * blk;         // indices covered by whole blocks of 8 columns
-            if (tile < full) {
-                const int b = tile / blk, i = tile - b * blk;
-                tn = 8 * b + (i & 7);
-                tm = i >> 3;
-            } else {
-                const int i = tile - full;
-                tm = i % tiles_m;
-                tn = (tiles_n / 8) * 8 + i / tiles_m;
-            }
-        }
+    int tm = 0, tn = 0;
+    auto set_tile_at = [&]() {
         m0 = tm * BM;
         n0 = tn * BN;
         a_voff0 = ((uint32_t)(m0 + (rt >> 3)) * (uint32_t)K + 8u * (rt & 7)) * 2u;
@@ -114,6 +120,33 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             s_voff[bl] = b_ok ? (uint32_t)bcol * 2u : kOut;
             z_voff[bl] = b_ok ? (uint32_t)(bcol >> 3) * 4u : kOut;
         }
+    };
+    auto set_tile = [&](int tile) {
+        tm = tile % tiles_m;
+        tn = tile / tiles_m;
+        if (p.map == 2) {
+            const int blk = 8 * tiles_m, full = (tiles_n / 8) * blk;         // indices covered by whole blocks of 8 columns
+            if (tile < full) {
+                const int b = tile / blk, i = tile - b * blk;
+                tn = 8 * b + (i & 7);
+                tm = i >> 3;
+            } else {
+                const int i = tile - full;
+                tm = i % tiles_m;
+                tn = (tiles_n / 8) * 8 + i / tiles_m;
+            }
+        }
+        set_tile_at();
+    };
+    // Tiles of a shared-out last round: that round is a rectangle (all row tiles of the column tiles
+    // from tn_first on; the host shares out only then), numbered row tile by row tile, so that the
+    // shares of different row tiles cut K at the same places and workgroups that hold the same
+    // (column tile, k range) for different rows run in step and meet in the same XCD's L2.
+    auto set_tile_tail = [&](int t, int tn_first) {
+        const int ntn = tiles_n - tn_first;
+        tm = t / ntn;
+        tn = tn_first + (t - tm * ntn);
+        set_tile_at();
     };
 
     // staging registers: x role: st[i] = piece i; weight role: fp16: st[8 b + i] = row i of block b
@@ -251,18 +284,30 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         store_fn(lds0, 0); store_fn(lds0, 1);
         load_fn(ks, 0); load_fn(ks, 1);
         __syncthreads();
+        PF_WALL(1);
+#ifdef MORPH_TIMING
+        unsigned long long pf_wait = 0;
+        const unsigned long long pf_t0 = __builtin_readcyclecounter();
+#endif
         int kt = k0;
         // two steps per trip so that each step names its buffers statically
         for (; kt + 2 <= k1; kt += 2) {
             step(kt, k1, lds0, lds1, store_fn, load_fn);
-            __syncthreads();
+            PF_BARRIER();
             step(kt + 1, k1, lds1, lds0, store_fn, load_fn);
-            __syncthreads();
+            PF_BARRIER();
         }
         if (kt < k1) {                                   // odd count: one more step out of lds0
             step(kt, k1, lds0, lds1, store_fn, load_fn);
-            __syncthreads();
+            PF_BARRIER();
         }
+        PF_WALL(2);
+#ifdef MORPH_TIMING
+        if (lane == 0 && blockIdx.x < 256 && p_ticks[(blockIdx.x * 8 + wave) * 2] == 0) {
+            p_ticks[(blockIdx.x * 8 + wave) * 2]     = __builtin_readcyclecounter() - pf_t0;
+            p_ticks[(blockIdx.x * 8 + wave) * 2 + 1] = pf_wait;
+        }
+#endif
     };
 
     // ---- write the finished tile: each wave parks its part in LDS as fp16 (pitch WN + 8), then
@@ -305,13 +350,16 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // parts in share order and writes the tile.
     const int G = gridDim.x, g = blockIdx.x;
     const int full_rounds = tiles / G;
+    PF_WALL(0);
     for (int r = 0; r < full_rounds; r++) {
         __syncthreads();                                 // LDS reuse after the previous tile's write-out
         set_tile(r * G + g);
         if (w_role) run_range(0, KT, store_w, load_w);
         else        run_range(0, KT, store_x, load_x);
         write_tile();
+        PF_WALL(3);
     }
+    PF_WALL(4);
     const int tail_first = full_rounds * G, tail_tiles = tiles - tail_first;
     if (tail_tiles == 0) return;
     if (!p.split_tail) {
@@ -338,7 +386,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         const int k0 = (int)(u - (long long)tile * KT);
         const int k1 = (u_end - u) < (KT - k0) ? k0 + (int)(u_end - u) : KT;
         __syncthreads();                                 // LDS reuse after the previous tile's write-out
-        set_tile(tail_first + tile);
+        set_tile_tail(tile, tail_first / tiles_m);
         if (w_role) run_range(k0, k1, store_w, load_w);
         else        run_range(k0, k1, store_x, load_x);
         u += k1 - k0;
@@ -407,6 +455,23 @@ hipError_t launch_tile(const GemmArgs& a, hipStream_t st)
 
 }  // namespace
 
+#ifdef MORPH_TIMING
+extern "C" int morph_debug_read_prefill_ticks(unsigned long long* host_out, int n)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(p_ticks), sizeof(unsigned long long) * n);
+}
+extern "C" int morph_debug_clear_prefill_ticks()
+{
+    static unsigned long long z[256 * 8 * 2];
+    if (hipMemcpyToSymbol(HIP_SYMBOL(p_wall), z, sizeof(unsigned long long) * 256 * 8) != hipSuccess) return 1;
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(p_ticks), z, sizeof(z));
+}
+extern "C" int morph_debug_read_prefill_wall(unsigned long long* host_out, int n)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(p_wall), sizeof(unsigned long long) * n);
+}
+#endif
+
 int prefill_compute_units()
 {
     static int cus = [] {
@@ -440,12 +505,22 @@ PrefillPlan plan_prefill(int M, int K, int N)
     pl.tiles = ((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn);
     pl.grid = pl.tiles < cus ? ((long long)pl.tiles * kt < cus ? pl.tiles * kt : cus) : cus;
     const int tail = pl.tiles % pl.grid;
-    // Sharing the k-tiles of a partial round out over all compute units (stream-K) costs the
-    // lock-step in which neighbouring workgroups fetch the same operand tiles, and measured slower
-    // than leaving compute units idle except when there are few tiles with a long K.  Tuning key
-    // 4 overrides: 1 = never, 2 = always.
+    // A last round that leaves most compute units without a tile may be shared out along K instead
+    // (stream-K): every workgroup takes an equal run of k-tiles of the remaining tiles, tiles cut in
+    // the middle are finished by whoever arrives last.  The kernel numbers those tiles row tile by
+    // row tile, which needs the remainder to be a rectangle (all row tiles of the last column
+    // tiles).  Measured, the fp32 partial tiles (256 KB each, written through and read back) cost
+    // more than the idle compute units except when there are few tiles with a long K, so that is
+    // the only case it is used in.  Tuning key 4 overrides: 1 = never, 2 = whenever the rectangle holds.
+    const int tiles_m = (M + pl.bm - 1) / pl.bm, tiles_n = pl.tiles / tiles_m;
+    const int map = (tuning_get(TUNE_PREFILL_MAP) == 1 || pl.grid % 8 != 0) ? 1 : 2;
+    const int tail_first = pl.tiles - tail;
+    const int blk = 8 * tiles_m, full = (tiles_n / 8) * blk;
+    const bool rect = map == 1 ? tail_first % tiles_m == 0
+                               : (tail_first <= full ? tail_first % blk == 0 : (tail_first - full) % tiles_m == 0);
     const int force = tuning_get(TUNE_PREFILL_SPLIT);
-    pl.split_tail = tail != 0 && (force == 2 || (force != 1 && pl.tiles < pl.grid && 2 * tail < pl.grid && kt >= 128));
+    const bool worth = pl.tiles < pl.grid && 2 * tail < pl.grid && kt >= 128;
+    pl.split_tail = tail != 0 && rect && force != 1 && (force == 2 || worth);
     // every share may end and begin inside a tile: two partial slots per workgroup, plus the counters
     pl.counter_bytes = ((size_t)pl.grid * sizeof(int) + 255) & ~(size_t)255;
     pl.partial_bytes = pl.split_tail ? (size_t)2 * pl.grid * pl.bm * pl.bn * sizeof(float) : 0;
