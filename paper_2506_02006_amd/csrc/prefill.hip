@@ -24,6 +24,8 @@
 #include "dev_common.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace morph {
 
 // Optional measurement for tuning builds (-DMORPH_TIMING): per wave of the first 256 workgroups, the
@@ -227,6 +229,11 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     };
 
     f32x16 acc[FM][FN];
+    // when the global loads of the next-but-one tile are issued: right behind the LDS stores that
+    // free their registers (x role: its halves of loads and stores use the same registers), or in
+    // the second half of the step (weight role: every store needs all rows of the staged block)
+    constexpr std::true_type  kEarly{};
+    constexpr std::false_type kLate{};
 
     const int frow = lane & 31, fk = (lane >> 5) * 8;
     // One loop step of a wave: multiply tile kt out of `cur` (four k-substeps of 16), park tile kt+1
@@ -235,8 +242,9 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // Order inside a substep: the fragment reads of the NEXT substep first (so that waiting for
     // them later does not also wait for the stores issued after them: LDS operations retire in
     // order), then the MFMAs with a piece of the staging work behind each.  Substeps 0 and 1 carry the
-    // LDS stores, substeps 2 and 3 the global loads.
-    auto step = [&](int kt, int kend, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn) {
+    // LDS stores of one half of the staged tile each; the global loads that refill the registers
+    // follow at once (x role: a step and a half to arrive) or in substeps 2 and 3 (weight role).
+    auto step = [&](int kt, int kend, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn, auto early) {
         const int ktl = kt + 2 < kend ? kt + 2 : kend - 1;
         const half_t* abase = cur + (wm0 + frow) * LDK + fk;
         const half_t* bbase = cur + BM * LDK + (wn0 + frow) * LDK + fk;
@@ -252,8 +260,15 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         for (int kk = 0; kk < BK / 16; kk++) {
             __builtin_amdgcn_sched_barrier(0);
             if (kk + 1 < BK / 16) read_frags((kk + 1) & 1, kk + 1);
-            if (kk < 2) store_fn(nxt, kk);               // buffer last read in step kt-1, behind a barrier
-            else        load_fn(ktl, kk - 2);
+            if constexpr (decltype(early)::value) {
+                if (kk < 2) {
+                    store_fn(nxt, kk);                   // buffer last read in step kt-1, behind a barrier
+                    load_fn(ktl, kk);                    // into the registers that half just left
+                }
+            } else {
+                if (kk < 2) store_fn(nxt, kk);
+                else        load_fn(ktl, kk - 2);
+            }
 #pragma unroll
             for (int i = 0; i < FM; i++)
 #pragma unroll
@@ -272,7 +287,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     };
 
     // k-tiles [k0, k1) of the current tile: acc = x[m0.., k-range] * W[k-range, n0..]
-    auto run_range = [&](int k0, int k1, auto store_fn, auto load_fn) {
+    auto run_range = [&](int k0, int k1, auto store_fn, auto load_fn, auto early) {
 #pragma unroll
         for (int i = 0; i < FM; i++)
 #pragma unroll
@@ -292,13 +307,13 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         int kt = k0;
         // two steps per trip so that each step names its buffers statically
         for (; kt + 2 <= k1; kt += 2) {
-            step(kt, k1, lds0, lds1, store_fn, load_fn);
+            step(kt, k1, lds0, lds1, store_fn, load_fn, early);
             PF_BARRIER();
-            step(kt + 1, k1, lds1, lds0, store_fn, load_fn);
+            step(kt + 1, k1, lds1, lds0, store_fn, load_fn, early);
             PF_BARRIER();
         }
         if (kt < k1) {                                   // odd count: one more step out of lds0
-            step(kt, k1, lds0, lds1, store_fn, load_fn);
+            step(kt, k1, lds0, lds1, store_fn, load_fn, early);
             PF_BARRIER();
         }
         PF_WALL(2);
@@ -354,8 +369,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     for (int r = 0; r < full_rounds; r++) {
         __syncthreads();                                 // LDS reuse after the previous tile's write-out
         set_tile(r * G + g);
-        if (w_role) run_range(0, KT, store_w, load_w);
-        else        run_range(0, KT, store_x, load_x);
+        if (w_role) run_range(0, KT, store_w, load_w, kLate);
+        else        run_range(0, KT, store_x, load_x, kEarly);
         write_tile();
         PF_WALL(3);
     }
@@ -366,8 +381,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         if (g < tail_tiles) {
             __syncthreads();
             set_tile(tail_first + g);
-            if (w_role) run_range(0, KT, store_w, load_w);
-            else        run_range(0, KT, store_x, load_x);
+            if (w_role) run_range(0, KT, store_w, load_w, kLate);
+            else        run_range(0, KT, store_x, load_x, kEarly);
             write_tile();
         }
         return;
@@ -387,8 +402,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         const int k1 = (u_end - u) < (KT - k0) ? k0 + (int)(u_end - u) : KT;
         __syncthreads();                                 // LDS reuse after the previous tile's write-out
         set_tile_tail(tile, tail_first / tiles_m);
-        if (w_role) run_range(k0, k1, store_w, load_w);
-        else        run_range(k0, k1, store_x, load_x);
+        if (w_role) run_range(k0, k1, store_w, load_w, kLate);
+        else        run_range(k0, k1, store_x, load_x, kEarly);
         u += k1 - k0;
         if (k0 == 0 && k1 == KT) {
             write_tile();
