@@ -62,9 +62,10 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     constexpr int WM = BM / WVM, WN = BN / WVN;        // wave tile
     constexpr int FM = WM / 32, FN = WN / 32;          // 32x32 MFMA blocks per wave tile
     constexpr int XP = BM * (BK / 8) / NH;             // 16-byte pieces of the x tile per x-role thread
-    constexpr int WB = (BK / 8) * (BN / 8) / NH;       // 8x8 weight blocks per weight-role thread
+    constexpr int NBLK = (BK / 8) * (BN / 8);          // 8x8 blocks of the weight tile
+    constexpr int WB = (NBLK + NH - 1) / NH;           // blocks per weight-role thread (the last waves may have none)
     static_assert(XP * NH == BM * (BK / 8) && (XP == 8 || XP == 16), "x tile divides over its role");
-    static_assert(WB * NH == (BK / 8) * (BN / 8) && (WB == 1 || WB == 2), "weight tile divides over its role");
+    static_assert((WB == 1 || WB == 2) && NBLK % 64 == 0 && (WB == 1 || NBLK == WB * NH), "weight tile divides over whole waves of its role");
     constexpr int NST = XP > (W4 ? 2 * WB : 8 * WB) ? XP : (W4 ? 2 * WB : 8 * WB);   // staging registers (x4)
 
     // Two separate objects (not halves of one array), so that the compiler knows a store into one
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         for (int bl = 0; bl < WB; bl++) {
             const int  idx = rt + NH * bl, kb = idx & 7, nb = idx >> 3;
             const int  bcol = n0 + 8 * nb;
-            const bool b_ok = bcol < N;
+            const bool b_ok = bcol < N && idx < NBLK;
             b_voff[bl] = b_ok ? (uint32_t)(8 * kb) * w_row + (W4 ? (uint32_t)(bcol >> 3) * 4u : (uint32_t)bcol * 2u) : kOut;
             s_voff[bl] = b_ok ? (uint32_t)bcol * 2u : kOut;
             z_voff[bl] = b_ok ? (uint32_t)(bcol >> 3) * 4u : kOut;
@@ -187,6 +188,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     };
     // unit u of the weight role = column pair (u % 4) of block (u / 4)
     auto store_w = [&](half_t* dst, int h) {
+        if (WB == 1 && rt >= NBLK) return;               // whole waves: the tile has fewer blocks than the role has threads
 #pragma unroll
         for (int u = 2 * WB * h; u < 2 * WB * (h + 1); u++) {
             const int bl = u >> 2, yb = u & 3;
@@ -464,6 +466,8 @@ hipError_t launch_tile(const GemmArgs& a, hipStream_t st)
 {
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const int tiles = tiles_m * tiles_n;
+    // (One kernel for both ways of running the last round: a variant without the sharing code
+    // spills no registers but was measured 8 % slower per k step; the spills sit outside the loop.)
     hipLaunchKernelGGL((prefill_kernel<W4, BM, BN, WVM, WVN>), dim3(a.grid), dim3(WVM * WVN * 64), 0, st, a, tiles_m, tiles);
     return hipGetLastError();
 }
@@ -498,25 +502,31 @@ int prefill_compute_units()
     return cus;
 }
 
-// Tile choice: the 256 x 256 tile is the most efficient per workgroup; with stream-K every compute
-// unit gets an equal share of k-tiles whatever the tile count, so the big tile is used whenever the
-// problem has at least one compute unit's worth of them per ... otherwise the smaller ones.
+// Tile choice: estimated time = rounds of tiles over the compute units x tile area x a measured
+// cost per flop of each configuration relative to the 256 x 256 tile (smaller tiles reuse their
+// operands less and stage relatively more): 256 x 192: 1.2, 256 x 128 (4 waves): 1.75, 128 x 128: 3.
 PrefillPlan plan_prefill(int M, int K, int N)
 {
     PrefillPlan pl;
     const int cus = prefill_compute_units();
     const int kt = K / BK;
-    int cfg = tuning_get(TUNE_PREFILL_TILE);             // 0 = by shape, 1 = 256x256 (8 waves), 2 = 128x128, 3 = 256x256 (4 waves), 4 = 256x128
+    int cfg = tuning_get(TUNE_PREFILL_TILE);             // 0 = by shape, 1 = 256x256 (8 waves), 2 = 128x128, 3 = 256x256 (4 waves), 4 = 256x128, 5 = 256x192
     if (cfg == 0) {
-        // the 256 x 256 tile is the most efficient per workgroup; smaller tiles when it would leave
-        // more than half of the compute units without a tile
-        const long long t256 = (long long)((M + 255) / 256) * ((N + 255) / 256);
+        struct Cand { int cfg, bm, bn; double f; };
+        const Cand cands[4] = {{1, 256, 256, 1.0}, {5, 256, 192, 1.2}, {4, 256, 128, 1.75}, {2, 128, 128, 3.0}};
+        double best = 0.0;
+        for (const Cand& c : cands) {
+            const long long t = (long long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+            const double cost = (double)((t + cus - 1) / cus) * c.bm * c.bn * c.f;
+            if (cfg == 0 || cost < best) { cfg = c.cfg; best = cost; }
+        }
+        // few tiles with a long K: the 256 x 128 tile with its last (only) round shared out along K
         const long long t256x128 = (long long)((M + 255) / 256) * ((N + 127) / 128);
-        cfg = 2 * t256 >= cus ? 1 : (2 * t256x128 >= cus || kt >= 128 ? 4 : 2);
+        if (t256x128 < cus && 2 * t256x128 < cus && kt >= 128) cfg = 4;
     }
     pl.config = cfg;
     pl.bm = (cfg == 2) ? 128 : 256;
-    pl.bn = (cfg == 2 || cfg == 4) ? 128 : 256;
+    pl.bn = (cfg == 2 || cfg == 4) ? 128 : (cfg == 5 ? 192 : 256);
     pl.tiles = ((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn);
     pl.grid = pl.tiles < cus ? ((long long)pl.tiles * kt < cus ? pl.tiles * kt : cus) : cus;
     const int tail = pl.tiles % pl.grid;
@@ -552,6 +562,7 @@ hipError_t launch_prefill(int is_w4, const GemmArgs& a0, hipStream_t st)
         case 1: return is_w4 ? launch_tile<true, 256, 256, 4, 2>(a, st) : launch_tile<false, 256, 256, 4, 2>(a, st);
         case 3: return is_w4 ? launch_tile<true, 256, 256, 2, 2>(a, st) : launch_tile<false, 256, 256, 2, 2>(a, st);
         case 4: return is_w4 ? launch_tile<true, 256, 128, 2, 2>(a, st) : launch_tile<false, 256, 128, 2, 2>(a, st);
+        case 5: return is_w4 ? launch_tile<true, 256, 192, 4, 2>(a, st) : launch_tile<false, 256, 192, 4, 2>(a, st);
         default: return is_w4 ? launch_tile<true, 128, 128, 2, 2>(a, st) : launch_tile<false, 128, 128, 2, 2>(a, st);
     }
 }

@@ -151,14 +151,20 @@ def test_prefill_fp16(B, oracle, M, K, N):
     check_fp16(B, oracle, M, K, N, seed=M)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4])
-def test_prefill_both_tiles(B, oracle, tile):
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("order", [1, 2])
+def test_prefill_every_tile_and_order(B, oracle, tile, order):
+    """Every tile configuration under both orders of dealing tiles to workgroups, on a shape with
+    ragged last tiles in both directions and more column tiles than one block of eight."""
     B.set_tuning(B.TUNE_PREFILL_TILE, tile)
+    B.set_tuning(B.TUNE_PREFILL_MAP, order)
     try:
         check_w4(B, oracle, 300, 512, 776, seed=tile)
         check_fp16(B, oracle, 300, 512, 776, seed=tile)
+        check_w4(B, oracle, 520, 256, 2312, seed=10 + tile)
     finally:
         B.set_tuning(B.TUNE_PREFILL_TILE, 0)
+        B.set_tuning(B.TUNE_PREFILL_MAP, 0)
 
 
 @pytest.mark.parametrize("split", [1, 2, 3, 7])
