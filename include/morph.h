@@ -54,9 +54,11 @@ enum { MORPH_GROUP_SIZE = 128 };
 
 /* ---- y = x * W with fp16 weights (the full-precision layer variant; Section 4.3, Appendix C) ----
  * x [M,K] fp16, w [K,N] fp16, y [M,N] fp16.  K % 128 == 0, N % 8 == 0, M >= 1.
- * M <= 64 takes the bandwidth-bound decode kernel (split along K; needs the workspace),
- * larger M the LDS-tiled MFMA kernel (k-tiles shared out evenly over the compute units; needs the
- * workspace whenever a share is not made of whole output tiles).
+ * Small M takes the streaming (decode) kernels, which read the weights once and work on slices of
+ * 32 rows (split along K; need the workspace), large M the LDS-tiled MFMA kernels (one workgroup
+ * per compute unit walking 256-wide tiles; need the workspace when a last round of tiles is shared
+ * out along K).  Up to 64 rows it is always the former, above 1024 always the latter; in between
+ * the library picks the faster one from the shape.
  * workspace: morph_workspace_bytes(MORPH_KIND_FP16, M, K, N) bytes prepared once with
  * morph_workspace_init(); may be NULL when that size is 0.  One workspace must not be used by
  * two calls that can run concurrently (different streams).
@@ -167,7 +169,8 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
  * 2 = 128x128, 3 = 256x256 with 4 waves, 4 = 256x128, 5 = 256x192), 3 = waves per decode workgroup (4 or 8),
  * 4 = prefill: sharing the last partial round of tiles out along K (1 = never, 2 = always),
  * 5 = prefill: order in which tiles are dealt to workgroups (1 = row tiles of a column tile first,
- * 2 = blocks of 8 column tiles spread over the 8 XCDs).
+ * 2 = blocks of 8 column tiles spread over the 8 XCDs), 6 = largest M the streaming kernels take
+ * (32 .. 1024; replaces the choice by shape).
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);
 

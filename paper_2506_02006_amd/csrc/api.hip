@@ -17,7 +17,33 @@ void tuning_set(int key, int value)
 
 namespace {
 
-constexpr int    kDecodeMaxM = 64;
+constexpr int    kStackMaxM  = 64;     // rows the per-step layer stack takes
+
+// Which kernel family runs a linear.  The streaming (decode) kernels take any M in slices of 32
+// rows; their time grows with the number of slices.  The LDS-tiled MFMA kernels need about a
+// microsecond per k step of 64 however small the problem.  Up to 64 rows the streaming kernels
+// always win; up to 1024 rows the two estimates below decide (constants measured on MI355X on
+// 7B / 8B / 13B-shaped layers); above, the MFMA kernels.  Tuning key 6 replaces the rule by a plain
+// threshold on M.
+bool takes_stream(int kind, int M, int K, int N)
+{
+    const int t = tuning_get(TUNE_DECODE_MAX_M);
+    if (t >= 32 && t <= 1024) return M <= t;
+    if (M <= 64) return true;
+    if (M > 1024) return false;
+    const int cus = prefill_compute_units();
+    const DecodePlan dp = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
+    const double ns_per_row = kind == MORPH_KIND_W4A16 ? 6.7 : 6.0;        // one workgroup walking its rows of K
+    const long long wgs = (long long)dp.tiles * dp.slices * dp.S;
+    const double est_stream = 8.0 + (double)((wgs + cus - 1) / cus) * ((double)K / dp.S) * ns_per_row * 1e-3;
+    const PrefillPlan pp = plan_prefill(M, K, N);
+    const double busy = pp.tiles < cus ? (double)pp.tiles / cus : 1.0;
+    const double step_us = 0.9 + 0.8 * busy * ((double)pp.bm * pp.bn / 65536.0);
+    double est_mfma = (double)((pp.tiles + cus - 1) / cus) * (K / 64) * step_us;
+    if (pp.split_tail) est_mfma *= 0.65;
+    return est_stream < est_mfma;
+}
+
 constexpr size_t k4G         = (size_t)1 << 32;
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -44,7 +70,7 @@ int check_sizes(int kind, int M, int K, int N)
 
 size_t workspace_need(int kind, int M, int K, int N)
 {
-    if (M > kDecodeMaxM) {
+    if (!takes_stream(kind, M, K, N)) {
         const PrefillPlan pp = plan_prefill(M, K, N);
         return pp.partial_bytes ? pp.counter_bytes + pp.partial_bytes : 0;
     }
@@ -56,9 +82,9 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
                int M, int K, int N, void* workspace, size_t workspace_bytes, hipStream_t st)
 {
     hipError_t e;
-    if (M <= kDecodeMaxM) {
+    if (takes_stream(kind, M, K, N)) {
         const DecodePlan pl = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
-        if (pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
+        if (pl.S > 1 && pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
         DecodeArgs a;
         a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
         a.M = M; a.K = K; a.N = N; a.S = pl.S;
@@ -225,7 +251,7 @@ int morph_stack_forward(const morph_layer_desc* layers, int n_layers, void* x_io
                         size_t workspace_bytes, int tap_layer, void* tap, void* stream)
 {
     if (!layers || !x_io || !scratch) return MORPH_ERR_NULL;
-    if (n_layers < 1 || M < 1 || M > kDecodeMaxM) return MORPH_ERR_SHAPE;
+    if (n_layers < 1 || M < 1 || M > kStackMaxM) return MORPH_ERR_SHAPE;
     if (hidden % MORPH_GROUP_SIZE || inter % MORPH_GROUP_SIZE || hidden < MORPH_GROUP_SIZE || inter < MORPH_GROUP_SIZE)
         return MORPH_ERR_SHAPE;
     if (!aligned16(x_io) || !aligned16(scratch) || (tap && !aligned16(tap))) return MORPH_ERR_ALIGN;

@@ -4,8 +4,8 @@
 //   * K is split over the waves of a workgroup and over S workgroups per column tile.  Waves are
 //     summed out of LDS in a fixed order; workgroups write fp32 partials (written through to
 //     memory) and the last one to arrive, found with an atomic counter, adds them in index order,
-//     so results do not depend on timing.  Rows above 32 are handled by a second slice of the
-//     grid (blockIdx.y) running the same kernel on rows 32..63.
+//     so results do not depend on timing.  Rows above 32 are handled by further slices of the
+//     grid running the same code on rows 32..63, 64..95, ...
 #include "decode_core.h"
 #include "kernels.h"
 
@@ -23,9 +23,26 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
 
     const int tid = threadIdx.x;
     const int S = p.S;
-    const int nt = blockIdx.x / S, sp = blockIdx.x - nt * S;
+    // Which (column tile, part of K, row slice) this workgroup takes.  With several row slices the
+    // slices of one (tile, part) are dealt to consecutive workgroups OF ONE XCD (workgroup g runs
+    // on XCD g % 8), so that they run at the same time on the same L2 and the weights leave
+    // memory once instead of once per slice.
+    int unit = blockIdx.x, slice = 0;
+    if (p.slices > 1) {
+        const int units = p.tiles * S, whole = (units >> 3) * 8 * p.slices;   // workgroups of whole rounds of 8 units
+        if ((int)blockIdx.x < whole) {
+            const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+            slice = j % p.slices;
+            unit  = (j / p.slices) * 8 + xcd;
+        } else {                                         // the last units (fewer than 8): slice by slice
+            const int r = blockIdx.x - whole, left = units & 7;
+            slice = r / left;
+            unit  = (units >> 3) * 8 + (r - slice * left);
+        }
+    }
+    const int nt = unit / S, sp = unit - nt * S;
     const int n0 = nt * TNB;                             // first column of the workgroup tile
-    const int mbase = blockIdx.y * 32;                   // first row of this slice
+    const int mbase = slice * 32;                        // first row of this slice
     const int M = (p.M - mbase) < MT * 16 ? (p.M - mbase) : MT * 16;   // rows of this slice
     const int N = p.N;
 
@@ -63,7 +80,7 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     // through to memory and read past the caches (scope bits on the instructions), which is all the
     // ordering needs: wait for the stores, count the arrival, and the last arriver reads.  No
     // whole-cache write-back or invalidate is issued.  Layout: [tile][split][item] f32x4.
-    const int tile_id = blockIdx.y * (gridDim.x / S) + nt;           // slices keep separate counters and partials
+    const int tile_id = slice * p.tiles + nt;                        // slices keep separate counters and partials
     constexpr uint32_t kPartBytes = (uint32_t)ITEMS * 16u;           // one workgroup's partial
     const float* tile_base = p.partial + (size_t)tile_id * S * ITEMS * 4;
     const __amdgpu_buffer_rsrc_t rp = make_rsrc(tile_base, (uint32_t)S * kPartBytes);
@@ -133,8 +150,12 @@ hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (attr != hipSuccess) return attr;
     }
-    const int tiles = (a.N + tnb - 1) / tnb;
-    hipLaunchKernelGGL((decode_kernel<W4, MT, kWaves>), dim3(tiles * a.S, slices), dim3(kWaves * 64), lds, st, a);
+    DecodeArgs b = a;
+    b.tiles  = (a.N + tnb - 1) / tnb;
+    b.slices = slices;
+    const int units = b.tiles * a.S;
+    const int grid  = units * slices;
+    hipLaunchKernelGGL((decode_kernel<W4, MT, kWaves>), dim3(grid), dim3(kWaves * 64), lds, st, b);
     return hipGetLastError();
 }
 

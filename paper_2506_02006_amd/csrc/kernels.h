@@ -24,6 +24,8 @@ struct DecodeArgs {
     int*            counters;  // [slices * tiles], zero on entry, zero on exit
     int             M, K, N;
     int             S;         // workgroups sharing one column tile (split along K)
+    int             tiles;     // column tiles (set by launch_decode)
+    int             slices;    // row slices of 32 (set by launch_decode)
 };
 struct DecodePlan {
     int    tile_n;             // columns per workgroup
@@ -32,7 +34,7 @@ struct DecodePlan {
     int    S;                  // split along K across workgroups
     size_t partial_bytes;      // 0 when S == 1
 };
-constexpr size_t kCounterBytes = 4096;   // head of the workspace: arrival counters
+constexpr size_t kCounterBytes = 65536;  // head of the workspace: arrival counters (one per column tile and row slice)
 DecodePlan plan_decode(int is_w4, int M, int K, int N);
 hipError_t launch_decode(int is_w4, const DecodeArgs& a, hipStream_t st);
 
@@ -57,6 +59,7 @@ struct PrefillPlan {
     size_t partial_bytes;  // 0 when every share is made of whole tiles
 };
 PrefillPlan plan_prefill(int M, int K, int N);
+int prefill_compute_units();   // compute units of the current device (256 when it cannot be asked)
 hipError_t launch_prefill(int is_w4, const GemmArgs& a, hipStream_t st);
 
 // ---- persistent layer stack, M <= 32 (stack.hip) ----
@@ -94,6 +97,6 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_COUNT = 8 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_COUNT = 8 };
 
 }  // namespace morph

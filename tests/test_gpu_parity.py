@@ -167,6 +167,20 @@ def test_prefill_every_tile_and_order(B, oracle, tile, order):
         B.set_tuning(B.TUNE_PREFILL_MAP, 0)
 
 
+@pytest.mark.parametrize("max_m", [32, 1024, 0], ids=["mfma", "stream", "auto"])
+@pytest.mark.parametrize("M", [65, 100, 257, 600])
+def test_mid_sizes_in_either_kernel_family(B, oracle, M, max_m):
+    """Between 64 and 1024 rows either family may run a linear: the streaming kernels in slices of
+    32 rows (more than 8 column tiles here, so that whole rounds of 8 units and a remainder both
+    occur) or the LDS-tiled MFMA kernels.  Both are forced in turn, then the library chooses."""
+    B.set_tuning(B.TUNE_DECODE_MAX_M, max_m)
+    try:
+        check_w4(B, oracle, M, 512, 2824, seed=M)
+        check_fp16(B, oracle, M, 384, 1480, seed=M + 1)
+    finally:
+        B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
+
+
 @pytest.mark.parametrize("split", [1, 2, 3, 7])
 def test_decode_every_split(B, oracle, split):
     """The K split across workgroups only changes the fp32 summation order."""
