@@ -19,8 +19,8 @@ namespace {
 
 constexpr int    kStackMaxM  = 64;     // rows the per-step layer stack takes
 
-// Which kernel family runs a linear.  The streaming (decode) kernels take any M in slices of 32
-// rows; their time grows with the number of slices.  The LDS-tiled MFMA kernels need about a
+// Which kernel family runs a linear.  The streaming (decode) kernels take any M in slices of 16 or
+// 32 rows; their time grows with the number of slices.  The LDS-tiled MFMA kernels need about a
 // microsecond per k step of 64 however small the problem.  Up to 64 rows the streaming kernels
 // always win; up to 1024 rows the two estimates below decide (constants measured on MI355X on
 // 7B / 8B / 13B-shaped layers); above, the MFMA kernels.  Tuning key 6 replaces the rule by a plain
@@ -87,7 +87,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         if (pl.S > 1 && pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
         DecodeArgs a;
         a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
-        a.M = M; a.K = K; a.N = N; a.S = pl.S;
+        a.M = M; a.K = K; a.N = N; a.S = pl.S; a.rows = pl.rows;
         a.partial = nullptr; a.counters = nullptr;
         if (pl.S > 1) {
             if (!workspace || workspace_bytes < kCounterBytes + pl.partial_bytes) return MORPH_ERR_WORKSPACE;

@@ -4,8 +4,8 @@
 //   * K is split over the waves of a workgroup and over S workgroups per column tile.  Waves are
 //     summed out of LDS in a fixed order; workgroups write fp32 partials (written through to
 //     memory) and the last one to arrive, found with an atomic counter, adds them in index order,
-//     so results do not depend on timing.  Rows above 32 are handled by further slices of the
-//     grid running the same code on rows 32..63, 64..95, ...
+//     so results do not depend on timing.  A workgroup takes a slice of 16 or 32 rows; further
+//     rows are handled by further slices of the grid running the same code.
 #include "decode_core.h"
 #include "kernels.h"
 
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     }
     const int nt = unit / S, sp = unit - nt * S;
     const int n0 = nt * TNB;                             // first column of the workgroup tile
-    const int mbase = slice * 32;                        // first row of this slice
+    const int mbase = slice * (MT * 16);                 // first row of this slice
     const int M = (p.M - mbase) < MT * 16 ? (p.M - mbase) : MT * 16;   // rows of this slice
     const int N = p.N;
 
@@ -130,13 +130,13 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     MORPH_TICK(5);
 }
 
-// Waves per workgroup: two M tiles (M > 16) halve the bytes a wave keeps in flight, so eight waves per
+// Waves per workgroup: two M tiles halve the bytes a wave keeps in flight, so eight waves per
 // compute unit in one workgroup do better there; one M tile runs best as two workgroups of four.
-inline int decode_waves(int M)
+inline int decode_waves(int rows)
 {
     const int t = tuning_get(TUNE_DECODE_WAVES);
     if (t == 4 || t == 8) return t;
-    return M > 16 ? 8 : 4;
+    return rows > 16 ? 8 : 4;
 }
 
 template <bool W4, int MT, int kWaves>
@@ -162,7 +162,7 @@ hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
 template <bool W4, int MT>
 hipError_t launch_one(const DecodeArgs& a, int slices, hipStream_t st)
 {
-    return decode_waves(a.M) == 8 ? launch_waves<W4, MT, 8>(a, slices, st) : launch_waves<W4, MT, 4>(a, slices, st);
+    return decode_waves(MT * 16) == 8 ? launch_waves<W4, MT, 8>(a, slices, st) : launch_waves<W4, MT, 4>(a, slices, st);
 }
 
 }  // namespace
@@ -179,14 +179,19 @@ extern "C" int morph_debug_clear_ticks()
 }
 #endif
 
-DecodePlan plan_decode(int is_w4, int M, int K, int N)
+namespace {
+
+// The plan for slices of `rows` rows (16: one MFMA row tile per workgroup, 32: two), with an
+// estimate of the launch time net of what does not depend on the choice.
+DecodePlan plan_rows(int is_w4, int M, int K, int N, int rows)
 {
     DecodePlan pl;
+    pl.rows   = rows;
     pl.tile_n = !is_w4 ? Tile<false, 1>::TN : 256;      // workgroup tile (W4: 1 x 256 or 2 x 128 columns)
-    const int kWaves = decode_waves(M);
-    const int wk = (is_w4 && M > 16) ? kWaves / Tile<true, 2>::WN : kWaves;   // waves of a workgroup along K
+    const int kWaves = decode_waves(rows);
+    const int wk = (is_w4 && rows > 16) ? kWaves / Tile<true, 2>::WN : kWaves;   // waves of a workgroup along K
     pl.tiles  = (N + pl.tile_n - 1) / pl.tile_n;
-    pl.slices = (M + 31) / 32;
+    pl.slices = (M + rows - 1) / rows;
     const int T = K / 32;
     int target = tuning_get(TUNE_DECODE_WGS);
     if (target <= 0) target = 256;                       // one workgroup per compute unit
@@ -201,16 +206,43 @@ DecodePlan plan_decode(int is_w4, int M, int K, int N)
     if (S > lim) S = (int)lim;
     if (S < 1) S = 1;
     pl.S = S;
-    // items of one workgroup tile: 16 rows x MT x tile columns, as fp32
-    const size_t tile_floats = (size_t)(M <= 16 ? 16 : 32) * pl.tile_n;
+    // items of one workgroup tile: rows x tile columns, as fp32
+    const size_t tile_floats = (size_t)rows * pl.tile_n;
     pl.partial_bytes = S > 1 ? (size_t)units * S * tile_floats * sizeof(float) : 0;
+    // Estimate (microseconds, W4 constants measured on MI355X): the rows of K one workgroup walks at
+    // the rate its waves unpack them, or the weights at the rate strips of them leave memory when
+    // that is slower; then the hand-over, whose last arriver reads S partial tiles on its own.
+    const double wgs = (double)units * S, fill = wgs < 256.0 ? wgs / 256.0 : 1.0;
+    const double walk = ((double)K / S) * (rows > 16 ? 6.7e-3 : 3.24e-3) * (double)(((long long)wgs + 255) / 256);
+    const double hbm  = ((double)K * N * 0.5) / (4.6e6 * fill);
+    pl.est_us = (walk > hbm ? walk : hbm) + (S > 1 ? 1.5 + (double)S * tile_floats * 4.0 / 2.0e5 : 0.0);
     return pl;
+}
+
+}  // namespace
+
+// Slices of 32 rows share the unpacking of a weight between two MFMA row tiles; slices of 16 rows
+// put twice the workgroups along M instead of along K, which halves both the split and the
+// partial tile the last arriver has to add up.  For the 4-bit kernels between 17 and 64 rows the
+// estimate decides, as long as all workgroups of the 16-row plan run at the same time.
+DecodePlan plan_decode(int is_w4, int M, int K, int N)
+{
+    const int t = tuning_get(TUNE_DECODE_SLICE);
+    if (t == 16 || t == 32) return plan_rows(is_w4, M, K, N, t);
+    if (M <= 16) return plan_rows(is_w4, M, K, N, 16);
+    const DecodePlan p32 = plan_rows(is_w4, M, K, N, 32);
+    if (!is_w4 || M > 64) return p32;
+    const DecodePlan p16 = plan_rows(is_w4, M, K, N, 16);
+    if (p16.tiles * p16.slices * p16.S > 256) return p32;
+    return p16.est_us < p32.est_us ? p16 : p32;
 }
 
 hipError_t launch_decode(int is_w4, const DecodeArgs& a, hipStream_t st)
 {
-    const int slices = (a.M + 31) / 32;
-    const bool one   = a.M <= 16;                        // a single 16-row MFMA tile
+    const int rows = a.rows;
+    if (rows != 16 && rows != 32) return hipErrorInvalidValue;
+    const int slices = (a.M + rows - 1) / rows;
+    const bool one   = rows == 16;                       // a single 16-row MFMA tile
     if (is_w4) return one ? launch_one<true, 1>(a, slices, st) : launch_one<true, 2>(a, slices, st);
     return one ? launch_one<false, 1>(a, slices, st) : launch_one<false, 2>(a, slices, st);
 }

@@ -20,19 +20,22 @@ struct DecodeArgs {
     const void*     scales;    // fp16 [K/128,N]      (W4 only)
     const void*     qzeros;    // uint32 [K/128,N/8]  (W4 only)
     void*           y;         // fp16 [M,N]
-    float*          partial;   // [slices * tiles][S][32][tile columns] fp32, used when S > 1
+    float*          partial;   // [slices * tiles][S][rows][tile columns] fp32, used when S > 1
     int*            counters;  // [slices * tiles], zero on entry, zero on exit
     int             M, K, N;
     int             S;         // workgroups sharing one column tile (split along K)
+    int             rows;      // rows per slice, 16 or 32 (from the plan)
     int             tiles;     // column tiles (set by launch_decode)
-    int             slices;    // row slices of 32 (set by launch_decode)
+    int             slices;    // row slices (set by launch_decode)
 };
 struct DecodePlan {
     int    tile_n;             // columns per workgroup
     int    tiles;              // ceil(N / tile_n)
-    int    slices;             // ceil(M / 32): row slices, each run by its own part of the grid
+    int    rows;               // rows per slice: 16 or 32
+    int    slices;             // ceil(M / rows): row slices, each run by its own part of the grid
     int    S;                  // split along K across workgroups
     size_t partial_bytes;      // 0 when S == 1
+    double est_us;             // estimated time of the parts of a launch that depend on the plan
 };
 constexpr size_t kCounterBytes = 65536;  // head of the workspace: arrival counters (one per column tile and row slice)
 DecodePlan plan_decode(int is_w4, int M, int K, int N);
@@ -97,6 +100,6 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_COUNT = 8 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_COUNT = 8 };
 
 }  // namespace morph

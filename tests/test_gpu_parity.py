@@ -181,6 +181,21 @@ def test_mid_sizes_in_either_kernel_family(B, oracle, M, max_m):
         B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
 
 
+@pytest.mark.parametrize("rows", [16, 32, 0], ids=["slices16", "slices32", "auto"])
+@pytest.mark.parametrize("M", [17, 40, 64])
+def test_decode_either_slice_height(B, oracle, M, rows):
+    """A streaming workgroup takes 16 or 32 rows; above 16 rows the library picks per shape.  Both
+    heights are forced in turn (a partly filled last slice included), with and without a split
+    along K, then the library chooses."""
+    B.set_tuning(B.TUNE_DECODE_SLICE, rows)
+    try:
+        check_w4(B, oracle, M, 1792, 520, seed=M + rows)
+        check_w4(B, oracle, M, 256, 2824, seed=M + rows + 1)
+        check_fp16(B, oracle, M, 1792, 264, seed=M + rows + 2)
+    finally:
+        B.set_tuning(B.TUNE_DECODE_SLICE, 0)
+
+
 @pytest.mark.parametrize("split", [1, 2, 3, 7])
 def test_decode_every_split(B, oracle, split):
     """The K split across workgroups only changes the fp32 summation order."""
