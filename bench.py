@@ -184,6 +184,26 @@ def main():
     torch.cuda.synchronize()
     del cal_src, cal_dst
 
+    # what this device reaches with nothing in the way: a contiguous read, a copy, back-to-back MFMAs
+    # (the library's probe kernels); the fractions above are against the data sheet, these give the
+    # second reference
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    big2 = torch.empty_like(big)
+    pout = torch.empty(B.probe_out_bytes(), dtype=torch.uint8, device=dev)
+    t_read = timed(lambda i: B.probe_read(big, pout), 10, 2) / 10
+    t_copy = timed(lambda i: B.copy(big, big2), 10, 2) / 10
+    flop_box = [0.0]
+    def mfma_probe(i):
+        flop_box[0] = B.probe_mfma(4000, pout)
+    t_mfma = timed(mfma_probe, 5, 1) / 5
+    peaks = {"read_GBs": round(big.numel() / t_read / 1e9, 1), "copy_GBs": round(2 * big.numel() / t_copy / 1e9, 1),
+             "mfma_f16_TFLOPs": round(flop_box[0] / t_mfma / 1e12, 1),
+             "how": "library probe kernels: 1 GiB contiguous read, 1 GiB copy (read + write bytes), "
+                    "32x32x16 fp16 MFMAs on registers, 8-wave workgroups"}
+    result["measured_peaks"] = peaks
+    roofline["frac_of_measured_read"] = round(value / peaks["read_GBs"], 4)
+    del big, big2, pout
+
     detail = {}
     sections = set() if args.quick else set(args.sections.split(","))
     if sections:
@@ -257,7 +277,8 @@ def main():
                     s = timed(lambda i: fn(), 10, 2) / 10
                     tf = 2.0 * M * K * N / s / 1e12
                     d13[f"{label}/{name}/M{M}"] = {"us": round(s * 1e6, 1), "TFLOPs": round(tf, 1),
-                                                   "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1)}
+                                                   "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1),
+                                                   "pct_measured_mfma": round(tf / peaks["mfma_f16_TFLOPs"] * 100, 1)}
                 # for orientation only: the vendor GEMM that torch.matmul dispatches to, same operands and layout
                 s = timed(lambda i: torch.matmul(x, w16, out=y), 10, 2) / 10
                 tf = 2.0 * M * K * N / s / 1e12

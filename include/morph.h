@@ -179,6 +179,18 @@ int morph_set_tuning(int key, int value);
  * calibrated against a transfer of known size. */
 int morph_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Peak probes, so that a benchmark can quote its fractions against what this very device reaches
+ * as well as against the data sheet.  Both write one word per thread into `out` (device, 16-byte
+ * aligned, at least morph_probe_out_bytes()), launch asynchronously on `stream` and touch nothing else.
+ *   morph_probe_read: loads every 16-byte vector of src[0..bytes) once (bytes % 16 == 0): bytes over
+ *     the launch time is the read bandwidth of a plain contiguous stream.
+ *   morph_probe_mfma: every wave issues iters x 4 independent 32x32x16 fp16 MFMAs on registers;
+ *     *flop (host, may be NULL) receives the flop of the launch: flop over the launch time is the rate
+ *     the matrix cores sustain with nothing else in the way (1 <= iters <= 2^24). */
+size_t morph_probe_out_bytes(void);
+int morph_probe_read(const void* src, size_t bytes, void* out, size_t out_bytes, void* stream);
+int morph_probe_mfma(int iters, void* out, size_t out_bytes, double* flop, void* stream);
+
 const char* morph_status_string(int status);
 
 #ifdef __cplusplus

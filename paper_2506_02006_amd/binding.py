@@ -24,6 +24,7 @@ EXPORTS = [
     "morph_stack_tap_bytes", "morph_stack_forward", "morph_stack_fused_workspace_bytes",
     "morph_stack_forward_fused", "morph_warmup_bytes", "morph_warmup",
     "morph_set_tuning", "morph_copy", "morph_status_string",
+    "morph_probe_out_bytes", "morph_probe_read", "morph_probe_mfma",
 ]
 
 
@@ -75,6 +76,10 @@ def lib() -> ctypes.CDLL:
     L.morph_warmup.argtypes = [vp, sz, vp]
     L.morph_set_tuning.argtypes = [i, i]
     L.morph_copy.argtypes = [vp, vp, sz, vp]
+    L.morph_probe_out_bytes.restype = sz
+    L.morph_probe_out_bytes.argtypes = []
+    L.morph_probe_read.argtypes = [vp, sz, vp, sz, vp]
+    L.morph_probe_mfma.argtypes = [ctypes.c_int, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
     L.morph_status_string.argtypes = [i]
     L.morph_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -193,6 +198,26 @@ def copy(src: torch.Tensor, dst: torch.Tensor):
     assert nbytes == dst.numel() * dst.element_size() and src.is_contiguous() and dst.is_contiguous()
     _check(lib().morph_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream()), "morph_copy")
     return dst
+
+
+def probe_out_bytes() -> int:
+    return int(lib().morph_probe_out_bytes())
+
+
+def probe_read(src: torch.Tensor, out: torch.Tensor):
+    """Launch the read-bandwidth probe over src; returns the bytes it reads."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().morph_probe_read(src.data_ptr(), nbytes, out.data_ptr(), out.numel() * out.element_size(), _stream()),
+           "morph_probe_read")
+    return nbytes
+
+
+def probe_mfma(iters: int, out: torch.Tensor) -> float:
+    """Launch the matrix-core probe; returns the flop of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(lib().morph_probe_mfma(iters, out.data_ptr(), out.numel() * out.element_size(), ctypes.byref(flop), _stream()),
+           "morph_probe_mfma")
+    return flop.value
 
 
 def set_tuning(key: int, value: int):

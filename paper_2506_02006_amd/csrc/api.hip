@@ -418,6 +418,27 @@ int morph_copy(const void* src, void* dst, size_t bytes, void* stream)
     return launch_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
 
+size_t morph_probe_out_bytes(void) { return kProbeOutBytes; }
+
+int morph_probe_read(const void* src, size_t bytes, void* out, size_t out_bytes, void* stream)
+{
+    if (!src || !out) return MORPH_ERR_NULL;
+    if (!aligned16(src) || !aligned16(out)) return MORPH_ERR_ALIGN;
+    if (bytes % 16 != 0) return MORPH_ERR_SHAPE;
+    if (out_bytes < kProbeOutBytes) return MORPH_ERR_WORKSPACE;
+    return launch_probe_read(src, bytes, out, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+int morph_probe_mfma(int iters, void* out, size_t out_bytes, double* flop, void* stream)
+{
+    if (!out) return MORPH_ERR_NULL;
+    if (!aligned16(out)) return MORPH_ERR_ALIGN;
+    if (iters < 1 || iters > (1 << 24)) return MORPH_ERR_SHAPE;
+    if (out_bytes < kProbeOutBytes) return MORPH_ERR_WORKSPACE;
+    if (flop) *flop = (double)kProbeBlocks * 8.0 * iters * 4.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return launch_probe_mfma(iters, out, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
 int morph_set_tuning(int key, int value)
 {
     if (key < 0 || key >= TUNE_COUNT) return MORPH_ERR_SHAPE;

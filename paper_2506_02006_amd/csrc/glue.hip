@@ -111,7 +111,60 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ s, 
         d[i] = s[i];
 }
 
+// Read-only stream: every vector of the buffer is loaded once; the XOR of what a thread saw goes
+// out so that the loads cannot be dropped.
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ s, size_t n16, uint32_t* __restrict__ out)
+{
+    u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {      // four independent loads in flight per thread
+        const u32x4 a = s[i], b = s[i + stride], c = s[i + 2 * stride], d = s[i + 3 * stride];
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n16; i += stride) acc ^= s[i];
+    out[blockIdx.x * (size_t)blockDim.x + threadIdx.x] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+}
+
+// Matrix-core issue rate: every wave runs `iters` rounds of four independent 32x32x16 fp16 MFMAs
+// on registers (no memory traffic inside the loop).
+constexpr int kProbeMfmaThreads = 512, kProbeMfmaPerIter = 4;
+__global__ __launch_bounds__(kProbeMfmaThreads) void probe_mfma_kernel(int iters, float* __restrict__ out)
+{
+    const int tid = threadIdx.x;
+    half8_t a, b;
+#pragma unroll
+    for (int j = 0; j < 8; j++) { a[j] = (half_t)(float)((tid + j) & 3); b[j] = (half_t)(float)((tid >> 2) & 1); }
+    f32x16 c0, c1, c2, c3;
+#pragma unroll
+    for (int j = 0; j < 16; j++) { c0[j] = 0.f; c1[j] = 0.f; c2[j] = 0.f; c3[j] = 0.f; }
+    for (int it = 0; it < iters; it++) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c3, 0, 0, 0);
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; j++) r += c0[j] + c1[j] + c2[j] + c3[j];
+    out[blockIdx.x * (size_t)kProbeMfmaThreads + tid] = r;
+}
+
 }  // namespace
+
+hipError_t launch_probe_read(const void* src, size_t bytes, void* out, hipStream_t st)
+{
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(kProbeBlocks), dim3(256), 0, st, (const u32x4*)src, n16, (uint32_t*)out);
+    return hipGetLastError();
+}
+
+// flop of one launch: blocks x waves x iters x 4 MFMAs x 2 x 32 x 32 x 16
+hipError_t launch_probe_mfma(int iters, void* out, hipStream_t st)
+{
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(kProbeBlocks), dim3(kProbeMfmaThreads), 0, st, iters, (float*)out);
+    return hipGetLastError();
+}
 
 hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, hipStream_t st)
 {

@@ -96,6 +96,11 @@ hipError_t launch_stack(const StackArgs& a, int grid, hipStream_t st);
 hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, hipStream_t st);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+// peak probes (glue.hip): kProbeBlocks workgroups each; the output buffer takes one word per thread
+constexpr int    kProbeBlocks   = 2048;
+constexpr size_t kProbeOutBytes = (size_t)kProbeBlocks * 512 * 4;
+hipError_t launch_probe_read(const void* src, size_t bytes, void* out, hipStream_t st);
+hipError_t launch_probe_mfma(int iters, void* out, hipStream_t st);
 
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);

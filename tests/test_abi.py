@@ -113,3 +113,15 @@ def test_glue_and_stack_validation(L):
     assert L.morph_warmup(None, 0, None) == 1
     assert L.morph_warmup(FAKE, 16, None) == 4
     assert L.morph_set_tuning(99, 1) == 2
+
+
+def test_probe_validation(L):
+    need = L.morph_probe_out_bytes()
+    assert need >= 2048 * 512 * 4
+    assert L.morph_probe_read(None, 1024, FAKE, need, None) == 1 and L.morph_probe_read(FAKE, 1024, None, need, None) == 1
+    assert L.morph_probe_read(FAKE + 4, 1024, FAKE, need, None) == 3
+    assert L.morph_probe_read(FAKE, 1000, FAKE, need, None) == 2
+    assert L.morph_probe_read(FAKE, 1024, FAKE, need - 1, None) == 4
+    assert L.morph_probe_mfma(10, None, need, None, None) == 1
+    assert L.morph_probe_mfma(0, FAKE, need, None, None) == 2
+    assert L.morph_probe_mfma(10, FAKE, 16, None, None) == 4

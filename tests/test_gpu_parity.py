@@ -366,3 +366,32 @@ def test_small_stack_every_layer_teacher_forced(B, oracle):
         st.forward(x, tap_layer=l)
         torch.cuda.synchronize()
         check_tapped_layer(oracle, st, kept[l], f"layer {l}")
+
+
+# ---------------- peak probes ----------------
+
+def test_probe_kernels_touch_what_they_claim(B):
+    """The read probe loads every vector exactly once (the XOR of its per-thread words equals the XOR
+    of the buffer) and the MFMA probe really multiplies (its sums follow from the operand patterns)."""
+    n = (1 << 22) + 4080                                  # not a multiple of the grid stride
+    src = torch.randint(0, 2 ** 31 - 1, (n,), dtype=torch.int32, device="cuda")
+    out = torch.zeros(B.probe_out_bytes() // 4, dtype=torch.int32, device="cuda")
+    assert B.probe_read(src, out) == 4 * n
+    torch.cuda.synchronize()
+    want = np.bitwise_xor.reduce(host(src).view(np.uint32))
+    got = np.bitwise_xor.reduce(host(out)[: 2048 * 256].view(np.uint32))
+    assert want == got
+    # A[i, k] = (lane + j) & 3 and B[k, n] = (lane >> 2) & 1 with lane = i (or n) + 32 * (k // 8), j = k % 8
+    iters = 3
+    fout = torch.zeros(B.probe_out_bytes() // 4, dtype=torch.float32, device="cuda")
+    flop = B.probe_mfma(iters, fout)
+    torch.cuda.synchronize()
+    assert flop == 2048 * 8 * iters * 4 * 2 * 32 * 32 * 16
+    A = np.zeros((32, 16)); Bm = np.zeros((16, 32))
+    for lane in range(64):
+        for j in range(8):
+            A[lane & 31, 8 * (lane >> 5) + j] = (lane + j) & 3
+            Bm[8 * (lane >> 5) + j, lane & 31] = (lane >> 2) & 1
+    per_wave = 4 * iters * (A @ Bm).sum()
+    waves = host(fout).reshape(-1, 64).sum(axis=1)
+    assert np.all(waves == per_wave), (waves[:4], per_wave)
