@@ -170,7 +170,8 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
  * 4 = prefill: sharing the last partial round of tiles out along K (1 = never, 2 = always),
  * 5 = prefill: order in which tiles are dealt to workgroups (1 = row tiles of a column tile first,
  * 2 = blocks of 8 column tiles spread over the 8 XCDs), 6 = largest M the streaming kernels take
- * (32 .. 1024; replaces the choice by shape), 7 = rows one streaming workgroup takes (16 or 32).
+ * (32 .. 1024; replaces the choice by shape), 7 = rows one streaming workgroup takes (16 or 32),
+ * 8 = non-temporal weight loads in the streaming kernels (1 = always, 2 = never).
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);
 

@@ -87,7 +87,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         if (pl.S > 1 && pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
         DecodeArgs a;
         a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
-        a.M = M; a.K = K; a.N = N; a.S = pl.S; a.rows = pl.rows;
+        a.M = M; a.K = K; a.N = N; a.S = pl.S; a.rows = pl.rows; a.stream_loads = pl.stream_loads;
         a.partial = nullptr; a.counters = nullptr;
         if (pl.S > 1) {
             if (!workspace || workspace_bytes < kCounterBytes + pl.partial_bytes) return MORPH_ERR_WORKSPACE;

@@ -120,7 +120,8 @@ struct TileGeom {
 // workgroup barrier, after which TileGeom::item_sum may be called by any thread.  The caller must
 // make sure (barrier) that nobody still reads yl from an earlier unit when this is entered.
 // XT: read x past the caches (it was written by other workgroups of the same kernel).
-template <bool W4, int MT, int kWaves, bool XT>
+// NT: load the weights non-temporally (they are read once by this workgroup alone).
+template <bool W4, int MT, int kWaves, bool XT, bool NT = false>
 __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
 {
     constexpr int WPL = Tile<W4, MT>::WPL;
@@ -129,6 +130,7 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     constexpr int WN  = Tile<W4, MT>::WN, WK = kWaves / WN;
     constexpr int NV  = MT * CPL;                        // f32x4 result vectors per lane
     constexpr int kAuxX = XT ? kAuxSystemScope : 0;
+    constexpr int kAuxW = NT ? kAuxStream : 0;
     typedef Stage<W4, MT, WPL> StageT;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -182,13 +184,13 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             if constexpr (W4 && WPL == 2) {
-                const u32x2 v = buf_load_u32x2(rw, vw, so + (uint32_t)i * row_bytes);
+                const u32x2 v = buf_load_u32x2<kAuxW>(rw, vw, so + (uint32_t)i * row_bytes);
                 st.w4[i][0] = v[0];
                 st.w4[i][WPL - 1] = v[1];
             } else if constexpr (W4) {
-                st.w4[i][0] = buf_load_u32(rw, vw, so + (uint32_t)i * row_bytes);
+                st.w4[i][0] = buf_load_u32<kAuxW>(rw, vw, so + (uint32_t)i * row_bytes);
             } else {
-                st.wh[i] = buf_load_u32x4(rw, vw, so + (uint32_t)i * row_bytes);
+                st.wh[i] = buf_load_u32x4<kAuxW>(rw, vw, so + (uint32_t)i * row_bytes);
             }
         }
 #pragma unroll

@@ -24,17 +24,23 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
+// AUX is the cache-policy operand: 0 = cached, kAuxStream = non-temporal (data read once: do not
+// keep it in the caches at the expense of what is reused).
+constexpr int kAuxStream = 2;
+template <int AUX = 0>
 __device__ __forceinline__ uint32_t buf_load_u32(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
 {
-    return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+    return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, AUX);
 }
+template <int AUX = 0>
 __device__ __forceinline__ u32x2 buf_load_u32x2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
 {
-    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, AUX);
 }
+template <int AUX = 0>
 __device__ __forceinline__ u32x4 buf_load_u32x4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
 {
-    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, AUX);
 }
 
 template <typename T, typename U>

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict
 
 // Matrix-core issue rate: every wave runs `iters` rounds of four independent 32x32x16 fp16 MFMAs
 // on registers (no memory traffic inside the loop).
-constexpr int kProbeMfmaThreads = 512, kProbeMfmaPerIter = 4;
+constexpr int kProbeMfmaThreads = 512;
 __global__ __launch_bounds__(kProbeMfmaThreads) void probe_mfma_kernel(int iters, float* __restrict__ out)
 {
     const int tid = threadIdx.x;

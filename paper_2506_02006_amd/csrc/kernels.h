@@ -25,6 +25,7 @@ struct DecodeArgs {
     int             M, K, N;
     int             S;         // workgroups sharing one column tile (split along K)
     int             rows;      // rows per slice, 16 or 32 (from the plan)
+    int             stream_loads;  // weights loaded non-temporally (from the plan; one-tile kernels only)
     int             tiles;     // column tiles (set by launch_decode)
     int             slices;    // row slices (set by launch_decode)
 };
@@ -36,6 +37,7 @@ struct DecodePlan {
     int    S;                  // split along K across workgroups
     size_t partial_bytes;      // 0 when S == 1
     double est_us;             // estimated time of the parts of a launch that depend on the plan
+    int    stream_loads;       // load the weights non-temporally
 };
 constexpr size_t kCounterBytes = 65536;  // head of the workspace: arrival counters (one per column tile and row slice)
 DecodePlan plan_decode(int is_w4, int M, int K, int N);
@@ -105,6 +107,6 @@ hipError_t launch_probe_mfma(int iters, void* out, hipStream_t st);
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_COUNT = 8 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_COUNT = 12 };
 
 }  // namespace morph

@@ -196,6 +196,18 @@ def test_decode_either_slice_height(B, oracle, M, rows):
         B.set_tuning(B.TUNE_DECODE_SLICE, 0)
 
 
+@pytest.mark.parametrize("mode", [1, 2], ids=["nontemporal", "cached"])
+def test_decode_weight_load_policy(B, oracle, mode):
+    """The one-tile streaming kernels exist with non-temporal and with cached weight loads."""
+    B.set_tuning(B.TUNE_DECODE_STREAM, mode)
+    try:
+        for M in (1, 16):
+            check_w4(B, oracle, M, 1792, 520, seed=M + mode)
+            check_fp16(B, oracle, M, 1792, 264, seed=M + mode)
+    finally:
+        B.set_tuning(B.TUNE_DECODE_STREAM, 0)
+
+
 @pytest.mark.parametrize("split", [1, 2, 3, 7])
 def test_decode_every_split(B, oracle, split):
     """The K split across workgroups only changes the fp32 summation order."""
