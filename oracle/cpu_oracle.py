@@ -20,6 +20,10 @@ What is computed (paper Section 4.3, footnote: weight-only INT4; Section 5.2:
   error_metric     O6  max |y - y_ref| / max |y_ref|
   stack glue       O7  the elementwise/row-norm steps between the four linears
                        of a synthetic decoder layer (fp64 numpy)
+  layer record     O8  the bytes of one layer (its four linears, in either form) as
+                       they sit in the pinned host pool and in the layer's device slot,
+                       and what an in-place swap leaves in the slot (Section 4.3,
+                       "Asynchronous In-place Layer Swapping"; Appendix C)
 """
 import ctypes
 import os
@@ -237,3 +241,78 @@ def glue_swiglu(gu: np.ndarray) -> np.ndarray:
     F = gu.shape[1] // 2
     g, u = gu[:, :F], gu[:, F:]
     return rms(g / (1.0 + np.exp(-g)) * u)
+
+
+# ---------------- O8: layer records and the in-place swap ----------------
+# Section 4.3 / Appendix C: every variant of a layer is kept whole in pinned host memory, every
+# layer owns one preallocated region of GPU memory, and a swap copies a variant to the START of
+# that region, so that the layer keeps its address.  A record is the layer's arrays one after the
+# other, linear by linear (qkv, o, gate_up, down); within a linear: the fp16 weight matrix, or
+# packed codes, then scales, then packed zeros.  Every array starts on a multiple of 256 bytes.
+
+RECORD_LINEARS = ("qkv", "o", "gate_up", "down")
+RECORD_ALIGN = 256
+
+
+def layer_shapes(hidden: int, inter: int) -> dict:
+    return {"qkv": (hidden, 3 * hidden), "o": (hidden, hidden), "gate_up": (hidden, 2 * inter), "down": (inter, hidden)}
+
+
+def _record_arrays(kind: str, K: int, N: int, G: int = 128):
+    """(dtype, shape) of the arrays of one linear in a record, in order."""
+    if kind == "fp16":
+        return [(np.float16, (K, N))]
+    return [(np.uint32, (K, N // 8)), (np.float16, (K // G, N)), (np.uint32, (K // G, N // 8))]
+
+
+def layer_record_bytes(kind: str, hidden: int, inter: int) -> int:
+    total = 0
+    for name in RECORD_LINEARS:
+        K, N = layer_shapes(hidden, inter)[name]
+        for dt, shp in _record_arrays(kind, K, N):
+            total += -(-int(np.prod(shp)) * np.dtype(dt).itemsize // RECORD_ALIGN) * RECORD_ALIGN
+    return total
+
+
+def layer_record_pack(kind: str, linears: dict, hidden: int, inter: int) -> np.ndarray:
+    """linears: name -> (w,) for fp16 or (qweight, scales, qzeros).  Returns the record as bytes
+    (padding bytes are zero)."""
+    out = np.zeros(layer_record_bytes(kind, hidden, inter), np.uint8)
+    pos = 0
+    for name in RECORD_LINEARS:
+        K, N = layer_shapes(hidden, inter)[name]
+        arrays = linears[name]
+        spec = _record_arrays(kind, K, N)
+        assert len(arrays) == len(spec), name
+        for a, (dt, shp) in zip(arrays, spec):
+            a = np.ascontiguousarray(a)
+            assert a.shape == shp and a.dtype.itemsize == np.dtype(dt).itemsize, (name, a.shape, a.dtype)
+            raw = a.view(np.uint8).reshape(-1)
+            out[pos:pos + raw.size] = raw
+            pos += -(-raw.size // RECORD_ALIGN) * RECORD_ALIGN
+    assert pos == out.size
+    return out
+
+
+def layer_record_unpack(kind: str, rec: np.ndarray, hidden: int, inter: int) -> dict:
+    """Inverse of layer_record_pack on the first layer_record_bytes() bytes of rec."""
+    rec = np.asarray(rec, np.uint8).reshape(-1)
+    out, pos = {}, 0
+    for name in RECORD_LINEARS:
+        K, N = layer_shapes(hidden, inter)[name]
+        arrays = []
+        for dt, shp in _record_arrays(kind, K, N):
+            nb = int(np.prod(shp)) * np.dtype(dt).itemsize
+            arrays.append(rec[pos:pos + nb].copy().view(dt).reshape(shp))
+            pos += -(-nb // RECORD_ALIGN) * RECORD_ALIGN
+        out[name] = tuple(arrays)
+    return out
+
+
+def swap_in_place(slot: np.ndarray, record: np.ndarray) -> np.ndarray:
+    """What a swap leaves in a layer's slot: the record over its first bytes, the rest as it was."""
+    slot = np.array(slot, np.uint8).reshape(-1)
+    record = np.asarray(record, np.uint8).reshape(-1)
+    assert record.size <= slot.size, "a slot is sized for the largest variant of its layer"
+    slot[:record.size] = record
+    return slot

@@ -391,3 +391,76 @@ def test_pins_catch_planted_mistakes(oracle):
     for name, Dm in mutants.items():
         assert not np.array_equal(Dm, D), name
         assert np.abs(Dm - W).max() > 0.5 * s.max() * 1.01, name      # breaks P1
+
+
+# ---------- P9 layer records and the in-place swap (Section 4.3, Appendix C) ----------
+
+def _tiny_layer(oracle, hidden, inter, seed):
+    shapes = oracle.layer_shapes(hidden, inter)
+    fp16, w4 = {}, {}
+    for t, name in enumerate(oracle.RECORD_LINEARS):
+        K, N = shapes[name]
+        W = synth.weights(91, K, N, layer_id=seed, tensor_id=t)
+        fp16[name] = (W.astype(np.float16),)
+        w4[name] = oracle.quantize_w4(W)
+    return fp16, w4
+
+
+def test_p9_record_sizes_match_paper_and_arrays(oracle):
+    # a 7B layer: every array is already a multiple of 256 bytes, so the record is the plain sum,
+    # which the paper quotes as about 0.4 GB (FP16) and about 0.1 GB (INT4)
+    assert oracle.layer_record_bytes("fp16", 4096, 11008) == 404_750_336
+    assert oracle.layer_record_bytes("w4", 4096, 11008) == 105_140_224
+    # a small layer whose arrays are NOT multiples of 256 bytes: each array is padded on its own
+    h, i = 128, 128
+    raw = 0
+    for K, N in oracle.layer_shapes(h, i).values():
+        raw += K * N // 2 + (K // 128) * N * 2 + (K // 128) * N // 2
+    assert oracle.layer_record_bytes("w4", h, i) > raw      # the packed zeros of one group row are 64 .. 192 bytes
+    assert oracle.layer_record_bytes("w4", h, i) % 256 == 0
+
+
+def test_p9_record_round_trip_and_order(oracle):
+    h, i = 256, 384
+    fp16, w4 = _tiny_layer(oracle, h, i, 1)
+    for kind, lin in (("fp16", fp16), ("w4", w4)):
+        rec = oracle.layer_record_pack(kind, lin, h, i)
+        assert rec.dtype == np.uint8 and rec.size == oracle.layer_record_bytes(kind, h, i)
+        back = oracle.layer_record_unpack(kind, rec, h, i)
+        for name in oracle.RECORD_LINEARS:
+            assert len(back[name]) == len(lin[name])
+            for a, b in zip(back[name], lin[name]):
+                assert a.shape == b.shape and np.array_equal(a.view(np.uint8), np.ascontiguousarray(b).view(np.uint8))
+    # the record starts with qkv's first array, and the arrays follow in the documented order
+    rec = oracle.layer_record_pack("w4", w4, h, i)
+    q = np.ascontiguousarray(w4["qkv"][0]).view(np.uint8).reshape(-1)
+    assert np.array_equal(rec[:q.size], q)
+    s0 = -(-q.size // 256) * 256
+    sc = np.ascontiguousarray(w4["qkv"][1]).view(np.uint8).reshape(-1)
+    assert np.array_equal(rec[s0:s0 + sc.size], sc)
+    d = np.ascontiguousarray(w4["down"][2]).view(np.uint8).reshape(-1)
+    tail = -(-d.size // 256) * 256
+    assert np.array_equal(rec[rec.size - tail: rec.size - tail + d.size], d)
+    # a linear computed from the unpacked record equals the one computed from the arrays
+    x = synth.activations(91, 3, h)
+    back = oracle.layer_record_unpack("w4", rec, h, i)
+    assert np.array_equal(oracle.linear_w4a16(x, *back["o"]), oracle.linear_w4a16(x, *w4["o"]))
+
+
+def test_p9_swap_in_place_keeps_the_address_and_the_rest(oracle):
+    h, i = 256, 384
+    fp16, w4 = _tiny_layer(oracle, h, i, 2)
+    r16 = oracle.layer_record_pack("fp16", fp16, h, i)
+    r4 = oracle.layer_record_pack("w4", w4, h, i)
+    assert r4.size < r16.size                      # the slot is sized for the fp16 variant
+    slot = oracle.swap_in_place(np.full(r16.size, 0xEE, np.uint8), r16)
+    assert np.array_equal(slot, r16)
+    s2 = oracle.swap_in_place(slot, r4)
+    assert np.array_equal(s2[:r4.size], r4) and np.array_equal(s2[r4.size:], r16[r4.size:])
+    assert np.array_equal(slot, r16)               # the input is not modified
+    # the W4 layer is read back whole from the slot; swapping fp16 back restores every byte
+    back = oracle.layer_record_unpack("w4", s2, h, i)
+    assert np.array_equal(back["down"][0], w4["down"][0])
+    assert np.array_equal(oracle.swap_in_place(s2, r16), r16)
+    with pytest.raises(AssertionError):
+        oracle.swap_in_place(np.zeros(r4.size, np.uint8), r16)
