@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="headline only, skip the detail sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--sections", default="config2,config3,config4,config5",
+    ap.add_argument("--sections", default="config2,config3,config4,config5,swap",
                     help="detail sections to run after the headline (comma separated; used by the profiling commands)")
     return ap.parse_args()
 
@@ -329,6 +329,95 @@ def main():
         if d5:
             detail["config5_stack_M32"] = d5
         del base16, base4
+
+        # ---- layers changing precision in place while the 32-layer stack decodes (M = 32) ----
+        if "swap" in sections:
+            Ls, h7, i7 = 32, 4096, 11008
+            sst = B.SwapStack(h7, i7, M5, Ls)
+            # two distinct layers' records in pinned host memory, shared by the layers in turn
+            host_recs = []
+            for j in range(2):
+                lay16 = {name: make_fp16(*shapes7[name]) for name in order}
+                recs = {}
+                for kind in (B.KIND_FP16, B.KIND_W4A16):
+                    rec = sst.new_host_record(kind)
+                    views = B.layer_record_views(kind, rec, h7, i7)
+                    for name in order:
+                        src = (lay16[name],) if kind == B.KIND_FP16 else B.quantize_layer(lay16[name])
+                        for dst, a in zip(views[name][1:], src):
+                            dst.copy_(a)
+                    recs[kind] = rec
+                host_recs.append(recs)
+                del lay16
+            torch.cuda.synchronize()
+            for l in range(Ls):
+                for kind in (B.KIND_FP16, B.KIND_W4A16):
+                    sst.set_host_record(l, kind, host_recs[l % 2][kind])
+                sst.load(l, B.KIND_FP16)
+            xs5 = rand_x(M5, h7)
+            rec_bytes = {kind: B.layer_record_bytes(kind, h7, i7) for kind in (B.KIND_FP16, B.KIND_W4A16)}
+
+            def copy_alone(kind, layer):
+                # the copy by itself, nothing else running (layer is left in `kind`)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record(sst.copy_stream)
+                B._check(B.lib().morph_layer_swap_async(sst.slots[layer].data_ptr(), sst.slot_bytes,
+                                                        sst.host[layer][kind].data_ptr(), kind, h7, i7,
+                                                        sst.copy_stream.cuda_stream), "morph_layer_swap_async")
+                e1.record(sst.copy_stream)
+                sst.copy_stream.synchronize()
+                sst._adopt(layer, kind)
+                return e0.elapsed_time(e1)
+
+            ms_w4 = min(copy_alone(B.KIND_W4A16, 31) for _ in range(3))
+            ms_16 = min(copy_alone(B.KIND_FP16, 31) for _ in range(3))
+            # steps without a swap (all fp16, launched eagerly as the swapping path has to be)
+            quiet = timed(lambda i: sst.step(xs5), 16, 3) / 16
+            # one layer per step goes to W4, from the last layer down: 32 steps, each carrying one copy
+            torch.cuda.synchronize()
+            sst.swap_events.clear()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for l in range(Ls - 1, -1, -1):
+                sst.swap(l, B.KIND_W4A16)
+                sst.step(xs5, timing=True)
+            sst.step(xs5)                                 # adopts the last one
+            e1.record()
+            torch.cuda.synchronize()
+            ramp_ms = e0.elapsed_time(e1)
+            under = [a.elapsed_time(b) for (_, _, a, b) in sst.swap_events]
+            quiet4 = timed(lambda i: sst.step(xs5), 16, 3) / 16
+            # and back: every step brings one layer's fp16 record (four times the bytes) into the slot the
+            # W4 variant is still needed from until the copy starts, so the next step waits for it
+            torch.cuda.synchronize()
+            b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            b0.record()
+            for l in range(Ls):
+                sst.swap(l, B.KIND_FP16)
+                sst.step(xs5)
+            sst.step(xs5)
+            b1.record()
+            torch.cuda.synchronize()
+            back_ms = b0.elapsed_time(b1)
+            # the same 33 steps without copies cost between 33 all-fp16 and 33 all-W4 steps; the mix of
+            # step t is t layers in W4, so the no-copy cost is the mean of the two quiet figures
+            expect_ms = 33 * 0.5 * (quiet + quiet4) * 1e3
+            detail["swap_llama7b_M32"] = {
+                "w4_record_MB": round(rec_bytes[B.KIND_W4A16] / 1e6, 1), "fp16_record_MB": round(rec_bytes[B.KIND_FP16] / 1e6, 1),
+                "copy_alone_ms": {"w4": round(ms_w4, 3), "fp16": round(ms_16, 3)},
+                "copy_alone_GBps": {"w4": round(rec_bytes[B.KIND_W4A16] / ms_w4 / 1e6, 1),
+                                    "fp16": round(rec_bytes[B.KIND_FP16] / ms_16 / 1e6, 1)},
+                "copy_under_decode_ms": {"w4_mean": round(sum(under) / len(under), 3), "w4_max": round(max(under), 3)},
+                "step_ms_all_fp16_eager": round(quiet * 1e3, 4), "step_ms_all_w4_eager": round(quiet4 * 1e3, 4),
+                "ramp_33_steps_with_32_swaps_ms": round(ramp_ms, 3), "ramp_expected_without_copies_ms": round(expect_ms, 3),
+                "ramp_overhead_pct": round((ramp_ms / expect_ms - 1) * 100, 2),
+                "decode_ms_lost_per_w4_swap": round((ramp_ms - expect_ms) / Ls, 3),
+                "ramp_back_33_steps_with_32_fp16_restores_ms": round(back_ms, 3),
+                "paper_context": "Section 4.3 quotes about 4 ms (INT4) and 16 ms (FP16) per Llama-2-7B layer over PCIe Gen4 "
+                                 "(26-28 GB/s), about 6 ms for a complete INT4 swap, overlapped with decoding",
+            }
+            del sst, host_recs
         result["detail"] = detail
 
     # ------------- CPU oracle baseline: bounded sample of the same workload -------------

@@ -157,6 +157,36 @@ int morph_stack_forward_fused(const morph_layer_desc* layers /* host */, int n_l
                               int M, int hidden, int inter, void* workspace, size_t workspace_bytes,
                               void* stream);
 
+/* ---- layer records and the in-place swap (Section 4.3, "Model Preloading" and "Asynchronous
+ * In-place Layer Swapping"; Appendix C) ----
+ * Every variant of a layer is kept whole ("record") in pinned host memory, every layer owns one
+ * region of device memory sized for its largest variant ("slot"), and a swap copies a record to
+ * the START of the slot, so that the layer keeps its address whatever its precision.
+ * Record layout: the arrays of the four linears one after the other in the order qkv, o,
+ * gate_up, down; for a linear of kind FP16 its [K,N] fp16 matrix, of kind W4A16 qweight
+ * [K,N/8] int32, then scales [K/128,N] fp16, then qzeros [K/128,N/8] int32; every array starts on a
+ * multiple of 256 bytes (padding in between is never read).  hidden and inter as in the stack
+ * calls (multiples of 128).
+ *   morph_layer_record_bytes: size of a record, a multiple of 256; 0 for a kind or shape that does
+ *     not exist.  A 7B layer: 404,750,336 bytes in fp16, 105,140,224 in W4.
+ *   morph_layer_record_desc: pointer arithmetic only (nothing is dereferenced, so `base` may be a
+ *     host or a device address, 256-byte aligned): fills *out (host) with the kind and the array
+ *     addresses of a record that starts at `base`, ready for the stack calls.
+ *   morph_layer_swap_async: enqueues ONE host-to-device copy of morph_layer_record_bytes() bytes from
+ *     host_record to slot on copy_stream and returns; slot 256-byte aligned and slot_bytes at least
+ *     the record size (WORKSPACE otherwise).  The copy is hipMemcpyAsync (the copy engines: no
+ *     compute unit is taken from the decode kernels); host_record should be pinned (pageable
+ *     memory works, but the runtime then stages the copy and the call may block).
+ *     ORDER IS THE CALLER'S: the copy must not start before the last kernel that reads the old
+ *     contents has finished, and no kernel may read the slot before the copy has finished (events
+ *     between the compute stream and copy_stream).  The library keeps no state: after the swap the
+ *     caller hands the stack calls a descriptor of the new kind made by morph_layer_record_desc().
+ *     The bytes of the slot beyond the record are left as they were. */
+size_t morph_layer_record_bytes(int kind, int hidden, int inter);
+int morph_layer_record_desc(int kind, const void* base, int hidden, int inter, morph_layer_desc* out);
+int morph_layer_swap_async(void* slot, size_t slot_bytes, const void* host_record, int kind, int hidden,
+                           int inter, void* copy_stream);
+
 /* Launch every kernel variant once on tiny internal dummies so that code objects are loaded
  * before serving starts (Section 4.3: kernels are precompiled ahead of time; Appendix C: with
  * dummy data).  `dummy` is a caller-provided device buffer of at least morph_warmup_bytes(). */

@@ -26,6 +26,7 @@ EXPORTS = [
     "morph_stack_forward_fused", "morph_warmup_bytes", "morph_warmup",
     "morph_set_tuning", "morph_copy", "morph_status_string",
     "morph_probe_out_bytes", "morph_probe_read", "morph_probe_mfma",
+    "morph_layer_record_bytes", "morph_layer_record_desc", "morph_layer_swap_async",
 ]
 
 
@@ -77,6 +78,10 @@ def lib() -> ctypes.CDLL:
     L.morph_warmup.argtypes = [vp, sz, vp]
     L.morph_set_tuning.argtypes = [i, i]
     L.morph_copy.argtypes = [vp, vp, sz, vp]
+    L.morph_layer_record_bytes.restype = sz
+    L.morph_layer_record_bytes.argtypes = [i, i, i]
+    L.morph_layer_record_desc.argtypes = [i, vp, i, i, ctypes.POINTER(LayerDesc)]
+    L.morph_layer_swap_async.argtypes = [vp, sz, vp, i, i, i, vp]
     L.morph_probe_out_bytes.restype = sz
     L.morph_probe_out_bytes.argtypes = []
     L.morph_probe_read.argtypes = [vp, sz, vp, sz, vp]
@@ -316,5 +321,155 @@ class LayerStack:
         for name, cols in sizes:
             nb = M * cols * 2
             out[name] = buf[off:off + nb].view(torch.float16).view(M, cols)
+            off += (nb + 255) & ~255
+        return out
+
+
+# ---------------- layer records and the in-place swap ----------------
+
+LINEAR_NAMES = ("qkv", "o", "gate_up", "down")
+
+
+def layer_record_bytes(kind: int, hidden: int, inter: int) -> int:
+    n = int(lib().morph_layer_record_bytes(kind, hidden, inter))
+    if n == 0:
+        raise MorphError(2, "morph_layer_record_bytes")
+    return n
+
+
+def layer_record_desc(kind: int, base_ptr: int, hidden: int, inter: int) -> LayerDesc:
+    d = LayerDesc()
+    _check(lib().morph_layer_record_desc(kind, base_ptr, hidden, inter, ctypes.byref(d)), "morph_layer_record_desc")
+    return d
+
+
+def layer_record_views(kind: int, buf: torch.Tensor, hidden: int, inter: int) -> dict:
+    """The arrays of a record that starts at buf[0] (uint8 tensor, host or device) as tensor views:
+    name -> ("fp16", w) | ("w4", qweight, scales, qzeros).  Offsets come from the library."""
+    assert buf.dtype == torch.uint8 and buf.is_contiguous() and buf.numel() >= layer_record_bytes(kind, hidden, inter)
+    base = buf.data_ptr()
+    d = layer_record_desc(kind, base, hidden, inter)
+    shapes = {"qkv": (hidden, 3 * hidden), "o": (hidden, hidden), "gate_up": (hidden, 2 * inter), "down": (inter, hidden)}
+    out = {}
+    for name in LINEAR_NAMES:
+        K, N = shapes[name]
+        ld = getattr(d, name)
+        def view(ptr, dtype, rows, cols):
+            off, nb = ptr - base, rows * cols * torch.empty((), dtype=dtype).element_size()
+            return buf[off:off + nb].view(dtype).view(rows, cols)
+        if kind == KIND_FP16:
+            out[name] = ("fp16", view(ld.w, torch.float16, K, N))
+        else:
+            out[name] = ("w4", view(ld.w, torch.int32, K, N // 8), view(ld.scales, torch.float16, K // 128, N),
+                         view(ld.qzeros, torch.int32, K // 128, N // 8))
+    return out
+
+
+class SwapStack:
+    """A stack of layers that live in fixed device slots and change precision in place while the
+    stack keeps decoding: every layer has a slot sized for its fp16 record and pinned host records
+    of the variants it may take; swap() enqueues the copy on a stream of its own, ordered by events
+    against the compute stream so that it starts after the last kernel that reads the old contents
+    and the next step waits for it only when it reaches that layer.
+
+    Marshalling and stream ordering only: copies are morph_layer_swap_async, steps morph_stack_forward."""
+
+    def __init__(self, hidden: int, inter: int, M: int, n_layers: int, device="cuda"):
+        self.hidden, self.inter, self.M, self.n_layers, self.device = hidden, inter, M, n_layers, device
+        self.slot_bytes = layer_record_bytes(KIND_FP16, hidden, inter)
+        self.slots = [torch.empty(self.slot_bytes, dtype=torch.uint8, device=device) for _ in range(n_layers)]
+        self.kinds = [None] * n_layers
+        self.host = [dict() for _ in range(n_layers)]          # kind -> pinned uint8 tensor (may be shared between layers)
+        self.desc = (LayerDesc * n_layers)()
+        self.copy_stream = torch.cuda.Stream(device=device)     # default priority
+        self.scratch = torch.empty(int(lib().morph_stack_scratch_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
+        self.tap = torch.empty(int(lib().morph_stack_tap_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
+        need = 0
+        for kind in (KIND_FP16, KIND_W4A16):
+            for K, N in ((hidden, 3 * hidden), (hidden, hidden), (hidden, 2 * inter), (inter, hidden)):
+                need = max(need, workspace_bytes(kind, M, K, N))
+        self.ws = new_workspace(need, device)
+        self._pending = {}        # layer -> kind: copy to be enqueued right after the layer's next use
+        self._arriving = {}       # layer -> (kind, event recorded behind the copy)
+        self.swap_events = []     # (layer, kind, start event, end event) of finished enqueues, for timing
+
+    def new_host_record(self, kind: int) -> torch.Tensor:
+        return torch.empty(layer_record_bytes(kind, self.hidden, self.inter), dtype=torch.uint8, pin_memory=True)
+
+    def set_host_record(self, layer: int, kind: int, rec: torch.Tensor):
+        assert rec.dtype == torch.uint8 and rec.is_pinned() and rec.numel() == layer_record_bytes(kind, self.hidden, self.inter)
+        self.host[layer][kind] = rec
+
+    def load(self, layer: int, kind: int):
+        """Bring a variant in outside of any step (synchronises): the initial placement."""
+        rec = self.host[layer][kind]
+        torch.cuda.synchronize()
+        _check(lib().morph_layer_swap_async(self.slots[layer].data_ptr(), self.slot_bytes, rec.data_ptr(), kind,
+                                            self.hidden, self.inter, self.copy_stream.cuda_stream), "morph_layer_swap_async")
+        self.copy_stream.synchronize()
+        self._adopt(layer, kind)
+
+    def _adopt(self, layer: int, kind: int):
+        self.kinds[layer] = kind
+        self.desc[layer] = layer_record_desc(kind, self.slots[layer].data_ptr(), self.hidden, self.inter)
+
+    def swap(self, layer: int, kind: int):
+        """Ask for layer to change to kind: the copy is enqueued during the next step, right behind
+        that step's use of the layer, and the step after that runs the new variant."""
+        assert kind in self.host[layer] and layer not in self._pending and layer not in self._arriving
+        self._pending[layer] = kind
+
+    def _run(self, x_io, lo: int, hi: int, tap_layer: int):
+        if hi <= lo:
+            return
+        first = ctypes.cast(ctypes.byref(self.desc, lo * ctypes.sizeof(LayerDesc)), ctypes.POINTER(LayerDesc))
+        _check(lib().morph_stack_forward(first, hi - lo, _dev(x_io, torch.float16, "x_io"), self.M, self.hidden,
+                                         self.inter, self.scratch.data_ptr(), self.scratch.numel(),
+                                         self.ws.data_ptr(), self.ws.numel(), tap_layer - lo if lo <= tap_layer < hi else -1,
+                                         self.tap.data_ptr(), _stream()), "morph_stack_forward")
+
+    def step(self, x_io: torch.Tensor, tap_layer: int = -1, timing: bool = False):
+        """One decode step in place on x_io [M, hidden]; services arriving and pending swaps."""
+        assert x_io.shape == (self.M, self.hidden)
+        compute = torch.cuda.current_stream()
+        marks = sorted(set(self._pending) | set(self._arriving))
+        lo = 0
+        for l in marks:
+            if l in self._arriving:
+                # the new variant is used from this step on: run up to the layer, wait for its copy
+                self._run(x_io, lo, l, tap_layer)
+                lo = l
+                kind, ready = self._arriving.pop(l)
+                compute.wait_event(ready)
+                self._adopt(l, kind)
+            if l in self._pending:
+                # old variant's last use, then the copy may start
+                self._run(x_io, lo, l + 1, tap_layer)
+                lo = l + 1
+                kind = self._pending.pop(l)
+                used = torch.cuda.Event()
+                used.record(compute)
+                self.copy_stream.wait_event(used)
+                t0 = torch.cuda.Event(enable_timing=True) if timing else None
+                if timing:
+                    t0.record(self.copy_stream)
+                _check(lib().morph_layer_swap_async(self.slots[l].data_ptr(), self.slot_bytes, self.host[l][kind].data_ptr(),
+                                                    kind, self.hidden, self.inter, self.copy_stream.cuda_stream),
+                       "morph_layer_swap_async")
+                ready = torch.cuda.Event(enable_timing=timing)
+                ready.record(self.copy_stream)
+                if timing:
+                    self.swap_events.append((l, kind, t0, ready))
+                self._arriving[l] = (kind, ready)
+        self._run(x_io, lo, self.n_layers, tap_layer)
+        return x_io
+
+    def tapped(self):
+        M, h, i = self.M, self.hidden, self.inter
+        sizes = [("x", h), ("qkv", 3 * h), ("a", h), ("o", h), ("r", h), ("gu", 2 * i), ("m", i), ("d", h)]
+        out, off = {}, 0
+        for name, cols in sizes:
+            nb = M * cols * 2
+            out[name] = self.tap[off:off + nb].view(torch.float16).view(M, cols)
             off += (nb + 255) & ~255
         return out

@@ -418,6 +418,71 @@ int morph_copy(const void* src, void* dst, size_t bytes, void* stream)
     return launch_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
 
+// ---- layer records and the in-place swap ----
+namespace {
+struct RecordLayout {
+    size_t off[4][3];     // [linear][array]: weights or codes, scales, zeros
+    size_t bytes;
+};
+// 0 bytes = a shape no layer can have
+RecordLayout record_layout(int kind, int hidden, int inter)
+{
+    RecordLayout L{};
+    if (kind != MORPH_KIND_FP16 && kind != MORPH_KIND_W4A16) return L;
+    if (hidden < MORPH_GROUP_SIZE || inter < MORPH_GROUP_SIZE || hidden % MORPH_GROUP_SIZE || inter % MORPH_GROUP_SIZE) return L;
+    const size_t KN[4][2] = {{(size_t)hidden, 3 * (size_t)hidden}, {(size_t)hidden, (size_t)hidden},
+                             {(size_t)hidden, 2 * (size_t)inter}, {(size_t)inter, (size_t)hidden}};
+    size_t pos = 0;
+    for (int l = 0; l < 4; l++) {
+        const size_t K = KN[l][0], N = KN[l][1], G = K / MORPH_GROUP_SIZE;
+        if (kind == MORPH_KIND_FP16) {
+            L.off[l][0] = pos; pos += up256(K * N * 2);
+            L.off[l][1] = L.off[l][2] = 0;
+        } else {
+            L.off[l][0] = pos; pos += up256(K * (N / 8) * 4);
+            L.off[l][1] = pos; pos += up256(G * N * 2);
+            L.off[l][2] = pos; pos += up256(G * (N / 8) * 4);
+        }
+    }
+    L.bytes = pos;
+    return L;
+}
+}  // namespace
+
+size_t morph_layer_record_bytes(int kind, int hidden, int inter) { return record_layout(kind, hidden, inter).bytes; }
+
+int morph_layer_record_desc(int kind, const void* base, int hidden, int inter, morph_layer_desc* out)
+{
+    if (!base || !out) return MORPH_ERR_NULL;
+    const RecordLayout L = record_layout(kind, hidden, inter);
+    if (L.bytes == 0) return MORPH_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(base) & 255u) return MORPH_ERR_ALIGN;
+    const char* b = reinterpret_cast<const char*>(base);
+    morph_linear_desc* lins[4] = {&out->qkv, &out->o, &out->gate_up, &out->down};
+    for (int l = 0; l < 4; l++) {
+        lins[l]->kind   = kind;
+        lins[l]->w      = b + L.off[l][0];
+        lins[l]->scales = kind == MORPH_KIND_W4A16 ? b + L.off[l][1] : nullptr;
+        lins[l]->qzeros = kind == MORPH_KIND_W4A16 ? b + L.off[l][2] : nullptr;
+    }
+    return MORPH_OK;
+}
+
+int morph_layer_swap_async(void* slot, size_t slot_bytes, const void* host_record, int kind, int hidden,
+                           int inter, void* copy_stream)
+{
+    if (!slot || !host_record) return MORPH_ERR_NULL;
+    const RecordLayout L = record_layout(kind, hidden, inter);
+    if (L.bytes == 0) return MORPH_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(slot) & 255u) || !aligned16(host_record)) return MORPH_ERR_ALIGN;
+    if (slot_bytes < L.bytes) return MORPH_ERR_WORKSPACE;
+    // The runtime's copy engine, not a kernel: a copy kernel of even one workgroup takes a compute
+    // unit away from decode launches that count on one workgroup per unit (measured: eight copy
+    // workgroups slowed the decode steps under them by a third).
+    const hipError_t e = hipMemcpyAsync(slot, host_record, L.bytes, hipMemcpyHostToDevice, (hipStream_t)copy_stream);
+    return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
 size_t morph_probe_out_bytes(void) { return kProbeOutBytes; }
 
 int morph_probe_read(const void* src, size_t bytes, void* out, size_t out_bytes, void* stream)

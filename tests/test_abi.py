@@ -125,3 +125,61 @@ def test_probe_validation(L):
     assert L.morph_probe_mfma(10, None, need, None, None) == 1
     assert L.morph_probe_mfma(0, FAKE, need, None, None) == 2
     assert L.morph_probe_mfma(10, FAKE, 16, None, None) == 4
+
+
+def test_layer_record_layout_agrees_with_oracle(L):
+    """Pointer arithmetic only, so it runs on a host buffer: every array of a record packed by the
+    oracle is found, whole, at the address the library's descriptor names."""
+    import numpy as np
+    from oracle import build as ob
+    ob.build(force=False)
+    from oracle import cpu_oracle as O
+    from paper_2506_02006_amd import binding, synth
+    h, i = 128, 256
+    shapes = O.layer_shapes(h, i)
+    lin16, lin4 = {}, {}
+    for t, name in enumerate(O.RECORD_LINEARS):
+        K, N = shapes[name]
+        W = synth.weights(92, K, N, tensor_id=t)
+        lin16[name] = (W.astype(np.float16),)
+        lin4[name] = O.quantize_w4(W)
+    for kind, kname, lin in ((0, "fp16", lin16), (1, "w4", lin4)):
+        rec = O.layer_record_pack(kname, lin, h, i)
+        assert L.morph_layer_record_bytes(kind, h, i) == rec.size
+        raw = np.zeros(rec.size + 256, np.uint8)
+        base = (raw.ctypes.data + 255) & ~255
+        buf = raw[base - raw.ctypes.data: base - raw.ctypes.data + rec.size]
+        buf[:] = rec
+        d = binding.LayerDesc()
+        assert L.morph_layer_record_desc(kind, base, h, i, ctypes.byref(d)) == 0
+        for name in O.RECORD_LINEARS:
+            ld = getattr(d, name)
+            assert ld.kind == kind
+            ptrs = (ld.w,) if kind == 0 else (ld.w, ld.scales, ld.qzeros)
+            if kind == 0:
+                assert not ld.scales and not ld.qzeros
+            for ptr, arr in zip(ptrs, lin[name]):
+                arr = np.ascontiguousarray(arr)
+                off = ptr - base
+                assert off % 256 == 0 and 0 <= off and off + arr.nbytes <= rec.size
+                assert np.array_equal(buf[off:off + arr.nbytes], arr.view(np.uint8).reshape(-1)), (kname, name)
+
+
+def test_layer_record_and_swap_validation(L):
+    from paper_2506_02006_amd import binding
+    d = binding.LayerDesc()
+    B256 = 0x7F0000001000
+    assert L.morph_layer_record_bytes(0, 4096, 11008) == 404750336
+    assert L.morph_layer_record_bytes(1, 4096, 11008) == 105140224
+    assert L.morph_layer_record_bytes(2, 4096, 11008) == 0 and L.morph_layer_record_bytes(1, 100, 128) == 0
+    assert L.morph_layer_record_bytes(1, 128, 0) == 0
+    assert L.morph_layer_record_desc(1, None, 128, 128, ctypes.byref(d)) == 1
+    assert L.morph_layer_record_desc(1, B256, 128, 128, None) == 1
+    assert L.morph_layer_record_desc(1, B256 + 16, 128, 128, ctypes.byref(d)) == 3
+    assert L.morph_layer_record_desc(3, B256, 128, 128, ctypes.byref(d)) == 2
+    need = L.morph_layer_record_bytes(1, 128, 128)
+    assert L.morph_layer_swap_async(None, need, B256, 1, 128, 128, None) == 1
+    assert L.morph_layer_swap_async(B256, need, None, 1, 128, 128, None) == 1
+    assert L.morph_layer_swap_async(B256, need, B256, 1, 128, 100, None) == 2
+    assert L.morph_layer_swap_async(B256 + 64, need, B256, 1, 128, 128, None) == 3
+    assert L.morph_layer_swap_async(B256, need - 1, B256, 1, 128, 128, None) == 4
