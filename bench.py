@@ -152,7 +152,7 @@ def main():
     avg_launch_s = sec / (args.steps * launches_per_step)
     roofline = {
         "bound": "hbm",
-        "kernel": "decode_kernel<true, 1, 4> (W4A16, M <= 16), mean over the 12 launches of a step",
+        "kernel": "decode_kernel<true, 1, 4, true> (W4A16, M <= 16), mean over the 12 launches of a step",
         "achieved": round(value, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",

@@ -20,6 +20,9 @@ What is computed (paper Section 4.3, footnote: weight-only INT4; Section 5.2:
   error_metric     O6  max |y - y_ref| / max |y_ref|
   stack glue       O7  the elementwise/row-norm steps between the four linears
                        of a synthetic decoder layer (fp64 numpy)
+  *_w8             O9  the 8-bit weight-only variant (Section 4.3 lists INT8 next to INT4;
+                       Appendix C: FP16, W8, W4): the same scheme with 255 steps, uint8 codes
+                       and zeros, four per word along N
   layer record     O8  the bytes of one layer (its four linears, in either form) as
                        they sit in the pinned host pool and in the layer's device slot,
                        and what an in-place swap leaves in the slot (Section 4.3,
@@ -51,6 +54,7 @@ def _load():
         _b.build(force=True)
     _lib = ctypes.CDLL(_LIB_PATH)
     _lib.oracle_quantize_w4.restype = ctypes.c_int
+    _lib.oracle_quantize_w8.restype = ctypes.c_int
     _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
 
@@ -192,6 +196,82 @@ def linear_fp16_at(x, w, rows, cols) -> np.ndarray:
     return out
 
 
+# ---------------- O9: the 8-bit variant ----------------
+
+def quantize_w8(W: np.ndarray, G: int = 128):
+    """W fp32 [K,N] -> (qweight uint32 [K,N/4], scales fp16 [ceil(K/G),N], qzeros uint32 [ceil(K/G),N/4])."""
+    W = _c(W, np.float32)
+    K, N = W.shape
+    NG = (K + G - 1) // G
+    qw = np.empty((K, N // 4), np.uint32)
+    sc = np.empty((NG, N), np.uint16)
+    qz = np.empty((NG, N // 4), np.uint32)
+    rc = _load().oracle_quantize_w8(_p(W, _f32p), K, N, G, _p(qw, _u32p), _p(sc, _u16p), _p(qz, _u32p))
+    if rc != 0:
+        raise ValueError("oracle_quantize_w8: bad shape (need N % 4 == 0, K >= 1, G >= 1)")
+    return qw, sc.view(np.float16), qz
+
+
+def unpack_w8(packed: np.ndarray, N: int) -> np.ndarray:
+    """packed uint32 [R, N/4] -> codes uint8 [R, N]; byte j of word c is column 4c + j."""
+    packed = _c(packed, np.uint32)
+    R = packed.shape[0]
+    assert packed.shape[1] * 4 == N
+    out = np.empty((R, N), np.uint8)
+    _load().oracle_unpack_w8(_p(packed, _u32p), R, N, _p(out, _u8p))
+    return out
+
+
+def dequant_w8(qw, sc, qz, G: int = 128, dtype=np.float32) -> np.ndarray:
+    """D [K,N] = (q - z) * s as float32 (exact) or float16 (one RNE rounding of it)."""
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    K, N = qw.shape[0], qw.shape[1] * 4
+    if dtype == np.float32:
+        D = np.empty((K, N), np.float32)
+        _load().oracle_dequant_w8_f32(_p(qw, _u32p), _p(sc.view(np.uint16), _u16p), _p(qz, _u32p), K, N, G, _p(D, _f32p))
+        return D
+    if dtype == np.float16:
+        D = np.empty((K, N), np.uint16)
+        _load().oracle_dequant_w8_f16(_p(qw, _u32p), _p(sc.view(np.uint16), _u16p), _p(qz, _u32p), K, N, G, _p(D, _u16p))
+        return D.view(np.float16)
+    raise TypeError("dtype must be float32 or float16")
+
+
+def linear_w8a16(x, qw, sc, qz, G: int = 128) -> np.ndarray:
+    """y [M,N] float64 = x * D32, k ascending."""
+    x = _c(x, np.float16)
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    M, K = x.shape
+    N = qw.shape[1] * 4
+    assert qw.shape[0] == K
+    y = np.empty((M, N), np.float64)
+    _load().oracle_linear_w8a16(_p(x.view(np.uint16), _u16p), _p(qw, _u32p), _p(sc.view(np.uint16), _u16p),
+                                _p(qz, _u32p), M, K, N, G, _p(y, _f64p))
+    return y
+
+
+def linear_w8a16_at(x, qw, sc, qz, rows, cols, G: int = 128) -> np.ndarray:
+    """The same at sampled output positions: out[p] = y[rows[p], cols[p]]."""
+    x = _c(x, np.float16)
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    rows = np.ascontiguousarray(rows, np.int32)
+    cols = np.ascontiguousarray(cols, np.int32)
+    M, K = x.shape
+    N = qw.shape[1] * 4
+    assert rows.shape == cols.shape and rows.min() >= 0 and rows.max() < M and cols.min() >= 0 and cols.max() < N
+    out = np.empty(rows.shape, np.float64)
+    _load().oracle_linear_w8a16_at(_p(x.view(np.uint16), _u16p), _p(qw, _u32p), _p(sc.view(np.uint16), _u16p),
+                                   _p(qz, _u32p), K, N, G, _p(rows, _i32p), _p(cols, _i32p),
+                                   ctypes.c_int64(rows.size), _p(out, _f64p))
+    return out
+
+
 def error_metric(y, y_ref) -> dict:
     """O6.  y: what the GPU produced (fp16, any shape); y_ref float64, not rounded.
     err = max |y - y_ref| / max |y_ref| over the whole call."""
@@ -248,7 +328,7 @@ def glue_swiglu(gu: np.ndarray) -> np.ndarray:
 # layer owns one preallocated region of GPU memory, and a swap copies a variant to the START of
 # that region, so that the layer keeps its address.  A record is the layer's arrays one after the
 # other, linear by linear (qkv, o, gate_up, down); within a linear: the fp16 weight matrix, or
-# packed codes, then scales, then packed zeros.  Every array starts on a multiple of 256 bytes.
+# packed codes (4-bit: eight per word, 8-bit: four per word), then scales, then packed zeros.  Every array starts on a multiple of 256 bytes.
 
 RECORD_LINEARS = ("qkv", "o", "gate_up", "down")
 RECORD_ALIGN = 256
@@ -262,7 +342,8 @@ def _record_arrays(kind: str, K: int, N: int, G: int = 128):
     """(dtype, shape) of the arrays of one linear in a record, in order."""
     if kind == "fp16":
         return [(np.float16, (K, N))]
-    return [(np.uint32, (K, N // 8)), (np.float16, (K // G, N)), (np.uint32, (K // G, N // 8))]
+    per_word = {"w4": 8, "w8": 4}[kind]
+    return [(np.uint32, (K, N // per_word)), (np.float16, (K // G, N)), (np.uint32, (K // G, N // per_word))]
 
 
 def layer_record_bytes(kind: str, hidden: int, inter: int) -> int:

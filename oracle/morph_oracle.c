@@ -276,6 +276,126 @@ void oracle_linear_fp16_at(const uint16_t *x, const uint16_t *w,
     }
 }
 
+/* ---------- W8: the 8-bit weight-only variant (Section 4.3 lists FP16, INT8, INT4 and INT3
+ * variants of every layer; Appendix C: FP16, W8, W4 are preloaded) ----------
+ * Same scheme as the 4-bit one with 255 steps instead of 15: asymmetric uint8 codes, one fp16
+ * scale and one uint8 zero point per (group of G consecutive k, column n), FOUR codes per 32-bit
+ * word along n: bits [8j+7:8j] of word c = column 4c + j.
+ *   qweight [K, N/4] uint32, scales [ceil(K/G), N] fp16, qzeros [ceil(K/G), N/4] uint32.
+ * (q - z) has at most 9 significant bits and the scale 11, so (q - z) * s is exact in fp32.
+ */
+int oracle_quantize_w8(const float *W, int K, int N, int G,
+                       uint32_t *qweight, uint16_t *scales, uint32_t *qzeros)
+{
+    if (K < 1 || N < 4 || (N % 4) || G < 1) return -1;
+    int NG = (K + G - 1) / G;
+    int NW = N / 4;
+    memset(qweight, 0, (size_t)K * NW * sizeof(uint32_t));
+    memset(qzeros, 0, (size_t)NG * NW * sizeof(uint32_t));
+    for (int g = 0; g < NG; g++) {
+        int k0 = g * G, k1 = (k0 + G < K) ? k0 + G : K;
+        for (int n = 0; n < N; n++) {
+            float lo = 0.0f, hi = 0.0f;                   /* range widened to contain 0 */
+            for (int k = k0; k < k1; k++) {
+                float w = W[(size_t)k * N + n];
+                if (w < lo) lo = w;
+                if (w > hi) hi = w;
+            }
+            float    s32 = (hi - lo) / 255.0f;            /* 255 steps cover the range */
+            uint16_t s   = f2h(s32);
+            if (h2f(s) < s32) s = (uint16_t)(s + 1);      /* rounded UP to fp16 */
+            if (s < 0x0400u) s = 0x0400u;                 /* floor at 2^-14 */
+            if (s > 0x7BFFu) s = 0x7BFFu;
+            float sf = h2f(s);
+            int z = (int)rintf(-lo / sf);
+            if (z < 0) z = 0;
+            if (z > 255) z = 255;
+            for (int k = k0; k < k1; k++) {
+                int q = (int)rintf(W[(size_t)k * N + n] / sf) + z;
+                if (q < 0) q = 0;
+                if (q > 255) q = 255;
+                qweight[(size_t)k * NW + (n >> 2)] |= (uint32_t)q << (8 * (n & 3));
+            }
+            qzeros[(size_t)g * NW + (n >> 2)] |= (uint32_t)z << (8 * (n & 3));
+            scales[(size_t)g * N + n] = s;
+        }
+    }
+    return 0;
+}
+
+/* packed [R, N/4] uint32 -> codes [R, N] uint8 */
+void oracle_unpack_w8(const uint32_t *packed, int R, int N, uint8_t *codes)
+{
+    int NW = N / 4;
+    for (int r = 0; r < R; r++)
+        for (int n = 0; n < N; n++)
+            codes[(size_t)r * N + n] =
+                (uint8_t)((packed[(size_t)r * NW + (n >> 2)] >> (8 * (n & 3))) & 0xFFu);
+}
+
+static inline float dq8(const uint32_t *qweight, const uint16_t *scales,
+                        const uint32_t *qzeros, int N, int G, int k, int n)
+{
+    int NW = N / 4, g = k / G, sh = 8 * (n & 3);
+    int q = (int)((qweight[(size_t)k * NW + (n >> 2)] >> sh) & 0xFFu);
+    int z = (int)((qzeros[(size_t)g * NW + (n >> 2)] >> sh) & 0xFFu);
+    return (float)(q - z) * h2f(scales[(size_t)g * N + n]);
+}
+
+void oracle_dequant_w8_f32(const uint32_t *qweight, const uint16_t *scales,
+                           const uint32_t *qzeros, int K, int N, int G, float *D)
+{
+    for (int k = 0; k < K; k++)
+        for (int n = 0; n < N; n++)
+            D[(size_t)k * N + n] = dq8(qweight, scales, qzeros, N, G, k, n);
+}
+
+void oracle_dequant_w8_f16(const uint32_t *qweight, const uint16_t *scales,
+                           const uint32_t *qzeros, int K, int N, int G, uint16_t *D)
+{
+    for (int k = 0; k < K; k++)
+        for (int n = 0; n < N; n++)
+            D[(size_t)k * N + n] = f2h(dq8(qweight, scales, qzeros, N, G, k, n));
+}
+
+/* y [M,N] fp64 = sum over ascending k of double(x[m,k]) * double(D32[k,n]) */
+void oracle_linear_w8a16(const uint16_t *x, const uint32_t *qweight,
+                         const uint16_t *scales, const uint32_t *qzeros,
+                         int M, int K, int N, int G, double *y)
+{
+    const int CB = 256;
+    int nblk = (N + CB - 1) / CB;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < nblk; b++) {
+        int n0 = b * CB, n1 = (n0 + CB < N) ? n0 + CB : N;
+        for (int m = 0; m < M; m++) {
+            double *ym = y + (size_t)m * N;
+            for (int n = n0; n < n1; n++) ym[n] = 0.0;
+            for (int k = 0; k < K; k++) {
+                double xv = (double)h2f(x[(size_t)m * K + k]);
+                for (int n = n0; n < n1; n++)
+                    ym[n] += xv * (double)dq8(qweight, scales, qzeros, N, G, k, n);
+            }
+        }
+    }
+}
+
+/* sampled outputs: y[i] for the pairs (rows[i], cols[i]) */
+void oracle_linear_w8a16_at(const uint16_t *x, const uint32_t *qweight,
+                            const uint16_t *scales, const uint32_t *qzeros,
+                            int K, int N, int G, const int32_t *rows, const int32_t *cols,
+                            int64_t count, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; i++) {
+        int m = rows[i], n = cols[i];
+        double acc = 0.0;
+        for (int k = 0; k < K; k++)
+            acc += (double)h2f(x[(size_t)m * K + k]) * (double)dq8(qweight, scales, qzeros, N, G, k, n);
+        y[i] = acc;
+    }
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -411,6 +411,9 @@ def test_p9_record_sizes_match_paper_and_arrays(oracle):
     # which the paper quotes as about 0.4 GB (FP16) and about 0.1 GB (INT4)
     assert oracle.layer_record_bytes("fp16", 4096, 11008) == 404_750_336
     assert oracle.layer_record_bytes("w4", 4096, 11008) == 105_140_224
+    # the 8-bit record: a byte per weight plus the fp16 scales plus a byte of zero per group and column
+    n_w = 4096 * 12288 + 4096 * 4096 + 4096 * 22016 + 11008 * 4096
+    assert oracle.layer_record_bytes("w8", 4096, 11008) == n_w + n_w // 128 * 2 + n_w // 128
     # a small layer whose arrays are NOT multiples of 256 bytes: each array is padded on its own
     h, i = 128, 128
     raw = 0
@@ -464,3 +467,110 @@ def test_p9_swap_in_place_keeps_the_address_and_the_rest(oracle):
     assert np.array_equal(oracle.swap_in_place(s2, r16), r16)
     with pytest.raises(AssertionError):
         oracle.swap_in_place(np.zeros(r4.size, np.uint8), r16)
+
+
+# ---------- P10 the 8-bit variant (Section 4.3 lists INT8 next to INT4; Appendix C: W8) ----------
+
+def pack_bytes(codes):
+    """rows of ints in [0,255], len % 4 == 0 -> rows of python ints; column 4c + j in bits [8j+7 : 8j] of word c."""
+    out = []
+    for row in codes:
+        words = []
+        for c in range(len(row) // 4):
+            w = 0
+            for j in range(4):
+                assert 0 <= row[4 * c + j] <= 255
+                w |= row[4 * c + j] << (8 * j)
+            words.append(w)
+        out.append(words)
+    return out
+
+
+def test_p10_unpack_byte_order(oracle):
+    rng = np.random.default_rng(5)
+    codes = rng.integers(0, 256, (3, 16))
+    packed = np.array(pack_bytes(codes.tolist()), np.uint32)
+    assert np.array_equal(oracle.unpack_w8(packed, 16), codes.astype(np.uint8))
+    one = np.zeros((1, 8), np.int64); one[0, 5] = 0xAB
+    assert pack_bytes(one.tolist())[0] == [0, 0xAB << 8]
+    assert oracle.unpack_w8(np.array([[0, 0xAB00]], np.uint32), 8)[0, 5] == 0xAB
+
+
+@pytest.mark.parametrize("G,K", [(128, 256), (32, 80), (8, 20)])
+def test_p10_round_trip_half_step(oracle, G, K):
+    rng = np.random.default_rng(300 + G + K)
+    N = 24
+    for name, W in _distributions(rng, K, N):
+        qw, sc, qz = oracle.quantize_w8(W, G)
+        s = sc.astype(np.float64)
+        assert (s >= 2.0 ** -14).all(), name
+        D = oracle.dequant_w8(qw, sc, qz, G).astype(np.float64)
+        step = np.repeat(s, G, axis=0)[:K]
+        assert (np.abs(W.astype(np.float64) - D) <= 0.5 * step * (1 + 1e-5)).all(), name
+        for g in range(s.shape[0]):                       # scale = range / 255 rounded UP to fp16
+            blk = W[g * G:(g + 1) * G].astype(np.float64)
+            rngw = np.maximum(blk.max(0), 0) - np.minimum(blk.min(0), 0)
+            floor = np.maximum(rngw / 255, 2.0 ** -14)
+            assert (s[g] >= floor * (1 - 1e-7)).all(), name
+            assert (s[g] <= floor * (1 + 2.0 ** -10) + 1e-30).all(), name
+    # sixteen times finer than the 4-bit grid on the same weights
+    W = (rng.standard_normal((256, 24)) * 0.02).astype(np.float32)
+    e8 = np.abs(W - oracle.dequant_w8(*oracle.quantize_w8(W))).max()
+    e4 = np.abs(W - oracle.dequant_w4(*oracle.quantize_w4(W))).max()
+    assert e8 < e4 / 10
+
+
+def test_p10_on_grid_exact(oracle):
+    """Weights that lie on a grid (q - z) * s with every code present come back bit for bit, codes included."""
+    rng = np.random.default_rng(7)
+    G, K, N = 128, 256, 16
+    s = np.array([2.0 ** -6, 3 * 2.0 ** -9, 0.0123, 1.5] * 4, np.float16)
+    z = rng.integers(0, 256, N)
+    q = rng.integers(0, 256, (K, N))
+    for g in range(K // G):
+        q[g * G + 0, :] = 0
+        q[g * G + 1, :] = 255                              # the range is exactly 255 steps
+        q[g * G + 2, :] = z                                # and contains 0
+    W = ((q - z[None, :]).astype(np.float64) * s.astype(np.float64)[None, :]).astype(np.float32)
+    qw, sc, qz = oracle.quantize_w8(W, G)
+    assert np.array_equal(sc, np.broadcast_to(s, (K // G, N)))
+    assert np.array_equal(oracle.unpack_w8(qz, N), np.broadcast_to(z, (K // G, N)).astype(np.uint8))
+    assert np.array_equal(oracle.unpack_w8(qw, N), q.astype(np.uint8))
+    assert np.array_equal(oracle.dequant_w8(qw, sc, qz, G).view(np.uint32), W.view(np.uint32))
+
+
+@pytest.mark.parametrize("K,G,M", [(8, 8, 1), (24, 8, 2), (64, 32, 3)])
+def test_p10_brute_force_fractions(oracle, K, G, M):
+    """Every output as an exact rational from hand-packed codes; the oracle's fp64 sum agrees to rounding."""
+    rng = np.random.default_rng(K * 7 + M)
+    N = 8
+    q = rng.integers(0, 256, (K, N))
+    z = rng.integers(0, 256, (K // G, N))
+    sc = rng.uniform(0.001, 0.02, (K // G, N)).astype(np.float16)
+    x = rng.standard_normal((M, K)).astype(np.float16)
+    qw = np.array(pack_bytes(q.tolist()), np.uint32)
+    qz = np.array(pack_bytes(z.tolist()), np.uint32)
+    y = oracle.linear_w8a16(x, qw, sc, qz, G)
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(0)
+            for k in range(K):
+                acc += half_to_fraction(x[m, k]) * (int(q[k, n]) - int(z[k // G, n])) * half_to_fraction(sc[k // G, n])
+            assert abs(Fraction(float(y[m, n])) - acc) <= abs(acc) * Fraction(1, 2 ** 40) + Fraction(1, 2 ** 60)
+    rows = np.array([0, M - 1]); cols = np.array([N - 1, 0])
+    assert np.array_equal(oracle.linear_w8a16_at(x, qw, sc, qz, rows, cols, G), y[rows, cols])
+
+
+def test_p10_identity_and_numpy_matmul(oracle):
+    rng = np.random.default_rng(11)
+    K, N, M = 256, 40, 5
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    qw, sc, qz = oracle.quantize_w8(W)
+    D = oracle.dequant_w8(qw, sc, qz)
+    eye = np.eye(K, dtype=np.float16)
+    assert np.array_equal(oracle.linear_w8a16(eye, qw, sc, qz), D.astype(np.float64))
+    x = rng.standard_normal((M, K)).astype(np.float16)
+    ref = x.astype(np.float64) @ D.astype(np.float64)
+    assert np.allclose(oracle.linear_w8a16(x, qw, sc, qz), ref, rtol=1e-12, atol=1e-12)
+    # fp16 form: one rounding of the exact value
+    assert np.array_equal(oracle.dequant_w8(qw, sc, qz, 128, np.float16), D.astype(np.float16))
