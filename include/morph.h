@@ -90,6 +90,19 @@ int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* sca
 int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_t* qzeros,
                         void* out, int out_dtype, int K, int N, int group_size, void* stream);
 
+/* ---- the 8-bit weight-only variant (Section 4.3 lists INT8 next to INT4 among the variants of
+ * a layer; Appendix C: FP16, W8 and W4 are preloaded) ----
+ * The same scheme with 255 steps: uint8 codes and zero points, FOUR per 32-bit word along N
+ * (bits [8j+7:8j] of word c = column 4c + j), group 128 along K, fp16 scale:
+ *   qweight int32 [K, N/4], scales fp16 [K/128, N], qzeros int32 [K/128, N/4];
+ *   s = (hi - lo) / 255 rounded UP to fp16, at least 2^-14;  z = clamp(rint(-lo / s), 0, 255);
+ *   q = clamp(rint(w / s) + z, 0, 255);  dequantized value (q - z) * s, exact in fp32.
+ * Arguments, alignment, errors and exactness as for the 4-bit calls (N % 8 == 0 here too). */
+int morph_quantize_layer_w8(const void* w, int w_dtype, int32_t* qweight, void* scales,
+                            int32_t* qzeros, int K, int N, int group_size, void* stream);
+int morph_dequantize_w8(const int32_t* qweight, const void* scales, const int32_t* qzeros,
+                        void* out, int out_dtype, int K, int N, int group_size, void* stream);
+
 /* Bytes of workspace a linear call of this kind and shape needs (0 = none).  Host only. */
 size_t morph_workspace_bytes(int kind, int M, int K, int N);
 

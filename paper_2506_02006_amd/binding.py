@@ -27,6 +27,7 @@ EXPORTS = [
     "morph_set_tuning", "morph_copy", "morph_status_string",
     "morph_probe_out_bytes", "morph_probe_read", "morph_probe_mfma",
     "morph_layer_record_bytes", "morph_layer_record_desc", "morph_layer_swap_async",
+    "morph_quantize_layer_w8", "morph_dequantize_w8",
 ]
 
 
@@ -61,6 +62,8 @@ def lib() -> ctypes.CDLL:
     L.morph_linear_w4a16.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.morph_quantize_layer.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w4.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
+    L.morph_quantize_layer_w8.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
+    L.morph_dequantize_w8.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_workspace_bytes.argtypes = [i, i, i, i]
     L.morph_workspace_bytes.restype = sz
     L.morph_workspace_init.argtypes = [vp, sz, vp]
@@ -175,6 +178,31 @@ def quantize_layer(w: torch.Tensor, group_size: int = GROUP):
     _check(lib().morph_quantize_layer(_dev(w, w.dtype, "w"), dt, qw.data_ptr(), sc.data_ptr(), qz.data_ptr(),
                                       K, N, group_size, _stream()), "morph_quantize_layer")
     return qw, sc, qz
+
+
+def quantize_layer_w8(w: torch.Tensor, group_size: int = GROUP):
+    """w [K,N] float32 or float16 on the GPU -> (qweight int32 [K,N/4], scales fp16 [K/128,N], qzeros int32 [K/128,N/4])."""
+    K, N = w.shape
+    if w.dtype not in (torch.float32, torch.float16):
+        raise TypeError("w must be float32 or float16")
+    dt = DTYPE_F32 if w.dtype == torch.float32 else DTYPE_F16
+    qw = torch.empty((K, N // 4), dtype=torch.int32, device=w.device)
+    sc = torch.empty((K // GROUP, N), dtype=torch.float16, device=w.device)
+    qz = torch.empty((K // GROUP, N // 4), dtype=torch.int32, device=w.device)
+    _check(lib().morph_quantize_layer_w8(_dev(w, w.dtype, "w"), dt, qw.data_ptr(), sc.data_ptr(), qz.data_ptr(),
+                                         K, N, group_size, _stream()), "morph_quantize_layer_w8")
+    return qw, sc, qz
+
+
+def dequantize_w8(qweight, scales, qzeros, dtype=torch.float32, group_size: int = GROUP) -> torch.Tensor:
+    K = qweight.shape[0]
+    N = scales.shape[1]
+    out = torch.empty((K, N), dtype=dtype, device=qweight.device)
+    dt = DTYPE_F32 if dtype == torch.float32 else DTYPE_F16
+    _check(lib().morph_dequantize_w8(_dev(qweight, torch.int32, "qweight"), _dev(scales, torch.float16, "scales"),
+                                     _dev(qzeros, torch.int32, "qzeros"), _dev(out, dtype, "out"), dt, K, N,
+                                     group_size, _stream()), "morph_dequantize_w8")
+    return out
 
 
 def dequantize_w4(qweight, scales, qzeros, dtype=torch.float32, group_size: int = GROUP) -> torch.Tensor:

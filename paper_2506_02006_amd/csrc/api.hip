@@ -151,8 +151,9 @@ int morph_linear_w4a16(const void* x, const int32_t* qweight, const void* scales
                       (hipStream_t)stream);
 }
 
-int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
-                         int K, int N, int group_size, void* stream)
+namespace {
+int quantize_any(int bits, const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
+                 int K, int N, int group_size, void* stream)
 {
     if (!w || !qweight || !scales || !qzeros) return MORPH_ERR_NULL;
     if (group_size != MORPH_GROUP_SIZE) return MORPH_ERR_SHAPE;
@@ -160,13 +161,13 @@ int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* sca
     if (int rc = check_shape(1, K, N)) return rc;
     if (!aligned16(w) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros)) return MORPH_ERR_ALIGN;
     if (K / MORPH_GROUP_SIZE > 65535) return MORPH_ERR_UNSUPPORTED;
-    hipError_t e = launch_quantize_w4(w, w_dtype == MORPH_DTYPE_F16, reinterpret_cast<uint32_t*>(qweight), scales,
-                                      reinterpret_cast<uint32_t*>(qzeros), K, N, (hipStream_t)stream);
+    hipError_t e = launch_quantize(bits, w, w_dtype == MORPH_DTYPE_F16, reinterpret_cast<uint32_t*>(qweight), scales,
+                                   reinterpret_cast<uint32_t*>(qzeros), K, N, (hipStream_t)stream);
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
 
-int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_t* qzeros, void* out,
-                        int out_dtype, int K, int N, int group_size, void* stream)
+int dequantize_any(int bits, const int32_t* qweight, const void* scales, const int32_t* qzeros, void* out,
+                   int out_dtype, int K, int N, int group_size, void* stream)
 {
     if (!qweight || !scales || !qzeros || !out) return MORPH_ERR_NULL;
     if (group_size != MORPH_GROUP_SIZE) return MORPH_ERR_SHAPE;
@@ -174,10 +175,35 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
     if (int rc = check_shape(1, K, N)) return rc;
     if (!aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(out)) return MORPH_ERR_ALIGN;
     if (K > 65535) return MORPH_ERR_UNSUPPORTED;
-    hipError_t e = launch_dequantize_w4(reinterpret_cast<const uint32_t*>(qweight), scales,
-                                        reinterpret_cast<const uint32_t*>(qzeros), out,
-                                        out_dtype == MORPH_DTYPE_F16, K, N, (hipStream_t)stream);
+    hipError_t e = launch_dequantize(bits, reinterpret_cast<const uint32_t*>(qweight), scales,
+                                     reinterpret_cast<const uint32_t*>(qzeros), out,
+                                     out_dtype == MORPH_DTYPE_F16, K, N, (hipStream_t)stream);
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+}  // namespace
+
+int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
+                         int K, int N, int group_size, void* stream)
+{
+    return quantize_any(4, w, w_dtype, qweight, scales, qzeros, K, N, group_size, stream);
+}
+
+int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_t* qzeros, void* out,
+                        int out_dtype, int K, int N, int group_size, void* stream)
+{
+    return dequantize_any(4, qweight, scales, qzeros, out, out_dtype, K, N, group_size, stream);
+}
+
+int morph_quantize_layer_w8(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
+                            int K, int N, int group_size, void* stream)
+{
+    return quantize_any(8, w, w_dtype, qweight, scales, qzeros, K, N, group_size, stream);
+}
+
+int morph_dequantize_w8(const int32_t* qweight, const void* scales, const int32_t* qzeros, void* out,
+                        int out_dtype, int K, int N, int group_size, void* stream)
+{
+    return dequantize_any(8, qweight, scales, qzeros, out, out_dtype, K, N, group_size, stream);
 }
 
 size_t morph_workspace_bytes(int kind, int M, int K, int N)

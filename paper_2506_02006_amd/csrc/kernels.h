@@ -8,10 +8,11 @@
 namespace morph {
 
 // ---- quantizer / verification dequantizer (quant.hip) ----
-hipError_t launch_quantize_w4(const void* w, int w_is_f16, uint32_t* qweight, void* scales,
-                              uint32_t* qzeros, int K, int N, hipStream_t st);
-hipError_t launch_dequantize_w4(const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
-                                void* out, int out_is_f16, int K, int N, hipStream_t st);
+// bits = 4 or 8
+hipError_t launch_quantize(int bits, const void* w, int w_is_f16, uint32_t* qweight, void* scales,
+                           uint32_t* qzeros, int K, int N, hipStream_t st);
+hipError_t launch_dequantize(int bits, const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
+                             void* out, int out_is_f16, int K, int N, hipStream_t st);
 
 // ---- decode, M <= 64 (decode.hip) ----
 struct DecodeArgs {

@@ -1,4 +1,4 @@
-// Quantizer (fp32/fp16 weights -> 4-bit layer record) and the verification dequantizer.
+// Quantizer (fp32/fp16 weights -> 4-bit or 8-bit layer record) and the verification dequantizer.
 // Format and arithmetic: see include/morph.h.  Both are exact procedures with one right answer;
 // neither sits on the per-token path.
 #include "dev_common.h"
@@ -12,18 +12,21 @@ namespace morph {
 constexpr int kQC = 64;                                   // columns per workgroup (34 KB of LDS: four workgroups per compute unit)
 constexpr int kQT = 256 / kQC;                            // threads per column in the range pass
 constexpr int kQP = kQC + 4;                              // LDS pitch in floats (keeps 16-byte alignment, skews the banks)
-template <typename WT>
-__global__ __launch_bounds__(256) void quantize_w4_kernel(const WT* __restrict__ w,
-                                                          uint32_t* __restrict__ qweight,
-                                                          half_t* __restrict__ scales,
-                                                          uint32_t* __restrict__ qzeros, int K, int N)
+// BITS = 4: 15 steps, eight codes per word; BITS = 8: 255 steps, four codes per word.
+template <typename WT, int BITS>
+__global__ __launch_bounds__(256) void quantize_kernel(const WT* __restrict__ w,
+                                                       uint32_t* __restrict__ qweight,
+                                                       half_t* __restrict__ scales,
+                                                       uint32_t* __restrict__ qzeros, int K, int N)
 {
+    constexpr int kLevels = (1 << BITS) - 1;                // largest code
+    constexpr int CPW = 32 / BITS;                          // codes per word
     __shared__ __align__(16) float tile[kGroup * kQP];
     __shared__ float part_lo[kQT][kQC], part_hi[kQT][kQC];
     __shared__ float sfl[kQC];
     __shared__ int   zl[kQC];
     const int tid = threadIdx.x;
-    const int NW = N >> 3;
+    const int NW = N / CPW;
     const int n0 = blockIdx.x * kQC;                        // first column
     const int g  = blockIdx.y;                              // group
     const WT* base = w + (size_t)g * kGroup * N + n0;
@@ -83,7 +86,7 @@ __global__ __launch_bounds__(256) void quantize_w4_kernel(const WT* __restrict__
             lo = part_lo[h][tid] < lo ? part_lo[h][tid] : lo;
             hi = part_hi[h][tid] > hi ? part_hi[h][tid] : hi;
         }
-        const float s32 = __fdiv_rn(hi - lo, 15.0f);
+        const float s32 = __fdiv_rn(hi - lo, (float)kLevels);
         half_t   s    = (half_t)s32;                        // round to nearest even
         uint16_t bits = bit_cast<uint16_t>(s);
         if ((float)s < s32) bits = (uint16_t)(bits + 1);    // round the step size up
@@ -92,22 +95,22 @@ __global__ __launch_bounds__(256) void quantize_w4_kernel(const WT* __restrict__
         s = bit_cast<half_t>(bits);
         const float sf = (float)s;
         int zz = (int)rintf(__fdiv_rn(-lo, sf));
-        zz     = zz < 0 ? 0 : (zz > 15 ? 15 : zz);
+        zz     = zz < 0 ? 0 : (zz > kLevels ? kLevels : zz);
         sfl[tid] = sf;
         zl[tid]  = zz;
         if (n0 + tid < N) scales[(size_t)g * N + n0 + tid] = s;
     }
     __syncthreads();
-    if (tid < kQC / 8 && n0 + 8 * tid < N) {
+    if (tid < kQC / CPW && n0 + CPW * tid < N) {
         uint32_t zword = 0;
 #pragma unroll
-        for (int j = 0; j < 8; j++) zword |= (uint32_t)zl[8 * tid + j] << (4 * j);
-        qzeros[(size_t)g * NW + (n0 >> 3) + tid] = zword;
+        for (int j = 0; j < CPW; j++) zword |= (uint32_t)zl[CPW * tid + j] << (BITS * j);
+        qzeros[(size_t)g * NW + n0 / CPW + tid] = zword;
     }
 
-    // ---- codes: a thread keeps one word column (its 8 scales and zero points) and walks the rows ----
+    // ---- codes: a thread keeps 8 columns (their scales and zero points) and walks the rows ----
     {
-        constexpr int WPR = kQC / 8;                        // words per row of the tile
+        constexpr int WPR = kQC / 8;                        // 8-column units per row of the tile
         const int cw = tid & (WPR - 1);
         float sf[8];
         int   z[8];
@@ -120,39 +123,43 @@ __global__ __launch_bounds__(256) void quantize_w4_kernel(const WT* __restrict__
                 const f32x4 a = *reinterpret_cast<const f32x4*>(tile + row * kQP + 8 * cw);
                 const f32x4 b = *reinterpret_cast<const f32x4*>(tile + row * kQP + 8 * cw + 4);
                 const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-                uint32_t word = 0;
+                uint32_t word[8 / CPW] = {};
 #pragma unroll
                 for (int j = 0; j < 8; j++) {
                     int q = (int)rintf(__fdiv_rn(v[j], sf[j])) + z[j];
-                    q     = q < 0 ? 0 : (q > 15 ? 15 : q);
-                    word |= (uint32_t)q << (4 * j);
+                    q     = q < 0 ? 0 : (q > kLevels ? kLevels : q);
+                    word[j / CPW] |= (uint32_t)q << (BITS * (j % CPW));
                 }
-                qweight[((size_t)g * kGroup + row) * NW + (n0 >> 3) + cw] = word;
+                uint32_t* dst = qweight + ((size_t)g * kGroup + row) * NW + (size_t)(n0 + 8 * cw) / CPW;
+                if constexpr (BITS == 4) dst[0] = word[0];
+                else *reinterpret_cast<u32x2*>(dst) = u32x2{word[0], word[1]};
             }
         }
     }
 }
 
-// One thread per packed word: 8 outputs of one row.
-template <typename OT>
-__global__ __launch_bounds__(256) void dequantize_w4_kernel(const uint32_t* __restrict__ qweight,
-                                                            const half_t* __restrict__ scales,
-                                                            const uint32_t* __restrict__ qzeros,
-                                                            OT* __restrict__ out, int K, int N)
+// One thread per 8 outputs of one row (one packed word of 4-bit codes, two of 8-bit codes).
+template <typename OT, int BITS>
+__global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restrict__ qweight,
+                                                         const half_t* __restrict__ scales,
+                                                         const uint32_t* __restrict__ qzeros,
+                                                         OT* __restrict__ out, int K, int N)
 {
-    const int NW = N >> 3;
-    const int c  = blockIdx.x * blockDim.x + threadIdx.x;
+    constexpr int CPW = 32 / BITS;
+    constexpr uint32_t kMask = (1u << BITS) - 1u;
+    const int NW = N / CPW;
+    const int c  = blockIdx.x * blockDim.x + threadIdx.x;  // 8-column unit
     const int k  = blockIdx.y;
-    if (c >= NW) return;
+    if (c >= (N >> 3)) return;
     const int      g  = k / kGroup;
-    const uint32_t qw = qweight[(size_t)k * NW + c];
-    const uint32_t zw = qzeros[(size_t)g * NW + c];
+    const uint32_t* qp = qweight + (size_t)k * NW + (size_t)c * (8 / CPW);
+    const uint32_t* zp = qzeros + (size_t)g * NW + (size_t)c * (8 / CPW);
     const half8_t  s  = *reinterpret_cast<const half8_t*>(scales + (size_t)g * N + (size_t)c * 8);
     float d[8];
 #pragma unroll
     for (int j = 0; j < 8; j++) {
-        int q = (int)((qw >> (4 * j)) & 15u), z = (int)((zw >> (4 * j)) & 15u);
-        d[j]  = (float)(q - z) * (float)s[j];               // exact: 4 x 11 significant bits
+        const int q = (int)((qp[j / CPW] >> (BITS * (j % CPW))) & kMask), z = (int)((zp[j / CPW] >> (BITS * (j % CPW))) & kMask);
+        d[j]  = (float)(q - z) * (float)s[j];               // exact: at most 9 x 11 significant bits
     }
     OT* o = out + (size_t)k * N + (size_t)c * 8;
     if constexpr (sizeof(OT) == 4) {
@@ -167,29 +174,33 @@ __global__ __launch_bounds__(256) void dequantize_w4_kernel(const uint32_t* __re
     }
 }
 
-hipError_t launch_quantize_w4(const void* w, int w_is_f16, uint32_t* qweight, void* scales,
-                              uint32_t* qzeros, int K, int N, hipStream_t st)
+hipError_t launch_quantize(int bits, const void* w, int w_is_f16, uint32_t* qweight, void* scales,
+                           uint32_t* qzeros, int K, int N, hipStream_t st)
 {
     dim3 grid((N + kQC - 1) / kQC, K / kGroup), block(256);
-    if (w_is_f16)
-        hipLaunchKernelGGL(quantize_w4_kernel<half_t>, grid, block, 0, st, (const half_t*)w, qweight,
-                           (half_t*)scales, qzeros, K, N);
-    else
-        hipLaunchKernelGGL(quantize_w4_kernel<float>, grid, block, 0, st, (const float*)w, qweight,
-                           (half_t*)scales, qzeros, K, N);
+    half_t* sc = (half_t*)scales;
+    if (bits == 4) {
+        if (w_is_f16) hipLaunchKernelGGL((quantize_kernel<half_t, 4>), grid, block, 0, st, (const half_t*)w, qweight, sc, qzeros, K, N);
+        else          hipLaunchKernelGGL((quantize_kernel<float, 4>), grid, block, 0, st, (const float*)w, qweight, sc, qzeros, K, N);
+    } else {
+        if (w_is_f16) hipLaunchKernelGGL((quantize_kernel<half_t, 8>), grid, block, 0, st, (const half_t*)w, qweight, sc, qzeros, K, N);
+        else          hipLaunchKernelGGL((quantize_kernel<float, 8>), grid, block, 0, st, (const float*)w, qweight, sc, qzeros, K, N);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_dequantize_w4(const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
-                                void* out, int out_is_f16, int K, int N, hipStream_t st)
+hipError_t launch_dequantize(int bits, const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
+                             void* out, int out_is_f16, int K, int N, hipStream_t st)
 {
     dim3 grid((N / 8 + 255) / 256, K), block(256);
-    if (out_is_f16)
-        hipLaunchKernelGGL(dequantize_w4_kernel<half_t>, grid, block, 0, st, qweight,
-                           (const half_t*)scales, qzeros, (half_t*)out, K, N);
-    else
-        hipLaunchKernelGGL(dequantize_w4_kernel<float>, grid, block, 0, st, qweight,
-                           (const half_t*)scales, qzeros, (float*)out, K, N);
+    const half_t* sc = (const half_t*)scales;
+    if (bits == 4) {
+        if (out_is_f16) hipLaunchKernelGGL((dequantize_kernel<half_t, 4>), grid, block, 0, st, qweight, sc, qzeros, (half_t*)out, K, N);
+        else            hipLaunchKernelGGL((dequantize_kernel<float, 4>), grid, block, 0, st, qweight, sc, qzeros, (float*)out, K, N);
+    } else {
+        if (out_is_f16) hipLaunchKernelGGL((dequantize_kernel<half_t, 8>), grid, block, 0, st, qweight, sc, qzeros, (half_t*)out, K, N);
+        else            hipLaunchKernelGGL((dequantize_kernel<float, 8>), grid, block, 0, st, qweight, sc, qzeros, (float*)out, K, N);
+    }
     return hipGetLastError();
 }
 
