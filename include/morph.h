@@ -48,7 +48,7 @@ typedef enum {
     MORPH_ERR_DEVICE = 6       /* the HIP runtime reported an error at launch                    */
 } morph_status;
 
-enum { MORPH_KIND_FP16 = 0, MORPH_KIND_W4A16 = 1 };
+enum { MORPH_KIND_FP16 = 0, MORPH_KIND_W4A16 = 1, MORPH_KIND_W8A16 = 2 };
 enum { MORPH_DTYPE_F32 = 0, MORPH_DTYPE_F16 = 1 };
 enum { MORPH_GROUP_SIZE = 128 };
 
@@ -97,7 +97,14 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
  *   qweight int32 [K, N/4], scales fp16 [K/128, N], qzeros int32 [K/128, N/4];
  *   s = (hi - lo) / 255 rounded UP to fp16, at least 2^-14;  z = clamp(rint(-lo / s), 0, 255);
  *   q = clamp(rint(w / s) + z, 0, 255);  dequantized value (q - z) * s, exact in fp32.
- * Arguments, alignment, errors and exactness as for the 4-bit calls (N % 8 == 0 here too). */
+ * Arguments, alignment, errors and exactness as for the 4-bit calls (N % 8 == 0 here too).
+ * morph_linear_w8a16: y = x * dequant(W8), kind MORPH_KIND_W8A16 for morph_workspace_bytes(), the
+ * layer descriptors of morph_stack_forward() and the layer records; the codes enter the matrix
+ * cores as they are (decode) or are dequantized into the LDS tile (prefill).  The persistent stack
+ * launch does not take 8-bit layers (UNSUPPORTED). */
+int morph_linear_w8a16(const void* x, const int32_t* qweight, const void* scales,
+                       const int32_t* qzeros, void* y, int M, int K, int N, int group_size,
+                       void* workspace, size_t workspace_bytes, void* stream);
 int morph_quantize_layer_w8(const void* w, int w_dtype, int32_t* qweight, void* scales,
                             int32_t* qzeros, int K, int N, int group_size, void* stream);
 int morph_dequantize_w8(const int32_t* qweight, const void* scales, const int32_t* qzeros,

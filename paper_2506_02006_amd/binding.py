@@ -11,7 +11,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmorph.so")
 
-KIND_FP16, KIND_W4A16 = 0, 1
+KIND_FP16, KIND_W4A16, KIND_W8A16 = 0, 1, 2
 DTYPE_F32, DTYPE_F16 = 0, 1
 GROUP = 128
 GLUE_QKV, GLUE_RESIDUAL, GLUE_SWIGLU, GLUE_RMS = 0, 1, 2, 3
@@ -27,7 +27,7 @@ EXPORTS = [
     "morph_set_tuning", "morph_copy", "morph_status_string",
     "morph_probe_out_bytes", "morph_probe_read", "morph_probe_mfma",
     "morph_layer_record_bytes", "morph_layer_record_desc", "morph_layer_swap_async",
-    "morph_quantize_layer_w8", "morph_dequantize_w8",
+    "morph_quantize_layer_w8", "morph_dequantize_w8", "morph_linear_w8a16",
 ]
 
 
@@ -62,6 +62,7 @@ def lib() -> ctypes.CDLL:
     L.morph_linear_w4a16.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.morph_quantize_layer.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w4.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
+    L.morph_linear_w8a16.argtypes = L.morph_linear_w4a16.argtypes
     L.morph_quantize_layer_w8.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w8.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_workspace_bytes.argtypes = [i, i, i, i]
@@ -160,6 +161,19 @@ def linear_w4a16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int 
                                     _dev(scales, torch.float16, "scales"), _dev(qzeros, torch.int32, "qzeros"),
                                     _dev(y, torch.float16, "y"), M, K, N, group_size, wp, wb, _stream()),
            "morph_linear_w4a16")
+    return y
+
+
+def linear_w8a16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:
+    M, K = x.shape
+    N = scales.shape[1]
+    assert qweight.shape == (K, N // 4), (qweight.shape, K, N)
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    wp, wb = _ws_args(ws)
+    _check(lib().morph_linear_w8a16(_dev(x, torch.float16, "x"), _dev(qweight, torch.int32, "qweight"),
+                                    _dev(scales, torch.float16, "scales"), _dev(qzeros, torch.int32, "qzeros"),
+                                    _dev(y, torch.float16, "y"), M, K, N, group_size, wp, wb, _stream()),
+           "morph_linear_w8a16")
     return y
 
 
@@ -301,6 +315,12 @@ class LayerStack:
                 if rec[0] == "fp16":
                     assert rec[1].shape == (K, N)
                     d.kind, d.w, d.scales, d.qzeros = KIND_FP16, _dev(rec[1], torch.float16, name), None, None
+                elif rec[0] == "w8":
+                    assert rec[1].shape == (K, N // 4)
+                    d.kind = KIND_W8A16
+                    d.w = _dev(rec[1], torch.int32, name)
+                    d.scales = _dev(rec[2], torch.float16, name)
+                    d.qzeros = _dev(rec[3], torch.int32, name)
                 else:
                     assert rec[1].shape == (K, N // 8)
                     d.kind = KIND_W4A16
@@ -388,8 +408,9 @@ def layer_record_views(kind: int, buf: torch.Tensor, hidden: int, inter: int) ->
         if kind == KIND_FP16:
             out[name] = ("fp16", view(ld.w, torch.float16, K, N))
         else:
-            out[name] = ("w4", view(ld.w, torch.int32, K, N // 8), view(ld.scales, torch.float16, K // 128, N),
-                         view(ld.qzeros, torch.int32, K // 128, N // 8))
+            per_word, tag = (4, "w8") if kind == KIND_W8A16 else (8, "w4")
+            out[name] = (tag, view(ld.w, torch.int32, K, N // per_word), view(ld.scales, torch.float16, K // 128, N),
+                         view(ld.qzeros, torch.int32, K // 128, N // per_word))
     return out
 
 
@@ -413,7 +434,7 @@ class SwapStack:
         self.scratch = torch.empty(int(lib().morph_stack_scratch_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
         self.tap = torch.empty(int(lib().morph_stack_tap_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
         need = 0
-        for kind in (KIND_FP16, KIND_W4A16):
+        for kind in (KIND_FP16, KIND_W4A16, KIND_W8A16):
             for K, N in ((hidden, 3 * hidden), (hidden, hidden), (hidden, 2 * inter), (inter, hidden)):
                 need = max(need, workspace_bytes(kind, M, K, N))
         self.ws = new_workspace(need, device)

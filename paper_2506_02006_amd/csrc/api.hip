@@ -32,7 +32,7 @@ bool takes_stream(int kind, int M, int K, int N)
     if (M <= 64) return true;
     if (M > 1024) return false;
     const int cus = prefill_compute_units();
-    const DecodePlan dp = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
+    const DecodePlan dp = plan_decode(kind, M, K, N);
     const double ns_per_row = kind == MORPH_KIND_W4A16 ? 6.7 : 6.0;        // one workgroup walking its rows of K
     const long long wgs = (long long)dp.tiles * dp.slices * dp.S;
     const double est_stream = 8.0 + (double)((wgs + cus - 1) / cus) * ((double)K / dp.S) * ns_per_row * 1e-3;
@@ -62,6 +62,8 @@ int check_sizes(int kind, int M, int K, int N)
     if (m * k * 2 >= k4G || m * n * 2 >= k4G) return MORPH_ERR_UNSUPPORTED;
     if (kind == MORPH_KIND_FP16) {
         if (k * n * 2 >= k4G) return MORPH_ERR_UNSUPPORTED;
+    } else if (kind == MORPH_KIND_W8A16) {
+        if (k * n >= k4G) return MORPH_ERR_UNSUPPORTED;
     } else {
         if (k * n / 2 >= k4G) return MORPH_ERR_UNSUPPORTED;
     }
@@ -74,7 +76,7 @@ size_t workspace_need(int kind, int M, int K, int N)
         const PrefillPlan pp = plan_prefill(M, K, N);
         return pp.partial_bytes ? pp.counter_bytes + pp.partial_bytes : 0;
     }
-    const DecodePlan pl = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
+    const DecodePlan pl = plan_decode(kind, M, K, N);
     return pl.S > 1 ? kCounterBytes + pl.partial_bytes : 0;
 }
 
@@ -83,7 +85,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
 {
     hipError_t e;
     if (takes_stream(kind, M, K, N)) {
-        const DecodePlan pl = plan_decode(kind == MORPH_KIND_W4A16, M, K, N);
+        const DecodePlan pl = plan_decode(kind, M, K, N);
         if (pl.S > 1 && pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
         DecodeArgs a;
         a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
@@ -95,7 +97,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
             a.counters = reinterpret_cast<int*>(workspace);
             a.partial  = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
         }
-        e = launch_decode(kind == MORPH_KIND_W4A16, a, st);
+        e = launch_decode(kind, a, st);
     } else {
         const PrefillPlan pp = plan_prefill(M, K, N);
         GemmArgs g;
@@ -110,7 +112,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
             g.counters = reinterpret_cast<int*>(workspace);
             g.partial  = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pp.counter_bytes);
         }
-        e = launch_prefill(kind == MORPH_KIND_W4A16, g, st);
+        e = launch_prefill(kind, g, st);
     }
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
@@ -119,10 +121,10 @@ int validate_linear(int kind, const void* x, const void* w, const void* scales, 
                     const void* y, int M, int K, int N)
 {
     if (!x || !w || !y) return MORPH_ERR_NULL;
-    if (kind == MORPH_KIND_W4A16 && (!scales || !qzeros)) return MORPH_ERR_NULL;
+    if (kind != MORPH_KIND_FP16 && (!scales || !qzeros)) return MORPH_ERR_NULL;
     if (int rc = check_shape(M, K, N)) return rc;
     if (!aligned16(x) || !aligned16(w) || !aligned16(y)) return MORPH_ERR_ALIGN;
-    if (kind == MORPH_KIND_W4A16 && (!aligned16(scales) || !aligned16(qzeros))) return MORPH_ERR_ALIGN;
+    if (kind != MORPH_KIND_FP16 && (!aligned16(scales) || !aligned16(qzeros))) return MORPH_ERR_ALIGN;
     return check_sizes(kind, M, K, N);
 }
 
@@ -182,6 +184,16 @@ int dequantize_any(int bits, const int32_t* qweight, const void* scales, const i
 }
 }  // namespace
 
+int morph_linear_w8a16(const void* x, const int32_t* qweight, const void* scales, const int32_t* qzeros,
+                       void* y, int M, int K, int N, int group_size, void* workspace,
+                       size_t workspace_bytes, void* stream)
+{
+    if (group_size != MORPH_GROUP_SIZE) return (x && qweight && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
+    if (int rc = validate_linear(MORPH_KIND_W8A16, x, qweight, scales, qzeros, y, M, K, N)) return rc;
+    return run_linear(MORPH_KIND_W8A16, x, qweight, scales, qzeros, y, M, K, N, workspace, workspace_bytes,
+                      (hipStream_t)stream);
+}
+
 int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
                          int K, int N, int group_size, void* stream)
 {
@@ -208,7 +220,7 @@ int morph_dequantize_w8(const int32_t* qweight, const void* scales, const int32_
 
 size_t morph_workspace_bytes(int kind, int M, int K, int N)
 {
-    if (kind != MORPH_KIND_FP16 && kind != MORPH_KIND_W4A16) return 0;
+    if (kind != MORPH_KIND_FP16 && kind != MORPH_KIND_W4A16 && kind != MORPH_KIND_W8A16) return 0;
     if (check_shape(M, K, N) != MORPH_OK) return 0;
     return workspace_need(kind, M, K, N);
 }
@@ -292,7 +304,7 @@ int morph_stack_forward(const morph_layer_desc* layers, int n_layers, void* x_io
         const Lin lins[4] = {{&layers[l].qkv, hidden, 3 * hidden}, {&layers[l].o, hidden, hidden},
                              {&layers[l].gate_up, hidden, 2 * inter}, {&layers[l].down, inter, hidden}};
         for (const Lin& li : lins) {
-            if (li.d->kind != MORPH_KIND_FP16 && li.d->kind != MORPH_KIND_W4A16) return MORPH_ERR_SHAPE;
+            if (li.d->kind != MORPH_KIND_FP16 && li.d->kind != MORPH_KIND_W4A16 && li.d->kind != MORPH_KIND_W8A16) return MORPH_ERR_SHAPE;
             if (int rc = validate_linear(li.d->kind, x_io, li.d->w, li.d->scales, li.d->qzeros, scratch, M, li.K, li.N))
                 return rc;
             size_t nb = workspace_need(li.d->kind, M, li.K, li.N);
@@ -402,6 +414,7 @@ int morph_stack_forward_fused(const morph_layer_desc* layers, int n_layers, void
         const morph_linear_desc* ds[4] = {&layers[l].qkv, &layers[l].o, &layers[l].gate_up, &layers[l].down};
         const int Ks[4] = {hidden, hidden, hidden, inter}, Ns[4] = {3 * hidden, hidden, 2 * inter, hidden};
         for (int q = 0; q < 4; q++) {
+            if (ds[q]->kind == MORPH_KIND_W8A16) return MORPH_ERR_UNSUPPORTED;   // the persistent launch knows fp16 and 4-bit layers
             if (ds[q]->kind != MORPH_KIND_FP16 && ds[q]->kind != MORPH_KIND_W4A16) return MORPH_ERR_SHAPE;
             if (int rc = validate_linear(ds[q]->kind, x_io, ds[q]->w, ds[q]->scales, ds[q]->qzeros, workspace, M, Ks[q], Ns[q]))
                 return rc;
@@ -454,7 +467,7 @@ struct RecordLayout {
 RecordLayout record_layout(int kind, int hidden, int inter)
 {
     RecordLayout L{};
-    if (kind != MORPH_KIND_FP16 && kind != MORPH_KIND_W4A16) return L;
+    if (kind != MORPH_KIND_FP16 && kind != MORPH_KIND_W4A16 && kind != MORPH_KIND_W8A16) return L;
     if (hidden < MORPH_GROUP_SIZE || inter < MORPH_GROUP_SIZE || hidden % MORPH_GROUP_SIZE || inter % MORPH_GROUP_SIZE) return L;
     const size_t KN[4][2] = {{(size_t)hidden, 3 * (size_t)hidden}, {(size_t)hidden, (size_t)hidden},
                              {(size_t)hidden, 2 * (size_t)inter}, {(size_t)inter, (size_t)hidden}};
@@ -465,9 +478,10 @@ RecordLayout record_layout(int kind, int hidden, int inter)
             L.off[l][0] = pos; pos += up256(K * N * 2);
             L.off[l][1] = L.off[l][2] = 0;
         } else {
-            L.off[l][0] = pos; pos += up256(K * (N / 8) * 4);
+            const size_t per_word = kind == MORPH_KIND_W8A16 ? 4 : 8;
+            L.off[l][0] = pos; pos += up256(K * (N / per_word) * 4);
             L.off[l][1] = pos; pos += up256(G * N * 2);
-            L.off[l][2] = pos; pos += up256(G * (N / 8) * 4);
+            L.off[l][2] = pos; pos += up256(G * (N / per_word) * 4);
         }
     }
     L.bytes = pos;
@@ -488,8 +502,8 @@ int morph_layer_record_desc(int kind, const void* base, int hidden, int inter, m
     for (int l = 0; l < 4; l++) {
         lins[l]->kind   = kind;
         lins[l]->w      = b + L.off[l][0];
-        lins[l]->scales = kind == MORPH_KIND_W4A16 ? b + L.off[l][1] : nullptr;
-        lins[l]->qzeros = kind == MORPH_KIND_W4A16 ? b + L.off[l][2] : nullptr;
+        lins[l]->scales = kind != MORPH_KIND_FP16 ? b + L.off[l][1] : nullptr;
+        lins[l]->qzeros = kind != MORPH_KIND_FP16 ? b + L.off[l][2] : nullptr;
     }
     return MORPH_OK;
 }

@@ -13,11 +13,11 @@ namespace morph {
 
 namespace {
 
-template <bool W4, int MT, int kWaves, bool NT>
+template <int Q, int MT, int kWaves, bool NT>
 __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kernel(DecodeArgs p)
 {
     MORPH_TICK(6);                                       // kernel entry
-    typedef TileGeom<W4, MT, kWaves> G;
+    typedef TileGeom<Q, MT, kWaves> G;
     constexpr int CPL = G::CPL, TN = G::TN, TNB = G::TNB, NV = G::NV, ITEMS = G::ITEMS;
     extern __shared__ __align__(16) f32x4 yl[];
 
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     job.x = (const half_t*)p.x + (size_t)mbase * p.K;
     job.w = p.w; job.scales = p.scales; job.qzeros = p.qzeros;
     job.M = M; job.K = p.K; job.N = N; job.n0 = n0; job.S = S; job.sp = sp;
-    tile_partial<W4, MT, kWaves, false, NT>(job, yl);
+    tile_partial<Q, MT, kWaves, false, NT>(job, yl);
 
     // ---- sum the waves that share columns (in the order of their k parts) and write out ----
     half_t* y = (half_t*)p.y + (size_t)mbase * N;
@@ -139,14 +139,14 @@ inline int decode_waves(int rows)
     return rows > 16 ? 8 : 4;
 }
 
-template <bool W4, int MT, int kWaves, bool NT>
+template <int Q, int MT, int kWaves, bool NT>
 hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
 {
-    constexpr int tnb = Tile<W4, MT>::TN * Tile<W4, MT>::WN;
-    constexpr size_t lds = TileGeom<W4, MT, kWaves>::kLdsBytes;
+    constexpr int tnb = Tile<Q, MT>::TN * Tile<Q, MT>::WN;
+    constexpr size_t lds = TileGeom<Q, MT, kWaves>::kLdsBytes;
     static_assert(lds <= 128 * 1024, "LDS of one compute unit");
     if (lds > 64 * 1024) {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<W4, MT, kWaves, NT>),
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Q, MT, kWaves, NT>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (attr != hipSuccess) return attr;
     }
@@ -155,18 +155,18 @@ hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
     b.slices = slices;
     const int units = b.tiles * a.S;
     const int grid  = units * slices;
-    hipLaunchKernelGGL((decode_kernel<W4, MT, kWaves, NT>), dim3(grid), dim3(kWaves * 64), lds, st, b);
+    hipLaunchKernelGGL((decode_kernel<Q, MT, kWaves, NT>), dim3(grid), dim3(kWaves * 64), lds, st, b);
     return hipGetLastError();
 }
 
-template <bool W4, int MT>
+template <int Q, int MT>
 hipError_t launch_one(const DecodeArgs& a, int slices, hipStream_t st)
 {
     const bool w8 = decode_waves(MT * 16) == 8;
     if constexpr (MT == 1) {
-        if (a.stream_loads) return w8 ? launch_waves<W4, MT, 8, true>(a, slices, st) : launch_waves<W4, MT, 4, true>(a, slices, st);
+        if (a.stream_loads) return w8 ? launch_waves<Q, MT, 8, true>(a, slices, st) : launch_waves<Q, MT, 4, true>(a, slices, st);
     }
-    return w8 ? launch_waves<W4, MT, 8, false>(a, slices, st) : launch_waves<W4, MT, 4, false>(a, slices, st);
+    return w8 ? launch_waves<Q, MT, 8, false>(a, slices, st) : launch_waves<Q, MT, 4, false>(a, slices, st);
 }
 
 }  // namespace
@@ -187,13 +187,14 @@ namespace {
 
 // The plan for slices of `rows` rows (16: one MFMA row tile per workgroup, 32: two), with an
 // estimate of the launch time net of what does not depend on the choice.
-DecodePlan plan_rows(int is_w4, int M, int K, int N, int rows)
+DecodePlan plan_rows(int q, int M, int K, int N, int rows)
 {
     DecodePlan pl;
     pl.rows   = rows;
-    pl.tile_n = !is_w4 ? Tile<false, 1>::TN : 256;      // workgroup tile (W4: 1 x 256 or 2 x 128 columns)
+    const bool is_w4 = q == 1;                          // q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes
+    pl.tile_n = !is_w4 ? Tile<0, 1>::TN : 256;          // workgroup tile (W4: 1 x 256 or 2 x 128 columns)
     const int kWaves = decode_waves(rows);
-    const int wk = (is_w4 && rows > 16) ? kWaves / Tile<true, 2>::WN : kWaves;   // waves of a workgroup along K
+    const int wk = (is_w4 && rows > 16) ? kWaves / Tile<1, 2>::WN : kWaves;   // waves of a workgroup along K
     pl.tiles  = (N + pl.tile_n - 1) / pl.tile_n;
     pl.slices = (M + rows - 1) / rows;
     const int T = K / 32;
@@ -234,26 +235,27 @@ DecodePlan plan_rows(int is_w4, int M, int K, int N, int rows)
 // put twice the workgroups along M instead of along K, which halves both the split and the
 // partial tile the last arriver has to add up.  For the 4-bit kernels between 17 and 64 rows the
 // estimate decides, as long as all workgroups of the 16-row plan run at the same time.
-DecodePlan plan_decode(int is_w4, int M, int K, int N)
+DecodePlan plan_decode(int q, int M, int K, int N)
 {
     const int t = tuning_get(TUNE_DECODE_SLICE);
-    if (t == 16 || t == 32) return plan_rows(is_w4, M, K, N, t);
-    if (M <= 16) return plan_rows(is_w4, M, K, N, 16);
-    const DecodePlan p32 = plan_rows(is_w4, M, K, N, 32);
-    if (!is_w4 || M > 64) return p32;
-    const DecodePlan p16 = plan_rows(is_w4, M, K, N, 16);
+    if (t == 16 || t == 32) return plan_rows(q, M, K, N, t);
+    if (M <= 16) return plan_rows(q, M, K, N, 16);
+    const DecodePlan p32 = plan_rows(q, M, K, N, 32);
+    if (q != 1 || M > 64) return p32;
+    const DecodePlan p16 = plan_rows(q, M, K, N, 16);
     if (p16.tiles * p16.slices * p16.S > 256) return p32;
     return p16.est_us < p32.est_us ? p16 : p32;
 }
 
-hipError_t launch_decode(int is_w4, const DecodeArgs& a, hipStream_t st)
+hipError_t launch_decode(int q, const DecodeArgs& a, hipStream_t st)
 {
     const int rows = a.rows;
     if (rows != 16 && rows != 32) return hipErrorInvalidValue;
     const int slices = (a.M + rows - 1) / rows;
     const bool one   = rows == 16;                       // a single 16-row MFMA tile
-    if (is_w4) return one ? launch_one<true, 1>(a, slices, st) : launch_one<true, 2>(a, slices, st);
-    return one ? launch_one<false, 1>(a, slices, st) : launch_one<false, 2>(a, slices, st);
+    if (q == 1) return one ? launch_one<1, 1>(a, slices, st) : launch_one<1, 2>(a, slices, st);
+    if (q == 2) return one ? launch_one<2, 1>(a, slices, st) : launch_one<2, 2>(a, slices, st);
+    return one ? launch_one<0, 1>(a, slices, st) : launch_one<0, 2>(a, slices, st);
 }
 
 }  // namespace morph

@@ -51,11 +51,15 @@ constexpr int NS     = 4;            // register stages: the k-step being comput
 // words per lane and row (128-byte runs per wave); with two M tiles a wave takes one word per lane
 // and two waves of a workgroup sit side by side (WN = 2) on the same rows, covering the 128-byte
 // run together.  Workgroup tile = WN * TN columns; the other kWaves / WN waves split K.
-template <bool W4, int MT> struct Tile;
-template <> struct Tile<true, 1>  { static constexpr int WPL = 2, CPL = 16, TN = 256, WN = 1; };
-template <> struct Tile<true, 2>  { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 2; };
-template <> struct Tile<false, 1> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 1; };
-template <> struct Tile<false, 2> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 1; };
+// Q names the weight format: 0 = fp16, 1 = 4-bit codes (eight per word), 2 = 8-bit codes (four per
+// word: a lane reads two words = 8 columns per row, 128-byte runs per wave, one MFMA per column).
+template <int Q, int MT> struct Tile;
+template <> struct Tile<1, 1> { static constexpr int WPL = 2, CPL = 16, TN = 256, WN = 1; };
+template <> struct Tile<1, 2> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 2; };
+template <> struct Tile<0, 1> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 1; };
+template <> struct Tile<0, 2> { static constexpr int WPL = 1, CPL = 8,  TN = 128, WN = 1; };
+template <> struct Tile<2, 1> { static constexpr int WPL = 2, CPL = 8,  TN = 128, WN = 1; };
+template <> struct Tile<2, 2> { static constexpr int WPL = 2, CPL = 8,  TN = 128, WN = 1; };
 
 template <int WPL>
 struct GroupRaw {                // scale / zero data of one group for this lane's 8 WPL columns
@@ -64,10 +68,10 @@ struct GroupRaw {                // scale / zero data of one group for this lane
 };
 
 // One k-step (32 rows) of operands as they arrive from memory.
-template <bool W4, int MT, int WPL>
+template <int Q, int MT, int WPL>
 struct Stage {
-    uint32_t w4[W4 ? 8 : 1][WPL];  // W4:   row i -> WPL packed words (8 WPL columns)
-    u32x4    wh[W4 ? 1 : 8];       // fp16: row i -> 8 halfs (8 columns)
+    uint32_t w4[Q ? 8 : 1][WPL];   // codes: row i -> WPL packed words (8 WPL columns of 4-bit, 4 WPL of 8-bit codes)
+    u32x4    wh[Q ? 1 : 8];        // fp16:  row i -> 8 halfs (8 columns)
     half8_t  a[MT];                // x rows (lane & 15) + 16 mt, 8 consecutive k
 };
 
@@ -86,11 +90,11 @@ struct TileJob {
 // Geometry of the result vectors in LDS: [wave][v][lane] f32x4; vector v = mt * CPL + j of lane
 // (c = lane & 15, b = lane >> 4) holds rows 16 mt + 4 b + r (r = 0..3) of column CPL c + j of the
 // wave's columns.  An "item" numbers the vectors of the whole workgroup tile: [column part][v][lane].
-template <bool W4, int MT, int kWaves>
+template <int Q, int MT, int kWaves>
 struct TileGeom {
-    static constexpr int CPL   = Tile<W4, MT>::CPL;
-    static constexpr int TN    = Tile<W4, MT>::TN;
-    static constexpr int WN    = Tile<W4, MT>::WN, WK = kWaves / WN;
+    static constexpr int CPL   = Tile<Q, MT>::CPL;
+    static constexpr int TN    = Tile<Q, MT>::TN;
+    static constexpr int WN    = Tile<Q, MT>::WN, WK = kWaves / WN;
     static constexpr int TNB   = TN * WN;              // columns of the workgroup tile
     static constexpr int NV    = MT * CPL;             // f32x4 result vectors per lane
     static constexpr int ITEMS = WN * NV * 64;         // f32x4 vectors of the workgroup tile
@@ -121,17 +125,18 @@ struct TileGeom {
 // make sure (barrier) that nobody still reads yl from an earlier unit when this is entered.
 // XT: read x past the caches (it was written by other workgroups of the same kernel).
 // NT: load the weights non-temporally (they are read once by this workgroup alone).
-template <bool W4, int MT, int kWaves, bool XT, bool NT = false>
+template <int Q, int MT, int kWaves, bool XT, bool NT = false>
 __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
 {
-    constexpr int WPL = Tile<W4, MT>::WPL;
-    constexpr int CPL = Tile<W4, MT>::CPL;
-    constexpr int TN  = Tile<W4, MT>::TN;
-    constexpr int WN  = Tile<W4, MT>::WN, WK = kWaves / WN;
+    constexpr bool W4 = Q == 1, W8 = Q == 2, QUANT = Q != 0;
+    constexpr int WPL = Tile<Q, MT>::WPL;
+    constexpr int CPL = Tile<Q, MT>::CPL;
+    constexpr int TN  = Tile<Q, MT>::TN;
+    constexpr int WN  = Tile<Q, MT>::WN, WK = kWaves / WN;
     constexpr int NV  = MT * CPL;                        // f32x4 result vectors per lane
     constexpr int kAuxX = XT ? kAuxSystemScope : 0;
     constexpr int kAuxW = NT ? kAuxStream : 0;
-    typedef Stage<W4, MT, WPL> StageT;
+    typedef Stage<Q, MT, WPL> StageT;
 
     const int tid = threadIdx.x, lane = tid & 63;
     // The wave index is the same in all 64 lanes: say so, so that everything derived from it (this
@@ -142,7 +147,7 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     const int n0 = p.n0;                                 // first column of the workgroup tile
     const int wn = wave % WN, wk = wave / WN;            // this wave's column part and k part
     const int M = p.M;
-    const int K = p.K, N = p.N, NW = N >> 3;
+    const int K = p.K, N = p.N, NW = W8 ? N >> 2 : N >> 3;   // packed words per row
     const int T  = K >> 5;                               // k-steps of 32 rows
     // The workgroup's steps [kb, ke) are shared out over its k parts in whole rounds of four steps
     // (one quantization group), so that no round is walked by two waves; with fewer rounds than
@@ -154,21 +159,21 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     const int ks0 = ga == gz ? 4 * ga : (4 * ga > kb ? 4 * ga : kb);
     const int ks1 = ga == gz ? 4 * ga : (4 * gz < ke ? 4 * gz : ke);
 
-    const uint32_t row_bytes = W4 ? (uint32_t)NW * 4u : (uint32_t)N * 2u;
+    const uint32_t row_bytes = QUANT ? (uint32_t)NW * 4u : (uint32_t)N * 2u;
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (uint32_t)K * row_bytes);
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (uint32_t)M * (uint32_t)K * 2u);
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.scales, W4 ? (uint32_t)(K / kGroup) * (uint32_t)N * 2u : 0u);
-    const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.qzeros, W4 ? (uint32_t)(K / kGroup) * (uint32_t)NW * 4u : 0u);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.scales, QUANT ? (uint32_t)(K / kGroup) * (uint32_t)N * 2u : 0u);
+    const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.qzeros, QUANT ? (uint32_t)(K / kGroup) * (uint32_t)NW * 4u : 0u);
 
     // This lane's first column; lanes that start beyond N read nothing (offset past the buffer).
     const int  ncol   = n0 + wn * TN + CPL * c;
     const bool col_ok = ncol < N;
     const uint32_t kOut = 0xFFFFFFF0u;
-    // W4: column n sits at byte n/2 of its row (8 columns per 4-byte word); fp16: at byte 2n.
-    const uint32_t col_byte = W4 ? (uint32_t)ncol / 2u : (uint32_t)ncol * 2u;
+    // Column n sits at byte n/2 (4-bit codes), n (8-bit codes) or 2n (fp16) of its row.
+    const uint32_t col_byte = W4 ? (uint32_t)ncol / 2u : W8 ? (uint32_t)ncol : (uint32_t)ncol * 2u;
     const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + col_byte : kOut;
     const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
-    const uint32_t voff_z = col_ok ? (uint32_t)(ncol >> 3) * 4u : kOut;
+    const uint32_t voff_z = col_ok ? col_byte : kOut;      // zero points are packed like the codes
     uint32_t voff_a[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) voff_a[mt] = ((uint32_t)(mt * 16 + c) * (uint32_t)K + 8u * b) * 2u;
@@ -183,11 +188,11 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
         const uint32_t vw   = voff_w | dm;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            if constexpr (W4 && WPL == 2) {
+            if constexpr (QUANT && WPL == 2) {
                 const u32x2 v = buf_load_u32x2<kAuxW>(rw, vw, so + (uint32_t)i * row_bytes);
                 st.w4[i][0] = v[0];
                 st.w4[i][WPL - 1] = v[1];
-            } else if constexpr (W4) {
+            } else if constexpr (QUANT) {
                 st.w4[i][0] = buf_load_u32<kAuxW>(rw, vw, so + (uint32_t)i * row_bytes);
             } else {
                 st.wh[i] = buf_load_u32x4<kAuxW>(rw, vw, so + (uint32_t)i * row_bytes);
@@ -210,7 +215,7 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
             gr.zq[0] = buf_load_u32(rz, voff_z | gm, gg * (uint32_t)NW * 4u);
         }
 #pragma unroll
-        for (int t = 0; t < WPL; t++)
+        for (int t = 0; t < CPL / 8; t++)                  // 8 fp16 scales per 16-byte load
             gr.sc[t] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u + 16u * t);
     };
 
@@ -218,20 +223,21 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     //   W4:   gacc[mt][t*8 + 2yb]     = sum x * byte        (byte = 16 q_hi + q_lo, times 2^-24)
     //         gacc[mt][t*8 + 2yb + 1] = sum x * 16 q_hi     (times 2^-24)
     //         xs[mt]                  = sum x               over the open group
+    //   W8:   gacc[mt][4t + yb]       = sum x * code        (times 2^-24)
     //   fp16: gacc[mt][j] is the result itself.
     f32x4 gacc[MT][CPL];
-    f32x4 xs[W4 ? MT : 1];
+    f32x4 xs[QUANT ? MT : 1];
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int mt = 0; mt < MT; mt++)
 #pragma unroll
         for (int j = 0; j < CPL; j++) gacc[mt][j] = zero4;
-    if constexpr (W4) {
+    if constexpr (QUANT) {
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) xs[mt] = zero4;
     }
     f32x4* ymine = yl + (size_t)wave * NV * 64 + lane;    // vector v at ymine[v * 64]
-    if constexpr (W4) {
+    if constexpr (QUANT) {
 #pragma unroll
         for (int v = 0; v < NV; v++) ymine[v * 64] = zero4;
     }
@@ -239,12 +245,34 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     // One k-step.  `first` (known at compile time: slot 0 of the unrolled group) starts the group
     // sums from zero instead of adding to them.
     auto compute = [&](const StageT& st, bool first) {
-        if constexpr (W4) {
+        if constexpr (QUANT) {
             const half_t  one  = (half_t)1.0f;
             const half8_t ones = {one, one, one, one, one, one, one, one};
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
                 xs[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], ones, first ? zero4 : xs[mt], 0, 0, 0);
+        }
+        if constexpr (W8) {
+            // a code byte in a 16-bit lane is the fp16 subnormal code * 2^-24: one MFMA per column
+#pragma unroll
+            for (int t = 0; t < WPL; t++) {
+#pragma unroll
+                for (int yb = 0; yb < 4; yb++) {
+                    uint32_t pr[4];
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const uint32_t r0 = st.w4[2 * q][t], r1 = st.w4[2 * q + 1][t];
+                        pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                              : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                    }
+                    const half8_t bcode = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
+                    const int j = 4 * t + yb;
+#pragma unroll
+                    for (int mt = 0; mt < MT; mt++)
+                        gacc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bcode, first ? zero4 : gacc[mt][j], 0, 0, 0);
+                }
+            }
+        } else if constexpr (W4) {
 #pragma unroll
             for (int t = 0; t < WPL; t++) {
 #pragma unroll
@@ -292,6 +320,28 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     //   low-nibble column:  y += s * (2^24 (acc_byte - acc_high) - z_lo * xs)
     //   high-nibble column: y += s * (2^20  acc_high             - z_hi * xs)
     auto flush_group = [&](const GroupRaw<WPL>& gr) {
+        if constexpr (W8) {
+            // y += s * (2^24 acc - z * xs)
+#pragma unroll
+            for (int t = 0; t < WPL; t++) {
+#pragma unroll
+                for (int yb = 0; yb < 4; yb++) {
+                    const int j = 4 * t + yb;
+                    const uint32_t sw = gr.sc[0][j >> 1];
+                    const float s  = (float)bit_cast<half_t>((uint16_t)((j & 1) ? sw >> 16 : sw & 0xFFFFu));
+                    const float z  = (float)((gr.zq[t] >> (8 * yb)) & 0xFFu);
+                    const float a1 = s * 16777216.0f, c1 = -s * z;
+#pragma unroll
+                    for (int mt = 0; mt < MT; mt++) {
+                        f32x4 y0 = ymine[(mt * CPL + j) * 64];
+#pragma unroll
+                        for (int r = 0; r < 4; r++)
+                            y0[r] = __builtin_fmaf(c1, xs[mt][r], __builtin_fmaf(a1, gacc[mt][j][r], y0[r]));
+                        ymine[(mt * CPL + j) * 64] = y0;
+                    }
+                }
+            }
+        }
         if constexpr (W4) {
 #pragma unroll
             for (int t = 0; t < WPL; t++) {
@@ -329,7 +379,7 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     const int g0 = ks0 >> 2, g1 = (ks1 + 3) >> 2;        // groups touched by [ks0, ks1)
     StageT        buf[NS];
     GroupRaw<WPL> gcur, gnext;
-    if constexpr (W4) load_group(gnext, g0);
+    if constexpr (QUANT) load_group(gnext, g0);
 #pragma unroll
     for (int i = 0; i < NS - 1; i++) {
         load_stage(buf[i], 4 * g0 + i);
@@ -337,12 +387,12 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     }
     MORPH_TICK(7);                                       // prologue loads issued
     for (int g = g0; g < g1; g++) {
-        if constexpr (W4) gcur = gnext;
+        if constexpr (QUANT) gcur = gnext;
 #pragma unroll
         for (int u = 0; u < NS; u++) {
             const int k = 4 * g + u;                     // step computed in this slot
             load_stage(buf[(u + NS - 1) % NS], k + NS - 1);
-            if constexpr (W4) {
+            if constexpr (QUANT) {
                 if (u == 1) load_group(gnext, g + 1);    // arrives well before the next group opens
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -351,13 +401,13 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
             compute(buf[u], u == 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (W4) flush_group(gcur);
+        if constexpr (QUANT) flush_group(gcur);
     }
     MORPH_TICK(1);
 
 
     // ---- leave the per-wave sums in LDS ----
-    if constexpr (!W4) {
+    if constexpr (!QUANT) {
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
 #pragma unroll

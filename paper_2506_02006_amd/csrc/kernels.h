@@ -41,8 +41,9 @@ struct DecodePlan {
     int    stream_loads;       // load the weights non-temporally
 };
 constexpr size_t kCounterBytes = 65536;  // head of the workspace: arrival counters (one per column tile and row slice)
-DecodePlan plan_decode(int is_w4, int M, int K, int N);
-hipError_t launch_decode(int is_w4, const DecodeArgs& a, hipStream_t st);
+// q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes (the MORPH_KIND_* values)
+DecodePlan plan_decode(int q, int M, int K, int N);
+hipError_t launch_decode(int q, const DecodeArgs& a, hipStream_t st);
 
 // ---- prefill, M > 64 (prefill.hip) ----
 struct GemmArgs {
@@ -66,7 +67,7 @@ struct PrefillPlan {
 };
 PrefillPlan plan_prefill(int M, int K, int N);
 int prefill_compute_units();   // compute units of the current device (256 when it cannot be asked)
-hipError_t launch_prefill(int is_w4, const GemmArgs& a, hipStream_t st);
+hipError_t launch_prefill(int q, const GemmArgs& a, hipStream_t st);   // q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes
 
 // ---- persistent layer stack, M <= 32 (stack.hip) ----
 constexpr int kStackWaves    = 8;      // waves per workgroup

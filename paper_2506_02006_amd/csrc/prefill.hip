@@ -54,9 +54,12 @@ constexpr int LDK = BK + 8;           // LDS pitch in halfs (144 bytes)
 // scheduling-group masks of __builtin_amdgcn_sched_group_barrier
 constexpr int kSgValu = 0x2, kSgMfma = 0x8, kSgVmemRead = 0x20, kSgDsRead = 0x100, kSgDsWrite = 0x200;
 
-template <bool W4, int BM, int BN, int WVM, int WVN>
+// Q: 0 = fp16 weights, 1 = 4-bit codes, 2 = 8-bit codes.
+template <int Q, int BM, int BN, int WVM, int WVN>
 __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kernel(GemmArgs p, int tiles_m, int tiles)
 {
+    constexpr bool W4 = Q == 1, W8 = Q == 2, QUANT = Q != 0;
+    constexpr int  RPB = W4 ? 2 : W8 ? 4 : 8;          // staging registers (x4) per 8x8 weight block
     constexpr int NT = WVM * WVN * 64;                 // threads
     constexpr int NH = NT / 2;                         // threads per staging role
     constexpr int WM = BM / WVM, WN = BN / WVN;        // wave tile
@@ -66,7 +69,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     constexpr int WB = (NBLK + NH - 1) / NH;           // blocks per weight-role thread (the last waves may have none)
     static_assert(XP * NH == BM * (BK / 8) && (XP == 8 || XP == 16), "x tile divides over its role");
     static_assert((WB == 1 || WB == 2) && NBLK % 64 == 0 && (WB == 1 || NBLK == WB * NH), "weight tile divides over whole waves of its role");
-    constexpr int NST = XP > (W4 ? 2 * WB : 8 * WB) ? XP : (W4 ? 2 * WB : 8 * WB);   // staging registers (x4)
+    constexpr int NST = XP > RPB * WB ? XP : RPB * WB;  // staging registers (x4)
 
     // Two separate objects (not halves of one array), so that the compiler knows a store into one
     // cannot alias a fragment read from the other and is free to interleave them.
@@ -76,16 +79,16 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool w_role = wave < (WVM * WVN) / 2;        // wave-uniform: this wave stages weights (else x)
     const int rt = w_role ? tid : tid - NH;            // thread index within its role
-    const int M = p.M, K = p.K, N = p.N, NW = N >> 3;
+    const int M = p.M, K = p.K, N = p.N, NW = W8 ? N >> 2 : N >> 3;   // packed words per row
     const int KT = K / BK;
     int m0 = 0, n0 = 0;                                // origin of the tile being worked on
     const int wm0 = (wave / WVN) * WM, wn0 = (wave % WVN) * WN;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (uint32_t)M * (uint32_t)K * 2u);
-    const uint32_t w_row = W4 ? (uint32_t)NW * 4u : (uint32_t)N * 2u;
+    const uint32_t w_row = QUANT ? (uint32_t)NW * 4u : (uint32_t)N * 2u;
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (uint32_t)K * w_row);
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.scales, W4 ? (uint32_t)(K / kGroup) * (uint32_t)N * 2u : 0u);
-    const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.qzeros, W4 ? (uint32_t)(K / kGroup) * (uint32_t)NW * 4u : 0u);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.scales, QUANT ? (uint32_t)(K / kGroup) * (uint32_t)N * 2u : 0u);
+    const __amdgpu_buffer_rsrc_t rz = make_rsrc(p.qzeros, QUANT ? (uint32_t)(K / kGroup) * (uint32_t)NW * 4u : 0u);
     const uint32_t kOut = 0xFFFFFFF0u;
 
     // x role: piece q = rt + NH i -> row q / 8, 8 halfs starting at k = 8 (q % 8).  Rows >= M read 0.
@@ -119,9 +122,10 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             const int  idx = rt + NH * bl, kb = idx & 7, nb = idx >> 3;
             const int  bcol = n0 + 8 * nb;
             const bool b_ok = bcol < N && idx < NBLK;
-            b_voff[bl] = b_ok ? (uint32_t)(8 * kb) * w_row + (W4 ? (uint32_t)(bcol >> 3) * 4u : (uint32_t)bcol * 2u) : kOut;
+            const uint32_t cbyte = W4 ? (uint32_t)bcol / 2u : W8 ? (uint32_t)bcol : (uint32_t)bcol * 2u;   // byte of the column in its row
+            b_voff[bl] = b_ok ? (uint32_t)(8 * kb) * w_row + cbyte : kOut;
             s_voff[bl] = b_ok ? (uint32_t)bcol * 2u : kOut;
-            z_voff[bl] = b_ok ? (uint32_t)(bcol >> 3) * 4u : kOut;
+            z_voff[bl] = b_ok ? cbyte : kOut;
         }
     };
     auto set_tile = [&](int tile) {
@@ -153,10 +157,11 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     };
 
     // staging registers: x role: st[i] = piece i; weight role: fp16: st[8 b + i] = row i of block b
-    // (8 halfs), W4: word i of block b = st[2 b + i / 4][i % 4], plus scales and zero points per block
+    // (8 halfs), W4: word i of block b = st[2 b + i / 4][i % 4], W8: the two words of row i =
+    // st[4 b + i / 2][2 (i % 2) + 0, 1], plus scales and zero points per block
     u32x4    st[NST];
     u32x4    sc_reg[WB];
-    uint32_t zq_reg[WB];
+    uint32_t zq_reg[WB][W8 ? 2 : 1];
 
     // Every staging function works on one half (h = 0, 1) of the thread's items, so that the loop can
     // spread the work over the k-substeps of a tile.
@@ -171,12 +176,22 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         for (int r = 4 * WB * h; r < 4 * WB * (h + 1); r++) {
             const int bl = r >> 3, i = r & 7;
             if constexpr (W4) st[2 * bl + (i >> 2)][i & 3] = buf_load_u32(rw, b_voff[bl], so + (uint32_t)i * w_row);
-            else              st[8 * bl + i] = buf_load_u32x4(rw, b_voff[bl], so + (uint32_t)i * w_row);
-            if constexpr (W4) {
+            else if constexpr (W8) {
+                const u32x2 v = buf_load_u32x2(rw, b_voff[bl], so + (uint32_t)i * w_row);
+                st[4 * bl + (i >> 1)][2 * (i & 1)]     = v[0];
+                st[4 * bl + (i >> 1)][2 * (i & 1) + 1] = v[1];
+            } else            st[8 * bl + i] = buf_load_u32x4(rw, b_voff[bl], so + (uint32_t)i * w_row);
+            if constexpr (QUANT) {
                 if (i == 0) {
                     const uint32_t g = (uint32_t)(kt * BK) / kGroup;
                     sc_reg[bl] = buf_load_u32x4(rs, s_voff[bl], g * (uint32_t)N * 2u);
-                    zq_reg[bl] = buf_load_u32(rz, z_voff[bl], g * (uint32_t)NW * 4u);
+                    if constexpr (W8) {
+                        const u32x2 z = buf_load_u32x2(rz, z_voff[bl], g * (uint32_t)NW * 4u);
+                        zq_reg[bl][0] = z[0];
+                        zq_reg[bl][W8 ? 1 : 0] = z[1];
+                    } else {
+                        zq_reg[bl][0] = buf_load_u32(rz, z_voff[bl], g * (uint32_t)NW * 4u);
+                    }
                 }
             }
         }
@@ -193,9 +208,33 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         for (int u = 2 * WB * h; u < 2 * WB * (h + 1); u++) {
             const int bl = u >> 2, yb = u & 3;
             half_t* bb = dst + b_lds[bl];
-            if constexpr (W4) {
+            if constexpr (W8) {
+                // columns 2yb, 2yb+1 of the block: bytes 2 (yb % 2), +1 of word yb / 2 of every row.
+                // The byte is ORed into the mantissa of 1024.0 (exactly 1024 + q), 1024 + z is taken off
+                // (exact), and one multiplication by the scale rounds once: exactly the fp16 dequantized value.
+                const uint32_t zq = zq_reg[bl][W8 ? (yb >> 1) : 0];
+                const uint32_t sw = sc_reg[bl][yb];
+                const half_t  s0 = bit_cast<half_t>((uint16_t)(sw & 0xFFFFu)), s1 = bit_cast<half_t>((uint16_t)(sw >> 16));
+                const half2_t s0p = {s0, s0}, s1p = {s1, s1};
+                const uint32_t z0 = (yb & 1) ? pair_bytes<2>(zq, zq) : pair_bytes<0>(zq, zq);
+                const uint32_t z1 = (yb & 1) ? pair_bytes<3>(zq, zq) : pair_bytes<1>(zq, zq);
+                const half2_t cz0 = bit_cast<half2_t>(z0 | 0xE400E400u), cz1 = bit_cast<half2_t>(z1 | 0xE400E400u);   // -(1024 + z)
+                half8_t c0, c1;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const uint32_t r0 = st[4 * bl + q][yb >> 1], r1 = st[4 * bl + q][2 + (yb >> 1)];               // rows 2q, 2q+1
+                    const uint32_t p0 = (yb & 1) ? pair_bytes<2>(r0, r1) : pair_bytes<0>(r0, r1);
+                    const uint32_t p1 = (yb & 1) ? pair_bytes<3>(r0, r1) : pair_bytes<1>(r0, r1);
+                    const half2_t v0 = (bit_cast<half2_t>(p0 | 0x64006400u) + cz0) * s0p;
+                    const half2_t v1 = (bit_cast<half2_t>(p1 | 0x64006400u) + cz1) * s1p;
+                    c0[2 * q] = v0[0]; c0[2 * q + 1] = v0[1];
+                    c1[2 * q] = v1[0]; c1[2 * q + 1] = v1[1];
+                }
+                *reinterpret_cast<half8_t*>(bb + (2 * yb) * LDK)     = c0;
+                *reinterpret_cast<half8_t*>(bb + (2 * yb + 1) * LDK) = c1;
+            } else if constexpr (W4) {
                 const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
-                const uint32_t zq = zq_reg[bl];
+                const uint32_t zq = zq_reg[bl][0];
                 const uint32_t zd = yb == 0 ? pair_bytes<0>(zq, zq) : yb == 1 ? pair_bytes<1>(zq, zq)
                                   : yb == 2 ? pair_bytes<2>(zq, zq) : pair_bytes<3>(zq, zq);
                 const half2_t czl = bit_cast<half2_t>((zd & 0x000F000Fu) | 0xE400E400u);   // -(1024 + z)
@@ -461,14 +500,14 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     }
 }
 
-template <bool W4, int BM, int BN, int WVM, int WVN>
+template <int Q, int BM, int BN, int WVM, int WVN>
 hipError_t launch_tile(const GemmArgs& a, hipStream_t st)
 {
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const int tiles = tiles_m * tiles_n;
     // (One kernel for both ways of running the last round: a variant without the sharing code
     // spills no registers but was measured 8 % slower per k step; the spills sit outside the loop.)
-    hipLaunchKernelGGL((prefill_kernel<W4, BM, BN, WVM, WVN>), dim3(a.grid), dim3(WVM * WVN * 64), 0, st, a, tiles_m, tiles);
+    hipLaunchKernelGGL((prefill_kernel<Q, BM, BN, WVM, WVN>), dim3(a.grid), dim3(WVM * WVN * 64), 0, st, a, tiles_m, tiles);
     return hipGetLastError();
 }
 
@@ -552,19 +591,26 @@ PrefillPlan plan_prefill(int M, int K, int N)
     return pl;
 }
 
-hipError_t launch_prefill(int is_w4, const GemmArgs& a0, hipStream_t st)
+template <int Q>
+static hipError_t launch_config(const GemmArgs& a, hipStream_t st)
+{
+    switch (a.config) {
+        case 1: return launch_tile<Q, 256, 256, 4, 2>(a, st);
+        case 3: return launch_tile<Q, 256, 256, 2, 2>(a, st);
+        case 4: return launch_tile<Q, 256, 128, 2, 2>(a, st);
+        case 5: return launch_tile<Q, 256, 192, 4, 2>(a, st);
+        default: return launch_tile<Q, 128, 128, 2, 2>(a, st);
+    }
+}
+
+// q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes
+hipError_t launch_prefill(int q, const GemmArgs& a0, hipStream_t st)
 {
     GemmArgs a = a0;
     const int force = tuning_get(TUNE_PREFILL_MAP);      // 0 = default (2), 1 / 2 = that map
     a.map = force == 1 ? 1 : 2;
     if (a.grid % 8 != 0) a.map = 1;
-    switch (a.config) {
-        case 1: return is_w4 ? launch_tile<true, 256, 256, 4, 2>(a, st) : launch_tile<false, 256, 256, 4, 2>(a, st);
-        case 3: return is_w4 ? launch_tile<true, 256, 256, 2, 2>(a, st) : launch_tile<false, 256, 256, 2, 2>(a, st);
-        case 4: return is_w4 ? launch_tile<true, 256, 128, 2, 2>(a, st) : launch_tile<false, 256, 128, 2, 2>(a, st);
-        case 5: return is_w4 ? launch_tile<true, 256, 192, 4, 2>(a, st) : launch_tile<false, 256, 192, 4, 2>(a, st);
-        default: return is_w4 ? launch_tile<true, 128, 128, 2, 2>(a, st) : launch_tile<false, 128, 128, 2, 2>(a, st);
-    }
+    return q == 1 ? launch_config<1>(a, st) : q == 2 ? launch_config<2>(a, st) : launch_config<0>(a, st);
 }
 
 }  // namespace morph
