@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="headline only, skip the detail sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--sections", default="config2,config3,config4,config5,swap",
+    ap.add_argument("--sections", default="config2,config3,config4,config5,swap,w8",
                     help="detail sections to run after the headline (comma separated; used by the profiling commands)")
     return ap.parse_args()
 
@@ -152,7 +152,7 @@ def main():
     avg_launch_s = sec / (args.steps * launches_per_step)
     roofline = {
         "bound": "hbm",
-        "kernel": "decode_kernel<true, 1, 4, true> (W4A16, M <= 16), mean over the 12 launches of a step",
+        "kernel": "decode_kernel<1, 1, 4, true> (W4A16, M <= 16), mean over the 12 launches of a step",
         "achieved": round(value, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
@@ -222,11 +222,14 @@ def main():
                         torch.matmul(x, r, out=y)
                     elif kind == B.KIND_W4A16:
                         B.linear_w4a16(x, r[0], r[1], r[2], w, out=y)
+                    elif kind == B.KIND_W8A16:
+                        B.linear_w8a16(x, r[0], r[1], r[2], w, out=y)
                     else:
                         B.linear_fp16(x, r, w, out=y)
             g = graph_of(run)
             s = timed(lambda i: g.replay(), max(2, reps // len(recs)), 2) / (max(2, reps // len(recs)) * len(recs))
-            nbytes = synth.w4_bytes(K, N, zeros=False) if kind == B.KIND_W4A16 else synth.fp16_bytes(K, N)
+            nbytes = (synth.w4_bytes(K, N, zeros=False) if kind == B.KIND_W4A16 else
+                      synth.w8_bytes(K, N, zeros=False) if kind == B.KIND_W8A16 else synth.fp16_bytes(K, N))
             return {"us": round(s * 1e6, 2), "GBps": round(nbytes / s / 1e9, 1),
                     "pct_hbm": round(nbytes / s / 1e9 / HBM_PEAK_GBS * 100, 1),
                     "TFLOPs": round(2.0 * M * K * N / s / 1e12, 2)}
@@ -236,10 +239,18 @@ def main():
         # its weights cached: 130 copies of the 4096 x 4096 W4 matrix, 4 of the fp16 gate_up.
         COLD_BYTES = 1.1e9
 
+        def make_w8(K, N):
+            w = rand_w(K, N)
+            rec = B.quantize_layer_w8(w)
+            del w
+            return rec
+
         def cold_pool(kind, K, N):
-            nbytes = synth.w4_bytes(K, N, zeros=True) if kind == B.KIND_W4A16 else synth.fp16_bytes(K, N)
+            nbytes = (synth.w4_bytes(K, N) if kind == B.KIND_W4A16 else
+                      synth.w8_bytes(K, N) if kind == B.KIND_W8A16 else synth.fp16_bytes(K, N))
             n = max(4, int(-(-COLD_BYTES // nbytes)))
-            return [make_w4(K, N) if kind == B.KIND_W4A16 else make_fp16(K, N) for _ in range(n)]
+            make = {B.KIND_W4A16: make_w4, B.KIND_W8A16: make_w8, B.KIND_FP16: make_fp16}[kind]
+            return [make(K, N) for _ in range(n)]
 
         del graphs, pool
         d7 = {}
@@ -258,6 +269,27 @@ def main():
                     d7[f"vendor_gemm_fp16/{name}/M{M}"] = per_linear(B.KIND_FP16, "llama7b", name, M, recs, reps=2 * len(recs), vendor=True)
                 del recs
             detail["config2_llama7b"] = d7
+
+        # ---- the 8-bit variant: 7B shapes at decode sizes, 13B shapes at M = 2048 ----
+        if "w8" in sections:
+            d8w = {}
+            for name in order:
+                recs = cold_pool(B.KIND_W8A16, *shapes7[name])
+                for M in (1, 16, 32):
+                    d8w[f"w8a16/{name}/M{M}"] = per_linear(B.KIND_W8A16, "llama7b", name, M, recs, reps=2 * len(recs))
+                del recs
+            for name in order:
+                K, N = synth.LAYER_SHAPES["llama13b"][name]
+                w8 = make_w8(K, N)
+                x = rand_x(2048, K)
+                y = torch.empty((2048, N), device=dev, dtype=torch.float16)
+                wsp = B.new_workspace(B.workspace_bytes(B.KIND_W8A16, 2048, K, N))
+                s8 = timed(lambda i: B.linear_w8a16(x, w8[0], w8[1], w8[2], wsp, out=y), 10, 2) / 10
+                tf = 2.0 * 2048 * K * N / s8 / 1e12
+                d8w[f"w8a16/13b_{name}/M2048"] = {"us": round(s8 * 1e6, 1), "TFLOPs": round(tf, 1),
+                                                  "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1)}
+                del w8
+            detail["w8a16_llama7b_decode_13b_prefill"] = d8w
 
         # ---- config 3: 8B GQA shapes, W4A16, M up to 64 ----
         if "config3" in sections:

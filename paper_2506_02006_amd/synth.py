@@ -65,5 +65,13 @@ def w4_bytes(K: int, N: int, zeros: bool = True) -> int:
     return b
 
 
+def w8_bytes(K: int, N: int, zeros: bool = True) -> int:
+    """Bytes of one 8-bit layer record: packed codes + fp16 scales (+ packed zeros)."""
+    b = K * N + (K // GROUP) * N * 2
+    if zeros:
+        b += (K // GROUP) * N
+    return b
+
+
 def fp16_bytes(K: int, N: int) -> int:
     return 2 * K * N
