@@ -23,6 +23,8 @@ What is computed (paper Section 4.3, footnote: weight-only INT4; Section 5.2:
   *_w8             O9  the 8-bit weight-only variant (Section 4.3 lists INT8 next to INT4;
                        Appendix C: FP16, W8, W4): the same scheme with 255 steps, uint8 codes
                        and zeros, four per word along N
+  cosine / LIS     O10 the layer-importance metrics (Section 4.2, Eq. 2-5): cosine similarity of
+                       activations, token by token, averaged; LIS = a1 LTS + a2 LRS + b MDS
   layer record     O8  the bytes of one layer (its four linears, in either form) as
                        they sit in the pinned host pool and in the layer's device slot,
                        and what an in-place swap leaves in the slot (Section 4.3,
@@ -397,3 +399,39 @@ def swap_in_place(slot: np.ndarray, record: np.ndarray) -> np.ndarray:
     assert record.size <= slot.size, "a slot is sized for the largest variant of its layer"
     slot[:record.size] = record
     return slot
+
+
+# ---------------- O10: cosine similarity and the layer importance score ----------------
+# Section 4.2 "Sensitivity Analysis for Layer Swapping": LTS_p = cos(h_p(x), x_p) (Eq. 2),
+# LRS_p = cos(h_p(x), h_p^Q(x)) (Eq. 3), MDS_p = cos(f^(Q)(x), f^(Q + {p})(x)) (Eq. 4) and
+# LIS_p = a1 LTS_p + a2 LRS_p + b MDS_p with a1 = a2 = 0.25, b = 0.5 (Eq. 5 and the text below it).
+# The activations are [tokens, hidden]; the cosine is taken per token and averaged over the tokens.
+
+LIS_ALPHA1, LIS_ALPHA2, LIS_BETA = 0.25, 0.25, 0.5
+
+
+def cosine_rows(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """cos of every row pair: <a_t, b_t> / (|a_t| |b_t|), fp64; 0 where either row is all zero."""
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    assert a.shape == b.shape and a.ndim == 2
+    out = np.zeros(a.shape[0], np.float64)
+    for t in range(a.shape[0]):
+        dot = 0.0
+        na = 0.0
+        nb = 0.0
+        for x, y in zip(a[t], b[t]):
+            dot += x * y
+            na += x * x
+            nb += y * y
+        out[t] = dot / np.sqrt(na * nb) if na > 0.0 and nb > 0.0 else 0.0
+    return out
+
+
+def cosine_mean(a: np.ndarray, b: np.ndarray) -> float:
+    return float(np.mean(cosine_rows(a, b)))
+
+
+def layer_importance(lts, lrs, mds) -> np.ndarray:
+    """Eq. 5 with the paper's weights."""
+    return LIS_ALPHA1 * np.asarray(lts, np.float64) + LIS_ALPHA2 * np.asarray(lrs, np.float64) + LIS_BETA * np.asarray(mds, np.float64)

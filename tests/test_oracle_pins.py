@@ -574,3 +574,42 @@ def test_p10_identity_and_numpy_matmul(oracle):
     assert np.allclose(oracle.linear_w8a16(x, qw, sc, qz), ref, rtol=1e-12, atol=1e-12)
     # fp16 form: one rounding of the exact value
     assert np.array_equal(oracle.dequant_w8(qw, sc, qz, 128, np.float16), D.astype(np.float16))
+
+
+# ---------- P11 cosine similarity and the layer importance score (Section 4.2, Eq. 2-5) ----------
+
+def test_p11_cosine_closed_forms(oracle):
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal((6, 40))
+    assert np.allclose(oracle.cosine_rows(a, a), 1.0, atol=1e-15)
+    assert np.allclose(oracle.cosine_rows(a, -a), -1.0, atol=1e-15)
+    assert np.allclose(oracle.cosine_rows(a, 3.5 * a), 1.0, atol=1e-15)            # scale invariant
+    e = np.zeros((2, 8)); e[0, 1] = 2.0; e[1, 5] = -1.0
+    f = np.zeros((2, 8)); f[0, 2] = 7.0; f[1, 5] = 4.0
+    assert np.array_equal(oracle.cosine_rows(e, f), [0.0, -1.0])                    # orthogonal, antiparallel
+    # a 3-4-5 triangle: cos between (3, 4) and (4, 3) is 24 / 25; between (1, 0) and (1, 1) is 1 / sqrt 2
+    assert np.allclose(oracle.cosine_rows(np.array([[3.0, 4.0], [1.0, 0.0]]), np.array([[4.0, 3.0], [1.0, 1.0]])),
+                       [24 / 25, 2 ** -0.5], atol=1e-15)
+    b = rng.standard_normal((6, 40))
+    c = oracle.cosine_rows(a, b)
+    assert np.all(np.abs(c) <= 1.0) and np.allclose(c, oracle.cosine_rows(b, a))     # Cauchy-Schwarz, symmetry
+    ref = np.einsum("th,th->t", a, b) / (np.linalg.norm(a, axis=1) * np.linalg.norm(b, axis=1))
+    assert np.allclose(c, ref, atol=1e-14)                                           # numpy's own routines
+    assert oracle.cosine_rows(np.zeros((1, 4)), np.ones((1, 4)))[0] == 0.0
+    # per token, then averaged: NOT the cosine of the flattened matrices
+    a2 = np.array([[1.0, 0.0], [0.0, 100.0]]); b2 = np.array([[0.0, 1.0], [0.0, 100.0]])
+    assert oracle.cosine_mean(a2, b2) == 0.5
+
+
+def test_p11_lis_weights_are_the_papers(oracle):
+    vals = {}
+    with open(os.path.join(GOLDEN, "paper_lis_weights.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                vals[k] = float(v)
+    assert (oracle.LIS_ALPHA1, oracle.LIS_ALPHA2, oracle.LIS_BETA) == (vals["alpha1"], vals["alpha2"], vals["beta"])
+    assert vals["alpha1"] + vals["alpha2"] + vals["beta"] == 1.0
+    lis = oracle.layer_importance([1.0, 0.0, 0.0, 0.2], [0.0, 1.0, 0.0, 0.4], [0.0, 0.0, 1.0, 0.8])
+    assert np.allclose(lis, [0.25, 0.25, 0.5, 0.05 + 0.1 + 0.4])
+    assert oracle.layer_importance([1.0], [1.0], [1.0])[0] == 1.0                    # identical activations everywhere
