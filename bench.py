@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="headline only, skip the detail sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--sections", default="config2,config3,config4,config5,swap,w8",
+    ap.add_argument("--sections", default="config2,config3,config4,config5,swap,w8,lis",
                     help="detail sections to run after the headline (comma separated; used by the profiling commands)")
     return ap.parse_args()
 
@@ -290,6 +290,21 @@ def main():
                                                   "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1)}
                 del w8
             detail["w8a16_llama7b_decode_13b_prefill"] = d8w
+
+        # ---- cosine similarity of activations (the layer-importance metrics): an HBM-bound reduction ----
+        if "lis" in sections:
+            dl = {}
+            for Mt, Ht in ((64, 4096), (4096, 4096), (16384, 4096)):
+                n_pairs = max(2, int(-(-6e8 // (4 * Mt * Ht))))                 # distinct tensor pairs, > 2 x the memory-side cache in total
+                aa = [rand_x(Mt, Ht) for _ in range(n_pairs)]
+                bb = [rand_x(Mt, Ht) for _ in range(n_pairs)]
+                g = graph_of(lambda: [B.cosine_rows(u, v) for u, v in zip(aa, bb)])
+                sl = timed(lambda i: g.replay(), 5, 1) / (5 * n_pairs)
+                nb = 4 * Mt * Ht
+                dl[f"cosine/tokens{Mt}_hidden{Ht}"] = {"us": round(sl * 1e6, 2), "GBps": round(nb / sl / 1e9, 1),
+                                                       "pct_hbm": round(nb / sl / 1e9 / HBM_PEAK_GBS * 100, 1)}
+                del aa, bb, g
+            detail["lis_cosine"] = dl
 
         # ---- config 3: 8B GQA shapes, W4A16, M up to 64 ----
         if "config3" in sections:

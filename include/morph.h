@@ -207,6 +207,15 @@ int morph_layer_record_desc(int kind, const void* base, int hidden, int inter, m
 int morph_layer_swap_async(void* slot, size_t slot_bytes, const void* host_record, int kind, int hidden,
                            int inter, void* copy_stream);
 
+/* ---- cosine similarity of activations (Section 4.2 "Sensitivity Analysis for Layer Swapping",
+ * Eq. 2-4: LTS, LRS and MDS are all cos(u, v) of two activation tensors) ----
+ * a, b: fp16 [M,H] on the device (M tokens, H % 8 == 0, 16-byte aligned).
+ * cos_out[t] (device, fp32 [M]) = <a_t, b_t> / (|a_t| |b_t|), sums in fp32 in a fixed order; 0 where a
+ * row is all zero.  mean_out (device, fp32 [1], may be NULL) = the mean over the M tokens, which is
+ * the value the metrics use.  The weights of Eq. 5 are applied by the caller. */
+int morph_cosine_rows(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H,
+                      void* stream);
+
 /* Launch every kernel variant once on tiny internal dummies so that code objects are loaded
  * before serving starts (Section 4.3: kernels are precompiled ahead of time; Appendix C: with
  * dummy data).  `dummy` is a caller-provided device buffer of at least morph_warmup_bytes(). */

@@ -27,7 +27,7 @@ EXPORTS = [
     "morph_set_tuning", "morph_copy", "morph_status_string",
     "morph_probe_out_bytes", "morph_probe_read", "morph_probe_mfma",
     "morph_layer_record_bytes", "morph_layer_record_desc", "morph_layer_swap_async",
-    "morph_quantize_layer_w8", "morph_dequantize_w8", "morph_linear_w8a16",
+    "morph_quantize_layer_w8", "morph_dequantize_w8", "morph_linear_w8a16", "morph_cosine_rows",
 ]
 
 
@@ -63,6 +63,7 @@ def lib() -> ctypes.CDLL:
     L.morph_quantize_layer.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w4.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_linear_w8a16.argtypes = L.morph_linear_w4a16.argtypes
+    L.morph_cosine_rows.argtypes = [vp, vp, vp, vp, i, i, vp]
     L.morph_quantize_layer_w8.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w8.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_workspace_bytes.argtypes = [i, i, i, i]
@@ -246,6 +247,20 @@ def copy(src: torch.Tensor, dst: torch.Tensor):
     assert nbytes == dst.numel() * dst.element_size() and src.is_contiguous() and dst.is_contiguous()
     _check(lib().morph_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream()), "morph_copy")
     return dst
+
+
+def cosine_rows(a: torch.Tensor, b: torch.Tensor):
+    """Per-token cosine of two fp16 [M,H] activation tensors and its mean: (fp32 [M], fp32 [1]) on the device."""
+    M, H = a.shape
+    assert b.shape == (M, H)
+    cos = torch.empty((M,), dtype=torch.float32, device=a.device)
+    mean = torch.empty((1,), dtype=torch.float32, device=a.device)
+    _check(lib().morph_cosine_rows(_dev(a, torch.float16, "a"), _dev(b, torch.float16, "b"), cos.data_ptr(),
+                                   mean.data_ptr(), M, H, _stream()), "morph_cosine_rows")
+    return cos, mean
+
+
+LIS_ALPHA1, LIS_ALPHA2, LIS_BETA = 0.25, 0.25, 0.5      # Section 4.2, below Eq. 5
 
 
 def probe_out_bytes() -> int:

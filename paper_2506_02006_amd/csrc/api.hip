@@ -523,6 +523,15 @@ int morph_layer_swap_async(void* slot, size_t slot_bytes, const void* host_recor
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
 
+int morph_cosine_rows(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H, void* stream)
+{
+    if (!a || !b || !cos_out) return MORPH_ERR_NULL;
+    if (M < 1 || H < 8 || H % 8 != 0) return MORPH_ERR_SHAPE;
+    if (!aligned16(a) || !aligned16(b) || (reinterpret_cast<uintptr_t>(cos_out) & 3u) ||
+        (mean_out && (reinterpret_cast<uintptr_t>(mean_out) & 3u))) return MORPH_ERR_ALIGN;
+    return launch_cosine_rows(a, b, cos_out, mean_out, M, H, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
 size_t morph_probe_out_bytes(void) { return kProbeOutBytes; }
 
 int morph_probe_read(const void* src, size_t bytes, void* out, size_t out_bytes, void* stream)

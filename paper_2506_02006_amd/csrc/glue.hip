@@ -111,6 +111,68 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ s, 
         d[i] = s[i];
 }
 
+// Cosine similarity of row t of a with row t of b (fp16 [M,H]), one workgroup per row.  Every
+// thread sums its share of the three dot products in fp32 in a fixed order, lanes and waves are
+// combined in a fixed order: the result does not depend on timing.
+__global__ __launch_bounds__(256) void cosine_rows_kernel(const half_t* __restrict__ a, const half_t* __restrict__ b,
+                                                          float* __restrict__ cos_out, int H)
+{
+    __shared__ float part[3][4];
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const half_t* ar = a + (size_t)row * H;
+    const half_t* br = b + (size_t)row * H;
+    float dot = 0.f, na = 0.f, nb = 0.f;
+    auto add = [&](const half8_t& x, const half8_t& y) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const float xf = (float)x[j], yf = (float)y[j];
+            dot = __builtin_fmaf(xf, yf, dot);
+            na  = __builtin_fmaf(xf, xf, na);
+            nb  = __builtin_fmaf(yf, yf, nb);
+        }
+    };
+    const int nv = H / 8;
+    int v = tid;
+    for (; v + 256 < nv; v += 512) {                       // four independent 16-byte loads in flight (read once: non-temporal)
+        const half8_t x0 = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(ar + 8 * v));
+        const half8_t y0 = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(br + 8 * v));
+        const half8_t x1 = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(ar + 8 * (v + 256)));
+        const half8_t y1 = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(br + 8 * (v + 256)));
+        add(x0, y0);
+        add(x1, y1);
+    }
+    for (; v < nv; v += 256)
+        add(*reinterpret_cast<const half8_t*>(ar + 8 * v), *reinterpret_cast<const half8_t*>(br + 8 * v));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        dot += __shfl_xor(dot, off, 64);
+        na  += __shfl_xor(na, off, 64);
+        nb  += __shfl_xor(nb, off, 64);
+    }
+    if ((tid & 63) == 0) { part[0][tid >> 6] = dot; part[1][tid >> 6] = na; part[2][tid >> 6] = nb; }
+    __syncthreads();
+    if (tid == 0) {
+        const float d = (part[0][0] + part[0][1]) + (part[0][2] + part[0][3]);
+        const float p = (part[1][0] + part[1][1]) + (part[1][2] + part[1][3]);
+        const float q = (part[2][0] + part[2][1]) + (part[2][2] + part[2][3]);
+        cos_out[row] = (p > 0.f && q > 0.f) ? d / (sqrtf(p) * sqrtf(q)) : 0.f;
+    }
+}
+
+// mean of n floats by one workgroup, fixed order
+__global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ v, int n, float* __restrict__ out)
+{
+    __shared__ float part[4];
+    const int tid = threadIdx.x;
+    float s = 0.f;
+    for (int i = tid; i < n; i += 256) s += v[i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((tid & 63) == 0) part[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) out[0] = ((part[0] + part[1]) + (part[2] + part[3])) / (float)n;
+}
+
 // Read-only stream: every vector of the buffer is loaded once; the XOR of what a thread saw goes
 // out so that the loads cannot be dropped.
 __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ s, size_t n16, uint32_t* __restrict__ out)
@@ -151,6 +213,14 @@ __global__ __launch_bounds__(kProbeMfmaThreads) void probe_mfma_kernel(int iters
 }
 
 }  // namespace
+
+hipError_t launch_cosine_rows(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H, hipStream_t st)
+{
+    hipLaunchKernelGGL(cosine_rows_kernel, dim3(M), dim3(256), 0, st, (const half_t*)a, (const half_t*)b, cos_out, H);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    if (mean_out) hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st, cos_out, M, mean_out);
+    return hipGetLastError();
+}
 
 hipError_t launch_probe_read(const void* src, size_t bytes, void* out, hipStream_t st)
 {

@@ -186,3 +186,12 @@ def test_layer_record_and_swap_validation(L):
     assert L.morph_layer_swap_async(B256, need, B256, 1, 128, 100, None) == 2
     assert L.morph_layer_swap_async(B256 + 64, need, B256, 1, 128, 128, None) == 3
     assert L.morph_layer_swap_async(B256, need - 1, B256, 1, 128, 128, None) == 4
+
+
+def test_cosine_rows_validation(L):
+    f = L.morph_cosine_rows
+    assert f(None, FAKE, FAKE, None, 4, 64, None) == 1 and f(FAKE, None, FAKE, None, 4, 64, None) == 1
+    assert f(FAKE, FAKE, None, None, 4, 64, None) == 1
+    assert f(FAKE, FAKE, FAKE, None, 0, 64, None) == 2 and f(FAKE, FAKE, FAKE, None, 4, 60, None) == 2
+    assert f(FAKE + 8, FAKE, FAKE, None, 4, 64, None) == 3 and f(FAKE, FAKE, FAKE + 2, None, 4, 64, None) == 3
+    assert f(FAKE, FAKE, FAKE, FAKE + 1, 4, 64, None) == 3
