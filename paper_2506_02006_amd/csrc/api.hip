@@ -594,8 +594,15 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
         if ((rc = morph_linear_fp16(x, w, y, m, kWK, kWN, ws, wsb, stream))) return rc;
         if ((rc = morph_linear_w4a16(x, q, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
     }
+    // the 8-bit variant: its codes (32 KB) go where the fp32 dummy matrix was
+    int32_t* q8 = reinterpret_cast<int32_t*>(f);
+    if ((rc = morph_quantize_layer_w8(w, MORPH_DTYPE_F16, q8, s, z, kWK, kWN, 128, stream))) return rc;
+    for (int m : ms)
+        if ((rc = morph_linear_w8a16(x, q8, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
+    if ((rc = morph_dequantize_w8(q8, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
     for (int op = MORPH_GLUE_QKV; op <= MORPH_GLUE_RMS; op++)
         if ((rc = morph_glue(op, w, x, y, 2, 64, stream))) return rc;
+    if ((rc = morph_cosine_rows(x, w, reinterpret_cast<float*>(y), reinterpret_cast<float*>(y) + 64, 2, 128, stream))) return rc;
     if (launch_copy(x, y, 4096, st) != hipSuccess) return MORPH_ERR_DEVICE;
     return MORPH_OK;
 }

@@ -24,7 +24,7 @@ from paper_2506_02006_amd import synth
 pytestmark = pytest.mark.gpu
 
 TOL = 5e-3
-KINDS = {"fp16": 0, "w4": 1}
+KINDS = {"fp16": 0, "w4": 1, "w8": 2}
 
 
 @pytest.fixture(scope="module")
@@ -57,12 +57,13 @@ def make_layers(oracle, hidden, inter, n_layers, config_id):
     shapes = oracle.layer_shapes(hidden, inter)
     layers = []
     for l in range(n_layers):
-        v = {"fp16": {}, "w4": {}}
+        v = {"fp16": {}, "w4": {}, "w8": {}}
         for t, name in enumerate(oracle.RECORD_LINEARS):
             K, N = shapes[name]
             W = synth.weights(config_id, K, N, layer_id=l, tensor_id=t)
             v["fp16"][name] = (W.astype(np.float16),)
             v["w4"][name] = oracle.quantize_w4(W)
+            v["w8"][name] = oracle.quantize_w8(W)
         layers.append(v)
     return layers
 
@@ -70,7 +71,7 @@ def make_layers(oracle, hidden, inter, n_layers, config_id):
 def build_swap_stack(B, oracle, layers, hidden, inter, M, start_kind="fp16"):
     st = B.SwapStack(hidden, inter, M, len(layers))
     for l, v in enumerate(layers):
-        for kname in ("fp16", "w4"):
+        for kname in ("fp16", "w4", "w8"):
             rec = st.new_host_record(KINDS[kname])
             rec.numpy()[:] = oracle.layer_record_pack(kname, v[kname], hidden, inter)
             st.set_host_record(l, KINDS[kname], rec)
@@ -208,6 +209,28 @@ def test_a_swap_every_step_without_host_synchronisation(B, oracle):
         xr = reference_step(B, layers, kinds, hidden, inter, M, xr)
         assert same_bits(host(outs[t]), xr), f"step {t}"
         kinds[l] = kname
+
+
+def test_swap_through_all_three_variants(B, oracle):
+    """fp16 -> 8-bit -> 4-bit -> fp16 on one layer (Section 4.3 lists INT8 next to INT4 among the
+    variants, and transitions between them), every state compared with a plain stack of that mix."""
+    hidden, inter, n_layers, M = 256, 384, 4, 6
+    layers = make_layers(oracle, hidden, inter, n_layers, 85)
+    st = build_swap_stack(B, oracle, layers, hidden, inter, M)
+    x0 = oracle.rms(synth.activations(85, M, hidden).astype(np.float64)).astype(np.float16)
+    kinds = ["fp16"] * n_layers
+    for kname in ("w8", "w4", "fp16"):
+        st.swap(2, KINDS[kname])
+        x = dev(x0).clone()
+        st.step(x)                                           # still the previous variant
+        assert same_bits(host(x), reference_step(B, layers, kinds, hidden, inter, M, x0)), kname
+        kinds[2] = kname
+        x = dev(x0).clone()
+        st.step(x)
+        torch.cuda.synchronize()
+        assert same_bits(host(x), reference_step(B, layers, kinds, hidden, inter, M, x0)), kname
+        want = oracle.layer_record_pack(kname, layers[2][kname], hidden, inter)
+        assert np.array_equal(host(st.slots[2])[:want.size], want)
 
 
 def test_swap_rejects_a_slot_that_is_too_small(B):
