@@ -2,8 +2,8 @@
 """Turn rocprofv3 output databases (rocpd sqlite, `*_results.db`) into the short text summaries kept
 under profiles/.
 
-    python profile_summary.py --trace gpurun_out/prof/q_results.db \
-        [--fetch gpurun_out/pmc_fetch/q_results.db --write gpurun_out/pmc_write/q_results.db] \
+    python profile_summary.py --trace OUT/prof/q_results.db \
+        [--fetch OUT/pmc_fetch/q_results.db --write OUT/pmc_write/q_results.db] \
         --command "<the rocprofv3 command lines>" > profiles/<kernel>_<workload>.txt
 
 --trace : a `rocprofv3 --kernel-trace --stats` run; prints count / mean / min / max duration per
