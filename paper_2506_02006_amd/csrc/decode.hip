@@ -163,7 +163,7 @@ template <int Q, int MT>
 hipError_t launch_one(const DecodeArgs& a, int slices, hipStream_t st)
 {
     const bool w8 = decode_waves(MT * 16) == 8;
-    if constexpr (MT == 1) {
+    if constexpr (MT == 1 || Q != 1) {                   // not the 4-bit two-tile kernel: its two column halves share cache lines
         if (a.stream_loads) return w8 ? launch_waves<Q, MT, 8, true>(a, slices, st) : launch_waves<Q, MT, 4, true>(a, slices, st);
     }
     return w8 ? launch_waves<Q, MT, 8, false>(a, slices, st) : launch_waves<Q, MT, 4, false>(a, slices, st);
@@ -223,9 +223,9 @@ DecodePlan plan_rows(int q, int M, int K, int N, int rows)
     pl.est_us = (walk > hbm ? walk : hbm) + (S > 1 ? 1.5 + (double)S * tile_floats * 4.0 / 2.0e5 : 0.0);
     // Non-temporal weight loads where one workgroup alone reads its rows, once: measured on graphs
     // that cycle through 1.26 GB of 7B layers, fp16 5.6 % and W4 2 % faster.  Never where slices,
-    // or the two column halves of the two-tile kernels, meet in the caches (up to 17 % slower).
+    // or the two column halves of the 4-bit two-tile kernel, meet in the caches (up to 17 % slower).
     const int nt = tuning_get(TUNE_DECODE_STREAM);
-    pl.stream_loads = nt ? nt == 1 : (pl.slices == 1 && rows == 16);
+    pl.stream_loads = nt ? (nt == 1 && (rows == 16 || q != 1)) : (pl.slices == 1 && (rows == 16 || q != 1));
     return pl;
 }
 
