@@ -33,7 +33,7 @@ bool takes_stream(int kind, int M, int K, int N)
     if (M > 1024) return false;
     const int cus = prefill_compute_units();
     const DecodePlan dp = plan_decode(kind, M, K, N);
-    const double ns_per_row = kind == MORPH_KIND_W4A16 ? 6.7 : 6.0;        // one workgroup walking its rows of K
+    const double ns_per_row = kind == MORPH_KIND_W4A16 ? 6.7 : kind == MORPH_KIND_W8A16 ? 4.5 : 6.0;   // one workgroup walking its rows of K
     const long long wgs = (long long)dp.tiles * dp.slices * dp.S;
     const double est_stream = 8.0 + (double)((wgs + cus - 1) / cus) * ((double)K / dp.S) * ns_per_row * 1e-3;
     const PrefillPlan pp = plan_prefill(M, K, N);
