@@ -202,7 +202,8 @@ def main():
     t_mfma = timed(mfma_probe, 5, 1) / 5
     peaks = {"read_GBs": round(big.numel() / t_read / 1e9, 1),
              "mfma_f16_TFLOPs": round(flop_box[0] / t_mfma / 1e12, 1),
-             "how": "library probe kernels: 1 GiB contiguous read; 32x32x16 fp16 MFMAs on registers, 8-wave workgroups"}
+             "how": "library probe kernels: 1 GiB read, a contiguous chunk per workgroup, non-temporal loads; "
+                    "32x32x16 fp16 MFMAs on registers, 8-wave workgroups"}
     result["measured_peaks"] = peaks
     roofline["frac_of_measured_read"] = round(value / peaks["read_GBs"], 4)
     del big, pout
