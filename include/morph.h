@@ -1,5 +1,6 @@
 /*
- * libmorph -- fp16 and weight-only 4-bit (W4A16) linear layers for MI355X (gfx950).
+ * libmorph -- fp16 and weight-only 4-bit / 8-bit (W4A16, W8A16) linear layers for MI355X (gfx950),
+ * with the in-place layer swap and the layer-importance cosine that go with them.
  *
  * The method served: a transformer whose decoder layers can be swapped at run time between a
  * full-precision fp16 variant and a 4-bit weight-only variant written over the same device
@@ -7,10 +8,12 @@
  * change between two decode steps (paper Section 4.3 "Runtime Layer Swapping"; Appendix C
  * "Implementation Details": FP16 / W8 / W4 variants, GEMM kernels precompiled, weights
  * overwritten in place without pointer remapping).  This library is the compute under that
- * mechanism: the four linear projections of a layer (QKV, O, gate/up, down) in either kind.
+ * mechanism: the four linear projections of a layer (QKV, O, gate/up, down) in either kind, plus
+ * the copy that swaps a layer's variant in place and the cosine the swap order is derived from.
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers on the current HIP device unless marked "host".
+ *     (Host pointers: the layer descriptors, and the pinned record morph_layer_swap_async copies.)
  *     The caller owns every buffer; the library never allocates, frees or keeps a pointer
  *     between calls (a layer's weights may be overwritten in place at any time between calls).
  *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = default stream)
@@ -55,7 +58,7 @@ enum { MORPH_GROUP_SIZE = 128 };
 /* ---- y = x * W with fp16 weights (the full-precision layer variant; Section 4.3, Appendix C) ----
  * x [M,K] fp16, w [K,N] fp16, y [M,N] fp16.  K % 128 == 0, N % 8 == 0, M >= 1.
  * Small M takes the streaming (decode) kernels, which read the weights once and work on slices of
- * 32 rows (split along K; need the workspace), large M the LDS-tiled MFMA kernels (one workgroup
+ * 16 or 32 rows (split along K; need the workspace), large M the LDS-tiled MFMA kernels (one workgroup
  * per compute unit walking 256-wide tiles; need the workspace when a last round of tiles is shared
  * out along K).  Up to 64 rows it is always the former, above 1024 always the latter; in between
  * the library picks the faster one from the shape.
