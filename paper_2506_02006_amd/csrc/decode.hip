@@ -96,6 +96,27 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     if (!*flag) return;
     // All loads of a thread's items are independent: they are issued together and summed in index
     // order (split 0 first), so the result does not depend on which workgroup arrived last.
+    if (M <= 4) {
+        // Only lanes 0..15 of a vector hold rows that exist: one such vector per thread and all
+        // splits in flight at once (a deep split is then fetched in one round trip instead of two).
+        constexpr int LIVE = (ITEMS / 64) * 16, CH4 = 16;
+        for (int L = tid; L < LIVE; L += kWaves * 64) {
+            const int it = (L >> 4) * 64 + (L & 15);
+            f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int s2 = 0; s2 < S; s2 += CH4) {
+                f32x4 v[CH4];
+#pragma unroll
+                for (int q = 0; q < CH4; q++)              // splits beyond S read past the buffer and come back as zeros
+                    v[q] = bit_cast<f32x4>(__builtin_amdgcn_raw_buffer_load_b128(rp, (uint32_t)it * 16u, (uint32_t)(s2 + q) * kPartBytes, kAuxSystemScope));
+#pragma unroll
+                for (int q = 0; q < CH4; q++) a += v[q];
+            }
+            item_store_y(it, a);
+        }
+        if (tid == 0) atomicExch(p.counters + tile_id, 0);
+        MORPH_TICK(5);
+        return;
+    }
     constexpr int IPT = ITEMS / (kWaves * 64);           // items per thread
     f32x4 acc[IPT];
 #pragma unroll
