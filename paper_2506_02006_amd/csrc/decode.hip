@@ -71,9 +71,18 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
         const int rem = it % (NV * 64), v = rem >> 6, ln = rem & 63;
         return 16 * (v / CPL) + 4 * (ln >> 4) < M;
     };
+    // With at most four rows only lanes 0..15 of a vector hold rows that exist: those vectors are
+    // numbered 0 .. LIVE-1 so that every thread gets one, instead of a quarter of the threads four.
+    constexpr int LIVE = (ITEMS / 64) * 16;
+    auto live_item = [](int L) { return (L >> 4) * 64 + (L & 15); };
+    const bool few = M <= 4;
     if (S == 1) {
-        for (int it = tid; it < ITEMS; it += kWaves * 64)
-            if (item_rows_live(it)) item_store_y(it, item_sum(it));
+        if (few) {
+            for (int L = tid; L < LIVE; L += kWaves * 64) item_store_y(live_item(L), item_sum(live_item(L)));
+        } else {
+            for (int it = tid; it < ITEMS; it += kWaves * 64)
+                if (item_rows_live(it)) item_store_y(it, item_sum(it));
+        }
         return;
     }
     // Partials cross workgroups that may sit on different XCDs (separate L2s).  They are written
@@ -84,8 +93,13 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     constexpr uint32_t kPartBytes = (uint32_t)ITEMS * 16u;           // one workgroup's partial
     const float* tile_base = p.partial + (size_t)tile_id * S * ITEMS * 4;
     const __amdgpu_buffer_rsrc_t rp = make_rsrc(tile_base, (uint32_t)S * kPartBytes);
-    for (int it = tid; it < ITEMS; it += kWaves * 64)
-        if (item_rows_live(it)) buf_store_through(rp, (uint32_t)sp * kPartBytes + (uint32_t)it * 16u, item_sum(it));
+    if (few) {
+        for (int L = tid; L < LIVE; L += kWaves * 64)
+            buf_store_through(rp, (uint32_t)sp * kPartBytes + (uint32_t)live_item(L) * 16u, item_sum(live_item(L)));
+    } else {
+        for (int it = tid; it < ITEMS; it += kWaves * 64)
+            if (item_rows_live(it)) buf_store_through(rp, (uint32_t)sp * kPartBytes + (uint32_t)it * 16u, item_sum(it));
+    }
     wait_stores();
     MORPH_TICK(3);
     __syncthreads();                                     // every wave is done reading yl
@@ -96,12 +110,12 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     if (!*flag) return;
     // All loads of a thread's items are independent: they are issued together and summed in index
     // order (split 0 first), so the result does not depend on which workgroup arrived last.
-    if (M <= 4) {
-        // Only lanes 0..15 of a vector hold rows that exist: one such vector per thread and all
-        // splits in flight at once (a deep split is then fetched in one round trip instead of two).
-        constexpr int LIVE = (ITEMS / 64) * 16, CH4 = 16;
+    if (few) {
+        // one live vector per thread and all splits in flight at once (a deep split is then fetched
+        // in one round trip instead of two)
+        constexpr int CH4 = 16;
         for (int L = tid; L < LIVE; L += kWaves * 64) {
-            const int it = (L >> 4) * 64 + (L & 15);
+            const int it = live_item(L);
             f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
             for (int s2 = 0; s2 < S; s2 += CH4) {
                 f32x4 v[CH4];
