@@ -233,7 +233,10 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
  * 5 = prefill: order in which tiles are dealt to workgroups (1 = row tiles of a column tile first,
  * 2 = blocks of 8 column tiles spread over the 8 XCDs), 6 = largest M the streaming kernels take
  * (32 .. 1024; replaces the choice by shape), 7 = rows one streaming workgroup takes (16 or 32),
- * 8 = non-temporal weight loads in the streaming kernels (1 = always, 2 = never).
+ * 8 = non-temporal weight loads in the streaming kernels (1 = always, 2 = never),
+ * 9 = streaming kernels: sum over the K splits shared out among the workgroups of a tile (1 = whenever
+ * possible, 2 = never, 3 = whenever possible and no workgroup waits for the others, which leaves every
+ * part to the last one out: exercises the path taken after a wait that ran out).
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);
 

@@ -18,6 +18,7 @@ GLUE_QKV, GLUE_RESIDUAL, GLUE_SWIGLU, GLUE_RMS = 0, 1, 2, 3
 TUNE_DECODE_SPLIT, TUNE_DECODE_WGS, TUNE_PREFILL_TILE, TUNE_DECODE_WAVES, TUNE_PREFILL_SPLIT, TUNE_PREFILL_MAP, TUNE_DECODE_MAX_M = 0, 1, 2, 3, 4, 5, 6
 TUNE_DECODE_SLICE = 7
 TUNE_DECODE_STREAM = 8
+TUNE_DECODE_SCATTER = 9
 
 EXPORTS = [
     "morph_linear_fp16", "morph_linear_w4a16", "morph_quantize_layer", "morph_dequantize_w4",

@@ -33,6 +33,7 @@ bool takes_stream(int kind, int M, int K, int N)
     if (M > 1024) return false;
     const int cus = prefill_compute_units();
     const DecodePlan dp = plan_decode(kind, M, K, N);
+    if (dp.S > 1 && dp.tiles * dp.slices > (int)(kCounterBytes / sizeof(int)) / 2) return false;   // more tiles than counters
     const double ns_per_row = kind == MORPH_KIND_W4A16 ? 6.7 : kind == MORPH_KIND_W8A16 ? 4.5 : 6.0;   // one workgroup walking its rows of K
     const long long wgs = (long long)dp.tiles * dp.slices * dp.S;
     const double est_stream = 8.0 + (double)((wgs + cus - 1) / cus) * ((double)K / dp.S) * ns_per_row * 1e-3;
@@ -86,10 +87,10 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
     hipError_t e;
     if (takes_stream(kind, M, K, N)) {
         const DecodePlan pl = plan_decode(kind, M, K, N);
-        if (pl.S > 1 && pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int))) return MORPH_ERR_UNSUPPORTED;
+        if (pl.S > 1 && pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int)) / 2) return MORPH_ERR_UNSUPPORTED;   // two counters per tile
         DecodeArgs a;
         a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
-        a.M = M; a.K = K; a.N = N; a.S = pl.S; a.rows = pl.rows; a.stream_loads = pl.stream_loads;
+        a.M = M; a.K = K; a.N = N; a.S = pl.S; a.rows = pl.rows; a.stream_loads = pl.stream_loads; a.scatter = pl.scatter; a.polls = pl.polls;
         a.partial = nullptr; a.counters = nullptr;
         if (pl.S > 1) {
             if (!workspace || workspace_bytes < kCounterBytes + pl.partial_bytes) return MORPH_ERR_WORKSPACE;

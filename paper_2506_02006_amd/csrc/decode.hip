@@ -13,6 +13,10 @@ namespace morph {
 
 namespace {
 
+constexpr int kScatterBase = 8192;                       // the polled counters sit behind the plain ones, 32 ints apart
+constexpr int kScatterTiles = 256;                       // as many tiles as have a line there
+constexpr int kScatterPolls = 4096;                      // bound of the wait for the other workgroups of a tile
+
 template <int Q, int MT, int kWaves, bool NT>
 __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kernel(DecodeArgs p)
 {
@@ -104,7 +108,60 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     MORPH_TICK(3);
     __syncthreads();                                     // every wave is done reading yl
     int* flag = reinterpret_cast<int*>(yl);
-    if (tid == 0) *flag = (atomicAdd(p.counters + tile_id, 1) == S - 1) ? 1 : 0;
+    if (p.scatter) {
+        // The sum over the splits is shared out: every workgroup of the tile waits (a bounded number
+        // of polls) until all S partials are there and then adds up its own S-th of the tile, instead
+        // of the last arriver adding up all of it alone.  Correctness never depends on the wait: every
+        // workgroup ends by adding its "done" bit to a second counter, and the last one to do so adds
+        // up whatever parts are still missing (a workgroup that gave up waiting leaves its part) and
+        // puts both counters back to zero; by then nobody polls any more.  Sums run over the splits in
+        // index order whoever computes them.
+        int* arrive = p.counters + kScatterBase + tile_id * 32;   // a 128-byte line of its own per tile: up to 16 workgroups poll it
+        int* depart = arrive + 16;
+        if (tid == 0) {
+            const int c = __hip_atomic_fetch_add(arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int complete = c == S - 1;
+            for (int i = 0; !complete && i < p.polls; i++) {
+                complete = __hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) >= S;
+                __builtin_amdgcn_s_sleep(4);
+            }
+            *flag = complete;
+        }
+        __syncthreads();
+        const int complete = *flag;
+        __syncthreads();                                 // the flag word is written again below
+        constexpr int NVEC = ITEMS / 64;                 // vectors of 64 lanes in the tile
+        auto reduce_part = [&](int j) {
+            const int v0 = (j * NVEC) / S, v1 = ((j + 1) * NVEC) / S;
+            for (int it = v0 * 64 + tid; it < v1 * 64; it += kWaves * 64) {
+                if (!item_rows_live(it)) continue;
+                f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int s2 = 0; s2 < S; s2 += 8) {
+                    f32x4 v[8];
+#pragma unroll
+                    for (int q = 0; q < 8; q++)            // splits beyond S read past the buffer and come back as zeros
+                        v[q] = bit_cast<f32x4>(__builtin_amdgcn_raw_buffer_load_b128(rp, (uint32_t)it * 16u, (uint32_t)(s2 + q) * kPartBytes, kAuxSystemScope));
+#pragma unroll
+                    for (int q = 0; q < 8; q++) a += v[q];
+                }
+                item_store_y(it, a);
+            }
+        };
+        if (complete) reduce_part(sp);
+        if (tid == 0) {
+            const int old = __hip_atomic_fetch_add(depart, 1 | (complete << (8 + sp)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = (old & 0xFF) == S - 1 ? (0x10000 | (((old >> 8) | (complete << sp)) & 0xFFFF)) : 0;
+        }
+        __syncthreads();
+        const int last = *flag;
+        if (last) {
+            for (int j = 0; j < S; j++)
+                if (!((last >> j) & 1)) reduce_part(j);  // parts whose owner gave up waiting: normally none
+            if (tid == 0) { atomicExch(arrive, 0); atomicExch(depart, 0); }
+        }
+        return;
+    }
+    if (tid == 0) *flag = (atomicAdd(p.counters + tile_id * p.cstride, 1) == S - 1) ? 1 : 0;
     __syncthreads();
     MORPH_TICK(4);
     if (!*flag) return;
@@ -127,7 +184,7 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
             }
             item_store_y(it, a);
         }
-        if (tid == 0) atomicExch(p.counters + tile_id, 0);
+        if (tid == 0) atomicExch(p.counters + tile_id * p.cstride, 0);
         MORPH_TICK(5);
         return;
     }
@@ -161,7 +218,7 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
         const int it = tid + i * kWaves * 64;
         if (item_rows_live(it)) item_store_y(it, acc[i]);
     }
-    if (tid == 0) atomicExch(p.counters + tile_id, 0);
+    if (tid == 0) atomicExch(p.counters + tile_id * p.cstride, 0);
     MORPH_TICK(5);
 }
 
@@ -188,6 +245,7 @@ hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
     DecodeArgs b = a;
     b.tiles  = (a.N + tnb - 1) / tnb;
     b.slices = slices;
+    b.cstride = b.tiles * slices <= 256 ? 32 : b.tiles * slices <= 512 ? 16 : 1;   // a cache line per arrival counter while they fit
     const int units = b.tiles * a.S;
     const int grid  = units * slices;
     hipLaunchKernelGGL((decode_kernel<Q, MT, kWaves, NT>), dim3(grid), dim3(kWaves * 64), lds, st, b);
@@ -259,6 +317,12 @@ DecodePlan plan_rows(int q, int M, int K, int N, int rows)
     // Non-temporal weight loads where one workgroup alone reads its rows, once: measured on graphs
     // that cycle through 1.26 GB of 7B layers, fp16 5.6 % and W4 2 % faster.  Never where slices,
     // or the two column halves of the 4-bit two-tile kernel, meet in the caches (up to 17 % slower).
+    // Sharing the sum over the splits out among the workgroups of a tile pays where that sum is long
+    // (measured: 4 .. 14 % at 16 to 64 rows, a loss of 3 % at 8): from 16 rows on and with at least
+    // three splits (16 at most: one bit per split in a counter; 256 tiles at most: a line each).
+    const int sc = tuning_get(TUNE_DECODE_SCATTER);
+    pl.scatter = S >= 2 && S <= 16 && units <= kScatterTiles && (sc == 1 || sc == 3 || (sc == 0 && S >= 3 && M >= 16));
+    pl.polls   = sc == 3 ? 0 : kScatterPolls;          // 3: nobody waits, so that the last one out has every part left to do (test hook)
     const int nt = tuning_get(TUNE_DECODE_STREAM);
     pl.stream_loads = nt ? (nt == 1 && (rows == 16 || q != 1)) : (pl.slices == 1 && (rows == 16 || q != 1));
     return pl;

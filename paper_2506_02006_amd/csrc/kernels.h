@@ -22,13 +22,16 @@ struct DecodeArgs {
     const void*     qzeros;    // uint32 [K/128,N/8]  (W4 only)
     void*           y;         // fp16 [M,N]
     float*          partial;   // [slices * tiles][S][rows][tile columns] fp32, used when S > 1
-    int*            counters;  // [slices * tiles], zero on entry, zero on exit
+    int*            counters;  // one per (slice, tile) at [t]; polled pairs at [8192 + 32 t]; zero on entry, zero on exit
     int             M, K, N;
     int             S;         // workgroups sharing one column tile (split along K)
     int             rows;      // rows per slice, 16 or 32 (from the plan)
     int             stream_loads;  // weights loaded non-temporally (from the plan; one-tile kernels only)
+    int             scatter;   // the sum over the splits is shared out among the workgroups of a tile (from the plan)
+    int             polls;     // bound of the wait for the other workgroups of a tile (from the plan)
     int             tiles;     // column tiles (set by launch_decode)
     int             slices;    // row slices (set by launch_decode)
+    int             cstride;   // ints between the arrival counters of two tiles (set by launch_decode)
 };
 struct DecodePlan {
     int    tile_n;             // columns per workgroup
@@ -39,6 +42,8 @@ struct DecodePlan {
     size_t partial_bytes;      // 0 when S == 1
     double est_us;             // estimated time of the parts of a launch that depend on the plan
     int    stream_loads;       // load the weights non-temporally
+    int    scatter;            // share the sum over the splits out among the workgroups of a tile
+    int    polls;              // how many times a workgroup looks for the others before it gives up
 };
 constexpr size_t kCounterBytes = 65536;  // head of the workspace: arrival counters (one per column tile and row slice)
 // q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes (the MORPH_KIND_* values)
@@ -110,6 +115,6 @@ hipError_t launch_probe_mfma(int iters, void* out, hipStream_t st);
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_COUNT = 12 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_DECODE_SCATTER = 9, TUNE_COUNT = 12 };
 
 }  // namespace morph

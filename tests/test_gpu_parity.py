@@ -407,3 +407,32 @@ def test_probe_kernels_touch_what_they_claim(B):
     per_wave = 4 * iters * (A @ Bm).sum()
     waves = host(fout).reshape(-1, 64).sum(axis=1)
     assert np.all(waves == per_wave), (waves[:4], per_wave)
+
+
+@pytest.mark.parametrize("mode", [1, 3], ids=["shared_out", "nobody_waits"])
+def test_decode_sum_over_splits_either_way(B, oracle, mode):
+    """The sum over the K splits is either shared out among the workgroups of a tile or done by the
+    last arriver alone; both give the same bits (same order of summation).  In the second variant no
+    workgroup waits for the others (the bound of the wait is set to zero from the host), so the last
+    one out finds every part but its own left over and does them: the path after a wait that ran out."""
+    shapes = [(5, 1792, 520), (16, 4096, 264), (33, 1792, 776), (64, 2048, 520)]
+    outs = {}
+    for m in (mode, 2):
+        B.set_tuning(B.TUNE_DECODE_SCATTER, m)
+        try:
+            for (M, K, N) in shapes:
+                check_w4(B, oracle, M, K, N, seed=M)
+                check_fp16(B, oracle, M, K, N, seed=M)
+                W = rand_w(M, K, N)
+                x = synth.activations(77, M, K, layer_id=M)
+                qw, sc, qz = oracle.quantize_w4(W)
+                ws = make_ws(B, B.KIND_W4A16, M, K, N)
+                y = B.linear_w4a16(dev(x), dev(qw), dev(sc), dev(qz), ws)
+                y2 = B.linear_w4a16(dev(x), dev(qw), dev(sc), dev(qz), ws)      # the same workspace again: counters were left at zero
+                torch.cuda.synchronize()
+                assert np.array_equal(host(y).view(np.uint16), host(y2).view(np.uint16))
+                outs.setdefault((M, K, N), []).append(host(y))
+        finally:
+            B.set_tuning(B.TUNE_DECODE_SCATTER, 0)
+    for k, (a, b) in outs.items():
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16)), k
