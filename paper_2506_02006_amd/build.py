@@ -16,8 +16,9 @@ LIB = os.path.join(HERE, "libmorph.so")
 SOURCES = ["api.hip", "quant.hip", "decode.hip", "prefill.hip", "glue.hip", "stack.hip"]
 
 # -packed-fp32-ops off: keep the compiler from forming packed fp32 instructions.
+# -amdgpu-kernarg-preload-count: leading scalar kernel arguments arrive in registers at wave launch.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _hipcc() -> str:

@@ -17,9 +17,27 @@ constexpr int kScatterBase = 8192;                       // the polled counters 
 constexpr int kScatterTiles = 256;                       // as many tiles as have a line there
 constexpr int kScatterPolls = 4096;                      // bound of the wait for the other workgroups of a tile
 
+// What a workgroup needs before its first load comes as scalar arguments, first in the list: the
+// compiler has them preloaded into scalar registers at wave launch (kernarg preload), so the start
+// does not wait for a load of the argument block from memory.  The rest (used at the hand-over)
+// follows in a structure that is fetched when it is needed.
+struct DecodeTail {
+    void*  y;
+    float* partial;
+    int*   counters;
+    int    rows, stream_loads, scatter, polls, cstride;
+};
+
 template <int Q, int MT, int kWaves, bool NT>
-__global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kernel(DecodeArgs p)
+__global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kernel(
+    const void* w, const void* x, const void* scales, const void* qzeros, int Ktot, int Ntot, int Mtot, int Stot,
+    int tiles, int slices, DecodeTail t)
 {
+    DecodeArgs p;
+    p.w = w; p.x = x; p.scales = scales; p.qzeros = qzeros; p.K = Ktot; p.N = Ntot; p.M = Mtot; p.S = Stot;
+    p.tiles = tiles; p.slices = slices;
+    p.y = t.y; p.partial = t.partial; p.counters = t.counters; p.rows = t.rows; p.stream_loads = t.stream_loads;
+    p.scatter = t.scatter; p.polls = t.polls; p.cstride = t.cstride;
     MORPH_TICK(6);                                       // kernel entry
     typedef TileGeom<Q, MT, kWaves> G;
     constexpr int CPL = G::CPL, TN = G::TN, TNB = G::TNB, NV = G::NV, ITEMS = G::ITEMS;
@@ -248,7 +266,11 @@ hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
     b.cstride = b.tiles * slices <= 256 ? 32 : b.tiles * slices <= 512 ? 16 : 1;   // a cache line per arrival counter while they fit
     const int units = b.tiles * a.S;
     const int grid  = units * slices;
-    hipLaunchKernelGGL((decode_kernel<Q, MT, kWaves, NT>), dim3(grid), dim3(kWaves * 64), lds, st, b);
+    DecodeTail t;
+    t.y = b.y; t.partial = b.partial; t.counters = b.counters; t.rows = b.rows; t.stream_loads = b.stream_loads;
+    t.scatter = b.scatter; t.polls = b.polls; t.cstride = b.cstride;
+    hipLaunchKernelGGL((decode_kernel<Q, MT, kWaves, NT>), dim3(grid), dim3(kWaves * 64), lds, st, b.w, b.x, b.scales,
+                       b.qzeros, b.K, b.N, b.M, b.S, b.tiles, b.slices, t);
     return hipGetLastError();
 }
 
