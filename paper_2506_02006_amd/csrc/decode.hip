@@ -331,20 +331,23 @@ DecodePlan plan_rows(int q, int M, int K, int N, int rows)
     pl.partial_bytes = S > 1 ? (size_t)units * S * tile_floats * sizeof(float) : 0;
     // Estimate (microseconds, W4 constants measured on MI355X): the rows of K one workgroup walks at
     // the rate its waves unpack them, or the weights at the rate strips of them leave memory when
-    // that is slower; then the hand-over, whose last arriver reads S partial tiles on its own.
+    // that is slower; then the hand-over.
     const double wgs = (double)units * S, fill = wgs < 256.0 ? wgs / 256.0 : 1.0;
     const double walk = ((double)K / S) * (rows > 16 ? 6.7e-3 : 3.24e-3) * (double)(((long long)wgs + 255) / 256);
     const double hbm  = ((double)K * N * 0.5) / (4.6e6 * fill);
-    pl.est_us = (walk > hbm ? walk : hbm) + (S > 1 ? 1.5 + (double)S * tile_floats * 4.0 / 2.0e5 : 0.0);
-    // Non-temporal weight loads where one workgroup alone reads its rows, once: measured on graphs
-    // that cycle through 1.26 GB of 7B layers, fp16 5.6 % and W4 2 % faster.  Never where slices,
-    // or the two column halves of the 4-bit two-tile kernel, meet in the caches (up to 17 % slower).
     // Sharing the sum over the splits out among the workgroups of a tile pays where that sum is long
     // (measured: 4 .. 14 % at 16 to 64 rows, a loss of 3 % at 8): from 16 rows on and with at least
     // three splits (16 at most: one bit per split in a counter; 256 tiles at most: a line each).
     const int sc = tuning_get(TUNE_DECODE_SCATTER);
     pl.scatter = S >= 2 && S <= 16 && units <= kScatterTiles && (sc == 1 || sc == 3 || (sc == 0 && S >= 3 && M >= 16));
     pl.polls   = sc == 3 ? 0 : kScatterPolls;          // 3: nobody waits, so that the last one out has every part left to do (test hook)
+    // hand-over: the last arriver reads S partial tiles on its own, or every workgroup one tile's worth
+    const double handover = S <= 1 ? 0.0 : pl.scatter ? 2.3 + (double)tile_floats * 4.0 / 2.0e5
+                                                       : 1.5 + (double)S * tile_floats * 4.0 / 2.0e5;
+    pl.est_us = (walk > hbm ? walk : hbm) + handover;
+    // Non-temporal weight loads where one workgroup alone reads its rows, once: measured on graphs
+    // that cycle through 1.26 GB of 7B layers, fp16 5.6 % and W4 2 % faster.  Never where slices,
+    // or the two column halves of the 4-bit two-tile kernel, meet in the caches (up to 17 % slower).
     const int nt = tuning_get(TUNE_DECODE_STREAM);
     pl.stream_loads = nt ? (nt == 1 && (rows == 16 || q != 1)) : (pl.slices == 1 && (rows == 16 || q != 1));
     return pl;
