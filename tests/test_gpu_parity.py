@@ -182,7 +182,7 @@ def test_mid_sizes_in_either_kernel_family(B, oracle, M, max_m):
 
 
 @pytest.mark.parametrize("rows", [16, 32, 0], ids=["slices16", "slices32", "auto"])
-@pytest.mark.parametrize("M", [17, 40, 64])
+@pytest.mark.parametrize("M", [3, 17, 40, 64])
 def test_decode_either_slice_height(B, oracle, M, rows):
     """A streaming workgroup takes 16 or 32 rows; above 16 rows the library picks per shape.  Both
     heights are forced in turn (a partly filled last slice included), with and without a split
