@@ -25,6 +25,8 @@ What is computed (paper Section 4.3, footnote: weight-only INT4; Section 5.2:
                        and zeros, four per word along N
   cosine / LIS     O10 the layer-importance metrics (Section 4.2, Eq. 2-5): cosine similarity of
                        activations, token by token, averaged; LIS = a1 LTS + a2 LRS + b MDS
+  *_bf16           O11 the same linear maps with x, dense weights and y in bfloat16 (arrays of
+                       numpy.uint16 bit patterns: numpy has no bfloat16); records unchanged
   layer record     O8  the bytes of one layer (its four linears, in either form) as
                        they sit in the pinned host pool and in the layer's device slot,
                        and what an in-place swap leaves in the slot (Section 4.3,
@@ -271,6 +273,95 @@ def linear_w8a16_at(x, qw, sc, qz, rows, cols, G: int = 128) -> np.ndarray:
     _load().oracle_linear_w8a16_at(_p(x.view(np.uint16), _u16p), _p(qw, _u32p), _p(sc.view(np.uint16), _u16p),
                                    _p(qz, _u32p), K, N, G, _p(rows, _i32p), _p(cols, _i32p),
                                    ctypes.c_int64(rows.size), _p(out, _f64p))
+    return out
+
+
+# ---------------- O11: bfloat16 tensors (uint16 bit patterns) ----------------
+
+def fp32_to_bf16(f: np.ndarray) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns (uint16), round to nearest even."""
+    f = _c(f, np.float32)
+    b = np.empty(f.shape, np.uint16)
+    _load().oracle_fp32_to_bf16(_p(f, _f32p), _p(b, _u16p), ctypes.c_int64(f.size))
+    return b
+
+
+def bf16_to_fp32(b: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> float32, exact."""
+    b = _c(b, np.uint16)
+    f = np.empty(b.shape, np.float32)
+    _load().oracle_bf16_to_fp32(_p(b, _u16p), _p(f, _f32p), ctypes.c_int64(b.size))
+    return f
+
+
+def dequant_bf16(bits: int, qw, sc, qz, G: int = 128) -> np.ndarray:
+    """(q - z) * s rounded once to bfloat16 -> uint16 bit patterns [K,N]; bits = 4 or 8."""
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    assert bits in (4, 8)
+    K, N = qw.shape[0], qw.shape[1] * (32 // bits)
+    D = np.empty((K, N), np.uint16)
+    _load().oracle_dequant_bf16(bits, _p(qw, _u32p), _p(sc.view(np.uint16), _u16p), _p(qz, _u32p), K, N, G, _p(D, _u16p))
+    return D
+
+
+def linear_q_bf16(bits: int, x, qw, sc, qz, G: int = 128) -> np.ndarray:
+    """x bfloat16 patterns [M,K] times the 4- or 8-bit record -> y float64 [M,N], k ascending."""
+    x = _c(x, np.uint16)
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    assert bits in (4, 8)
+    M, K = x.shape
+    N = qw.shape[1] * (32 // bits)
+    assert qw.shape[0] == K and sc.shape == ((K + G - 1) // G, N)
+    y = np.empty((M, N), np.float64)
+    _load().oracle_linear_q_a16(_p(x, _u16p), 1, bits, _p(qw, _u32p), _p(sc.view(np.uint16), _u16p), _p(qz, _u32p),
+                                M, K, N, G, _p(y, _f64p))
+    return y
+
+
+def linear_q_bf16_at(bits: int, x, qw, sc, qz, rows, cols, G: int = 128) -> np.ndarray:
+    """The same at sampled output positions."""
+    x = _c(x, np.uint16)
+    qw = _c(qw, np.uint32)
+    sc = _c(sc, np.float16)
+    qz = _c(qz, np.uint32)
+    rows = np.ascontiguousarray(rows, np.int32)
+    cols = np.ascontiguousarray(cols, np.int32)
+    M, K = x.shape
+    N = qw.shape[1] * (32 // bits)
+    assert rows.shape == cols.shape and rows.min() >= 0 and rows.max() < M and cols.min() >= 0 and cols.max() < N
+    out = np.empty(rows.shape, np.float64)
+    _load().oracle_linear_q_a16_at(_p(x, _u16p), 1, bits, _p(qw, _u32p), _p(sc.view(np.uint16), _u16p), _p(qz, _u32p),
+                                   K, N, G, _p(rows, _i32p), _p(cols, _i32p), ctypes.c_int64(rows.size), _p(out, _f64p))
+    return out
+
+
+def linear_bf16(x, w) -> np.ndarray:
+    """x [M,K], w [K,N] bfloat16 patterns -> y float64 [M,N], k ascending."""
+    x = _c(x, np.uint16)
+    w = _c(w, np.uint16)
+    M, K = x.shape
+    assert w.shape[0] == K
+    N = w.shape[1]
+    y = np.empty((M, N), np.float64)
+    _load().oracle_linear_dense16(_p(x, _u16p), _p(w, _u16p), 1, M, K, N, _p(y, _f64p))
+    return y
+
+
+def linear_bf16_at(x, w, rows, cols) -> np.ndarray:
+    x = _c(x, np.uint16)
+    w = _c(w, np.uint16)
+    rows = np.ascontiguousarray(rows, np.int32)
+    cols = np.ascontiguousarray(cols, np.int32)
+    M, K = x.shape
+    N = w.shape[1]
+    assert rows.shape == cols.shape and rows.min() >= 0 and rows.max() < M and cols.min() >= 0 and cols.max() < N
+    out = np.empty(rows.shape, np.float64)
+    _load().oracle_linear_dense16_at(_p(x, _u16p), _p(w, _u16p), 1, K, N, _p(rows, _i32p), _p(cols, _i32p),
+                                     ctypes.c_int64(rows.size), _p(out, _f64p))
     return out
 
 

@@ -396,6 +396,137 @@ void oracle_linear_w8a16_at(const uint16_t *x, const uint32_t *qweight,
     }
 }
 
+/* ---------- O11: bfloat16 activations and outputs ----------
+ * The same linear maps with the 16-bit tensors (x, dense weights, y) in bfloat16 instead of
+ * fp16, the format the models the paper serves are published in (Section 5.1 lists Llama 2 and
+ * Llama 3 checkpoints); the quantized records are unchanged (their scales stay fp16).
+ * bfloat16 = the upper 16 bits of a binary32: 1 sign, 8 exponent, 7 fraction bits.
+ * `fmt` below names the 16-bit format of a tensor: 0 = fp16, 1 = bfloat16.
+ */
+
+/* bfloat16 -> binary32: exact, the pattern is the upper half of the word. */
+static float b2f(uint16_t b)
+{
+    uint32_t bits = (uint32_t)b << 16;
+    float    f;
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+/* binary32 -> bfloat16, round to nearest, ties to even.  The 16 dropped bits are compared with
+ * one half (0x8000) of the kept unit; a carry out of the fraction moves into the exponent, and
+ * out of the largest finite exponent into infinity, which is what rounding means there.
+ * NaN stays NaN (quiet bit set so that a payload in the dropped bits cannot turn it into inf). */
+static uint16_t f2b(float f)
+{
+    uint32_t x;
+    memcpy(&x, &f, 4);
+    if ((x & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((x >> 16) | 0x0040u);
+    uint32_t keep = x >> 16, rem = x & 0xFFFFu;
+    if (rem > 0x8000u || (rem == 0x8000u && (keep & 1u))) keep++;
+    return (uint16_t)keep;
+}
+
+void oracle_bf16_to_fp32(const uint16_t *b, float *f, int64_t n)
+{
+    for (int64_t i = 0; i < n; i++) f[i] = b2f(b[i]);
+}
+
+void oracle_fp32_to_bf16(const float *f, uint16_t *b, int64_t n)
+{
+    for (int64_t i = 0; i < n; i++) b[i] = f2b(f[i]);
+}
+
+static inline double a2d(uint16_t v, int fmt)
+{
+    return (double)(fmt ? b2f(v) : h2f(v));
+}
+
+static inline float dqb(int bits, const uint32_t *qweight, const uint16_t *scales,
+                        const uint32_t *qzeros, int N, int G, int k, int n)
+{
+    return bits == 8 ? dq8(qweight, scales, qzeros, N, G, k, n) : dq(qweight, scales, qzeros, N, G, k, n);
+}
+
+/* D [K,N] as bfloat16: the exact (q - z) * s rounded once (RNE).  bits = 4 or 8. */
+void oracle_dequant_bf16(int bits, const uint32_t *qweight, const uint16_t *scales,
+                         const uint32_t *qzeros, int K, int N, int G, uint16_t *D)
+{
+    for (int k = 0; k < K; k++)
+        for (int n = 0; n < N; n++)
+            D[(size_t)k * N + n] = f2b(dqb(bits, qweight, scales, qzeros, N, G, k, n));
+}
+
+/* y [M,N] fp64 = sum over ascending k of x[m,k] * D32[k,n]; x in format xfmt, bits = 4 or 8. */
+void oracle_linear_q_a16(const uint16_t *x, int xfmt, int bits, const uint32_t *qweight,
+                         const uint16_t *scales, const uint32_t *qzeros,
+                         int M, int K, int N, int G, double *y)
+{
+    const int CB = 256;
+    int nblk = (N + CB - 1) / CB;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < nblk; b++) {
+        int n0 = b * CB, n1 = (n0 + CB < N) ? n0 + CB : N;
+        for (int m = 0; m < M; m++) {
+            double *ym = y + (size_t)m * N;
+            for (int n = n0; n < n1; n++) ym[n] = 0.0;
+            for (int k = 0; k < K; k++) {
+                double xv = a2d(x[(size_t)m * K + k], xfmt);
+                for (int n = n0; n < n1; n++)
+                    ym[n] += xv * (double)dqb(bits, qweight, scales, qzeros, N, G, k, n);
+            }
+        }
+    }
+}
+
+void oracle_linear_q_a16_at(const uint16_t *x, int xfmt, int bits, const uint32_t *qweight,
+                            const uint16_t *scales, const uint32_t *qzeros, int K, int N, int G,
+                            const int32_t *rows, const int32_t *cols, int64_t count, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; i++) {
+        int m = rows[i], n = cols[i];
+        double acc = 0.0;
+        for (int k = 0; k < K; k++)
+            acc += a2d(x[(size_t)m * K + k], xfmt) * (double)dqb(bits, qweight, scales, qzeros, N, G, k, n);
+        y[i] = acc;
+    }
+}
+
+/* y [M,N] fp64 = sum over ascending k of x[m,k] * w[k,n], both tensors in format fmt. */
+void oracle_linear_dense16(const uint16_t *x, const uint16_t *w, int fmt,
+                           int M, int K, int N, double *y)
+{
+    const int CB = 256;
+    int nblk = (N + CB - 1) / CB;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < nblk; b++) {
+        int n0 = b * CB, n1 = (n0 + CB < N) ? n0 + CB : N;
+        for (int m = 0; m < M; m++) {
+            double *ym = y + (size_t)m * N;
+            for (int n = n0; n < n1; n++) ym[n] = 0.0;
+            for (int k = 0; k < K; k++) {
+                double xv = a2d(x[(size_t)m * K + k], fmt);
+                const uint16_t *wk = w + (size_t)k * N;
+                for (int n = n0; n < n1; n++) ym[n] += xv * a2d(wk[n], fmt);
+            }
+        }
+    }
+}
+
+void oracle_linear_dense16_at(const uint16_t *x, const uint16_t *w, int fmt, int K, int N,
+                              const int32_t *rows, const int32_t *cols, int64_t count, double *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < count; i++) {
+        int m = rows[i], n = cols[i];
+        double acc = 0.0;
+        for (int k = 0; k < K; k++)
+            acc += a2d(x[(size_t)m * K + k], fmt) * a2d(w[(size_t)k * N + n], fmt);
+        y[i] = acc;
+    }
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

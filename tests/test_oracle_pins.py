@@ -7,6 +7,8 @@ Pin names (used in the oracle's documentation):
   P3 brute force with exact rationals   P4 closed forms (ones, one-hot)
   P5 identity activations               P6 numpy float64 matmul
   P7 the paper's layer sizes            P8 quantization-noise level (sanity)
+  P9 layer records and swap             P10 the 8-bit variant
+  P11 cosine / importance score         P12 bfloat16 tensors
 """
 import os
 from fractions import Fraction
@@ -613,3 +615,131 @@ def test_p11_lis_weights_are_the_papers(oracle):
     lis = oracle.layer_importance([1.0, 0.0, 0.0, 0.2], [0.0, 1.0, 0.0, 0.4], [0.0, 0.0, 1.0, 0.8])
     assert np.allclose(lis, [0.25, 0.25, 0.5, 0.05 + 0.1 + 0.4])
     assert oracle.layer_importance([1.0], [1.0], [1.0])[0] == 1.0                    # identical activations everywhere
+
+
+# ---------- P12 bfloat16 tensors (O11) ----------
+# Pinned to things the oracle does not compute itself: torch's CPU bfloat16 conversion (a library
+# routine), the definition of the format written out with exact rationals, exact rational dot
+# products, numpy's float64 matmul, and identity activations.
+
+def bf16_to_fraction(bits: int) -> Fraction:
+    """The value of a finite bfloat16 pattern from the definition: 1 sign, 8 exponent (bias 127),
+    7 fraction bits; exponent field 0 = subnormal."""
+    sign = -1 if bits & 0x8000 else 1
+    e, m = (bits >> 7) & 0xFF, bits & 0x7F
+    assert e != 255
+    if e == 0:
+        return sign * Fraction(m, 128) * Fraction(2) ** -126
+    return sign * (1 + Fraction(m, 128)) * Fraction(2) ** (e - 127)
+
+
+def test_p12_bf16_to_fp32_all_patterns(oracle):
+    torch = pytest.importorskip("torch")
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    got = oracle.bf16_to_fp32(bits)
+    want = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+    # and against the definition of the format, on a spread of finite patterns
+    for b in list(range(0, 0x7F80, 997)) + [0x0001, 0x007F, 0x0080, 0x3F80, 0x7F7F, 0x8001, 0xBF80, 0xFF7F]:
+        assert Fraction(float(got[b])) == bf16_to_fraction(b), hex(b)
+
+
+def test_p12_fp32_to_bf16_matches_torch_rne(oracle):
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(12)
+    parts = [rng.standard_normal(100000, dtype=np.float32) * np.float32(s) for s in (1e-39, 1e-30, 1e-3, 1.0, 300.0, 1e30, 5e37)]
+    # every finite bfloat16 value, the midpoint to its upper neighbour (a tie) and its two float32 neighbours
+    b = np.arange(0x7F7F, dtype=np.uint32)
+    mid = ((b << 16) | 0x8000).astype(np.uint32)
+    ties = np.concatenate([mid, mid - 1, mid + 1, (b << 16).astype(np.uint32)]).view(np.float32)
+    special = np.array([0.0, -0.0, np.inf, -np.inf, 3.3895314e38, 3.4028235e38, -3.4028235e38, 1e-45, -1e-45], np.float32)
+    f = np.concatenate(parts + [ties, -ties, special])
+    got = oracle.fp32_to_bf16(f)
+    want = torch.from_numpy(f).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    # a tie goes to the even neighbour, both ways (written out)
+    one_and_half_ulp = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8], np.float32)     # between 1, 1+2^-7, 1+2^-6
+    assert oracle.fp32_to_bf16(one_and_half_ulp).tolist() == [0x3F80, 0x3F82]
+    # NaN stays NaN whatever its payload
+    nan = np.array([0x7F800001, 0x7FC00000, 0xFF80FFFF], np.uint32).view(np.float32)
+    out = oracle.fp32_to_bf16(nan)
+    assert all((int(v) & 0x7F80) == 0x7F80 and (int(v) & 0x7F) != 0 for v in out)
+    # round trip: every bfloat16 value is a fixed point
+    allb = np.arange(0x7F80, dtype=np.uint32).astype(np.uint16)
+    assert np.array_equal(oracle.fp32_to_bf16(oracle.bf16_to_fp32(allb)), allb)
+
+
+@pytest.mark.parametrize("bits,K,G,M", [(4, 8, 8, 1), (4, 40, 16, 3), (8, 24, 8, 2), (8, 64, 32, 3)])
+def test_p12_quantized_linear_fractions(oracle, bits, K, G, M):
+    rng = np.random.default_rng(bits * 100 + K + M)
+    N, L = 8, 1 << bits
+    NG = (K + G - 1) // G
+    q = rng.integers(0, L, (K, N))
+    z = rng.integers(0, L, (NG, N))
+    sc = rng.uniform(0.001, 0.05, (NG, N)).astype(np.float16)
+    # bfloat16 activations over a range fp16 could not hold (2^-30 .. 2^30), small dyadic mantissas
+    xb = ((rng.integers(0, 2, (M, K)) << 15) | (rng.integers(97, 158, (M, K)) << 7) | rng.integers(0, 128, (M, K))).astype(np.uint16)
+    pack = pack_nibbles if bits == 4 else pack_bytes
+    qw = np.array(pack(q.tolist()), np.uint32)
+    qz = np.array(pack(z.tolist()), np.uint32)
+    y = oracle.linear_q_bf16(bits, xb, qw, sc, qz, G)
+    Db = oracle.dequant_bf16(bits, qw, sc, qz, G)
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(0)
+            for k in range(K):
+                d = (int(q[k, n]) - int(z[k // G, n])) * half_to_fraction(sc[k // G, n])
+                acc += bf16_to_fraction(int(xb[m, k])) * d
+                if m == 0:
+                    # the bfloat16 form of a weight: nearest representable value, within half a unit of the exact one
+                    v = bf16_to_fraction(int(Db[k, n]))
+                    lo = bf16_to_fraction(int(Db[k, n]) & 0x7FFF)
+                    ulp = bf16_to_fraction((int(Db[k, n]) & 0x7FFF) + 1) - lo if (int(Db[k, n]) & 0x7FFF) < 0x7F7F else None
+                    assert ulp is None or abs(v - d) <= ulp / 2, (k, n)
+            # the terms span 60 binades: the fp64 sum is compared with the exact one at fp64's own precision
+            terms_max = max(abs(bf16_to_fraction(int(xb[m, k]))) for k in range(K)) * L * Fraction(float(sc.max()))
+            assert abs(Fraction(float(y[m, n])) - acc) <= terms_max * K * Fraction(1, 2 ** 52), (m, n)
+    rows = np.array([0, M - 1]); cols = np.array([N - 1, 0])
+    assert np.array_equal(oracle.linear_q_bf16_at(bits, xb, qw, sc, qz, rows, cols, G), y[rows, cols])
+
+
+def test_p12_dense_linear_fractions_and_matmul(oracle):
+    rng = np.random.default_rng(13)
+    M, K, N = 3, 24, 5
+    xb = oracle.fp32_to_bf16((rng.integers(-8, 9, (M, K)) / 8).astype(np.float32))
+    wb = oracle.fp32_to_bf16((rng.integers(-64, 65, (K, N)) / 256).astype(np.float32))
+    y = oracle.linear_bf16(xb, wb)
+    for m in range(M):
+        for n in range(N):
+            acc = sum(bf16_to_fraction(int(xb[m, k])) * bf16_to_fraction(int(wb[k, n])) for k in range(K))
+            assert Fraction(float(y[m, n])) == acc
+    assert np.array_equal(oracle.linear_bf16_at(xb, wb, np.array([0, 2, 1]), np.array([4, 0, 3])), y[[0, 2, 1], [4, 0, 3]])
+    # a transposed operand or a swapped format would show here: numpy float64 matmul of the widened tensors
+    M, K, N = 7, 384, 40
+    xf = rng.standard_normal((M, K)).astype(np.float32)
+    wf = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    xb, wb = oracle.fp32_to_bf16(xf), oracle.fp32_to_bf16(wf)
+    ref = oracle.bf16_to_fp32(xb).astype(np.float64) @ oracle.bf16_to_fp32(wb).astype(np.float64)
+    assert np.allclose(oracle.linear_bf16(xb, wb), ref, rtol=1e-12, atol=1e-13)
+    # the patterns are not fp16: read as fp16 the same bits give a different product
+    assert not np.allclose(oracle.linear_fp16(xb.view(np.float16), wb.view(np.float16)), ref, rtol=1e-3, atol=1e-3)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_p12_identity_and_numpy_matmul(oracle, bits):
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(14 + bits)
+    K, N, M = 256, 40, 5
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float32)
+    qw, sc, qz = (oracle.quantize_w4 if bits == 4 else oracle.quantize_w8)(W)
+    D = (oracle.dequant_w4 if bits == 4 else oracle.dequant_w8)(qw, sc, qz)
+    eye = oracle.fp32_to_bf16(np.eye(K, dtype=np.float32))
+    assert np.array_equal(oracle.linear_q_bf16(bits, eye, qw, sc, qz), D.astype(np.float64))
+    xb = oracle.fp32_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    ref = oracle.bf16_to_fp32(xb).astype(np.float64) @ D.astype(np.float64)
+    assert np.allclose(oracle.linear_q_bf16(bits, xb, qw, sc, qz), ref, rtol=1e-12, atol=1e-12)
+    # bfloat16 form of the weights: one rounding of the exact value (torch's conversion as the second opinion)
+    want = torch.from_numpy(D).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.dequant_bf16(bits, qw, sc, qz), want)
