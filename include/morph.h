@@ -22,6 +22,7 @@
  *     nothing was launched and the outputs are untouched.
  *   - Matrices are row-major.  x, y, w must not overlap.  No bias term.
  *   - fp16 = IEEE binary16.  Accumulation is fp32; outputs are rounded once to fp16.
+ *     (The *_bf16 entry points take bfloat16 where the others take fp16: see there.)
  *   - Built ahead of time for gfx950 only; nothing is compiled at run time.
  *
  * The 4-bit layer record (the "uniform INT4" weight-only flavour, paper Section 5.2
@@ -52,7 +53,7 @@ typedef enum {
 } morph_status;
 
 enum { MORPH_KIND_FP16 = 0, MORPH_KIND_W4A16 = 1, MORPH_KIND_W8A16 = 2 };
-enum { MORPH_DTYPE_F32 = 0, MORPH_DTYPE_F16 = 1 };
+enum { MORPH_DTYPE_F32 = 0, MORPH_DTYPE_F16 = 1, MORPH_DTYPE_BF16 = 2 };
 enum { MORPH_GROUP_SIZE = 128 };
 
 /* ---- y = x * W with fp16 weights (the full-precision layer variant; Section 4.3, Appendix C) ----
@@ -79,7 +80,8 @@ int morph_linear_w4a16(const void* x, const int32_t* qweight, const void* scales
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- produce the 4-bit record of one weight matrix (the variant that gets swapped in) ----
- * w [K,N] in w_dtype (MORPH_DTYPE_F32 or MORPH_DTYPE_F16).  Per (group g, column n):
+ * w [K,N] in w_dtype (MORPH_DTYPE_F32, MORPH_DTYPE_F16 or MORPH_DTYPE_BF16; 16-bit values are
+ * widened exactly).  Per (group g, column n):
  *   lo = min(0, min w), hi = max(0, max w) over the group's 128 rows;
  *   s  = (hi - lo) / 15 rounded UP to fp16, at least 2^-14;   z = clamp(rint(-lo / s), 0, 15);
  *   q  = clamp(rint(w / s) + z, 0, 15)   (IEEE fp32 division, round half to even).
@@ -88,8 +90,8 @@ int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* sca
                          int32_t* qzeros, int K, int N, int group_size, void* stream);
 
 /* ---- verification export: the dequantized matrix itself ----
- * out [K,N] = (q - z) * s, as fp32 (exact: at most 15 significant bits) or as fp16 (that value
- * rounded once, to nearest even).  Not on the serving path. */
+ * out [K,N] = (q - z) * s, as fp32 (exact: at most 15 significant bits) or as fp16 / bfloat16
+ * (that value rounded once, to nearest even).  Not on the serving path. */
 int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_t* qzeros,
                         void* out, int out_dtype, int K, int N, int group_size, void* stream);
 
@@ -112,6 +114,27 @@ int morph_quantize_layer_w8(const void* w, int w_dtype, int32_t* qweight, void* 
                             int32_t* qzeros, int K, int N, int group_size, void* stream);
 int morph_dequantize_w8(const int32_t* qweight, const void* scales, const int32_t* qzeros,
                         void* out, int out_dtype, int K, int N, int group_size, void* stream);
+
+/* ---- the same three linears with bfloat16 activations and outputs ----
+ * (Section 5.1: the models served include Llama 2 and Llama 3 checkpoints, the latter published in
+ * bfloat16; Section 4.3: a layer's variants differ in their weights only, so the activations keep
+ * the model's own 16-bit format.)
+ * x [M,K] and y [M,N] are bfloat16 (1 sign, 8 exponent, 7 fraction bits: the upper half of an
+ * fp32); morph_linear_bf16 also takes w [K,N] in bfloat16.  The 4-bit and 8-bit records are the
+ * ones described above, unchanged (fp16 scales): a layer record serves either activation format.
+ * Accumulation is fp32; y is rounded once, to nearest even.  Decode sizes feed the codes to the
+ * bfloat16 matrix instruction as they are; the LDS-tiled kernels hold (q - z) * s rounded once
+ * to bfloat16.  The quantized kinds multiply x by 2^64 on its way into the matrix cores (the codes
+ * sit at the bottom of the bfloat16 range): |x| must stay below 2^63, beyond that y is inf / NaN.
+ * M dispatch, workspace (same kinds, same sizes), alignment and errors as for the fp16 calls. */
+int morph_linear_bf16(const void* x, const void* w, void* y, int M, int K, int N,
+                      void* workspace, size_t workspace_bytes, void* stream);
+int morph_linear_w4a16_bf16(const void* x, const int32_t* qweight, const void* scales,
+                            const int32_t* qzeros, void* y, int M, int K, int N, int group_size,
+                            void* workspace, size_t workspace_bytes, void* stream);
+int morph_linear_w8a16_bf16(const void* x, const int32_t* qweight, const void* scales,
+                            const int32_t* qzeros, void* y, int M, int K, int N, int group_size,
+                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace a linear call of this kind and shape needs (0 = none).  Host only. */
 size_t morph_workspace_bytes(int kind, int M, int K, int N);

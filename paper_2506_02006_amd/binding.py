@@ -12,7 +12,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmorph.so")
 
 KIND_FP16, KIND_W4A16, KIND_W8A16 = 0, 1, 2
-DTYPE_F32, DTYPE_F16 = 0, 1
+DTYPE_F32, DTYPE_F16, DTYPE_BF16 = 0, 1, 2
+_DTYPES = {torch.float32: DTYPE_F32, torch.float16: DTYPE_F16, torch.bfloat16: DTYPE_BF16}
 GROUP = 128
 GLUE_QKV, GLUE_RESIDUAL, GLUE_SWIGLU, GLUE_RMS = 0, 1, 2, 3
 TUNE_DECODE_SPLIT, TUNE_DECODE_WGS, TUNE_PREFILL_TILE, TUNE_DECODE_WAVES, TUNE_PREFILL_SPLIT, TUNE_PREFILL_MAP, TUNE_DECODE_MAX_M = 0, 1, 2, 3, 4, 5, 6
@@ -29,6 +30,7 @@ EXPORTS = [
     "morph_probe_out_bytes", "morph_probe_read", "morph_probe_mfma",
     "morph_layer_record_bytes", "morph_layer_record_desc", "morph_layer_swap_async",
     "morph_quantize_layer_w8", "morph_dequantize_w8", "morph_linear_w8a16", "morph_cosine_rows",
+    "morph_linear_bf16", "morph_linear_w4a16_bf16", "morph_linear_w8a16_bf16",
 ]
 
 
@@ -64,6 +66,9 @@ def lib() -> ctypes.CDLL:
     L.morph_quantize_layer.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w4.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_linear_w8a16.argtypes = L.morph_linear_w4a16.argtypes
+    L.morph_linear_bf16.argtypes = L.morph_linear_fp16.argtypes
+    L.morph_linear_w4a16_bf16.argtypes = L.morph_linear_w4a16.argtypes
+    L.morph_linear_w8a16_bf16.argtypes = L.morph_linear_w4a16.argtypes
     L.morph_cosine_rows.argtypes = [vp, vp, vp, vp, i, i, vp]
     L.morph_quantize_layer_w8.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w8.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
@@ -142,6 +147,40 @@ def _ws_args(ws):
     return ws.data_ptr(), ws.numel()
 
 
+def linear_bf16(x: torch.Tensor, w: torch.Tensor, ws=None, out=None) -> torch.Tensor:
+    """x [M,K], w [K,N] bfloat16 -> y [M,N] bfloat16."""
+    M, K = x.shape
+    K2, N = w.shape
+    assert K == K2
+    y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    wp, wb = _ws_args(ws)
+    _check(lib().morph_linear_bf16(_dev(x, torch.bfloat16, "x"), _dev(w, torch.bfloat16, "w"),
+                                   _dev(y, torch.bfloat16, "y"), M, K, N, wp, wb, _stream()), "morph_linear_bf16")
+    return y
+
+
+def _linear_quant_bf16(fn_name: str, per_word: int, x, qweight, scales, qzeros, ws, out, group_size):
+    M, K = x.shape
+    N = scales.shape[1]
+    assert qweight.shape == (K, N // per_word), (qweight.shape, K, N)
+    y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    wp, wb = _ws_args(ws)
+    _check(getattr(lib(), fn_name)(_dev(x, torch.bfloat16, "x"), _dev(qweight, torch.int32, "qweight"),
+                                   _dev(scales, torch.float16, "scales"), _dev(qzeros, torch.int32, "qzeros"),
+                                   _dev(y, torch.bfloat16, "y"), M, K, N, group_size, wp, wb, _stream()), fn_name)
+    return y
+
+
+def linear_w4a16_bf16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:
+    """x bfloat16 [M,K] times the 4-bit record (fp16 scales) -> y bfloat16 [M,N]."""
+    return _linear_quant_bf16("morph_linear_w4a16_bf16", 8, x, qweight, scales, qzeros, ws, out, group_size)
+
+
+def linear_w8a16_bf16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:
+    """x bfloat16 [M,K] times the 8-bit record (fp16 scales) -> y bfloat16 [M,N]."""
+    return _linear_quant_bf16("morph_linear_w8a16_bf16", 4, x, qweight, scales, qzeros, ws, out, group_size)
+
+
 def linear_fp16(x: torch.Tensor, w: torch.Tensor, ws=None, out=None) -> torch.Tensor:
     M, K = x.shape
     K2, N = w.shape
@@ -180,14 +219,11 @@ def linear_w8a16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int 
 
 
 def quantize_layer(w: torch.Tensor, group_size: int = GROUP):
-    """w [K,N] float32 or float16 on the GPU -> (qweight int32 [K,N/8], scales fp16 [K/128,N], qzeros int32 [K/128,N/8])."""
+    """w [K,N] float32, float16 or bfloat16 on the GPU -> (qweight int32 [K,N/8], scales fp16 [K/128,N], qzeros int32 [K/128,N/8])."""
     K, N = w.shape
-    if w.dtype == torch.float32:
-        dt = DTYPE_F32
-    elif w.dtype == torch.float16:
-        dt = DTYPE_F16
-    else:
-        raise TypeError("w must be float32 or float16")
+    if w.dtype not in _DTYPES:
+        raise TypeError("w must be float32, float16 or bfloat16")
+    dt = _DTYPES[w.dtype]
     qw = torch.empty((K, N // 8), dtype=torch.int32, device=w.device)
     sc = torch.empty((K // GROUP, N), dtype=torch.float16, device=w.device)
     qz = torch.empty((K // GROUP, N // 8), dtype=torch.int32, device=w.device)
@@ -197,11 +233,11 @@ def quantize_layer(w: torch.Tensor, group_size: int = GROUP):
 
 
 def quantize_layer_w8(w: torch.Tensor, group_size: int = GROUP):
-    """w [K,N] float32 or float16 on the GPU -> (qweight int32 [K,N/4], scales fp16 [K/128,N], qzeros int32 [K/128,N/4])."""
+    """w [K,N] float32, float16 or bfloat16 on the GPU -> (qweight int32 [K,N/4], scales fp16 [K/128,N], qzeros int32 [K/128,N/4])."""
     K, N = w.shape
-    if w.dtype not in (torch.float32, torch.float16):
-        raise TypeError("w must be float32 or float16")
-    dt = DTYPE_F32 if w.dtype == torch.float32 else DTYPE_F16
+    if w.dtype not in _DTYPES:
+        raise TypeError("w must be float32, float16 or bfloat16")
+    dt = _DTYPES[w.dtype]
     qw = torch.empty((K, N // 4), dtype=torch.int32, device=w.device)
     sc = torch.empty((K // GROUP, N), dtype=torch.float16, device=w.device)
     qz = torch.empty((K // GROUP, N // 4), dtype=torch.int32, device=w.device)
@@ -214,7 +250,7 @@ def dequantize_w8(qweight, scales, qzeros, dtype=torch.float32, group_size: int 
     K = qweight.shape[0]
     N = scales.shape[1]
     out = torch.empty((K, N), dtype=dtype, device=qweight.device)
-    dt = DTYPE_F32 if dtype == torch.float32 else DTYPE_F16
+    dt = _DTYPES[dtype]
     _check(lib().morph_dequantize_w8(_dev(qweight, torch.int32, "qweight"), _dev(scales, torch.float16, "scales"),
                                      _dev(qzeros, torch.int32, "qzeros"), _dev(out, dtype, "out"), dt, K, N,
                                      group_size, _stream()), "morph_dequantize_w8")
@@ -225,7 +261,7 @@ def dequantize_w4(qweight, scales, qzeros, dtype=torch.float32, group_size: int 
     K = qweight.shape[0]
     N = scales.shape[1]
     out = torch.empty((K, N), dtype=dtype, device=qweight.device)
-    dt = DTYPE_F32 if dtype == torch.float32 else DTYPE_F16
+    dt = _DTYPES[dtype]
     _check(lib().morph_dequantize_w4(_dev(qweight, torch.int32, "qweight"), _dev(scales, torch.float16, "scales"),
                                      _dev(qzeros, torch.int32, "qzeros"), _dev(out, dtype, "out"), dt, K, N,
                                      group_size, _stream()), "morph_dequantize_w4")

@@ -81,8 +81,9 @@ size_t workspace_need(int kind, int M, int K, int N)
     return pl.S > 1 ? kCounterBytes + pl.partial_bytes : 0;
 }
 
+// bf: the 16-bit tensors (x, y, the weights of kind FP16) are bfloat16 instead of fp16
 int run_linear(int kind, const void* x, const void* w, const void* scales, const void* qzeros, void* y,
-               int M, int K, int N, void* workspace, size_t workspace_bytes, hipStream_t st)
+               int M, int K, int N, void* workspace, size_t workspace_bytes, hipStream_t st, int bf = 0)
 {
     hipError_t e;
     if (takes_stream(kind, M, K, N)) {
@@ -91,7 +92,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         DecodeArgs a;
         a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
         a.M = M; a.K = K; a.N = N; a.S = pl.S; a.rows = pl.rows; a.stream_loads = pl.stream_loads; a.scatter = pl.scatter; a.polls = pl.polls;
-        a.partial = nullptr; a.counters = nullptr;
+        a.partial = nullptr; a.counters = nullptr; a.bf = bf;
         if (pl.S > 1) {
             if (!workspace || workspace_bytes < kCounterBytes + pl.partial_bytes) return MORPH_ERR_WORKSPACE;
             if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
@@ -104,7 +105,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         GemmArgs g;
         g.x = x; g.w = w; g.scales = scales; g.qzeros = qzeros; g.y = y; g.M = M; g.K = K; g.N = N;
         g.config = pp.config; g.grid = pp.grid; g.split_tail = pp.split_tail;
-        g.partial = nullptr; g.counters = nullptr;
+        g.partial = nullptr; g.counters = nullptr; g.bf = bf;
         if (pp.counter_bytes > ((size_t)1 << 20)) return MORPH_ERR_UNSUPPORTED;   // more tiles than counters are zeroed for
         if (pp.partial_bytes) {
             if (!workspace || workspace_bytes < pp.counter_bytes + pp.partial_bytes) return MORPH_ERR_WORKSPACE;
@@ -160,11 +161,11 @@ int quantize_any(int bits, const void* w, int w_dtype, int32_t* qweight, void* s
 {
     if (!w || !qweight || !scales || !qzeros) return MORPH_ERR_NULL;
     if (group_size != MORPH_GROUP_SIZE) return MORPH_ERR_SHAPE;
-    if (w_dtype != MORPH_DTYPE_F32 && w_dtype != MORPH_DTYPE_F16) return MORPH_ERR_SHAPE;
+    if (w_dtype != MORPH_DTYPE_F32 && w_dtype != MORPH_DTYPE_F16 && w_dtype != MORPH_DTYPE_BF16) return MORPH_ERR_SHAPE;
     if (int rc = check_shape(1, K, N)) return rc;
     if (!aligned16(w) || !aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros)) return MORPH_ERR_ALIGN;
     if (K / MORPH_GROUP_SIZE > 65535) return MORPH_ERR_UNSUPPORTED;
-    hipError_t e = launch_quantize(bits, w, w_dtype == MORPH_DTYPE_F16, reinterpret_cast<uint32_t*>(qweight), scales,
+    hipError_t e = launch_quantize(bits, w, w_dtype, reinterpret_cast<uint32_t*>(qweight), scales,
                                    reinterpret_cast<uint32_t*>(qzeros), K, N, (hipStream_t)stream);
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
@@ -174,13 +175,13 @@ int dequantize_any(int bits, const int32_t* qweight, const void* scales, const i
 {
     if (!qweight || !scales || !qzeros || !out) return MORPH_ERR_NULL;
     if (group_size != MORPH_GROUP_SIZE) return MORPH_ERR_SHAPE;
-    if (out_dtype != MORPH_DTYPE_F32 && out_dtype != MORPH_DTYPE_F16) return MORPH_ERR_SHAPE;
+    if (out_dtype != MORPH_DTYPE_F32 && out_dtype != MORPH_DTYPE_F16 && out_dtype != MORPH_DTYPE_BF16) return MORPH_ERR_SHAPE;
     if (int rc = check_shape(1, K, N)) return rc;
     if (!aligned16(qweight) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(out)) return MORPH_ERR_ALIGN;
     if (K > 65535) return MORPH_ERR_UNSUPPORTED;
     hipError_t e = launch_dequantize(bits, reinterpret_cast<const uint32_t*>(qweight), scales,
                                      reinterpret_cast<const uint32_t*>(qzeros), out,
-                                     out_dtype == MORPH_DTYPE_F16, K, N, (hipStream_t)stream);
+                                     out_dtype, K, N, (hipStream_t)stream);
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
 }  // namespace
@@ -193,6 +194,34 @@ int morph_linear_w8a16(const void* x, const int32_t* qweight, const void* scales
     if (int rc = validate_linear(MORPH_KIND_W8A16, x, qweight, scales, qzeros, y, M, K, N)) return rc;
     return run_linear(MORPH_KIND_W8A16, x, qweight, scales, qzeros, y, M, K, N, workspace, workspace_bytes,
                       (hipStream_t)stream);
+}
+
+int morph_linear_bf16(const void* x, const void* w, void* y, int M, int K, int N, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    if (int rc = validate_linear(MORPH_KIND_FP16, x, w, nullptr, nullptr, y, M, K, N)) return rc;
+    return run_linear(MORPH_KIND_FP16, x, w, nullptr, nullptr, y, M, K, N, workspace, workspace_bytes,
+                      (hipStream_t)stream, 1);
+}
+
+int morph_linear_w4a16_bf16(const void* x, const int32_t* qweight, const void* scales, const int32_t* qzeros,
+                            void* y, int M, int K, int N, int group_size, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    if (group_size != MORPH_GROUP_SIZE) return (x && qweight && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
+    if (int rc = validate_linear(MORPH_KIND_W4A16, x, qweight, scales, qzeros, y, M, K, N)) return rc;
+    return run_linear(MORPH_KIND_W4A16, x, qweight, scales, qzeros, y, M, K, N, workspace, workspace_bytes,
+                      (hipStream_t)stream, 1);
+}
+
+int morph_linear_w8a16_bf16(const void* x, const int32_t* qweight, const void* scales, const int32_t* qzeros,
+                            void* y, int M, int K, int N, int group_size, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    if (group_size != MORPH_GROUP_SIZE) return (x && qweight && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
+    if (int rc = validate_linear(MORPH_KIND_W8A16, x, qweight, scales, qzeros, y, M, K, N)) return rc;
+    return run_linear(MORPH_KIND_W8A16, x, qweight, scales, qzeros, y, M, K, N, workspace, workspace_bytes,
+                      (hipStream_t)stream, 1);
 }
 
 int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
@@ -594,13 +623,21 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     for (int m : ms) {
         if ((rc = morph_linear_fp16(x, w, y, m, kWK, kWN, ws, wsb, stream))) return rc;
         if ((rc = morph_linear_w4a16(x, q, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
+        if ((rc = morph_linear_bf16(x, w, y, m, kWK, kWN, ws, wsb, stream))) return rc;
+        if ((rc = morph_linear_w4a16_bf16(x, q, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
     }
     // the 8-bit variant: its codes (32 KB) go where the fp32 dummy matrix was
     int32_t* q8 = reinterpret_cast<int32_t*>(f);
     if ((rc = morph_quantize_layer_w8(w, MORPH_DTYPE_F16, q8, s, z, kWK, kWN, 128, stream))) return rc;
-    for (int m : ms)
+    for (int m : ms) {
         if ((rc = morph_linear_w8a16(x, q8, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
+        if ((rc = morph_linear_w8a16_bf16(x, q8, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
+    }
     if ((rc = morph_dequantize_w8(q8, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
+    if ((rc = morph_dequantize_w8(q8, s, z, w, MORPH_DTYPE_BF16, kWK, kWN, 128, stream))) return rc;
+    if ((rc = morph_dequantize_w4(q, s, z, w, MORPH_DTYPE_BF16, kWK, kWN, 128, stream))) return rc;
+    if ((rc = morph_quantize_layer(w, MORPH_DTYPE_BF16, q, s, z, kWK, kWN, 128, stream))) return rc;
+    if ((rc = morph_quantize_layer_w8(w, MORPH_DTYPE_BF16, q8, s, z, kWK, kWN, 128, stream))) return rc;
     for (int op = MORPH_GLUE_QKV; op <= MORPH_GLUE_RMS; op++)
         if ((rc = morph_glue(op, w, x, y, 2, 64, stream))) return rc;
     if ((rc = morph_cosine_rows(x, w, reinterpret_cast<float*>(y), reinterpret_cast<float*>(y) + 64, 2, 128, stream))) return rc;

@@ -28,7 +28,8 @@ struct DecodeTail {
     int    rows, stream_loads, scatter, polls, cstride;
 };
 
-template <int Q, int MT, int kWaves, bool NT>
+// BF: x, y (and the weights of the fp16 kind) are bfloat16 instead of fp16.
+template <int Q, int MT, int kWaves, bool NT, bool BF>
 __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kernel(
     const void* w, const void* x, const void* scales, const void* qzeros, int Ktot, int Ntot, int Mtot, int Stot,
     int tiles, int slices, DecodeTail t)
@@ -72,10 +73,10 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
     job.x = (const half_t*)p.x + (size_t)mbase * p.K;
     job.w = p.w; job.scales = p.scales; job.qzeros = p.qzeros;
     job.M = M; job.K = p.K; job.N = N; job.n0 = n0; job.S = S; job.sp = sp;
-    tile_partial<Q, MT, kWaves, false, NT>(job, yl);
+    tile_partial<Q, MT, kWaves, false, NT, BF>(job, yl);
 
     // ---- sum the waves that share columns (in the order of their k parts) and write out ----
-    half_t* y = (half_t*)p.y + (size_t)mbase * N;
+    uint16_t* y = (uint16_t*)p.y + (size_t)mbase * N;
     auto item_sum = [&](int it) { return G::item_sum(yl, it); };
     auto item_store_y = [&](int it, f32x4 acc) {
         const int pn = it / (NV * 64), rem = it - pn * (NV * 64);
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(kWaves * 64, kWaves == 4 ? 2 : 1) void decode_kerne
         if (col < N) {
 #pragma unroll
             for (int r = 0; r < 4; r++)
-                if (row + r < M) y[(size_t)(row + r) * N + col] = (half_t)acc[r];
+                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<BF>(acc[r]);
         }
     };
     auto item_rows_live = [&](int it) {                  // does the vector hold any row below M?
@@ -249,14 +250,14 @@ inline int decode_waves(int rows)
     return rows > 16 ? 8 : 4;
 }
 
-template <int Q, int MT, int kWaves, bool NT>
+template <int Q, int MT, int kWaves, bool NT, bool BF>
 hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
 {
     constexpr int tnb = Tile<Q, MT>::TN * Tile<Q, MT>::WN;
     constexpr size_t lds = TileGeom<Q, MT, kWaves>::kLdsBytes;
     static_assert(lds <= 128 * 1024, "LDS of one compute unit");
     if (lds > 64 * 1024) {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Q, MT, kWaves, NT>),
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<Q, MT, kWaves, NT, BF>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (attr != hipSuccess) return attr;
     }
@@ -269,19 +270,27 @@ hipError_t launch_waves(const DecodeArgs& a, int slices, hipStream_t st)
     DecodeTail t;
     t.y = b.y; t.partial = b.partial; t.counters = b.counters; t.rows = b.rows; t.stream_loads = b.stream_loads;
     t.scatter = b.scatter; t.polls = b.polls; t.cstride = b.cstride;
-    hipLaunchKernelGGL((decode_kernel<Q, MT, kWaves, NT>), dim3(grid), dim3(kWaves * 64), lds, st, b.w, b.x, b.scales,
+    hipLaunchKernelGGL((decode_kernel<Q, MT, kWaves, NT, BF>), dim3(grid), dim3(kWaves * 64), lds, st, b.w, b.x, b.scales,
                        b.qzeros, b.K, b.N, b.M, b.S, b.tiles, b.slices, t);
     return hipGetLastError();
 }
 
-template <int Q, int MT>
+template <int Q, int MT, bool BF>
 hipError_t launch_one(const DecodeArgs& a, int slices, hipStream_t st)
 {
     const bool w8 = decode_waves(MT * 16) == 8;
     if constexpr (MT == 1 || Q != 1) {                   // not the 4-bit two-tile kernel: its two column halves share cache lines
-        if (a.stream_loads) return w8 ? launch_waves<Q, MT, 8, true>(a, slices, st) : launch_waves<Q, MT, 4, true>(a, slices, st);
+        if (a.stream_loads) return w8 ? launch_waves<Q, MT, 8, true, BF>(a, slices, st) : launch_waves<Q, MT, 4, true, BF>(a, slices, st);
     }
-    return w8 ? launch_waves<Q, MT, 8, false>(a, slices, st) : launch_waves<Q, MT, 4, false>(a, slices, st);
+    return w8 ? launch_waves<Q, MT, 8, false, BF>(a, slices, st) : launch_waves<Q, MT, 4, false, BF>(a, slices, st);
+}
+
+template <bool BF>
+hipError_t launch_format(int q, bool one, const DecodeArgs& a, int slices, hipStream_t st)
+{
+    if (q == 1) return one ? launch_one<1, 1, BF>(a, slices, st) : launch_one<1, 2, BF>(a, slices, st);
+    if (q == 2) return one ? launch_one<2, 1, BF>(a, slices, st) : launch_one<2, 2, BF>(a, slices, st);
+    return one ? launch_one<0, 1, BF>(a, slices, st) : launch_one<0, 2, BF>(a, slices, st);
 }
 
 }  // namespace
@@ -377,9 +386,7 @@ hipError_t launch_decode(int q, const DecodeArgs& a, hipStream_t st)
     if (rows != 16 && rows != 32) return hipErrorInvalidValue;
     const int slices = (a.M + rows - 1) / rows;
     const bool one   = rows == 16;                       // a single 16-row MFMA tile
-    if (q == 1) return one ? launch_one<1, 1>(a, slices, st) : launch_one<1, 2>(a, slices, st);
-    if (q == 2) return one ? launch_one<2, 1>(a, slices, st) : launch_one<2, 2>(a, slices, st);
-    return one ? launch_one<0, 1>(a, slices, st) : launch_one<0, 2>(a, slices, st);
+    return a.bf ? launch_format<true>(q, one, a, slices, st) : launch_format<false>(q, one, a, slices, st);
 }
 
 }  // namespace morph

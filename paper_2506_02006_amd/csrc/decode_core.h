@@ -25,6 +25,12 @@
 //     two waves share each SIMD.  The vector ALU does one permute and one AND per four weights
 //     plus that fold.
 //   * K is split over the waves of a workgroup (and, by the caller, over workgroups).
+//   * bfloat16 activations (BF): the same with v_mfma_f32_16x16x32_bf16.  A code byte b in a 16-bit
+//     lane is then the bfloat16 value b * 2^-133 (bit patterns below 256 are linear in value: the
+//     subnormals and the first normal binade; the matrix core honours them, measured).  So that
+//     the fp32 sums stay far from the bottom of the fp32 range, x is multiplied by 2^64 on its way
+//     into the MFMA (exact: a power of two, |x| < 2^63 assumed) and the fold takes it out again:
+//     y += s * (2^69 * acc - z * 2^-64 * rowsum(2^64 x)).
 #pragma once
 #include "dev_common.h"
 
@@ -120,12 +126,35 @@ struct TileGeom {
     }
 };
 
+// The 16x16x32 MFMA on 16-bit operands held as fp16 vectors: fp16, or the same bits read as bfloat16.
+template <bool BF>
+__device__ __forceinline__ f32x4 mfma16(half8_t a, half8_t b, f32x4 c)
+{
+    if constexpr (BF) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(bit_cast<bf16x8_t>(a), bit_cast<bf16x8_t>(b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// Eight bfloat16 values times 2^64 (through fp32, where the product of a power of two is exact and
+// zero stays zero; the low 16 bits of each product are zero, so taking the upper halves loses nothing).
+__device__ __forceinline__ half8_t bf16x8_times_2p64(half8_t v)
+{
+    const u32x4 w = bit_cast<u32x4>(v);
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const float lo = bit_cast<float>(w[i] << 16) * 0x1p64f, hi = bit_cast<float>(w[i] & 0xFFFF0000u) * 0x1p64f;
+        o[i] = __builtin_amdgcn_perm(bit_cast<uint32_t>(hi), bit_cast<uint32_t>(lo), 0x07060302u);
+    }
+    return bit_cast<half8_t>(o);
+}
+
 // Runs the k loop of one unit and leaves every wave's sums in its region of yl; ends with a
 // workgroup barrier, after which TileGeom::item_sum may be called by any thread.  The caller must
 // make sure (barrier) that nobody still reads yl from an earlier unit when this is entered.
 // XT: read x past the caches (it was written by other workgroups of the same kernel).
 // NT: load the weights non-temporally (they are read once by this workgroup alone).
-template <int Q, int MT, int kWaves, bool XT, bool NT = false>
+// BF: x (and fp16-kind weights) are bfloat16.
+template <int Q, int MT, int kWaves, bool XT, bool NT = false, bool BF = false>
 __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
 {
     constexpr bool W4 = Q == 1, W8 = Q == 2, QUANT = Q != 0;
@@ -245,12 +274,18 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     // One k-step.  `first` (known at compile time: slot 0 of the unrolled group) starts the group
     // sums from zero instead of adding to them.
     auto compute = [&](const StageT& st, bool first) {
+        half8_t xa[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            if constexpr (BF && QUANT) xa[mt] = bf16x8_times_2p64(st.a[mt]);
+            else xa[mt] = st.a[mt];
+        }
         if constexpr (QUANT) {
-            const half_t  one  = (half_t)1.0f;
-            const half8_t ones = {one, one, one, one, one, one, one, one};
+            const uint32_t one2 = BF ? 0x3F803F80u : 0x3C003C00u;           // 1.0 twice
+            const half8_t  ones = bit_cast<half8_t>(u32x4{one2, one2, one2, one2});
 #pragma unroll
             for (int mt = 0; mt < MT; mt++)
-                xs[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], ones, first ? zero4 : xs[mt], 0, 0, 0);
+                xs[mt] = mfma16<BF>(xa[mt], ones, first ? zero4 : xs[mt]);
         }
         if constexpr (W8) {
             // a code byte in a 16-bit lane is the fp16 subnormal code * 2^-24: one MFMA per column
@@ -269,7 +304,7 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
                     const int j = 4 * t + yb;
 #pragma unroll
                     for (int mt = 0; mt < MT; mt++)
-                        gacc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bcode, first ? zero4 : gacc[mt][j], 0, 0, 0);
+                        gacc[mt][j] = mfma16<BF>(xa[mt], bcode, first ? zero4 : gacc[mt][j]);
                 }
             }
         } else if constexpr (W4) {
@@ -290,8 +325,8 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
                     const int j0 = t * 8 + 2 * yb;
 #pragma unroll
                     for (int mt = 0; mt < MT; mt++) {
-                        gacc[mt][j0]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bbyte, first ? zero4 : gacc[mt][j0], 0, 0, 0);
-                        gacc[mt][j0 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bhigh, first ? zero4 : gacc[mt][j0 + 1], 0, 0, 0);
+                        gacc[mt][j0]     = mfma16<BF>(xa[mt], bbyte, first ? zero4 : gacc[mt][j0]);
+                        gacc[mt][j0 + 1] = mfma16<BF>(xa[mt], bhigh, first ? zero4 : gacc[mt][j0 + 1]);
                     }
                 }
             }
@@ -309,8 +344,8 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
                 const half8_t bo = bit_cast<half8_t>(u32x4{o[0], o[1], o[2], o[3]});
 #pragma unroll
                 for (int mt = 0; mt < MT; mt++) {
-                    gacc[mt][2 * jj]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], be, gacc[mt][2 * jj], 0, 0, 0);
-                    gacc[mt][2 * jj + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(st.a[mt], bo, gacc[mt][2 * jj + 1], 0, 0, 0);
+                    gacc[mt][2 * jj]     = mfma16<BF>(xa[mt], be, gacc[mt][2 * jj]);
+                    gacc[mt][2 * jj + 1] = mfma16<BF>(xa[mt], bo, gacc[mt][2 * jj + 1]);
                 }
             }
         }
@@ -319,6 +354,10 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
     // Fold the group sums into the running result in LDS:
     //   low-nibble column:  y += s * (2^24 (acc_byte - acc_high) - z_lo * xs)
     //   high-nibble column: y += s * (2^20  acc_high             - z_hi * xs)
+    // (bfloat16: the code patterns weigh 2^-133 instead of 2^-24 and x came in times 2^64)
+    constexpr float kByte = BF ? 0x1p69f : 16777216.0f;   // what a whole-byte sum is multiplied by
+    constexpr float kHigh = BF ? 0x1p65f : 1048576.0f;    // ... a sum over bytes masked to their high nibble (16 q_hi)
+    constexpr float kXs   = BF ? 0x1p-64f : 1.0f;         // ... the row sums of x
     auto flush_group = [&](const GroupRaw<WPL>& gr) {
         if constexpr (W8) {
             // y += s * (2^24 acc - z * xs)
@@ -330,7 +369,7 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
                     const uint32_t sw = gr.sc[0][j >> 1];
                     const float s  = (float)bit_cast<half_t>((uint16_t)((j & 1) ? sw >> 16 : sw & 0xFFFFu));
                     const float z  = (float)((gr.zq[t] >> (8 * yb)) & 0xFFu);
-                    const float a1 = s * 16777216.0f, c1 = -s * z;
+                    const float a1 = s * kByte, c1 = -s * z * kXs;
 #pragma unroll
                     for (int mt = 0; mt < MT; mt++) {
                         f32x4 y0 = ymine[(mt * CPL + j) * 64];
@@ -354,8 +393,8 @@ __device__ __forceinline__ void tile_partial(const TileJob& p, f32x4* yl)
                     const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
                     const float z_lo = (float)((zlo >> (8 * yb)) & 0xFFu);
                     const float z_hi = (float)((zhi >> (8 * yb)) & 0xFFu);
-                    const float a_lo = s_lo * 16777216.0f, a_hi = s_hi * 1048576.0f;
-                    const float c_lo = -s_lo * z_lo, c_hi = -s_hi * z_hi;
+                    const float a_lo = s_lo * kByte, a_hi = s_hi * kHigh;
+                    const float c_lo = -s_lo * z_lo * kXs, c_hi = -s_hi * z_hi * kXs;
                     const int j0 = t * 8 + 2 * yb;
 #pragma unroll
                     for (int mt = 0; mt < MT; mt++) {

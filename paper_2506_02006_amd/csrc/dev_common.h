@@ -9,6 +9,8 @@ typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16   bf16_t;
+typedef __bf16   bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float    f32x4   __attribute__((ext_vector_type(4)));
 typedef float    f32x16  __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2   __attribute__((ext_vector_type(2)));
@@ -90,6 +92,21 @@ __device__ __forceinline__ void wait_stores()
 __device__ __forceinline__ float h2f_bits(uint32_t bits16)
 {
     return (float)bit_cast<half_t>((uint16_t)bits16);
+}
+
+// The 16-bit tensors (x, dense weights, y) are fp16 or, with BF, bfloat16 (the upper half of an
+// fp32).  Widening is exact; narrowing rounds once, to nearest even.
+template <bool BF>
+__device__ __forceinline__ float widen16(uint32_t bits16)
+{
+    if constexpr (BF) return bit_cast<float>(bits16 << 16);
+    else return h2f_bits(bits16);
+}
+template <bool BF>
+__device__ __forceinline__ uint16_t narrow16(float f)
+{
+    if constexpr (BF) return bit_cast<uint16_t>((bf16_t)f);
+    else return bit_cast<uint16_t>((half_t)f);
 }
 
 }  // namespace morph

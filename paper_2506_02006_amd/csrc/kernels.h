@@ -8,11 +8,11 @@
 namespace morph {
 
 // ---- quantizer / verification dequantizer (quant.hip) ----
-// bits = 4 or 8
-hipError_t launch_quantize(int bits, const void* w, int w_is_f16, uint32_t* qweight, void* scales,
+// bits = 4 or 8; dtype: 0 = fp32, 1 = fp16, 2 = bf16 (the MORPH_DTYPE_* values)
+hipError_t launch_quantize(int bits, const void* w, int w_dtype, uint32_t* qweight, void* scales,
                            uint32_t* qzeros, int K, int N, hipStream_t st);
 hipError_t launch_dequantize(int bits, const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
-                             void* out, int out_is_f16, int K, int N, hipStream_t st);
+                             void* out, int out_dtype, int K, int N, hipStream_t st);
 
 // ---- decode, M <= 64 (decode.hip) ----
 struct DecodeArgs {
@@ -32,6 +32,7 @@ struct DecodeArgs {
     int             tiles;     // column tiles (set by launch_decode)
     int             slices;    // row slices (set by launch_decode)
     int             cstride;   // ints between the arrival counters of two tiles (set by launch_decode)
+    int             bf;        // x, dense weights and y are bfloat16 instead of fp16
 };
 struct DecodePlan {
     int    tile_n;             // columns per workgroup
@@ -64,6 +65,7 @@ struct GemmArgs {
     int         grid;      // workgroups (PrefillPlan::grid)
     int         split_tail; // share the last partial round out along K (PrefillPlan::split_tail)
     int         map;        // schedule index -> tile: 1 = column-major over (row tile, column tile), 2 = blocks of 8 column tiles dealt out to 8 XCDs (set by launch_prefill)
+    int         bf;         // x, dense weights and y are bfloat16 instead of fp16
 };
 struct PrefillPlan {
     int    config, bm, bn, tiles, grid, split_tail;

@@ -54,8 +54,19 @@ constexpr int LDK = BK + 8;           // LDS pitch in halfs (144 bytes)
 // scheduling-group masks of __builtin_amdgcn_sched_group_barrier
 constexpr int kSgValu = 0x2, kSgMfma = 0x8, kSgVmemRead = 0x20, kSgDsRead = 0x100, kSgDsWrite = 0x200;
 
+// two fp32 values rounded (to nearest even) into the two bfloat16 halves of a word
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float  f32x2_t  __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return bit_cast<uint32_t>(__builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
+}
+
 // Q: 0 = fp16 weights, 1 = 4-bit codes, 2 = 8-bit codes.
-template <int Q, int BM, int BN, int WVM, int WVN>
+// BF: x, y and the weights of kind 0 are bfloat16 (v_mfma_f32_32x32x16_bf16); the weight tile of the
+// quantized kinds then holds (q - z) * s rounded once to bfloat16: (q - z) is formed exactly in
+// fp16 as below, widened, multiplied by the scale in fp32 (exact) and narrowed.
+template <int Q, int BM, int BN, int WVM, int WVN, bool BF>
 __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kernel(GemmArgs p, int tiles_m, int tiles)
 {
     constexpr bool W4 = Q == 1, W8 = Q == 2, QUANT = Q != 0;
@@ -219,19 +230,24 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                 const uint32_t z0 = (yb & 1) ? pair_bytes<2>(zq, zq) : pair_bytes<0>(zq, zq);
                 const uint32_t z1 = (yb & 1) ? pair_bytes<3>(zq, zq) : pair_bytes<1>(zq, zq);
                 const half2_t cz0 = bit_cast<half2_t>(z0 | 0xE400E400u), cz1 = bit_cast<half2_t>(z1 | 0xE400E400u);   // -(1024 + z)
-                half8_t c0, c1;
+                u32x4 c0, c1;
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
                     const uint32_t r0 = st[4 * bl + q][yb >> 1], r1 = st[4 * bl + q][2 + (yb >> 1)];               // rows 2q, 2q+1
                     const uint32_t p0 = (yb & 1) ? pair_bytes<2>(r0, r1) : pair_bytes<0>(r0, r1);
                     const uint32_t p1 = (yb & 1) ? pair_bytes<3>(r0, r1) : pair_bytes<1>(r0, r1);
-                    const half2_t v0 = (bit_cast<half2_t>(p0 | 0x64006400u) + cz0) * s0p;
-                    const half2_t v1 = (bit_cast<half2_t>(p1 | 0x64006400u) + cz1) * s1p;
-                    c0[2 * q] = v0[0]; c0[2 * q + 1] = v0[1];
-                    c1[2 * q] = v1[0]; c1[2 * q + 1] = v1[1];
+                    const half2_t d0 = bit_cast<half2_t>(p0 | 0x64006400u) + cz0;                                  // q - z, exact
+                    const half2_t d1 = bit_cast<half2_t>(p1 | 0x64006400u) + cz1;
+                    if constexpr (BF) {
+                        c0[q] = pack_bf16x2((float)d0[0] * (float)s0, (float)d0[1] * (float)s0);
+                        c1[q] = pack_bf16x2((float)d1[0] * (float)s1, (float)d1[1] * (float)s1);
+                    } else {
+                        c0[q] = bit_cast<uint32_t>(d0 * s0p);
+                        c1[q] = bit_cast<uint32_t>(d1 * s1p);
+                    }
                 }
-                *reinterpret_cast<half8_t*>(bb + (2 * yb) * LDK)     = c0;
-                *reinterpret_cast<half8_t*>(bb + (2 * yb + 1) * LDK) = c1;
+                *reinterpret_cast<u32x4*>(bb + (2 * yb) * LDK)     = c0;
+                *reinterpret_cast<u32x4*>(bb + (2 * yb + 1) * LDK) = c1;
             } else if constexpr (W4) {
                 const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
                 const uint32_t zq = zq_reg[bl][0];
@@ -242,19 +258,26 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                 const uint32_t sw = sc_reg[bl][yb];                                        // scales of columns 2yb, 2yb+1
                 const half_t  s0 = bit_cast<half_t>((uint16_t)(sw & 0xFFFFu)), s1 = bit_cast<half_t>((uint16_t)(sw >> 16));
                 const half2_t s0p = {s0, s0}, s1p = {s1, s1};
-                half8_t lo8, hi8;
+                u32x4 lo8, hi8;
+                // bfloat16: 16 (q_hi - z_hi) is formed exactly and the 1/16 goes into the fp32 scale
+                const half2_t czh16 = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xE400E400u);  // -(1024 + 16 z)
+                const float   s1_16 = (float)s1 * 0.0625f;
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
                     const uint32_t r0 = st[2 * bl + ((2 * q) >> 2)][(2 * q) & 3], r1 = st[2 * bl + ((2 * q + 1) >> 2)][(2 * q + 1) & 3];
                     const uint32_t pr = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
                                       : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
-                    const half2_t lo = (nib_lo_1024(pr) + czl) * s0p;                      // (q - z) * s, one rounding
-                    const half2_t hi = (nib_hi_1024(pr) * sixteenth + czh) * s1p;
-                    lo8[2 * q] = lo[0]; lo8[2 * q + 1] = lo[1];
-                    hi8[2 * q] = hi[0]; hi8[2 * q + 1] = hi[1];
+                    if constexpr (BF) {
+                        const half2_t dl = nib_lo_1024(pr) + czl, dh = nib_hi_1024(pr) + czh16;
+                        lo8[q] = pack_bf16x2((float)dl[0] * (float)s0, (float)dl[1] * (float)s0);
+                        hi8[q] = pack_bf16x2((float)dh[0] * s1_16, (float)dh[1] * s1_16);
+                    } else {
+                        lo8[q] = bit_cast<uint32_t>((nib_lo_1024(pr) + czl) * s0p);         // (q - z) * s, one rounding
+                        hi8[q] = bit_cast<uint32_t>((nib_hi_1024(pr) * sixteenth + czh) * s1p);
+                    }
                 }
-                *reinterpret_cast<half8_t*>(bb + (2 * yb) * LDK)     = lo8;
-                *reinterpret_cast<half8_t*>(bb + (2 * yb + 1) * LDK) = hi8;
+                *reinterpret_cast<u32x4*>(bb + (2 * yb) * LDK)     = lo8;
+                *reinterpret_cast<u32x4*>(bb + (2 * yb + 1) * LDK) = hi8;
             } else {
                 uint32_t e[4], o[4];
 #pragma unroll
@@ -314,7 +337,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             for (int i = 0; i < FM; i++)
 #pragma unroll
                 for (int j = 0; j < FN; j++)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[kk & 1][i], bf[kk & 1][j], acc[i][j], 0, 0, 0);
+                    if constexpr (BF) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bit_cast<bf16x8_t>(af[kk & 1][i]), bit_cast<bf16x8_t>(bf[kk & 1][j]), acc[i][j], 0, 0, 0);
+                    else              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[kk & 1][i], bf[kk & 1][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_group_barrier(kSgDsRead, FM + FN, 0);
 #pragma unroll
             for (int g = 0; g < FM * FN; g++) {
@@ -382,7 +406,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int row = 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    et[row * EP + 32 * j + (lane & 31)] = (half_t)acc[i][j][r];
+                    reinterpret_cast<uint16_t*>(et)[row * EP + 32 * j + (lane & 31)] = narrow16<BF>(acc[i][j][r]);
                 }
         // (a wave reads back only what it wrote itself; LDS operations of one wave complete in order)
         constexpr int VPR = WN / 8;                    // 16-byte pieces per tile row
@@ -500,14 +524,14 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     }
 }
 
-template <int Q, int BM, int BN, int WVM, int WVN>
+template <int Q, int BM, int BN, int WVM, int WVN, bool BF>
 hipError_t launch_tile(const GemmArgs& a, hipStream_t st)
 {
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const int tiles = tiles_m * tiles_n;
     // (One kernel for both ways of running the last round: a variant without the sharing code
     // spills no registers but was measured 8 % slower per k step; the spills sit outside the loop.)
-    hipLaunchKernelGGL((prefill_kernel<Q, BM, BN, WVM, WVN>), dim3(a.grid), dim3(WVM * WVN * 64), 0, st, a, tiles_m, tiles);
+    hipLaunchKernelGGL((prefill_kernel<Q, BM, BN, WVM, WVN, BF>), dim3(a.grid), dim3(WVM * WVN * 64), 0, st, a, tiles_m, tiles);
     return hipGetLastError();
 }
 
@@ -591,15 +615,15 @@ PrefillPlan plan_prefill(int M, int K, int N)
     return pl;
 }
 
-template <int Q>
+template <int Q, bool BF>
 static hipError_t launch_config(const GemmArgs& a, hipStream_t st)
 {
     switch (a.config) {
-        case 1: return launch_tile<Q, 256, 256, 4, 2>(a, st);
-        case 3: return launch_tile<Q, 256, 256, 2, 2>(a, st);
-        case 4: return launch_tile<Q, 256, 128, 2, 2>(a, st);
-        case 5: return launch_tile<Q, 256, 192, 4, 2>(a, st);
-        default: return launch_tile<Q, 128, 128, 2, 2>(a, st);
+        case 1: return launch_tile<Q, 256, 256, 4, 2, BF>(a, st);
+        case 3: return launch_tile<Q, 256, 256, 2, 2, BF>(a, st);
+        case 4: return launch_tile<Q, 256, 128, 2, 2, BF>(a, st);
+        case 5: return launch_tile<Q, 256, 192, 4, 2, BF>(a, st);
+        default: return launch_tile<Q, 128, 128, 2, 2, BF>(a, st);
     }
 }
 
@@ -610,7 +634,8 @@ hipError_t launch_prefill(int q, const GemmArgs& a0, hipStream_t st)
     const int force = tuning_get(TUNE_PREFILL_MAP);      // 0 = default (2), 1 / 2 = that map
     a.map = force == 1 ? 1 : 2;
     if (a.grid % 8 != 0) a.map = 1;
-    return q == 1 ? launch_config<1>(a, st) : q == 2 ? launch_config<2>(a, st) : launch_config<0>(a, st);
+    if (a.bf) return q == 1 ? launch_config<1, true>(a, st) : q == 2 ? launch_config<2, true>(a, st) : launch_config<0, true>(a, st);
+    return q == 1 ? launch_config<1, false>(a, st) : q == 2 ? launch_config<2, false>(a, st) : launch_config<0, false>(a, st);
 }
 
 }  // namespace morph

@@ -1,4 +1,4 @@
-// Quantizer (fp32/fp16 weights -> 4-bit or 8-bit layer record) and the verification dequantizer.
+// Quantizer (fp32/fp16/bf16 weights -> 4-bit or 8-bit layer record) and the verification dequantizer.
 // Format and arithmetic: see include/morph.h.  Both are exact procedures with one right answer;
 // neither sits on the per-token path.
 #include "dev_common.h"
@@ -13,6 +13,7 @@ constexpr int kQC = 64;                                   // columns per workgro
 constexpr int kQT = 256 / kQC;                            // threads per column in the range pass
 constexpr int kQP = kQC + 4;                              // LDS pitch in floats (keeps 16-byte alignment, skews the banks)
 // BITS = 4: 15 steps, eight codes per word; BITS = 8: 255 steps, four codes per word.
+// WT: float, or a 16-bit type (half_t, bf16_t) whose values are widened exactly.
 template <typename WT, int BITS>
 __global__ __launch_bounds__(256) void quantize_kernel(const WT* __restrict__ w,
                                                        uint32_t* __restrict__ qweight,
@@ -46,19 +47,19 @@ __global__ __launch_bounds__(256) void quantize_kernel(const WT* __restrict__ w,
             *reinterpret_cast<f32x4*>(tile + row * kQP + 4 * pc) = v[i];
         }
     } else {
-        constexpr int PPR = kQC / 8;
-        half8_t v[kGroup * PPR / 256];
-        const half8_t zero8 = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+        constexpr int  PPR = kQC / 8;
+        constexpr bool BF  = sizeof(WT) == 2 && !__is_same(WT, half_t);
+        u32x4 v[kGroup * PPR / 256];
 #pragma unroll
         for (int i = 0; i < kGroup * PPR / 256; i++) {
             const int p = tid + 256 * i, row = p / PPR, pc = p - row * PPR;
-            v[i] = n0 + 8 * pc < N ? *reinterpret_cast<const half8_t*>(base + (size_t)row * N + 8 * pc) : zero8;
+            v[i] = n0 + 8 * pc < N ? *reinterpret_cast<const u32x4*>(base + (size_t)row * N + 8 * pc) : u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int i = 0; i < kGroup * PPR / 256; i++) {
             const int p = tid + 256 * i, row = p / PPR, pc = p - row * PPR;
-            const f32x4 a = {(float)v[i][0], (float)v[i][1], (float)v[i][2], (float)v[i][3]};
-            const f32x4 b = {(float)v[i][4], (float)v[i][5], (float)v[i][6], (float)v[i][7]};
+            const f32x4 a = {widen16<BF>(v[i][0] & 0xFFFFu), widen16<BF>(v[i][0] >> 16), widen16<BF>(v[i][1] & 0xFFFFu), widen16<BF>(v[i][1] >> 16)};
+            const f32x4 b = {widen16<BF>(v[i][2] & 0xFFFFu), widen16<BF>(v[i][2] >> 16), widen16<BF>(v[i][3] & 0xFFFFu), widen16<BF>(v[i][3] >> 16)};
             *reinterpret_cast<f32x4*>(tile + row * kQP + 8 * pc)     = a;
             *reinterpret_cast<f32x4*>(tile + row * kQP + 8 * pc + 4) = b;
         }
@@ -167,40 +168,47 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
         reinterpret_cast<f32x4*>(o)[0] = a;
         reinterpret_cast<f32x4*>(o)[1] = b;
     } else {
-        half8_t h;
+        constexpr bool BF = !__is_same(OT, half_t);
+        uint32_t h[4];
 #pragma unroll
-        for (int j = 0; j < 8; j++) h[j] = (half_t)d[j];    // one rounding, to nearest even
-        *reinterpret_cast<half8_t*>(o) = h;
+        for (int j = 0; j < 4; j++)                         // one rounding, to nearest even
+            h[j] = (uint32_t)narrow16<BF>(d[2 * j]) | ((uint32_t)narrow16<BF>(d[2 * j + 1]) << 16);
+        *reinterpret_cast<u32x4*>(o) = u32x4{h[0], h[1], h[2], h[3]};
     }
 }
 
-hipError_t launch_quantize(int bits, const void* w, int w_is_f16, uint32_t* qweight, void* scales,
-                           uint32_t* qzeros, int K, int N, hipStream_t st)
+// dtype: 0 = fp32, 1 = fp16, 2 = bf16 (the MORPH_DTYPE_* values)
+template <int BITS>
+static void quantize_bits(const void* w, int dtype, uint32_t* qweight, half_t* sc, uint32_t* qzeros, int K, int N, hipStream_t st)
 {
     dim3 grid((N + kQC - 1) / kQC, K / kGroup), block(256);
-    half_t* sc = (half_t*)scales;
-    if (bits == 4) {
-        if (w_is_f16) hipLaunchKernelGGL((quantize_kernel<half_t, 4>), grid, block, 0, st, (const half_t*)w, qweight, sc, qzeros, K, N);
-        else          hipLaunchKernelGGL((quantize_kernel<float, 4>), grid, block, 0, st, (const float*)w, qweight, sc, qzeros, K, N);
-    } else {
-        if (w_is_f16) hipLaunchKernelGGL((quantize_kernel<half_t, 8>), grid, block, 0, st, (const half_t*)w, qweight, sc, qzeros, K, N);
-        else          hipLaunchKernelGGL((quantize_kernel<float, 8>), grid, block, 0, st, (const float*)w, qweight, sc, qzeros, K, N);
-    }
+    if (dtype == 1)      hipLaunchKernelGGL((quantize_kernel<half_t, BITS>), grid, block, 0, st, (const half_t*)w, qweight, sc, qzeros, K, N);
+    else if (dtype == 2) hipLaunchKernelGGL((quantize_kernel<bf16_t, BITS>), grid, block, 0, st, (const bf16_t*)w, qweight, sc, qzeros, K, N);
+    else                 hipLaunchKernelGGL((quantize_kernel<float, BITS>), grid, block, 0, st, (const float*)w, qweight, sc, qzeros, K, N);
+}
+
+hipError_t launch_quantize(int bits, const void* w, int w_dtype, uint32_t* qweight, void* scales,
+                           uint32_t* qzeros, int K, int N, hipStream_t st)
+{
+    if (bits == 4) quantize_bits<4>(w, w_dtype, qweight, (half_t*)scales, qzeros, K, N, st);
+    else           quantize_bits<8>(w, w_dtype, qweight, (half_t*)scales, qzeros, K, N, st);
     return hipGetLastError();
 }
 
-hipError_t launch_dequantize(int bits, const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
-                             void* out, int out_is_f16, int K, int N, hipStream_t st)
+template <int BITS>
+static void dequantize_bits(const uint32_t* qweight, const half_t* sc, const uint32_t* qzeros, void* out, int dtype, int K, int N, hipStream_t st)
 {
     dim3 grid((N / 8 + 255) / 256, K), block(256);
-    const half_t* sc = (const half_t*)scales;
-    if (bits == 4) {
-        if (out_is_f16) hipLaunchKernelGGL((dequantize_kernel<half_t, 4>), grid, block, 0, st, qweight, sc, qzeros, (half_t*)out, K, N);
-        else            hipLaunchKernelGGL((dequantize_kernel<float, 4>), grid, block, 0, st, qweight, sc, qzeros, (float*)out, K, N);
-    } else {
-        if (out_is_f16) hipLaunchKernelGGL((dequantize_kernel<half_t, 8>), grid, block, 0, st, qweight, sc, qzeros, (half_t*)out, K, N);
-        else            hipLaunchKernelGGL((dequantize_kernel<float, 8>), grid, block, 0, st, qweight, sc, qzeros, (float*)out, K, N);
-    }
+    if (dtype == 1)      hipLaunchKernelGGL((dequantize_kernel<half_t, BITS>), grid, block, 0, st, qweight, sc, qzeros, (half_t*)out, K, N);
+    else if (dtype == 2) hipLaunchKernelGGL((dequantize_kernel<bf16_t, BITS>), grid, block, 0, st, qweight, sc, qzeros, (bf16_t*)out, K, N);
+    else                 hipLaunchKernelGGL((dequantize_kernel<float, BITS>), grid, block, 0, st, qweight, sc, qzeros, (float*)out, K, N);
+}
+
+hipError_t launch_dequantize(int bits, const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
+                             void* out, int out_dtype, int K, int N, hipStream_t st)
+{
+    if (bits == 4) dequantize_bits<4>(qweight, (const half_t*)scales, qzeros, out, out_dtype, K, N, st);
+    else           dequantize_bits<8>(qweight, (const half_t*)scales, qzeros, out, out_dtype, K, N, st);
     return hipGetLastError();
 }
 

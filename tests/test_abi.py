@@ -65,10 +65,27 @@ def test_linear_fp16_validation(L):
     assert f(FAKE, FAKE, FAKE, 8, 4096, 4096, None, 0, None) == 4
 
 
+def test_bf16_linear_validation(L):
+    """The bfloat16 entry points validate like their fp16 siblings (nothing is launched on an error)."""
+    f = L.morph_linear_bf16
+    assert f(None, FAKE, FAKE, 1, 128, 8, None, 0, None) == 1
+    assert f(FAKE, FAKE, FAKE, 1, 100, 8, None, 0, None) == 2
+    assert f(FAKE, FAKE + 2, FAKE, 1, 128, 8, None, 0, None) == 3
+    assert f(FAKE, FAKE, FAKE, 8, 4096, 4096, None, 0, None) == 4
+    for g in (L.morph_linear_w4a16_bf16, L.morph_linear_w8a16_bf16):
+        assert g(FAKE, FAKE, None, FAKE, FAKE, 1, 128, 8, 128, None, 0, None) == 1
+        assert g(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 128, 8, 64, None, 0, None) == 2
+        assert g(FAKE, FAKE, FAKE, FAKE, FAKE, 0, 128, 8, 128, None, 0, None) == 2
+        assert g(FAKE, FAKE, FAKE + 4, FAKE, FAKE, 1, 128, 8, 128, None, 0, None) == 3
+        assert g(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 4096, 4096, 128, None, 0, None) == 4
+        assert g(FAKE, FAKE, FAKE, FAKE, FAKE, 1, 128 * 1024 * 64, 1024, 128, None, 0, None) == 5
+
+
 def test_quantize_dequantize_validation(L):
     q, d = L.morph_quantize_layer, L.morph_dequantize_w4
     assert q(None, 0, FAKE, FAKE, FAKE, 128, 8, 128, None) == 1
-    assert q(FAKE, 2, FAKE, FAKE, FAKE, 128, 8, 128, None) == 2
+    assert q(FAKE, 3, FAKE, FAKE, FAKE, 128, 8, 128, None) == 2      # 0, 1, 2 = fp32, fp16, bf16
+    assert q(FAKE, -1, FAKE, FAKE, FAKE, 128, 8, 128, None) == 2
     assert q(FAKE, 0, FAKE, FAKE, FAKE, 128, 12, 128, None) == 2
     assert q(FAKE, 0, FAKE, FAKE, FAKE, 128, 8, 32, None) == 2
     assert q(FAKE + 4, 0, FAKE, FAKE, FAKE, 128, 8, 128, None) == 3

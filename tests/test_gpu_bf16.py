@@ -1,0 +1,290 @@
+"""GPU parity of the bfloat16 entry points (x, dense weights and y in bfloat16; 4-bit / 8-bit records
+unchanged) against the CPU oracle.
+
+Bars
+  * quantizer from bfloat16 masters, dequantizer to bfloat16: bit for bit;
+  * identity activations: y equals the bfloat16-rounded dequantized weight bit for bit, through both
+    kernel families;
+  * linears: max|y - y_ref| / max|y_ref| <= 1e-2.  bfloat16 keeps 8 significant bits: rounding y
+    alone costs up to 2^-8 = 3.9e-3 of |y| (half a unit in the last place, just above a power of
+    two), and the LDS-tiled kernels round each dequantized weight to bfloat16 once more (about 1e-3
+    of a typical output in all); measured 1.8e-3 .. 4.1e-3; an indexing mistake is O(1).
+bfloat16 arrays travel as uint16 bit patterns on the numpy side (numpy has no such type).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2506_02006_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2506_02006_amd import binding
+    binding.lib()
+    binding.warmup()
+    return binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def dev_bf(bits):
+    """uint16 bit patterns -> bfloat16 tensor on the GPU (same bits)."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def host_bf(t):
+    """bfloat16 tensor -> uint16 bit patterns."""
+    return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def widen(oracle, bits):
+    return oracle.bf16_to_fp32(bits).astype(np.float64)
+
+
+KINDS = ("dense", "w4", "w8")
+
+
+def make_case(oracle, kind, M, K, N, dist="normal", seed=0, x_scale=1.0):
+    W = synth.weights(86, K, N, layer_id=seed, dist=dist)
+    x = synth.activations(86, M, K, layer_id=seed).astype(np.float32) * np.float32(x_scale)
+    xb = oracle.fp32_to_bf16(x)
+    if kind == "dense":
+        wb = oracle.fp32_to_bf16(W)
+        return xb, (wb,)
+    return xb, (oracle.quantize_w4(W) if kind == "w4" else oracle.quantize_w8(W))
+
+
+def run_gpu(B, kind, xb, rec, M, K, N):
+    if kind == "dense":
+        ws = B.new_workspace(B.workspace_bytes(B.KIND_FP16, M, K, N))
+        return B.linear_bf16(dev_bf(xb), dev_bf(rec[0]), ws)
+    k, fn = (B.KIND_W4A16, B.linear_w4a16_bf16) if kind == "w4" else (B.KIND_W8A16, B.linear_w8a16_bf16)
+    ws = B.new_workspace(B.workspace_bytes(k, M, K, N))
+    return fn(dev_bf(xb), dev(rec[0]), dev(rec[1]), dev(rec[2]), ws)
+
+
+def run_oracle(oracle, kind, xb, rec):
+    if kind == "dense":
+        return oracle.linear_bf16(xb, rec[0])
+    return oracle.linear_q_bf16(4 if kind == "w4" else 8, xb, *rec)
+
+
+def check(B, oracle, kind, M, K, N, dist="normal", seed=0, x_scale=1.0):
+    xb, rec = make_case(oracle, kind, M, K, N, dist, seed, x_scale)
+    y = run_gpu(B, kind, xb, rec, M, K, N)
+    torch.cuda.synchronize()
+    r = oracle.error_metric(widen(oracle, host_bf(y)), run_oracle(oracle, kind, xb, rec))
+    say(f"  bf16 {kind:5s} M={M} K={K} N={N} x*{x_scale:g}: err={r['err']:.3e} at {r['argmax']}")
+    assert r["finite"] and r["err"] <= TOL, r
+    return r
+
+
+# ---------------- quantizer and dequantizer ----------------
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("K,N", [(128, 8), (384, 264), (1024, 2056)])
+def test_quantize_from_bf16_masters_bit_exact(B, oracle, bits, K, N):
+    W = synth.weights(86, K, N, layer_id=2, dist="student_t5")
+    wb = oracle.fp32_to_bf16(W)
+    qw, sc, qz = (oracle.quantize_w4 if bits == 4 else oracle.quantize_w8)(oracle.bf16_to_fp32(wb))
+    gq, gs, gz = (B.quantize_layer if bits == 4 else B.quantize_layer_w8)(dev_bf(wb))
+    assert np.array_equal(host(gs).view(np.uint16), sc.view(np.uint16))
+    assert np.array_equal(host(gz).view(np.uint32), qz)
+    assert np.array_equal(host(gq).view(np.uint32), qw)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("K,N", [(128, 8), (384, 264), (1024, 4096)])
+def test_dequantize_to_bf16_bit_exact(B, oracle, bits, K, N):
+    rng = np.random.default_rng(K + N + bits)
+    per = 32 // bits
+    qw = rng.integers(0, 2 ** 32, (K, N // per), dtype=np.uint64).astype(np.uint32)
+    qz = rng.integers(0, 2 ** 32, (K // 128, N // per), dtype=np.uint64).astype(np.uint32)
+    sc = rng.uniform(2.0 ** -14, 3.0, (K // 128, N)).astype(np.float16)
+    fn = B.dequantize_w4 if bits == 4 else B.dequantize_w8
+    got = host_bf(fn(dev(qw), dev(sc), dev(qz), torch.bfloat16))
+    assert np.array_equal(got, oracle.dequant_bf16(bits, qw, sc, qz))
+
+
+# ---------------- linears ----------------
+
+DECODE_SHAPES = [(1, 128, 8), (1, 4096, 4096), (3, 384, 264), (8, 256, 2048), (16, 1024, 1032), (17, 512, 1024),
+                 (32, 11008, 512), (33, 640, 776), (49, 1280, 264), (64, 768, 1288)]
+PREFILL_SHAPES = [(65, 256, 264), (100, 384, 776), (128, 128, 128), (256, 1024, 512), (300, 512, 1288), (513, 256, 520)]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("M,K,N", DECODE_SHAPES)
+def test_decode_bf16(B, oracle, kind, M, K, N):
+    check(B, oracle, kind, M, K, N, "student_t5" if M % 2 else "normal", seed=M)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("M,K,N", PREFILL_SHAPES)
+def test_prefill_bf16(B, oracle, kind, M, K, N):
+    check(B, oracle, kind, M, K, N, seed=M)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("split", [1, 2, 3, 7])
+def test_decode_bf16_every_split(B, oracle, kind, split):
+    B.set_tuning(B.TUNE_DECODE_SPLIT, split)
+    try:
+        for M in (1, 16, 33, 64):
+            check(B, oracle, kind, M, 1792, 520, seed=split)
+    finally:
+        B.set_tuning(B.TUNE_DECODE_SPLIT, 0)
+
+
+@pytest.mark.parametrize("rows", [16, 32])
+@pytest.mark.parametrize("mode", [1, 2, 3], ids=["shared", "last-arriver", "shared-nobody-waits"])
+def test_decode_bf16_w4_slices_and_hand_over(B, oracle, rows, mode):
+    B.set_tuning(B.TUNE_DECODE_SLICE, rows)
+    B.set_tuning(B.TUNE_DECODE_SCATTER, mode)
+    try:
+        for M in (3, 17, 40, 64):
+            check(B, oracle, "w4", M, 2048, 776, seed=rows + mode)
+    finally:
+        B.set_tuning(B.TUNE_DECODE_SLICE, 0)
+        B.set_tuning(B.TUNE_DECODE_SCATTER, 0)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+def test_prefill_bf16_every_tile(B, oracle, kind, tile):
+    B.set_tuning(B.TUNE_PREFILL_TILE, tile)
+    try:
+        check(B, oracle, kind, 300, 512, 776, seed=tile)
+        check(B, oracle, kind, 520, 256, 2312, seed=10 + tile)
+    finally:
+        B.set_tuning(B.TUNE_PREFILL_TILE, 0)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_prefill_bf16_shared_last_round(B, oracle, kind):
+    B.set_tuning(B.TUNE_PREFILL_SPLIT, 2)
+    try:
+        check(B, oracle, kind, 300, 8192, 520, seed=5)
+    finally:
+        B.set_tuning(B.TUNE_PREFILL_SPLIT, 0)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("max_m", [32, 1024, 0], ids=["mfma", "stream", "auto"])
+def test_mid_sizes_bf16_in_either_family(B, oracle, kind, max_m):
+    B.set_tuning(B.TUNE_DECODE_MAX_M, max_m)
+    try:
+        check(B, oracle, kind, 130, 512, 2824, seed=max_m)
+    finally:
+        B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
+
+
+@pytest.mark.parametrize("kind", ["w4", "w8"])
+@pytest.mark.parametrize("M", [16, 32, 64, 128, 256])
+def test_identity_activations_reproduce_bf16_dequantized(B, oracle, kind, M):
+    """x = rows of the identity: every output is a single term, so y must equal the dequantized
+    weight rounded once to bfloat16, bit for bit, through the real kernels (streaming up to 64
+    rows, LDS-tiled above): pins nibble / byte order, group indexing, the 2^64 that x carries into
+    the matrix cores and out again, and the bfloat16 rounding."""
+    K, N = 256, 520
+    W = synth.weights(86, K, N, layer_id=3)
+    bits = 4 if kind == "w4" else 8
+    rec = oracle.quantize_w4(W) if bits == 4 else oracle.quantize_w8(W)
+    Db = oracle.dequant_bf16(bits, *rec)
+    one = int(oracle.fp32_to_bf16(np.array([1.0], np.float32))[0])
+    for start in range(0, K, M):
+        xb = np.zeros((M, K), np.uint16)
+        xb[np.arange(M), start + np.arange(M)] = one
+        y = host_bf(run_gpu(B, kind, xb, rec, M, K, N))
+        assert np.array_equal(y, Db[start:start + M]), (M, start)
+
+
+@pytest.mark.parametrize("M", [8, 48, 200])
+def test_identity_activations_reproduce_bf16_weights(B, oracle, M):
+    K, N = 256, 520
+    wb = oracle.fp32_to_bf16(synth.weights(86, K, N, layer_id=4))
+    one = int(oracle.fp32_to_bf16(np.array([1.0], np.float32))[0])
+    xb = np.zeros((M, K), np.uint16)
+    xb[np.arange(M), np.arange(M)] = one
+    y = host_bf(run_gpu(B, "dense", xb, (wb,), M, K, N))
+    assert np.array_equal(y & 0x7FFF, wb[:M] & 0x7FFF) and np.array_equal(y[(wb[:M] & 0x7FFF) != 0], wb[:M][(wb[:M] & 0x7FFF) != 0])
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("M", [4, 40, 160])
+@pytest.mark.parametrize("x_scale", [2.0 ** -40, 2.0 ** 40])
+def test_activations_far_outside_the_fp16_range(B, oracle, kind, M, x_scale):
+    """The reason for the format: activations of magnitude 2^-40 and 2^40 (fp16 ends at 2^16)."""
+    check(B, oracle, kind, M, 512, 776, seed=M, x_scale=x_scale)
+
+
+def test_zero_rows_give_zero(B, oracle):
+    """An all-zero activation row must give exact zeros (the factor that x carries into the
+    matrix cores must leave zero alone)."""
+    K, N = 512, 520
+    W = synth.weights(86, K, N, layer_id=6)
+    for kind in KINDS:
+        for M in (5, 70):
+            xb, rec = make_case(oracle, kind, M, K, N, seed=6)
+            xb[1, :] = 0
+            xb[M - 1, :] = 0x8000                    # minus zero
+            y = host_bf(run_gpu(B, kind, xb, rec, M, K, N))
+            assert not (y[1] & 0x7FFF).any() and not (y[M - 1] & 0x7FFF).any(), (kind, M)
+
+
+# ---------------- at the sizes the benchmark times ----------------
+
+def sample_positions(rng, M, N):
+    rows = sorted({0, M - 1} | set(rng.integers(0, M, 14).tolist()) | {r for r in (127, 128, 255, 256) if r < M})
+    cols = sorted({0, N - 1} | set(rng.integers(0, N, 60).tolist()) | {c for c in (255, 256, 127, 128) if c < N})
+    rr, cc = np.meshgrid(np.array(rows), np.array(cols), indexing="ij")
+    return rr.ravel(), cc.ravel()
+
+
+@pytest.mark.parametrize("family,linear,M", [("llama7b", "qkv", 1), ("llama7b", "down", 16), ("llama3_8b", "gate_up", 64),
+                                             ("llama13b", "qkv", 2048), ("llama13b", "down", 512)])
+def test_full_size_layers_sampled(B, oracle, family, linear, M):
+    K, N = synth.LAYER_SHAPES[family][linear]
+    W = synth.layer_weights(86, family, linear)
+    xb = oracle.fp32_to_bf16(synth.activations(86, M, K).astype(np.float32))
+    rows, cols = sample_positions(np.random.default_rng(M + K), M, N)
+    rec = oracle.quantize_w4(W)
+    y = host_bf(run_gpu(B, "w4", xb, rec, M, K, N))
+    torch.cuda.synchronize()
+    ref = oracle.linear_q_bf16_at(4, xb, *rec, rows, cols)
+    got = widen(oracle, y[rows, cols])
+    # the denominator of the bar is the largest output of the whole call; the sample's largest is a lower bound of it
+    err = np.abs(got - ref).max() / np.abs(ref).max()
+    say(f"  bf16 w4 {family} {linear} M={M}: sampled err={err:.3e} over {rows.size} outputs")
+    assert np.isfinite(got).all() and err <= TOL
+    wb = oracle.fp32_to_bf16(W)
+    del W
+    y = host_bf(run_gpu(B, "dense", xb, (wb,), M, K, N))
+    ref = oracle.linear_bf16_at(xb, wb, rows, cols)
+    got = widen(oracle, y[rows, cols])
+    err = np.abs(got - ref).max() / np.abs(ref).max()
+    say(f"  bf16 dense {family} {linear} M={M}: sampled err={err:.3e}")
+    assert np.isfinite(got).all() and err <= TOL
