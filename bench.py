@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="headline only, skip the detail sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--sections", default="config2,config3,config4,config5,swap,w8,lis",
+    ap.add_argument("--sections", default="config2,config3,config4,config5,swap,w8,bf16,lis",
                     help="detail sections to run after the headline (comma separated; used by the profiling commands)")
     return ap.parse_args()
 
@@ -152,7 +152,7 @@ def main():
     avg_launch_s = sec / (args.steps * launches_per_step)
     roofline = {
         "bound": "hbm",
-        "kernel": "decode_kernel<1, 1, 4, true> (W4A16, M <= 16), mean over the 12 launches of a step",
+        "kernel": "decode_kernel<1, 1, 4, true, false> (W4A16, M <= 16), mean over the 12 launches of a step",
         "achieved": round(value, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
@@ -212,15 +212,23 @@ def main():
     sections = set() if args.quick else set(args.sections.split(","))
     if sections:
         # ---- per linear and per M, one shape back to back over the pool (W4A16 and fp16) ----
-        def per_linear(kind, family, name, M, recs, reps=60, vendor=False):
+        def per_linear(kind, family, name, M, recs, reps=60, vendor=False, bf=False):
             K, N = synth.LAYER_SHAPES[family][name]
             x = rand_x(M, K)
             y = torch.empty((M, N), device=dev, dtype=torch.float16)
+            if bf:
+                x, y = x.to(torch.bfloat16), y.to(torch.bfloat16)
             w = B.new_workspace(B.workspace_bytes(kind, M, K, N))
             def run():
                 for r in recs:
                     if vendor:
                         torch.matmul(x, r, out=y)
+                    elif bf and kind == B.KIND_W4A16:
+                        B.linear_w4a16_bf16(x, r[0], r[1], r[2], w, out=y)
+                    elif bf and kind == B.KIND_W8A16:
+                        B.linear_w8a16_bf16(x, r[0], r[1], r[2], w, out=y)
+                    elif bf:
+                        B.linear_bf16(x, r, w, out=y)
                     elif kind == B.KIND_W4A16:
                         B.linear_w4a16(x, r[0], r[1], r[2], w, out=y)
                     elif kind == B.KIND_W8A16:
@@ -291,6 +299,35 @@ def main():
                                                   "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1)}
                 del w8
             detail["w8a16_llama7b_decode_13b_prefill"] = d8w
+
+        # ---- bfloat16 activations and outputs: 7B shapes at decode sizes, 13B shapes at M = 2048 ----
+        if "bf16" in sections:
+            dbf = {}
+            for kind, label in ((B.KIND_W4A16, "w4a16_bf16"), (B.KIND_FP16, "bf16")):
+                for name in order:
+                    recs = cold_pool(kind, *shapes7[name])
+                    if kind == B.KIND_FP16:
+                        recs = [r.view(torch.bfloat16) for r in recs]       # any bit pattern times the same bytes
+                        for r in recs:
+                            r.normal_(0.0, 0.02, generator=gen)
+                    for M in (1, 16, 32):
+                        dbf[f"{label}/{name}/M{M}"] = per_linear(kind, "llama7b", name, M, recs, reps=2 * len(recs), bf=True)
+                    del recs
+            for name in order:
+                K, N = synth.LAYER_SHAPES["llama13b"][name]
+                w4 = make_w4(K, N)
+                wb = rand_w(K, N).to(torch.bfloat16)
+                x = rand_x(2048, K).to(torch.bfloat16)
+                y = torch.empty((2048, N), device=dev, dtype=torch.bfloat16)
+                wsp = B.new_workspace(max(B.workspace_bytes(B.KIND_W4A16, 2048, K, N), B.workspace_bytes(B.KIND_FP16, 2048, K, N)))
+                for label, fn in (("w4a16_bf16", lambda: B.linear_w4a16_bf16(x, w4[0], w4[1], w4[2], wsp, out=y)),
+                                  ("bf16", lambda: B.linear_bf16(x, wb, wsp, out=y))):
+                    sb = timed(lambda i: fn(), 10, 2) / 10
+                    tf = 2.0 * 2048 * K * N / sb / 1e12
+                    dbf[f"{label}/13b_{name}/M2048"] = {"us": round(sb * 1e6, 1), "TFLOPs": round(tf, 1),
+                                                        "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1)}
+                del w4, wb
+            detail["bf16_llama7b_decode_13b_prefill"] = dbf
 
         # ---- cosine similarity of activations (the layer-importance metrics): an HBM-bound reduction ----
         if "lis" in sections:

@@ -61,6 +61,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
     return bit_cast<uint32_t>(__builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
+// The two fp16 halves of d, each times the fp32 scale s (exact in fp32), rounded into the two bfloat16
+// halves of a word.  Written as fused multiply-adds with a zero addend so that the fp16 operand is
+// widened inside the instruction (v_fma_mix_f32) instead of by a conversion of its own.
+__device__ __forceinline__ uint32_t scale_to_bf16x2(half2_t d, float s)
+{
+    return pack_bf16x2(__builtin_fmaf((float)d[0], s, 0.0f), __builtin_fmaf((float)d[1], s, 0.0f));
+}
 
 // Q: 0 = fp16 weights, 1 = 4-bit codes, 2 = 8-bit codes.
 // BF: x, y and the weights of kind 0 are bfloat16 (v_mfma_f32_32x32x16_bf16); the weight tile of the
@@ -239,8 +246,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                     const half2_t d0 = bit_cast<half2_t>(p0 | 0x64006400u) + cz0;                                  // q - z, exact
                     const half2_t d1 = bit_cast<half2_t>(p1 | 0x64006400u) + cz1;
                     if constexpr (BF) {
-                        c0[q] = pack_bf16x2((float)d0[0] * (float)s0, (float)d0[1] * (float)s0);
-                        c1[q] = pack_bf16x2((float)d1[0] * (float)s1, (float)d1[1] * (float)s1);
+                        c0[q] = scale_to_bf16x2(d0, (float)s0);
+                        c1[q] = scale_to_bf16x2(d1, (float)s1);
                     } else {
                         c0[q] = bit_cast<uint32_t>(d0 * s0p);
                         c1[q] = bit_cast<uint32_t>(d1 * s1p);
@@ -269,8 +276,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                                       : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
                     if constexpr (BF) {
                         const half2_t dl = nib_lo_1024(pr) + czl, dh = nib_hi_1024(pr) + czh16;
-                        lo8[q] = pack_bf16x2((float)dl[0] * (float)s0, (float)dl[1] * (float)s0);
-                        hi8[q] = pack_bf16x2((float)dh[0] * s1_16, (float)dh[1] * s1_16);
+                        lo8[q] = scale_to_bf16x2(dl, (float)s0);
+                        hi8[q] = scale_to_bf16x2(dh, s1_16);
                     } else {
                         lo8[q] = bit_cast<uint32_t>((nib_lo_1024(pr) + czl) * s0p);         // (q - z) * s, one rounding
                         hi8[q] = bit_cast<uint32_t>((nib_hi_1024(pr) * sixteenth + czh) * s1p);
