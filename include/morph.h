@@ -125,7 +125,8 @@ int morph_dequantize_w8(const int32_t* qweight, const void* scales, const int32_
  * Accumulation is fp32; y is rounded once, to nearest even.  Decode sizes feed the codes to the
  * bfloat16 matrix instruction as they are; the LDS-tiled kernels hold (q - z) * s rounded once
  * to bfloat16.  The quantized kinds multiply x by 2^64 on its way into the matrix cores (the codes
- * sit at the bottom of the bfloat16 range): |x| must stay below 2^63, beyond that y is inf / NaN.
+ * sit at the bottom of the bfloat16 range) and sum 128 of them per group in fp32: |x| must stay
+ * below 2^56, beyond that y may be inf / NaN; rows whose largest |x| is below about 2^-64 lose precision.
  * M dispatch, workspace (same kinds, same sizes), alignment and errors as for the fp16 calls. */
 int morph_linear_bf16(const void* x, const void* w, void* y, int M, int K, int N,
                       void* workspace, size_t workspace_bytes, void* stream);

@@ -29,7 +29,8 @@
 //     lane is then the bfloat16 value b * 2^-133 (bit patterns below 256 are linear in value: the
 //     subnormals and the first normal binade; the matrix core honours them, measured).  So that
 //     the fp32 sums stay far from the bottom of the fp32 range, x is multiplied by 2^64 on its way
-//     into the MFMA (exact: a power of two, |x| < 2^63 assumed) and the fold takes it out again:
+//     into the MFMA (exact: a power of two; |x| < 2^56 assumed, so that a group of 128 sums cannot
+//     overflow) and the fold takes it out again:
 //     y += s * (2^69 * acc - z * 2^-64 * rowsum(2^64 x)).
 #pragma once
 #include "dev_common.h"
