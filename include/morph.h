@@ -242,6 +242,10 @@ int morph_layer_swap_async(void* slot, size_t slot_bytes, const void* host_recor
  * the value the metrics use.  The weights of Eq. 5 are applied by the caller. */
 int morph_cosine_rows(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H,
                       void* stream);
+/* The same for bfloat16 activations (a, b: bfloat16 [M,H]).  The three sums of a row are fp32: rows
+ * whose sum of squares leaves the fp32 range (|x| beyond about 2^60) give 0 or NaN. */
+int morph_cosine_rows_bf16(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H,
+                           void* stream);
 
 /* Launch every kernel variant once on tiny internal dummies so that code objects are loaded
  * before serving starts (Section 4.3: kernels are precompiled ahead of time; Appendix C: with

@@ -30,7 +30,7 @@ EXPORTS = [
     "morph_probe_out_bytes", "morph_probe_read", "morph_probe_mfma",
     "morph_layer_record_bytes", "morph_layer_record_desc", "morph_layer_swap_async",
     "morph_quantize_layer_w8", "morph_dequantize_w8", "morph_linear_w8a16", "morph_cosine_rows",
-    "morph_linear_bf16", "morph_linear_w4a16_bf16", "morph_linear_w8a16_bf16",
+    "morph_linear_bf16", "morph_linear_w4a16_bf16", "morph_linear_w8a16_bf16", "morph_cosine_rows_bf16",
 ]
 
 
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
     L.morph_linear_w4a16_bf16.argtypes = L.morph_linear_w4a16.argtypes
     L.morph_linear_w8a16_bf16.argtypes = L.morph_linear_w4a16.argtypes
     L.morph_cosine_rows.argtypes = [vp, vp, vp, vp, i, i, vp]
+    L.morph_cosine_rows_bf16.argtypes = [vp, vp, vp, vp, i, i, vp]
     L.morph_quantize_layer_w8.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w8.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_workspace_bytes.argtypes = [i, i, i, i]
@@ -287,13 +288,18 @@ def copy(src: torch.Tensor, dst: torch.Tensor):
 
 
 def cosine_rows(a: torch.Tensor, b: torch.Tensor):
-    """Per-token cosine of two fp16 [M,H] activation tensors and its mean: (fp32 [M], fp32 [1]) on the device."""
+    """Per-token cosine of two fp16 (or two bfloat16) [M,H] activation tensors and its mean:
+    (fp32 [M], fp32 [1]) on the device."""
     M, H = a.shape
     assert b.shape == (M, H)
     cos = torch.empty((M,), dtype=torch.float32, device=a.device)
     mean = torch.empty((1,), dtype=torch.float32, device=a.device)
-    _check(lib().morph_cosine_rows(_dev(a, torch.float16, "a"), _dev(b, torch.float16, "b"), cos.data_ptr(),
-                                   mean.data_ptr(), M, H, _stream()), "morph_cosine_rows")
+    if a.dtype == torch.bfloat16:
+        _check(lib().morph_cosine_rows_bf16(_dev(a, torch.bfloat16, "a"), _dev(b, torch.bfloat16, "b"), cos.data_ptr(),
+                                            mean.data_ptr(), M, H, _stream()), "morph_cosine_rows_bf16")
+    else:
+        _check(lib().morph_cosine_rows(_dev(a, torch.float16, "a"), _dev(b, torch.float16, "b"), cos.data_ptr(),
+                                       mean.data_ptr(), M, H, _stream()), "morph_cosine_rows")
     return cos, mean
 
 

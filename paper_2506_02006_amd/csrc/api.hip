@@ -553,13 +553,25 @@ int morph_layer_swap_async(void* slot, size_t slot_bytes, const void* host_recor
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
 
-int morph_cosine_rows(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H, void* stream)
+namespace {
+int cosine_any(const void* a, const void* b, int bf, float* cos_out, float* mean_out, int M, int H, void* stream)
 {
     if (!a || !b || !cos_out) return MORPH_ERR_NULL;
     if (M < 1 || H < 8 || H % 8 != 0) return MORPH_ERR_SHAPE;
     if (!aligned16(a) || !aligned16(b) || (reinterpret_cast<uintptr_t>(cos_out) & 3u) ||
         (mean_out && (reinterpret_cast<uintptr_t>(mean_out) & 3u))) return MORPH_ERR_ALIGN;
-    return launch_cosine_rows(a, b, cos_out, mean_out, M, H, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+    return launch_cosine_rows(a, b, bf, cos_out, mean_out, M, H, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+}  // namespace
+
+int morph_cosine_rows(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H, void* stream)
+{
+    return cosine_any(a, b, 0, cos_out, mean_out, M, H, stream);
+}
+
+int morph_cosine_rows_bf16(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H, void* stream)
+{
+    return cosine_any(a, b, 1, cos_out, mean_out, M, H, stream);
 }
 
 size_t morph_probe_out_bytes(void) { return kProbeOutBytes; }
@@ -641,6 +653,7 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     for (int op = MORPH_GLUE_QKV; op <= MORPH_GLUE_RMS; op++)
         if ((rc = morph_glue(op, w, x, y, 2, 64, stream))) return rc;
     if ((rc = morph_cosine_rows(x, w, reinterpret_cast<float*>(y), reinterpret_cast<float*>(y) + 64, 2, 128, stream))) return rc;
+    if ((rc = morph_cosine_rows_bf16(x, w, reinterpret_cast<float*>(y), reinterpret_cast<float*>(y) + 64, 2, 128, stream))) return rc;
     if (launch_copy(x, y, 4096, st) != hipSuccess) return MORPH_ERR_DEVICE;
     return MORPH_OK;
 }

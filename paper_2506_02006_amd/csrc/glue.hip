@@ -111,21 +111,23 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ s, 
         d[i] = s[i];
 }
 
-// Cosine similarity of row t of a with row t of b (fp16 [M,H]), one workgroup per row.  Every
-// thread sums its share of the three dot products in fp32 in a fixed order, lanes and waves are
-// combined in a fixed order: the result does not depend on timing.
-__global__ __launch_bounds__(256) void cosine_rows_kernel(const half_t* __restrict__ a, const half_t* __restrict__ b,
+// Cosine similarity of row t of a with row t of b (fp16 or, with BF, bfloat16 [M,H]), one workgroup
+// per row.  Every thread sums its share of the three dot products in fp32 in a fixed order, lanes and
+// waves are combined in a fixed order: the result does not depend on timing.
+template <bool BF>
+__global__ __launch_bounds__(256) void cosine_rows_kernel(const uint16_t* __restrict__ a, const uint16_t* __restrict__ b,
                                                           float* __restrict__ cos_out, int H)
 {
     __shared__ float part[3][4];
     const int row = blockIdx.x, tid = threadIdx.x;
-    const half_t* ar = a + (size_t)row * H;
-    const half_t* br = b + (size_t)row * H;
+    const u32x4* ar = reinterpret_cast<const u32x4*>(a + (size_t)row * H);     // vectors of 8 values
+    const u32x4* br = reinterpret_cast<const u32x4*>(b + (size_t)row * H);
     float dot = 0.f, na = 0.f, nb = 0.f;
-    auto add = [&](const half8_t& x, const half8_t& y) {
+    auto add = [&](const u32x4& x, const u32x4& y) {
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            const float xf = (float)x[j], yf = (float)y[j];
+            const float xf = widen16<BF>((j & 1) ? x[j >> 1] >> 16 : x[j >> 1] & 0xFFFFu);
+            const float yf = widen16<BF>((j & 1) ? y[j >> 1] >> 16 : y[j >> 1] & 0xFFFFu);
             dot = __builtin_fmaf(xf, yf, dot);
             na  = __builtin_fmaf(xf, xf, na);
             nb  = __builtin_fmaf(yf, yf, nb);
@@ -134,15 +136,14 @@ __global__ __launch_bounds__(256) void cosine_rows_kernel(const half_t* __restri
     const int nv = H / 8;
     int v = tid;
     for (; v + 256 < nv; v += 512) {                       // four independent 16-byte loads in flight (read once: non-temporal)
-        const half8_t x0 = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(ar + 8 * v));
-        const half8_t y0 = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(br + 8 * v));
-        const half8_t x1 = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(ar + 8 * (v + 256)));
-        const half8_t y1 = __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(br + 8 * (v + 256)));
+        const u32x4 x0 = __builtin_nontemporal_load(ar + v);
+        const u32x4 y0 = __builtin_nontemporal_load(br + v);
+        const u32x4 x1 = __builtin_nontemporal_load(ar + v + 256);
+        const u32x4 y1 = __builtin_nontemporal_load(br + v + 256);
         add(x0, y0);
         add(x1, y1);
     }
-    for (; v < nv; v += 256)
-        add(*reinterpret_cast<const half8_t*>(ar + 8 * v), *reinterpret_cast<const half8_t*>(br + 8 * v));
+    for (; v < nv; v += 256) add(ar[v], br[v]);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         dot += __shfl_xor(dot, off, 64);
@@ -219,9 +220,10 @@ __global__ __launch_bounds__(kProbeMfmaThreads) void probe_mfma_kernel(int iters
 
 }  // namespace
 
-hipError_t launch_cosine_rows(const void* a, const void* b, float* cos_out, float* mean_out, int M, int H, hipStream_t st)
+hipError_t launch_cosine_rows(const void* a, const void* b, int bf, float* cos_out, float* mean_out, int M, int H, hipStream_t st)
 {
-    hipLaunchKernelGGL(cosine_rows_kernel, dim3(M), dim3(256), 0, st, (const half_t*)a, (const half_t*)b, cos_out, H);
+    if (bf) hipLaunchKernelGGL(cosine_rows_kernel<true>, dim3(M), dim3(256), 0, st, (const uint16_t*)a, (const uint16_t*)b, cos_out, H);
+    else    hipLaunchKernelGGL(cosine_rows_kernel<false>, dim3(M), dim3(256), 0, st, (const uint16_t*)a, (const uint16_t*)b, cos_out, H);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     if (mean_out) hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st, cos_out, M, mean_out);
     return hipGetLastError();

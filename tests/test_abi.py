@@ -205,8 +205,9 @@ def test_layer_record_and_swap_validation(L):
     assert L.morph_layer_swap_async(B256, need - 1, B256, 1, 128, 128, None) == 4
 
 
-def test_cosine_rows_validation(L):
-    f = L.morph_cosine_rows
+@pytest.mark.parametrize("fname", ["morph_cosine_rows", "morph_cosine_rows_bf16"])
+def test_cosine_rows_validation(L, fname):
+    f = getattr(L, fname)
     assert f(None, FAKE, FAKE, None, 4, 64, None) == 1 and f(FAKE, None, FAKE, None, 4, 64, None) == 1
     assert f(FAKE, FAKE, None, None, 4, 64, None) == 1
     assert f(FAKE, FAKE, FAKE, None, 0, 64, None) == 2 and f(FAKE, FAKE, FAKE, None, 4, 60, None) == 2

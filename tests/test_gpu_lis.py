@@ -110,3 +110,29 @@ def test_layer_importance_scores_of_a_small_stack(B, oracle):
     assert np.abs(lis - lis_ref).max() <= 2e-5
     # replacing a layer by its 4-bit variant changes little, a layer itself changes a lot
     assert min(lrs) > 0.99 and max(lts) < 0.99 and min(mds) > 0.9
+
+
+@pytest.mark.parametrize("M,H", [(1, 8), (5, 264), (33, 4096), (64, 11008)])
+@pytest.mark.parametrize("scale", [1.0, 2.0 ** 30, 2.0 ** -30])
+def test_cosine_rows_bf16_against_oracle(B, oracle, M, H, scale):
+    """bfloat16 activations (bit patterns made by the oracle's pinned conversion), also at magnitudes
+    fp16 cannot hold; the cosine does not depend on the scale, the sums inside do."""
+    rng = np.random.default_rng(M * 1000 + H + 7)
+    a32 = (rng.standard_normal((M, H)) * scale).astype(np.float32)
+    b32 = (0.7 * a32 + 0.5 * scale * rng.standard_normal((M, H))).astype(np.float32)
+    ab, bb = oracle.fp32_to_bf16(a32), oracle.fp32_to_bf16(b32)
+    if M >= 5:
+        bb[0] = ab[0]
+        bb[1] = ab[1] ^ 0x8000           # antiparallel: the sign bit of every element
+        ab[3] = 0
+    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    cos, mean = B.cosine_rows(to_dev(ab), to_dev(bb))
+    torch.cuda.synchronize()
+    ref = oracle.cosine_rows(oracle.bf16_to_fp32(ab), oracle.bf16_to_fp32(bb))
+    tol = 2e-5 if H <= 4096 else 3e-5
+    err = np.abs(host(cos).astype(np.float64) - ref).max()
+    say(f"  cosine bf16 M={M} H={H} x{scale:g}: max |diff| = {err:.2e}")
+    assert err <= tol
+    assert abs(float(host(mean)[0]) - ref.mean()) <= tol
+    if M >= 5:
+        assert host(cos)[3] == 0.0 and abs(host(cos)[0] - 1.0) <= tol and abs(host(cos)[1] + 1.0) <= tol
