@@ -256,7 +256,8 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
 /* Override a kernel-selection heuristic (0 restores the default).  For benchmarking sweeps only;
  * defaults are chosen from the shape.  Keys: 0 = K-split factor of the decode kernels,
  * 1 = target workgroup count of the decode kernels, 2 = prefill tile (1 = 256x256 with 8 waves,
- * 2 = 128x128, 3 = 256x256 with 4 waves, 4 = 256x128, 5 = 256x192), 3 = waves per decode workgroup (4 or 8),
+ * 2 = 128x128, 3 = 256x256 with 4 waves, 4 = 256x128 with 4 waves, 5 = 256x192, 6 = 256x128 with 8 waves),
+ * 3 = waves per decode workgroup (4 or 8),
  * 4 = prefill: sharing the last partial round of tiles out along K (1 = never, 2 = always),
  * 5 = prefill: order in which tiles are dealt to workgroups (1 = row tiles of a column tile first,
  * 2 = blocks of 8 column tiles spread over the 8 XCDs), 6 = largest M the streaming kernels take
@@ -265,6 +266,8 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
  * 9 = streaming kernels: sum over the K splits shared out among the workgroups of a tile (1 = whenever
  * possible, 2 = never, 3 = whenever possible and no workgroup waits for the others, which leaves every
  * part to the last one out: exercises the path taken after a wait that ran out).
+ * 10 = prefill: number of workgroups (at most one per compute unit; with key 4 = 2 and fewer tiles than
+ * that, K is shared out over them).
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);
 

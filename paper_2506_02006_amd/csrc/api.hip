@@ -34,14 +34,18 @@ bool takes_stream(int kind, int M, int K, int N)
     const int cus = prefill_compute_units();
     const DecodePlan dp = plan_decode(kind, M, K, N);
     if (dp.S > 1 && dp.tiles * dp.slices > (int)(kCounterBytes / sizeof(int)) / 2) return false;   // more tiles than counters
-    const double ns_per_row = kind == MORPH_KIND_W4A16 ? 6.7 : kind == MORPH_KIND_W8A16 ? 4.5 : 6.0;   // one workgroup walking its rows of K
+    // one workgroup walking its rows of K; fp16 rows come faster when many slices share them in the L2s
+    const double ns_per_row = kind == MORPH_KIND_W4A16 ? 6.7 : kind == MORPH_KIND_W8A16 ? 4.5 : (dp.slices >= 8 ? 4.5 : 6.0);
     const long long wgs = (long long)dp.tiles * dp.slices * dp.S;
     const double est_stream = 8.0 + (double)((wgs + cus - 1) / cus) * ((double)K / dp.S) * ns_per_row * 1e-3;
     const PrefillPlan pp = plan_prefill(M, K, N);
-    const double busy = pp.tiles < cus ? (double)pp.tiles / cus : 1.0;
-    const double step_us = 0.9 + 0.8 * busy * ((double)pp.bm * pp.bn / 65536.0);
-    double est_mfma = (double)((pp.tiles + cus - 1) / cus) * (K / 64) * step_us;
-    if (pp.split_tail) est_mfma *= 0.65;
+    double est_mfma = pp.est_us;                         // the planner's own estimate when it chose by shape
+    if (est_mfma <= 0.0) {
+        const double busy = pp.tiles < cus ? (double)pp.tiles / cus : 1.0;
+        const double step_us = 0.9 + 0.8 * busy * ((double)pp.bm * pp.bn / 65536.0);
+        est_mfma = (double)((pp.tiles + cus - 1) / cus) * (K / 64) * step_us;
+        if (pp.split_tail) est_mfma *= 0.65;
+    }
     return est_stream < est_mfma;
 }
 

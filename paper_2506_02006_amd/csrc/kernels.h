@@ -71,6 +71,7 @@ struct PrefillPlan {
     int    config, bm, bn, tiles, grid, split_tail;
     size_t counter_bytes;  // head of the workspace
     size_t partial_bytes;  // 0 when every share is made of whole tiles
+    double est_us;         // estimated time when the configuration was chosen by shape (0 when forced)
 };
 PrefillPlan plan_prefill(int M, int K, int N);
 int prefill_compute_units();   // compute units of the current device (256 when it cannot be asked)
@@ -117,6 +118,6 @@ hipError_t launch_probe_mfma(int iters, void* out, hipStream_t st);
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_DECODE_SCATTER = 9, TUNE_COUNT = 12 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_DECODE_SCATTER = 9, TUNE_PREFILL_GRID = 10, TUNE_COUNT = 12 };
 
 }  // namespace morph

@@ -572,50 +572,66 @@ int prefill_compute_units()
     return cus;
 }
 
-// Tile choice: estimated time = rounds of tiles over the compute units x tile area x a measured
-// cost per flop of each configuration relative to the 256 x 256 tile (smaller tiles reuse their
-// operands less and stage relatively more): 256 x 192: 1.2, 256 x 128 (4 waves): 1.75, 128 x 128: 3.
+// Tile and split choice by estimated time (constants measured on MI355X on 13B-shaped layers, us):
+//   one k step of 64 takes  256x256: 1.2 + 0.6 occ,  256x192: 1.15 + 0.3 occ,  256x128 (8 waves):
+//   1.0 + 0.17 occ,  128x128: 0.95   (occ = share of the compute units that hold a workgroup: the
+//   clock gives way as more of them multiply);
+//   time = rounds of workgroups over the compute units x k steps per workgroup x that.
+// Where the tiles do not fill half the compute units, K may be cut into s equal parts per tile
+// (workgroups = tiles x s, every part of every tile a workgroup of its own, so that workgroups on
+// the same k range still walk in step and share operands through the L2s); the parts meet through
+// fp32 partial tiles in memory, which costs about 15 + 11.5 s us with 256x128 tiles (128 KB per
+// part) and 11 s us with 128x128 tiles; with 256-wide tiles it never paid (256 KB per part).
+// Measured at M = 256 / 512 on the 13B shapes: o-proj 80 -> 57 us at M = 256, down-proj 134 -> 101 us
+// (M = 256) and 148 -> 137 us (M = 512).
 PrefillPlan plan_prefill(int M, int K, int N)
 {
     PrefillPlan pl;
     const int cus = prefill_compute_units();
     const int kt = K / BK;
-    int cfg = tuning_get(TUNE_PREFILL_TILE);             // 0 = by shape, 1 = 256x256 (8 waves), 2 = 128x128, 3 = 256x256 (4 waves), 4 = 256x128, 5 = 256x192
+    const int force = tuning_get(TUNE_PREFILL_SPLIT);   // 1 = never share K out, 2 = whenever the tiles allow it
+    int cfg = tuning_get(TUNE_PREFILL_TILE);             // 0 = by shape, 1 = 256x256 (8 waves), 2 = 128x128, 3 = 256x256 (4 waves), 4 = 256x128 (4 waves), 5 = 256x192, 6 = 256x128 (8 waves)
+    int parts = 1;                                       // equal parts of K per tile (by shape only)
+    double best = 0.0;
     if (cfg == 0) {
-        struct Cand { int cfg, bm, bn; double f; };
-        const Cand cands[4] = {{1, 256, 256, 1.0}, {5, 256, 192, 1.2}, {4, 256, 128, 1.75}, {2, 128, 128, 3.0}};
-        double best = 0.0;
+        struct Cand { int cfg, bm, bn; double t0, t1, h0, h1; };   // step time t0 + t1 occ; hand-over h0 + h1 s (h1 = 0: never split)
+        const Cand cands[4] = {{1, 256, 256, 1.2, 0.6, 0.0, 0.0}, {5, 256, 192, 1.15, 0.3, 0.0, 0.0},
+                               {6, 256, 128, 1.0, 0.17, 15.0, 11.5}, {2, 128, 128, 0.95, 0.0, 0.0, 11.0}};
         for (const Cand& c : cands) {
             const long long t = (long long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
-            const double cost = (double)((t + cus - 1) / cus) * c.bm * c.bn * c.f;
-            if (cfg == 0 || cost < best) { cfg = c.cfg; best = cost; }
+            const int smax = (c.h1 > 0.0 && force != 1 && 2 * t <= cus) ? (int)(cus / t) : 1;
+            for (int sp = 1; sp <= smax && sp <= 4 && sp <= kt; sp++) {
+                const long long wgs = t * sp;
+                const double occ = wgs < cus ? (double)wgs / cus : 1.0;
+                const double est = (double)((wgs + cus - 1) / cus) * ((kt + sp - 1) / sp) * (c.t0 + c.t1 * occ)
+                                 + (sp > 1 ? c.h0 + c.h1 * sp : 0.0);
+                if (cfg == 0 || est < best) { cfg = c.cfg; parts = sp; best = est; }
+            }
         }
-        // few tiles with a long K: the 256 x 128 tile with its last (only) round shared out along K
-        const long long t256x128 = (long long)((M + 255) / 256) * ((N + 127) / 128);
-        if (t256x128 < cus && 2 * t256x128 < cus && kt >= 128) cfg = 4;
     }
     pl.config = cfg;
     pl.bm = (cfg == 2) ? 128 : 256;
-    pl.bn = (cfg == 2 || cfg == 4) ? 128 : (cfg == 5 ? 192 : 256);
+    pl.bn = (cfg == 2 || cfg == 4 || cfg == 6) ? 128 : (cfg == 5 ? 192 : 256);
     pl.tiles = ((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn);
     pl.grid = pl.tiles < cus ? ((long long)pl.tiles * kt < cus ? pl.tiles * kt : cus) : cus;
+    if (parts > 1) pl.grid = pl.tiles * parts;
+    const int forced_grid = tuning_get(TUNE_PREFILL_GRID);
+    if (forced_grid > 0 && forced_grid <= cus && (long long)forced_grid <= (long long)pl.tiles * kt) pl.grid = forced_grid;
+    pl.est_us = best;
     const int tail = pl.tiles % pl.grid;
-    // A last round that leaves most compute units without a tile may be shared out along K instead
-    // (stream-K): every workgroup takes an equal run of k-tiles of the remaining tiles, tiles cut in
-    // the middle are finished by whoever arrives last.  The kernel numbers those tiles row tile by
-    // row tile, which needs the remainder to be a rectangle (all row tiles of the last column
-    // tiles).  Measured, the fp32 partial tiles (256 KB each, written through and read back) cost
-    // more than the idle compute units except when there are few tiles with a long K, so that is
-    // the only case it is used in.  Tuning key 4 overrides: 1 = never, 2 = whenever the rectangle holds.
+    // The tiles left over after the full rounds (all of them when there are fewer tiles than
+    // workgroups) may be shared out along K: every workgroup takes an equal run of their k-tiles,
+    // tiles cut in the middle are finished by whoever arrives last (stream-K; with workgroups = tiles x
+    // parts the cuts fall on the same k for every tile).  The kernel numbers those tiles row tile by
+    // row tile, which needs the remainder to be a rectangle (all row tiles of the last column tiles).
+    // By shape it is used only as chosen above; tuning key 4 = 2 forces it wherever the rectangle holds.
     const int tiles_m = (M + pl.bm - 1) / pl.bm, tiles_n = pl.tiles / tiles_m;
     const int map = (tuning_get(TUNE_PREFILL_MAP) == 1 || pl.grid % 8 != 0) ? 1 : 2;
     const int tail_first = pl.tiles - tail;
     const int blk = 8 * tiles_m, full = (tiles_n / 8) * blk;
     const bool rect = map == 1 ? tail_first % tiles_m == 0
                                : (tail_first <= full ? tail_first % blk == 0 : (tail_first - full) % tiles_m == 0);
-    const int force = tuning_get(TUNE_PREFILL_SPLIT);
-    const bool worth = pl.tiles < pl.grid && 2 * tail < pl.grid && kt >= 128;
-    pl.split_tail = tail != 0 && rect && force != 1 && (force == 2 || worth);
+    pl.split_tail = tail != 0 && rect && force != 1 && (force == 2 || parts > 1 || (forced_grid > 0 && pl.grid > pl.tiles));
     // every share may end and begin inside a tile: two partial slots per workgroup, plus the counters
     pl.counter_bytes = ((size_t)pl.grid * sizeof(int) + 255) & ~(size_t)255;
     pl.partial_bytes = pl.split_tail ? (size_t)2 * pl.grid * pl.bm * pl.bn * sizeof(float) : 0;
@@ -630,6 +646,7 @@ static hipError_t launch_config(const GemmArgs& a, hipStream_t st)
         case 3: return launch_tile<Q, 256, 256, 2, 2, BF>(a, st);
         case 4: return launch_tile<Q, 256, 128, 2, 2, BF>(a, st);
         case 5: return launch_tile<Q, 256, 192, 4, 2, BF>(a, st);
+        case 6: return launch_tile<Q, 256, 128, 4, 2, BF>(a, st);
         default: return launch_tile<Q, 128, 128, 2, 2, BF>(a, st);
     }
 }
