@@ -173,7 +173,7 @@ def test_decode_bf16_w4_slices_and_hand_over(B, oracle, rows, mode):
 
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
 def test_prefill_bf16_every_tile(B, oracle, kind, tile):
     B.set_tuning(B.TUNE_PREFILL_TILE, tile)
     try:

@@ -151,7 +151,7 @@ def test_prefill_fp16(B, oracle, M, K, N):
     check_fp16(B, oracle, M, K, N, seed=M)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("order", [1, 2])
 def test_prefill_every_tile_and_order(B, oracle, tile, order):
     """Every tile configuration under both orders of dealing tiles to workgroups, on a shape with
@@ -165,6 +165,40 @@ def test_prefill_every_tile_and_order(B, oracle, tile, order):
     finally:
         B.set_tuning(B.TUNE_PREFILL_TILE, 0)
         B.set_tuning(B.TUNE_PREFILL_MAP, 0)
+
+
+@pytest.mark.parametrize("tile,parts", [(6, 2), (6, 3), (6, 4), (2, 2), (2, 3), (1, 2)])
+def test_prefill_k_cut_into_equal_parts(B, oracle, tile, parts):
+    """Few tiles: K is cut into `parts` equal parts per tile, workgroups = tiles x parts, the parts meet
+    through fp32 partial tiles and the last one to arrive adds them in a fixed order.  Forced here
+    (tile, workgroup count, sharing on) with a k-tile count that the parts do and do not divide."""
+    bm, bn = {1: (256, 256), 2: (128, 128), 6: (256, 128)}[tile]
+    B.set_tuning(B.TUNE_PREFILL_TILE, tile)
+    B.set_tuning(B.TUNE_PREFILL_SPLIT, 2)
+    B.set_tuning(B.TUNE_DECODE_MAX_M, 32)
+    try:
+        for M, K, N in ((300, 1536, 776), (130, 1408, 520)):
+            tiles = -(-M // bm) * -(-N // bn)
+            B.set_tuning(B.TUNE_PREFILL_GRID, tiles * parts)
+            check_w4(B, oracle, M, K, N, seed=tile + parts)
+            check_fp16(B, oracle, M, K, N, seed=tile + parts + 1)
+    finally:
+        B.set_tuning(B.TUNE_PREFILL_TILE, 0)
+        B.set_tuning(B.TUNE_PREFILL_SPLIT, 0)
+        B.set_tuning(B.TUNE_PREFILL_GRID, 0)
+        B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
+
+
+def test_prefill_k_cut_chosen_by_shape(B, oracle):
+    """A long K with few tiles: the plan itself cuts K (nothing forced but the kernel family)."""
+    B.set_tuning(B.TUNE_DECODE_MAX_M, 32)
+    try:
+        M, K, N = 130, 8192, 520
+        assert B.workspace_bytes(B.KIND_W4A16, M, K, N) > 0          # partial tiles: K is being shared out
+        check_w4(B, oracle, M, K, N, seed=21)
+        check_fp16(B, oracle, M, K, N, seed=22)
+    finally:
+        B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
 
 
 @pytest.mark.parametrize("max_m", [32, 1024, 0], ids=["mfma", "stream", "auto"])

@@ -110,7 +110,7 @@ def test_decode_w8_every_split(B, oracle, split):
         B.set_tuning(B.TUNE_DECODE_SPLIT, 0)
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
 def test_prefill_w8_every_tile(B, oracle, tile):
     B.set_tuning(B.TUNE_PREFILL_TILE, tile)
     try:
