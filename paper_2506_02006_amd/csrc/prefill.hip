@@ -464,7 +464,10 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     constexpr int PART_VEC = FM * FN * 4;              // f32x4 vectors per lane of one partial
     constexpr uint32_t kPartBytes = (uint32_t)BM * BN * 4u;
     const __amdgpu_buffer_rsrc_t rp = make_rsrc(p.partial, (uint32_t)(2 * G) * kPartBytes);
-    const uint32_t lane_off = ((uint32_t)wave * 64u + lane) * (PART_VEC * 16u);
+    // a partial tile is stored vector by vector: [vector of the accumulator layout][thread], so that one
+    // store or load instruction of a wave covers 1 KB of consecutive bytes
+    const uint32_t lane_off = ((uint32_t)wave * 64u + lane) * 16u;
+    constexpr uint32_t kVecStride = (uint32_t)NT * 16u;
 
     long long u = share_begin(g);
     const long long u_end = share_begin(g + 1);
@@ -496,7 +499,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
                     const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                    buf_store_through(rp, my_slot * kPartBytes + lane_off + (uint32_t)((i * FN + j) * 4 + q) * 16u, v);
+                    buf_store_through(rp, my_slot * kPartBytes + lane_off + (uint32_t)((i * FN + j) * 4 + q) * kVecStride, v);
                 }
         wait_stores();
         __syncthreads();
@@ -520,7 +523,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                 for (int j = 0; j < FN; j++)
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
-                        const f32x4 v = buf_load_through(rp, slot * kPartBytes + lane_off + (uint32_t)((i * FN + j) * 4 + q) * 16u);
+                        const f32x4 v = buf_load_through(rp, slot * kPartBytes + lane_off + (uint32_t)((i * FN + j) * 4 + q) * kVecStride);
 #pragma unroll
                         for (int e = 0; e < 4; e++) acc[i][j][4 * q + e] += v[e];
                     }
@@ -580,10 +583,11 @@ int prefill_compute_units()
 // Where the tiles do not fill half the compute units, K may be cut into s equal parts per tile
 // (workgroups = tiles x s, every part of every tile a workgroup of its own, so that workgroups on
 // the same k range still walk in step and share operands through the L2s); the parts meet through
-// fp32 partial tiles in memory, which costs about 15 + 11.5 s us with 256x128 tiles (128 KB per
-// part) and 11 s us with 128x128 tiles; with 256-wide tiles it never paid (256 KB per part).
-// Measured at M = 256 / 512 on the 13B shapes: o-proj 80 -> 57 us at M = 256, down-proj 134 -> 101 us
-// (M = 256) and 148 -> 137 us (M = 512).
+// fp32 partial tiles in memory (stored vector by vector, so that every store and load instruction
+// of a wave covers 1 KB of consecutive bytes), which costs about 7 + 3.5 s us with 256x128 tiles
+// (128 KB per part) and 4 + 3 s us with 128x128 tiles; with 256x256 tiles (about 45 + 7 s us) it
+// never paid.  Measured on the 13B shapes (W4): o-proj 80 -> 38 us at M = 256 and 76 -> 48 us at
+// M = 512, down-proj 134 -> 69 us (M = 256) and 148 -> 100 us (M = 512).
 PrefillPlan plan_prefill(int M, int K, int N)
 {
     PrefillPlan pl;
@@ -596,11 +600,11 @@ PrefillPlan plan_prefill(int M, int K, int N)
     if (cfg == 0) {
         struct Cand { int cfg, bm, bn; double t0, t1, h0, h1; };   // step time t0 + t1 occ; hand-over h0 + h1 s (h1 = 0: never split)
         const Cand cands[4] = {{1, 256, 256, 1.2, 0.6, 0.0, 0.0}, {5, 256, 192, 1.15, 0.3, 0.0, 0.0},
-                               {6, 256, 128, 1.0, 0.17, 15.0, 11.5}, {2, 128, 128, 0.95, 0.0, 0.0, 11.0}};
+                               {6, 256, 128, 1.0, 0.17, 7.0, 3.5}, {2, 128, 128, 0.95, 0.0, 4.0, 3.0}};
         for (const Cand& c : cands) {
             const long long t = (long long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
             const int smax = (c.h1 > 0.0 && force != 1 && 2 * t <= cus) ? (int)(cus / t) : 1;
-            for (int sp = 1; sp <= smax && sp <= 4 && sp <= kt; sp++) {
+            for (int sp = 1; sp <= smax && sp <= 8 && 4 * sp <= kt; sp++) {
                 const long long wgs = t * sp;
                 const double occ = wgs < cus ? (double)wgs / cus : 1.0;
                 const double est = (double)((wgs + cus - 1) / cus) * ((kt + sp - 1) / sp) * (c.t0 + c.t1 * occ)
