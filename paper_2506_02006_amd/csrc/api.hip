@@ -110,6 +110,8 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         g.x = x; g.w = w; g.scales = scales; g.qzeros = qzeros; g.y = y; g.M = M; g.K = K; g.N = N;
         g.config = pp.config; g.grid = pp.grid; g.split_tail = pp.split_tail;
         g.partial = nullptr; g.counters = nullptr; g.bf = bf;
+        g.parts = pp.parts;
+        g.polls = tuning_get(TUNE_DECODE_SCATTER) == 3 ? 0 : 4096;   // key 9 = 3: nobody waits (exercises the path taken after a wait that ran out)
         if (pp.counter_bytes > ((size_t)1 << 20)) return MORPH_ERR_UNSUPPORTED;   // more tiles than counters are zeroed for
         if (pp.partial_bytes) {
             if (!workspace || workspace_bytes < pp.counter_bytes + pp.partial_bytes) return MORPH_ERR_WORKSPACE;

@@ -66,9 +66,12 @@ struct GemmArgs {
     int         split_tail; // share the last partial round out along K (PrefillPlan::split_tail)
     int         map;        // schedule index -> tile: 1 = column-major over (row tile, column tile), 2 = blocks of 8 column tiles dealt out to 8 XCDs (set by launch_prefill)
     int         bf;         // x, dense weights and y are bfloat16 instead of fp16
+    int         parts;      // > 1: K is cut into this many equal parts per tile, workgroups = tiles x parts (PrefillPlan::parts)
+    int         polls;      // bound of a workgroup's wait for the other parts of its tile
 };
 struct PrefillPlan {
     int    config, bm, bn, tiles, grid, split_tail;
+    int    parts;          // > 1: equal parts of K per tile (then grid = tiles x parts)
     size_t counter_bytes;  // head of the workspace
     size_t partial_bytes;  // 0 when every share is made of whole tiles
     double est_us;         // estimated time when the configuration was chosen by shape (0 when forced)

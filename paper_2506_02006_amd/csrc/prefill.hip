@@ -404,7 +404,12 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     static_assert((size_t)WM * EP * (WVM * WVN / 2) <= (size_t)(BM + BN) * LDK, "epilogue fits in the staging LDS");
     constexpr int HALF_WAVES = WVM * WVN / 2;
     half_t* y = (half_t*)p.y;
-    auto write_tile = [&]() {                            // the range's last barrier freed the staging buffers
+    // A "unit" of a wave's part of the tile is one f32x4 of the accumulator layout taken over the wave:
+    // unit (i * FN + j) * 4 + q = rows 8q .. 8q+7 of the 32 x 32 block (i, j), i.e. 8 rows x 32 columns.
+    // write_units stores the units named in `mask` (the whole tile: all ones).
+    constexpr int UNITS = FM * FN * 4;
+    static_assert(UNITS <= 64, "unit mask is one 64-bit word");
+    auto write_units = [&](uint64_t mask) {              // the range's last barrier freed the staging buffers
         half_t* et = (wave < HALF_WAVES ? lds0 : lds1) + (size_t)(wave % HALF_WAVES) * WM * EP;
 #pragma unroll
         for (int i = 0; i < FM; i++)
@@ -413,7 +418,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int row = 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    reinterpret_cast<uint16_t*>(et)[row * EP + 32 * j + (lane & 31)] = narrow16<BF>(acc[i][j][r]);
+                    if ((mask >> ((i * FN + j) * 4 + (r >> 2))) & 1ull)
+                        reinterpret_cast<uint16_t*>(et)[row * EP + 32 * j + (lane & 31)] = narrow16<BF>(acc[i][j][r]);
                 }
         // (a wave reads back only what it wrote itself; LDS operations of one wave complete in order)
         constexpr int VPR = WN / 8;                    // 16-byte pieces per tile row
@@ -421,10 +427,12 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         for (int v = lane; v < WM * VPR; v += 64) {
             const int row = v / VPR, cv = v - row * VPR;
             const int grow = m0 + wm0 + row, gcol = n0 + wn0 + 8 * cv;
-            if (grow < M && gcol < N)
+            const int unit = ((row >> 5) * FN + (cv >> 2)) * 4 + ((row & 31) >> 3);
+            if (grow < M && gcol < N && ((mask >> unit) & 1ull))
                 *reinterpret_cast<u32x4*>(y + (size_t)grow * N + gcol) = *reinterpret_cast<const u32x4*>(et + row * EP + 8 * cv);
         }
     };
+    auto write_tile = [&]() { write_units(~0ull); };
 
     // ---- work distribution.  The grid is one workgroup per compute unit (or fewer).  Full rounds:
     // workgroup g takes tile r * G + g whole, all workgroups walking K in step, so that neighbours
@@ -459,15 +467,102 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         }
         return;
     }
-    const long long units = (long long)tail_tiles * KT;
-    auto share_begin = [&](int gg) { return (long long)gg * units / G; };
     constexpr int PART_VEC = FM * FN * 4;              // f32x4 vectors per lane of one partial
     constexpr uint32_t kPartBytes = (uint32_t)BM * BN * 4u;
-    const __amdgpu_buffer_rsrc_t rp = make_rsrc(p.partial, (uint32_t)(2 * G) * kPartBytes);
     // a partial tile is stored vector by vector: [vector of the accumulator layout][thread], so that one
     // store or load instruction of a wave covers 1 KB of consecutive bytes
     const uint32_t lane_off = ((uint32_t)wave * 64u + lane) * 16u;
     constexpr uint32_t kVecStride = (uint32_t)NT * 16u;
+
+    // (compiled into the 8-wave 256 x 128 and the 128 x 128 configurations only, the ones the plan uses it with:
+    // in the larger ones the extra code made the compiler spill accumulators)
+    constexpr bool kEqualParts = (BM * BN <= 256 * 128) && (WVM * WVN == 8 || BM == 128);
+    if constexpr (kEqualParts) if (p.parts > 1) {
+        // ---- K cut into `parts` equal parts per tile: workgroup g = tile * parts + part.  Each stores
+        // its partial tile, counts its arrival at the tile's counter and waits (a bounded number of
+        // polls) until all parts are there; then every workgroup adds up, over the parts in index
+        // order, the units of the tile whose number is congruent to its own part, and writes them:
+        // the sum over the parts is shared out instead of being left to the last arriver.
+        // Correctness never depends on the wait: every workgroup ends by adding a "done" bit to a second
+        // counter, and the last one out adds up whatever units are still missing (their owner gave up
+        // waiting) and puts both counters back to zero; by then nobody polls any more.
+        const int parts = p.parts;
+        const int tile = g / parts, part = g - tile * parts;
+        if (tile >= tiles) return;
+        const int k0 = (int)(((long long)part * KT) / parts), k1 = (int)(((long long)(part + 1) * KT) / parts);
+        __syncthreads();
+        set_tile_tail(tile, 0);
+        if (w_role) run_range(k0, k1, store_w, load_w, kLate);
+        else        run_range(k0, k1, store_x, load_x, kEarly);
+        const __amdgpu_buffer_rsrc_t rt_ = make_rsrc(p.partial + (size_t)tile * parts * (kPartBytes / 4), (uint32_t)parts * kPartBytes);
+#pragma unroll
+        for (int i = 0; i < FM; i++)
+#pragma unroll
+            for (int j = 0; j < FN; j++)
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    buf_store_through(rt_, (uint32_t)part * kPartBytes + lane_off + (uint32_t)((i * FN + j) * 4 + q) * kVecStride, v);
+                }
+        wait_stores();
+        __syncthreads();
+        int* flag   = reinterpret_cast<int*>(lds0);
+        int* arrive = p.counters + tile * 64;             // a 256-byte stretch per tile: arrivals, and 128 bytes on, departures
+        int* depart = arrive + 32;
+        if (tid == 0) {
+            const int c = __hip_atomic_fetch_add(arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int complete = c == parts - 1;
+            for (int i = 0; !complete && i < p.polls; i++) {
+                complete = __hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) >= parts;
+                __builtin_amdgcn_s_sleep(4);
+            }
+            *flag = complete;
+        }
+        __syncthreads();
+        const int complete = *flag;
+        __syncthreads();                                 // the flag word is written again below, and the LDS is about to hold output
+        // units u with u % parts == j: summed over the parts in index order (eight loads in flight; parts
+        // beyond the last read past the tile's stretch of the buffer and come back as zeros), then written
+        auto reduce_units = [&](int j) {
+            uint64_t mask = 0;
+#pragma unroll
+            for (int u = 0; u < UNITS; u++) {
+                if (u % parts != j) continue;
+                mask |= 1ull << u;
+                f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int p0 = 0; p0 < parts; p0 += 8) {
+                    f32x4 v[8];
+#pragma unroll
+                    for (int q = 0; q < 8; q++)
+                        v[q] = bit_cast<f32x4>(__builtin_amdgcn_raw_buffer_load_b128(rt_, lane_off + (uint32_t)u * kVecStride, (uint32_t)(p0 + q) * kPartBytes, kAuxSystemScope));
+#pragma unroll
+                    for (int q = 0; q < 8; q++) sum += v[q];
+                }
+                const int b = u >> 2, q = u & 3;
+#pragma unroll
+                for (int e = 0; e < 4; e++) acc[b / FN][b % FN][4 * q + e] = sum[e];
+            }
+            write_units(mask);                           // (every wave stages and reads back its own region only)
+        };
+        if (complete) reduce_units(part);
+        if (tid == 0) {
+            const int old = __hip_atomic_fetch_add(depart, 1 | (complete << (8 + part)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *flag = (old & 0xFF) == parts - 1 ? (0x1000000 | (((old >> 8) | (complete << part)) & 0xFFFF)) : 0;
+        }
+        __syncthreads();
+        const int last = *flag;
+        __syncthreads();
+        if (last) {
+            for (int j = 0; j < parts; j++)
+                if (!((last >> j) & 1)) reduce_units(j);  // units whose owner gave up waiting: normally none
+            if (tid == 0) { atomicExch(arrive, 0); atomicExch(depart, 0); }
+        }
+        return;
+    }
+
+    const long long units = (long long)tail_tiles * KT;
+    auto share_begin = [&](int gg) { return (long long)gg * units / G; };
+    const __amdgpu_buffer_rsrc_t rp = make_rsrc(p.partial, (uint32_t)(2 * G) * kPartBytes);
 
     long long u = share_begin(g);
     const long long u_end = share_begin(g + 1);
@@ -585,9 +680,13 @@ int prefill_compute_units()
 // the same k range still walk in step and share operands through the L2s); the parts meet through
 // fp32 partial tiles in memory (stored vector by vector, so that every store and load instruction
 // of a wave covers 1 KB of consecutive bytes), which costs about 7 + 3.5 s us with 256x128 tiles
-// (128 KB per part) and 4 + 3 s us with 128x128 tiles; with 256x256 tiles (about 45 + 7 s us) it
+// (128 KB per part) and 4 + 3 s us with 128x128 tiles when the last arriver adds the parts up, and
+// about 10 + 1.3 s us when every workgroup adds up its share of the tile (used from four parts on: with
+// two or three the waiting costs more than it saves); with 256x256 tiles (about 45 + 7 s us) it
 // never paid.  Measured on the 13B shapes (W4): o-proj 80 -> 38 us at M = 256 and 76 -> 48 us at
 // M = 512, down-proj 134 -> 69 us (M = 256) and 148 -> 100 us (M = 512).
+constexpr int kSharedFrom = 4;   // parts of K per tile from which the sum over the parts is shared out (below, the last arriver adds them: measured faster)
+
 PrefillPlan plan_prefill(int M, int K, int N)
 {
     PrefillPlan pl;
@@ -607,8 +706,9 @@ PrefillPlan plan_prefill(int M, int K, int N)
             for (int sp = 1; sp <= smax && sp <= 8 && 4 * sp <= kt; sp++) {
                 const long long wgs = t * sp;
                 const double occ = wgs < cus ? (double)wgs / cus : 1.0;
-                const double est = (double)((wgs + cus - 1) / cus) * ((kt + sp - 1) / sp) * (c.t0 + c.t1 * occ)
-                                 + (sp > 1 ? c.h0 + c.h1 * sp : 0.0);
+                // from four parts on the sum over the parts is shared out among the workgroups of a tile
+                const double hand = sp == 1 ? 0.0 : sp >= kSharedFrom ? c.h0 + 3.0 + 1.3 * sp : c.h0 + c.h1 * sp;
+                const double est = (double)((wgs + cus - 1) / cus) * ((kt + sp - 1) / sp) * (c.t0 + c.t1 * occ) + hand;
                 if (cfg == 0 || est < best) { cfg = c.cfg; parts = sp; best = est; }
             }
         }
@@ -636,9 +736,13 @@ PrefillPlan plan_prefill(int M, int K, int N)
     const bool rect = map == 1 ? tail_first % tiles_m == 0
                                : (tail_first <= full ? tail_first % blk == 0 : (tail_first - full) % tiles_m == 0);
     pl.split_tail = tail != 0 && rect && force != 1 && (force == 2 || parts > 1 || (forced_grid > 0 && pl.grid > pl.tiles));
-    // every share may end and begin inside a tile: two partial slots per workgroup, plus the counters
-    pl.counter_bytes = ((size_t)pl.grid * sizeof(int) + 255) & ~(size_t)255;
-    pl.partial_bytes = pl.split_tail ? (size_t)2 * pl.grid * pl.bm * pl.bn * sizeof(float) : 0;
+    // workgroups = tiles x parts: the equal-parts scheme (one partial slot per workgroup, two counters a
+    // tile, 256 bytes apart from the next tile's); otherwise every share may end and begin inside a
+    // tile: two partial slots per workgroup, one counter a tile
+    pl.parts = ((cfg == 6 || cfg == 2) && pl.split_tail && pl.tiles < pl.grid && pl.grid % pl.tiles == 0 && pl.grid / pl.tiles >= kSharedFrom && pl.grid / pl.tiles <= 16) ? pl.grid / pl.tiles : 1;
+    const size_t counters = pl.parts > 1 ? (size_t)pl.tiles * 256 : (size_t)pl.grid * sizeof(int);
+    pl.counter_bytes = (counters + 255) & ~(size_t)255;
+    pl.partial_bytes = !pl.split_tail ? 0 : (size_t)(pl.parts > 1 ? 1 : 2) * pl.grid * pl.bm * pl.bn * sizeof(float);
     return pl;
 }
 

@@ -167,12 +167,17 @@ def test_prefill_every_tile_and_order(B, oracle, tile, order):
         B.set_tuning(B.TUNE_PREFILL_MAP, 0)
 
 
-@pytest.mark.parametrize("tile,parts", [(6, 2), (6, 3), (6, 4), (2, 2), (2, 3), (1, 2)])
-def test_prefill_k_cut_into_equal_parts(B, oracle, tile, parts):
+@pytest.mark.parametrize("wait", [0, 3], ids=["wait", "nobody-waits"])
+@pytest.mark.parametrize("tile,parts", [(6, 2), (6, 3), (6, 4), (6, 7), (2, 2), (2, 3), (2, 5), (1, 2)])
+def test_prefill_k_cut_into_equal_parts(B, oracle, tile, parts, wait):
     """Few tiles: K is cut into `parts` equal parts per tile, workgroups = tiles x parts, the parts meet
-    through fp32 partial tiles and the last one to arrive adds them in a fixed order.  Forced here
-    (tile, workgroup count, sharing on) with a k-tile count that the parts do and do not divide."""
+    through fp32 partial tiles; with the 256 x 128 and 128 x 128 tiles every workgroup then adds up its
+    share of the tile's units over the parts in a fixed order (wait = 3: no workgroup waits for the
+    others, so the last one out has every unit left to do: the path taken after a wait that ran out);
+    with the 256 x 256 tile the last one to arrive adds them.  Forced here (tile, workgroup count,
+    sharing on) with k-tile counts that the parts do and do not divide."""
     bm, bn = {1: (256, 256), 2: (128, 128), 6: (256, 128)}[tile]
+    B.set_tuning(B.TUNE_DECODE_SCATTER, wait)
     B.set_tuning(B.TUNE_PREFILL_TILE, tile)
     B.set_tuning(B.TUNE_PREFILL_SPLIT, 2)
     B.set_tuning(B.TUNE_DECODE_MAX_M, 32)
@@ -187,6 +192,7 @@ def test_prefill_k_cut_into_equal_parts(B, oracle, tile, parts):
         B.set_tuning(B.TUNE_PREFILL_SPLIT, 0)
         B.set_tuning(B.TUNE_PREFILL_GRID, 0)
         B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
+        B.set_tuning(B.TUNE_DECODE_SCATTER, 0)
 
 
 def test_prefill_k_cut_chosen_by_shape(B, oracle):
