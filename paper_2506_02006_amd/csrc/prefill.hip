@@ -683,7 +683,7 @@ int prefill_compute_units()
 // (128 KB per part) and 4 + 3 s us with 128x128 tiles when the last arriver adds the parts up, and
 // about 10 + 1.3 s us when every workgroup adds up its share of the tile (used from four parts on: with
 // two or three the waiting costs more than it saves); with 256x256 tiles (about 45 + 7 s us) it
-// never paid.  Measured on the 13B shapes (W4): o-proj 80 -> 38 us at M = 256 and 76 -> 48 us at
+// never paid; with 256x192 tiles two parts cost about 18 us, three 34.  Measured on the 13B shapes (W4): o-proj 80 -> 38 us at M = 256 and 76 -> 48 us at
 // M = 512, down-proj 134 -> 69 us (M = 256) and 148 -> 100 us (M = 512).
 constexpr int kSharedFrom = 4;   // parts of K per tile from which the sum over the parts is shared out (below, the last arriver adds them: measured faster)
 
@@ -697,9 +697,9 @@ PrefillPlan plan_prefill(int M, int K, int N)
     int parts = 1;                                       // equal parts of K per tile (by shape only)
     double best = 0.0;
     if (cfg == 0) {
-        struct Cand { int cfg, bm, bn; double t0, t1, h0, h1; };   // step time t0 + t1 occ; hand-over h0 + h1 s (h1 = 0: never split)
-        const Cand cands[4] = {{1, 256, 256, 1.2, 0.6, 0.0, 0.0}, {5, 256, 192, 1.15, 0.3, 0.0, 0.0},
-                               {6, 256, 128, 1.0, 0.17, 7.0, 3.5}, {2, 128, 128, 0.95, 0.0, 4.0, 3.0}};
+        struct Cand { int cfg, bm, bn; double t0, t1, h0, h1; bool shared; };   // step time t0 + t1 occ; hand-over h0 + h1 s (h1 = 0: never split)
+        const Cand cands[4] = {{1, 256, 256, 1.2, 0.6, 0.0, 0.0, false}, {5, 256, 192, 1.15, 0.3, -14.0, 16.0, false},
+                               {6, 256, 128, 1.0, 0.17, 7.0, 3.5, true}, {2, 128, 128, 0.95, 0.0, 4.0, 3.0, true}};
         for (const Cand& c : cands) {
             const long long t = (long long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
             const int smax = (c.h1 > 0.0 && force != 1 && 2 * t <= cus) ? (int)(cus / t) : 1;
@@ -707,7 +707,7 @@ PrefillPlan plan_prefill(int M, int K, int N)
                 const long long wgs = t * sp;
                 const double occ = wgs < cus ? (double)wgs / cus : 1.0;
                 // from four parts on the sum over the parts is shared out among the workgroups of a tile
-                const double hand = sp == 1 ? 0.0 : sp >= kSharedFrom ? c.h0 + 3.0 + 1.3 * sp : c.h0 + c.h1 * sp;
+                const double hand = sp == 1 ? 0.0 : (c.shared && sp >= kSharedFrom) ? c.h0 + 3.0 + 1.3 * sp : c.h0 + c.h1 * sp;
                 const double est = (double)((wgs + cus - 1) / cus) * ((kt + sp - 1) / sp) * (c.t0 + c.t1 * occ) + hand;
                 if (cfg == 0 || est < best) { cfg = c.cfg; parts = sp; best = est; }
             }
