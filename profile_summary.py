@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--write")
     ap.add_argument("--command", default="")
     ap.add_argument("--note", default="")
+    ap.add_argument("--min-launches", type=int, default=3, help="leave out (kernel, grid) rows with fewer launches (warm-up on dummies)")
     ap.add_argument("--mean-of", default="", help="kernel name prefix: print its launch-weighted mean traffic and duration")
     ap.add_argument("--counters", help="results db of a further --pmc run")
     ap.add_argument("--like", default="prefill_kernel", help="kernel name substring for --counters")
@@ -62,6 +63,8 @@ def main():
         print("\nkernel durations (rocprofv3 --kernel-trace), microseconds")
         print(f"{'kernel':58s} {'grid(threads)':>14s} {'n':>6s} {'mean':>9s} {'min':>9s} {'max':>9s}")
         for name, gx, gy, n, avg, mn, mx in trace_rows(a.trace):
+            if n < a.min_launches:
+                continue
             print(f"{short(name)[:58]:58s} {str(gx) + 'x' + str(gy):>14s} {n:6d} {avg:9.2f} {mn:9.2f} {mx:9.2f}")
     if a.fetch and a.write:
         f, w = pmc_rows(a.fetch, "FETCH_SIZE"), pmc_rows(a.write, "WRITE_SIZE")
@@ -77,7 +80,7 @@ def main():
               f"WRITE_SIZE read {w[kc][1]:.1f}  ->  scale factors {f_scale:.4f} (fetch), {w_scale:.4f} (write)")
         print(f"{'kernel':58s} {'grid(threads)':>14s} {'n':>6s} {'fetch MB':>10s} {'write MB':>10s} {'total MB':>10s}")
         for k in sorted(f):
-            if k not in w:
+            if k not in w or f[k][0] < a.min_launches:
                 continue
             fm = f[k][1] * f_scale * 1024 / 1e6
             wm = w[k][1] * w_scale * 1024 / 1e6
@@ -102,6 +105,8 @@ def main():
         for k in keys:
             vals = {r[3]: (r[4], r[5]) for r in rows if (short(r[0]), r[1], r[2]) == k}
             n = max(v[0] for v in vals.values())
+            if n < a.min_launches:
+                continue
             print(f"{k[0][:70]}  grid {k[1]}x{k[2]}  launches {n}")
             for cn in names:
                 if cn in vals:
