@@ -467,7 +467,6 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         }
         return;
     }
-    constexpr int PART_VEC = FM * FN * 4;              // f32x4 vectors per lane of one partial
     constexpr uint32_t kPartBytes = (uint32_t)BM * BN * 4u;
     // a partial tile is stored vector by vector: [vector of the accumulator layout][thread], so that one
     // store or load instruction of a wave covers 1 KB of consecutive bytes
@@ -642,6 +641,10 @@ hipError_t launch_tile(const GemmArgs& a, hipStream_t st)
 
 }  // namespace
 
+// The file may be compiled as two objects to halve the build time (the build script does):
+// MORPH_PREFILL_PART = 0: the fp16 kernels, the plan and the entry; = 1: the bfloat16 kernels only.
+// Without the macro everything lands in one object.
+#if !defined(MORPH_PREFILL_PART) || MORPH_PREFILL_PART == 0
 #ifdef MORPH_TIMING
 extern "C" int morph_debug_read_prefill_ticks(unsigned long long* host_out, int n)
 {
@@ -746,6 +749,8 @@ PrefillPlan plan_prefill(int M, int K, int N)
     return pl;
 }
 
+#endif
+
 template <int Q, bool BF>
 static hipError_t launch_config(const GemmArgs& a, hipStream_t st)
 {
@@ -759,6 +764,16 @@ static hipError_t launch_config(const GemmArgs& a, hipStream_t st)
     }
 }
 
+#if !defined(MORPH_PREFILL_PART) || MORPH_PREFILL_PART == 1
+hipError_t launch_prefill_bf16(int q, const GemmArgs& a, hipStream_t st)
+{
+    return q == 1 ? launch_config<1, true>(a, st) : q == 2 ? launch_config<2, true>(a, st) : launch_config<0, true>(a, st);
+}
+#else
+hipError_t launch_prefill_bf16(int q, const GemmArgs& a, hipStream_t st);   // in the other object
+#endif
+
+#if !defined(MORPH_PREFILL_PART) || MORPH_PREFILL_PART == 0
 // q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes
 hipError_t launch_prefill(int q, const GemmArgs& a0, hipStream_t st)
 {
@@ -766,8 +781,9 @@ hipError_t launch_prefill(int q, const GemmArgs& a0, hipStream_t st)
     const int force = tuning_get(TUNE_PREFILL_MAP);      // 0 = default (2), 1 / 2 = that map
     a.map = force == 1 ? 1 : 2;
     if (a.grid % 8 != 0) a.map = 1;
-    if (a.bf) return q == 1 ? launch_config<1, true>(a, st) : q == 2 ? launch_config<2, true>(a, st) : launch_config<0, true>(a, st);
+    if (a.bf) return launch_prefill_bf16(q, a, st);
     return q == 1 ? launch_config<1, false>(a, st) : q == 2 ? launch_config<2, false>(a, st) : launch_config<0, false>(a, st);
 }
+#endif
 
 }  // namespace morph
