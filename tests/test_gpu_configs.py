@@ -156,6 +156,40 @@ def test_config4_llama13b_prefill(B, oracle, linear):
         assert np.abs(y4.astype(np.float32) - y16.astype(np.float32)).max() <= 0.2 * scale
 
 
+@pytest.mark.parametrize("linear", ["o", "down"])
+def test_llama13b_few_tiles_k_cut_into_parts(B, oracle, linear):
+    """The 13B shapes with few output tiles at M = 128, 256 and 1024 through the LDS-tiled kernels: the
+    plan cuts K into equal parts per tile there (up to eight at these sizes; the sum over the parts
+    shared out among the workgroups from four parts on).  Sampled outputs against the oracle."""
+    K, N = synth.LAYER_SHAPES["llama13b"][linear]
+    W = synth.layer_weights(4, "llama13b", linear)
+    rec = oracle.quantize_w4(W)
+    rec_dev = tuple(dev(a) for a in rec)
+    w16 = W.astype(np.float16)
+    w16_dev = dev(w16)
+    del W
+    rng = np.random.default_rng([synth.BASE_SEED, 44, synth._TENSOR_ID[linear]])
+    B.set_tuning(B.TUNE_DECODE_MAX_M, 32)
+    try:
+        for M in (128, 256, 1024):
+            x = synth.activations(4, M, K, tensor_id=M)
+            xd = dev(x)
+            rows, cols = sample_positions(rng, M, N)
+            need = max(B.workspace_bytes(B.KIND_W4A16, M, K, N), B.workspace_bytes(B.KIND_FP16, M, K, N))
+            assert need > 0                                   # partial tiles: K is being cut
+            ws = B.new_workspace(need)
+            for rep in range(2):                              # twice on one workspace: counters must come back to zero
+                y4 = host(B.linear_w4a16(xd, *rec_dev, ws))
+                y16 = host(B.linear_fp16(xd, w16_dev, ws))
+                e4 = oracle.error_metric(y4[rows, cols], oracle.linear_w4a16_at(x, *rec, rows, cols))
+                e16 = oracle.error_metric(y16[rows, cols], oracle.linear_fp16_at(x, w16, rows, cols))
+                say(f"  13B {linear} M={M} run {rep}: {rows.size} sampled outputs, w4a16 err={e4['err']:.3e} fp16 err={e16['err']:.3e}")
+                assert np.isfinite(y4).all() and np.isfinite(y16).all()
+                assert e4["err"] <= TOL and e16["err"] <= TOL
+    finally:
+        B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
+
+
 def oracle_linear(oracle, rec, x):
     return oracle.linear_fp16(x, rec[1]) if rec[0] == "fp16" else oracle.linear_w4a16(x, rec[1], rec[2], rec[3])
 
