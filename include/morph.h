@@ -155,6 +155,8 @@ int morph_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  * H % 8 == 0, H <= 65536.  b is ignored except for RESIDUAL.  out may not alias a or b. */
 enum { MORPH_GLUE_QKV = 0, MORPH_GLUE_RESIDUAL = 1, MORPH_GLUE_SWIGLU = 2, MORPH_GLUE_RMS = 3 };
 int morph_glue(int op, const void* a, const void* b, void* out, int M, int H, void* stream);
+/* The same with a, b and out in bfloat16 (fp32 arithmetic as above, one rounding to bfloat16). */
+int morph_glue_bf16(int op, const void* a, const void* b, void* out, int M, int H, void* stream);
 
 /* ---- one decode step through a stack of layers of mixed kinds (Sections 3 and 4.1: quantized
  * and full-precision layers coexist; Section 4.3: kernels of every precision are ready) ----
@@ -184,6 +186,14 @@ int morph_stack_forward(const morph_layer_desc* layers /* host */, int n_layers,
                         int M, int hidden, int inter, void* scratch, size_t scratch_bytes,
                         void* workspace, size_t workspace_bytes, int tap_layer, void* tap,
                         void* stream);
+
+/* The same step with bfloat16 activations: x_io, the scratch intermediates and the tap are bfloat16, the
+ * linears are the *_bf16 ones (a descriptor of kind MORPH_KIND_FP16 then names a bfloat16 matrix) and
+ * the elementwise steps morph_glue_bf16.  Sizes, layouts and errors as for morph_stack_forward. */
+int morph_stack_forward_bf16(const morph_layer_desc* layers /* host */, int n_layers, void* x_io,
+                             int M, int hidden, int inter, void* scratch, size_t scratch_bytes,
+                             void* workspace, size_t workspace_bytes, int tap_layer, void* tap,
+                             void* stream);
 
 /* ---- the same decode step in one persistent launch per 16 layers (M <= 32) ----
  * Same chain and same layer records as morph_stack_forward, without scratch and tap: everything the

@@ -32,6 +32,7 @@ EXPORTS = [
     "morph_layer_record_bytes", "morph_layer_record_desc", "morph_layer_swap_async",
     "morph_quantize_layer_w8", "morph_dequantize_w8", "morph_linear_w8a16", "morph_cosine_rows",
     "morph_linear_bf16", "morph_linear_w4a16_bf16", "morph_linear_w8a16_bf16", "morph_cosine_rows_bf16",
+    "morph_glue_bf16", "morph_stack_forward_bf16",
 ]
 
 
@@ -78,11 +79,13 @@ def lib() -> ctypes.CDLL:
     L.morph_workspace_bytes.restype = sz
     L.morph_workspace_init.argtypes = [vp, sz, vp]
     L.morph_glue.argtypes = [i, vp, vp, vp, i, i, vp]
+    L.morph_glue_bf16.argtypes = [i, vp, vp, vp, i, i, vp]
     L.morph_stack_scratch_bytes.argtypes = [i, i, i]
     L.morph_stack_scratch_bytes.restype = sz
     L.morph_stack_tap_bytes.argtypes = [i, i, i]
     L.morph_stack_tap_bytes.restype = sz
     L.morph_stack_forward.argtypes = [ctypes.POINTER(LayerDesc), i, vp, i, i, i, vp, sz, vp, sz, i, vp, vp]
+    L.morph_stack_forward_bf16.argtypes = L.morph_stack_forward.argtypes
     L.morph_stack_fused_workspace_bytes.argtypes = [i, i, i]
     L.morph_stack_fused_workspace_bytes.restype = sz
     L.morph_stack_forward_fused.argtypes = [ctypes.POINTER(LayerDesc), i, vp, i, i, i, vp, sz, vp]
@@ -271,12 +274,17 @@ def dequantize_w4(qweight, scales, qzeros, dtype=torch.float32, group_size: int 
 
 
 def glue(op: int, a: torch.Tensor, b=None, H=None) -> torch.Tensor:
+    """Elementwise + row-norm step on fp16 or bfloat16 rows (the dtype of a decides)."""
     M = a.shape[0]
     if H is None:
         H = a.shape[1] // (3 if op == GLUE_QKV else 2 if op == GLUE_SWIGLU else 1)
-    out = torch.empty((M, H), dtype=torch.float16, device=a.device)
-    bp = _dev(b, torch.float16, "b") if b is not None else None
-    _check(lib().morph_glue(op, _dev(a, torch.float16, "a"), bp, out.data_ptr(), M, H, _stream()), "morph_glue")
+    dt = a.dtype
+    if dt not in (torch.float16, torch.bfloat16):
+        raise TypeError("a must be float16 or bfloat16")
+    out = torch.empty((M, H), dtype=dt, device=a.device)
+    bp = _dev(b, dt, "b") if b is not None else None
+    fn = lib().morph_glue_bf16 if dt == torch.bfloat16 else lib().morph_glue
+    _check(fn(op, _dev(a, dt, "a"), bp, out.data_ptr(), M, H, _stream()), "morph_glue")
     return out
 
 
@@ -342,7 +350,8 @@ class LayerStack:
     """Host-side record of a stack of layers of mixed kinds plus the buffers one decode step needs.
     Holds references to the weight tensors so they outlive the raw pointers."""
 
-    def __init__(self, hidden: int, inter: int, M: int, device="cuda"):
+    def __init__(self, hidden: int, inter: int, M: int, device="cuda", dtype=torch.float16):
+        self.dtype = dtype                 # format of the activations (and of the weights of "fp16" layers)
         self.hidden, self.inter, self.M = hidden, inter, M
         self.device = device
         self.layers = []      # list of dict name -> ("fp16", w) | ("w4", qw, sc, qz)
@@ -373,7 +382,7 @@ class LayerStack:
                 d = getattr(arr[li], name)
                 if rec[0] == "fp16":
                     assert rec[1].shape == (K, N)
-                    d.kind, d.w, d.scales, d.qzeros = KIND_FP16, _dev(rec[1], torch.float16, name), None, None
+                    d.kind, d.w, d.scales, d.qzeros = KIND_FP16, _dev(rec[1], self.dtype, name), None, None
                 elif rec[0] == "w8":
                     assert rec[1].shape == (K, N // 4)
                     d.kind = KIND_W8A16
@@ -392,18 +401,21 @@ class LayerStack:
         self._desc = arr
 
     def forward(self, x_io: torch.Tensor, tap_layer: int = -1):
-        """One decode step in place on x_io [M,hidden] fp16."""
+        """One decode step in place on x_io [M,hidden] (fp16, or bfloat16 for a stack made with that dtype)."""
         if self._desc is None:
             self._build()
         assert x_io.shape == (self.M, self.hidden)
-        _check(lib().morph_stack_forward(self._desc, len(self.layers), _dev(x_io, torch.float16, "x_io"), self.M,
-                                         self.hidden, self.inter, self.scratch.data_ptr(), self.scratch.numel(),
-                                         self.ws.data_ptr(), self.ws.numel(), tap_layer, self.tap.data_ptr(),
-                                         _stream()), "morph_stack_forward")
+        fn = lib().morph_stack_forward_bf16 if self.dtype == torch.bfloat16 else lib().morph_stack_forward
+        _check(fn(self._desc, len(self.layers), _dev(x_io, self.dtype, "x_io"), self.M,
+                  self.hidden, self.inter, self.scratch.data_ptr(), self.scratch.numel(),
+                  self.ws.data_ptr(), self.ws.numel(), tap_layer, self.tap.data_ptr(),
+                  _stream()), "morph_stack_forward")
         return x_io
 
     def forward_fused(self, x_io: torch.Tensor):
-        """The same decode step in one persistent launch per 16 layers (M <= 32), in place on x_io."""
+        """The same decode step in one persistent launch per 16 layers (M <= 32), in place on x_io (fp16 only)."""
+        if self.dtype != torch.float16:
+            raise TypeError("the persistent stack launch takes fp16 activations only")
         if self._desc is None:
             self._build()
         assert x_io.shape == (self.M, self.hidden)
@@ -427,7 +439,7 @@ class LayerStack:
         buf = self.tap
         for name, cols in sizes:
             nb = M * cols * 2
-            out[name] = buf[off:off + nb].view(torch.float16).view(M, cols)
+            out[name] = buf[off:off + nb].view(self.dtype).view(M, cols)
             off += (nb + 255) & ~255
         return out
 

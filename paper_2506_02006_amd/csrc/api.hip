@@ -272,14 +272,26 @@ int morph_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
 
-int morph_glue(int op, const void* a, const void* b, void* out, int M, int H, void* stream)
+namespace {
+int glue_any(int op, const void* a, const void* b, void* out, int M, int H, int bf, void* stream)
 {
     if (op < MORPH_GLUE_QKV || op > MORPH_GLUE_RMS) return MORPH_ERR_SHAPE;
     if (!a || !out || (op == MORPH_GLUE_RESIDUAL && !b)) return MORPH_ERR_NULL;
     if (M < 1 || H < 8 || H % 8 != 0 || H > 65536) return MORPH_ERR_SHAPE;
     if (!aligned16(a) || !aligned16(out) || (op == MORPH_GLUE_RESIDUAL && !aligned16(b))) return MORPH_ERR_ALIGN;
-    hipError_t e = launch_glue(op, a, b, out, M, H, (hipStream_t)stream);
+    hipError_t e = launch_glue(op, a, b, out, M, H, bf, (hipStream_t)stream);
     return e == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+}  // namespace
+
+int morph_glue(int op, const void* a, const void* b, void* out, int M, int H, void* stream)
+{
+    return glue_any(op, a, b, out, M, H, 0, stream);
+}
+
+int morph_glue_bf16(int op, const void* a, const void* b, void* out, int M, int H, void* stream)
+{
+    return glue_any(op, a, b, out, M, H, 1, stream);
 }
 
 // ---- layer stack ----
@@ -320,9 +332,9 @@ size_t morph_stack_tap_bytes(int M, int hidden, int inter)
     return stack_layout(M, hidden, inter).total;
 }
 
-int morph_stack_forward(const morph_layer_desc* layers, int n_layers, void* x_io, int M, int hidden,
-                        int inter, void* scratch, size_t scratch_bytes, void* workspace,
-                        size_t workspace_bytes, int tap_layer, void* tap, void* stream)
+static int stack_forward_any(const morph_layer_desc* layers, int n_layers, void* x_io, int M, int hidden,
+                             int inter, void* scratch, size_t scratch_bytes, void* workspace,
+                             size_t workspace_bytes, int tap_layer, void* tap, void* stream, int bf)
 {
     if (!layers || !x_io || !scratch) return MORPH_ERR_NULL;
     if (n_layers < 1 || M < 1 || M > kStackMaxM) return MORPH_ERR_SHAPE;
@@ -356,10 +368,10 @@ int morph_stack_forward(const morph_layer_desc* layers, int n_layers, void* x_io
          *d = sc + L.d, *xn = sc + L.xn;
     void* x = x_io;
     auto lin = [&](const morph_linear_desc& ld, const void* in, void* out, int K, int N) {
-        return run_linear(ld.kind, in, ld.w, ld.scales, ld.qzeros, out, M, K, N, workspace, workspace_bytes, st);
+        return run_linear(ld.kind, in, ld.w, ld.scales, ld.qzeros, out, M, K, N, workspace, workspace_bytes, st, bf);
     };
     auto glue = [&](int op, const void* p, const void* q, void* out, int H) {
-        return launch_glue(op, p, q, out, M, H, st) == hipSuccess ? (int)MORPH_OK : (int)MORPH_ERR_DEVICE;
+        return launch_glue(op, p, q, out, M, H, bf, st) == hipSuccess ? (int)MORPH_OK : (int)MORPH_ERR_DEVICE;
     };
     for (int l = 0; l < n_layers; l++) {
         const morph_layer_desc& ly = layers[l];
@@ -386,6 +398,22 @@ int morph_stack_forward(const morph_layer_desc* layers, int n_layers, void* x_io
         if (launch_copy(x, x_io, ((size_t)M * hidden * 2 + 15) & ~(size_t)15, st) != hipSuccess) return MORPH_ERR_DEVICE;
     }
     return MORPH_OK;
+}
+
+int morph_stack_forward(const morph_layer_desc* layers, int n_layers, void* x_io, int M, int hidden,
+                        int inter, void* scratch, size_t scratch_bytes, void* workspace,
+                        size_t workspace_bytes, int tap_layer, void* tap, void* stream)
+{
+    return stack_forward_any(layers, n_layers, x_io, M, hidden, inter, scratch, scratch_bytes, workspace, workspace_bytes,
+                             tap_layer, tap, stream, 0);
+}
+
+int morph_stack_forward_bf16(const morph_layer_desc* layers, int n_layers, void* x_io, int M, int hidden,
+                             int inter, void* scratch, size_t scratch_bytes, void* workspace,
+                             size_t workspace_bytes, int tap_layer, void* tap, void* stream)
+{
+    return stack_forward_any(layers, n_layers, x_io, M, hidden, inter, scratch, scratch_bytes, workspace, workspace_bytes,
+                             tap_layer, tap, stream, 1);
 }
 
 // ---- the same stack in one persistent launch per 16 layers ----
@@ -658,6 +686,8 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     if ((rc = morph_quantize_layer_w8(w, MORPH_DTYPE_BF16, q8, s, z, kWK, kWN, 128, stream))) return rc;
     for (int op = MORPH_GLUE_QKV; op <= MORPH_GLUE_RMS; op++)
         if ((rc = morph_glue(op, w, x, y, 2, 64, stream))) return rc;
+    for (int op = MORPH_GLUE_QKV; op <= MORPH_GLUE_RMS; op++)
+        if ((rc = morph_glue_bf16(op, w, x, y, 2, 64, stream))) return rc;
     if ((rc = morph_cosine_rows(x, w, reinterpret_cast<float*>(y), reinterpret_cast<float*>(y) + 64, 2, 128, stream))) return rc;
     if ((rc = morph_cosine_rows_bf16(x, w, reinterpret_cast<float*>(y), reinterpret_cast<float*>(y) + 64, 2, 128, stream))) return rc;
     if (launch_copy(x, y, 4096, st) != hipSuccess) return MORPH_ERR_DEVICE;

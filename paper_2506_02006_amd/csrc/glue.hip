@@ -10,49 +10,60 @@ namespace {
 
 constexpr float kRmsEps = 1e-6f;
 
-// value vector (8 consecutive columns starting at column 8v of the output row)
-template <int OP>
-__device__ __forceinline__ void glue_values(const half_t* a, const half_t* b, int H, int v, float out[8])
+// eight consecutive 16-bit values (fp16, or bfloat16 with BF) widened to fp32
+template <bool BF>
+__device__ __forceinline__ void load8(const uint16_t* p, float out[8])
 {
+    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int j = 0; j < 8; j++) out[j] = widen16<BF>((j & 1) ? w[j >> 1] >> 16 : w[j >> 1] & 0xFFFFu);
+}
+template <bool BF>
+__device__ __forceinline__ void store8(uint16_t* p, const float v[8], float scale)
+{
+    u32x4 w;
+#pragma unroll
+    for (int j = 0; j < 4; j++)
+        w[j] = (uint32_t)narrow16<BF>(v[2 * j] * scale) | ((uint32_t)narrow16<BF>(v[2 * j + 1] * scale) << 16);
+    *reinterpret_cast<u32x4*>(p) = w;
+}
+
+// value vector (8 consecutive columns starting at column 8v of the output row)
+template <int OP, bool BF>
+__device__ __forceinline__ void glue_values(const uint16_t* a, const uint16_t* b, int H, int v, float out[8])
+{
+    float x0[8], x1[8], x2[8];
     if constexpr (OP == 0) {            // q + k + v slices of one row of [3H]
-        half8_t x0 = *reinterpret_cast<const half8_t*>(a + 8 * v);
-        half8_t x1 = *reinterpret_cast<const half8_t*>(a + H + 8 * v);
-        half8_t x2 = *reinterpret_cast<const half8_t*>(a + 2 * H + 8 * v);
+        load8<BF>(a + 8 * v, x0); load8<BF>(a + H + 8 * v, x1); load8<BF>(a + 2 * H + 8 * v, x2);
 #pragma unroll
-        for (int j = 0; j < 8; j++) out[j] = (float)x0[j] + (float)x1[j] + (float)x2[j];
+        for (int j = 0; j < 8; j++) out[j] = x0[j] + x1[j] + x2[j];
     } else if constexpr (OP == 1) {     // a + b
-        half8_t x0 = *reinterpret_cast<const half8_t*>(a + 8 * v);
-        half8_t x1 = *reinterpret_cast<const half8_t*>(b + 8 * v);
+        load8<BF>(a + 8 * v, x0); load8<BF>(b + 8 * v, x1);
 #pragma unroll
-        for (int j = 0; j < 8; j++) out[j] = (float)x0[j] + (float)x1[j];
+        for (int j = 0; j < 8; j++) out[j] = x0[j] + x1[j];
     } else if constexpr (OP == 2) {     // silu(gate) * up, gate = a[:H], up = a[H:]
-        half8_t g = *reinterpret_cast<const half8_t*>(a + 8 * v);
-        half8_t u = *reinterpret_cast<const half8_t*>(a + H + 8 * v);
+        load8<BF>(a + 8 * v, x0); load8<BF>(a + H + 8 * v, x1);
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            float gf = (float)g[j];
-            out[j]   = gf / (1.0f + __expf(-gf)) * (float)u[j];
-        }
+        for (int j = 0; j < 8; j++) out[j] = x0[j] / (1.0f + __expf(-x0[j])) * x1[j];
     } else {
-        half8_t x0 = *reinterpret_cast<const half8_t*>(a + 8 * v);
-#pragma unroll
-        for (int j = 0; j < 8; j++) out[j] = (float)x0[j];
+        load8<BF>(a + 8 * v, out);
     }
 }
 
 // One workgroup per row.  Every thread computes its fp32 values once and keeps up to kGlueCache
 // vectors of them in registers across the row-wide sum of squares (rows wider than
 // 8 * kGlueThreads * kGlueCache columns recompute the rest: their inputs are still in cache).
+// BF: the rows are bfloat16 instead of fp16.
 constexpr int kGlueThreads = 512, kGlueCache = 4;
-template <int OP>
-__global__ __launch_bounds__(kGlueThreads) void glue_kernel(const half_t* __restrict__ a, const half_t* __restrict__ b,
-                                                            half_t* __restrict__ out, int H)
+template <int OP, bool BF>
+__global__ __launch_bounds__(kGlueThreads) void glue_kernel(const uint16_t* __restrict__ a, const uint16_t* __restrict__ b,
+                                                            uint16_t* __restrict__ out, int H)
 {
     __shared__ float wsum[kGlueThreads / 64];
     const int row = blockIdx.x, tid = threadIdx.x;
     const int in_cols = OP == 0 ? 3 * H : (OP == 2 ? 2 * H : H);
-    const half_t* ar = a + (size_t)row * in_cols;
-    const half_t* br = OP == 1 ? b + (size_t)row * H : nullptr;
+    const uint16_t* ar = a + (size_t)row * in_cols;
+    const uint16_t* br = OP == 1 ? b + (size_t)row * H : nullptr;
     const int nv = H / 8;
     float xc[kGlueCache][8];
     float ss = 0.f;
@@ -60,14 +71,14 @@ __global__ __launch_bounds__(kGlueThreads) void glue_kernel(const half_t* __rest
     for (int c = 0; c < kGlueCache; c++) {
         const int v = tid + c * kGlueThreads;
         if (v < nv) {
-            glue_values<OP>(ar, br, H, v, xc[c]);
+            glue_values<OP, BF>(ar, br, H, v, xc[c]);
 #pragma unroll
             for (int j = 0; j < 8; j++) ss += xc[c][j] * xc[c][j];
         }
     }
     for (int v = tid + kGlueCache * kGlueThreads; v < nv; v += kGlueThreads) {
         float x[8];
-        glue_values<OP>(ar, br, H, v, x);
+        glue_values<OP, BF>(ar, br, H, v, x);
 #pragma unroll
         for (int j = 0; j < 8; j++) ss += x[j] * x[j];
     }
@@ -82,20 +93,12 @@ __global__ __launch_bounds__(kGlueThreads) void glue_kernel(const half_t* __rest
 #pragma unroll
     for (int c = 0; c < kGlueCache; c++) {
         const int v = tid + c * kGlueThreads;
-        if (v < nv) {
-            half8_t h;
-#pragma unroll
-            for (int j = 0; j < 8; j++) h[j] = (half_t)(xc[c][j] * inv);
-            *reinterpret_cast<half8_t*>(out + (size_t)row * H + 8 * v) = h;
-        }
+        if (v < nv) store8<BF>(out + (size_t)row * H + 8 * v, xc[c], inv);
     }
     for (int v = tid + kGlueCache * kGlueThreads; v < nv; v += kGlueThreads) {
         float x[8];
-        glue_values<OP>(ar, br, H, v, x);
-        half8_t h;
-#pragma unroll
-        for (int j = 0; j < 8; j++) h[j] = (half_t)(x[j] * inv);
-        *reinterpret_cast<half8_t*>(out + (size_t)row * H + 8 * v) = h;
+        glue_values<OP, BF>(ar, br, H, v, x);
+        store8<BF>(out + (size_t)row * H + 8 * v, x, inv);
     }
 }
 
@@ -243,17 +246,21 @@ hipError_t launch_probe_mfma(int iters, void* out, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, hipStream_t st)
+template <bool BF>
+static void launch_glue_format(int op, const uint16_t* ha, const uint16_t* hb, uint16_t* ho, int M, int H, hipStream_t st)
 {
-    const half_t* ha = (const half_t*)a;
-    const half_t* hb = (const half_t*)b;
-    half_t*       ho = (half_t*)out;
     switch (op) {
-        case 0: hipLaunchKernelGGL(glue_kernel<0>, dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
-        case 1: hipLaunchKernelGGL(glue_kernel<1>, dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
-        case 2: hipLaunchKernelGGL(glue_kernel<2>, dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
-        default: hipLaunchKernelGGL(glue_kernel<3>, dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
+        case 0: hipLaunchKernelGGL((glue_kernel<0, BF>), dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
+        case 1: hipLaunchKernelGGL((glue_kernel<1, BF>), dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
+        case 2: hipLaunchKernelGGL((glue_kernel<2, BF>), dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
+        default: hipLaunchKernelGGL((glue_kernel<3, BF>), dim3(M), dim3(kGlueThreads), 0, st, ha, hb, ho, H); break;
     }
+}
+
+hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, int bf, hipStream_t st)
+{
+    if (bf) launch_glue_format<true>(op, (const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, M, H, st);
+    else    launch_glue_format<false>(op, (const uint16_t*)a, (const uint16_t*)b, (uint16_t*)out, M, H, st);
     return hipGetLastError();
 }
 

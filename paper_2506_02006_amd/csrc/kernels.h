@@ -108,7 +108,7 @@ int        stack_grid();   // workgroups of the persistent grid on the current d
 hipError_t launch_stack(const StackArgs& a, int grid, hipStream_t st);
 
 // ---- glue (glue.hip) ----
-hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, hipStream_t st);
+hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, int bf, hipStream_t st);   // bf: rows are bfloat16
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_cosine_rows(const void* a, const void* b, int bf, float* cos_out, float* mean_out, int M, int H, hipStream_t st);   // bf: rows are bfloat16
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t st);

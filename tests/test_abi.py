@@ -108,17 +108,22 @@ def test_workspace_bytes_rules(L):
 
 def test_glue_and_stack_validation(L):
     from paper_2506_02006_amd.binding import LayerDesc
-    assert L.morph_glue(9, FAKE, None, FAKE, 1, 64, None) == 2
-    assert L.morph_glue(1, FAKE, None, FAKE, 1, 64, None) == 1
-    assert L.morph_glue(0, FAKE, None, FAKE, 1, 60, None) == 2
+    for glue in (L.morph_glue, L.morph_glue_bf16):
+        assert glue(9, FAKE, None, FAKE, 1, 64, None) == 2
+        assert glue(1, FAKE, None, FAKE, 1, 64, None) == 1
+        assert glue(0, FAKE, None, FAKE, 1, 60, None) == 2
     assert L.morph_stack_scratch_bytes(32, 4096, 11008) > 32 * (12288 + 22016) * 2
     assert L.morph_stack_tap_bytes(32, 4096, 11008) == L.morph_stack_scratch_bytes(32, 4096, 11008)
     arr = (LayerDesc * 1)()
     for name in ("qkv", "o", "gate_up", "down"):
         d = getattr(arr[0], name)
         d.kind, d.w, d.scales, d.qzeros = 0, FAKE, None, None
-    sf = L.morph_stack_forward
     big = 1 << 30
+    sb = L.morph_stack_forward_bf16
+    assert sb(arr, 1, None, 32, 256, 384, FAKE, big, FAKE, big, -1, None, None) == 1
+    assert sb(arr, 1, FAKE, 65, 256, 384, FAKE, big, FAKE, big, -1, None, None) == 2
+    assert sb(arr, 1, FAKE, 32, 256, 384, FAKE, 16, FAKE, big, -1, None, None) == 4
+    sf = L.morph_stack_forward
     assert sf(arr, 1, None, 32, 256, 384, FAKE, big, FAKE, big, -1, None, None) == 1
     assert sf(arr, 1, FAKE, 65, 256, 384, FAKE, big, FAKE, big, -1, None, None) == 2
     assert sf(arr, 1, FAKE, 32, 200, 384, FAKE, big, FAKE, big, -1, None, None) == 2

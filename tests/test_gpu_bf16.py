@@ -288,3 +288,74 @@ def test_full_size_layers_sampled(B, oracle, family, linear, M):
     err = np.abs(got - ref).max() / np.abs(ref).max()
     say(f"  bf16 dense {family} {linear} M={M}: sampled err={err:.3e}")
     assert np.isfinite(got).all() and err <= TOL
+
+
+# ---------------- the elementwise steps and the layer stack in bfloat16 ----------------
+
+def test_glue_ops_bf16(B, oracle):
+    """fp32 arithmetic on the widened values, one rounding to bfloat16: the oracle's fp64 result must be
+    met within half a unit in the last place of bfloat16 (2^-8 of the value, 2^-8 of the largest here)."""
+    rng = np.random.default_rng(6)
+    M, H = 5, 1384
+    qkv = oracle.fp32_to_bf16((rng.standard_normal((M, 3 * H)) * 2).astype(np.float32))
+    a = oracle.fp32_to_bf16(rng.standard_normal((M, H)).astype(np.float32))
+    b = oracle.fp32_to_bf16((rng.standard_normal((M, H)) * 3).astype(np.float32))
+    gu = oracle.fp32_to_bf16((rng.standard_normal((M, 2 * H)) * 2).astype(np.float32))
+    w = lambda bits: oracle.bf16_to_fp32(bits)
+    cases = [(B.GLUE_QKV, qkv, None, oracle.glue_qkv(w(qkv))), (B.GLUE_RESIDUAL, a, b, oracle.glue_residual(w(a), w(b))),
+             (B.GLUE_SWIGLU, gu, None, oracle.glue_swiglu(w(gu))), (B.GLUE_RMS, a, None, oracle.rms(w(a)))]
+    for op, p, q, want in cases:
+        got = widen(oracle, host_bf(B.glue(op, dev_bf(p), dev_bf(q) if q is not None else None)))
+        r = oracle.error_metric(got, want)
+        say(f"  glue bf16 op={op}: err={r['err']:.3e}")
+        assert r["finite"] and r["err"] <= 2.0 ** -8
+
+
+def test_stack_bf16_with_all_three_kinds(B, oracle):
+    """A stack with bfloat16 activations: dense bfloat16, 4-bit and 8-bit layers side by side; every
+    linear and every elementwise step of one layer of each kind against the oracle on the inputs it
+    actually saw."""
+    hidden, inter, M = 256, 384, 7
+    shapes = oracle.layer_shapes(hidden, inter)
+    kinds = ["fp16", "w8", "w4", "w8", "fp16"]            # "fp16" = the full-precision variant, here in bfloat16
+    st = B.LayerStack(hidden, inter, M, dtype=torch.bfloat16)
+    hostrecs = []
+    for l, kname in enumerate(kinds):
+        rec, hr = {}, {}
+        for t, name in enumerate(oracle.RECORD_LINEARS):
+            K, N = shapes[name]
+            W = synth.weights(88, K, N, layer_id=l, tensor_id=t)
+            if kname == "fp16":
+                wb = oracle.fp32_to_bf16(W)
+                hr[name] = (wb,)
+                rec[name] = ("fp16", dev_bf(wb))
+            else:
+                arrays = oracle.quantize_w8(W) if kname == "w8" else oracle.quantize_w4(W)
+                hr[name] = arrays
+                rec[name] = (kname,) + tuple(dev(a) for a in arrays)
+        st.add_layer(rec)
+        hostrecs.append(hr)
+    x0 = oracle.fp32_to_bf16(oracle.rms(synth.activations(88, M, hidden).astype(np.float64)).astype(np.float32))
+
+    def lin(kname, xb, arrays):
+        if kname == "fp16":
+            return oracle.linear_bf16(xb, arrays[0])
+        return oracle.linear_q_bf16(4 if kname == "w4" else 8, xb, *arrays)
+
+    for tap in (0, 1, 2):
+        x = dev_bf(x0).clone()
+        st.forward(x, tap_layer=tap)
+        torch.cuda.synchronize()
+        t = {k: host_bf(v) for k, v in st.tapped().items()}
+        for name, xin, yout in (("qkv", "x", "qkv"), ("o", "a", "o"), ("gate_up", "r", "gu"), ("down", "m", "d")):
+            r = oracle.error_metric(widen(oracle, t[yout]), lin(kinds[tap], t[xin], hostrecs[tap][name]))
+            say(f"  bf16 stack layer {tap} ({kinds[tap]}) {name}: err={r['err']:.3e}")
+            assert r["finite"] and r["err"] <= TOL, r
+        f = lambda k: oracle.bf16_to_fp32(t[k])
+        for label, got, want in (("a", t["a"], oracle.glue_qkv(f("qkv"))), ("r", t["r"], oracle.glue_residual(f("x"), f("o"))),
+                                 ("m", t["m"], oracle.glue_swiglu(f("gu")))):
+            r = oracle.error_metric(widen(oracle, got), want)
+            say(f"  bf16 stack layer {tap} glue {label}: err={r['err']:.3e}")
+            assert r["finite"] and r["err"] <= 2.0 ** -8
+    out = widen(oracle, host_bf(x))
+    assert np.isfinite(out).all() and abs(np.sqrt((out ** 2).mean()) - 1.0) < 0.05      # the chain stays at unit RMS
