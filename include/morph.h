@@ -278,6 +278,8 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream);
  * part to the last one out: exercises the path taken after a wait that ran out).
  * 10 = prefill: number of workgroups (at most one per compute unit; with key 4 = 2 and fewer tiles than
  * that, K is shared out over them).
+ * 11 = prefill: who stages the tiles into LDS (1 = half the waves the weight tile and half the x tile,
+ * 2 = every wave an equal share of both; quantized kinds only).
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);
 

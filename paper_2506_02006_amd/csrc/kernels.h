@@ -68,6 +68,7 @@ struct GemmArgs {
     int         bf;         // x, dense weights and y are bfloat16 instead of fp16
     int         parts;      // > 1: K is cut into this many equal parts per tile, workgroups = tiles x parts (PrefillPlan::parts)
     int         polls;      // bound of a workgroup's wait for the other parts of its tile
+    int         uniform;    // staging shared out evenly over all waves instead of by role (set by launch_prefill)
 };
 struct PrefillPlan {
     int    config, bm, bn, tiles, grid, split_tail;
@@ -121,6 +122,6 @@ hipError_t launch_probe_mfma(int iters, void* out, hipStream_t st);
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_DECODE_SCATTER = 9, TUNE_PREFILL_GRID = 10, TUNE_COUNT = 12 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_DECODE_SCATTER = 9, TUNE_PREFILL_GRID = 10, TUNE_PREFILL_STAGING = 11, TUNE_COUNT = 12 };
 
 }  // namespace morph

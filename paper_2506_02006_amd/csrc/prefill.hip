@@ -73,7 +73,12 @@ __device__ __forceinline__ uint32_t scale_to_bf16x2(half2_t d, float s)
 // BF: x, y and the weights of kind 0 are bfloat16 (v_mfma_f32_32x32x16_bf16); the weight tile of the
 // quantized kinds then holds (q - z) * s rounded once to bfloat16: (q - z) is formed exactly in
 // fp16 as below, widened, multiplied by the scale in fp32 (exact) and narrowed.
-template <int Q, int BM, int BN, int WVM, int WVN, bool BF>
+// UNI: staging is shared out evenly instead of by role: every thread stages BM * 8 / threads pieces of
+// the x tile and one (or two) half blocks of the weight tile (8 rows x 4 columns: two column pairs).
+// A wave is in-order: while its MFMAs queue behind the other wave of its SIMD its own staging work
+// stalls too, so a wave that carries all of the dequantization was late at every barrier (measured:
+// the x-role waves waited 900 of 3100 cycles per k step of the 4-bit kernel, the weight-role waves 160).
+template <int Q, int BM, int BN, int WVM, int WVN, bool BF, bool UNI>
 __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kernel(GemmArgs p, int tiles_m, int tiles)
 {
     constexpr bool W4 = Q == 1, W8 = Q == 2, QUANT = Q != 0;
@@ -122,6 +127,21 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         const int idx = rt + NH * bl;
         b_lds[bl] = BM * LDK + (8 * (idx >> 3)) * LDK + 8 * (idx & 7);
     }
+    // uniform staging: x piece q = tid + NT i; half block number tid + NT s = 2 * block + half
+    constexpr int XPU = BM * (BK / 8) / NT;            // x pieces per thread
+    constexpr int NHB = 2 * NBLK;                      // half blocks of the weight tile
+    constexpr int HB  = (NHB + NT - 1) / NT;           // half blocks per thread (the last threads may have none)
+    static_assert(!UNI || (XPU * NT == BM * (BK / 8) && HB >= 1 && HB <= 2), "uniform staging divides over the threads");
+    uint32_t ux_voff0 = 0;
+    const uint32_t ux_vstep = (uint32_t)(NT / 8) * (uint32_t)K * 2u;
+    const int      ux_lds0  = (tid >> 3) * LDK + 8 * (tid & 7);
+    uint32_t ub_voff[HB], us_voff[HB], uz_voff[HB];
+    int      ub_lds[HB];
+#pragma unroll
+    for (int sl = 0; sl < HB; sl++) {
+        const int idx = tid + NT * sl, h = QUANT ? idx / NBLK : idx & 1, blk = QUANT ? idx - h * NBLK : idx >> 1;
+        ub_lds[sl] = BM * LDK + (8 * (blk >> 3) + 4 * h) * LDK + 8 * (blk & 7);
+    }
     // Schedule index -> tile.  Workgroups with consecutive indices run at the same time, and
     // workgroup g sits on XCD g % 8, each XCD with an L2 of its own.  Map 1 walks the row tiles of
     // one column tile first: the 32 workgroups of an XCD then work on ONE x tile and 32 different
@@ -144,6 +164,19 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             b_voff[bl] = b_ok ? (uint32_t)(8 * kb) * w_row + cbyte : kOut;
             s_voff[bl] = b_ok ? (uint32_t)bcol * 2u : kOut;
             z_voff[bl] = b_ok ? cbyte : kOut;
+        }
+        if constexpr (UNI) {
+            ux_voff0 = ((uint32_t)(m0 + (tid >> 3)) * (uint32_t)K + 8u * (tid & 7)) * 2u;
+#pragma unroll
+            for (int sl = 0; sl < HB; sl++) {
+                const int  idx = tid + NT * sl, h = QUANT ? idx / NBLK : idx & 1, blk = QUANT ? idx - h * NBLK : idx >> 1, kb = blk & 7, nb = blk >> 3;
+                const int  bcol = n0 + 8 * nb + 4 * h;
+                const bool ok = bcol < N && idx < NHB;
+                const uint32_t cbyte = W4 ? (uint32_t)bcol / 2u : W8 ? (uint32_t)bcol : (uint32_t)bcol * 2u;
+                ub_voff[sl] = ok ? (uint32_t)(8 * kb) * w_row + cbyte : kOut;
+                us_voff[sl] = ok ? (uint32_t)bcol * 2u : kOut;
+                uz_voff[sl] = ok ? cbyte : kOut;
+            }
         }
     };
     auto set_tile = [&](int tile) {
@@ -299,12 +332,120 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         }
     };
 
+    // ---- uniform staging (UNI): part kk = 0 .. 3 of a step ----
+    //   loads:  0: the x pieces; 2: half block 0 (with its scales and zero points); 3: half block 1
+    //   stores: 0: the x pieces; 1: half block 0; 2: half block 1
+    // (a half block is stored before the part that loads it again; the x pieces are loaded right
+    // behind their stores, a step and a half before they are needed)
+    u32x4    ux[UNI ? XPU : 1];
+    uint32_t uw[UNI ? HB : 1][8][QUANT ? 1 : 2];       // row i of the half block: 4 codes (2 or 4 bytes) or 4 halfs
+    u32x2    usc[UNI ? HB : 1];
+    uint32_t uzq[UNI ? HB : 1];
+    auto load_u = [&](int kt, int kk) {
+        if (kk == 0) {
+#pragma unroll
+            for (int i = 0; i < XPU; i++)
+                ux[i] = buf_load_u32x4(rx, ux_voff0 + (uint32_t)i * ux_vstep, (uint32_t)kt * (BK * 2u));
+        }
+#pragma unroll
+        for (int sl = 0; sl < HB; sl++) {
+            if (HB == 1 ? kk != 3 : kk != 2 + sl) continue;
+            const uint32_t so = (uint32_t)kt * BK * w_row;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                if constexpr (W4) uw[sl][i][0] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rw, ub_voff[sl], so + (uint32_t)i * w_row, 0);
+                else if constexpr (W8) uw[sl][i][0] = buf_load_u32(rw, ub_voff[sl], so + (uint32_t)i * w_row);
+                else {
+                    const u32x2 v = buf_load_u32x2(rw, ub_voff[sl], so + (uint32_t)i * w_row);
+                    uw[sl][i][0] = v[0];
+                    uw[sl][i][QUANT ? 0 : 1] = v[1];
+                }
+            }
+            if constexpr (QUANT) {
+                const uint32_t g = (uint32_t)(kt * BK) / kGroup;
+                usc[sl] = buf_load_u32x2(rs, us_voff[sl], g * (uint32_t)N * 2u);
+                if constexpr (W4) uzq[sl] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rz, uz_voff[sl], g * (uint32_t)NW * 4u, 0);
+                else              uzq[sl] = buf_load_u32(rz, uz_voff[sl], g * (uint32_t)NW * 4u);
+            }
+        }
+    };
+    auto store_u = [&](half_t* dst, int kk) {
+        if (kk == 0) {
+            half_t* base = dst + ux_lds0;
+#pragma unroll
+            for (int i = 0; i < XPU; i++) *reinterpret_cast<u32x4*>(base + i * (NT / 8) * LDK) = ux[i];
+        }
+#pragma unroll
+        for (int sl = 0; sl < HB; sl++) {
+            if (HB * NT != NHB && tid + NT * sl >= NHB) continue;         // whole waves: fewer half blocks than thread slots
+            half_t* bb = dst + ub_lds[sl];
+#pragma unroll
+            for (int j = 0; j < 2; j++) {                                 // column pair j of the half block
+                if (HB == 1 ? kk != 1 + j : kk != 1 + sl) continue;
+                u32x4 c0, c1;                                             // its two columns: 8 consecutive k each
+                const uint32_t sw = usc[sl][j];
+                const half_t  s0 = bit_cast<half_t>((uint16_t)(sw & 0xFFFFu)), s1 = bit_cast<half_t>((uint16_t)(sw >> 16));
+                const half2_t s0p = {s0, s0}, s1p = {s1, s1};
+                if constexpr (W4) {
+                    const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
+                    const uint32_t zq = uzq[sl];
+                    const uint32_t zd = j == 0 ? pair_bytes<0>(zq, zq) : pair_bytes<1>(zq, zq);
+                    const half2_t czl = bit_cast<half2_t>((zd & 0x000F000Fu) | 0xE400E400u);     // -(1024 + z)
+                    const half2_t czh = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xD400D400u);     // -(64 + z)
+                    const half2_t czh16 = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xE400E400u);   // -(1024 + 16 z)
+                    const float   s1_16 = (float)s1 * 0.0625f;
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const uint32_t r0 = uw[sl][2 * q][0], r1 = uw[sl][2 * q + 1][0];
+                        const uint32_t pr = j == 0 ? pair_bytes<0>(r0, r1) : pair_bytes<1>(r0, r1);
+                        if constexpr (BF) {
+                            c0[q] = scale_to_bf16x2(nib_lo_1024(pr) + czl, (float)s0);
+                            c1[q] = scale_to_bf16x2(nib_hi_1024(pr) + czh16, s1_16);
+                        } else {
+                            c0[q] = bit_cast<uint32_t>((nib_lo_1024(pr) + czl) * s0p);
+                            c1[q] = bit_cast<uint32_t>((nib_hi_1024(pr) * sixteenth + czh) * s1p);
+                        }
+                    }
+                } else if constexpr (W8) {
+                    const uint32_t zq = uzq[sl];
+                    const uint32_t z0 = j == 0 ? pair_bytes<0>(zq, zq) : pair_bytes<2>(zq, zq);
+                    const uint32_t z1 = j == 0 ? pair_bytes<1>(zq, zq) : pair_bytes<3>(zq, zq);
+                    const half2_t cz0 = bit_cast<half2_t>(z0 | 0xE400E400u), cz1 = bit_cast<half2_t>(z1 | 0xE400E400u);   // -(1024 + z)
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const uint32_t r0 = uw[sl][2 * q][0], r1 = uw[sl][2 * q + 1][0];
+                        const uint32_t p0 = j == 0 ? pair_bytes<0>(r0, r1) : pair_bytes<2>(r0, r1);
+                        const uint32_t p1 = j == 0 ? pair_bytes<1>(r0, r1) : pair_bytes<3>(r0, r1);
+                        const half2_t d0 = bit_cast<half2_t>(p0 | 0x64006400u) + cz0, d1 = bit_cast<half2_t>(p1 | 0x64006400u) + cz1;
+                        if constexpr (BF) {
+                            c0[q] = scale_to_bf16x2(d0, (float)s0);
+                            c1[q] = scale_to_bf16x2(d1, (float)s1);
+                        } else {
+                            c0[q] = bit_cast<uint32_t>(d0 * s0p);
+                            c1[q] = bit_cast<uint32_t>(d1 * s1p);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const uint32_t r0 = uw[sl][2 * q][QUANT ? 0 : j], r1 = uw[sl][2 * q + 1][QUANT ? 0 : j];
+                        c0[q] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);
+                        c1[q] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);
+                    }
+                }
+                *reinterpret_cast<u32x4*>(bb + (2 * j) * LDK)     = c0;
+                *reinterpret_cast<u32x4*>(bb + (2 * j + 1) * LDK) = c1;
+            }
+        }
+    };
+
     f32x16 acc[FM][FN];
     // when the global loads of the next-but-one tile are issued: right behind the LDS stores that
     // free their registers (x role: its halves of loads and stores use the same registers), or in
     // the second half of the step (weight role: every store needs all rows of the staged block)
-    constexpr std::true_type  kEarly{};
-    constexpr std::false_type kLate{};
+    constexpr std::integral_constant<int, 1> kEarly{};
+    constexpr std::integral_constant<int, 0> kLate{};
+    constexpr std::integral_constant<int, 2> kUniform{};   // uniform staging: the functions take the part 0 .. 3 themselves
 
     const int frow = lane & 31, fk = (lane >> 5) * 8;
     // One loop step of a wave: multiply tile kt out of `cur` (four k-substeps of 16), park tile kt+1
@@ -331,7 +472,10 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         for (int kk = 0; kk < BK / 16; kk++) {
             __builtin_amdgcn_sched_barrier(0);
             if (kk + 1 < BK / 16) read_frags((kk + 1) & 1, kk + 1);
-            if constexpr (decltype(early)::value) {
+            if constexpr (decltype(early)::value == 2) {
+                store_fn(nxt, kk);
+                load_fn(ktl, kk);
+            } else if constexpr (decltype(early)::value == 1) {
                 if (kk < 2) {
                     store_fn(nxt, kk);                   // buffer last read in step kt-1, behind a barrier
                     load_fn(ktl, kk);                    // into the registers that half just left
@@ -367,9 +511,13 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
         const int ks = k0 + 1 < k1 ? k0 + 1 : k0;
-        load_fn(k0, 0); load_fn(k0, 1);
-        store_fn(lds0, 0); store_fn(lds0, 1);
-        load_fn(ks, 0); load_fn(ks, 1);
+        constexpr int kParts = decltype(early)::value == 2 ? 4 : 2;
+#pragma unroll
+        for (int h = 0; h < kParts; h++) load_fn(k0, h);
+#pragma unroll
+        for (int h = 0; h < kParts; h++) store_fn(lds0, h);
+#pragma unroll
+        for (int h = 0; h < kParts; h++) load_fn(ks, h);
         __syncthreads();
         PF_WALL(1);
 #ifdef MORPH_TIMING
@@ -395,6 +543,12 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             p_ticks[(blockIdx.x * 8 + wave) * 2 + 1] = pf_wait;
         }
 #endif
+    };
+
+    auto run_tile = [&](int k0, int k1) {
+        if constexpr (UNI) run_range(k0, k1, store_u, load_u, kUniform);
+        else if (w_role)   run_range(k0, k1, store_w, load_w, kLate);
+        else               run_range(k0, k1, store_x, load_x, kEarly);
     };
 
     // ---- write the finished tile: each wave parks its part in LDS as fp16 (pitch WN + 8), then
@@ -449,8 +603,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     for (int r = 0; r < full_rounds; r++) {
         __syncthreads();                                 // LDS reuse after the previous tile's write-out
         set_tile(r * G + g);
-        if (w_role) run_range(0, KT, store_w, load_w, kLate);
-        else        run_range(0, KT, store_x, load_x, kEarly);
+        run_tile(0, KT);
         write_tile();
         PF_WALL(3);
     }
@@ -461,8 +614,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         if (g < tail_tiles) {
             __syncthreads();
             set_tile(tail_first + g);
-            if (w_role) run_range(0, KT, store_w, load_w, kLate);
-            else        run_range(0, KT, store_x, load_x, kEarly);
+            run_tile(0, KT);
             write_tile();
         }
         return;
@@ -491,8 +643,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         const int k0 = (int)(((long long)part * KT) / parts), k1 = (int)(((long long)(part + 1) * KT) / parts);
         __syncthreads();
         set_tile_tail(tile, 0);
-        if (w_role) run_range(k0, k1, store_w, load_w, kLate);
-        else        run_range(k0, k1, store_x, load_x, kEarly);
+        run_tile(k0, k1);
         const __amdgpu_buffer_rsrc_t rt_ = make_rsrc(p.partial + (size_t)tile * parts * (kPartBytes / 4), (uint32_t)parts * kPartBytes);
 #pragma unroll
         for (int i = 0; i < FM; i++)
@@ -571,8 +722,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         const int k1 = (u_end - u) < (KT - k0) ? k0 + (int)(u_end - u) : KT;
         __syncthreads();                                 // LDS reuse after the previous tile's write-out
         set_tile_tail(tile, tail_first / tiles_m);
-        if (w_role) run_range(k0, k1, store_w, load_w, kLate);
-        else        run_range(k0, k1, store_x, load_x, kEarly);
+        run_tile(k0, k1);
         u += k1 - k0;
         if (k0 == 0 && k1 == KT) {
             write_tile();
@@ -628,14 +778,14 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     }
 }
 
-template <int Q, int BM, int BN, int WVM, int WVN, bool BF>
+template <int Q, int BM, int BN, int WVM, int WVN, bool BF, bool UNI>
 hipError_t launch_tile(const GemmArgs& a, hipStream_t st)
 {
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const int tiles = tiles_m * tiles_n;
     // (One kernel for both ways of running the last round: a variant without the sharing code
     // spills no registers but was measured 8 % slower per k step; the spills sit outside the loop.)
-    hipLaunchKernelGGL((prefill_kernel<Q, BM, BN, WVM, WVN, BF>), dim3(a.grid), dim3(WVM * WVN * 64), 0, st, a, tiles_m, tiles);
+    hipLaunchKernelGGL((prefill_kernel<Q, BM, BN, WVM, WVN, BF, UNI>), dim3(a.grid), dim3(WVM * WVN * 64), 0, st, a, tiles_m, tiles);
     return hipGetLastError();
 }
 
@@ -751,17 +901,27 @@ PrefillPlan plan_prefill(int M, int K, int N)
 
 #endif
 
+template <int Q, bool BF, bool UNI>
+static hipError_t launch_staging(const GemmArgs& a, hipStream_t st)
+{
+    switch (a.config) {
+        case 1: return launch_tile<Q, 256, 256, 4, 2, BF, UNI>(a, st);
+        case 3: return launch_tile<Q, 256, 256, 2, 2, BF, UNI>(a, st);
+        case 4: return launch_tile<Q, 256, 128, 2, 2, BF, UNI>(a, st);
+        case 5: return launch_tile<Q, 256, 192, 4, 2, BF, UNI>(a, st);
+        case 6: return launch_tile<Q, 256, 128, 4, 2, BF, UNI>(a, st);
+        default: return launch_tile<Q, 128, 128, 2, 2, BF, UNI>(a, st);
+    }
+}
+
 template <int Q, bool BF>
 static hipError_t launch_config(const GemmArgs& a, hipStream_t st)
 {
-    switch (a.config) {
-        case 1: return launch_tile<Q, 256, 256, 4, 2, BF>(a, st);
-        case 3: return launch_tile<Q, 256, 256, 2, 2, BF>(a, st);
-        case 4: return launch_tile<Q, 256, 128, 2, 2, BF>(a, st);
-        case 5: return launch_tile<Q, 256, 192, 4, 2, BF>(a, st);
-        case 6: return launch_tile<Q, 256, 128, 4, 2, BF>(a, st);
-        default: return launch_tile<Q, 128, 128, 2, 2, BF>(a, st);
+    // (the dense kinds were slower with uniform staging on most shapes: not instantiated for them)
+    if constexpr (Q != 0) {
+        if (a.uniform) return launch_staging<Q, BF, true>(a, st);
     }
+    return launch_staging<Q, BF, false>(a, st);
 }
 
 #if !defined(MORPH_PREFILL_PART) || MORPH_PREFILL_PART == 1
@@ -781,6 +941,13 @@ hipError_t launch_prefill(int q, const GemmArgs& a0, hipStream_t st)
     const int force = tuning_get(TUNE_PREFILL_MAP);      // 0 = default (2), 1 / 2 = that map
     a.map = force == 1 ? 1 : 2;
     if (a.grid % 8 != 0) a.map = 1;
+    // Staging shared out evenly over all waves, or by role (half the waves the weight tile, half the x
+    // tile).  Measured on 7B / 13B shapes at M = 256 .. 2048: evenly is never slower than 3 % and up
+    // to 18 % faster for the 8-bit kind (its weight role carries twice the loads of the 4-bit one);
+    // for the 4-bit kind it wins where K is cut into parts (+1 .. 14 %) and loses elsewhere (up to
+    // 14 %); the dense kinds lose.  Tuning key 11: 1 = by role, 2 = evenly (quantized kinds).
+    const int staging = tuning_get(TUNE_PREFILL_STAGING);
+    a.uniform = staging == 2 || (staging == 0 && (q == 2 || (q == 1 && a.split_tail)));
     if (a.bf) return launch_prefill_bf16(q, a, st);
     return q == 1 ? launch_config<1, false>(a, st) : q == 2 ? launch_config<2, false>(a, st) : launch_config<0, false>(a, st);
 }

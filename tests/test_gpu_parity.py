@@ -207,6 +207,42 @@ def test_prefill_k_cut_chosen_by_shape(B, oracle):
         B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
 
 
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
+def test_prefill_staging_by_role_or_evenly(B, oracle, tile):
+    """The LDS tiles are staged either by role (half the waves the weight tile, half the x tile) or
+    evenly (every thread some x pieces and a half block of weights).  Same arithmetic: both must meet
+    the oracle and agree bit for bit, for the 4-bit and the 8-bit kind, fp16 and bfloat16 activations."""
+    B.set_tuning(B.TUNE_PREFILL_TILE, tile)
+    B.set_tuning(B.TUNE_DECODE_MAX_M, 32)
+    try:
+        for M, K, N in ((300, 512, 776), (130, 1408, 520)):
+            W = rand_w(tile, K, N)
+            x = synth.activations(77, M, K, layer_id=tile)
+            xd, xb = dev(x), dev(x).to(torch.bfloat16)
+            for bits in (4, 8):
+                rec = oracle.quantize_w4(W) if bits == 4 else oracle.quantize_w8(W)
+                rd = tuple(dev(a) for a in rec)
+                kind = B.KIND_W4A16 if bits == 4 else B.KIND_W8A16
+                ws = make_ws(B, kind, M, K, N)
+                ref = (oracle.linear_w4a16 if bits == 4 else oracle.linear_w8a16)(x, *rec)
+                outs = {}
+                for mode in (1, 2):
+                    B.set_tuning(B.TUNE_PREFILL_STAGING, mode)
+                    y = (B.linear_w4a16 if bits == 4 else B.linear_w8a16)(xd, *rd, ws)
+                    yb = (B.linear_w4a16_bf16 if bits == 4 else B.linear_w8a16_bf16)(xb, *rd, ws)
+                    torch.cuda.synchronize()
+                    r = oracle.error_metric(host(y), ref)
+                    say(f"  staging {mode} tile {tile} w{bits} M={M}: err={r['err']:.3e}")
+                    assert r["finite"] and r["err"] <= TOL, r
+                    outs[mode] = (y, yb)
+                assert torch.equal(outs[1][0], outs[2][0])
+                assert torch.equal(outs[1][1].view(torch.int16), outs[2][1].view(torch.int16))
+    finally:
+        B.set_tuning(B.TUNE_PREFILL_TILE, 0)
+        B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
+        B.set_tuning(B.TUNE_PREFILL_STAGING, 0)
+
+
 @pytest.mark.parametrize("max_m", [32, 1024, 0], ids=["mfma", "stream", "auto"])
 @pytest.mark.parametrize("M", [65, 100, 257, 600])
 def test_mid_sizes_in_either_kernel_family(B, oracle, M, max_m):
