@@ -211,8 +211,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // (8 halfs), W4: word i of block b = st[2 b + i / 4][i % 4], W8: the two words of row i =
     // st[4 b + i / 2][2 (i % 2) + 0, 1], plus scales and zero points per block
     u32x4    st[NST];
-    u32x4    sc_reg[WB];
-    uint32_t zq_reg[WB][W8 ? 2 : 1];
+    u32x4    sc_reg[2 * WB];                           // (second half: the other register set of the spread scheme)
+    uint32_t zq_reg[2 * WB][W8 ? 2 : 1];
 
     // Every staging function works on one half (h = 0, 1) of the thread's items, so that the loop can
     // spread the work over the k-substeps of a tile.
@@ -221,12 +221,13 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         for (int i = (XP / 2) * h; i < (XP / 2) * (h + 1); i++)
             st[i] = buf_load_u32x4(rx, a_voff0 + (uint32_t)i * a_vstep, (uint32_t)kt * (BK * 2u));
     };
-    auto load_w = [&](int kt, int h) {
+    // ro: first staging register of the set, set: which scales / zero points (0 except in the spread scheme)
+    auto load_w_set = [&](int kt, int h, int ro, int set) {
         const uint32_t so = (uint32_t)kt * BK * w_row;
 #pragma unroll
         for (int r = 4 * WB * h; r < 4 * WB * (h + 1); r++) {
             const int bl = r >> 3, i = r & 7;
-            if constexpr (W4) st[2 * bl + (i >> 2)][i & 3] = buf_load_u32(rw, b_voff[bl], so + (uint32_t)i * w_row);
+            if constexpr (W4) st[ro + 2 * bl + (i >> 2)][i & 3] = buf_load_u32(rw, b_voff[bl], so + (uint32_t)i * w_row);
             else if constexpr (W8) {
                 const u32x2 v = buf_load_u32x2(rw, b_voff[bl], so + (uint32_t)i * w_row);
                 st[4 * bl + (i >> 1)][2 * (i & 1)]     = v[0];
@@ -235,28 +236,29 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             if constexpr (QUANT) {
                 if (i == 0) {
                     const uint32_t g = (uint32_t)(kt * BK) / kGroup;
-                    sc_reg[bl] = buf_load_u32x4(rs, s_voff[bl], g * (uint32_t)N * 2u);
+                    sc_reg[set * WB + bl] = buf_load_u32x4(rs, s_voff[bl], g * (uint32_t)N * 2u);
                     if constexpr (W8) {
                         const u32x2 z = buf_load_u32x2(rz, z_voff[bl], g * (uint32_t)NW * 4u);
                         zq_reg[bl][0] = z[0];
                         zq_reg[bl][W8 ? 1 : 0] = z[1];
                     } else {
-                        zq_reg[bl][0] = buf_load_u32(rz, z_voff[bl], g * (uint32_t)NW * 4u);
+                        zq_reg[set * WB + bl][0] = buf_load_u32(rz, z_voff[bl], g * (uint32_t)NW * 4u);
                     }
                 }
             }
         }
     };
+    auto load_w = [&](int kt, int h) { load_w_set(kt, h, 0, 0); };
     auto store_x = [&](half_t* dst, int h) {
         half_t* base = dst + a_lds0;
 #pragma unroll
         for (int i = (XP / 2) * h; i < (XP / 2) * (h + 1); i++) *reinterpret_cast<u32x4*>(base + i * (NH / 8) * LDK) = st[i];
     };
     // unit u of the weight role = column pair (u % 4) of block (u / 4)
-    auto store_w = [&](half_t* dst, int h) {
+    auto store_w_units = [&](half_t* dst, int u0, int u1, int ro, int set) {
         if (WB == 1 && rt >= NBLK) return;               // whole waves: the tile has fewer blocks than the role has threads
 #pragma unroll
-        for (int u = 2 * WB * h; u < 2 * WB * (h + 1); u++) {
+        for (int u = u0; u < u1; u++) {
             const int bl = u >> 2, yb = u & 3;
             half_t* bb = dst + b_lds[bl];
             if constexpr (W8) {
@@ -290,12 +292,12 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                 *reinterpret_cast<u32x4*>(bb + (2 * yb + 1) * LDK) = c1;
             } else if constexpr (W4) {
                 const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
-                const uint32_t zq = zq_reg[bl][0];
+                const uint32_t zq = zq_reg[set * WB + bl][0];
                 const uint32_t zd = yb == 0 ? pair_bytes<0>(zq, zq) : yb == 1 ? pair_bytes<1>(zq, zq)
                                   : yb == 2 ? pair_bytes<2>(zq, zq) : pair_bytes<3>(zq, zq);
                 const half2_t czl = bit_cast<half2_t>((zd & 0x000F000Fu) | 0xE400E400u);   // -(1024 + z)
                 const half2_t czh = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xD400D400u);   // -(64 + z)
-                const uint32_t sw = sc_reg[bl][yb];                                        // scales of columns 2yb, 2yb+1
+                const uint32_t sw = sc_reg[set * WB + bl][yb];                              // scales of columns 2yb, 2yb+1
                 const half_t  s0 = bit_cast<half_t>((uint16_t)(sw & 0xFFFFu)), s1 = bit_cast<half_t>((uint16_t)(sw >> 16));
                 const half2_t s0p = {s0, s0}, s1p = {s1, s1};
                 u32x4 lo8, hi8;
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                 const float   s1_16 = (float)s1 * 0.0625f;
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
-                    const uint32_t r0 = st[2 * bl + ((2 * q) >> 2)][(2 * q) & 3], r1 = st[2 * bl + ((2 * q + 1) >> 2)][(2 * q + 1) & 3];
+                    const uint32_t r0 = st[ro + 2 * bl + ((2 * q) >> 2)][(2 * q) & 3], r1 = st[ro + 2 * bl + ((2 * q + 1) >> 2)][(2 * q + 1) & 3];
                     const uint32_t pr = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
                                       : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
                     if constexpr (BF) {
@@ -331,6 +333,16 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             }
         }
     };
+
+    auto store_w = [&](half_t* dst, int h) { store_w_units(dst, 2 * WB * h, 2 * WB * (h + 1), 0, 0); };
+    // Spread scheme of the weight role (4-bit kind, one block per thread): two register sets, so
+    // that the loads of the next-but-one tile need not wait for the stores of the next one, and one
+    // column pair of the block dequantized and stored in each of the four k-substeps instead of two
+    // pairs in each of the first two.
+    // (measured on 7B / 13B shapes at M = 300 .. 2048: 0 .. 5 % faster, same bits)
+    constexpr bool kSpread = W4 && !UNI && WB == 1 && 2 * RPB * WB <= NST;
+    auto store_w_spread = [&](half_t* dst, int kk, int set) { store_w_units(dst, kk, kk + 1, RPB * WB * set, set); };
+    auto load_w_spread  = [&](int kt, int h, int set) { load_w_set(kt, h, RPB * WB * set, set); };
 
     // ---- uniform staging (UNI): part kk = 0 .. 3 of a step ----
     //   loads:  0: the x pieces; 2: half block 0 (with its scales and zero points); 3: half block 1
@@ -446,6 +458,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     constexpr std::integral_constant<int, 1> kEarly{};
     constexpr std::integral_constant<int, 0> kLate{};
     constexpr std::integral_constant<int, 2> kUniform{};   // uniform staging: the functions take the part 0 .. 3 themselves
+    constexpr std::integral_constant<int, 3> kSpreadMode{}; // weight role, spread scheme: functions take (part, register set)
 
     const int frow = lane & 31, fk = (lane >> 5) * 8;
     // One loop step of a wave: multiply tile kt out of `cur` (four k-substeps of 16), park tile kt+1
@@ -456,7 +469,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // order), then the MFMAs with a piece of the staging work behind each.  Substeps 0 and 1 carry the
     // LDS stores of one half of the staged tile each; the global loads that refill the registers
     // follow at once (x role: a step and a half to arrive) or in substeps 2 and 3 (weight role).
-    auto step = [&](int kt, int kend, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn, auto early) {
+    // setc: the register set that holds tile kt + 1 (spread scheme only)
+    auto step = [&](int kt, int kend, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn, auto early, auto setc) {
         const int ktl = kt + 2 < kend ? kt + 2 : kend - 1;
         const half_t* abase = cur + (wm0 + frow) * LDK + fk;
         const half_t* bbase = cur + BM * LDK + (wn0 + frow) * LDK + fk;
@@ -472,7 +486,10 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         for (int kk = 0; kk < BK / 16; kk++) {
             __builtin_amdgcn_sched_barrier(0);
             if (kk + 1 < BK / 16) read_frags((kk + 1) & 1, kk + 1);
-            if constexpr (decltype(early)::value == 2) {
+            if constexpr (decltype(early)::value == 3) {
+                store_fn(nxt, kk, decltype(setc)::value);
+                if (kk < 2) load_fn(ktl, kk, 1 - decltype(setc)::value);
+            } else if constexpr (decltype(early)::value == 2) {
                 store_fn(nxt, kk);
                 load_fn(ktl, kk);
             } else if constexpr (decltype(early)::value == 1) {
@@ -511,13 +528,23 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
         const int ks = k0 + 1 < k1 ? k0 + 1 : k0;
-        constexpr int kParts = decltype(early)::value == 2 ? 4 : 2;
+        constexpr int kMode = decltype(early)::value;
+        constexpr std::integral_constant<int, 0> kSet0{};
+        constexpr std::integral_constant<int, 1> kSet1{};
+        if constexpr (kMode == 3) {                      // tile k0 into set 0 and on to LDS, tile k0 + 1 into set 1
+            load_fn(k0, 0, 0); load_fn(k0, 1, 0);
 #pragma unroll
-        for (int h = 0; h < kParts; h++) load_fn(k0, h);
+            for (int h = 0; h < 4; h++) store_fn(lds0, h, 0);
+            load_fn(ks, 0, 1); load_fn(ks, 1, 1);
+        } else {
+            constexpr int kParts = kMode == 2 ? 4 : 2;
 #pragma unroll
-        for (int h = 0; h < kParts; h++) store_fn(lds0, h);
+            for (int h = 0; h < kParts; h++) load_fn(k0, h);
 #pragma unroll
-        for (int h = 0; h < kParts; h++) load_fn(ks, h);
+            for (int h = 0; h < kParts; h++) store_fn(lds0, h);
+#pragma unroll
+            for (int h = 0; h < kParts; h++) load_fn(ks, h);
+        }
         __syncthreads();
         PF_WALL(1);
 #ifdef MORPH_TIMING
@@ -525,15 +552,15 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         const unsigned long long pf_t0 = __builtin_readcyclecounter();
 #endif
         int kt = k0;
-        // two steps per trip so that each step names its buffers statically
+        // two steps per trip so that each step names its buffers (and register sets) statically
         for (; kt + 2 <= k1; kt += 2) {
-            step(kt, k1, lds0, lds1, store_fn, load_fn, early);
+            step(kt, k1, lds0, lds1, store_fn, load_fn, early, kSet1);
             PF_BARRIER();
-            step(kt + 1, k1, lds1, lds0, store_fn, load_fn, early);
+            step(kt + 1, k1, lds1, lds0, store_fn, load_fn, early, kSet0);
             PF_BARRIER();
         }
         if (kt < k1) {                                   // odd count: one more step out of lds0
-            step(kt, k1, lds0, lds1, store_fn, load_fn, early);
+            step(kt, k1, lds0, lds1, store_fn, load_fn, early, kSet1);
             PF_BARRIER();
         }
         PF_WALL(2);
@@ -547,7 +574,10 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
 
     auto run_tile = [&](int k0, int k1) {
         if constexpr (UNI) run_range(k0, k1, store_u, load_u, kUniform);
-        else if (w_role)   run_range(k0, k1, store_w, load_w, kLate);
+        else if (w_role) {
+            if constexpr (kSpread) run_range(k0, k1, store_w_spread, load_w_spread, kSpreadMode);
+            else                   run_range(k0, k1, store_w, load_w, kLate);
+        }
         else               run_range(k0, k1, store_x, load_x, kEarly);
     };
 
