@@ -230,8 +230,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             if constexpr (W4) st[ro + 2 * bl + (i >> 2)][i & 3] = buf_load_u32(rw, b_voff[bl], so + (uint32_t)i * w_row);
             else if constexpr (W8) {
                 const u32x2 v = buf_load_u32x2(rw, b_voff[bl], so + (uint32_t)i * w_row);
-                st[4 * bl + (i >> 1)][2 * (i & 1)]     = v[0];
-                st[4 * bl + (i >> 1)][2 * (i & 1) + 1] = v[1];
+                st[ro + 4 * bl + (i >> 1)][2 * (i & 1)]     = v[0];
+                st[ro + 4 * bl + (i >> 1)][2 * (i & 1) + 1] = v[1];
             } else            st[8 * bl + i] = buf_load_u32x4(rw, b_voff[bl], so + (uint32_t)i * w_row);
             if constexpr (QUANT) {
                 if (i == 0) {
@@ -239,8 +239,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                     sc_reg[set * WB + bl] = buf_load_u32x4(rs, s_voff[bl], g * (uint32_t)N * 2u);
                     if constexpr (W8) {
                         const u32x2 z = buf_load_u32x2(rz, z_voff[bl], g * (uint32_t)NW * 4u);
-                        zq_reg[bl][0] = z[0];
-                        zq_reg[bl][W8 ? 1 : 0] = z[1];
+                        zq_reg[set * WB + bl][0] = z[0];
+                        zq_reg[set * WB + bl][W8 ? 1 : 0] = z[1];
                     } else {
                         zq_reg[set * WB + bl][0] = buf_load_u32(rz, z_voff[bl], g * (uint32_t)NW * 4u);
                     }
@@ -265,8 +265,8 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                 // columns 2yb, 2yb+1 of the block: bytes 2 (yb % 2), +1 of word yb / 2 of every row.
                 // The byte is ORed into the mantissa of 1024.0 (exactly 1024 + q), 1024 + z is taken off
                 // (exact), and one multiplication by the scale rounds once: exactly the fp16 dequantized value.
-                const uint32_t zq = zq_reg[bl][W8 ? (yb >> 1) : 0];
-                const uint32_t sw = sc_reg[bl][yb];
+                const uint32_t zq = zq_reg[set * WB + bl][W8 ? (yb >> 1) : 0];
+                const uint32_t sw = sc_reg[set * WB + bl][yb];
                 const half_t  s0 = bit_cast<half_t>((uint16_t)(sw & 0xFFFFu)), s1 = bit_cast<half_t>((uint16_t)(sw >> 16));
                 const half2_t s0p = {s0, s0}, s1p = {s1, s1};
                 const uint32_t z0 = (yb & 1) ? pair_bytes<2>(zq, zq) : pair_bytes<0>(zq, zq);
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                 u32x4 c0, c1;
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
-                    const uint32_t r0 = st[4 * bl + q][yb >> 1], r1 = st[4 * bl + q][2 + (yb >> 1)];               // rows 2q, 2q+1
+                    const uint32_t r0 = st[ro + 4 * bl + q][yb >> 1], r1 = st[ro + 4 * bl + q][2 + (yb >> 1)];               // rows 2q, 2q+1
                     const uint32_t p0 = (yb & 1) ? pair_bytes<2>(r0, r1) : pair_bytes<0>(r0, r1);
                     const uint32_t p1 = (yb & 1) ? pair_bytes<3>(r0, r1) : pair_bytes<1>(r0, r1);
                     const half2_t d0 = bit_cast<half2_t>(p0 | 0x64006400u) + cz0;                                  // q - z, exact
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // column pair of the block dequantized and stored in each of the four k-substeps instead of two
     // pairs in each of the first two.
     // (measured on 7B / 13B shapes at M = 300 .. 2048: 0 .. 5 % faster, same bits)
-    constexpr bool kSpread = W4 && !UNI && WB == 1 && 2 * RPB * WB <= NST;
+    constexpr bool kSpread = QUANT && !UNI && WB == 1 && 2 * RPB * WB <= NST;
     auto store_w_spread = [&](half_t* dst, int kk, int set) { store_w_units(dst, kk, kk + 1, RPB * WB * set, set); };
     auto load_w_spread  = [&](int kt, int h, int set) { load_w_set(kt, h, RPB * WB * set, set); };
 
