@@ -151,7 +151,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // for fp16, +0..3 % for W4).
     const int tiles_n = tiles / tiles_m;
     int tm = 0, tn = 0;
-    auto set_tile_at = [&]() {
+    auto set_tile_at = [&]() __attribute__((always_inline)) {
         m0 = tm * BM;
         n0 = tn * BN;
         a_voff0 = ((uint32_t)(m0 + (rt >> 3)) * (uint32_t)K + 8u * (rt & 7)) * 2u;
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             }
         }
     };
-    auto set_tile = [&](int tile) {
+    auto set_tile = [&](int tile) __attribute__((always_inline)) {
         tm = tile % tiles_m;
         tn = tile / tiles_m;
         if (p.map == 2) {
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // from tn_first on; the host shares out only then), numbered row tile by row tile, so that the
     // shares of different row tiles cut K at the same places and workgroups that hold the same
     // (column tile, k range) for different rows run in step and meet in the same XCD's L2.
-    auto set_tile_tail = [&](int t, int tn_first) {
+    auto set_tile_tail = [&](int t, int tn_first) __attribute__((always_inline)) {
         const int ntn = tiles_n - tn_first;
         tm = t / ntn;
         tn = tn_first + (t - tm * ntn);
@@ -216,13 +216,16 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
 
     // Every staging function works on one half (h = 0, 1) of the thread's items, so that the loop can
     // spread the work over the k-substeps of a tile.
-    auto load_x = [&](int kt, int h) {
+    auto load_x = [&](int kt, int h) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = (XP / 2) * h; i < (XP / 2) * (h + 1); i++)
             st[i] = buf_load_u32x4(rx, a_voff0 + (uint32_t)i * a_vstep, (uint32_t)kt * (BK * 2u));
     };
-    // ro: first staging register of the set, set: which scales / zero points (0 except in the spread scheme)
-    auto load_w_set = [&](int kt, int h, int ro, int set) {
+    // ro: first staging register of the set, set: which scales / zero points (0 except in the spread scheme).
+    // (The staging functions index registers with their arguments: they must be inlined so that the
+    // indices are constants; left to the inliner's judgement the bfloat16 variants were not, and their
+    // staging registers went to scratch memory: 40 times slower.)
+    auto load_w_set = [&](int kt, int h, int ro, int set) __attribute__((always_inline)) {
         const uint32_t so = (uint32_t)kt * BK * w_row;
 #pragma unroll
         for (int r = 4 * WB * h; r < 4 * WB * (h + 1); r++) {
@@ -248,14 +251,14 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             }
         }
     };
-    auto load_w = [&](int kt, int h) { load_w_set(kt, h, 0, 0); };
-    auto store_x = [&](half_t* dst, int h) {
+    auto load_w = [&](int kt, int h) __attribute__((always_inline)) { load_w_set(kt, h, 0, 0); };
+    auto store_x = [&](half_t* dst, int h) __attribute__((always_inline)) {
         half_t* base = dst + a_lds0;
 #pragma unroll
         for (int i = (XP / 2) * h; i < (XP / 2) * (h + 1); i++) *reinterpret_cast<u32x4*>(base + i * (NH / 8) * LDK) = st[i];
     };
     // unit u of the weight role = column pair (u % 4) of block (u / 4)
-    auto store_w_units = [&](half_t* dst, int u0, int u1, int ro, int set) {
+    auto store_w_units = [&](half_t* dst, int u0, int u1, int ro, int set) __attribute__((always_inline)) {
         if (WB == 1 && rt >= NBLK) return;               // whole waves: the tile has fewer blocks than the role has threads
 #pragma unroll
         for (int u = u0; u < u1; u++) {
@@ -334,15 +337,15 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         }
     };
 
-    auto store_w = [&](half_t* dst, int h) { store_w_units(dst, 2 * WB * h, 2 * WB * (h + 1), 0, 0); };
+    auto store_w = [&](half_t* dst, int h) __attribute__((always_inline)) { store_w_units(dst, 2 * WB * h, 2 * WB * (h + 1), 0, 0); };
     // Spread scheme of the weight role (4-bit kind, one block per thread): two register sets, so
     // that the loads of the next-but-one tile need not wait for the stores of the next one, and one
     // column pair of the block dequantized and stored in each of the four k-substeps instead of two
     // pairs in each of the first two.
     // (measured on 7B / 13B shapes at M = 300 .. 2048: 0 .. 5 % faster, same bits)
     constexpr bool kSpread = QUANT && !UNI && WB == 1 && 2 * RPB * WB <= NST;
-    auto store_w_spread = [&](half_t* dst, int kk, int set) { store_w_units(dst, kk, kk + 1, RPB * WB * set, set); };
-    auto load_w_spread  = [&](int kt, int h, int set) { load_w_set(kt, h, RPB * WB * set, set); };
+    auto store_w_spread = [&](half_t* dst, int kk, int set) __attribute__((always_inline)) { store_w_units(dst, kk, kk + 1, RPB * WB * set, set); };
+    auto load_w_spread  = [&](int kt, int h, int set) __attribute__((always_inline)) { load_w_set(kt, h, RPB * WB * set, set); };
 
     // ---- uniform staging (UNI): part kk = 0 .. 3 of a step ----
     //   loads:  0: the x pieces; 2: half block 0 (with its scales and zero points); 3: half block 1
@@ -353,7 +356,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     uint32_t uw[UNI ? HB : 1][8][QUANT ? 1 : 2];       // row i of the half block: 4 codes (2 or 4 bytes) or 4 halfs
     u32x2    usc[UNI ? HB : 1];
     uint32_t uzq[UNI ? HB : 1];
-    auto load_u = [&](int kt, int kk) {
+    auto load_u = [&](int kt, int kk) __attribute__((always_inline)) {
         if (kk == 0) {
 #pragma unroll
             for (int i = 0; i < XPU; i++)
@@ -381,7 +384,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
             }
         }
     };
-    auto store_u = [&](half_t* dst, int kk) {
+    auto store_u = [&](half_t* dst, int kk) __attribute__((always_inline)) {
         if (kk == 0) {
             half_t* base = dst + ux_lds0;
 #pragma unroll
@@ -470,12 +473,12 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // LDS stores of one half of the staged tile each; the global loads that refill the registers
     // follow at once (x role: a step and a half to arrive) or in substeps 2 and 3 (weight role).
     // setc: the register set that holds tile kt + 1 (spread scheme only)
-    auto step = [&](int kt, int kend, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn, auto early, auto setc) {
+    auto step = [&](int kt, int kend, const half_t* cur, half_t* nxt, auto store_fn, auto load_fn, auto early, auto setc) __attribute__((always_inline)) {
         const int ktl = kt + 2 < kend ? kt + 2 : kend - 1;
         const half_t* abase = cur + (wm0 + frow) * LDK + fk;
         const half_t* bbase = cur + BM * LDK + (wn0 + frow) * LDK + fk;
         half8_t af[2][FM], bf[2][FN];
-        auto read_frags = [&](int set, int kk) {
+        auto read_frags = [&](int set, int kk) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < FM; i++) af[set][i] = *reinterpret_cast<const half8_t*>(abase + i * 32 * LDK + kk * 16);
 #pragma unroll
@@ -520,7 +523,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     };
 
     // k-tiles [k0, k1) of the current tile: acc = x[m0.., k-range] * W[k-range, n0..]
-    auto run_range = [&](int k0, int k1, auto store_fn, auto load_fn, auto early) {
+    auto run_range = [&](int k0, int k1, auto store_fn, auto load_fn, auto early) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < FM; i++)
 #pragma unroll
@@ -572,7 +575,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
 #endif
     };
 
-    auto run_tile = [&](int k0, int k1) {
+    auto run_tile = [&](int k0, int k1) __attribute__((always_inline)) {
         if constexpr (UNI) run_range(k0, k1, store_u, load_u, kUniform);
         else if (w_role) {
             if constexpr (kSpread) run_range(k0, k1, store_w_spread, load_w_spread, kSpreadMode);
@@ -593,7 +596,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     // write_units stores the units named in `mask` (the whole tile: all ones).
     constexpr int UNITS = FM * FN * 4;
     static_assert(UNITS <= 64, "unit mask is one 64-bit word");
-    auto write_units = [&](uint64_t mask) {              // the range's last barrier freed the staging buffers
+    auto write_units = [&](uint64_t mask) __attribute__((always_inline)) {              // the range's last barrier freed the staging buffers
         half_t* et = (wave < HALF_WAVES ? lds0 : lds1) + (size_t)(wave % HALF_WAVES) * WM * EP;
 #pragma unroll
         for (int i = 0; i < FM; i++)
@@ -616,7 +619,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
                 *reinterpret_cast<u32x4*>(y + (size_t)grow * N + gcol) = *reinterpret_cast<const u32x4*>(et + row * EP + 8 * cv);
         }
     };
-    auto write_tile = [&]() { write_units(~0ull); };
+    auto write_tile = [&]() __attribute__((always_inline)) { write_units(~0ull); };
 
     // ---- work distribution.  The grid is one workgroup per compute unit (or fewer).  Full rounds:
     // workgroup g takes tile r * G + g whole, all workgroups walking K in step, so that neighbours
@@ -703,7 +706,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
         __syncthreads();                                 // the flag word is written again below, and the LDS is about to hold output
         // units u with u % parts == j: summed over the parts in index order (eight loads in flight; parts
         // beyond the last read past the tile's stretch of the buffer and come back as zeros), then written
-        auto reduce_units = [&](int j) {
+        auto reduce_units = [&](int j) __attribute__((always_inline)) {
             uint64_t mask = 0;
 #pragma unroll
             for (int u = 0; u < UNITS; u++) {
@@ -741,7 +744,7 @@ __global__ __launch_bounds__(WVM * WVN * 64, (WVM * WVN) / 4) void prefill_kerne
     }
 
     const long long units = (long long)tail_tiles * KT;
-    auto share_begin = [&](int gg) { return (long long)gg * units / G; };
+    auto share_begin = [&](int gg) __attribute__((always_inline)) { return (long long)gg * units / G; };
     const __amdgpu_buffer_rsrc_t rp = make_rsrc(p.partial, (uint32_t)(2 * G) * kPartBytes);
 
     long long u = share_begin(g);

@@ -359,3 +359,39 @@ def test_stack_bf16_with_all_three_kinds(B, oracle):
             assert r["finite"] and r["err"] <= 2.0 ** -8
     out = widen(oracle, host_bf(x))
     assert np.isfinite(out).all() and abs(np.sqrt((out ** 2).mean()) - 1.0) < 0.05      # the chain stays at unit RMS
+
+
+def test_bf16_kernels_are_not_slower_by_a_large_factor(B):
+    """A guard against a performance cliff (not a benchmark): the bfloat16 variants run the same code
+    as the fp16 ones but for the matrix instruction and the dequantization's last step; a variant whose
+    staging registers end up in scratch memory still passes every parity test and runs 40 times slower
+    (seen once).  Here each bfloat16 kernel must stay within twice the time of its fp16 sibling."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / 5
+
+    for M, K, N in ((1024, 4096, 4096), (16, 4096, 4096)):
+        w = torch.randn((K, N), device="cuda", generator=gen) * 0.02
+        x = torch.randn((M, K), device="cuda", generator=gen).half()
+        xb = x.to(torch.bfloat16)
+        q4, q8 = B.quantize_layer(w), B.quantize_layer_w8(w)
+        w16, wb = w.half(), w.to(torch.bfloat16)
+        ws = B.new_workspace(max(B.workspace_bytes(k, M, K, N) for k in (B.KIND_FP16, B.KIND_W4A16, B.KIND_W8A16)))
+        pairs = [("w4", lambda: B.linear_w4a16(x, *q4, ws), lambda: B.linear_w4a16_bf16(xb, *q4, ws)),
+                 ("w8", lambda: B.linear_w8a16(x, *q8, ws), lambda: B.linear_w8a16_bf16(xb, *q8, ws)),
+                 ("dense", lambda: B.linear_fp16(x, w16, ws), lambda: B.linear_bf16(xb, wb, ws))]
+        for label, f16, fbf in pairs:
+            t16, tbf = timed(f16), timed(fbf)
+            say(f"  M={M} {label}: fp16 {t16 * 1e3:.1f} us, bf16 {tbf * 1e3:.1f} us")
+            assert tbf < 2.0 * t16 + 0.02, (M, label, t16, tbf)
