@@ -20,8 +20,18 @@ UNITS = [("prefill.hip", "prefill", ["-DMORPH_PREFILL_PART=0"]), ("prefill.hip",
 
 # -packed-fp32-ops off: keep the compiler from forming packed fp32 instructions.
 # -amdgpu-kernarg-preload-count: leading scalar kernel arguments arrive in registers at wave launch.
+# -Rpass-analysis=kernel-resource-usage: the compiler reports registers and scratch memory of every kernel;
+#   _check_resources() below turns a kernel that keeps data in scratch memory into a build error.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-kernarg-preload-count=16"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-kernarg-preload-count=16",
+               "-Rpass-analysis=kernel-resource-usage"]
+
+# Scratch memory (bytes per lane) a kernel may use.  The hot kernels keep everything in registers; a
+# few hundred bytes of spills outside the loops are tolerated in the largest tile.  A kernel whose
+# staging arrays or closures end up in scratch memory still computes the right thing, 40 times slower
+# (seen once: a lambda the inliner had left out of line), so this is checked at build time.
+SCRATCH_BUDGET = 400
+SCRATCH_BUDGET_BY_NAME = {"ELi256ELi256ELi2ELi2E": 2048}    # the 4-wave 256 x 256 tile (test-only configuration)
 
 
 def _hipcc() -> str:
@@ -36,12 +46,45 @@ def _compile(unit, extra) -> str:
     obj = os.path.join(OBJ, name + ".o")
     cmd = [_hipcc()] + HIPCC_FLAGS + defines + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+    lines = r.stdout.splitlines()
+    usage, out, skip = _resource_remarks(lines)
+    out = "\n".join(l for i, l in enumerate(lines) if i not in skip and "packed-fp32-ops" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{out}")
     if out.strip():
         print(out, file=sys.stderr)
+    _check_resources(name, usage)
     return obj
+
+
+def _resource_remarks(lines):
+    """Parse the kernel-resource-usage remarks: {kernel: {field: value}}, and the line numbers they occupy."""
+    usage, skip, cur = {}, set(), None
+    for i, l in enumerate(lines):
+        if "[-Rpass-analysis=kernel-resource-usage]" in l:
+            skip.update((i, i + 1, i + 2))                  # the remark and the two source lines echoed after it
+            body = l.split("remark:", 1)[1].rsplit("[-Rpass", 1)[0].strip()
+            key, _, val = body.partition(":")
+            if key.strip() == "Function Name":
+                cur = val.strip()
+                usage[cur] = {}
+            elif cur is not None:
+                usage[cur][key.strip()] = val.strip()
+    return usage, None, skip
+
+
+def _check_resources(unit_name, usage):
+    report = os.path.join(OBJ, unit_name + ".resources.txt")
+    bad = []
+    with open(report, "w") as f:
+        for k, u in sorted(usage.items()):
+            scratch = int(u.get("ScratchSize [bytes/lane]", "0"))
+            f.write(f"{k}  VGPRs {u.get('VGPRs')}  AGPRs {u.get('AGPRs')}  scratch {scratch}  dynamic stack {u.get('Dynamic Stack')}\n")
+            budget = max([SCRATCH_BUDGET] + [b for pat, b in SCRATCH_BUDGET_BY_NAME.items() if pat in k])
+            if scratch > budget or u.get("Dynamic Stack") == "True":
+                bad.append(f"{k}: {scratch} bytes of scratch per lane (budget {budget}), dynamic stack {u.get('Dynamic Stack')}")
+    if bad:
+        raise RuntimeError("kernels that keep data in scratch memory (see the note at SCRATCH_BUDGET):\n  " + "\n  ".join(bad))
 
 
 def build(extra_flags=(), jobs: int = 7) -> str:
