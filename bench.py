@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--quick", action="store_true", help="headline only, skip the detail sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--sections", default="config2,config3,config4,config5,swap,w8,bf16,lis",
+    ap.add_argument("--sections", default="config2,config3,config4,config5,swap,w8,bf16,lis,quant",
                     help="detail sections to run after the headline (comma separated; used by the profiling commands)")
     return ap.parse_args()
 
@@ -343,6 +343,32 @@ def main():
                                                        "pct_hbm": round(nb / sl / 1e9 / HBM_PEAK_GBS * 100, 1)}
                 del aa, bb, g
             detail["lis_cosine"] = dl
+
+        # ---- the quantizer and the dequantizer export (off the per-token path): HBM-bound scans ----
+        if "quant" in sections:
+            dq = {}
+            for name in order:
+                K, N = shapes7[name]
+                for src_dt, label in ((torch.float32, "fp32"), (torch.float16, "fp16")):
+                    esz = 4 if src_dt == torch.float32 else 2
+                    n_src = max(2, int(-(-6e8 // (esz * K * N))))               # distinct masters, > 2 x the memory-side cache in total
+                    srcs = [rand_w(K, N).to(src_dt) for _ in range(n_src)]
+                    for bits, fn, out_b in ((4, B.quantize_layer, synth.w4_bytes(K, N)), (8, B.quantize_layer_w8, synth.w8_bytes(K, N))):
+                        g = graph_of(lambda: [fn(u) for u in srcs])
+                        sq = timed(lambda i: g.replay(), 3, 1) / (3 * n_src)
+                        nb = esz * K * N + out_b
+                        dq[f"quantize_w{bits}_from_{label}/{name}"] = {"us": round(sq * 1e6, 1), "GBps": round(nb / sq / 1e9, 1),
+                                                                      "pct_hbm": round(nb / sq / 1e9 / HBM_PEAK_GBS * 100, 1)}
+                        del g
+                    del srcs
+                recs = cold_pool(B.KIND_W4A16, K, N)[:8]
+                g = graph_of(lambda: [B.dequantize_w4(r[0], r[1], r[2], dtype=torch.float16) for r in recs])
+                sd = timed(lambda i: g.replay(), 3, 1) / (3 * len(recs))
+                nb = synth.w4_bytes(K, N) + 2 * K * N
+                dq[f"dequantize_w4_to_fp16/{name}"] = {"us": round(sd * 1e6, 1), "GBps": round(nb / sd / 1e9, 1),
+                                                       "pct_hbm": round(nb / sd / 1e9 / HBM_PEAK_GBS * 100, 1)}
+                del g, recs
+            detail["quantizer_llama7b"] = dq
 
         # ---- config 3: 8B GQA shapes, W4A16, M up to 64 ----
         if "config3" in sections:
