@@ -138,3 +138,28 @@ def test_activations_just_under_4_gib(B, oracle, kind):
     check(oracle, f"x near the limit, {kind}", y, ref, rs, cs)
     del xd, y, ws
     torch.cuda.empty_cache()
+
+
+def test_quantizer_and_dequantizer_beyond_4_gib(B, oracle):
+    """The quantizer and the dequantizer export address with 64 bits: 2.1e9 weights from a 4.3 GB fp16
+    master into a 4-bit record, and that record out again as 8.6 GB of fp32.  Columns are independent, so
+    slabs of columns (the first, the last, and one across column 65536) are compared bit for bit with the
+    oracle run on the slab alone."""
+    K, N = 16384, 131064
+    rng = np.random.default_rng([synth.BASE_SEED, 98])
+    say(f"  quantizer {K} x {N}: making the master")
+    w = random_fp16_bits(rng, (K, N))
+    gq, gs, gz = B.quantize_layer(dev(w))
+    out = B.dequantize_w4(gq, gs, gz, dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert out.numel() * 4 > LIMIT
+    for c0, c1 in ((0, 64), (65536 - 32, 65536 + 32), (N - 64, N)):
+        say(f"  columns {c0} .. {c1}")
+        qw, sc, qz = oracle.quantize_w4(w[:, c0:c1].view(np.float16).astype(np.float32))
+        assert np.array_equal(gs[:, c0:c1].cpu().numpy().view(np.uint16), sc.view(np.uint16))
+        assert np.array_equal(gz[:, c0 // 8:c1 // 8].cpu().numpy().view(np.uint32), qz)
+        assert np.array_equal(gq[:, c0 // 8:c1 // 8].cpu().numpy().view(np.uint32), qw)
+        d = oracle.dequant_w4(qw, sc, qz)
+        assert np.array_equal(out[:, c0:c1].cpu().numpy().view(np.uint32), d.view(np.uint32))
+    del gq, gs, gz, out
+    torch.cuda.empty_cache()
