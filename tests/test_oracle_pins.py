@@ -359,11 +359,77 @@ def test_o7_glue_closed_forms(oracle):
     assert np.allclose(r * np.sqrt(np.mean(v * v, axis=1, keepdims=True) + 1e-6), v)
     qkv = rng.standard_normal((2, 12))
     assert np.allclose(oracle.glue_qkv(qkv), oracle.rms(qkv[:, :4] + qkv[:, 4:8] + qkv[:, 8:]))
-    gu = np.array([[0.0, 2.0, 5.0, 3.0]])                       # gate = [0, 2], up = [5, 3]
-    want = np.array([[0.0, 2.0 / (1 + np.exp(-2.0)) * 3.0]])
-    assert np.allclose(oracle.glue_swiglu(gu), oracle.rms(want))
     a = rng.standard_normal((2, 8))
     assert np.allclose(oracle.glue_residual(a, -a), 0.0)
+
+
+def _swiglu_by_hand(gate, up):
+    """rms(silu(gate) * up) of one row written out with math.exp and math.sqrt: silu(g) = g / (1 + e^-g),
+    rms(v) = v / sqrt(mean(v^2) + 1e-6).  Shares nothing with the oracle."""
+    import math
+    prod = [g / (1.0 + math.exp(-g)) * u for g, u in zip(gate, up)]
+    scale = math.sqrt(sum(p * p for p in prod) / len(prod) + 1e-6)
+    return [p / scale for p in prod]
+
+
+def _swiglu_pin_holds(fn) -> bool:
+    """The checks that pin glue_swiglu; True when `fn` passes all of them."""
+    ok = True
+    # three elements, distinct gates and ups, one negative gate, a second row of its own
+    rows = [([1.0, -2.0, 0.5], [3.0, 1.0, -4.0]), ([-0.25, 4.0, 2.0], [2.0, -0.5, 1.5])]
+    gu = np.array([g + u for g, u in rows])                    # [M, 2F]: gate half, then up half
+    got = np.asarray(fn(gu), np.float64)
+    want = np.array([_swiglu_by_hand(g, u) for g, u in rows])
+    ok &= got.shape == want.shape and bool(np.allclose(got, want, rtol=1e-12, atol=1e-14))
+    # ratios of the elements of a row do not depend on the normalisation: silu(1)*3 : silu(-2)*1 : silu(.5)*-4
+    import math
+    s = lambda g: g / (1.0 + math.exp(-g))
+    if got.shape == want.shape and got[0, 1] != 0.0:
+        ok &= bool(np.isclose(got[0, 0] / got[0, 1], (s(1.0) * 3.0) / (s(-2.0) * 1.0), rtol=1e-12))
+        ok &= bool(np.isclose(got[0, 2] / got[0, 1], (s(0.5) * -4.0) / (s(-2.0) * 1.0), rtol=1e-12))
+    if got.shape == want.shape:
+        ok &= bool(got[0, 1] < 0 < got[0, 0])                     # silu of a negative gate is negative, not zero
+    # tiny values: the 1e-6 under the root decides the scale (mean(v^2) = 1e-8 here)
+    tiny = np.array([[2e-4, 2e-4, 1.0, 1.0]])                  # gate = up-row chosen so silu(g) * u ~ 1e-4
+    g0 = 2e-4 / (1.0 + math.exp(-2e-4))
+    want_tiny = g0 / math.sqrt(g0 * g0 + 1e-6)
+    got_tiny = np.asarray(fn(tiny), np.float64)
+    ok &= got_tiny.shape == (1, 2) and bool(np.allclose(got_tiny, want_tiny, rtol=1e-12))
+    return bool(ok)
+
+
+def test_o7_swiglu_pinned_by_hand_values(oracle):
+    """glue_swiglu against values written out by hand, and the mistakes it must not survive: each
+    mutant below is the oracle's formula with one plausible error and has to fail the same checks."""
+    assert _swiglu_pin_holds(oracle.glue_swiglu)
+
+    def halves(gu):
+        gu = np.asarray(gu, np.float64)
+        F = gu.shape[1] // 2
+        return gu[:, :F], gu[:, F:]
+
+    def rms_eps(v, eps):
+        return v / np.sqrt(np.mean(v * v, axis=-1, keepdims=True) + eps)
+
+    from scipy.special import erf
+    mutants = {
+        "no activation":     lambda gu: rms_eps(halves(gu)[0] * halves(gu)[1], 1e-6),
+        "relu":              lambda gu: rms_eps(np.maximum(halves(gu)[0], 0.0) * halves(gu)[1], 1e-6),
+        "gelu":              lambda gu: rms_eps(0.5 * halves(gu)[0] * (1.0 + erf(halves(gu)[0] / np.sqrt(2.0))) * halves(gu)[1], 1e-6),
+        "sigmoid only":      lambda gu: rms_eps(1.0 / (1.0 + np.exp(-halves(gu)[0])) * halves(gu)[1], 1e-6),
+        "halves swapped":    lambda gu: rms_eps(halves(gu)[1] / (1.0 + np.exp(-halves(gu)[1])) * halves(gu)[0], 1e-6),
+        "interleaved halves": lambda gu: rms_eps(np.asarray(gu, np.float64)[:, 0::2] / (1.0 + np.exp(-np.asarray(gu, np.float64)[:, 0::2]))
+                                                * np.asarray(gu, np.float64)[:, 1::2], 1e-6),
+        "silu(-g)":          lambda gu: rms_eps(halves(gu)[0] / (1.0 + np.exp(halves(gu)[0])) * halves(gu)[1], 1e-6),
+        "eps 1e-5":          lambda gu: rms_eps(halves(gu)[0] / (1.0 + np.exp(-halves(gu)[0])) * halves(gu)[1], 1e-5),
+        "no eps":            lambda gu: rms_eps(halves(gu)[0] / (1.0 + np.exp(-halves(gu)[0])) * halves(gu)[1], 0.0),
+        "no normalisation":  lambda gu: halves(gu)[0] / (1.0 + np.exp(-halves(gu)[0])) * halves(gu)[1],
+        "norm over all rows": lambda gu: (lambda p: p / np.sqrt(np.mean(p * p) + 1e-6))(halves(gu)[0] / (1.0 + np.exp(-halves(gu)[0])) * halves(gu)[1]),
+    }
+    for name, fn in mutants.items():
+        assert not _swiglu_pin_holds(fn), f"the pin lets the mutant '{name}' through"
+    # and the reference form of the correct formula, written independently here, passes
+    assert _swiglu_pin_holds(lambda gu: rms_eps(halves(gu)[0] / (1.0 + np.exp(-halves(gu)[0])) * halves(gu)[1], 1e-6))
 
 
 # ---------- planted mistakes: each must be caught by a pin above ----------
