@@ -13,8 +13,7 @@ timed steps / elapsed time, in GB/s.  The JSON line also carries:
   roofline      the W4A16 decode kernel against the 8 TB/s HBM peak, over the same timed region
   cpu_baseline  the CPU oracle (as it stands) on a bounded sample of the same workload
   detail        per-shape figures: fp16 for comparison, M up to 64 on the 8B-shaped layer, prefill
-                TFLOP/s on the 13B-shaped layer at M = 512 / 2048 (with the vendor fp16 GEMM behind
-                torch.matmul on the same operands for orientation), the 32-layer mixed stack
+                TFLOP/s on the 13B-shaped layer at M = 512 / 2048, the 32-layer mixed stack
 """
 import argparse
 import json
@@ -212,7 +211,7 @@ def main():
     sections = set() if args.quick else set(args.sections.split(","))
     if sections:
         # ---- per linear and per M, one shape back to back over the pool (W4A16 and fp16) ----
-        def per_linear(kind, family, name, M, recs, reps=60, vendor=False, bf=False):
+        def per_linear(kind, family, name, M, recs, reps=60, bf=False):
             K, N = synth.LAYER_SHAPES[family][name]
             x = rand_x(M, K)
             y = torch.empty((M, N), device=dev, dtype=torch.float16)
@@ -221,9 +220,7 @@ def main():
             w = B.new_workspace(B.workspace_bytes(kind, M, K, N))
             def run():
                 for r in recs:
-                    if vendor:
-                        torch.matmul(x, r, out=y)
-                    elif bf and kind == B.KIND_W4A16:
+                    if bf and kind == B.KIND_W4A16:
                         B.linear_w4a16_bf16(x, r[0], r[1], r[2], w, out=y)
                     elif bf and kind == B.KIND_W8A16:
                         B.linear_w8a16_bf16(x, r[0], r[1], r[2], w, out=y)
@@ -273,9 +270,6 @@ def main():
                 recs = cold_pool(B.KIND_FP16, *shapes7[name])
                 for M in (1, 4, 16):
                     d7[f"fp16/{name}/M{M}"] = per_linear(B.KIND_FP16, "llama7b", name, M, recs, reps=2 * len(recs))
-                # for orientation only: the vendor GEMM that torch.matmul dispatches to, same operands and layout
-                for M in (1, 16):
-                    d7[f"vendor_gemm_fp16/{name}/M{M}"] = per_linear(B.KIND_FP16, "llama7b", name, M, recs, reps=2 * len(recs), vendor=True)
                 del recs
             detail["config2_llama7b"] = d7
 
@@ -399,11 +393,6 @@ def main():
                     d13[f"{label}/{name}/M{M}"] = {"us": round(s * 1e6, 1), "TFLOPs": round(tf, 1),
                                                    "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1),
                                                    "pct_measured_mfma": round(tf / peaks["mfma_f16_TFLOPs"] * 100, 1)}
-                # for orientation only: the vendor GEMM that torch.matmul dispatches to, same operands and layout
-                s = timed(lambda i: torch.matmul(x, w16, out=y), 10, 2) / 10
-                tf = 2.0 * M * K * N / s / 1e12
-                d13[f"vendor_gemm_fp16/{name}/M{M}"] = {"us": round(s * 1e6, 1), "TFLOPs": round(tf, 1),
-                                                        "pct_mfma": round(tf / MFMA_F16_PEAK_TFLOPS * 100, 1)}
             del w4, w16
         if d13:
             detail["config4_llama13b_prefill"] = d13

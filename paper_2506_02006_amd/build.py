@@ -15,7 +15,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmorph.so")
 # (source, object name, extra defines): prefill.hip is compiled as two objects (fp16 / bfloat16 kernels) to halve the build time
 UNITS = [("prefill.hip", "prefill", ["-DMORPH_PREFILL_PART=0"]), ("prefill.hip", "prefill_bf16", ["-DMORPH_PREFILL_PART=1"]),
-         ("decode.hip", "decode", []), ("stack.hip", "stack", []), ("api.hip", "api", []), ("quant.hip", "quant", []),
+         ("decode.hip", "decode", []), ("decode_small.hip", "decode_small", []), ("stack.hip", "stack", []), ("api.hip", "api", []), ("quant.hip", "quant", []),
          ("glue.hip", "glue", [])]
 
 # -packed-fp32-ops off: keep the compiler from forming packed fp32 instructions.
@@ -87,16 +87,25 @@ def _check_resources(unit_name, usage):
         raise RuntimeError("kernels that keep data in scratch memory (see the note at SCRATCH_BUDGET):\n  " + "\n  ".join(bad))
 
 
-def build(extra_flags=(), jobs: int = 7) -> str:
+def build(extra_flags=(), jobs: int = 7, timing: bool = False) -> str:
+    """timing=True builds libmorph_timing.so instead: the same kernels with phase timestamps compiled in
+    (-DMORPH_TIMING, csrc/ticks.h), for profile_phases.py; objects go to _build/timing/."""
+    global OBJ
+    lib = LIB
+    if timing:
+        extra_flags = list(extra_flags) + ["-DMORPH_TIMING"]
+        OBJ = os.path.join(HERE, "_build", "timing")
+        lib = os.path.join(HERE, "libmorph_timing.so")
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda u: _compile(u, extra_flags), UNITS))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(sys.argv[1:]))
+    args = sys.argv[1:]
+    print(build([a for a in args if a != "--timing"], timing="--timing" in args))

@@ -33,7 +33,7 @@ bool takes_stream(int kind, int M, int K, int N)
     if (M > 1024) return false;
     const int cus = prefill_compute_units();
     const DecodePlan dp = plan_decode(kind, M, K, N);
-    if (dp.S > 1 && dp.tiles * dp.slices > (int)(kCounterBytes / sizeof(int)) / 2) return false;   // more tiles than counters
+    if (dp.S > 1 && dp.tiles * dp.slices > kPlainCounters / 2) return false;   // more tiles than counters
     // one workgroup walking its rows of K; fp16 rows come faster when many slices share them in the L2s
     const double ns_per_row = kind == MORPH_KIND_W4A16 ? 6.7 : kind == MORPH_KIND_W8A16 ? 4.5 : (dp.slices >= 8 ? 4.5 : 6.0);
     const long long wgs = (long long)dp.tiles * dp.slices * dp.S;
@@ -79,10 +79,10 @@ size_t workspace_need(int kind, int M, int K, int N)
 {
     if (!takes_stream(kind, M, K, N)) {
         const PrefillPlan pp = plan_prefill(M, K, N);
-        return pp.partial_bytes ? pp.counter_bytes + pp.partial_bytes : 0;
+        return pp.partial_bytes ? kScratchOffset + pp.partial_bytes : 0;
     }
     const DecodePlan pl = plan_decode(kind, M, K, N);
-    return pl.S > 1 ? kCounterBytes + pl.partial_bytes : 0;
+    return pl.S > 1 ? kScratchOffset + (pl.small ? 0 : pl.partial_bytes) : 0;
 }
 
 // bf: the 16-bit tensors (x, y, the weights of kind FP16) are bfloat16 instead of fp16
@@ -92,16 +92,29 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
     hipError_t e;
     if (takes_stream(kind, M, K, N)) {
         const DecodePlan pl = plan_decode(kind, M, K, N);
-        if (pl.S > 1 && pl.tiles * pl.slices > (int)(kCounterBytes / sizeof(int)) / 2) return MORPH_ERR_UNSUPPORTED;   // two counters per tile
+        if (pl.small) {
+            SmallArgs s;
+            s.x = x; s.w = w; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
+            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf;
+            s.slots = nullptr; s.ctl = nullptr;
+            if (pl.S > 1) {
+                if (!workspace || workspace_bytes < kScratchOffset) return MORPH_ERR_WORKSPACE;
+                if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
+                s.ctl    = reinterpret_cast<int*>(workspace) + kDepartBase;
+                s.slots  = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+            }
+            return launch_decode_small(s, st) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+        }
+        if (pl.S > 1 && pl.tiles * pl.slices > kPlainCounters / 2) return MORPH_ERR_UNSUPPORTED;   // two counters per tile
         DecodeArgs a;
         a.x = x; a.w = w; a.scales = scales; a.qzeros = qzeros; a.y = y;
         a.M = M; a.K = K; a.N = N; a.S = pl.S; a.rows = pl.rows; a.stream_loads = pl.stream_loads; a.scatter = pl.scatter; a.polls = pl.polls;
         a.partial = nullptr; a.counters = nullptr; a.bf = bf;
         if (pl.S > 1) {
-            if (!workspace || workspace_bytes < kCounterBytes + pl.partial_bytes) return MORPH_ERR_WORKSPACE;
+            if (!workspace || workspace_bytes < kScratchOffset + pl.partial_bytes) return MORPH_ERR_WORKSPACE;
             if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
             a.counters = reinterpret_cast<int*>(workspace);
-            a.partial  = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+            a.partial  = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kScratchOffset);
         }
         e = launch_decode(kind, a, st);
     } else {
@@ -112,13 +125,13 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         g.partial = nullptr; g.counters = nullptr; g.bf = bf;
         g.parts = pp.parts;
         g.polls = tuning_get(TUNE_DECODE_SCATTER) == 3 ? 0 : 4096;   // key 9 = 3: nobody waits (exercises the path taken after a wait that ran out)
-        if (pp.counter_bytes > ((size_t)1 << 20)) return MORPH_ERR_UNSUPPORTED;   // more tiles than counters are zeroed for
+        if (pp.counter_bytes > kCounterBytes) return MORPH_ERR_UNSUPPORTED;   // more tiles than the workspace has counters for
         if (pp.partial_bytes) {
-            if (!workspace || workspace_bytes < pp.counter_bytes + pp.partial_bytes) return MORPH_ERR_WORKSPACE;
+            if (!workspace || workspace_bytes < kScratchOffset + pp.partial_bytes) return MORPH_ERR_WORKSPACE;
             if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
             if ((size_t)2 * pp.grid * pp.bm * pp.bn * sizeof(float) >= k4G) return MORPH_ERR_UNSUPPORTED;
             g.counters = reinterpret_cast<int*>(workspace);
-            g.partial  = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + pp.counter_bytes);
+            g.partial  = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kScratchOffset);
         }
         e = launch_prefill(kind, g, st);
     }

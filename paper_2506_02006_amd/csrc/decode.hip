@@ -295,17 +295,7 @@ hipError_t launch_format(int q, bool one, const DecodeArgs& a, int slices, hipSt
 
 }  // namespace
 
-#ifdef MORPH_TIMING
-extern "C" int morph_debug_read_ticks(unsigned long long* host_out, int n)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_ticks), sizeof(unsigned long long) * n);
-}
-extern "C" int morph_debug_clear_ticks()
-{
-    static unsigned long long z[8192 * 16];
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_ticks), z, sizeof(z));
-}
-#endif
+MORPH_TICK_EXPORTS(ticks)
 
 namespace {
 
@@ -313,7 +303,7 @@ namespace {
 // estimate of the launch time net of what does not depend on the choice.
 DecodePlan plan_rows(int q, int M, int K, int N, int rows)
 {
-    DecodePlan pl;
+    DecodePlan pl{};
     pl.rows   = rows;
     const bool is_w4 = q == 1;                          // q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes
     pl.tile_n = !is_w4 ? Tile<0, 1>::TN : 256;          // workgroup tile (W4: 1 x 256 or 2 x 128 columns)
@@ -370,8 +360,42 @@ DecodePlan plan_rows(int q, int M, int K, int N, int rows)
 // put twice the workgroups along M instead of along K, which halves both the split and the
 // partial tile the last arriver has to add up.  For the 4-bit kernels between 17 and 64 rows the
 // estimate decides, as long as all workgroups of the 16-row plan run at the same time.
+// At most 16 rows of 4-bit weights: the kernel of decode_small.hip.  One workgroup per compute unit;
+// K is shared out over S <= 16 workgroups per column tile of 256 (one "share done" bit each in the
+// tile's counter), every workgroup keeping at least four k-steps, one per wave.
+static DecodePlan plan_small(int M, int K, int N)
+{
+    DecodePlan pl{};
+    pl.small  = 1;
+    pl.rows   = 16;
+    pl.slices = 1;
+    pl.tile_n = 256;
+    pl.tiles  = (N + 255) / 256;
+    const int T = K / 32;
+    int target = tuning_get(TUNE_DECODE_WGS);
+    if (target <= 0) target = 256;
+    int S = target / pl.tiles;
+    if (S > T / 4) S = T / 4;                            // every workgroup keeps at least one quantization group
+    if (S > 16) S = 16;
+    const int forced = tuning_get(TUNE_DECODE_SPLIT);
+    if (forced > 0) S = forced > 16 ? 16 : forced;
+    if (S > T / 4) S = T / 4;
+    if (S < 1) S = 1;
+    pl.S = S;
+    const size_t nvec = (size_t)256 * ((M + 3) / 4);     // vectors of four rows per tile
+    pl.partial_bytes = S > 1 ? (size_t)pl.tiles * S * nvec * 16 : 0;
+    pl.polls = tuning_get(TUNE_DECODE_SCATTER) == 3 ? 0 : 4096;   // 3: nobody looks, the last workgroup out adds everything up (test hook)
+    pl.stream_loads = 1;
+    pl.scatter = S > 1;
+    return pl;
+}
+
 DecodePlan plan_decode(int q, int M, int K, int N)
 {
+    if (q == 1 && M <= 16 && tuning_get(TUNE_SMALL) != 2) {
+        const DecodePlan ps = plan_small(M, K, N);
+        if (ps.partial_bytes <= kSlotBytes && (ps.S == 1 || ps.tiles <= 256)) return ps;
+    }
     const int t = tuning_get(TUNE_DECODE_SLICE);
     if (t == 16 || t == 32) return plan_rows(q, M, K, N, t);
     if (M <= 16) return plan_rows(q, M, K, N, 16);

@@ -34,23 +34,9 @@
 //     y += s * (2^69 * acc - z * 2^-64 * rowsum(2^64 x)).
 #pragma once
 #include "dev_common.h"
+#include "ticks.h"
 
 namespace morph {
-
-// Optional phase timestamps for tuning builds (-DMORPH_TIMING): thread 0 of every workgroup stores
-// the shader clock and the 100 MHz wall clock at a few points.  Compiled out of the product library.
-#ifdef MORPH_TIMING
-static __device__ unsigned long long g_ticks[8192 * 16];   // one copy per translation unit
-#define MORPH_TICK(i)                                                                          \
-    do {                                                                                       \
-        if (threadIdx.x == 0 && blockIdx.y == 0 && blockIdx.x < 8192) {                        \
-            g_ticks[blockIdx.x * 16 + 2 * (i)]     = __builtin_readcyclecounter();             \
-            g_ticks[blockIdx.x * 16 + 2 * (i) + 1] = wall_clock64();                           \
-        }                                                                                      \
-    } while (0)
-#else
-#define MORPH_TICK(i) do { } while (0)
-#endif
 
 constexpr int NS     = 4;            // register stages: the k-step being computed and three in flight
 

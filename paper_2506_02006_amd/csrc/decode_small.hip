@@ -1,0 +1,424 @@
+// W4A16 linears of at most 16 rows (the decode step proper): y[M,N] = x[M,K] * dequant(W4), bound
+// by the rate at which the packed codes leave HBM.  At these sizes a launch lasts a few
+// microseconds, of which the memory system needs one to deliver its first byte and every exchange
+// between workgroups through memory costs most of another, so the kernel is built around:
+//   * a short head: the division of K over workgroups and waves is prepared on the host, and a wave
+//     reaches its first load after a few dozen instructions;
+//   * loads that run three k-steps (of 32 rows) ahead of their use through a ring of four register
+//     stages in a loop unrolled by four (= one quantization group); a wave takes whole groups, so
+//     the only loads that fall outside its range are the last three slots' (pushed past the buffer,
+//     they return zeros without memory traffic) and the compiler's wait counts are exact;
+//   * running results in registers, and a fold that touches only accumulator components whose
+//     rows exist (M = 1: one of four);
+//   * a hand-over between the workgroups that split K which stays inside one XCD's L2 whenever the
+//     workgroups of a column tile share an XCD (see the end of the kernel).
+//
+// The multiply itself is the matrix-core scheme of the other streaming kernels: x as the A operand
+// of v_mfma_f32_16x16x32_f16 (rows beyond M read as zero), the codes as B without conversion -- a
+// 16-bit lane holding the byte 16 q_hi + q_lo IS that number times 2^-24 (fp16 subnormal), or times
+// 2^-133 read as bfloat16.  Per byte two MFMAs (whole byte; byte masked to its high nibble), one
+// more against a B of 2^-24 for the row sums of x; per group of 128 rows the sums are folded into
+// the running results:
+//     low-nibble column:   Y += s * (acc_byte - acc_high) - (s * z_lo) * xsum        (in units of 2^-24)
+//     high-nibble column:  Y += s *  acc_high             - (s * 16 z_hi) * xsum     (in units of 2^-20)
+// and the powers of two are taken out once, at the end.
+#include "dev_common.h"
+#include "kernels.h"
+#include "ticks.h"
+
+namespace morph {
+
+namespace {
+
+constexpr int kSmWaves = 4;
+constexpr int kRing    = 4;                      // register stages = slots of the unrolled loop (one quantization group)
+constexpr int kAhead   = 3;                      // k-steps a load runs ahead of its use
+
+struct SmallStage {
+    u32x2   w[8];                                // row 8b + i of the k-step: two packed words = 16 columns
+    half8_t a;                                   // x row (lane & 15), 8 consecutive k
+};
+struct SmallGroup {
+    u32x2 zq;                                    // zero points of the lane's 16 columns
+    u32x4 sc[2];                                 // their scales
+};
+
+// Per column tile, one word per split in the workspace's counter region (any content between launches):
+// the split's flag = 16 x (a counter its workgroup raises by one when its partial sums are in place)
+// + where those sums can be read: 0 = in memory, 1 + x = in the L2 of XCD x.  A reader compares the
+// counter with the value it found when it started.
+constexpr int kCtlInts = kSmallCtlInts;
+
+struct SmallTail {
+    void*     y;
+    uint32_t* slots;                             // [tile][split][vector] f32x4 partial sums (no content between launches)
+    int*      ctl;                               // kCtlInts per tile
+    int       polls;                             // looks at the flags before a workgroup stops waiting
+    int       nb;                                // groups of four rows that exist: ceil(M / 4)
+    int       tiles;                             // column tiles of 256
+    int       far;                               // write the hand-over through to memory instead of leaving it in the L2
+    int       inv_s;                             // ceil(65536 / S): j / S = (j * inv_s) >> 16 for the j that occur
+};
+
+template <bool BF>
+__device__ __forceinline__ f32x4 mfma_small(half8_t a, half8_t b, f32x4 c)
+{
+    if constexpr (BF) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(bit_cast<bf16x8_t>(a), bit_cast<bf16x8_t>(b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// Eight bfloat16 values times 2^64 (exact through fp32; zero stays zero).
+__device__ __forceinline__ half8_t bf16x8_up64(half8_t v)
+{
+    const u32x4 w = bit_cast<u32x4>(v);
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const float lo = bit_cast<float>(w[i] << 16) * 0x1p64f, hi = bit_cast<float>(w[i] & 0xFFFF0000u) * 0x1p64f;
+        o[i] = __builtin_amdgcn_perm(bit_cast<uint32_t>(hi), bit_cast<uint32_t>(lo), 0x07060302u);
+    }
+    return bit_cast<half8_t>(o);
+}
+
+// A compiler-level fence: buffer loads are plain reads to the compiler, which would otherwise keep
+// the value of the first look for all later ones.
+__device__ __forceinline__ void reload_fence() { asm volatile("" ::: "memory"); }
+
+// RL: accumulator components per lane that hold rows which exist (1: M = 1; 4 otherwise).
+// BF: x and y are bfloat16.
+template <int RL, bool BF>
+__global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
+    const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int M, int S,
+    int q_groups, int r_groups, SmallTail t)
+{
+    __shared__ __align__(16) f32x4 yl[kSmWaves * 16 * 64];     // [wave][column j of the lane][lane]
+    __shared__ uint32_t fresh_word;
+
+    MORPH_TICK(0);                                       // kernel entry
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, b = lane >> 4;
+    // Workgroup L runs on XCD L % 8 (workgroups are dealt to the XCDs in turn).  The S workgroups of a
+    // column tile are given the same L % 8, so that they meet in one L2: within XCD `xcd` the
+    // workgroups j = L / 8 walk (tile slot, split), tile = 8 * slot + xcd.  Tiles that do not exist
+    // (the last slot of an XCD when the tile count is no multiple of 8) leave at once.
+    const int L = blockIdx.x, xcd = L & 7, jj = L >> 3;
+    const int slot = (jj * t.inv_s) >> 16, sp = jj - slot * S;
+    const int tile = slot * 8 + xcd;
+    if (tile >= t.tiles) return;
+    const int n0 = tile * 256;
+    const int NW = N >> 3;
+
+    const uint32_t row_bytes = (uint32_t)NW * 4u;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
+    const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
+    // without a split there is no control block and no slot (null pointers): a range of zero makes every access fall outside
+    const __amdgpu_buffer_rsrc_t rc = make_rsrc(S > 1 ? t.ctl + (size_t)tile * kCtlInts : nullptr, S > 1 ? kCtlInts * 4u : 0u);
+
+    const int  ncol   = n0 + 16 * c;                     // this lane's first column
+    const bool col_ok = ncol < N;
+    const uint32_t kOut = 0xFFFFFFF0u;
+    const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + (uint32_t)ncol / 2u : kOut;
+    const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
+    const uint32_t voff_z = col_ok ? (uint32_t)ncol / 2u : kOut;
+    const uint32_t voff_a = ((uint32_t)c * (uint32_t)K + 8u * b) * 2u;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+    // The k loop runs for one split at a time: normally once, for this workgroup's own split; see the
+    // hand-over below for when it runs again.  begin_pass() fixes the range and requests its first loads.
+    int      ga = 0, gz = 0, ks1 = 0;
+    SmallStage st[kRing];
+    SmallGroup gcur, gnxt;
+    auto load_stage = [&](SmallStage& sg, int ks) {
+        const bool     dead = ks >= ks1;
+        const uint32_t dm   = dead ? kOut : 0u;
+        const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
+        const uint32_t vw   = voff_w | dm;
+#pragma unroll
+        for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32x2<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+        sg.a = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, voff_a | dm, dead ? 0u : (uint32_t)ks * 64u, 0));
+    };
+    auto load_group = [&](SmallGroup& gr, int g) {
+        const bool     dead = g >= gz;
+        const uint32_t gm   = dead ? kOut : 0u;
+        const uint32_t gg   = dead ? 0u : (uint32_t)g;
+        gr.zq    = buf_load_u32x2(rz, voff_z | gm, gg * row_bytes);
+        gr.sc[0] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u);
+        gr.sc[1] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u + 16u);
+    };
+    auto begin_pass = [&](int split) {
+        // quantization groups (128 rows = four k-steps) of the split, then of this wave: no division on the device
+        const int gb = split * q_groups + (split < r_groups ? split : r_groups);
+        const int ng = q_groups + (split < r_groups ? 1 : 0);
+        ga = gb + ((wave * ng) >> 2);
+        gz = gb + (((wave + 1) * ng) >> 2);
+        ks1 = 4 * gz;
+#pragma unroll
+        for (int i = 0; i < kAhead; i++) {
+            load_stage(st[i], 4 * ga + i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        load_group(gnxt, ga);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- everything the wave needs first is requested before anything else happens ----
+    uint32_t base = 0;                                   // wave 0: the tile's flags as found (lane q: split q)
+    begin_pass(sp);
+    // and the first wave reads the tile's flags as they stand: whatever a flag's counter turns into
+    // later was done in this launch
+    if (S > 1 && wave == 0 && lane < S) base = __builtin_amdgcn_raw_buffer_load_b32(rc, (uint32_t)lane * 4u, 0, kAuxSystemScope);
+    __builtin_amdgcn_sched_barrier(0);
+    MORPH_TICK(1);                                       // first loads issued
+
+    // A vector = four rows (4 b .. 4 b + 3) of one column; the tile has 256 nb of them, numbered
+    // id = j * 16 nb + lane (lanes 0 .. 16 nb - 1 are the ones whose rows exist).
+    const int nb = t.nb;                                 // groups of four rows that exist
+    const int lanes = 16 * nb, nvec = 16 * lanes;
+    auto vec_sum = [&](int id) {                         // over the waves, in the order of their k ranges
+        const int j = id / lanes, ln = id - j * lanes;
+        f32x4 a = yl[j * 64 + ln];
+#pragma unroll
+        for (int q = 1; q < kSmWaves; q++) a += yl[(q * 16 + j) * 64 + ln];
+        return a;
+    };
+    uint16_t* y = (uint16_t*)t.y;
+    auto vec_store_y = [&](int id, f32x4 acc) {
+        const int j = id / lanes, ln = id - j * lanes;
+        const int col = n0 + 16 * (ln & 15) + j, row = 4 * (ln >> 4);
+        if (col < N) {
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<BF>(acc[r]);
+        }
+    };
+    const uint32_t slot_bytes = (uint32_t)nvec * 16u;
+    const __amdgpu_buffer_rsrc_t rp = make_rsrc(S > 1 ? t.slots + (size_t)tile * S * nvec * 4 : nullptr, S > 1 ? (uint32_t)S * slot_bytes : 0u);
+    const int v0 = (sp * nvec) / S, v1 = ((sp + 1) * nvec) / S;   // my share of the tile's vectors: at most two per thread
+
+    // gacc[2 yb + 8 t]: sum of x * byte, gacc[.. + 1]: sum of x * (byte & 0xF0), over the open group
+    auto compute = [&](const SmallStage& sg, bool first, f32x4 (&gacc)[16], f32x4& xs) {
+        half8_t xa;
+        if constexpr (BF) xa = bf16x8_up64(sg.a);
+        else xa = sg.a;
+        const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
+        xs = mfma_small<BF>(xa, tiny, first ? zero4 : xs);
+#pragma unroll
+        for (int t2 = 0; t2 < 2; t2++) {
+#pragma unroll
+            for (int yb = 0; yb < 4; yb++) {
+                uint32_t pr[4], ph[4];
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
+                    pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                          : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                    ph[q] = pr[q] & 0x00F000F0u;
+                }
+                const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
+                const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
+                const int j0 = t2 * 8 + 2 * yb;
+                gacc[j0]     = mfma_small<BF>(xa, bbyte, first ? zero4 : gacc[j0]);
+                gacc[j0 + 1] = mfma_small<BF>(xa, bhigh, first ? zero4 : gacc[j0 + 1]);
+            }
+        }
+    };
+    // the group's sums go into the running results yr[column j of the lane][row 4 b + r]
+    auto fold = [&](const SmallGroup& gr, const f32x4 (&gacc)[16], const f32x4& xs, float (&yr)[16][RL]) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; t2++) {
+            const uint32_t zw  = gr.zq[t2];
+            const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;     // z of the even columns; 16 z of the odd ones
+#pragma unroll
+            for (int yb = 0; yb < 4; yb++) {
+                const uint32_t sw = gr.sc[t2][yb];
+                const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+                const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+                const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
+                const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
+                const int j0 = t2 * 8 + 2 * yb;
+#pragma unroll
+                for (int r = 0; r < RL; r++) {
+                    const float d = gacc[j0][r] - gacc[j0 + 1][r];
+                    yr[j0][r]     = __builtin_fmaf(-c_lo, xs[r], __builtin_fmaf(s_lo, d, yr[j0][r]));
+                    yr[j0 + 1][r] = __builtin_fmaf(-c_hi, xs[r], __builtin_fmaf(s_hi, gacc[j0 + 1][r], yr[j0 + 1][r]));
+                }
+            }
+        }
+    };
+    // The k loop of the split begin_pass() was called for; every wave leaves its sums in LDS (the powers
+    // of two taken out) and the workgroup meets at a barrier.
+    auto run_pass = [&]() {
+        f32x4 gacc[16], xs;
+        float yr[16][RL];
+#pragma unroll
+        for (int j = 0; j < 16; j++) {
+            gacc[j] = zero4;
+#pragma unroll
+            for (int r = 0; r < RL; r++) yr[j][r] = 0.f;
+        }
+        xs = zero4;
+        for (int g = ga; g < gz; g++) {
+            gcur = gnxt;
+#pragma unroll
+            for (int u = 0; u < kRing; u++) {
+                load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
+                if (u == 1) load_group(gnxt, g + 1);     // arrives well before the next group ends
+                __builtin_amdgcn_sched_barrier(0);
+                compute(st[u], u == 0, gacc, xs);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            fold(gcur, gacc, xs, yr);
+        }
+        constexpr float kEven = BF ? 0x1p69f : 0x1p24f;  // low-nibble (even) columns
+        constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;  // high-nibble (odd) columns: their sums carry a factor 16
+        if (b < nb) {
+#pragma unroll
+            for (int j = 0; j < 16; j++) {
+                f32x4 v = zero4;
+#pragma unroll
+                for (int r = 0; r < RL; r++) v[r] = yr[j][r] * ((j & 1) ? kOdd : kEven);
+                yl[(wave * 16 + j) * 64 + lane] = v;
+            }
+        }
+        __syncthreads();
+    };
+
+    run_pass();
+    MORPH_TICK(3);                                       // all waves done
+    if (S == 1) {
+        for (int id = tid; id < nvec; id += kSmWaves * 64) vec_store_y(id, vec_sum(id));
+        return;
+    }
+
+    // ---- hand-over between the S workgroups of a column tile ----
+    // Every workgroup puts its partial vectors into its slot -- except those of its own share,
+    // vectors [v0, v1), which stay with it -- waits for the stores to be acknowledged and raises its
+    // flag's counter by one.  Then it polls the S flags of the tile (one load per look), and when every
+    // counter differs from what it was when this workgroup started, it adds its share up over the
+    // splits, in split order, and stores y.  No arrival count, no atomic, nothing to put back: a
+    // counter can only have changed during this launch, after its owner's partial sums were in place.
+    // (A workgroup that starts so late that a flag was raised before it looked sees no change, and
+    // goes the slow way below.)
+    //   Where the data travels: the workgroups of a tile are placed on one XCD (see the top), so the
+    // stores are plain -- sums and flag stay in that XCD's L2, where the scoped loads of the others find
+    // them without a trip to memory -- and the flag says which XCD that is.  A reader that finds
+    // itself elsewhere (the placement is the hardware's; this only happens if it deals workgroups
+    // out differently) must not trust what it reads from memory, and takes that split the slow way.
+    // With t.far the stores are written through to memory and the flag says so.
+    //   Correctness does not rest on the others: the wait is bounded, and a workgroup that stops
+    // waiting works out the missing partial sums of its share itself -- it runs the k loop again for
+    // every split whose flag did not move.  Whoever adds a vector up, and wherever the terms come
+    // from, they are the same numbers added in split order.
+    uint32_t my_xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(my_xcc));
+    const uint32_t where = t.far ? 0u : (my_xcc & 0xFu) + 1u;
+    f32x4 keep[2];                                       // my own partial sums of my share
+    for (int i = 0; i < 2; i++) {
+        const int id = v0 + tid + i * kSmWaves * 64;
+        keep[i] = id < v1 ? vec_sum(id) : zero4;
+    }
+    for (int id = tid; id < nvec; id += kSmWaves * 64) {
+        if (id >= v0 && id < v1) continue;               // my share stays here
+        const u32x4 v = bit_cast<u32x4>(vec_sum(id));
+        const uint32_t off = (uint32_t)sp * slot_bytes + (uint32_t)id * 16u;
+        if (where) __builtin_amdgcn_raw_buffer_store_b128(v, rp, off, 0, 0);
+        else __builtin_amdgcn_raw_buffer_store_b128(v, rp, off, 0, kAuxSystemScope);
+    }
+    wait_stores();
+    __syncthreads();
+    MORPH_TICK(4);                                       // partials in place
+    const uint32_t want = (1u << S) - 1u;
+    if (wave == 0) {
+        if (lane == sp) {
+            const uint32_t up = (((base >> 4) + 1u) << 4) | where;
+            if (where) __builtin_amdgcn_raw_buffer_store_b32(up, rc, (uint32_t)sp * 4u, 0, 0);
+            else __builtin_amdgcn_raw_buffer_store_b32(up, rc, (uint32_t)sp * 4u, 0, kAuxSystemScope);
+        }
+        uint32_t moved = 1u << sp, usable = 1u << sp;
+        for (int look = 0; look < t.polls && moved != want; look++) {
+            reload_fence();
+            uint32_t f = base;
+            if (lane < S) f = __builtin_amdgcn_raw_buffer_load_b32(rc, (uint32_t)lane * 4u, 0, kAuxSystemScope);
+            reload_fence();
+            moved  = ((uint32_t)__builtin_amdgcn_ballot_w64((f >> 4) != (base >> 4)) & want) | (1u << sp);
+            usable = ((uint32_t)__builtin_amdgcn_ballot_w64((f >> 4) != (base >> 4) && ((f & 15u) == 0u || (f & 15u) == (my_xcc & 0xFu) + 1u)) & want) | (1u << sp);
+        }
+        if (lane == 0) fresh_word = usable;
+    }
+    __syncthreads();
+    const uint32_t fresh = fresh_word;                   // splits whose partial sums are in their slots, readable from here
+    MORPH_TICK(5);                                       // all flags seen (or no longer waited for)
+    if (fresh == want) {                                 // the usual way out
+        for (int i = 0; i < 2; i++) {
+            const int id = v0 + tid + i * kSmWaves * 64;
+            if (id >= v1) break;
+            u32x4 v[16];
+            reload_fence();
+#pragma unroll
+            for (int q = 0; q < 16; q++) {               // splits beyond S lie past the buffer and read as zeros
+                const uint32_t off = (q < S && q != sp) ? (uint32_t)q * slot_bytes + (uint32_t)id * 16u : 0xFFFFFFF0u;
+                v[q] = __builtin_amdgcn_raw_buffer_load_b128(rp, off, 0, kAuxSystemScope);
+            }
+            f32x4 acc = zero4;
+#pragma unroll
+            for (int q = 0; q < 16; q++)
+                if (q < S) acc += (q == sp) ? keep[i] : bit_cast<f32x4>(v[q]);
+            vec_store_y(id, acc);
+        }
+        MORPH_TICK(6);                                   // own share stored
+        return;
+    }
+
+    // ---- the slow way: the splits in order, each taken from its slot if it is there, worked out here if not ----
+    f32x4 total[2] = {zero4, zero4};
+    for (int q = 0; q < S; q++) {
+        if (q != sp && !((fresh >> q) & 1)) {
+            __syncthreads();                             // everyone is done reading the sums in LDS
+            begin_pass(q);
+            run_pass();
+        }
+        for (int i = 0; i < 2; i++) {
+            const int id = v0 + tid + i * kSmWaves * 64;
+            if (id >= v1) break;
+            if (q == sp) total[i] += keep[i];
+            else if ((fresh >> q) & 1) {
+                reload_fence();
+                total[i] += bit_cast<f32x4>(__builtin_amdgcn_raw_buffer_load_b128(rp, (uint32_t)q * slot_bytes + (uint32_t)id * 16u, 0, kAuxSystemScope));
+            } else total[i] += vec_sum(id);
+        }
+    }
+    for (int i = 0; i < 2; i++) {
+        const int id = v0 + tid + i * kSmWaves * 64;
+        if (id < v1) vec_store_y(id, total[i]);
+    }
+}
+
+template <int RL, bool BF>
+hipError_t launch_small_t(const SmallArgs& a, hipStream_t st)
+{
+    const int G = a.K / kGroup;
+    SmallTail t;
+    t.y = a.y; t.slots = a.slots; t.ctl = a.ctl; t.polls = a.polls; t.nb = (a.M + 3) / 4;
+    t.tiles = a.tiles; t.far = a.far; t.inv_s = (65536 + a.S - 1) / a.S;
+    const int grid = 8 * ((a.tiles + 7) / 8) * a.S;
+    hipLaunchKernelGGL((decode_small_kernel<RL, BF>), dim3(grid), dim3(kSmWaves * 64), 0, st,
+                       (const uint32_t*)a.w, a.x, a.scales, (const uint32_t*)a.qzeros, a.K, a.N, a.M, a.S, G / a.S, G % a.S, t);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+MORPH_TICK_EXPORTS(small_ticks)
+
+hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
+{
+    if (a.M < 1 || a.M > 16 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1) return hipErrorInvalidValue;
+    if (a.S > 1 && a.tiles > 256) return hipErrorInvalidValue;
+    if (a.M == 1) return a.bf ? launch_small_t<1, true>(a, st) : launch_small_t<1, false>(a, st);
+    return a.bf ? launch_small_t<4, true>(a, st) : launch_small_t<4, false>(a, st);
+}
+
+}  // namespace morph

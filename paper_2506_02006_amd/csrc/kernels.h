@@ -45,11 +45,42 @@ struct DecodePlan {
     int    stream_loads;       // load the weights non-temporally
     int    scatter;            // share the sum over the splits out among the workgroups of a tile
     int    polls;              // how many times a workgroup looks for the others before it gives up
+    int    small;              // the launch goes to the kernel for at most 16 rows of 4-bit weights (decode_small.hip)
 };
-constexpr size_t kCounterBytes = 65536;  // head of the workspace: arrival counters (one per column tile and row slice)
+// Workspace layout, the same for every kernel family so that one workspace serves any sequence of calls:
+//   [0, kCounterBytes)                 counters, zero between launches
+//   [kCounterBytes, kScratchOffset)    hand-over slots of decode_small.hip, no content between launches
+//   [kScratchOffset, ...)              partial sums of the other kernels, no content between launches
+constexpr size_t kCounterBytes  = (size_t)1 << 20;
+constexpr size_t kSlotBytes     = (size_t)8 << 20;
+constexpr size_t kScratchOffset = kCounterBytes + kSlotBytes;
+// Inside the counters: the streaming kernels' plain arrival counters are ints [0, kPlainCounters), their
+// polled pairs follow 32 ints apart; the departure counters of decode_small.hip start at int kDepartBase
+// (256 tiles x kSmallCtlInts ints); the LDS-tiled kernels use what their plan asks for, from int 0.
+constexpr int kPlainCounters = 16384;
+constexpr int kDepartBase    = 65536;
+constexpr int kSmallCtlInts  = 96;
 // q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes (the MORPH_KIND_* values)
 DecodePlan plan_decode(int q, int M, int K, int N);
 hipError_t launch_decode(int q, const DecodeArgs& a, hipStream_t st);
+
+// ---- 4-bit weights, M <= 16 (decode_small.hip) ----
+struct SmallArgs {
+    const void* x;         // fp16 / bfloat16 [M,K]
+    const void* w;         // uint32 [K,N/8]
+    const void* scales;    // fp16 [K/128,N]
+    const void* qzeros;    // uint32 [K/128,N/8]
+    void*       y;         // fp16 / bfloat16 [M,N]
+    uint32_t*   slots;     // [tile][split][vector] x 16 bytes of partial sums (S > 1)
+    int*        ctl;       // kSmallCtlInts per tile: departure counter, flags, tags; zero on entry, zero on exit (S > 1)
+    int         M, K, N;
+    int         S;         // workgroups sharing one column tile (1 .. 16)
+    int         tiles;     // column tiles of 256
+    int         polls;     // looks at the others' flags before a workgroup gives up
+    int         far;       // hand-over always written through to memory, never left in an L2 (test hook)
+    int         bf;
+};
+hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st);
 
 // ---- prefill, M > 64 (prefill.hip) ----
 struct GemmArgs {
@@ -122,6 +153,6 @@ hipError_t launch_probe_mfma(int iters, void* out, hipStream_t st);
 // tuning knobs (morph_set_tuning)
 int  tuning_get(int key);
 void tuning_set(int key, int value);
-enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_DECODE_SCATTER = 9, TUNE_PREFILL_GRID = 10, TUNE_PREFILL_STAGING = 11, TUNE_COUNT = 12 };
+enum { TUNE_DECODE_SPLIT = 0, TUNE_DECODE_WGS = 1, TUNE_PREFILL_TILE = 2, TUNE_DECODE_WAVES = 3, TUNE_PREFILL_SPLIT = 4, TUNE_PREFILL_MAP = 5, TUNE_DECODE_MAX_M = 6, TUNE_DECODE_SLICE = 7, TUNE_DECODE_STREAM = 8, TUNE_DECODE_SCATTER = 9, TUNE_PREFILL_GRID = 10, TUNE_PREFILL_STAGING = 11, TUNE_SMALL = 12, TUNE_SMALL_DEPTH = 13, TUNE_COUNT = 14 };
 
 }  // namespace morph

@@ -469,7 +469,7 @@ extern "C" int morph_debug_read_stack_ticks(unsigned long long* host_out, int n)
 }
 extern "C" int morph_debug_read_stack_core_ticks(unsigned long long* host_out, int n)
 {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_ticks), sizeof(unsigned long long) * n);
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(morph::g_ticks), sizeof(unsigned long long) * n);
 }
 #endif
 
