@@ -372,8 +372,11 @@ static DecodePlan plan_small(int M, int K, int N)
     pl.tile_n = 256;
     pl.tiles  = (N + 255) / 256;
     const int T = K / 32;
+    // Never more workgroups than compute units: the workgroups of a tile wait for each other's partial
+    // sums, which is quick only while all of them run at the same time (one per compute unit: the kernel
+    // uses more than half the registers and the LDS of one).
     int target = tuning_get(TUNE_DECODE_WGS);
-    if (target <= 0) target = 256;
+    if (target <= 0) target = prefill_compute_units();
     int S = target / pl.tiles;
     if (S > T / 4) S = T / 4;                            // every workgroup keeps at least one quantization group
     if (S > 16) S = 16;

@@ -155,13 +155,13 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
         ga = gb + ((wave * ng) >> 2);
         gz = gb + (((wave + 1) * ng) >> 2);
         ks1 = 4 * gz;
+        load_group(gnxt, ga);                            // first, so that what waits for it does not wait for the stages too
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < kAhead; i++) {
             load_stage(st[i], 4 * ga + i);
             __builtin_amdgcn_sched_barrier(0);
         }
-        load_group(gnxt, ga);
-        __builtin_amdgcn_sched_barrier(0);
     };
 
     // ---- everything the wave needs first is requested before anything else happens ----
