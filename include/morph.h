@@ -79,6 +79,23 @@ int morph_linear_w4a16(const void* x, const int32_t* qweight, const void* scales
                        const int32_t* qzeros, void* y, int M, int K, int N, int group_size,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- morph_linear_w4a16 for callers that cannot allocate ----
+ * For code that runs under HIP graph capture, tight serving loops and harnesses that forbid
+ * hipMalloc: the same call for decode sizes (M <= 16) without a workspace argument.  What the kernel
+ * hands between its workgroups lives in an array that is part of the library's device image
+ * (morph_noalloc_scratch_bytes() bytes, about 4.1 MB, on every device that loads the library, until
+ * the process ends); the call allocates nothing, frees nothing and calls no allocating routine.
+ * Same arguments, validation and results (bit for bit) as morph_linear_w4a16.
+ * UNSUPPORTED: M > 16, or a shape whose hand-over does not fit the array (more than 256 column tiles of
+ * 256 with K split, or more than 4 MiB of partial sums: no shape of a 7B .. 70B layer comes near).
+ * All calls on one device share that device's array: two calls that can overlap (different streams)
+ * race, exactly as two calls sharing a workspace would.  Nothing has to be cleared between calls: the
+ * kernel takes the array's contents as it finds them. */
+int morph_linear_w4a16_noalloc(const void* x, const int32_t* qweight, const void* scales,
+                               const int32_t* qzeros, void* y, int M, int K, int N, int group_size,
+                               void* stream);
+size_t morph_noalloc_scratch_bytes(void);
+
 /* ---- produce the 4-bit record of one weight matrix (the variant that gets swapped in) ----
  * w [K,N] in w_dtype (MORPH_DTYPE_F32, MORPH_DTYPE_F16 or MORPH_DTYPE_BF16; 16-bit values are
  * widened exactly).  Per (group g, column n):

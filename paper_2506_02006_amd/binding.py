@@ -34,6 +34,7 @@ EXPORTS = [
     "morph_quantize_layer_w8", "morph_dequantize_w8", "morph_linear_w8a16", "morph_cosine_rows",
     "morph_linear_bf16", "morph_linear_w4a16_bf16", "morph_linear_w8a16_bf16", "morph_cosine_rows_bf16",
     "morph_glue_bf16", "morph_stack_forward_bf16",
+    "morph_linear_w4a16_noalloc", "morph_noalloc_scratch_bytes",
 ]
 
 
@@ -66,6 +67,9 @@ def lib() -> ctypes.CDLL:
     vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     L.morph_linear_fp16.argtypes = [vp, vp, vp, i, i, i, vp, sz, vp]
     L.morph_linear_w4a16.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.morph_linear_w4a16_noalloc.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
+    L.morph_noalloc_scratch_bytes.argtypes = []
+    L.morph_noalloc_scratch_bytes.restype = sz
     L.morph_quantize_layer.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w4.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_linear_w8a16.argtypes = L.morph_linear_w4a16.argtypes
@@ -107,7 +111,8 @@ def lib() -> ctypes.CDLL:
     L.morph_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
         if name not in ("morph_workspace_bytes", "morph_stack_scratch_bytes", "morph_stack_tap_bytes",
-                        "morph_stack_fused_workspace_bytes", "morph_warmup_bytes", "morph_status_string"):
+                        "morph_stack_fused_workspace_bytes", "morph_warmup_bytes", "morph_status_string",
+                        "morph_probe_out_bytes", "morph_layer_record_bytes", "morph_noalloc_scratch_bytes"):
             getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -209,6 +214,19 @@ def linear_w4a16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int 
                                     _dev(y, torch.float16, "y"), M, K, N, group_size, wp, wb, _stream()),
            "morph_linear_w4a16")
     return y
+
+
+def linear_w4a16_noalloc(x, qweight, scales, qzeros, out, group_size: int = GROUP) -> torch.Tensor:
+    """morph_linear_w4a16 for decode sizes without a workspace: the library's own device array holds what
+    the kernel hands between workgroups.  `out` is required (this wrapper allocates nothing either)."""
+    M, K = x.shape
+    N = scales.shape[1]
+    assert qweight.shape == (K, N // 8), (qweight.shape, K, N)
+    _check(lib().morph_linear_w4a16_noalloc(_dev(x, torch.float16, "x"), _dev(qweight, torch.int32, "qweight"),
+                                            _dev(scales, torch.float16, "scales"), _dev(qzeros, torch.int32, "qzeros"),
+                                            _dev(out, torch.float16, "y"), M, K, N, group_size, _stream()),
+           "morph_linear_w4a16_noalloc")
+    return out
 
 
 def linear_w8a16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:

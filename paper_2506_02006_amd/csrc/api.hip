@@ -164,6 +164,58 @@ int morph_linear_fp16(const void* x, const void* w, void* y, int M, int K, int N
                       (hipStream_t)stream);
 }
 
+// ---- the decode-size 4-bit linear for callers that cannot allocate ----
+// Control words and hand-over slots of the kernel for at most 16 rows live in a file-scope device
+// array instead of a caller's workspace: kNoAllocCtlBytes of flags (any content is a valid start, see
+// decode_small.hip), then kNoAllocSlotBytes of partial sums.  Every device that loads the library
+// holds its own copy until the process ends.
+namespace {
+constexpr size_t kNoAllocCtlBytes  = (size_t)256 * kSmallCtlInts * sizeof(int);   // 256 column tiles
+constexpr size_t kNoAllocSlotBytes = (size_t)4 << 20;
+constexpr int    kNoAllocMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kNoAllocCtlBytes + kNoAllocSlotBytes];
+namespace {
+std::atomic<unsigned char*> g_scratch_ptr[kNoAllocMaxDevices];
+
+// The array's address on the current device: `scratch` itself is only the host's handle of the symbol.
+unsigned char* scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kNoAllocMaxDevices) return nullptr;
+    unsigned char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return nullptr;
+    g_scratch_ptr[dev].store(static_cast<unsigned char*>(sym), std::memory_order_release);
+    return static_cast<unsigned char*>(sym);
+}
+}  // namespace
+
+int morph_linear_w4a16_noalloc(const void* x, const int32_t* qweight, const void* scales, const int32_t* qzeros,
+                               void* y, int M, int K, int N, int group_size, void* stream)
+{
+    if (group_size != MORPH_GROUP_SIZE) return (x && qweight && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
+    if (int rc = validate_linear(MORPH_KIND_W4A16, x, qweight, scales, qzeros, y, M, K, N)) return rc;
+    if (M > 16) return MORPH_ERR_UNSUPPORTED;            // decode sizes only
+    const DecodePlan pl = plan_decode(MORPH_KIND_W4A16, M, K, N);
+    if (!pl.small) return MORPH_ERR_UNSUPPORTED;
+    if (pl.S > 1 && (pl.partial_bytes > kNoAllocSlotBytes || pl.tiles > 256)) return MORPH_ERR_UNSUPPORTED;   // beyond the array
+    SmallArgs s;
+    s.x = x; s.w = qweight; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
+    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = 0; s.bf = 0;
+    s.slots = nullptr; s.ctl = nullptr;
+    if (pl.S > 1) {
+        unsigned char* p = scratch_on_current_device();
+        if (!p) return MORPH_ERR_DEVICE;
+        s.ctl   = reinterpret_cast<int*>(p);
+        s.slots = reinterpret_cast<uint32_t*>(p + kNoAllocCtlBytes);
+    }
+    return launch_decode_small(s, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+size_t morph_noalloc_scratch_bytes(void) { return sizeof(scratch); }
+
 int morph_linear_w4a16(const void* x, const int32_t* qweight, const void* scales, const int32_t* qzeros,
                        void* y, int M, int K, int N, int group_size, void* workspace,
                        size_t workspace_bytes, void* stream)

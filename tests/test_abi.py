@@ -57,6 +57,19 @@ def test_linear_w4a16_validation(L):
     assert call(M=1, K=128 * 1024 * 64, N=1024) == 5
 
 
+def test_linear_w4a16_noalloc_validation(L):
+    """The allocation-free variant: same argument checks, decode sizes only, sizes beyond its array refused."""
+    f = L.morph_linear_w4a16_noalloc
+    def call(x=FAKE, q=FAKE, s=FAKE, z=FAKE, y=FAKE, M=4, K=256, N=64, g=128):
+        return f(x, q, s, z, y, M, K, N, g, None)
+    assert call(x=None) == 1 and call(q=None) == 1 and call(s=None) == 1 and call(z=None) == 1 and call(y=None) == 1
+    assert call(M=0) == 2 and call(K=200) == 2 and call(N=60) == 2 and call(g=64) == 2
+    assert call(x=FAKE + 8) == 3 and call(y=FAKE + 8) == 3
+    assert call(M=17) == 5 and call(M=512, K=4096, N=4096) == 5          # not a decode size
+    assert call(M=1, K=128 * 1024 * 64, N=1024) == 5                       # 4 GiB limit on a single array
+    assert 0 < L.morph_noalloc_scratch_bytes() <= 8 << 20
+
+
 def test_linear_fp16_validation(L):
     f = L.morph_linear_fp16
     assert f(None, FAKE, FAKE, 1, 128, 8, None, 0, None) == 1
