@@ -110,8 +110,8 @@ def test_config3_llama3_8b_heavy_tails(B, oracle, linear):
 
 
 def sample_positions(rng, M, N):
-    """Rows / columns on both sides of tile boundaries of the kernels (multiples of 128; every one
-    along M, a seeded subset along N), the first and last ones, plus seeded random positions."""
+    """A mesh of rows x columns on both sides of multiples of 128 (every one along M, a seeded subset
+    along N), the first and last ones, plus seeded random positions."""
     def edges(L, limit):
         bounds = np.arange(128, L, 128)
         if len(bounds) > limit:
@@ -126,8 +126,34 @@ def sample_positions(rng, M, N):
     return rr.ravel(), cc.ravel()
 
 
+def band_rows(rng, M, at_least=64):
+    """Row 0, row M - 1, both sides of every multiple of 256 (the row-tile boundaries of the widest tile),
+    and seeded random rows up to `at_least`."""
+    s = {0, M - 1}
+    for e in range(256, M, 256):
+        s.update((e - 1, e))
+    while len(s) < at_least:
+        s.add(int(rng.integers(0, M)))
+    return np.array(sorted(s))
+
+
+def band_cols(rng, N, at_least=64):
+    """Column 0, column N - 1, both sides of every multiple of 64 -- which covers the column-tile
+    boundaries of every tile width the planner can pick (128, 192, 256) -- and seeded random columns."""
+    s = {0, N - 1}
+    for e in range(64, N, 64):
+        s.update((e - 1, e))
+    while len(s) < at_least:
+        s.add(int(rng.integers(0, N)))
+    return np.array(sorted(s))
+
+
 @pytest.mark.parametrize("linear", synth.LINEAR_ORDER)
 def test_config4_llama13b_prefill(B, oracle, linear):
+    """Every 13B linear at M = 512 and 2048, both kinds, in the launch configuration bench.py times.
+    Checked against the oracle on two bands that together cross every tile of any plan: ALL columns
+    of at least 64 rows (first, last, both sides of every 256-row boundary, seeded others) and ALL
+    rows of the columns on both sides of every multiple of 64 (at least 64 of them)."""
     K, N = synth.LAYER_SHAPES["llama13b"][linear]
     W = synth.layer_weights(4, "llama13b", linear)
     rec = oracle.quantize_w4(W)
@@ -139,18 +165,30 @@ def test_config4_llama13b_prefill(B, oracle, linear):
     for M in (512, 2048):
         x = synth.activations(4, M, K, tensor_id=M)
         xd = dev(x)
-        rows, cols = sample_positions(rng, M, N)
+        rows, cols = band_rows(rng, M), band_cols(rng, N)
+        assert len(rows) >= 64 and len(cols) >= 64
         ws = B.new_workspace(max(B.workspace_bytes(B.KIND_W4A16, M, K, N), B.workspace_bytes(B.KIND_FP16, M, K, N)))
         y4 = host(B.linear_w4a16(xd, *rec_dev, ws))
         y16 = host(B.linear_fp16(xd, w16_dev, ws))
         assert np.isfinite(y4).all() and np.isfinite(y16).all()
-        ref4 = oracle.linear_w4a16_at(x, *rec, rows, cols)
-        ref16 = oracle.linear_fp16_at(x, w16, rows, cols)
-        e4 = oracle.error_metric(y4[rows, cols], ref4)
-        e16 = oracle.error_metric(y16[rows, cols], ref16)
-        say(f"  config4/{linear} M={M}: {rows.size} sampled outputs, w4a16 err={e4['err']:.3e} fp16 err={e16['err']:.3e}")
-        assert e4["err"] <= TOL and e16["err"] <= TOL
-        # properties that hold for every output: the two weight sets differ by the quantization
+        t0 = time.perf_counter()
+        # band 1: all columns of the chosen rows (the oracle's full product on those rows of x)
+        ref4_r = oracle.linear_w4a16(x[rows], *rec)
+        ref16_r = oracle.linear_fp16(x[rows], w16)
+        # band 2: all rows of the chosen columns
+        rr, cc = np.meshgrid(np.arange(M), cols, indexing="ij")
+        ref4_c = oracle.linear_w4a16_at(x, *rec, rr.ravel(), cc.ravel()).reshape(M, len(cols))
+        ref16_c = oracle.linear_fp16_at(x, w16, rr.ravel(), cc.ravel()).reshape(M, len(cols))
+        t_oracle = time.perf_counter() - t0
+        # one normalisation for both bands of a kind: the largest |y_ref| seen
+        for kind, y, ref_r, ref_c in (("w4a16", y4, ref4_r, ref4_c), ("fp16", y16, ref16_r, ref16_c)):
+            top = max(np.abs(ref_r).max(), np.abs(ref_c).max())
+            e_r = np.abs(y[rows].astype(np.float64) - ref_r).max() / top
+            e_c = np.abs(y[:, cols].astype(np.float64) - ref_c).max() / top
+            say(f"  config4/{linear} M={M} {kind}: {len(rows)} rows x {N} columns err={e_r:.3e}, "
+                f"{M} rows x {len(cols)} columns err={e_c:.3e} (oracle {t_oracle:.1f} s for both kinds)")
+            assert e_r <= TOL and e_c <= TOL, (linear, M, kind, e_r, e_c)
+        # a property that holds for every output: the two weight sets differ by the quantization
         # noise only, so the two results agree to a few percent of the output scale everywhere
         scale = np.abs(y16.astype(np.float32)).max()
         assert np.abs(y4.astype(np.float32) - y16.astype(np.float32)).max() <= 0.2 * scale
@@ -188,6 +226,36 @@ def test_llama13b_few_tiles_k_cut_into_parts(B, oracle, linear):
                 assert e4["err"] <= TOL and e16["err"] <= TOL
     finally:
         B.set_tuning(B.TUNE_DECODE_MAX_M, 0)
+
+
+def test_one_workspace_through_every_kernel_family(B, oracle):
+    """One workspace, sized for the largest need, handed to calls that take different kernel families
+    and different plans in turn -- LDS-tiled with K cut into parts (13B qkv, o, down at M = 256), the
+    streaming kernels at M = 48, the small-M kernel at M = 1 and 16 -- twice over, every output
+    against the oracle.  Counters, flags and partial sums of one call must not disturb the next."""
+    shapes = {n: synth.LAYER_SHAPES["llama13b"][n] for n in ("qkv", "o", "down")}
+    recs, xs = {}, {}
+    for n, (K, N) in shapes.items():
+        recs[n] = oracle.quantize_w4(synth.layer_weights(4, "llama13b", n))
+    Ms = (256, 48, 1, 16)
+    need = max(B.workspace_bytes(B.KIND_W4A16, M, K, N) for M in Ms for (K, N) in shapes.values())
+    assert need > 0
+    ws = B.new_workspace(need)
+    rng = np.random.default_rng([synth.BASE_SEED, 45])
+    dev_recs = {n: tuple(dev(a) for a in recs[n]) for n in shapes}
+    for rep in range(2):
+        for M in Ms:
+            for n, (K, N) in shapes.items():
+                x = synth.activations(4, M, K, tensor_id=1000 + M)
+                y = host(B.linear_w4a16(dev(x), *dev_recs[n], ws))
+                assert np.isfinite(y).all()
+                if M <= 48:
+                    e = oracle.error_metric(y, oracle.linear_w4a16(x, *recs[n]))["err"]
+                else:
+                    rows, cols = sample_positions(rng, M, N)
+                    e = oracle.error_metric(y[rows, cols], oracle.linear_w4a16_at(x, *recs[n], rows, cols))["err"]
+                say(f"  shared workspace, pass {rep}: {n} M={M}: err={e:.3e}")
+                assert e <= TOL, (rep, n, M, e)
 
 
 def oracle_linear(oracle, rec, x):
