@@ -1,6 +1,7 @@
 // The C ABI of include/morph.h: argument validation on the host, kernel selection by shape,
 // launches on the caller's stream.  Nothing here allocates, synchronises or remembers a pointer.
 #include "../../include/morph.h"
+#include "../../include/morph_bench.h"
 #include "kernels.h"
 
 #include <atomic>
@@ -730,7 +731,7 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     if ((rc = morph_quantize_layer(w, MORPH_DTYPE_F16, q, s, z, kWK, kWN, 128, stream))) return rc;
     if ((rc = morph_dequantize_w4(q, s, z, f, MORPH_DTYPE_F32, kWK, kWN, 128, stream))) return rc;
     if ((rc = morph_dequantize_w4(q, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
-    const int ms[] = {1, 17, 33, 49, kWM};
+    const int ms[] = {1, 4, 17, 33, 49, kWM};            // one-row and several-row small kernels, both slice heights, the tiled kernels
     for (int m : ms) {
         if ((rc = morph_linear_fp16(x, w, y, m, kWK, kWN, ws, wsb, stream))) return rc;
         if ((rc = morph_linear_w4a16(x, q, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;

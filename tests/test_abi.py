@@ -7,7 +7,10 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "morph.h")
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("morph.h", "morph_bench.h")]   # the serving interface; bench and test tooling
+
+
+FAKE = 0x7F0000001000          # non-null, 16-byte aligned, never dereferenced on these paths
 
 
 @pytest.fixture(scope="module")
@@ -18,10 +21,12 @@ def L():
     return binding.lib()
 
 
-def declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(morph_[a-z0-9_]+)\s*\(", text)))
+def declared_symbols(headers=HEADERS):
+    names = set()
+    for h in headers:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names.update(re.findall(r"\b(morph_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_exports_every_declared_symbol(L):
@@ -31,6 +36,26 @@ def test_exports_every_declared_symbol(L):
     for n in names:
         assert hasattr(L, n), n
     assert sorted(binding.EXPORTS) == names
+    # the tooling lives in its own header: the serving interface names no tuning knob and no probe
+    serving = declared_symbols(HEADERS[:1])
+    assert not [n for n in serving if "tuning" in n or "probe" in n or n == "morph_copy"]
+
+
+def test_workspace_sized_before_a_tuning_change_is_refused_not_overrun(L):
+    """morph_set_tuning is process-wide state that changes the plan, and with it the workspace a call
+    needs.  A workspace sized under the old plan must be refused (before any launch), not written past."""
+    M, K, N = 32, 4096, 4096
+    before = L.morph_workspace_bytes(1, M, K, N)
+    assert before > 0
+    try:
+        assert L.morph_set_tuning(0, 32) == 0                 # key 0: K split 32 ways instead of the plan's own
+        after = L.morph_workspace_bytes(1, M, K, N)
+        assert after > before
+        rc = L.morph_linear_w4a16(FAKE, FAKE, FAKE, FAKE, FAKE, M, K, N, 128, FAKE, before, None)
+        assert rc == 4                                        # MORPH_ERR_WORKSPACE; nothing was launched
+    finally:
+        assert L.morph_set_tuning(0, 0) == 0
+    assert L.morph_workspace_bytes(1, M, K, N) == before
 
 
 def test_status_strings(L):
@@ -38,7 +63,6 @@ def test_status_strings(L):
         assert isinstance(L.morph_status_string(s), bytes) and L.morph_status_string(s)
 
 
-FAKE = 0x7F0000001000          # non-null, 16-byte aligned, never dereferenced on these paths
 
 
 def test_linear_w4a16_validation(L):
