@@ -22,6 +22,8 @@ TUNE_DECODE_STREAM = 8
 TUNE_DECODE_SCATTER = 9
 TUNE_PREFILL_GRID = 10
 TUNE_PREFILL_STAGING = 11
+TUNE_SMALL = 12
+TUNE_SMALL_FAR = 13
 
 EXPORTS = [
     "morph_linear_fp16", "morph_linear_w4a16", "morph_quantize_layer", "morph_dequantize_w4",

@@ -377,7 +377,8 @@ static DecodePlan plan_small(int M, int K, int N)
     // uses more than half the registers and the LDS of one).
     int target = tuning_get(TUNE_DECODE_WGS);
     if (target <= 0) target = prefill_compute_units();
-    int S = target / pl.tiles;
+    const int slices = M > 32 ? 2 : 1;                   // slices of 32 rows, a workgroup each
+    int S = target / (pl.tiles * slices);
     if (S > T / 4) S = T / 4;                            // every workgroup keeps at least one quantization group
     if (S > 16) S = 16;
     const int forced = tuning_get(TUNE_DECODE_SPLIT);
@@ -385,8 +386,10 @@ static DecodePlan plan_small(int M, int K, int N)
     if (S > T / 4) S = T / 4;
     if (S < 1) S = 1;
     pl.S = S;
-    const size_t nvec = (size_t)256 * ((M + 3) / 4);     // vectors of four rows per tile
-    pl.partial_bytes = S > 1 ? (size_t)pl.tiles * S * nvec * 16 : 0;
+    // vectors of four rows per tile: up to 16 rows only the groups of four that exist, beyond whole tiles of 16 rows
+    const size_t nvec = M <= 16 ? (size_t)256 * ((M + 3) / 4) : (size_t)2048;
+    pl.slices = slices;
+    pl.partial_bytes = S > 1 ? (size_t)pl.tiles * slices * S * nvec * 16 : 0;
     pl.polls = tuning_get(TUNE_DECODE_SCATTER) == 3 ? 0 : 4096;   // 3: nobody looks, the last workgroup out adds everything up (test hook)
     pl.stream_loads = 1;
     pl.scatter = S > 1;
@@ -395,11 +398,12 @@ static DecodePlan plan_small(int M, int K, int N)
 
 DecodePlan plan_decode(int q, int M, int K, int N)
 {
-    if (q == 1 && M <= 16 && tuning_get(TUNE_SMALL) != 2) {
+    const int t = tuning_get(TUNE_DECODE_SLICE);        // a forced slice height means the general streaming kernels
+    const int small_rows = tuning_get(TUNE_SMALL) == 3 ? 16 : 64;       // 3: the register-tiled kernel only up to 16 rows
+    if (q == 1 && M <= small_rows && tuning_get(TUNE_SMALL) != 2 && t != 16 && t != 32) {
         const DecodePlan ps = plan_small(M, K, N);
-        if (ps.partial_bytes <= kSlotBytes && (ps.S == 1 || ps.tiles <= 256)) return ps;
+        if (ps.partial_bytes <= kSlotBytes && (ps.S == 1 || ps.tiles * ps.slices <= 256)) return ps;
     }
-    const int t = tuning_get(TUNE_DECODE_SLICE);
     if (t == 16 || t == 32) return plan_rows(q, M, K, N, t);
     if (M <= 16) return plan_rows(q, M, K, N, 16);
     const DecodePlan p32 = plan_rows(q, M, K, N, 32);

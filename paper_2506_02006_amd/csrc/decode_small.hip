@@ -1,27 +1,37 @@
-// W4A16 linears of at most 16 rows (the decode step proper): y[M,N] = x[M,K] * dequant(W4), bound
-// by the rate at which the packed codes leave HBM.  At these sizes a launch lasts a few
-// microseconds, of which the memory system needs one to deliver its first byte and every exchange
-// between workgroups through memory costs most of another, so the kernel is built around:
+// W4A16 linears of at most 64 rows (the decode step): y[M,N] = x[M,K] * dequant(W4), bound by the
+// rate at which the packed codes leave HBM.  At these sizes a launch lasts a few microseconds, of
+// which the memory system needs one to deliver its first byte and every exchange between workgroups
+// through memory costs most of another, so the kernel is built around:
 //   * a short head: the division of K over workgroups and waves is prepared on the host, and a wave
 //     reaches its first load after a few dozen instructions;
 //   * loads that run three k-steps (of 32 rows) ahead of their use through a ring of four register
 //     stages in a loop unrolled by four (= one quantization group); a wave takes whole groups, so
 //     the only loads that fall outside its range are the last three slots' (pushed past the buffer,
 //     they return zeros without memory traffic) and the compiler's wait counts are exact;
-//   * running results in registers, and a fold that touches only accumulator components whose
-//     rows exist (M = 1: one of four);
-//   * a hand-over between the workgroups that split K which stays inside one XCD's L2 whenever the
-//     workgroups of a column tile share an XCD (see the end of the kernel).
+//   * one workgroup takes up to 32 rows of its columns (MT tiles of 16), so that up to there every
+//     weight is read and unpacked once; beyond, two workgroups on the same XCD take a slice of 32 rows
+//     each and the second reading is served by that XCD's L2;
+//   * results in registers until the k loop is over;
+//   * a hand-over between the workgroups that split K which stays inside one XCD's L2 (see the end
+//     of the kernel).
 //
-// The multiply itself is the matrix-core scheme of the other streaming kernels: x as the A operand
-// of v_mfma_f32_16x16x32_f16 (rows beyond M read as zero), the codes as B without conversion -- a
-// 16-bit lane holding the byte 16 q_hi + q_lo IS that number times 2^-24 (fp16 subnormal), or times
-// 2^-133 read as bfloat16.  Per byte two MFMAs (whole byte; byte masked to its high nibble), one
-// more against a B of 2^-24 for the row sums of x; per group of 128 rows the sums are folded into
-// the running results:
-//     low-nibble column:   Y += s * (acc_byte - acc_high) - (s * z_lo) * xsum        (in units of 2^-24)
-//     high-nibble column:  Y += s *  acc_high             - (s * 16 z_hi) * xsum     (in units of 2^-20)
-// and the powers of two are taken out once, at the end.
+// The multiply runs on the matrix cores, v_mfma_f32_16x16x32_f16 / _bf16, x as the A operand (rows
+// beyond M read as zero), the weights as B.  B wants, per lane, 8 consecutive k of one column, while a
+// packed word holds 8 consecutive columns of one k: a lane loads the same two words from 8
+// consecutive rows and pairs bytes across rows (v_perm_b32).  The codes then enter the MFMA without
+// conversion -- a 16-bit lane holding the byte 16 q_hi + q_lo IS that number times 2^-24 (fp16
+// subnormal), or times 2^-133 read as bfloat16.  Per byte two MFMAs per tile of rows (whole byte; byte
+// masked to its high nibble), one more against a B of 2^-24 for the row sums of x; per group of 128
+// rows the sums are folded into running results:
+//     low-nibble column:   Y += s * (acc_byte - acc_high) - (s * z_lo) * xsum     (in units of 2^-24)
+//     high-nibble column:  Y += s *  acc_high             - (s * 16 z_hi) * xsum  (in units of 2^-20)
+// and the powers of two are taken out once, at the end.  With one row the fold touches only the one
+// accumulator component that holds it (RL = 1).  One wave has a SIMD to itself, so the loop is bound
+// by the number of instructions it issues (a vector instruction every 4.5 clocks, measured; an MFMA
+// adds 8 and runs beside them): unpacking costs two vector instructions per four weights and the
+// fold five per result and group, against nine per four weights for dequantizing them first.
+#include <type_traits>
+
 #include "dev_common.h"
 #include "kernels.h"
 #include "ticks.h"
@@ -34,9 +44,10 @@ constexpr int kSmWaves = 4;
 constexpr int kRing    = 4;                      // register stages = slots of the unrolled loop (one quantization group)
 constexpr int kAhead   = 3;                      // k-steps a load runs ahead of its use
 
+template <int MT>
 struct SmallStage {
     u32x2   w[8];                                // row 8b + i of the k-step: two packed words = 16 columns
-    half8_t a;                                   // x row (lane & 15), 8 consecutive k
+    half8_t a[MT];                               // x rows 16 mt + (lane & 15), 8 consecutive k
 };
 struct SmallGroup {
     u32x2 zq;                                    // zero points of the lane's 16 columns
@@ -54,8 +65,9 @@ struct SmallTail {
     uint32_t* slots;                             // [tile][split][vector] f32x4 partial sums (no content between launches)
     int*      ctl;                               // kCtlInts per tile
     int       polls;                             // looks at the flags before a workgroup stops waiting
-    int       nb;                                // groups of four rows that exist: ceil(M / 4)
+    int       nb;                                // MT = 1: groups of four rows that exist, ceil(M / 4)
     int       tiles;                             // column tiles of 256
+    int       sl_shift;                          // 0: one slice of rows; 1: two slices of 32 rows, workgroups (tile, slice, split)
     int       far;                               // write the hand-over through to memory instead of leaving it in the L2
     int       inv_s;                             // ceil(65536 / S): j / S = (j * inv_s) >> 16 for the j that occur
 };
@@ -84,14 +96,15 @@ __device__ __forceinline__ half8_t bf16x8_up64(half8_t v)
 // the value of the first look for all later ones.
 __device__ __forceinline__ void reload_fence() { asm volatile("" ::: "memory"); }
 
-// RL: accumulator components per lane that hold rows which exist (1: M = 1; 4 otherwise).
-// BF: x and y are bfloat16.
-template <int RL, bool BF>
+// MT: tiles of 16 rows one workgroup takes (1 or 2).  RL (MT = 1 only): accumulator components per lane
+// that hold rows which exist (1: M = 1; 4 otherwise).  BF: x and y are bfloat16.
+template <int MT, int RL, bool BF>
 __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
-    const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int M, int S,
+    const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int M_all, int S,
     int q_groups, int r_groups, SmallTail t)
 {
-    __shared__ __align__(16) f32x4 yl[kSmWaves * 16 * 64];     // [wave][column j of the lane][lane]
+    // one tile of 16 rows at a time: [wave][lane][column j of the lane, stored at j ^ (lane & 15)]
+    __shared__ __align__(16) f32x4 yl[kSmWaves * 64 * 16];
     __shared__ uint32_t fresh_word;
 
     MORPH_TICK(0);                                       // kernel entry
@@ -100,14 +113,19 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     const int c = lane & 15, b = lane >> 4;
     // Workgroup L runs on XCD L % 8 (workgroups are dealt to the XCDs in turn).  The S workgroups of a
     // column tile are given the same L % 8, so that they meet in one L2: within XCD `xcd` the
-    // workgroups j = L / 8 walk (tile slot, split), tile = 8 * slot + xcd.  Tiles that do not exist
-    // (the last slot of an XCD when the tile count is no multiple of 8) leave at once.
+    // workgroups j = L / 8 walk (tile slot, slice of rows, split), tile = 8 * slot + xcd.  Tiles that do
+    // not exist (the last slot of an XCD when the tile count is no multiple of 8) leave at once.
     const int L = blockIdx.x, xcd = L & 7, jj = L >> 3;
-    const int slot = (jj * t.inv_s) >> 16, sp = jj - slot * S;
+    const int pair = (jj * t.inv_s) >> 16, sp = jj - pair * S;
+    const int slot = pair >> t.sl_shift, slice = pair - (slot << t.sl_shift);
     const int tile = slot * 8 + xcd;
     if (tile >= t.tiles) return;
+    const int unit = (tile << t.sl_shift) + slice;       // who shares flags and slots: the splits of one (tile, slice)
     const int n0 = tile * 256;
     const int NW = N >> 3;
+    // this workgroup's rows: a slice is 32 rows
+    const int M = M_all - 32 * slice < 16 * MT ? M_all - 32 * slice : 16 * MT;
+    const uint16_t* x = (const uint16_t*)x_all + (size_t)(32 * slice) * K;
 
     const uint32_t row_bytes = (uint32_t)NW * 4u;
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
@@ -115,7 +133,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
     const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
     // without a split there is no control block and no slot (null pointers): a range of zero makes every access fall outside
-    const __amdgpu_buffer_rsrc_t rc = make_rsrc(S > 1 ? t.ctl + (size_t)tile * kCtlInts : nullptr, S > 1 ? kCtlInts * 4u : 0u);
+    const __amdgpu_buffer_rsrc_t rc = make_rsrc(S > 1 ? t.ctl + (size_t)unit * kCtlInts : nullptr, S > 1 ? kCtlInts * 4u : 0u);
 
     const int  ncol   = n0 + 16 * c;                     // this lane's first column
     const bool col_ok = ncol < N;
@@ -123,22 +141,24 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + (uint32_t)ncol / 2u : kOut;
     const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
     const uint32_t voff_z = col_ok ? (uint32_t)ncol / 2u : kOut;
-    const uint32_t voff_a = ((uint32_t)c * (uint32_t)K + 8u * b) * 2u;
+    const uint32_t voff_a = ((uint32_t)c * (uint32_t)K + 8u * b) * 2u;     // row c; tile mt of the rows lies 16 rows further on
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
     // The k loop runs for one split at a time: normally once, for this workgroup's own split; see the
     // hand-over below for when it runs again.  begin_pass() fixes the range and requests its first loads.
     int      ga = 0, gz = 0, ks1 = 0;
-    SmallStage st[kRing];
+    SmallStage<MT> st[kRing];
     SmallGroup gcur, gnxt;
-    auto load_stage = [&](SmallStage& sg, int ks) {
+    auto load_stage = [&](SmallStage<MT>& sg, int ks) {
         const bool     dead = ks >= ks1;
         const uint32_t dm   = dead ? kOut : 0u;
         const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
         const uint32_t vw   = voff_w | dm;
 #pragma unroll
         for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32x2<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
-        sg.a = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, voff_a | dm, dead ? 0u : (uint32_t)ks * 64u, 0));
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)                  // rows at or beyond M lie past the buffer
+            sg.a[mt] = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, (voff_a + (uint32_t)mt * 32u * (uint32_t)K) | dm, dead ? 0u : (uint32_t)ks * 64u, 0));
     };
     auto load_group = [&](SmallGroup& gr, int g) {
         const bool     dead = g >= gz;
@@ -173,21 +193,25 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     __builtin_amdgcn_sched_barrier(0);
     MORPH_TICK(1);                                       // first loads issued
 
-    // A vector = four rows (4 b .. 4 b + 3) of one column; the tile has 256 nb of them, numbered
-    // id = j * 16 nb + lane (lanes 0 .. 16 nb - 1 are the ones whose rows exist).
-    const int nb = t.nb;                                 // groups of four rows that exist
-    const int lanes = 16 * nb, nvec = 16 * lanes;
-    auto vec_sum = [&](int id) {                         // over the waves, in the order of their k ranges
-        const int j = id / lanes, ln = id - j * lanes;
-        f32x4 a = yl[j * 64 + ln];
+    // A vector = four rows of one column.  Vector (mt, ln, j): column n0 + 16 (ln & 15) + j, rows
+    // 16 mt + 4 (ln >> 4) ..; its number is id = mt * per_tile + 16 ln + j, so that 256 consecutive
+    // numbers are 256 consecutive columns.  With one tile of rows only lanes 0 .. 16 nb - 1 hold rows
+    // that exist, and only their vectors are numbered.
+    const int lanes = MT == 1 ? 16 * t.nb : 64;          // lanes that hold rows
+    const int per_tile = 16 * lanes;                     // vectors of one tile of 16 rows
+    const int nvec = MT * per_tile;
+    auto vec_sum = [&](int lid) {                        // vector lid of the tile now in LDS, over the waves in the order of their k ranges
+        const int ln = lid >> 4, j = (lid ^ ln) & 15;
+        f32x4 a = yl[ln * 16 + j];
 #pragma unroll
-        for (int q = 1; q < kSmWaves; q++) a += yl[(q * 16 + j) * 64 + ln];
+        for (int q = 1; q < kSmWaves; q++) a += yl[(q * 64 + ln) * 16 + j];
         return a;
     };
-    uint16_t* y = (uint16_t*)t.y;
+    uint16_t* y = (uint16_t*)t.y + (size_t)(32 * slice) * N;
     auto vec_store_y = [&](int id, f32x4 acc) {
-        const int j = id / lanes, ln = id - j * lanes;
-        const int col = n0 + 16 * (ln & 15) + j, row = 4 * (ln >> 4);
+        const int mt = MT == 1 ? 0 : id >> 10, lid = MT == 1 ? id : id & 1023;
+        const int ln = lid >> 4, j = lid & 15;
+        const int col = n0 + 16 * (ln & 15) + j, row = 16 * mt + 4 * (ln >> 4);
         if (col < N) {
 #pragma unroll
             for (int r = 0; r < 4; r++)
@@ -195,71 +219,25 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
         }
     };
     const uint32_t slot_bytes = (uint32_t)nvec * 16u;
-    const __amdgpu_buffer_rsrc_t rp = make_rsrc(S > 1 ? t.slots + (size_t)tile * S * nvec * 4 : nullptr, S > 1 ? (uint32_t)S * slot_bytes : 0u);
-    const int v0 = (sp * nvec) / S, v1 = ((sp + 1) * nvec) / S;   // my share of the tile's vectors: at most two per thread
+    const __amdgpu_buffer_rsrc_t rp = make_rsrc(S > 1 ? t.slots + (size_t)unit * S * nvec * 4 : nullptr, S > 1 ? (uint32_t)S * slot_bytes : 0u);
+    const int v0 = (sp * nvec) / S, v1 = ((sp + 1) * nvec) / S;   // my share of the tile's vectors
 
-    // gacc[2 yb + 8 t]: sum of x * byte, gacc[.. + 1]: sum of x * (byte & 0xF0), over the open group
-    auto compute = [&](const SmallStage& sg, bool first, f32x4 (&gacc)[16], f32x4& xs) {
-        half8_t xa;
-        if constexpr (BF) xa = bf16x8_up64(sg.a);
-        else xa = sg.a;
-        const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
-        xs = mfma_small<BF>(xa, tiny, first ? zero4 : xs);
+    // The k loop of the split begin_pass() was called for, then `sink(id, sum over the waves)` for every
+    // vector of the tile, one tile of 16 rows at a time through LDS.
+    auto run_pass = [&](auto&& sink) {
+        // gacc[mt][2 yb + 8 t]: sum of x * byte, gacc[mt][.. + 1]: sum of x * (byte & 0xF0), over the open group
+        f32x4 gacc[MT][16], xs[MT];
+        float yr[MT][16][RL];                            // running results, column j of the lane, row 16 mt + 4 b + r
 #pragma unroll
-        for (int t2 = 0; t2 < 2; t2++) {
+        for (int mt = 0; mt < MT; mt++) {
 #pragma unroll
-            for (int yb = 0; yb < 4; yb++) {
-                uint32_t pr[4], ph[4];
+            for (int j = 0; j < 16; j++) {
+                gacc[mt][j] = zero4;
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
-                    const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
-                    pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
-                          : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
-                    ph[q] = pr[q] & 0x00F000F0u;
-                }
-                const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
-                const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
-                const int j0 = t2 * 8 + 2 * yb;
-                gacc[j0]     = mfma_small<BF>(xa, bbyte, first ? zero4 : gacc[j0]);
-                gacc[j0 + 1] = mfma_small<BF>(xa, bhigh, first ? zero4 : gacc[j0 + 1]);
+                for (int r = 0; r < RL; r++) yr[mt][j][r] = 0.f;
             }
+            xs[mt] = zero4;
         }
-    };
-    // the group's sums go into the running results yr[column j of the lane][row 4 b + r]
-    auto fold = [&](const SmallGroup& gr, const f32x4 (&gacc)[16], const f32x4& xs, float (&yr)[16][RL]) {
-#pragma unroll
-        for (int t2 = 0; t2 < 2; t2++) {
-            const uint32_t zw  = gr.zq[t2];
-            const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;     // z of the even columns; 16 z of the odd ones
-#pragma unroll
-            for (int yb = 0; yb < 4; yb++) {
-                const uint32_t sw = gr.sc[t2][yb];
-                const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
-                const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
-                const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
-                const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
-                const int j0 = t2 * 8 + 2 * yb;
-#pragma unroll
-                for (int r = 0; r < RL; r++) {
-                    const float d = gacc[j0][r] - gacc[j0 + 1][r];
-                    yr[j0][r]     = __builtin_fmaf(-c_lo, xs[r], __builtin_fmaf(s_lo, d, yr[j0][r]));
-                    yr[j0 + 1][r] = __builtin_fmaf(-c_hi, xs[r], __builtin_fmaf(s_hi, gacc[j0 + 1][r], yr[j0 + 1][r]));
-                }
-            }
-        }
-    };
-    // The k loop of the split begin_pass() was called for; every wave leaves its sums in LDS (the powers
-    // of two taken out) and the workgroup meets at a barrier.
-    auto run_pass = [&]() {
-        f32x4 gacc[16], xs;
-        float yr[16][RL];
-#pragma unroll
-        for (int j = 0; j < 16; j++) {
-            gacc[j] = zero4;
-#pragma unroll
-            for (int r = 0; r < RL; r++) yr[j][r] = 0.f;
-        }
-        xs = zero4;
         for (int g = ga; g < gz; g++) {
             gcur = gnxt;
 #pragma unroll
@@ -267,41 +245,98 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
                 load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
                 if (u == 1) load_group(gnxt, g + 1);     // arrives well before the next group ends
                 __builtin_amdgcn_sched_barrier(0);
-                compute(st[u], u == 0, gacc, xs);
+                const SmallStage<MT>& sg = st[u];
+                const bool first = u == 0;
+                half8_t xa[MT];
+                const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) {
+                    if constexpr (BF) xa[mt] = bf16x8_up64(sg.a[mt]);
+                    else xa[mt] = sg.a[mt];
+                    xs[mt] = mfma_small<BF>(xa[mt], tiny, first ? zero4 : xs[mt]);
+                }
+#pragma unroll
+                for (int t2 = 0; t2 < 2; t2++) {
+#pragma unroll
+                    for (int yb = 0; yb < 4; yb++) {
+                        uint32_t pr[4], ph[4];
+#pragma unroll
+                        for (int q = 0; q < 4; q++) {
+                            const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
+                            pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                                  : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                            ph[q] = pr[q] & 0x00F000F0u;
+                        }
+                        const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
+                        const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
+                        const int j0 = t2 * 8 + 2 * yb;
+#pragma unroll
+                        for (int mt = 0; mt < MT; mt++) {
+                            gacc[mt][j0]     = mfma_small<BF>(xa[mt], bbyte, first ? zero4 : gacc[mt][j0]);
+                            gacc[mt][j0 + 1] = mfma_small<BF>(xa[mt], bhigh, first ? zero4 : gacc[mt][j0 + 1]);
+                        }
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            fold(gcur, gacc, xs, yr);
-        }
-        constexpr float kEven = BF ? 0x1p69f : 0x1p24f;  // low-nibble (even) columns
-        constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;  // high-nibble (odd) columns: their sums carry a factor 16
-        if (b < nb) {
+            // the group's sums go into the running results
 #pragma unroll
-            for (int j = 0; j < 16; j++) {
-                f32x4 v = zero4;
+            for (int t2 = 0; t2 < 2; t2++) {
+                const uint32_t zw  = gcur.zq[t2];
+                const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;     // z of the even columns; 16 z of the odd ones
 #pragma unroll
-                for (int r = 0; r < RL; r++) v[r] = yr[j][r] * ((j & 1) ? kOdd : kEven);
-                yl[(wave * 16 + j) * 64 + lane] = v;
+                for (int yb = 0; yb < 4; yb++) {
+                    const uint32_t sw = gcur.sc[t2][yb];
+                    const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+                    const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+                    const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
+                    const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
+                    const int j0 = t2 * 8 + 2 * yb;
+#pragma unroll
+                    for (int mt = 0; mt < MT; mt++) {
+#pragma unroll
+                        for (int r = 0; r < RL; r++) {
+                            const float d = gacc[mt][j0][r] - gacc[mt][j0 + 1][r];
+                            yr[mt][j0][r]     = __builtin_fmaf(-c_lo, xs[mt][r], __builtin_fmaf(s_lo, d, yr[mt][j0][r]));
+                            yr[mt][j0 + 1][r] = __builtin_fmaf(-c_hi, xs[mt][r], __builtin_fmaf(s_hi, gacc[mt][j0 + 1][r], yr[mt][j0 + 1][r]));
+                        }
+                    }
+                }
             }
         }
-        __syncthreads();
+        // the powers of two come out; every wave leaves its sums in LDS, one tile of 16 rows at a time
+        constexpr float kEven = BF ? 0x1p69f : 0x1p24f;  // low-nibble (even) columns
+        constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;  // high-nibble (odd) columns: their sums carry a factor 16
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            if (mt > 0) __syncthreads();                 // the tile before has been read
+            if (MT > 1 || b < t.nb) {
+#pragma unroll
+                for (int j = 0; j < 16; j++) {
+                    f32x4 v = zero4;
+#pragma unroll
+                    for (int r = 0; r < RL; r++) v[r] = yr[mt][j][r] * ((j & 1) ? kOdd : kEven);
+                    yl[(wave * 64 + lane) * 16 + (j ^ c)] = v;
+                }
+            }
+            __syncthreads();
+            for (int lid = tid; lid < per_tile; lid += kSmWaves * 64) sink(mt * per_tile + lid, vec_sum(lid));
+        }
     };
 
-    run_pass();
-    MORPH_TICK(3);                                       // all waves done
     if (S == 1) {
-        for (int id = tid; id < nvec; id += kSmWaves * 64) vec_store_y(id, vec_sum(id));
+        run_pass([&](int id, f32x4 v) { vec_store_y(id, v); });
         return;
     }
 
     // ---- hand-over between the S workgroups of a column tile ----
-    // Every workgroup puts its partial vectors into its slot -- except those of its own share,
-    // vectors [v0, v1), which stay with it -- waits for the stores to be acknowledged and raises its
-    // flag's counter by one.  Then it polls the S flags of the tile (one load per look), and when every
-    // counter differs from what it was when this workgroup started, it adds its share up over the
-    // splits, in split order, and stores y.  No arrival count, no atomic, nothing to put back: a
-    // counter can only have changed during this launch, after its owner's partial sums were in place.
-    // (A workgroup that starts so late that a flag was raised before it looked sees no change, and
-    // goes the slow way below.)
+    // Every workgroup puts its partial vectors into its slot, waits for the stores to be acknowledged
+    // and raises its flag's counter by one.  Then it polls the S flags of the tile (one load per look),
+    // and when every counter differs from what it was when this workgroup started, it adds its share
+    // of the vectors, [v0, v1), up over the splits, in split order, and stores y.  No arrival count, no
+    // atomic, nothing to put back: a counter can only have changed during this launch, after its
+    // owner's partial sums were in place.  (A workgroup that starts so late that a flag was raised
+    // before it looked sees no change, and goes the slow way below.)
     //   Where the data travels: the workgroups of a tile are placed on one XCD (see the top), so the
     // stores are plain -- sums and flag stay in that XCD's L2, where the scoped loads of the others find
     // them without a trip to memory -- and the flag says which XCD that is.  A reader that finds
@@ -310,23 +345,20 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     // With t.far the stores are written through to memory and the flag says so.
     //   Correctness does not rest on the others: the wait is bounded, and a workgroup that stops
     // waiting works out the missing partial sums of its share itself -- it runs the k loop again for
-    // every split whose flag did not move.  Whoever adds a vector up, and wherever the terms come
-    // from, they are the same numbers added in split order.
+    // every split whose flag did not move, and puts that split's vectors of its share where the
+    // split's owner puts them (the same numbers from the same instructions: if both write, they
+    // write the same bits).  Whoever adds a vector up, and wherever the terms come from, they are
+    // added in split order.
     uint32_t my_xcc;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(my_xcc));
     const uint32_t where = t.far ? 0u : (my_xcc & 0xFu) + 1u;
-    f32x4 keep[2];                                       // my own partial sums of my share
-    for (int i = 0; i < 2; i++) {
-        const int id = v0 + tid + i * kSmWaves * 64;
-        keep[i] = id < v1 ? vec_sum(id) : zero4;
-    }
-    for (int id = tid; id < nvec; id += kSmWaves * 64) {
-        if (id >= v0 && id < v1) continue;               // my share stays here
-        const u32x4 v = bit_cast<u32x4>(vec_sum(id));
-        const uint32_t off = (uint32_t)sp * slot_bytes + (uint32_t)id * 16u;
-        if (where) __builtin_amdgcn_raw_buffer_store_b128(v, rp, off, 0, 0);
-        else __builtin_amdgcn_raw_buffer_store_b128(v, rp, off, 0, kAuxSystemScope);
-    }
+    auto put = [&](int split, int id, f32x4 v) {
+        const uint32_t off = (uint32_t)split * slot_bytes + (uint32_t)id * 16u;
+        if (where) __builtin_amdgcn_raw_buffer_store_b128(bit_cast<u32x4>(v), rp, off, 0, 0);
+        else __builtin_amdgcn_raw_buffer_store_b128(bit_cast<u32x4>(v), rp, off, 0, kAuxSystemScope);
+    };
+    run_pass([&](int id, f32x4 v) { put(sp, id, v); });
+    MORPH_TICK(3);                                       // all waves done, partial sums on their way
     wait_stores();
     __syncthreads();
     MORPH_TICK(4);                                       // partials in place
@@ -351,62 +383,62 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     __syncthreads();
     const uint32_t fresh = fresh_word;                   // splits whose partial sums are in their slots, readable from here
     MORPH_TICK(5);                                       // all flags seen (or no longer waited for)
-    if (fresh == want) {                                 // the usual way out
-        for (int i = 0; i < 2; i++) {
-            const int id = v0 + tid + i * kSmWaves * 64;
-            if (id >= v1) break;
-            u32x4 v[16];
+
+    // ---- the slow way, for every split that is not there: worked out here ----
+    if (fresh != want) {
+        for (int q = 0; q < S; q++) {
+            if ((fresh >> q) & 1) continue;
+            __syncthreads();                             // everyone is done with the sums in LDS
+            begin_pass(q);
+            run_pass([&](int id, f32x4 v) { if (id >= v0 && id < v1) put(q, id, v); });
+        }
+        wait_stores();
+        __syncthreads();
+    }
+
+    // ---- my share: every vector summed over the splits in split order ----
+    auto gather = [&](auto width) {
+        constexpr int W = decltype(width)::value;        // S <= W; splits beyond S lie past the buffer and read as zeros
+        for (int id = v0 + tid; id < v1; id += kSmWaves * 64) {
+            u32x4 v[W];
             reload_fence();
 #pragma unroll
-            for (int q = 0; q < 16; q++) {               // splits beyond S lie past the buffer and read as zeros
-                const uint32_t off = (q < S && q != sp) ? (uint32_t)q * slot_bytes + (uint32_t)id * 16u : 0xFFFFFFF0u;
+            for (int q = 0; q < W; q++) {
+                const uint32_t off = q < S ? (uint32_t)q * slot_bytes + (uint32_t)id * 16u : 0xFFFFFFF0u;
                 v[q] = __builtin_amdgcn_raw_buffer_load_b128(rp, off, 0, kAuxSystemScope);
             }
             f32x4 acc = zero4;
 #pragma unroll
-            for (int q = 0; q < 16; q++)
-                if (q < S) acc += (q == sp) ? keep[i] : bit_cast<f32x4>(v[q]);
+            for (int q = 0; q < W; q++)
+                if (q < S) acc += bit_cast<f32x4>(v[q]);
             vec_store_y(id, acc);
         }
-        MORPH_TICK(6);                                   // own share stored
-        return;
-    }
-
-    // ---- the slow way: the splits in order, each taken from its slot if it is there, worked out here if not ----
-    f32x4 total[2] = {zero4, zero4};
-    for (int q = 0; q < S; q++) {
-        if (q != sp && !((fresh >> q) & 1)) {
-            __syncthreads();                             // everyone is done reading the sums in LDS
-            begin_pass(q);
-            run_pass();
-        }
-        for (int i = 0; i < 2; i++) {
-            const int id = v0 + tid + i * kSmWaves * 64;
-            if (id >= v1) break;
-            if (q == sp) total[i] += keep[i];
-            else if ((fresh >> q) & 1) {
-                reload_fence();
-                total[i] += bit_cast<f32x4>(__builtin_amdgcn_raw_buffer_load_b128(rp, (uint32_t)q * slot_bytes + (uint32_t)id * 16u, 0, kAuxSystemScope));
-            } else total[i] += vec_sum(id);
-        }
-    }
-    for (int i = 0; i < 2; i++) {
-        const int id = v0 + tid + i * kSmWaves * 64;
-        if (id < v1) vec_store_y(id, total[i]);
-    }
+    };
+    if (S <= 4) gather(std::integral_constant<int, 4>{});
+    else gather(std::integral_constant<int, 16>{});
+    MORPH_TICK(6);                                       // own share stored
 }
 
-template <int RL, bool BF>
+template <int MT, int RL, bool BF>
 hipError_t launch_small_t(const SmallArgs& a, hipStream_t st)
 {
     const int G = a.K / kGroup;
     SmallTail t;
     t.y = a.y; t.slots = a.slots; t.ctl = a.ctl; t.polls = a.polls; t.nb = (a.M + 3) / 4;
     t.tiles = a.tiles; t.far = a.far; t.inv_s = (65536 + a.S - 1) / a.S;
-    const int grid = 8 * ((a.tiles + 7) / 8) * a.S;
-    hipLaunchKernelGGL((decode_small_kernel<RL, BF>), dim3(grid), dim3(kSmWaves * 64), 0, st,
+    t.sl_shift = a.M > 32 ? 1 : 0;
+    const int grid = 8 * ((a.tiles + 7) / 8) * a.S << t.sl_shift;
+    hipLaunchKernelGGL((decode_small_kernel<MT, RL, BF>), dim3(grid), dim3(kSmWaves * 64), 0, st,
                        (const uint32_t*)a.w, a.x, a.scales, (const uint32_t*)a.qzeros, a.K, a.N, a.M, a.S, G / a.S, G % a.S, t);
     return hipGetLastError();
+}
+
+template <bool BF>
+hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
+{
+    if (a.M == 1)  return launch_small_t<1, 1, BF>(a, st);
+    if (a.M <= 16) return launch_small_t<1, 4, BF>(a, st);
+    return launch_small_t<2, 4, BF>(a, st);              // beyond 32 rows: two slices
 }
 
 }  // namespace
@@ -415,10 +447,9 @@ MORPH_TICK_EXPORTS(small_ticks)
 
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
 {
-    if (a.M < 1 || a.M > 16 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1) return hipErrorInvalidValue;
-    if (a.S > 1 && a.tiles > 256) return hipErrorInvalidValue;
-    if (a.M == 1) return a.bf ? launch_small_t<1, true>(a, st) : launch_small_t<1, false>(a, st);
-    return a.bf ? launch_small_t<4, true>(a, st) : launch_small_t<4, false>(a, st);
+    if (a.M < 1 || a.M > 64 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1) return hipErrorInvalidValue;
+    if (a.S > 1 && a.tiles * (a.M > 32 ? 2 : 1) > 256) return hipErrorInvalidValue;     // flags for 256 (tile, slice) pairs
+    return a.bf ? launch_small_m<true>(a, st) : launch_small_m<false>(a, st);
 }
 
 }  // namespace morph

@@ -109,4 +109,19 @@ __device__ __forceinline__ uint16_t narrow16(float f)
     else return bit_cast<uint16_t>((half_t)f);
 }
 
+// two fp32 values rounded (to nearest even) into the two bfloat16 halves of a word
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float  f32x2_t  __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return bit_cast<uint32_t>(__builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
+}
+// The two fp16 halves of d, each times the fp32 scale s (exact in fp32), rounded into the two bfloat16
+// halves of a word.  Written as fused multiply-adds with a zero addend so that the fp16 operand is
+// widened inside the instruction (v_fma_mix_f32) instead of by a conversion of its own.
+__device__ __forceinline__ uint32_t scale_to_bf16x2(half2_t d, float s)
+{
+    return pack_bf16x2(__builtin_fmaf((float)d[0], s, 0.0f), __builtin_fmaf((float)d[1], s, 0.0f));
+}
+
 }  // namespace morph

@@ -52,7 +52,7 @@ struct DecodePlan {
 //   [kCounterBytes, kScratchOffset)    hand-over slots of decode_small.hip, no content between launches
 //   [kScratchOffset, ...)              partial sums of the other kernels, no content between launches
 constexpr size_t kCounterBytes  = (size_t)1 << 20;
-constexpr size_t kSlotBytes     = (size_t)8 << 20;
+constexpr size_t kSlotBytes     = (size_t)16 << 20;
 constexpr size_t kScratchOffset = kCounterBytes + kSlotBytes;
 // Inside the counters: the streaming kernels' plain arrival counters are ints [0, kPlainCounters), their
 // polled pairs follow 32 ints apart; the departure counters of decode_small.hip start at int kDepartBase

@@ -45,6 +45,7 @@ def test_workspace_sized_before_a_tuning_change_is_refused_not_overrun(L):
     """morph_set_tuning is process-wide state that changes the plan, and with it the workspace a call
     needs.  A workspace sized under the old plan must be refused (before any launch), not written past."""
     M, K, N = 32, 4096, 4096
+    assert L.morph_set_tuning(12, 2) == 0                     # key 12: the general streaming kernels, whose workspace grows with the split
     before = L.morph_workspace_bytes(1, M, K, N)
     assert before > 0
     try:
@@ -56,6 +57,7 @@ def test_workspace_sized_before_a_tuning_change_is_refused_not_overrun(L):
     finally:
         assert L.morph_set_tuning(0, 0) == 0
     assert L.morph_workspace_bytes(1, M, K, N) == before
+    assert L.morph_set_tuning(12, 0) == 0
 
 
 def test_status_strings(L):
