@@ -18,18 +18,22 @@
 // The multiply runs on the matrix cores, v_mfma_f32_16x16x32_f16 / _bf16, x as the A operand (rows
 // beyond M read as zero), the weights as B.  B wants, per lane, 8 consecutive k of one column, while a
 // packed word holds 8 consecutive columns of one k: a lane loads the same two words from 8
-// consecutive rows and pairs bytes across rows (v_perm_b32).  The codes then enter the MFMA without
-// conversion -- a 16-bit lane holding the byte 16 q_hi + q_lo IS that number times 2^-24 (fp16
-// subnormal), or times 2^-133 read as bfloat16.  Per byte two MFMAs per tile of rows (whole byte; byte
-// masked to its high nibble), one more against a B of 2^-24 for the row sums of x; per group of 128
-// rows the sums are folded into running results:
-//     low-nibble column:   Y += s * (acc_byte - acc_high) - (s * z_lo) * xsum     (in units of 2^-24)
-//     high-nibble column:  Y += s *  acc_high             - (s * 16 z_hi) * xsum  (in units of 2^-20)
-// and the powers of two are taken out once, at the end.  With one row the fold touches only the one
-// accumulator component that holds it (RL = 1).  One wave has a SIMD to itself, so the loop is bound
-// by the number of instructions it issues (a vector instruction every 4.5 clocks, measured; an MFMA
-// adds 8 and runs beside them): unpacking costs two vector instructions per four weights and the
-// fold five per result and group, against nine per four weights for dequantizing them first.
+// consecutive rows and pairs bytes across rows (v_perm_b32).  From there two schemes:
+//   MT = 1 (M <= 16): the codes enter the MFMA without conversion -- a 16-bit lane holding the byte
+//     16 q_hi + q_lo IS that number times 2^-24 (fp16 subnormal), or times 2^-133 read as bfloat16.
+//     Per byte two MFMAs (whole byte; byte masked to its high nibble), one more against a B of 2^-24
+//     for the row sums of x; per group of 128 rows the sums are folded into running results:
+//         low-nibble column:   Y += s * (acc_byte - acc_high) - (s * z_lo) * xsum     (in units of 2^-24)
+//         high-nibble column:  Y += s *  acc_high             - (s * 16 z_hi) * xsum  (in units of 2^-20)
+//     and the powers of two are taken out once, at the end.  With one row the fold touches only the
+//     one accumulator component that holds it (RL = 1).
+//   MT = 2 (slices of 17 .. 32 rows): the group sums and the running results of that scheme would
+//     need more registers than a wave has (a reload from scratch memory inside the loop waits for
+//     every load in flight, which undoes the prefetch), so the pairs of codes are dequantized
+//     instead, exactly: nibble ORed into the mantissa of 1024 (high nibble: times 1/16, into that of
+//     64), zero point subtracted (exact), one multiply by the scale (one rounding: the fp16 /
+//     bfloat16 value of (q - z) s), and the MFMAs add straight into the results.  x reaches the
+//     waves through LDS (see the kernel).
 #include <type_traits>
 
 #include "dev_common.h"
@@ -47,7 +51,7 @@ constexpr int kAhead   = 3;                      // k-steps a load runs ahead of
 template <int MT>
 struct SmallStage {
     u32x2   w[8];                                // row 8b + i of the k-step: two packed words = 16 columns
-    half8_t a[MT];                               // x rows 16 mt + (lane & 15), 8 consecutive k
+    half8_t a;                                   // MT = 1: x row (lane & 15), 8 consecutive k (MT = 2: x comes through LDS)
 };
 struct SmallGroup {
     u32x2 zq;                                    // zero points of the lane's 16 columns
@@ -103,8 +107,15 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int M_all, int S,
     int q_groups, int r_groups, SmallTail t)
 {
-    // one tile of 16 rows at a time: [wave][lane][column j of the lane, stored at j ^ (lane & 15)]
+    // After the k loop, the results of one tile of 16 rows at a time: [wave][lane][column j of the lane,
+    // stored at j ^ (lane & 15)].  During it (MT = 2), each wave keeps in its 16 KB two groups of x: 32
+    // rows of 128 k, a row = 16 pieces of 16 bytes, piece p stored at p ^ (row & 15) -- whole rows come
+    // from memory in whole cache lines (a lane that fetched the 8 k of its own MFMA operand for every
+    // step would touch 16 lines per load and use half of each), and both the store (16 lanes = the 16
+    // pieces of a row) and the MFMA-shaped load (16 lanes = the same piece of 16 rows) are free of bank
+    // conflicts.
     __shared__ __align__(16) f32x4 yl[kSmWaves * 64 * 16];
+    constexpr bool XL = MT > 1;                          // x through LDS
     __shared__ uint32_t fresh_word;
 
     MORPH_TICK(0);                                       // kernel entry
@@ -156,9 +167,30 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
         const uint32_t vw   = voff_w | dm;
 #pragma unroll
         for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32x2<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+        if constexpr (!XL)                               // rows at or beyond M lie past the buffer
+            sg.a = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, voff_a | dm, dead ? 0u : (uint32_t)ks * 64u, 0));
+    };
+    // x of a whole group for this wave: load i takes rows 4 i + (lane >> 4), piece (lane & 15) of each
+    u32x4 xg[XL ? 8 : 1];
+    const uint32_t voff_x = ((uint32_t)(lane >> 4) * (uint32_t)K + 8u * (uint32_t)(lane & 15)) * 2u;
+    u32x4* const xl = reinterpret_cast<u32x4*>(yl) + wave * 1024;    // this wave's 16 KB: two buffers of 512 pieces
+    auto load_xgroup = [&](int g) {
+        if constexpr (XL) {
+            const bool     dead = g >= gz;
+            const uint32_t dm   = dead ? kOut : 0u;
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++)                  // rows at or beyond M lie past the buffer
-            sg.a[mt] = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, (voff_a + (uint32_t)mt * 32u * (uint32_t)K) | dm, dead ? 0u : (uint32_t)ks * 64u, 0));
+            for (int i = 0; i < 8; i++)                  // rows at or beyond M lie past the buffer (the row is in the vector offset)
+                xg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (voff_x + (uint32_t)i * 8u * (uint32_t)K) | dm, dead ? 0u : (uint32_t)g * 256u, 0);
+        }
+    };
+    auto store_xgroup = [&](int buf) {
+        if constexpr (XL) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const int row = 4 * i + (lane >> 4);
+                xl[buf * 512 + row * 16 + ((lane ^ row) & 15)] = xg[i];
+            }
+        }
     };
     auto load_group = [&](SmallGroup& gr, int g) {
         const bool     dead = g >= gz;
@@ -176,6 +208,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
         gz = gb + (((wave + 1) * ng) >> 2);
         ks1 = 4 * gz;
         load_group(gnxt, ga);                            // first, so that what waits for it does not wait for the stages too
+        load_xgroup(ga);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < kAhead; i++) {
@@ -225,99 +258,169 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     // The k loop of the split begin_pass() was called for, then `sink(id, sum over the waves)` for every
     // vector of the tile, one tile of 16 rows at a time through LDS.
     auto run_pass = [&](auto&& sink) {
-        // gacc[mt][2 yb + 8 t]: sum of x * byte, gacc[mt][.. + 1]: sum of x * (byte & 0xF0), over the open group
-        f32x4 gacc[MT][16], xs[MT];
-        float yr[MT][16][RL];                            // running results, column j of the lane, row 16 mt + 4 b + r
-#pragma unroll
-        for (int mt = 0; mt < MT; mt++) {
-#pragma unroll
-            for (int j = 0; j < 16; j++) {
-                gacc[mt][j] = zero4;
-#pragma unroll
-                for (int r = 0; r < RL; r++) yr[mt][j][r] = 0.f;
-            }
-            xs[mt] = zero4;
-        }
-        for (int g = ga; g < gz; g++) {
-            gcur = gnxt;
-#pragma unroll
-            for (int u = 0; u < kRing; u++) {
-                load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
-                if (u == 1) load_group(gnxt, g + 1);     // arrives well before the next group ends
-                __builtin_amdgcn_sched_barrier(0);
-                const SmallStage<MT>& sg = st[u];
-                const bool first = u == 0;
-                half8_t xa[MT];
-                const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
-#pragma unroll
-                for (int mt = 0; mt < MT; mt++) {
-                    if constexpr (BF) xa[mt] = bf16x8_up64(sg.a[mt]);
-                    else xa[mt] = sg.a[mt];
-                    xs[mt] = mfma_small<BF>(xa[mt], tiny, first ? zero4 : xs[mt]);
+        f32x4 res[MT][16];                               // rows 16 mt + 4 b + r of column 16 c + j, when the loop is over
+        if constexpr (!XL) {
+            // gacc[mt][2 yb + 8 t]: sum of x * byte, gacc[mt][.. + 1]: sum of x * (byte & 0xF0), over the open group
+            f32x4 gacc[MT][16], xs[MT];
+            float yr[MT][16][RL];                            // running results, column j of the lane, row 16 mt + 4 b + r
+    #pragma unroll
+            for (int mt = 0; mt < MT; mt++) {
+    #pragma unroll
+                for (int j = 0; j < 16; j++) {
+                    gacc[mt][j] = zero4;
+    #pragma unroll
+                    for (int r = 0; r < RL; r++) yr[mt][j][r] = 0.f;
                 }
-#pragma unroll
-                for (int t2 = 0; t2 < 2; t2++) {
-#pragma unroll
-                    for (int yb = 0; yb < 4; yb++) {
-                        uint32_t pr[4], ph[4];
-#pragma unroll
-                        for (int q = 0; q < 4; q++) {
-                            const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
-                            pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
-                                  : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
-                            ph[q] = pr[q] & 0x00F000F0u;
-                        }
-                        const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
-                        const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
-                        const int j0 = t2 * 8 + 2 * yb;
-#pragma unroll
-                        for (int mt = 0; mt < MT; mt++) {
-                            gacc[mt][j0]     = mfma_small<BF>(xa[mt], bbyte, first ? zero4 : gacc[mt][j0]);
-                            gacc[mt][j0 + 1] = mfma_small<BF>(xa[mt], bhigh, first ? zero4 : gacc[mt][j0 + 1]);
-                        }
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                xs[mt] = zero4;
             }
-            // the group's sums go into the running results
-#pragma unroll
-            for (int t2 = 0; t2 < 2; t2++) {
-                const uint32_t zw  = gcur.zq[t2];
-                const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;     // z of the even columns; 16 z of the odd ones
-#pragma unroll
-                for (int yb = 0; yb < 4; yb++) {
-                    const uint32_t sw = gcur.sc[t2][yb];
-                    const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
-                    const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
-                    const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
-                    const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
-                    const int j0 = t2 * 8 + 2 * yb;
-#pragma unroll
+            for (int g = ga; g < gz; g++) {
+                gcur = gnxt;
+    #pragma unroll
+                for (int u = 0; u < kRing; u++) {
+                    load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
+                    if (u == 1) load_group(gnxt, g + 1);     // arrives well before the next group ends
+                    __builtin_amdgcn_sched_barrier(0);
+                    const SmallStage<MT>& sg = st[u];
+                    const bool first = u == 0;
+                    half8_t xa[MT];
+                    const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
+    #pragma unroll
                     for (int mt = 0; mt < MT; mt++) {
-#pragma unroll
-                        for (int r = 0; r < RL; r++) {
-                            const float d = gacc[mt][j0][r] - gacc[mt][j0 + 1][r];
-                            yr[mt][j0][r]     = __builtin_fmaf(-c_lo, xs[mt][r], __builtin_fmaf(s_lo, d, yr[mt][j0][r]));
-                            yr[mt][j0 + 1][r] = __builtin_fmaf(-c_hi, xs[mt][r], __builtin_fmaf(s_hi, gacc[mt][j0 + 1][r], yr[mt][j0 + 1][r]));
+                        if constexpr (BF) xa[mt] = bf16x8_up64(sg.a);
+                        else xa[mt] = sg.a;
+                        xs[mt] = mfma_small<BF>(xa[mt], tiny, first ? zero4 : xs[mt]);
+                    }
+    #pragma unroll
+                    for (int t2 = 0; t2 < 2; t2++) {
+    #pragma unroll
+                        for (int yb = 0; yb < 4; yb++) {
+                            uint32_t pr[4], ph[4];
+    #pragma unroll
+                            for (int q = 0; q < 4; q++) {
+                                const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
+                                pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                                      : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                                ph[q] = pr[q] & 0x00F000F0u;
+                            }
+                            const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
+                            const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
+                            const int j0 = t2 * 8 + 2 * yb;
+    #pragma unroll
+                            for (int mt = 0; mt < MT; mt++) {
+                                gacc[mt][j0]     = mfma_small<BF>(xa[mt], bbyte, first ? zero4 : gacc[mt][j0]);
+                                gacc[mt][j0 + 1] = mfma_small<BF>(xa[mt], bhigh, first ? zero4 : gacc[mt][j0 + 1]);
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // the group's sums go into the running results
+    #pragma unroll
+                for (int t2 = 0; t2 < 2; t2++) {
+                    const uint32_t zw  = gcur.zq[t2];
+                    const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;     // z of the even columns; 16 z of the odd ones
+    #pragma unroll
+                    for (int yb = 0; yb < 4; yb++) {
+                        const uint32_t sw = gcur.sc[t2][yb];
+                        const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+                        const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+                        const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
+                        const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
+                        const int j0 = t2 * 8 + 2 * yb;
+    #pragma unroll
+                        for (int mt = 0; mt < MT; mt++) {
+    #pragma unroll
+                            for (int r = 0; r < RL; r++) {
+                                const float d = gacc[mt][j0][r] - gacc[mt][j0 + 1][r];
+                                yr[mt][j0][r]     = __builtin_fmaf(-c_lo, xs[mt][r], __builtin_fmaf(s_lo, d, yr[mt][j0][r]));
+                                yr[mt][j0 + 1][r] = __builtin_fmaf(-c_hi, xs[mt][r], __builtin_fmaf(s_hi, gacc[mt][j0 + 1][r], yr[mt][j0 + 1][r]));
+                            }
                         }
                     }
                 }
             }
+            // the powers of two come out
+            constexpr float kEven = BF ? 0x1p69f : 0x1p24f;      // low-nibble (even) columns
+            constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;      // high-nibble (odd) columns: their sums carry a factor 16
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int j = 0; j < 16; j++) {
+                    res[mt][j] = zero4;
+#pragma unroll
+                    for (int r = 0; r < RL; r++) res[mt][j][r] = yr[mt][j][r] * ((j & 1) ? kOdd : kEven);
+                }
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+                for (int j = 0; j < 16; j++) res[mt][j] = zero4;
+            int xb = 0;                                  // the x buffer of the open group
+            store_xgroup(0);
+            for (int g = ga; g < gz; g++) {
+                gcur = gnxt;
+#pragma unroll
+                for (int u = 0; u < kRing; u++) {
+                    load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
+                    if (u == 0) load_xgroup(g + 1);      // issued before three stages of weights: a wait for it does not wait for them
+                    if (u == 1) load_group(gnxt, g + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const SmallStage<MT>& sg = st[u];
+                    half8_t xa[MT];
+#pragma unroll
+                    for (int mt = 0; mt < MT; mt++) xa[mt] = bit_cast<half8_t>(xl[xb * 512 + (16 * mt + c) * 16 + ((4 * u + b) ^ c)]);
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; t2++) {
+                        const uint32_t zq = gcur.zq[t2];
+#pragma unroll
+                        for (int yb = 0; yb < 4; yb++) {
+                            // the two columns of this byte: scale, and zero point as the constant that takes it out
+                            const uint32_t sw = gcur.sc[t2][yb];
+                            const half_t s0 = bit_cast<half_t>((uint16_t)(sw & 0xFFFFu)), s1 = bit_cast<half_t>((uint16_t)(sw >> 16));
+                            const uint32_t zd = yb == 0 ? pair_bytes<0>(zq, zq) : yb == 1 ? pair_bytes<1>(zq, zq)
+                                              : yb == 2 ? pair_bytes<2>(zq, zq) : pair_bytes<3>(zq, zq);
+                            const half2_t czl = bit_cast<half2_t>((zd & 0x000F000Fu) | 0xE400E400u);   // -(1024 + z), even column
+                            uint32_t lo8[4], hi8[4];
+#pragma unroll
+                            for (int q = 0; q < 4; q++) {
+                                const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
+                                const uint32_t pr = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                                                  : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                                if constexpr (BF) {
+                                    const half2_t czh16 = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xE400E400u);  // -(1024 + 16 z), odd column
+                                    lo8[q] = scale_to_bf16x2(nib_lo_1024(pr) + czl, (float)s0);
+                                    hi8[q] = scale_to_bf16x2(nib_hi_1024(pr) + czh16, (float)s1 * 0.0625f);
+                                } else {
+                                    const half2_t czh = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xD400D400u);    // -(64 + z), odd column
+                                    const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
+                                    const half2_t s0p = {s0, s0}, s1p = {s1, s1};
+                                    lo8[q] = bit_cast<uint32_t>((nib_lo_1024(pr) + czl) * s0p);                 // (q - z) * s, one rounding
+                                    hi8[q] = bit_cast<uint32_t>((nib_hi_1024(pr) * sixteenth + czh) * s1p);
+                                }
+                            }
+                            const half8_t blo = bit_cast<half8_t>(u32x4{lo8[0], lo8[1], lo8[2], lo8[3]});
+                            const half8_t bhi = bit_cast<half8_t>(u32x4{hi8[0], hi8[1], hi8[2], hi8[3]});
+                            const int j0 = t2 * 8 + 2 * yb;
+#pragma unroll
+                            for (int mt = 0; mt < MT; mt++) {
+                                res[mt][j0]     = mfma_small<BF>(xa[mt], blo, res[mt][j0]);
+                                res[mt][j0 + 1] = mfma_small<BF>(xa[mt], bhi, res[mt][j0 + 1]);
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                store_xgroup(xb ^ 1);                    // the next group's x, requested at the top of this one
+                xb ^= 1;
+            }
         }
-        // the powers of two come out; every wave leaves its sums in LDS, one tile of 16 rows at a time
-        constexpr float kEven = BF ? 0x1p69f : 0x1p24f;  // low-nibble (even) columns
-        constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;  // high-nibble (odd) columns: their sums carry a factor 16
+        // every wave leaves its sums in LDS, one tile of 16 rows at a time
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) {
             if (mt > 0) __syncthreads();                 // the tile before has been read
             if (MT > 1 || b < t.nb) {
 #pragma unroll
-                for (int j = 0; j < 16; j++) {
-                    f32x4 v = zero4;
-#pragma unroll
-                    for (int r = 0; r < RL; r++) v[r] = yr[mt][j][r] * ((j & 1) ? kOdd : kEven);
-                    yl[(wave * 64 + lane) * 16 + (j ^ c)] = v;
-                }
+                for (int j = 0; j < 16; j++) yl[(wave * 64 + lane) * 16 + (j ^ c)] = res[mt][j];
             }
             __syncthreads();
             for (int lid = tid; lid < per_tile; lid += kSmWaves * 64) sink(mt * per_tile + lid, vec_sum(lid));
