@@ -379,7 +379,8 @@ static DecodePlan plan_small(int M, int K, int N)
     if (target <= 0) target = prefill_compute_units();
     const int slices = M > 32 ? 2 : 1;                   // slices of 32 rows, a workgroup each
     int S = target / (pl.tiles * slices);
-    if (S > T / 4) S = T / 4;                            // every workgroup keeps at least one quantization group
+    const int most = M <= 16 ? T / 4 : (T / 8 > 0 ? T / 8 : 1);   // every workgroup keeps a quantization group; beyond 16 rows, each half of its waves one
+    if (S > most) S = most;
     if (S > 16) S = 16;
     const int forced = tuning_get(TUNE_DECODE_SPLIT);
     if (forced > 0) S = forced > 16 ? 16 : forced;

@@ -1,39 +1,42 @@
 // W4A16 linears of at most 64 rows (the decode step): y[M,N] = x[M,K] * dequant(W4), bound by the
 // rate at which the packed codes leave HBM.  At these sizes a launch lasts a few microseconds, of
 // which the memory system needs one to deliver its first byte and every exchange between workgroups
-// through memory costs most of another, so the kernel is built around:
+// through memory costs most of another, so the kernels here are built around:
 //   * a short head: the division of K over workgroups and waves is prepared on the host, and a wave
 //     reaches its first load after a few dozen instructions;
 //   * loads that run three k-steps (of 32 rows) ahead of their use through a ring of four register
 //     stages in a loop unrolled by four (= one quantization group); a wave takes whole groups, so
 //     the only loads that fall outside its range are the last three slots' (pushed past the buffer,
 //     they return zeros without memory traffic) and the compiler's wait counts are exact;
-//   * one workgroup takes up to 32 rows of its columns (MT tiles of 16), so that up to there every
-//     weight is read and unpacked once; beyond, two workgroups on the same XCD take a slice of 32 rows
-//     each and the second reading is served by that XCD's L2;
-//   * results in registers until the k loop is over;
-//   * a hand-over between the workgroups that split K which stays inside one XCD's L2 (see the end
-//     of the kernel).
+//   * results in registers until the k loop is over, and no reload from scratch memory inside the
+//     loop (such a reload waits for every load in flight, which undoes the prefetch);
+//   * a hand-over between the workgroups that split K which stays inside one XCD's L2 (see
+//     finish_over_splits).
 //
 // The multiply runs on the matrix cores, v_mfma_f32_16x16x32_f16 / _bf16, x as the A operand (rows
 // beyond M read as zero), the weights as B.  B wants, per lane, 8 consecutive k of one column, while a
-// packed word holds 8 consecutive columns of one k: a lane loads the same two words from 8
-// consecutive rows and pairs bytes across rows (v_perm_b32).  From there two schemes:
-//   MT = 1 (M <= 16): the codes enter the MFMA without conversion -- a 16-bit lane holding the byte
-//     16 q_hi + q_lo IS that number times 2^-24 (fp16 subnormal), or times 2^-133 read as bfloat16.
-//     Per byte two MFMAs (whole byte; byte masked to its high nibble), one more against a B of 2^-24
-//     for the row sums of x; per group of 128 rows the sums are folded into running results:
-//         low-nibble column:   Y += s * (acc_byte - acc_high) - (s * z_lo) * xsum     (in units of 2^-24)
-//         high-nibble column:  Y += s *  acc_high             - (s * 16 z_hi) * xsum  (in units of 2^-20)
-//     and the powers of two are taken out once, at the end.  With one row the fold touches only the
-//     one accumulator component that holds it (RL = 1).
-//   MT = 2 (slices of 17 .. 32 rows): the group sums and the running results of that scheme would
-//     need more registers than a wave has (a reload from scratch memory inside the loop waits for
-//     every load in flight, which undoes the prefetch), so the pairs of codes are dequantized
-//     instead, exactly: nibble ORed into the mantissa of 1024 (high nibble: times 1/16, into that of
-//     64), zero point subtracted (exact), one multiply by the scale (one rounding: the fp16 /
-//     bfloat16 value of (q - z) s), and the MFMAs add straight into the results.  x reaches the
-//     waves through LDS (see the kernel).
+// packed word holds 8 consecutive columns of one k: a lane loads the same words from 8 consecutive
+// rows and pairs bytes across rows (v_perm_b32).  The codes then enter the MFMA without conversion --
+// a 16-bit lane holding the byte 16 q_hi + q_lo IS that number times 2^-24 (fp16 subnormal), or times
+// 2^-133 read as bfloat16.  Per byte two MFMAs per tile of 16 rows (whole byte; byte masked to its
+// high nibble), one more against a B of 2^-24 for the row sums of x; per group of 128 rows the sums
+// are folded into running results:
+//     low-nibble column:   Y += s * (acc_byte - acc_high) - (s * z_lo) * xsum     (in units of 2^-24)
+//     high-nibble column:  Y += s *  acc_high             - (s * 16 z_hi) * xsum  (in units of 2^-20)
+// and the powers of two are taken out once, at the end.  One wave has a SIMD to itself, so beyond a
+// few rows the loop is bound by the number of instructions the wave issues (measured: a vector
+// instruction every 4.5 clocks, an MFMA adds 8 and runs beside them): unpacking this way costs two
+// vector instructions per four weights and the fold five per result and group, against nine per
+// four weights for dequantizing them first.
+//
+// Two kernels:
+//   decode_small_kernel, M <= 16: a wave takes 256 columns (16 per lane, 8-byte loads) of all rows;
+//     with one row the fold touches only the one accumulator component that holds it (RL = 1).
+//   decode_mid_kernel, 17 <= M <= 64: the group sums and running results of 32 rows by 256 columns
+//     do not fit a wave's registers, so a wave takes 128 columns (8 per lane, 4-byte loads) of a slice
+//     of at most 32 rows, two waves side by side and two along K; beyond 32 rows two workgroups on
+//     the same XCD take a slice each and the second reading of the weights is served by that XCD's
+//     L2.  x reaches the waves through LDS, in whole cache lines.
 #include <type_traits>
 
 #include "dev_common.h"
@@ -48,28 +51,18 @@ constexpr int kSmWaves = 4;
 constexpr int kRing    = 4;                      // register stages = slots of the unrolled loop (one quantization group)
 constexpr int kAhead   = 3;                      // k-steps a load runs ahead of its use
 
-template <int MT>
-struct SmallStage {
-    u32x2   w[8];                                // row 8b + i of the k-step: two packed words = 16 columns
-    half8_t a;                                   // MT = 1: x row (lane & 15), 8 consecutive k (MT = 2: x comes through LDS)
-};
-struct SmallGroup {
-    u32x2 zq;                                    // zero points of the lane's 16 columns
-    u32x4 sc[2];                                 // their scales
-};
-
-// Per column tile, one word per split in the workspace's counter region (any content between launches):
-// the split's flag = 16 x (a counter its workgroup raises by one when its partial sums are in place)
-// + where those sums can be read: 0 = in memory, 1 + x = in the L2 of XCD x.  A reader compares the
-// counter with the value it found when it started.
+// Per (column tile, slice of rows), one word per split in the workspace's counter region (any content
+// between launches): the split's flag = 16 x (a counter its workgroup raises by one when its partial
+// sums are in place) + where those sums can be read: 0 = in memory, 1 + x = in the L2 of XCD x.  A
+// reader compares the counter with the value it found when it started.
 constexpr int kCtlInts = kSmallCtlInts;
 
 struct SmallTail {
     void*     y;
-    uint32_t* slots;                             // [tile][split][vector] f32x4 partial sums (no content between launches)
-    int*      ctl;                               // kCtlInts per tile
+    uint32_t* slots;                             // [unit][split][vector] f32x4 partial sums (no content between launches)
+    int*      ctl;                               // kCtlInts per unit
     int       polls;                             // looks at the flags before a workgroup stops waiting
-    int       nb;                                // MT = 1: groups of four rows that exist, ceil(M / 4)
+    int       nb;                                // M <= 16: groups of four rows that exist, ceil(M / 4)
     int       tiles;                             // column tiles of 256
     int       sl_shift;                          // 0: one slice of rows; 1: two slices of 32 rows, workgroups (tile, slice, split)
     int       far;                               // write the hand-over through to memory instead of leaving it in the L2
@@ -100,358 +93,66 @@ __device__ __forceinline__ half8_t bf16x8_up64(half8_t v)
 // the value of the first look for all later ones.
 __device__ __forceinline__ void reload_fence() { asm volatile("" ::: "memory"); }
 
-// MT: tiles of 16 rows one workgroup takes (1 or 2).  RL (MT = 1 only): accumulator components per lane
-// that hold rows which exist (1: M = 1; 4 otherwise).  BF: x and y are bfloat16.
-template <int MT, int RL, bool BF>
-__global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
-    const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int M_all, int S,
-    int q_groups, int r_groups, SmallTail t)
+// Which (column tile, slice of rows, split) a workgroup is.  Workgroup L runs on XCD L % 8 (workgroups
+// are dealt to the XCDs in turn).  The S workgroups of a unit = (tile, slice) are given the same L % 8,
+// so that they meet in one L2, and so are the two slices of a tile, which read the same weights:
+// within XCD `xcd` the workgroups j = L / 8 walk (tile slot, slice, split), tile = 8 * slot + xcd.
+// Tiles that do not exist (the last slot of an XCD when the tile count is no multiple of 8) have
+// tile >= tiles and leave at once.
+struct Place { int tile, slice, sp, unit; };
+__device__ __forceinline__ Place place_of(const SmallTail& t, int S)
 {
-    // After the k loop, the results of one tile of 16 rows at a time: [wave][lane][column j of the lane,
-    // stored at j ^ (lane & 15)].  During it (MT = 2), each wave keeps in its 16 KB two groups of x: 32
-    // rows of 128 k, a row = 16 pieces of 16 bytes, piece p stored at p ^ (row & 15) -- whole rows come
-    // from memory in whole cache lines (a lane that fetched the 8 k of its own MFMA operand for every
-    // step would touch 16 lines per load and use half of each), and both the store (16 lanes = the 16
-    // pieces of a row) and the MFMA-shaped load (16 lanes = the same piece of 16 rows) are free of bank
-    // conflicts.
-    __shared__ __align__(16) f32x4 yl[kSmWaves * 64 * 16];
-    constexpr bool XL = MT > 1;                          // x through LDS
-    __shared__ uint32_t fresh_word;
-
-    MORPH_TICK(0);                                       // kernel entry
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int c = lane & 15, b = lane >> 4;
-    // Workgroup L runs on XCD L % 8 (workgroups are dealt to the XCDs in turn).  The S workgroups of a
-    // column tile are given the same L % 8, so that they meet in one L2: within XCD `xcd` the
-    // workgroups j = L / 8 walk (tile slot, slice of rows, split), tile = 8 * slot + xcd.  Tiles that do
-    // not exist (the last slot of an XCD when the tile count is no multiple of 8) leave at once.
     const int L = blockIdx.x, xcd = L & 7, jj = L >> 3;
-    const int pair = (jj * t.inv_s) >> 16, sp = jj - pair * S;
-    const int slot = pair >> t.sl_shift, slice = pair - (slot << t.sl_shift);
-    const int tile = slot * 8 + xcd;
-    if (tile >= t.tiles) return;
-    const int unit = (tile << t.sl_shift) + slice;       // who shares flags and slots: the splits of one (tile, slice)
-    const int n0 = tile * 256;
-    const int NW = N >> 3;
-    // this workgroup's rows: a slice is 32 rows
-    const int M = M_all - 32 * slice < 16 * MT ? M_all - 32 * slice : 16 * MT;
-    const uint16_t* x = (const uint16_t*)x_all + (size_t)(32 * slice) * K;
+    const int pair = (jj * t.inv_s) >> 16;
+    Place p;
+    p.sp = jj - pair * S;
+    const int slot = pair >> t.sl_shift;
+    p.slice = pair - (slot << t.sl_shift);
+    p.tile = slot * 8 + xcd;
+    p.unit = (p.tile << t.sl_shift) + p.slice;
+    return p;
+}
 
-    const uint32_t row_bytes = (uint32_t)NW * 4u;
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
-    const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
-    const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
-    // without a split there is no control block and no slot (null pointers): a range of zero makes every access fall outside
-    const __amdgpu_buffer_rsrc_t rc = make_rsrc(S > 1 ? t.ctl + (size_t)unit * kCtlInts : nullptr, S > 1 ? kCtlInts * 4u : 0u);
-
-    const int  ncol   = n0 + 16 * c;                     // this lane's first column
-    const bool col_ok = ncol < N;
-    const uint32_t kOut = 0xFFFFFFF0u;
-    const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + (uint32_t)ncol / 2u : kOut;
-    const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
-    const uint32_t voff_z = col_ok ? (uint32_t)ncol / 2u : kOut;
-    const uint32_t voff_a = ((uint32_t)c * (uint32_t)K + 8u * b) * 2u;     // row c; tile mt of the rows lies 16 rows further on
-    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
-
-    // The k loop runs for one split at a time: normally once, for this workgroup's own split; see the
-    // hand-over below for when it runs again.  begin_pass() fixes the range and requests its first loads.
-    int      ga = 0, gz = 0, ks1 = 0;
-    SmallStage<MT> st[kRing];
-    SmallGroup gcur, gnxt;
-    auto load_stage = [&](SmallStage<MT>& sg, int ks) {
-        const bool     dead = ks >= ks1;
-        const uint32_t dm   = dead ? kOut : 0u;
-        const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
-        const uint32_t vw   = voff_w | dm;
-#pragma unroll
-        for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32x2<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
-        if constexpr (!XL)                               // rows at or beyond M lie past the buffer
-            sg.a = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, voff_a | dm, dead ? 0u : (uint32_t)ks * 64u, 0));
-    };
-    // x of a whole group for this wave: load i takes rows 4 i + (lane >> 4), piece (lane & 15) of each
-    u32x4 xg[XL ? 8 : 1];
-    const uint32_t voff_x = ((uint32_t)(lane >> 4) * (uint32_t)K + 8u * (uint32_t)(lane & 15)) * 2u;
-    u32x4* const xl = reinterpret_cast<u32x4*>(yl) + wave * 1024;    // this wave's 16 KB: two buffers of 512 pieces
-    auto load_xgroup = [&](int g) {
-        if constexpr (XL) {
-            const bool     dead = g >= gz;
-            const uint32_t dm   = dead ? kOut : 0u;
-#pragma unroll
-            for (int i = 0; i < 8; i++)                  // rows at or beyond M lie past the buffer (the row is in the vector offset)
-                xg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (voff_x + (uint32_t)i * 8u * (uint32_t)K) | dm, dead ? 0u : (uint32_t)g * 256u, 0);
-        }
-    };
-    auto store_xgroup = [&](int buf) {
-        if constexpr (XL) {
-#pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const int row = 4 * i + (lane >> 4);
-                xl[buf * 512 + row * 16 + ((lane ^ row) & 15)] = xg[i];
-            }
-        }
-    };
-    auto load_group = [&](SmallGroup& gr, int g) {
-        const bool     dead = g >= gz;
-        const uint32_t gm   = dead ? kOut : 0u;
-        const uint32_t gg   = dead ? 0u : (uint32_t)g;
-        gr.zq    = buf_load_u32x2(rz, voff_z | gm, gg * row_bytes);
-        gr.sc[0] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u);
-        gr.sc[1] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u + 16u);
-    };
-    auto begin_pass = [&](int split) {
-        // quantization groups (128 rows = four k-steps) of the split, then of this wave: no division on the device
-        const int gb = split * q_groups + (split < r_groups ? split : r_groups);
-        const int ng = q_groups + (split < r_groups ? 1 : 0);
-        ga = gb + ((wave * ng) >> 2);
-        gz = gb + (((wave + 1) * ng) >> 2);
-        ks1 = 4 * gz;
-        load_group(gnxt, ga);                            // first, so that what waits for it does not wait for the stages too
-        load_xgroup(ga);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < kAhead; i++) {
-            load_stage(st[i], 4 * ga + i);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    // ---- everything the wave needs first is requested before anything else happens ----
-    uint32_t base = 0;                                   // wave 0: the tile's flags as found (lane q: split q)
-    begin_pass(sp);
-    // and the first wave reads the tile's flags as they stand: whatever a flag's counter turns into
-    // later was done in this launch
-    if (S > 1 && wave == 0 && lane < S) base = __builtin_amdgcn_raw_buffer_load_b32(rc, (uint32_t)lane * 4u, 0, kAuxSystemScope);
-    __builtin_amdgcn_sched_barrier(0);
-    MORPH_TICK(1);                                       // first loads issued
-
-    // A vector = four rows of one column.  Vector (mt, ln, j): column n0 + 16 (ln & 15) + j, rows
-    // 16 mt + 4 (ln >> 4) ..; its number is id = mt * per_tile + 16 ln + j, so that 256 consecutive
-    // numbers are 256 consecutive columns.  With one tile of rows only lanes 0 .. 16 nb - 1 hold rows
-    // that exist, and only their vectors are numbered.
-    const int lanes = MT == 1 ? 16 * t.nb : 64;          // lanes that hold rows
-    const int per_tile = 16 * lanes;                     // vectors of one tile of 16 rows
-    const int nvec = MT * per_tile;
-    auto vec_sum = [&](int lid) {                        // vector lid of the tile now in LDS, over the waves in the order of their k ranges
-        const int ln = lid >> 4, j = (lid ^ ln) & 15;
-        f32x4 a = yl[ln * 16 + j];
-#pragma unroll
-        for (int q = 1; q < kSmWaves; q++) a += yl[(q * 64 + ln) * 16 + j];
-        return a;
-    };
-    uint16_t* y = (uint16_t*)t.y + (size_t)(32 * slice) * N;
-    auto vec_store_y = [&](int id, f32x4 acc) {
-        const int mt = MT == 1 ? 0 : id >> 10, lid = MT == 1 ? id : id & 1023;
-        const int ln = lid >> 4, j = lid & 15;
-        const int col = n0 + 16 * (ln & 15) + j, row = 16 * mt + 4 * (ln >> 4);
-        if (col < N) {
-#pragma unroll
-            for (int r = 0; r < 4; r++)
-                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<BF>(acc[r]);
-        }
-    };
-    const uint32_t slot_bytes = (uint32_t)nvec * 16u;
-    const __amdgpu_buffer_rsrc_t rp = make_rsrc(S > 1 ? t.slots + (size_t)unit * S * nvec * 4 : nullptr, S > 1 ? (uint32_t)S * slot_bytes : 0u);
-    const int v0 = (sp * nvec) / S, v1 = ((sp + 1) * nvec) / S;   // my share of the tile's vectors
-
-    // The k loop of the split begin_pass() was called for, then `sink(id, sum over the waves)` for every
-    // vector of the tile, one tile of 16 rows at a time through LDS.
-    auto run_pass = [&](auto&& sink) {
-        f32x4 res[MT][16];                               // rows 16 mt + 4 b + r of column 16 c + j, when the loop is over
-        if constexpr (!XL) {
-            // gacc[mt][2 yb + 8 t]: sum of x * byte, gacc[mt][.. + 1]: sum of x * (byte & 0xF0), over the open group
-            f32x4 gacc[MT][16], xs[MT];
-            float yr[MT][16][RL];                            // running results, column j of the lane, row 16 mt + 4 b + r
-    #pragma unroll
-            for (int mt = 0; mt < MT; mt++) {
-    #pragma unroll
-                for (int j = 0; j < 16; j++) {
-                    gacc[mt][j] = zero4;
-    #pragma unroll
-                    for (int r = 0; r < RL; r++) yr[mt][j][r] = 0.f;
-                }
-                xs[mt] = zero4;
-            }
-            for (int g = ga; g < gz; g++) {
-                gcur = gnxt;
-    #pragma unroll
-                for (int u = 0; u < kRing; u++) {
-                    load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
-                    if (u == 1) load_group(gnxt, g + 1);     // arrives well before the next group ends
-                    __builtin_amdgcn_sched_barrier(0);
-                    const SmallStage<MT>& sg = st[u];
-                    const bool first = u == 0;
-                    half8_t xa[MT];
-                    const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
-    #pragma unroll
-                    for (int mt = 0; mt < MT; mt++) {
-                        if constexpr (BF) xa[mt] = bf16x8_up64(sg.a);
-                        else xa[mt] = sg.a;
-                        xs[mt] = mfma_small<BF>(xa[mt], tiny, first ? zero4 : xs[mt]);
-                    }
-    #pragma unroll
-                    for (int t2 = 0; t2 < 2; t2++) {
-    #pragma unroll
-                        for (int yb = 0; yb < 4; yb++) {
-                            uint32_t pr[4], ph[4];
-    #pragma unroll
-                            for (int q = 0; q < 4; q++) {
-                                const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
-                                pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
-                                      : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
-                                ph[q] = pr[q] & 0x00F000F0u;
-                            }
-                            const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
-                            const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
-                            const int j0 = t2 * 8 + 2 * yb;
-    #pragma unroll
-                            for (int mt = 0; mt < MT; mt++) {
-                                gacc[mt][j0]     = mfma_small<BF>(xa[mt], bbyte, first ? zero4 : gacc[mt][j0]);
-                                gacc[mt][j0 + 1] = mfma_small<BF>(xa[mt], bhigh, first ? zero4 : gacc[mt][j0 + 1]);
-                            }
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                // the group's sums go into the running results
-    #pragma unroll
-                for (int t2 = 0; t2 < 2; t2++) {
-                    const uint32_t zw  = gcur.zq[t2];
-                    const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;     // z of the even columns; 16 z of the odd ones
-    #pragma unroll
-                    for (int yb = 0; yb < 4; yb++) {
-                        const uint32_t sw = gcur.sc[t2][yb];
-                        const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
-                        const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
-                        const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
-                        const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
-                        const int j0 = t2 * 8 + 2 * yb;
-    #pragma unroll
-                        for (int mt = 0; mt < MT; mt++) {
-    #pragma unroll
-                            for (int r = 0; r < RL; r++) {
-                                const float d = gacc[mt][j0][r] - gacc[mt][j0 + 1][r];
-                                yr[mt][j0][r]     = __builtin_fmaf(-c_lo, xs[mt][r], __builtin_fmaf(s_lo, d, yr[mt][j0][r]));
-                                yr[mt][j0 + 1][r] = __builtin_fmaf(-c_hi, xs[mt][r], __builtin_fmaf(s_hi, gacc[mt][j0 + 1][r], yr[mt][j0 + 1][r]));
-                            }
-                        }
-                    }
-                }
-            }
-            // the powers of two come out
-            constexpr float kEven = BF ? 0x1p69f : 0x1p24f;      // low-nibble (even) columns
-            constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;      // high-nibble (odd) columns: their sums carry a factor 16
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-                for (int j = 0; j < 16; j++) {
-                    res[mt][j] = zero4;
-#pragma unroll
-                    for (int r = 0; r < RL; r++) res[mt][j][r] = yr[mt][j][r] * ((j & 1) ? kOdd : kEven);
-                }
-        } else {
-#pragma unroll
-            for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-                for (int j = 0; j < 16; j++) res[mt][j] = zero4;
-            int xb = 0;                                  // the x buffer of the open group
-            store_xgroup(0);
-            for (int g = ga; g < gz; g++) {
-                gcur = gnxt;
-#pragma unroll
-                for (int u = 0; u < kRing; u++) {
-                    load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
-                    if (u == 0) load_xgroup(g + 1);      // issued before three stages of weights: a wait for it does not wait for them
-                    if (u == 1) load_group(gnxt, g + 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    const SmallStage<MT>& sg = st[u];
-                    half8_t xa[MT];
-#pragma unroll
-                    for (int mt = 0; mt < MT; mt++) xa[mt] = bit_cast<half8_t>(xl[xb * 512 + (16 * mt + c) * 16 + ((4 * u + b) ^ c)]);
-#pragma unroll
-                    for (int t2 = 0; t2 < 2; t2++) {
-                        const uint32_t zq = gcur.zq[t2];
-#pragma unroll
-                        for (int yb = 0; yb < 4; yb++) {
-                            // the two columns of this byte: scale, and zero point as the constant that takes it out
-                            const uint32_t sw = gcur.sc[t2][yb];
-                            const half_t s0 = bit_cast<half_t>((uint16_t)(sw & 0xFFFFu)), s1 = bit_cast<half_t>((uint16_t)(sw >> 16));
-                            const uint32_t zd = yb == 0 ? pair_bytes<0>(zq, zq) : yb == 1 ? pair_bytes<1>(zq, zq)
-                                              : yb == 2 ? pair_bytes<2>(zq, zq) : pair_bytes<3>(zq, zq);
-                            const half2_t czl = bit_cast<half2_t>((zd & 0x000F000Fu) | 0xE400E400u);   // -(1024 + z), even column
-                            uint32_t lo8[4], hi8[4];
-#pragma unroll
-                            for (int q = 0; q < 4; q++) {
-                                const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
-                                const uint32_t pr = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
-                                                  : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
-                                if constexpr (BF) {
-                                    const half2_t czh16 = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xE400E400u);  // -(1024 + 16 z), odd column
-                                    lo8[q] = scale_to_bf16x2(nib_lo_1024(pr) + czl, (float)s0);
-                                    hi8[q] = scale_to_bf16x2(nib_hi_1024(pr) + czh16, (float)s1 * 0.0625f);
-                                } else {
-                                    const half2_t czh = bit_cast<half2_t>((zd & 0x00F000F0u) | 0xD400D400u);    // -(64 + z), odd column
-                                    const half2_t sixteenth = {(half_t)0.0625f, (half_t)0.0625f};
-                                    const half2_t s0p = {s0, s0}, s1p = {s1, s1};
-                                    lo8[q] = bit_cast<uint32_t>((nib_lo_1024(pr) + czl) * s0p);                 // (q - z) * s, one rounding
-                                    hi8[q] = bit_cast<uint32_t>((nib_hi_1024(pr) * sixteenth + czh) * s1p);
-                                }
-                            }
-                            const half8_t blo = bit_cast<half8_t>(u32x4{lo8[0], lo8[1], lo8[2], lo8[3]});
-                            const half8_t bhi = bit_cast<half8_t>(u32x4{hi8[0], hi8[1], hi8[2], hi8[3]});
-                            const int j0 = t2 * 8 + 2 * yb;
-#pragma unroll
-                            for (int mt = 0; mt < MT; mt++) {
-                                res[mt][j0]     = mfma_small<BF>(xa[mt], blo, res[mt][j0]);
-                                res[mt][j0 + 1] = mfma_small<BF>(xa[mt], bhi, res[mt][j0 + 1]);
-                            }
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                store_xgroup(xb ^ 1);                    // the next group's x, requested at the top of this one
-                xb ^= 1;
-            }
-        }
-        // every wave leaves its sums in LDS, one tile of 16 rows at a time
-#pragma unroll
-        for (int mt = 0; mt < MT; mt++) {
-            if (mt > 0) __syncthreads();                 // the tile before has been read
-            if (MT > 1 || b < t.nb) {
-#pragma unroll
-                for (int j = 0; j < 16; j++) yl[(wave * 64 + lane) * 16 + (j ^ c)] = res[mt][j];
-            }
-            __syncthreads();
-            for (int lid = tid; lid < per_tile; lid += kSmWaves * 64) sink(mt * per_tile + lid, vec_sum(lid));
-        }
-    };
-
+// ---- what follows the k loop: the hand-over between the S workgroups of a unit ----
+// run_pass(sink) runs the k loop of the split begin_pass() was last called for (the caller has called
+// it for this workgroup's own split) and hands every vector (four rows of one column) of the unit's
+// nvec, summed over the waves, to sink(id, value); store_y(id, value) writes a finished vector.
+//   Every workgroup puts its partial vectors into its slot, waits for the stores to be acknowledged
+// and raises its flag's counter by one.  Then it polls the S flags of the unit (one load per look),
+// and when every counter differs from what it was when this workgroup started (`base`, read by the
+// first wave before anything else, lane q: split q), it adds its share of the vectors, [v0, v1), up
+// over the splits, in split order, and stores y.  No arrival count, no atomic, nothing to put back: a
+// counter can only have changed during this launch, after its owner's partial sums were in place.  (A
+// workgroup that starts so late that a flag was raised before it looked sees no change, and goes the
+// slow way below.)
+//   Where the data travels: the workgroups of a unit are placed on one XCD, so the stores are plain --
+// sums and flag stay in that XCD's L2, where the scoped loads of the others find them without a trip
+// to memory -- and the flag says which XCD that is.  A reader that finds itself elsewhere (the
+// placement is the hardware's; this only happens if it deals workgroups out differently) must not
+// trust what it reads from memory, and takes that split the slow way.  With t.far the stores are
+// written through to memory and the flag says so.
+//   Correctness does not rest on the others: the wait is bounded, and a workgroup that stops waiting
+// works out the missing partial sums of its share itself -- it runs the k loop again for every split
+// whose flag did not move, and puts that split's vectors of its share where the split's owner puts
+// them (the same numbers from the same instructions: if both write, they write the same bits).
+// Whoever adds a vector up, and wherever the terms come from, they are added in split order.
+template <class RunPass, class BeginPass, class StoreY>
+__device__ __forceinline__ void finish_over_splits(const SmallTail& t, int S, const Place& p, int nvec, uint32_t base,
+                                                   uint32_t* fresh_word, RunPass&& run_pass, BeginPass&& begin_pass, StoreY&& store_y)
+{
     if (S == 1) {
-        run_pass([&](int id, f32x4 v) { vec_store_y(id, v); });
+        run_pass([&](int id, f32x4 v) { store_y(id, v); });
         return;
     }
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sp = p.sp;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    const uint32_t slot_bytes = (uint32_t)nvec * 16u;
+    const __amdgpu_buffer_rsrc_t rc = make_rsrc(t.ctl + (size_t)p.unit * kCtlInts, kCtlInts * 4u);
+    const __amdgpu_buffer_rsrc_t rp = make_rsrc(t.slots + (size_t)p.unit * S * nvec * 4, (uint32_t)S * slot_bytes);
+    const int v0 = (sp * nvec) / S, v1 = ((sp + 1) * nvec) / S;   // my share of the unit's vectors
 
-    // ---- hand-over between the S workgroups of a column tile ----
-    // Every workgroup puts its partial vectors into its slot, waits for the stores to be acknowledged
-    // and raises its flag's counter by one.  Then it polls the S flags of the tile (one load per look),
-    // and when every counter differs from what it was when this workgroup started, it adds its share
-    // of the vectors, [v0, v1), up over the splits, in split order, and stores y.  No arrival count, no
-    // atomic, nothing to put back: a counter can only have changed during this launch, after its
-    // owner's partial sums were in place.  (A workgroup that starts so late that a flag was raised
-    // before it looked sees no change, and goes the slow way below.)
-    //   Where the data travels: the workgroups of a tile are placed on one XCD (see the top), so the
-    // stores are plain -- sums and flag stay in that XCD's L2, where the scoped loads of the others find
-    // them without a trip to memory -- and the flag says which XCD that is.  A reader that finds
-    // itself elsewhere (the placement is the hardware's; this only happens if it deals workgroups
-    // out differently) must not trust what it reads from memory, and takes that split the slow way.
-    // With t.far the stores are written through to memory and the flag says so.
-    //   Correctness does not rest on the others: the wait is bounded, and a workgroup that stops
-    // waiting works out the missing partial sums of its share itself -- it runs the k loop again for
-    // every split whose flag did not move, and puts that split's vectors of its share where the
-    // split's owner puts them (the same numbers from the same instructions: if both write, they
-    // write the same bits).  Whoever adds a vector up, and wherever the terms come from, they are
-    // added in split order.
     uint32_t my_xcc;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(my_xcc));
     const uint32_t where = t.far ? 0u : (my_xcc & 0xFu) + 1u;
@@ -481,10 +182,10 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
             moved  = ((uint32_t)__builtin_amdgcn_ballot_w64((f >> 4) != (base >> 4)) & want) | (1u << sp);
             usable = ((uint32_t)__builtin_amdgcn_ballot_w64((f >> 4) != (base >> 4) && ((f & 15u) == 0u || (f & 15u) == (my_xcc & 0xFu) + 1u)) & want) | (1u << sp);
         }
-        if (lane == 0) fresh_word = usable;
+        if (lane == 0) *fresh_word = usable;
     }
     __syncthreads();
-    const uint32_t fresh = fresh_word;                   // splits whose partial sums are in their slots, readable from here
+    const uint32_t fresh = *fresh_word;                  // splits whose partial sums are in their slots, readable from here
     MORPH_TICK(5);                                       // all flags seen (or no longer waited for)
 
     // ---- the slow way, for every split that is not there: worked out here ----
@@ -502,7 +203,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     // ---- my share: every vector summed over the splits in split order ----
     auto gather = [&](auto width) {
         constexpr int W = decltype(width)::value;        // S <= W; splits beyond S lie past the buffer and read as zeros
-        for (int id = v0 + tid; id < v1; id += kSmWaves * 64) {
+        for (int id = v0 + tid; id < v1; id += (int)blockDim.x) {
             u32x4 v[W];
             reload_fence();
 #pragma unroll
@@ -514,7 +215,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
 #pragma unroll
             for (int q = 0; q < W; q++)
                 if (q < S) acc += bit_cast<f32x4>(v[q]);
-            vec_store_y(id, acc);
+            store_y(id, acc);
         }
     };
     if (S <= 4) gather(std::integral_constant<int, 4>{});
@@ -522,8 +223,448 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     MORPH_TICK(6);                                       // own share stored
 }
 
-template <int MT, int RL, bool BF>
-hipError_t launch_small_t(const SmallArgs& a, hipStream_t st)
+// The unit's flags as they stand when the workgroup starts (first wave, lane q: split q): whatever a
+// flag's counter turns into later was done in this launch.
+__device__ __forceinline__ uint32_t flags_as_found(const SmallTail& t, int S, const Place& p, int wave, int lane)
+{
+    if (S > 1 && wave == 0 && lane < S) {
+        const __amdgpu_buffer_rsrc_t rc = make_rsrc(t.ctl + (size_t)p.unit * kCtlInts, kCtlInts * 4u);
+        return __builtin_amdgcn_raw_buffer_load_b32(rc, (uint32_t)lane * 4u, 0, kAuxSystemScope);
+    }
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------------
+// M <= 16.  RL: accumulator components per lane that hold rows which exist (1: M = 1; 4 otherwise).
+// BF: x and y are bfloat16.
+// ------------------------------------------------------------------------------------------------
+struct SmallStage {
+    u32x2   w[8];                                // row 8b + i of the k-step: two packed words = 16 columns
+    half8_t a;                                   // x row (lane & 15), 8 consecutive k
+};
+struct SmallGroup {
+    u32x2 zq;                                    // zero points of the lane's 16 columns
+    u32x4 sc[2];                                 // their scales
+};
+
+template <int RL, bool BF>
+__global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
+    const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int M, int S,
+    int q_groups, int r_groups, SmallTail t)
+{
+    // after the k loop: [wave][lane][column j of the lane, stored at j ^ (lane & 15)]
+    __shared__ __align__(16) f32x4 yl[kSmWaves * 64 * 16];
+    __shared__ uint32_t fresh_word;
+
+    MORPH_TICK(0);                                       // kernel entry
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, b = lane >> 4;
+    const Place p = place_of(t, S);
+    if (p.tile >= t.tiles) return;
+    const int n0 = p.tile * 256;
+    const int NW = N >> 3;
+
+    const uint32_t row_bytes = (uint32_t)NW * 4u;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
+    const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
+
+    const int  ncol   = n0 + 16 * c;                     // this lane's first column
+    const bool col_ok = ncol < N;
+    const uint32_t kOut = 0xFFFFFFF0u;
+    const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + (uint32_t)ncol / 2u : kOut;
+    const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
+    const uint32_t voff_z = col_ok ? (uint32_t)ncol / 2u : kOut;
+    const uint32_t voff_a = ((uint32_t)c * (uint32_t)K + 8u * b) * 2u;     // rows at or beyond M lie past the buffer
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+    // The k loop runs for one split at a time: normally once, for this workgroup's own split; see
+    // finish_over_splits for when it runs again.  begin_pass() fixes the range and requests its first loads.
+    int      ga = 0, gz = 0, ks1 = 0;
+    SmallStage st[kRing];
+    SmallGroup gcur, gnxt;
+    auto load_stage = [&](SmallStage& sg, int ks) {
+        const bool     dead = ks >= ks1;
+        const uint32_t dm   = dead ? kOut : 0u;
+        const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
+        const uint32_t vw   = voff_w | dm;
+#pragma unroll
+        for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32x2<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+        sg.a = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, voff_a | dm, dead ? 0u : (uint32_t)ks * 64u, 0));
+    };
+    auto load_group = [&](SmallGroup& gr, int g) {
+        const bool     dead = g >= gz;
+        const uint32_t gm   = dead ? kOut : 0u;
+        const uint32_t gg   = dead ? 0u : (uint32_t)g;
+        gr.zq    = buf_load_u32x2(rz, voff_z | gm, gg * row_bytes);
+        gr.sc[0] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u);
+        gr.sc[1] = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u + 16u);
+    };
+    auto begin_pass = [&](int split) {
+        // quantization groups (128 rows = four k-steps) of the split, then of this wave: no division on the device
+        const int gb = split * q_groups + (split < r_groups ? split : r_groups);
+        const int ng = q_groups + (split < r_groups ? 1 : 0);
+        ga = gb + ((wave * ng) >> 2);
+        gz = gb + (((wave + 1) * ng) >> 2);
+        ks1 = 4 * gz;
+        load_group(gnxt, ga);                            // first, so that what waits for it does not wait for the stages too
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kAhead; i++) {
+            load_stage(st[i], 4 * ga + i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- everything the wave needs first is requested before anything else happens ----
+    begin_pass(p.sp);
+    const uint32_t base = flags_as_found(t, S, p, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MORPH_TICK(1);                                       // first loads issued
+
+    // A vector = four rows of one column.  Vector (ln, j): column n0 + 16 (ln & 15) + j, rows
+    // 4 (ln >> 4) ..; its number is id = 16 ln + j, so that 256 consecutive numbers are 256 consecutive
+    // columns.  Only lanes 0 .. 16 nb - 1 hold rows that exist, and only their vectors are numbered.
+    const int nvec = 256 * t.nb;
+    auto vec_sum = [&](int id) {                         // over the waves in the order of their k ranges
+        const int ln = id >> 4, j = (id ^ ln) & 15;
+        f32x4 a = yl[ln * 16 + j];
+#pragma unroll
+        for (int q = 1; q < kSmWaves; q++) a += yl[(q * 64 + ln) * 16 + j];
+        return a;
+    };
+    uint16_t* y = (uint16_t*)t.y;
+    auto vec_store_y = [&](int id, f32x4 acc) {
+        const int ln = id >> 4, j = id & 15;
+        const int col = n0 + 16 * (ln & 15) + j, row = 4 * (ln >> 4);
+        if (col < N) {
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<BF>(acc[r]);
+        }
+    };
+
+    auto run_pass = [&](auto&& sink) {
+        // gacc[2 yb + 8 t]: sum of x * byte, gacc[.. + 1]: sum of x * (byte & 0xF0), over the open group
+        f32x4 gacc[16], xs;
+        float yr[16][RL];                                // running results, column j of the lane, row 4 b + r
+#pragma unroll
+        for (int j = 0; j < 16; j++) {
+            gacc[j] = zero4;
+#pragma unroll
+            for (int r = 0; r < RL; r++) yr[j][r] = 0.f;
+        }
+        xs = zero4;
+        for (int g = ga; g < gz; g++) {
+            gcur = gnxt;
+#pragma unroll
+            for (int u = 0; u < kRing; u++) {
+                load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
+                if (u == 1) load_group(gnxt, g + 1);     // arrives well before the next group ends
+                __builtin_amdgcn_sched_barrier(0);
+                const SmallStage& sg = st[u];
+                const bool first = u == 0;
+                half8_t xa;
+                if constexpr (BF) xa = bf16x8_up64(sg.a);
+                else xa = sg.a;
+                const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
+                xs = mfma_small<BF>(xa, tiny, first ? zero4 : xs);
+#pragma unroll
+                for (int t2 = 0; t2 < 2; t2++) {
+#pragma unroll
+                    for (int yb = 0; yb < 4; yb++) {
+                        uint32_t pr[4], ph[4];
+#pragma unroll
+                        for (int q = 0; q < 4; q++) {
+                            const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
+                            pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                                  : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                            ph[q] = pr[q] & 0x00F000F0u;
+                        }
+                        const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
+                        const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
+                        const int j0 = t2 * 8 + 2 * yb;
+                        gacc[j0]     = mfma_small<BF>(xa, bbyte, first ? zero4 : gacc[j0]);
+                        gacc[j0 + 1] = mfma_small<BF>(xa, bhigh, first ? zero4 : gacc[j0 + 1]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // the group's sums go into the running results
+#pragma unroll
+            for (int t2 = 0; t2 < 2; t2++) {
+                const uint32_t zw  = gcur.zq[t2];
+                const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;     // z of the even columns; 16 z of the odd ones
+#pragma unroll
+                for (int yb = 0; yb < 4; yb++) {
+                    const uint32_t sw = gcur.sc[t2][yb];
+                    const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+                    const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+                    const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
+                    const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
+                    const int j0 = t2 * 8 + 2 * yb;
+#pragma unroll
+                    for (int r = 0; r < RL; r++) {
+                        const float d = gacc[j0][r] - gacc[j0 + 1][r];
+                        yr[j0][r]     = __builtin_fmaf(-c_lo, xs[r], __builtin_fmaf(s_lo, d, yr[j0][r]));
+                        yr[j0 + 1][r] = __builtin_fmaf(-c_hi, xs[r], __builtin_fmaf(s_hi, gacc[j0 + 1][r], yr[j0 + 1][r]));
+                    }
+                }
+            }
+        }
+        // the powers of two come out; every wave leaves its sums in LDS
+        constexpr float kEven = BF ? 0x1p69f : 0x1p24f;  // low-nibble (even) columns
+        constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;  // high-nibble (odd) columns: their sums carry a factor 16
+        if (b < t.nb) {
+#pragma unroll
+            for (int j = 0; j < 16; j++) {
+                f32x4 v = zero4;
+#pragma unroll
+                for (int r = 0; r < RL; r++) v[r] = yr[j][r] * ((j & 1) ? kOdd : kEven);
+                yl[(wave * 64 + lane) * 16 + (j ^ c)] = v;
+            }
+        }
+        __syncthreads();
+        for (int id = tid; id < nvec; id += kSmWaves * 64) sink(id, vec_sum(id));
+    };
+
+    finish_over_splits(t, S, p, nvec, base, &fresh_word, run_pass, begin_pass, vec_store_y);
+}
+
+// ------------------------------------------------------------------------------------------------
+// 17 <= M <= 64, in slices of at most 32 rows = two MFMA tiles.  Wave (kh, ch) = (wave >> 1, wave & 1)
+// takes half kh of the workgroup's quantization groups and columns n0 + 128 ch ..; lane (c, b) the 8
+// columns 8 c .. of those = one packed word per row.  With this many rows the loop is bound by the
+// instructions a wave issues: one wave gets an issue slot only every four to five clocks whatever
+// the instruction (and a second wave per SIMD is out of reach: group sums, running results and the
+// staged loads need more than the 256 registers a wave would then have).
+// ------------------------------------------------------------------------------------------------
+struct MidStage {
+    uint32_t w[8];                               // row 8b + i of the k-step: one packed word = 8 columns
+};
+struct MidGroup {
+    uint32_t zq;                                 // zero points of the lane's 8 columns
+    u32x4    sc;                                 // their scales
+};
+
+template <bool BF>
+__global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
+    const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int M_all, int S,
+    int q_groups, int r_groups, SmallTail t)
+{
+    // During the k loop each wave keeps in its 16 KB two groups of x: 32 rows of 128 k, a row = 16 pieces
+    // of 16 bytes, piece p stored at p ^ (row & 15) -- whole rows come from memory in whole cache
+    // lines (a lane that fetched the 8 k of its own MFMA operand for every step would touch 16 lines
+    // per load and use half of each), and both the store (16 lanes = the 16 pieces of a row) and the
+    // MFMA-shaped load (16 lanes = the same piece of 16 rows) are free of bank conflicts.  After the
+    // loop, the first half holds the results of one tile of 16 rows at a time:
+    // [kh][4-row group b][column of the tile, the 8 of a lane stored at j ^ (c & 7)].
+    __shared__ __align__(16) u32x4 sm[kSmWaves * 1024];
+    __shared__ uint32_t fresh_word;
+
+    MORPH_TICK(0);                                       // kernel entry
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kh = wave >> 1, ch = wave & 1;
+    const int c = lane & 15, b = lane >> 4;
+    const Place p = place_of(t, S);
+    if (p.tile >= t.tiles) return;
+    const int n0 = p.tile * 256;
+    const int NW = N >> 3;
+    // this workgroup's rows: a slice is 32 rows
+    const int M = M_all - 32 * p.slice < 32 ? M_all - 32 * p.slice : 32;
+    const uint16_t* x = (const uint16_t*)x_all + (size_t)(32 * p.slice) * K;
+
+    const uint32_t row_bytes = (uint32_t)NW * 4u;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
+    const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
+
+    const int  ncol   = n0 + 128 * ch + 8 * c;           // this lane's first column
+    const bool col_ok = ncol < N;
+    const uint32_t kOut = 0xFFFFFFF0u;
+    const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + (uint32_t)ncol / 2u : kOut;
+    const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
+    const uint32_t voff_z = col_ok ? (uint32_t)ncol / 2u : kOut;
+    // x of a whole group: load i takes rows 4 i + (lane >> 4), piece (lane & 15) of each; rows at or beyond M lie past the buffer
+    const uint32_t voff_x = ((uint32_t)b * (uint32_t)K + 8u * (uint32_t)c) * 2u;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    u32x4* const xl = sm + wave * 1024;                  // this wave's 16 KB: two buffers of 512 pieces
+
+    int      ga = 0, gz = 0, ks1 = 0;
+    MidStage st[kRing];
+    MidGroup gcur, gnxt;
+    u32x4    xg[8];
+    auto load_stage = [&](MidStage& sg, int ks) {
+        const bool     dead = ks >= ks1;
+        const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
+        const uint32_t vw   = voff_w | (dead ? kOut : 0u);
+#pragma unroll
+        for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+    };
+    auto load_group = [&](MidGroup& gr, int g) {
+        const bool     dead = g >= gz;
+        const uint32_t gm   = dead ? kOut : 0u;
+        const uint32_t gg   = dead ? 0u : (uint32_t)g;
+        gr.zq = buf_load_u32(rz, voff_z | gm, gg * row_bytes);
+        gr.sc = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u);
+    };
+    auto load_xgroup = [&](int g) {
+        const bool     dead = g >= gz;
+        const uint32_t dm   = dead ? kOut : 0u;
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+            xg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (voff_x + (uint32_t)i * 8u * (uint32_t)K) | dm, dead ? 0u : (uint32_t)g * 256u, 0);
+    };
+    auto store_xgroup = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const int row = 4 * i + b;
+            xl[buf * 512 + row * 16 + ((c ^ row) & 15)] = xg[i];
+        }
+    };
+    auto begin_pass = [&](int split) {
+        // quantization groups of the split, then of this wave's half: no division on the device
+        const int gb = split * q_groups + (split < r_groups ? split : r_groups);
+        const int ng = q_groups + (split < r_groups ? 1 : 0);
+        ga = gb + ((kh * ng) >> 1);
+        gz = gb + (((kh + 1) * ng) >> 1);
+        ks1 = 4 * gz;
+        load_group(gnxt, ga);
+        load_xgroup(ga);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kAhead; i++) {
+            load_stage(st[i], 4 * ga + i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    begin_pass(p.sp);
+    const uint32_t base = flags_as_found(t, S, p, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MORPH_TICK(1);                                       // first loads issued
+
+    // A vector = four rows of one column; vector (mt, rq, col): column n0 + col, rows 16 mt + 4 rq ..;
+    // its number is id = 1024 mt + 256 rq + col.
+    constexpr int nvec = 2048;
+    uint16_t* y = (uint16_t*)t.y + (size_t)(32 * p.slice) * N;
+    auto vec_store_y = [&](int id, f32x4 acc) {
+        const int col = n0 + (id & 255), row = 4 * (id >> 8);
+        if (col < N) {
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<BF>(acc[r]);
+        }
+    };
+
+    auto run_pass = [&](auto&& sink) {
+        // gacc[mt][2 yb]: sum of x * byte, gacc[mt][2 yb + 1]: sum of x * (byte & 0xF0), over the open group
+        f32x4 gacc[2][8], xs[2];
+        float yr[2][8][4];                               // running results, column j of the lane, row 16 mt + 4 b + r
+#pragma unroll
+        for (int mt = 0; mt < 2; mt++) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                gacc[mt][j] = zero4;
+#pragma unroll
+                for (int r = 0; r < 4; r++) yr[mt][j][r] = 0.f;
+            }
+            xs[mt] = zero4;
+        }
+        int xb = 0;                                      // the x buffer of the open group
+        store_xgroup(0);
+        for (int g = ga; g < gz; g++) {
+            gcur = gnxt;
+#pragma unroll
+            for (int u = 0; u < kRing; u++) {
+                load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
+                if (u == 0) load_xgroup(g + 1);          // issued before three stages of weights: a wait for it does not wait for them
+                if (u == 1) load_group(gnxt, g + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                const MidStage& sg = st[u];
+                const bool first = u == 0;
+                const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
+                half8_t xa[2];
+#pragma unroll
+                for (int mt = 0; mt < 2; mt++) {
+                    const half8_t xv = bit_cast<half8_t>(xl[xb * 512 + (16 * mt + c) * 16 + ((4 * u + b) ^ c)]);
+                    if constexpr (BF) xa[mt] = bf16x8_up64(xv);
+                    else xa[mt] = xv;
+                    xs[mt] = mfma_small<BF>(xa[mt], tiny, first ? zero4 : xs[mt]);
+                }
+#pragma unroll
+                for (int yb = 0; yb < 4; yb++) {
+                    uint32_t pr[4], ph[4];
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const uint32_t r0 = sg.w[2 * q], r1 = sg.w[2 * q + 1];
+                        pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                              : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                        ph[q] = pr[q] & 0x00F000F0u;
+                    }
+                    const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
+                    const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
+#pragma unroll
+                    for (int mt = 0; mt < 2; mt++) {
+                        gacc[mt][2 * yb]     = mfma_small<BF>(xa[mt], bbyte, first ? zero4 : gacc[mt][2 * yb]);
+                        gacc[mt][2 * yb + 1] = mfma_small<BF>(xa[mt], bhigh, first ? zero4 : gacc[mt][2 * yb + 1]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            store_xgroup(xb ^ 1);                        // the next group's x, requested at the top of this one
+            xb ^= 1;
+            // the group's sums go into the running results
+            const uint32_t zw  = gcur.zq;
+            const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;         // z of the even columns; 16 z of the odd ones
+#pragma unroll
+            for (int yb = 0; yb < 4; yb++) {
+                const uint32_t sw = gcur.sc[yb];
+                const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+                const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+                const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
+                const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
+#pragma unroll
+                for (int mt = 0; mt < 2; mt++) {
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        const float d = gacc[mt][2 * yb][r] - gacc[mt][2 * yb + 1][r];
+                        yr[mt][2 * yb][r]     = __builtin_fmaf(-c_lo, xs[mt][r], __builtin_fmaf(s_lo, d, yr[mt][2 * yb][r]));
+                        yr[mt][2 * yb + 1][r] = __builtin_fmaf(-c_hi, xs[mt][r], __builtin_fmaf(s_hi, gacc[mt][2 * yb + 1][r], yr[mt][2 * yb + 1][r]));
+                    }
+                }
+            }
+        }
+        // the powers of two come out; one tile of 16 rows at a time through LDS, summed over the two halves of K
+        constexpr float kEven = BF ? 0x1p69f : 0x1p24f;  // low-nibble (even) columns
+        constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;  // high-nibble (odd) columns: their sums carry a factor 16
+#pragma unroll
+        for (int mt = 0; mt < 2; mt++) {
+            __syncthreads();                             // every wave is done with its x, or with the tile before
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                f32x4 v;
+#pragma unroll
+                for (int r = 0; r < 4; r++) v[r] = yr[mt][j][r] * ((j & 1) ? kOdd : kEven);
+                sm[kh * 1024 + b * 256 + ch * 128 + c * 8 + (j ^ (c & 7))] = bit_cast<u32x4>(v);
+            }
+            __syncthreads();
+            for (int lid = tid; lid < 1024; lid += kSmWaves * 64) {
+                const int pos = (lid & ~7) | ((lid ^ (lid >> 3)) & 7);      // column 8 c + j sits at j ^ (c & 7)
+                sink(mt * 1024 + lid, bit_cast<f32x4>(sm[pos]) + bit_cast<f32x4>(sm[1024 + pos]));
+            }
+        }
+    };
+
+    finish_over_splits(t, S, p, nvec, base, &fresh_word, run_pass, begin_pass, vec_store_y);
+}
+
+template <class Kernel>
+hipError_t launch_small_with(Kernel kernel, int waves, const SmallArgs& a, hipStream_t st)
 {
     const int G = a.K / kGroup;
     SmallTail t;
@@ -531,7 +672,7 @@ hipError_t launch_small_t(const SmallArgs& a, hipStream_t st)
     t.tiles = a.tiles; t.far = a.far; t.inv_s = (65536 + a.S - 1) / a.S;
     t.sl_shift = a.M > 32 ? 1 : 0;
     const int grid = 8 * ((a.tiles + 7) / 8) * a.S << t.sl_shift;
-    hipLaunchKernelGGL((decode_small_kernel<MT, RL, BF>), dim3(grid), dim3(kSmWaves * 64), 0, st,
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(waves * 64), 0, st,
                        (const uint32_t*)a.w, a.x, a.scales, (const uint32_t*)a.qzeros, a.K, a.N, a.M, a.S, G / a.S, G % a.S, t);
     return hipGetLastError();
 }
@@ -539,9 +680,9 @@ hipError_t launch_small_t(const SmallArgs& a, hipStream_t st)
 template <bool BF>
 hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
 {
-    if (a.M == 1)  return launch_small_t<1, 1, BF>(a, st);
-    if (a.M <= 16) return launch_small_t<1, 4, BF>(a, st);
-    return launch_small_t<2, 4, BF>(a, st);              // beyond 32 rows: two slices
+    if (a.M == 1)  return launch_small_with(decode_small_kernel<1, BF>, kSmWaves, a, st);
+    if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF>, kSmWaves, a, st);
+    return launch_small_with(decode_mid_kernel<BF>, kSmWaves, a, st);      // beyond 32 rows: two slices
 }
 
 }  // namespace
