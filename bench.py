@@ -151,7 +151,7 @@ def main():
     avg_launch_s = sec / (args.steps * launches_per_step)
     roofline = {
         "bound": "hbm",
-        "kernel": "decode_kernel<1, 1, 4, true, false> (W4A16, M <= 16), mean over the 12 launches of a step",
+        "kernel": "decode_small_kernel<RL, false> (W4A16, M <= 16; RL = 1 for M = 1, else 4), mean over the 12 launches of a step",
         "achieved": round(value, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",

@@ -30,8 +30,9 @@
 // four weights for dequantizing them first.
 //
 // Two kernels:
-//   decode_small_kernel, M <= 16: a wave takes 256 columns (16 per lane, 8-byte loads) of all rows;
-//     with one row the fold touches only the one accumulator component that holds it (RL = 1).
+//   decode_small_kernel, M <= 16: a wave takes 256 columns (16 per lane, 8-byte loads) of all rows.
+//     Up to four rows, row m is fed to the MFMA as its row 4 m, which comes out as the first of a
+//     lane's four accumulator components, and the fold touches only that one (RL = 1).
 //   decode_mid_kernel, 17 <= M <= 64: the group sums and running results of 32 rows by 256 columns
 //     do not fit a wave's registers, so a wave takes 128 columns (8 per lane, 4-byte loads) of a slice
 //     of at most 32 rows, two waves side by side and two along K; beyond 32 rows two workgroups on
@@ -235,7 +236,8 @@ __device__ __forceinline__ uint32_t flags_as_found(const SmallTail& t, int S, co
 }
 
 // ------------------------------------------------------------------------------------------------
-// M <= 16.  RL: accumulator components per lane that hold rows which exist (1: M = 1; 4 otherwise).
+// M <= 16.  RL: accumulator components per lane that hold rows (1: M <= 4, x row m is MFMA row 4 m and
+// lane (c, b) holds row b of its columns; 4 otherwise, lane (c, b) holds rows 4 b .. 4 b + 3).
 // BF: x and y are bfloat16.
 // ------------------------------------------------------------------------------------------------
 struct SmallStage {
@@ -277,7 +279,9 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + (uint32_t)ncol / 2u : kOut;
     const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
     const uint32_t voff_z = col_ok ? (uint32_t)ncol / 2u : kOut;
-    const uint32_t voff_a = ((uint32_t)c * (uint32_t)K + 8u * b) * 2u;     // rows at or beyond M lie past the buffer
+    // the x row this lane feeds to the MFMA as its row c; rows at or beyond M lie past the buffer
+    const uint32_t voff_a = RL == 1 ? ((c & 3) ? kOut : ((uint32_t)(c >> 2) * (uint32_t)K + 8u * b) * 2u)
+                                    : ((uint32_t)c * (uint32_t)K + 8u * b) * 2u;
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
     // The k loop runs for one split at a time: normally once, for this workgroup's own split; see
@@ -417,10 +421,15 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
         // the powers of two come out; every wave leaves its sums in LDS
         constexpr float kEven = BF ? 0x1p69f : 0x1p24f;  // low-nibble (even) columns
         constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;  // high-nibble (odd) columns: their sums carry a factor 16
-        if (b < t.nb) {
+        if constexpr (RL == 1) {
+            // lane (c, b) holds row b of column j: the four lanes of a column make up its vector
+            float* const yf = reinterpret_cast<float*>(yl);
+#pragma unroll
+            for (int j = 0; j < 16; j++) yf[((wave * 64 + c) * 16 + (j ^ c)) * 4 + b] = yr[j][0] * ((j & 1) ? kOdd : kEven);
+        } else if (b < t.nb) {
 #pragma unroll
             for (int j = 0; j < 16; j++) {
-                f32x4 v = zero4;
+                f32x4 v;
 #pragma unroll
                 for (int r = 0; r < RL; r++) v[r] = yr[j][r] * ((j & 1) ? kOdd : kEven);
                 yl[(wave * 64 + lane) * 16 + (j ^ c)] = v;
@@ -680,7 +689,7 @@ hipError_t launch_small_with(Kernel kernel, int waves, const SmallArgs& a, hipSt
 template <bool BF>
 hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
 {
-    if (a.M == 1)  return launch_small_with(decode_small_kernel<1, BF>, kSmWaves, a, st);
+    if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, BF>, kSmWaves, a, st);
     if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF>, kSmWaves, a, st);
     return launch_small_with(decode_mid_kernel<BF>, kSmWaves, a, st);      // beyond 32 rows: two slices
 }
