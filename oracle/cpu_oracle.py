@@ -27,6 +27,10 @@ What is computed (paper Section 4.3, footnote: weight-only INT4; Section 5.2:
                        activations, token by token, averaged; LIS = a1 LTS + a2 LRS + b MDS
   *_bf16           O11 the same linear maps with x, dense weights and y in bfloat16 (arrays of
                        numpy.uint16 bit patterns: numpy has no bfloat16); records unchanged
+  native W4 codes  O12 the same 4-bit codes stored in the order the decode kernel's lanes consume
+                       them (a storage format of this library, not of the paper: the paper's
+                       Section 4.3 only says the variants are pre-quantized and preloaded): where
+                       nibble (k, n) sits, written out element by element
   layer record     O8  the bytes of one layer (its four linears, in either form) as
                        they sit in the pinned host pool and in the layer's device slot,
                        and what an in-place swap leaves in the slot (Section 4.3,
@@ -138,6 +142,65 @@ def dequant_w4(qw, sc, qz, G: int = 128, dtype=np.float32) -> np.ndarray:
                                       K, N, G, _p(D, _u16p))
         return D.view(np.float16)
     raise TypeError("dtype must be float32 or float16")
+
+
+def native_w4_bytes(K: int, N: int) -> int:
+    """O12.  Bytes of the native code array: column tiles of 256 (the last one padded), k-steps of 32
+    rows, 4096 bytes per (tile, k-step) block."""
+    return ((N + 255) // 256) * (K // 32) * 4096
+
+
+def native_w4_position(k, n, K: int):
+    """O12.  Where the code of row k, column n sits in the native array: (byte offset, nibble), nibble 0
+    = bits 3..0.  Works on integers and on numpy integer arrays alike.
+
+    A block = one column tile of 256 and one k-step of 32 rows, blocks in (tile, k-step) order.  Inside
+    a block the decode kernel's lane (c, b), c = 0..15, b = 0..3, lane number 16 b + c, owns columns
+    16 c .. 16 c + 15 of the tile and rows 8 b .. 8 b + 7 of the k-step: 64 bytes, fetched by four
+    16-byte loads.  Load i = 2 h + p covers column half h (columns 8 h .. 8 h + 7 of the lane's 16) and
+    column-pair pair p (of the four pairs (0,1) (2,3) (4,5) (6,7) in that half, pairs 2 p and 2 p + 1);
+    a load's 1024 bytes hold the 64 lanes' 16 bytes in lane order.  A lane's 16 bytes are four words,
+    word q for rows 2 q, 2 q + 1 of its 8; a word's byte 2 r + e belongs to row 2 q + r and column
+    pair 2 p + e; a byte holds the pair's even column in its low nibble, the odd one in its high."""
+    KS = K // 32
+    tile, cn = n // 256, n % 256
+    c, col = cn // 16, cn % 16
+    h, pair, odd = col // 8, (col % 8) // 2, col % 2
+    p, e = pair // 2, pair % 2
+    ks, kr = k // 32, k % 32
+    b, q, r = kr // 8, (kr % 8) // 2, kr % 2
+    lane, i = 16 * b + c, 2 * h + p
+    byte = (((tile * KS + ks) * 4 + i) * 64 + lane) * 16 + 4 * q + 2 * r + e
+    return byte, odd
+
+
+def repack_w4_native(qw: np.ndarray) -> np.ndarray:
+    """O12.  Canonical packed codes uint32 [K, N/8] -> native array uint8 [native_w4_bytes(K, N)];
+    columns of the last tile beyond N hold code 0."""
+    qw = _c(qw, np.uint32)
+    K, N = qw.shape[0], qw.shape[1] * 8
+    assert K % 32 == 0
+    codes = unpack_w4(qw, N)
+    kk, nn = np.meshgrid(np.arange(K, dtype=np.int64), np.arange(N, dtype=np.int64), indexing="ij")
+    byte, odd = native_w4_position(kk, nn, K)
+    out = np.zeros(native_w4_bytes(K, N), np.uint8)
+    low = odd == 0
+    out[byte[low]] |= codes[low]                      # every byte is named once per nibble
+    out[byte[~low]] |= codes[~low] << 4
+    return out
+
+
+def unpack_w4_native(native: np.ndarray, K: int, N: int) -> np.ndarray:
+    """O12.  Native array -> canonical packed codes uint32 [K, N/8]."""
+    native = _c(native, np.uint8)
+    assert native.size == native_w4_bytes(K, N) and N % 8 == 0
+    kk, nn = np.meshgrid(np.arange(K, dtype=np.int64), np.arange(N, dtype=np.int64), indexing="ij")
+    byte, odd = native_w4_position(kk, nn, K)
+    codes = (native[byte] >> (4 * odd).astype(np.uint8)) & 0xF
+    qw = np.zeros((K, N // 8), np.uint32)
+    for j in range(8):
+        qw |= codes[:, j::8].astype(np.uint32) << np.uint32(4 * j)
+    return qw
 
 
 def linear_w4a16(x, qw, sc, qz, G: int = 128) -> np.ndarray:

@@ -809,3 +809,100 @@ def test_p12_identity_and_numpy_matmul(oracle, bits):
     # bfloat16 form of the weights: one rounding of the exact value (torch's conversion as the second opinion)
     want = torch.from_numpy(D).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(oracle.dequant_bf16(bits, qw, sc, qz), want)
+
+
+# ---------------------------------------------------------------------------------------------
+# O12: the native storage order of the 4-bit codes (this library's format for the decode kernel)
+# ---------------------------------------------------------------------------------------------
+def _native_golden():
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "native_w4_layout.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(tuple(int(v) for v in line.split()))
+    return rows
+
+
+def _native_pins_hold(position, repack, unpack, nbytes):
+    """The pins of O12 as a predicate over the oracle's functions (so that planted mistakes can be
+    shown to fail them): hand-worked positions; one nibble in, one nibble out, inside its block; round
+    trip; size."""
+    K, N = 128, 512
+    for k, n, byte, nib in _native_golden():
+        b, o = position(k, n, K)
+        if (int(b), int(o)) != (byte, nib):
+            return False
+    if nbytes(K, N) != 2 * 4 * 4096 or nbytes(256, 264) != 2 * 8 * 4096:
+        return False
+    rng = np.random.default_rng(5)
+    # a single code in an otherwise empty matrix lands in exactly one nibble, inside its own block
+    for _ in range(40):
+        k, n, code = int(rng.integers(0, K)), int(rng.integers(0, N)), int(rng.integers(1, 16))
+        qw = np.zeros((K, N // 8), np.uint32)
+        qw[k, n // 8] = np.uint32(code << (4 * (n % 8)))
+        nat = repack(qw)
+        nz = np.flatnonzero(nat)
+        if nz.size != 1 or nat.size != nbytes(K, N):
+            return False
+        block = (n // 256) * (K // 32) + k // 32
+        if nz[0] // 4096 != block or int(nat[nz[0]]) not in (code, code << 4):
+            return False
+    # every code survives the round trip, ragged last tile included
+    for (K2, N2) in ((128, 512), (256, 264), (32, 8)):
+        qw = rng.integers(0, 2 ** 32, (K2, N2 // 8), dtype=np.uint64).astype(np.uint32)
+        nat = repack(qw)
+        if not np.array_equal(unpack(nat, K2, N2), qw):
+            return False
+        # the padding columns of the last tile hold code 0: the nibble counts agree
+        total = sum(int(np.count_nonzero((nat >> s) & 0xF)) for s in (0, 4))
+        codes = sum(int(np.count_nonzero((qw >> np.uint32(4 * j)) & 0xF)) for j in range(8))
+        if total != codes:
+            return False
+    return True
+
+
+def test_p13_native_code_order_pinned_by_hand_positions(oracle):
+    assert _native_pins_hold(oracle.native_w4_position, oracle.repack_w4_native, oracle.unpack_w4_native, oracle.native_w4_bytes)
+
+
+def test_p13_native_pins_catch_planted_mistakes(oracle):
+    """Plausible slips in the position formula (swapped roles, a forgotten factor) must fail the pins."""
+    def variant(**swap):
+        def position(k, n, K):
+            KS = K // 32
+            tile, cn = n // 256, n % 256
+            c, col = cn // 16, cn % 16
+            h, pair, odd = col // 8, (col % 8) // 2, col % 2
+            p, e = pair // 2, pair % 2
+            ks, kr = k // 32, k % 32
+            b, q, r = kr // 8, (kr % 8) // 2, kr % 2
+            if swap.get("pe"):
+                p, e = pair % 2, pair // 2
+            if swap.get("qr"):
+                q, r = kr % 4, (kr % 8) // 4
+            lane = 16 * b + c if not swap.get("lane") else 4 * c + b
+            i = 2 * h + p if not swap.get("load") else 2 * p + h
+            blk = tile * KS + ks if not swap.get("blk") else ks * ((512 + 255) // 256) + tile
+            byte = ((blk * 4 + i) * 64 + lane) * 16 + 4 * q + (2 * r + e if not swap.get("re") else 2 * e + r)
+            return byte, (odd if not swap.get("nib") else 1 - odd)
+        def repack(qw):
+            K, N = qw.shape[0], qw.shape[1] * 8
+            codes = oracle.unpack_w4(qw, N)
+            kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+            byte, odd = position(kk, nn, K)
+            out = np.zeros(oracle.native_w4_bytes(K, N), np.uint8)
+            np.bitwise_or.at(out, byte, (codes << (4 * odd)).astype(np.uint8))
+            return out
+        def unpack(nat, K, N):
+            kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+            byte, odd = position(kk, nn, K)
+            codes = (nat[byte] >> (4 * odd).astype(np.uint8)) & 0xF
+            qw = np.zeros((K, N // 8), np.uint32)
+            for j in range(8):
+                qw |= codes[:, j::8].astype(np.uint32) << np.uint32(4 * j)
+            return qw
+        return position, repack, unpack
+    assert _native_pins_hold(*variant(), oracle.native_w4_bytes)                 # the faithful copy passes
+    for slip in ("pe", "qr", "lane", "load", "blk", "re", "nib"):
+        assert not _native_pins_hold(*variant(**{slip: True}), oracle.native_w4_bytes), slip
