@@ -112,6 +112,35 @@ int morph_quantize_layer(const void* w, int w_dtype, int32_t* qweight, void* sca
 int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_t* qzeros,
                         void* out, int out_dtype, int K, int N, int group_size, void* stream);
 
+/* ---- native storage order of the 4-bit codes ----
+ * The paper (Section 4.3) has the quantized variants of a layer prepared ahead of time and kept in
+ * pinned host memory; how their bytes are ordered is the implementation's business.  The canonical
+ * record above is the interchange form; the decode kernel for at most 16 rows can also read the codes
+ * in the order its lanes consume them, which makes every load of a wave one contiguous kilobyte and
+ * halves the number of loads.  Scales and zero points stay as they are.
+ *   native array: morph_w4_native_bytes(K, N) bytes = ceil(N / 256) * (K / 32) blocks of 4096 bytes, one
+ *   per (column tile of 256, k-step of 32 rows), tiles outermost.  In a block, for b = 0..3, c = 0..15,
+ *   h, p = 0..1, q = 0..3, r, e = 0..1: the byte at ((2 h + p) * 64 + 16 b + c) * 16 + 4 q + 2 r + e holds,
+ *   for row 32 ks + 8 b + 2 q + r, the codes of columns 256 tile + 16 c + 8 h + 4 p + 2 e (low nibble) and
+ *   the next one (high nibble), i.e. byte 2 p + e of canonical word 32 tile + 2 c + h of that row.  Columns
+ *   at or beyond N (padding of the last tile) hold code 0.
+ * morph_repack_w4_native / morph_unpack_w4_native convert between the two (device arrays, exact);
+ * morph_quantize_layer_native = morph_quantize_layer into qweight_tmp (canonical size) followed by the
+ * repack; morph_dequantize_w4_native is morph_dequantize_w4 on the native array (the same values);
+ * morph_linear_w4a16_native is morph_linear_w4a16 on it for M <= 16 and fp16 activations (the same
+ * bits: the arithmetic and its order do not change), MORPH_ERR_UNSUPPORTED otherwise; workspace of
+ * morph_workspace_bytes(MORPH_KIND_W4A16, M, K, N).  Arguments, alignment and errors as above. */
+size_t morph_w4_native_bytes(int K, int N);
+int morph_repack_w4_native(const int32_t* qweight, void* native, int K, int N, void* stream);
+int morph_unpack_w4_native(const void* native, int32_t* qweight, int K, int N, void* stream);
+int morph_quantize_layer_native(const void* w, int w_dtype, void* native, void* scales, int32_t* qzeros,
+                                int32_t* qweight_tmp, int K, int N, int group_size, void* stream);
+int morph_dequantize_w4_native(const void* native, const void* scales, const int32_t* qzeros, void* out,
+                               int out_dtype, int K, int N, int group_size, void* stream);
+int morph_linear_w4a16_native(const void* x, const void* native, const void* scales, const int32_t* qzeros,
+                              void* y, int M, int K, int N, int group_size, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
 /* ---- the 8-bit weight-only variant (Section 4.3 lists INT8 next to INT4 among the variants of
  * a layer; Appendix C: FP16, W8 and W4 are preloaded) ----
  * The same scheme with 255 steps: uint8 codes and zero points, FOUR per 32-bit word along N

@@ -37,6 +37,8 @@ EXPORTS = [
     "morph_linear_bf16", "morph_linear_w4a16_bf16", "morph_linear_w8a16_bf16", "morph_cosine_rows_bf16",
     "morph_glue_bf16", "morph_stack_forward_bf16",
     "morph_linear_w4a16_noalloc", "morph_noalloc_scratch_bytes",
+    "morph_w4_native_bytes", "morph_repack_w4_native", "morph_unpack_w4_native", "morph_quantize_layer_native",
+    "morph_dequantize_w4_native", "morph_linear_w4a16_native",
 ]
 
 
@@ -72,6 +74,13 @@ def lib() -> ctypes.CDLL:
     L.morph_linear_w4a16_noalloc.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_noalloc_scratch_bytes.argtypes = []
     L.morph_noalloc_scratch_bytes.restype = sz
+    L.morph_w4_native_bytes.argtypes = [i, i]
+    L.morph_w4_native_bytes.restype = sz
+    L.morph_repack_w4_native.argtypes = [vp, vp, i, i, vp]
+    L.morph_unpack_w4_native.argtypes = [vp, vp, i, i, vp]
+    L.morph_quantize_layer_native.argtypes = [vp, i, vp, vp, vp, vp, i, i, i, vp]
+    L.morph_dequantize_w4_native.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
+    L.morph_linear_w4a16_native.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.morph_quantize_layer.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w4.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_linear_w8a16.argtypes = L.morph_linear_w4a16.argtypes
@@ -229,6 +238,64 @@ def linear_w4a16_noalloc(x, qweight, scales, qzeros, out, group_size: int = GROU
                                             _dev(out, torch.float16, "y"), M, K, N, group_size, _stream()),
            "morph_linear_w4a16_noalloc")
     return out
+
+
+def w4_native_bytes(K: int, N: int) -> int:
+    return int(lib().morph_w4_native_bytes(K, N))
+
+
+def repack_w4_native(qweight: torch.Tensor) -> torch.Tensor:
+    """Canonical packed codes int32 [K, N/8] -> the native array (uint8, morph_w4_native_bytes(K, N))."""
+    K, N = qweight.shape[0], qweight.shape[1] * 8
+    out = torch.empty(w4_native_bytes(K, N), dtype=torch.uint8, device=qweight.device)
+    _check(lib().morph_repack_w4_native(_dev(qweight, torch.int32, "qweight"), out.data_ptr(), K, N, _stream()),
+           "morph_repack_w4_native")
+    return out
+
+
+def unpack_w4_native(native: torch.Tensor, K: int, N: int) -> torch.Tensor:
+    assert native.numel() == w4_native_bytes(K, N)
+    out = torch.empty((K, N // 8), dtype=torch.int32, device=native.device)
+    _check(lib().morph_unpack_w4_native(_dev(native, torch.uint8, "native"), out.data_ptr(), K, N, _stream()),
+           "morph_unpack_w4_native")
+    return out
+
+
+def quantize_layer_native(w: torch.Tensor, group_size: int = GROUP):
+    """w [K,N] on the GPU -> (native codes uint8, scales fp16 [K/128,N], qzeros int32 [K/128,N/8])."""
+    K, N = w.shape
+    dt = _DTYPES[w.dtype]
+    nat = torch.empty(w4_native_bytes(K, N), dtype=torch.uint8, device=w.device)
+    tmp = torch.empty((K, N // 8), dtype=torch.int32, device=w.device)
+    sc = torch.empty((K // GROUP, N), dtype=torch.float16, device=w.device)
+    qz = torch.empty((K // GROUP, N // 8), dtype=torch.int32, device=w.device)
+    _check(lib().morph_quantize_layer_native(_dev(w, w.dtype, "w"), dt, nat.data_ptr(), sc.data_ptr(), qz.data_ptr(),
+                                             tmp.data_ptr(), K, N, group_size, _stream()), "morph_quantize_layer_native")
+    return nat, sc, qz
+
+
+def dequantize_w4_native(native, scales, qzeros, dtype=torch.float32, group_size: int = GROUP) -> torch.Tensor:
+    N = scales.shape[1]
+    K = scales.shape[0] * GROUP
+    out = torch.empty((K, N), dtype=dtype, device=native.device)
+    _check(lib().morph_dequantize_w4_native(_dev(native, torch.uint8, "native"), _dev(scales, torch.float16, "scales"),
+                                            _dev(qzeros, torch.int32, "qzeros"), _dev(out, dtype, "out"), _DTYPES[dtype], K, N,
+                                            group_size, _stream()), "morph_dequantize_w4_native")
+    return out
+
+
+def linear_w4a16_native(x, native, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:
+    """morph_linear_w4a16 on the native code array (M <= 16, fp16)."""
+    M, K = x.shape
+    N = scales.shape[1]
+    assert native.numel() == w4_native_bytes(K, N), (native.numel(), K, N)
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    wp, wb = _ws_args(ws)
+    _check(lib().morph_linear_w4a16_native(_dev(x, torch.float16, "x"), _dev(native, torch.uint8, "native"),
+                                           _dev(scales, torch.float16, "scales"), _dev(qzeros, torch.int32, "qzeros"),
+                                           _dev(y, torch.float16, "y"), M, K, N, group_size, wp, wb, _stream()),
+           "morph_linear_w4a16_native")
+    return y
 
 
 def linear_w8a16(x, qweight, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:

@@ -96,7 +96,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         if (pl.small) {
             SmallArgs s;
             s.x = x; s.w = w; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
-            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf;
+            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf; s.native = 0;
             s.slots = nullptr; s.ctl = nullptr;
             if (pl.S > 1) {
                 if (!workspace || workspace_bytes < kScratchOffset) return MORPH_ERR_WORKSPACE;
@@ -204,7 +204,7 @@ int morph_linear_w4a16_noalloc(const void* x, const int32_t* qweight, const void
     if (pl.S > 1 && (pl.partial_bytes > kNoAllocSlotBytes || pl.tiles > 256)) return MORPH_ERR_UNSUPPORTED;   // beyond the array
     SmallArgs s;
     s.x = x; s.w = qweight; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
-    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = 0; s.bf = 0;
+    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = 0; s.bf = 0; s.native = 0;
     s.slots = nullptr; s.ctl = nullptr;
     if (pl.S > 1) {
         unsigned char* p = scratch_on_current_device();
@@ -306,6 +306,74 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
                         int out_dtype, int K, int N, int group_size, void* stream)
 {
     return dequantize_any(4, qweight, scales, qzeros, out, out_dtype, K, N, group_size, stream);
+}
+
+// ---- the native storage order of the 4-bit codes ----
+size_t morph_w4_native_bytes(int K, int N)
+{
+    if (check_shape(1, K, N) != MORPH_OK) return 0;
+    return (size_t)((N + 255) / 256) * (size_t)(K / 32) * 4096;
+}
+
+int morph_repack_w4_native(const int32_t* qweight, void* native, int K, int N, void* stream)
+{
+    if (!qweight || !native) return MORPH_ERR_NULL;
+    if (int rc = check_shape(1, K, N)) return rc;
+    if (!aligned16(qweight) || !aligned16(native)) return MORPH_ERR_ALIGN;
+    if (morph_w4_native_bytes(K, N) >= k4G) return MORPH_ERR_UNSUPPORTED;
+    return launch_repack_native(reinterpret_cast<const uint32_t*>(qweight), native, K, N, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+int morph_unpack_w4_native(const void* native, int32_t* qweight, int K, int N, void* stream)
+{
+    if (!qweight || !native) return MORPH_ERR_NULL;
+    if (int rc = check_shape(1, K, N)) return rc;
+    if (!aligned16(qweight) || !aligned16(native)) return MORPH_ERR_ALIGN;
+    if (K > 65535 || morph_w4_native_bytes(K, N) >= k4G) return MORPH_ERR_UNSUPPORTED;
+    return launch_unpack_native(native, reinterpret_cast<uint32_t*>(qweight), K, N, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+int morph_quantize_layer_native(const void* w, int w_dtype, void* native, void* scales, int32_t* qzeros,
+                                int32_t* qweight_tmp, int K, int N, int group_size, void* stream)
+{
+    if (!native) return MORPH_ERR_NULL;
+    if (int rc = quantize_any(4, w, w_dtype, qweight_tmp, scales, qzeros, K, N, group_size, stream)) return rc;
+    return morph_repack_w4_native(qweight_tmp, native, K, N, stream);
+}
+
+int morph_dequantize_w4_native(const void* native, const void* scales, const int32_t* qzeros, void* out,
+                               int out_dtype, int K, int N, int group_size, void* stream)
+{
+    if (!native || !scales || !qzeros || !out) return MORPH_ERR_NULL;
+    if (group_size != MORPH_GROUP_SIZE) return MORPH_ERR_SHAPE;
+    if (out_dtype != MORPH_DTYPE_F32 && out_dtype != MORPH_DTYPE_F16 && out_dtype != MORPH_DTYPE_BF16) return MORPH_ERR_SHAPE;
+    if (int rc = check_shape(1, K, N)) return rc;
+    if (!aligned16(native) || !aligned16(scales) || !aligned16(qzeros) || !aligned16(out)) return MORPH_ERR_ALIGN;
+    if (K > 65535 || morph_w4_native_bytes(K, N) >= k4G) return MORPH_ERR_UNSUPPORTED;
+    return launch_dequantize_native(native, scales, reinterpret_cast<const uint32_t*>(qzeros), out, out_dtype, K, N,
+                                    (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+}
+
+int morph_linear_w4a16_native(const void* x, const void* native, const void* scales, const int32_t* qzeros,
+                              void* y, int M, int K, int N, int group_size, void* workspace,
+                              size_t workspace_bytes, void* stream)
+{
+    if (group_size != MORPH_GROUP_SIZE) return (x && native && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
+    if (int rc = validate_linear(MORPH_KIND_W4A16, x, native, scales, qzeros, y, M, K, N)) return rc;
+    if (M > 16 || morph_w4_native_bytes(K, N) >= k4G) return MORPH_ERR_UNSUPPORTED;
+    const DecodePlan pl = plan_decode(MORPH_KIND_W4A16, M, K, N);
+    if (!pl.small) return MORPH_ERR_UNSUPPORTED;         // only the kernel for at most 16 rows reads this order
+    SmallArgs s;
+    s.x = x; s.w = native; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
+    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = 0; s.native = 1;
+    s.slots = nullptr; s.ctl = nullptr;
+    if (pl.S > 1) {
+        if (!workspace || workspace_bytes < kScratchOffset) return MORPH_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
+        s.ctl   = reinterpret_cast<int*>(workspace) + kDepartBase;
+        s.slots = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
+    }
+    return launch_decode_small(s, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
 }
 
 int morph_quantize_layer_w8(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,

@@ -241,7 +241,8 @@ __device__ __forceinline__ uint32_t flags_as_found(const SmallTail& t, int S, co
 // BF: x and y are bfloat16.
 // ------------------------------------------------------------------------------------------------
 struct SmallStage {
-    u32x2   w[8];                                // row 8b + i of the k-step: two packed words = 16 columns
+    u32x4   w[4];                                // canonical codes: words (2 i, 2 i + 1) = row 8b + i of the k-step, two packed words = 16 columns each;
+                                                 // native codes: load i of the lane's 64 bytes
     half8_t a;                                   // x row (lane & 15), 8 consecutive k
 };
 struct SmallGroup {
@@ -249,7 +250,10 @@ struct SmallGroup {
     u32x4 sc[2];                                 // their scales
 };
 
-template <int RL, bool BF>
+// NAT: the codes come in the native storage order (see quant.hip): a block of 4096 bytes per (column
+// tile, k-step), in it 16 contiguous bytes per lane and load -- a load instruction reads 1 KB in one
+// piece, and a step takes four loads instead of eight.
+template <int RL, bool BF, bool NAT>
 __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int M, int S,
     int q_groups, int r_groups, SmallTail t)
@@ -268,7 +272,8 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     const int NW = N >> 3;
 
     const uint32_t row_bytes = (uint32_t)NW * 4u;
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
+    const uint32_t ksteps = (uint32_t)K >> 5;
+    const __amdgpu_buffer_rsrc_t rw = NAT ? make_rsrc(w, (uint32_t)t.tiles * ksteps * 4096u) : make_rsrc(w, (uint32_t)K * row_bytes);
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
     const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
@@ -293,9 +298,19 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
         const bool     dead = ks >= ks1;
         const uint32_t dm   = dead ? kOut : 0u;
         const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
-        const uint32_t vw   = voff_w | dm;
+        if constexpr (NAT) {
+            const uint32_t sn = dead ? 0u : ((uint32_t)p.tile * ksteps + (uint32_t)ks) * 4096u;
 #pragma unroll
-        for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32x2<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+            for (int i = 0; i < 4; i++) sg.w[i] = buf_load_u32x4<kAuxStream>(rw, ((uint32_t)lane * 16u) | dm, sn + (uint32_t)i * 1024u);
+        } else {
+            const uint32_t vw = voff_w | dm;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const u32x2 v = buf_load_u32x2<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+                sg.w[i >> 1][2 * (i & 1)] = v[0];
+                sg.w[i >> 1][2 * (i & 1) + 1] = v[1];
+            }
+        }
         sg.a = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, voff_a | dm, dead ? 0u : (uint32_t)ks * 64u, 0));
     };
     auto load_group = [&](SmallGroup& gr, int g) {
@@ -382,9 +397,16 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
                         uint32_t pr[4], ph[4];
 #pragma unroll
                         for (int q = 0; q < 4; q++) {
-                            const uint32_t r0 = sg.w[2 * q][t2], r1 = sg.w[2 * q + 1][t2];
-                            pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
-                                  : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                            if constexpr (NAT) {
+                                // word q of load 2 t2 + yb / 2: bytes (yb & 1) and 2 + (yb & 1) are rows 2 q and 2 q + 1
+                                const uint32_t wq = sg.w[2 * t2 + (yb >> 1)][q];
+                                pr[q] = (yb & 1) ? __builtin_amdgcn_perm(0u, wq, 0x0c030c01u) : (wq & 0x00FF00FFu);
+                            } else {
+                                // row 8b + i sits in words (2 i, 2 i + 1) of the stage
+                                const uint32_t r0 = sg.w[q][t2], r1 = sg.w[q][2 + t2];
+                                pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                                      : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                            }
                             ph[q] = pr[q] & 0x00F000F0u;
                         }
                         const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
@@ -689,8 +711,14 @@ hipError_t launch_small_with(Kernel kernel, int waves, const SmallArgs& a, hipSt
 template <bool BF>
 hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
 {
-    if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, BF>, kSmWaves, a, st);
-    if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF>, kSmWaves, a, st);
+    if (a.native) {
+        if constexpr (BF) return hipErrorInvalidValue;
+        else if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, false, true>, kSmWaves, a, st);
+        else if (a.M <= 16) return launch_small_with(decode_small_kernel<4, false, true>, kSmWaves, a, st);
+        else return hipErrorInvalidValue;
+    }
+    if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, BF, false>, kSmWaves, a, st);
+    if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF, false>, kSmWaves, a, st);
     return launch_small_with(decode_mid_kernel<BF>, kSmWaves, a, st);      // beyond 32 rows: two slices
 }
 

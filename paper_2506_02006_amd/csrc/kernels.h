@@ -14,6 +14,12 @@ hipError_t launch_quantize(int bits, const void* w, int w_dtype, uint32_t* qweig
 hipError_t launch_dequantize(int bits, const uint32_t* qweight, const void* scales, const uint32_t* qzeros,
                              void* out, int out_dtype, int K, int N, hipStream_t st);
 
+// the native storage order of the 4-bit codes (quant.hip): canonical -> native, back, and the verification dequantizer on it
+hipError_t launch_repack_native(const uint32_t* qweight, void* native, int K, int N, hipStream_t st);
+hipError_t launch_unpack_native(const void* native, uint32_t* qweight, int K, int N, hipStream_t st);
+hipError_t launch_dequantize_native(const void* native, const void* scales, const uint32_t* qzeros,
+                                    void* out, int out_dtype, int K, int N, hipStream_t st);
+
 // ---- decode, M <= 64 (decode.hip) ----
 struct DecodeArgs {
     const void*     x;         // fp16 [M,K]
@@ -67,7 +73,7 @@ hipError_t launch_decode(int q, const DecodeArgs& a, hipStream_t st);
 // ---- 4-bit weights, M <= 16 (decode_small.hip) ----
 struct SmallArgs {
     const void* x;         // fp16 / bfloat16 [M,K]
-    const void* w;         // uint32 [K,N/8]
+    const void* w;         // uint32 [K,N/8], or the native array of the codes (native = 1)
     const void* scales;    // fp16 [K/128,N]
     const void* qzeros;    // uint32 [K/128,N/8]
     void*       y;         // fp16 / bfloat16 [M,N]
@@ -79,6 +85,7 @@ struct SmallArgs {
     int         polls;     // looks at the others' flags before a workgroup gives up
     int         far;       // hand-over always written through to memory, never left in an L2 (test hook)
     int         bf;
+    int         native;    // w is in the native storage order (M <= 16, fp16 only)
 };
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st);
 

@@ -139,8 +139,58 @@ __global__ __launch_bounds__(256) void quantize_kernel(const WT* __restrict__ w,
     }
 }
 
+// ---- the native storage order of the 4-bit codes (what decode_small.hip's lanes consume) ----
+// A block = one column tile of 256 and one k-step of 32 rows, 4096 bytes, blocks in (tile, k-step)
+// order.  Lane (c, b) of the decode kernel (lane number 16 b + c) owns columns 16 c .. 16 c + 15 of
+// the tile and rows 8 b .. 8 b + 7 of the k-step: four 16-byte loads, load i = 2 h + p for column half
+// h and byte pair p of the canonical word of that half; a load's 1024 bytes hold the 64 lanes' 16
+// bytes in lane order; a lane's 16 bytes are four words, word q for rows 2 q, 2 q + 1 of its 8; byte
+// 2 r + e of a word is byte 2 p + e of the canonical word (columns 8 h + 4 p + 2 e, + 1) of row 2 q + r.
+//
+// Canonical word wd (columns 8 wd ..) of row k, gathered from the native array.
+__device__ __forceinline__ uint32_t native_word(const uint8_t* __restrict__ nat, int KS, int k, int wd)
+{
+    const int tile = wd >> 5, c = (wd & 31) >> 1, h = wd & 1;
+    const int ks = k >> 5, kr = k & 31, b = kr >> 3, q = (kr & 7) >> 1, r = kr & 1;
+    const uint8_t* blk = nat + ((size_t)tile * KS + ks) * 4096 + (size_t)(16 * b + c) * 16 + 4 * q + 2 * r;
+    uint32_t out = 0;
+#pragma unroll
+    for (int y = 0; y < 4; y++) out |= (uint32_t)blk[(2 * h + (y >> 1)) * 1024 + (y & 1)] << (8 * y);
+    return out;
+}
+
+// One thread per word of the native array: its four bytes come from two canonical words (rows 2 q,
+// 2 q + 1); words of columns at or beyond N (the padding of the last tile) are zero.
+__global__ __launch_bounds__(256) void repack_native_kernel(const uint32_t* __restrict__ qweight, uint32_t* __restrict__ nat,
+                                                            int K, int N, size_t words)
+{
+    const size_t wi = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (wi >= words) return;
+    const int KS = K >> 5, NW = N >> 3;
+    const int q = (int)(wi & 3), lane = (int)((wi >> 2) & 63), i = (int)((wi >> 8) & 3);
+    const size_t blk = wi >> 10;
+    const int ks = (int)(blk % KS), tile = (int)(blk / KS);
+    const int c = lane & 15, b = lane >> 4, h = i >> 1, p = i & 1;
+    const int wd = tile * 32 + 2 * c + h, k = ks * 32 + 8 * b + 2 * q;
+    uint32_t out = 0;
+    if (wd < NW) {
+        const uint32_t w0 = qweight[(size_t)k * NW + wd], w1 = qweight[(size_t)(k + 1) * NW + wd];
+        out = ((w0 >> (16 * p)) & 0xFFFFu) | (((w1 >> (16 * p)) & 0xFFFFu) << 16);
+    }
+    nat[wi] = out;
+}
+
+// One thread per canonical word.
+__global__ __launch_bounds__(256) void unpack_native_kernel(const uint8_t* __restrict__ nat, uint32_t* __restrict__ qweight, int K, int N)
+{
+    const int NW = N >> 3;
+    const int wd = blockIdx.x * 256 + threadIdx.x, k = blockIdx.y;
+    if (wd < NW) qweight[(size_t)k * NW + wd] = native_word(nat, K >> 5, k, wd);
+}
+
 // One thread per 8 outputs of one row (one packed word of 4-bit codes, two of 8-bit codes).
-template <typename OT, int BITS>
+// NAT: qweight is the native array of 4-bit codes.
+template <typename OT, int BITS, bool NAT = false>
 __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restrict__ qweight,
                                                          const half_t* __restrict__ scales,
                                                          const uint32_t* __restrict__ qzeros,
@@ -153,7 +203,12 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
     const int k  = blockIdx.y;
     if (c >= (N >> 3)) return;
     const int      g  = k / kGroup;
-    const uint32_t* qp = qweight + (size_t)k * NW + (size_t)c * (8 / CPW);
+    uint32_t qp[8 / CPW];
+    if constexpr (NAT) qp[0] = native_word(reinterpret_cast<const uint8_t*>(qweight), K >> 5, k, c);
+    else {
+#pragma unroll
+        for (int j = 0; j < 8 / CPW; j++) qp[j] = qweight[(size_t)k * NW + (size_t)c * (8 / CPW) + j];
+    }
     const uint32_t* zp = qzeros + (size_t)g * NW + (size_t)c * (8 / CPW);
     const half8_t  s  = *reinterpret_cast<const half8_t*>(scales + (size_t)g * N + (size_t)c * 8);
     float d[8];
@@ -202,6 +257,31 @@ static void dequantize_bits(const uint32_t* qweight, const half_t* sc, const uin
     if (dtype == 1)      hipLaunchKernelGGL((dequantize_kernel<half_t, BITS>), grid, block, 0, st, qweight, sc, qzeros, (half_t*)out, K, N);
     else if (dtype == 2) hipLaunchKernelGGL((dequantize_kernel<bf16_t, BITS>), grid, block, 0, st, qweight, sc, qzeros, (bf16_t*)out, K, N);
     else                 hipLaunchKernelGGL((dequantize_kernel<float, BITS>), grid, block, 0, st, qweight, sc, qzeros, (float*)out, K, N);
+}
+
+hipError_t launch_repack_native(const uint32_t* qweight, void* native, int K, int N, hipStream_t st)
+{
+    const size_t words = (size_t)((N + 255) / 256) * (K / 32) * 1024;
+    hipLaunchKernelGGL(repack_native_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, qweight, (uint32_t*)native, K, N, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_native(const void* native, uint32_t* qweight, int K, int N, hipStream_t st)
+{
+    hipLaunchKernelGGL(unpack_native_kernel, dim3(((N >> 3) + 255) / 256, K), dim3(256), 0, st, (const uint8_t*)native, qweight, K, N);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize_native(const void* native, const void* scales, const uint32_t* qzeros,
+                                    void* out, int out_dtype, int K, int N, hipStream_t st)
+{
+    dim3 grid(((N >> 3) + 255) / 256, K), block(256);
+    const uint32_t* nat = (const uint32_t*)native;
+    const half_t* sc = (const half_t*)scales;
+    if (out_dtype == 1)      hipLaunchKernelGGL((dequantize_kernel<half_t, 4, true>), grid, block, 0, st, nat, sc, qzeros, (half_t*)out, K, N);
+    else if (out_dtype == 2) hipLaunchKernelGGL((dequantize_kernel<bf16_t, 4, true>), grid, block, 0, st, nat, sc, qzeros, (bf16_t*)out, K, N);
+    else                     hipLaunchKernelGGL((dequantize_kernel<float, 4, true>), grid, block, 0, st, nat, sc, qzeros, (float*)out, K, N);
+    return hipGetLastError();
 }
 
 hipError_t launch_dequantize(int bits, const uint32_t* qweight, const void* scales, const uint32_t* qzeros,

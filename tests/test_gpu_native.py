@@ -1,0 +1,127 @@
+"""GPU parity of the native storage order of the 4-bit codes: the repack, its inverse and the
+dequantizer against the oracle's element-by-element definition, bit for bit; the decode kernel on the
+native array against the oracle (tolerance of the linears) and against the canonical entry point (the
+same bits: storage order does not enter the arithmetic)."""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from paper_2506_02006_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2506_02006_amd import binding
+    binding.lib()
+    binding.warmup()
+    return binding
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+@pytest.mark.parametrize("K,N", [(128, 8), (128, 512), (256, 264), (384, 2824), (1024, 4096)])
+def test_repack_and_unpack_bit_exact(B, oracle, K, N):
+    say(f"native repack K={K} N={N}")
+    rng = np.random.default_rng(K + N)
+    qw = rng.integers(0, 2 ** 32, (K, N // 8), dtype=np.uint64).astype(np.uint32)      # arbitrary codes
+    nat = B.repack_w4_native(dev(qw))
+    assert nat.numel() == oracle.native_w4_bytes(K, N) == B.w4_native_bytes(K, N)
+    assert np.array_equal(host(nat), oracle.repack_w4_native(qw))
+    back = B.unpack_w4_native(nat, K, N)
+    assert np.array_equal(host(back).view(np.uint32), qw)
+
+
+@pytest.mark.parametrize("K,N", [(128, 8), (384, 264), (1024, 4096)])
+def test_dequantize_native_bit_exact(B, oracle, K, N):
+    say(f"native dequantize K={K} N={N}")
+    rng = np.random.default_rng(K + N + 1)
+    qw = rng.integers(0, 2 ** 32, (K, N // 8), dtype=np.uint64).astype(np.uint32)
+    qz = rng.integers(0, 2 ** 32, (K // 128, N // 8), dtype=np.uint64).astype(np.uint32)
+    sc = np.abs(synth.weights(3, K // 128, N, layer_id=1)).astype(np.float16) + np.float16(1e-3)
+    nat = dev(oracle.repack_w4_native(qw))
+    d32 = B.dequantize_w4_native(nat, dev(sc), dev(qz), torch.float32)
+    assert np.array_equal(host(d32), oracle.dequant_w4(qw, sc, qz))
+    d16 = B.dequantize_w4_native(nat, dev(sc), dev(qz), torch.float16)
+    assert np.array_equal(host(d16).view(np.uint16), oracle.dequant_w4(qw, sc, qz, dtype=np.float16).view(np.uint16))
+
+
+def test_quantize_layer_native_is_quantize_then_repack(B, oracle):
+    K, N = 512, 776
+    W = synth.weights(77, K, N, layer_id=9)
+    qw, sc, qz = oracle.quantize_w4(W)
+    nat, sc_d, qz_d = B.quantize_layer_native(dev(W))
+    assert np.array_equal(host(nat), oracle.repack_w4_native(qw))
+    assert np.array_equal(host(sc_d).view(np.uint16), sc.view(np.uint16))
+    assert np.array_equal(host(qz_d).view(np.uint32), qz)
+
+
+@pytest.mark.parametrize("split", [0, 1, 3])
+@pytest.mark.parametrize("M", [1, 2, 4, 5, 16])
+def test_decode_on_native_codes(B, oracle, M, split):
+    """Several column tiles with a ragged last one, with and without a split along K."""
+    B.set_tuning(B.TUNE_DECODE_SPLIT, split)
+    try:
+        for (K, N) in ((1792, 520), (256, 2824), (4096, 264)):
+            W = synth.weights(77, K, N, layer_id=M + split)
+            x = synth.activations(77, M, K, layer_id=M)
+            qw, sc, qz = oracle.quantize_w4(W)
+            ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
+            nat = B.repack_w4_native(dev(qw))
+            y = B.linear_w4a16_native(dev(x), nat, dev(sc), dev(qz), ws)
+            y_canon = B.linear_w4a16(dev(x), dev(qw), dev(sc), dev(qz), ws)
+            torch.cuda.synchronize()
+            r = oracle.error_metric(host(y), oracle.linear_w4a16(x, qw, sc, qz))
+            say(f"  native M={M} K={K} N={N} split={split}: err={r['err']:.3e}")
+            assert r["finite"] and r["err"] <= TOL, r
+            assert np.array_equal(host(y).view(np.uint16), host(y_canon).view(np.uint16))
+    finally:
+        B.set_tuning(B.TUNE_DECODE_SPLIT, 0)
+
+
+def test_identity_activations_on_native_codes(B, oracle):
+    """x = rows of the identity: y must be the fp16-rounded dequantized weight, bit for bit: pins the
+    order of rows, columns and nibbles through the kernel."""
+    K, N, M = 256, 520, 16
+    W = synth.weights(77, K, N, layer_id=3)
+    qw, sc, qz = oracle.quantize_w4(W)
+    D16 = oracle.dequant_w4(qw, sc, qz, dtype=np.float16)
+    nat = B.repack_w4_native(dev(qw))
+    ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
+    for start in (0, 37, K - M):
+        x = np.zeros((M, K), np.float16)
+        x[np.arange(M), start + np.arange(M)] = 1.0
+        y = B.linear_w4a16_native(dev(x), nat, dev(sc), dev(qz), ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(y).view(np.uint16), D16[start:start + M].view(np.uint16))
+
+
+def test_native_rejects_what_it_does_not_serve(B):
+    K, N = 256, 264
+    x = torch.zeros((17, K), dtype=torch.float16, device="cuda")
+    nat = torch.zeros(B.w4_native_bytes(K, N), dtype=torch.uint8, device="cuda")
+    sc = torch.zeros((K // 128, N), dtype=torch.float16, device="cuda")
+    qz = torch.zeros((K // 128, N // 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.MorphError) as e:
+        B.linear_w4a16_native(x, nat, sc, qz, None)
+    assert e.value.status == 5                            # MORPH_ERR_UNSUPPORTED: more than 16 rows
