@@ -122,6 +122,8 @@ def main():
     # ------------- headline: config 2, W4A16 decode -------------
     n_pool = 12                                     # 12 x 105 MB = 1.26 GB of distinct W4 layers
     pool = [{name: make_w4(*shapes7[name]) for name in order} for _ in range(n_pool)]
+    # the same codes in the order the decode kernel's lanes consume them (what a server would keep resident)
+    pool_native = [{name: B.repack_w4_native(layer[name][0]) for name in order} for layer in pool]
     xs = {(M, K): rand_x(M, K) for M in Ms for K in (4096, 11008)}
     ys = {(M, name): torch.empty((M, shapes7[name][1]), device=dev, dtype=torch.float16) for M in Ms for name in order}
     ws_bytes = max(B.workspace_bytes(B.KIND_W4A16, M, *shapes7[name]) for M in Ms for name in order)
@@ -131,27 +133,32 @@ def main():
     # layers of the pool (one layer's 105 MB would otherwise still sit in the 256 MB memory-side
     # cache when the next M value reads it again), and four steps walk the whole pool once, so a
     # layer is read again only after 1.26 GB of other weights.
-    def step_fn(layers):
+    def step_fn(first, native):
         def run():
-            for M, layer in zip(Ms, layers):
+            for M, li in zip(Ms, range(first, first + len(Ms))):
                 for name in order:
                     K, N = shapes7[name]
-                    qw, sc, qz = layer[name]
-                    B.linear_w4a16(xs[(M, K)], qw, sc, qz, ws, out=ys[(M, name)])
+                    qw, sc, qz = pool[li][name]
+                    if native:
+                        B.linear_w4a16_native(xs[(M, K)], pool_native[li][name], sc, qz, ws, out=ys[(M, name)])
+                    else:
+                        B.linear_w4a16(xs[(M, K)], qw, sc, qz, ws, out=ys[(M, name)])
         return run
 
     n_graphs = n_pool // len(Ms)
-    graphs = [graph_of(step_fn(pool[len(Ms) * g: len(Ms) * (g + 1)])) for g in range(n_graphs)]
+    graphs = [graph_of(step_fn(len(Ms) * g, True)) for g in range(n_graphs)]
+    graphs_canonical = [graph_of(step_fn(len(Ms) * g, False)) for g in range(n_graphs)]
     launches_per_step = len(Ms) * len(order)
     bytes_ws = sum(synth.w4_bytes(K, N, zeros=False) for K, N in shapes7.values())      # codes + scales
     bytes_all = sum(synth.w4_bytes(K, N, zeros=True) for K, N in shapes7.values())
     sec = timed(lambda i: graphs[i % n_graphs].replay(), args.steps, args.warmup)
+    sec_canonical = timed(lambda i: graphs_canonical[i % n_graphs].replay(), args.steps, args.warmup)
     step_bytes = len(Ms) * bytes_ws
     value = step_bytes * args.steps / sec / 1e9
     avg_launch_s = sec / (args.steps * launches_per_step)
     roofline = {
         "bound": "hbm",
-        "kernel": "decode_small_kernel<RL, false> (W4A16, M <= 16; RL = 1 for M = 1, else 4), mean over the 12 launches of a step",
+        "kernel": "decode_small_kernel<RL, false, true> (W4A16, M <= 16, codes in native order; RL = 1 up to 4 rows, else 4), mean over the 12 launches of a step",
         "achieved": round(value, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
@@ -176,8 +183,12 @@ def main():
         "config": {"workload": "llama7b decoder-layer linears (qkv 4096x12288, o 4096x4096, gate_up 4096x22016, "
                                "down 11008x4096), W4A16 group 128, decode M in {1,4,16}; 12 launches per step, "
                                f"layer pool {n_pool} x {bytes_all / 1e6:.1f} MB",
-                   "bytes_counted": "packed codes + fp16 scales", "launch": "HIP graph replay"},
+                   "bytes_counted": "packed codes + fp16 scales", "launch": "HIP graph replay",
+                   "code_order": "native (morph_linear_w4a16_native); the same step on canonical records under canonical_order"},
         "roofline": roofline,
+        "canonical_order": {"value": round(step_bytes * args.steps / sec_canonical / 1e9, 1), "unit": "GB/s",
+                            "ms_per_step": round(sec_canonical / args.steps * 1e3, 5),
+                            "entry": "morph_linear_w4a16 on the interchange records (the form the layer records and the stack use)"},
     }
 
     # calibration transfer for hardware byte counters: a plain copy of known size (not timed)
@@ -258,7 +269,7 @@ def main():
             make = {B.KIND_W4A16: make_w4, B.KIND_W8A16: make_w8, B.KIND_FP16: make_fp16}[kind]
             return [make(K, N) for _ in range(n)]
 
-        del graphs, pool
+        del graphs, graphs_canonical, pool, pool_native
         d7 = {}
         if "config2" in sections:
             for name in order:
