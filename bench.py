@@ -427,14 +427,7 @@ def main():
             nbytes = sum((bytes_ws if l in swapped else sum(synth.fp16_bytes(*shapes7[n]) for n in order)) for l in range(L5))
             d5[f"k{k}"] = {"ms": round(s * 1e3, 4), "GBps": round(nbytes / s / 1e9, 1),
                            "pct_hbm": round(nbytes / s / 1e9 / HBM_PEAK_GBS * 100, 1), "weight_GB": round(nbytes / 1e9, 3)}
-            # the same step as two persistent launches of 16 layers each
-            g5f = graph_of(lambda: st.forward_fused(x5))
-            sf = timed(lambda i: g5f.replay(), 10, 2) / 10
-            if st.fused_abandoned():
-                raise RuntimeError("persistent stack launch was abandoned at a barrier")
-            d5[f"k{k}"].update({"persistent_ms": round(sf * 1e3, 4), "persistent_GBps": round(nbytes / sf / 1e9, 1),
-                                "persistent_pct_hbm": round(nbytes / sf / 1e9 / HBM_PEAK_GBS * 100, 1)})
-            del g5, g5f, st
+            del g5, st
         if d5:
             detail["config5_stack_M32"] = d5
         del base16, base4

@@ -241,24 +241,6 @@ int morph_stack_forward_bf16(const morph_layer_desc* layers /* host */, int n_la
                              void* workspace, size_t workspace_bytes, int tap_layer, void* tap,
                              void* stream);
 
-/* ---- the same decode step in one persistent launch per 16 layers (M <= 32) ----
- * Same chain and same layer records as morph_stack_forward, without scratch and tap: everything the
- * launch needs between its phases lives in `workspace` (morph_stack_fused_workspace_bytes() bytes,
- * prepared once with morph_workspace_init(); it must not be handed to any other entry point, and
- * not to two calls that can run concurrently).  One workgroup per compute unit stays resident and
- * walks all linears, meeting at grid-wide barriers, so the call needs the device to itself; the
- * weights of the next linear are pulled towards the caches while a barrier is waited for.
- * Rounding differs from the unfused chain in one place: the RMS scale of a row is applied to the
- * fp32 output sums of the next linear instead of to its fp16 input ((s v) W = s (v W)); the
- * activations between linears are stored unscaled.
- * Every wait inside the kernel is bounded.  If a barrier ever times out, the launch is abandoned:
- * the int32 at byte 8 of the workspace becomes non-zero, x_io is left undefined, and later calls
- * with that workspace do nothing until it is prepared again.
- * Errors: SHAPE for M > 32; DEVICE when the kernel cannot be resident on the current device. */
-size_t morph_stack_fused_workspace_bytes(int M, int hidden, int inter);
-int morph_stack_forward_fused(const morph_layer_desc* layers /* host */, int n_layers, void* x_io,
-                              int M, int hidden, int inter, void* workspace, size_t workspace_bytes,
-                              void* stream);
 
 /* ---- layer records and the in-place swap (Section 4.3, "Model Preloading" and "Asynchronous
  * In-place Layer Swapping"; Appendix C) ----

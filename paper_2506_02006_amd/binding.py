@@ -28,8 +28,7 @@ TUNE_SMALL_FAR = 13
 EXPORTS = [
     "morph_linear_fp16", "morph_linear_w4a16", "morph_quantize_layer", "morph_dequantize_w4",
     "morph_workspace_bytes", "morph_workspace_init", "morph_glue", "morph_stack_scratch_bytes",
-    "morph_stack_tap_bytes", "morph_stack_forward", "morph_stack_fused_workspace_bytes",
-    "morph_stack_forward_fused", "morph_warmup_bytes", "morph_warmup",
+    "morph_stack_tap_bytes", "morph_stack_forward", "morph_warmup_bytes", "morph_warmup",
     "morph_set_tuning", "morph_copy", "morph_status_string",
     "morph_probe_out_bytes", "morph_probe_read", "morph_probe_mfma",
     "morph_layer_record_bytes", "morph_layer_record_desc", "morph_layer_swap_async",
@@ -102,9 +101,6 @@ def lib() -> ctypes.CDLL:
     L.morph_stack_tap_bytes.restype = sz
     L.morph_stack_forward.argtypes = [ctypes.POINTER(LayerDesc), i, vp, i, i, i, vp, sz, vp, sz, i, vp, vp]
     L.morph_stack_forward_bf16.argtypes = L.morph_stack_forward.argtypes
-    L.morph_stack_fused_workspace_bytes.argtypes = [i, i, i]
-    L.morph_stack_fused_workspace_bytes.restype = sz
-    L.morph_stack_forward_fused.argtypes = [ctypes.POINTER(LayerDesc), i, vp, i, i, i, vp, sz, vp]
     L.morph_warmup_bytes.argtypes = []
     L.morph_warmup_bytes.restype = sz
     L.morph_warmup.argtypes = [vp, sz, vp]
@@ -122,7 +118,7 @@ def lib() -> ctypes.CDLL:
     L.morph_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
         if name not in ("morph_workspace_bytes", "morph_stack_scratch_bytes", "morph_stack_tap_bytes",
-                        "morph_stack_fused_workspace_bytes", "morph_warmup_bytes", "morph_status_string",
+                        "morph_warmup_bytes", "morph_status_string",
                         "morph_probe_out_bytes", "morph_layer_record_bytes", "morph_noalloc_scratch_bytes"):
             getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -447,7 +443,6 @@ class LayerStack:
         self.scratch = torch.empty(int(lib().morph_stack_scratch_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
         self.tap = torch.empty(int(lib().morph_stack_tap_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
         self.ws = None
-        self.fused_ws = None
 
     def add_layer(self, linears: dict):
         self.layers.append(linears)
@@ -499,25 +494,6 @@ class LayerStack:
                   self.ws.data_ptr(), self.ws.numel(), tap_layer, self.tap.data_ptr(),
                   _stream()), "morph_stack_forward")
         return x_io
-
-    def forward_fused(self, x_io: torch.Tensor):
-        """The same decode step in one persistent launch per 16 layers (M <= 32), in place on x_io (fp16 only)."""
-        if self.dtype != torch.float16:
-            raise TypeError("the persistent stack launch takes fp16 activations only")
-        if self._desc is None:
-            self._build()
-        assert x_io.shape == (self.M, self.hidden)
-        if self.fused_ws is None:
-            self.fused_ws = new_workspace(int(lib().morph_stack_fused_workspace_bytes(self.M, self.hidden, self.inter)),
-                                          self.device)
-        _check(lib().morph_stack_forward_fused(self._desc, len(self.layers), _dev(x_io, torch.float16, "x_io"), self.M,
-                                               self.hidden, self.inter, self.fused_ws.data_ptr(),
-                                               self.fused_ws.numel(), _stream()), "morph_stack_forward_fused")
-        return x_io
-
-    def fused_abandoned(self) -> bool:
-        """True if a fused launch gave up at a barrier (synchronises)."""
-        return self.fused_ws is not None and int(self.fused_ws[8:12].view(torch.int32).item()) != 0
 
     def tapped(self):
         """Views into the tap buffer: x, qkv, a, o, r, gu, m, d as fp16 tensors (valid after a forward with tap_layer set)."""

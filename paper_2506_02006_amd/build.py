@@ -15,7 +15,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmorph.so")
 # (source, object name, extra defines): prefill.hip is compiled as two objects (fp16 / bfloat16 kernels) to halve the build time
 UNITS = [("prefill.hip", "prefill", ["-DMORPH_PREFILL_PART=0"]), ("prefill.hip", "prefill_bf16", ["-DMORPH_PREFILL_PART=1"]),
-         ("decode.hip", "decode", []), ("decode_small.hip", "decode_small", []), ("stack.hip", "stack", []), ("api.hip", "api", []), ("quant.hip", "quant", []),
+         ("decode.hip", "decode", []), ("decode_small.hip", "decode_small", []), ("api.hip", "api", []), ("quant.hip", "quant", []),
          ("glue.hip", "glue", [])]
 
 # -packed-fp32-ops off: keep the compiler from forming packed fp32 instructions.

@@ -550,103 +550,6 @@ int morph_stack_forward_bf16(const morph_layer_desc* layers, int n_layers, void*
                              tap_layer, tap, stream, 1);
 }
 
-// ---- the same stack in one persistent launch per 16 layers ----
-// workspace layout: barrier words @0 (16 KB); then, each with one slot per layer of a launch plus
-// one: row scales, sum-of-squares shares (32 x 256 floats per buffer), activations X, A, U [M,h] and
-// Mm [M,i] as fp16; then the fp32 partial products.
-namespace {
-struct FusedLayout {
-    size_t sync, rs, ss, act, act_stride, act_off[4], partial, total;
-};
-FusedLayout fused_layout(int M, int h, int i)
-{
-    FusedLayout L;
-    const size_t m = (size_t)M, mp = M <= 16 ? 16 : 32, slots = kStackMaxLayers + 1;
-    L.sync = 0;
-    size_t off = 16384;
-    L.rs = off; off += up256(slots * 4 * 32 * sizeof(float));
-    L.ss = off; off += up256(slots * 4 * 32 * kStackMaxGrid * sizeof(float));
-    L.act_off[0] = 0;
-    L.act_off[1] = L.act_off[0] + up256(m * h * 2);
-    L.act_off[2] = L.act_off[1] + up256(m * h * 2);
-    L.act_off[3] = L.act_off[2] + up256(m * h * 2);
-    L.act_stride = L.act_off[3] + up256(m * i * 2);
-    L.act = off; off += slots * L.act_stride;
-    // parts of K x columns never exceeds grid x tile width (256 x 256) unless a single part is wider
-    size_t cols = 65536;
-    if ((size_t)3 * h > cols) cols = (size_t)3 * h;
-    if ((size_t)2 * i > cols) cols = (size_t)2 * i;
-    L.partial = off; off += up256(cols * mp * 4);
-    L.total = off;
-    return L;
-}
-int fused_shape_ok(int M, int hidden, int inter)
-{
-    if (M < 1 || M > 32) return MORPH_ERR_SHAPE;
-    if (hidden % MORPH_GROUP_SIZE || inter % MORPH_GROUP_SIZE || hidden < MORPH_GROUP_SIZE || inter < MORPH_GROUP_SIZE)
-        return MORPH_ERR_SHAPE;
-    return MORPH_OK;
-}
-}  // namespace
-
-size_t morph_stack_fused_workspace_bytes(int M, int hidden, int inter)
-{
-    if (fused_shape_ok(M, hidden, inter) != MORPH_OK) return 0;
-    return fused_layout(M, hidden, inter).total;
-}
-
-int morph_stack_forward_fused(const morph_layer_desc* layers, int n_layers, void* x_io, int M, int hidden,
-                              int inter, void* workspace, size_t workspace_bytes, void* stream)
-{
-    if (!layers || !x_io || !workspace) return MORPH_ERR_NULL;
-    if (n_layers < 1) return MORPH_ERR_SHAPE;
-    if (int rc = fused_shape_ok(M, hidden, inter)) return rc;
-    if (!aligned16(x_io) || !aligned16(workspace)) return MORPH_ERR_ALIGN;
-    const FusedLayout L = fused_layout(M, hidden, inter);
-    if (workspace_bytes < L.total) return MORPH_ERR_WORKSPACE;
-    const int grid = stack_grid();
-    if (grid < 1) return MORPH_ERR_DEVICE;
-    const int widest = hidden > inter ? hidden : inter;
-    if ((size_t)((widest + grid - 1) / grid) * 32 + 576 > (size_t)kStackReduceLdsFloats) return MORPH_ERR_UNSUPPORTED;
-    for (int l = 0; l < n_layers; l++) {
-        const morph_linear_desc* ds[4] = {&layers[l].qkv, &layers[l].o, &layers[l].gate_up, &layers[l].down};
-        const int Ks[4] = {hidden, hidden, hidden, inter}, Ns[4] = {3 * hidden, hidden, 2 * inter, hidden};
-        for (int q = 0; q < 4; q++) {
-            if (ds[q]->kind == MORPH_KIND_W8A16) return MORPH_ERR_UNSUPPORTED;   // the persistent launch knows fp16 and 4-bit layers
-            if (ds[q]->kind != MORPH_KIND_FP16 && ds[q]->kind != MORPH_KIND_W4A16) return MORPH_ERR_SHAPE;
-            if (int rc = validate_linear(ds[q]->kind, x_io, ds[q]->w, ds[q]->scales, ds[q]->qzeros, workspace, M, Ks[q], Ns[q]))
-                return rc;
-        }
-    }
-    char* ws = reinterpret_cast<char*>(workspace);
-    for (int l0 = 0; l0 < n_layers; l0 += kStackMaxLayers) {
-        StackArgs a;
-        a.n_layers = n_layers - l0 < kStackMaxLayers ? n_layers - l0 : kStackMaxLayers;
-        for (int l = 0; l < a.n_layers; l++) {
-            const morph_linear_desc* ds[4] = {&layers[l0 + l].qkv, &layers[l0 + l].o, &layers[l0 + l].gate_up, &layers[l0 + l].down};
-            for (int q = 0; q < 4; q++) {
-                const bool w4 = ds[q]->kind == MORPH_KIND_W4A16;
-                a.lin[l][q].w = ds[q]->w;
-                a.lin[l][q].scales = w4 ? ds[q]->scales : nullptr;
-                a.lin[l][q].qzeros = w4 ? ds[q]->qzeros : nullptr;
-            }
-        }
-        for (int l = a.n_layers; l < kStackMaxLayers; l++)
-            for (int q = 0; q < 4; q++) a.lin[l][q] = StackLinear{nullptr, nullptr, nullptr};
-        a.x_io = reinterpret_cast<_Float16*>(x_io);
-        a.act = ws + L.act;
-        a.act_stride = L.act_stride;
-        for (int b = 0; b < 4; b++) a.act_off[b] = L.act_off[b];
-        a.ss = reinterpret_cast<float*>(ws + L.ss);
-        a.rs = reinterpret_cast<float*>(ws + L.rs);
-        a.partial = reinterpret_cast<float*>(ws + L.partial);
-        a.sync = reinterpret_cast<int*>(ws + L.sync);
-        a.M = M; a.hidden = hidden; a.inter = inter;
-        if (launch_stack(a, grid, (hipStream_t)stream) != hipSuccess) return MORPH_ERR_DEVICE;
-    }
-    return MORPH_OK;
-}
-
 int morph_copy(const void* src, void* dst, size_t bytes, void* stream)
 {
     if (!src || !dst) return MORPH_ERR_NULL;

@@ -119,33 +119,6 @@ PrefillPlan plan_prefill(int M, int K, int N);
 int prefill_compute_units();   // compute units of the current device (256 when it cannot be asked)
 hipError_t launch_prefill(int q, const GemmArgs& a, hipStream_t st);   // q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes
 
-// ---- persistent layer stack, M <= 32 (stack.hip) ----
-constexpr int kStackWaves    = 8;      // waves per workgroup
-constexpr int kStackMaxGrid  = 256;    // workgroups (columns of the sum-of-squares arrays)
-constexpr int kStackMaxLayers = 16;    // layers per launch (their pointers travel as kernel arguments)
-constexpr int kStackReduceLdsFloats = 32768;   // LDS floats the reduce phase may use (576 + columns per workgroup * 32)
-struct StackLinear {
-    const void* w;         // fp16 [K,N] or uint32 [K,N/8]
-    const void* scales;    // fp16 [K/128,N]; null marks an fp16 linear
-    const void* qzeros;    // uint32 [K/128,N/8]
-};
-struct StackArgs {
-    StackLinear lin[kStackMaxLayers][4];   // qkv, o, gate_up, down of each layer
-    _Float16*   x_io;      // [M,hidden] input of the first layer, output of the last
-    // Everything one workgroup writes and many read lives at an address of its own per layer of the
-    // launch (slot 0 .. kStackMaxLayers), so that it can be read through the caches: a cache can
-    // hold no older copy of a line that nobody read before it was written.
-    char*       act;       // slot s at act + s * act_stride: X | A | U [M,hidden], Mm [M,inter], fp16 without row scale
-    size_t      act_stride, act_off[4];
-    float*      ss;        // [slot][4][32][kStackMaxGrid] shares of every row's sum of squares
-    float*      rs;        // [slot][4][32] row scales once they are known
-    float*      partial;   // [part of K][N][16 or 32] fp32
-    int*        sync;      // barrier words (16 KB, see stack.hip); [2] = abort flag; zero between launches
-    int         n_layers, M, hidden, inter;
-};
-int        stack_grid();   // workgroups of the persistent grid on the current device (0: unavailable)
-hipError_t launch_stack(const StackArgs& a, int grid, hipStream_t st);
-
 // ---- glue (glue.hip) ----
 hipError_t launch_glue(int op, const void* a, const void* b, void* out, int M, int H, int bf, hipStream_t st);   // bf: rows are bfloat16
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);

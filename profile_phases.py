@@ -1,9 +1,11 @@
 #!/usr/bin/env python3
-"""Where the time of one decode launch goes: phase timestamps of the kernel for at most 16 rows of
-4-bit weights (csrc/decode_small.hip), read from the timing build of the library.
+"""Where the time of one decode launch goes: phase timestamps of the kernels for at most 64 rows of
+4-bit weights (csrc/decode_small.hip), read from the timing build of the library; and, with --prefill,
+the shader clock the chip holds inside the k loop of the LDS-tiled MFMA kernels (csrc/prefill.hip).
 
     python -m paper_2506_02006_amd.build --timing      # writes paper_2506_02006_amd/libmorph_timing.so
     python profile_phases.py [--M 1,16] [--family llama7b]
+    python profile_phases.py --prefill [--M 2048] [--family llama13b]
 
 The timing build compiles the MORPH_TICK points in (csrc/ticks.h): thread 0 of every workgroup stores
 the 100 MHz wall clock at a few points.  Reading the clock costs the first wave a few hundred
@@ -24,11 +26,68 @@ LABELS = ["kernel entry", "first loads issued", "(unused)", "all waves done, sum
           "all flags seen", "own share stored"]
 
 
+def prefill_clock(args, torch, B, L, synth):
+    """The timing build keeps, for each wave of the first 256 workgroups, the shader-clock cycles of the k
+    loop of the workgroup's first tile and the part of them spent waiting at the loop's barriers, and for
+    thread 0 the 100 MHz wall clock at the loop's start and end: cycles / wall time = the clock the chip
+    held there."""
+    L.morph_debug_read_prefill_ticks.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    L.morph_debug_read_prefill_wall.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    dev = "cuda"
+    for name in synth.LINEAR_ORDER:
+        K, N = synth.LAYER_SHAPES[args.family][name]
+        w32 = torch.randn((K, N), device=dev) * 0.02
+        w4 = B.quantize_layer(w32)
+        w16 = w32.half()
+        del w32
+        for M in [int(m) for m in args.M.split(",")]:
+            x = torch.randn((M, K), device=dev).half()
+            y = torch.empty((M, N), device=dev, dtype=torch.float16)
+            ws = B.new_workspace(max(B.workspace_bytes(B.KIND_W4A16, M, K, N), B.workspace_bytes(B.KIND_FP16, M, K, N), 4096))
+            for label, fn in (("w4a16", lambda: B.linear_w4a16(x, w4[0], w4[1], w4[2], ws, out=y)),
+                              ("fp16", lambda: B.linear_fp16(x, w16, ws, out=y))):
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(10):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 100.0
+                L.morph_debug_clear_prefill_ticks()
+                torch.cuda.synchronize()
+                fn()
+                torch.cuda.synchronize()
+                t = np.zeros(256 * 8 * 2, np.uint64)
+                wl = np.zeros(256 * 8, np.uint64)
+                L.morph_debug_read_prefill_ticks(t.ctypes.data, t.size)
+                L.morph_debug_read_prefill_wall(wl.ctypes.data, wl.size)
+                t = t.reshape(256, 8, 2).astype(np.float64)
+                wl = wl.reshape(256, 8).astype(np.float64)
+                live = (wl[:, 1] > 0) & (wl[:, 2] > wl[:, 1]) & (t[:, 0, 0] > 0)
+                mhz = t[live, 0, 0] / ((wl[live, 2] - wl[live, 1]) * 0.01)
+                wait = t[live][:, :, 1].sum() / np.maximum(t[live][:, :, 0].sum(), 1.0)
+                tf = 2.0 * M * K * N / (us * 1e-6) / 1e12
+                at_clock = 2500.0 * mhz.mean() / 2400.0
+                print(f"{args.family} {name} {K}x{N} M={M} {label}: {us:7.1f} us = {tf:6.1f} TFLOP/s ({tf / 25.0:4.1f} % of 2.5 PFLOP/s); "
+                      f"shader clock inside the k loop {mhz.mean():6.0f} MHz (min {mhz.min():.0f}, max {mhz.max():.0f}, {int(live.sum())} workgroups); "
+                      f"at that clock the matrix cores peak at {at_clock:6.0f} TFLOP/s -> {tf / at_clock * 100:4.1f} %; "
+                      f"{wait * 100:4.1f} % of the loop's cycles at its barriers", flush=True)
+        del w4, w16
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--M", default="1,16")
-    ap.add_argument("--family", default="llama7b")
+    ap.add_argument("--family", default=None)
+    ap.add_argument("--prefill", action="store_true", help="shader clock and barrier share inside the k loop of the prefill kernels")
     args = ap.parse_args()
+    if args.family is None:
+        args.family = "llama13b" if args.prefill else "llama7b"
+    if args.prefill and args.M == "1,16":
+        args.M = "2048"
     import torch
     from paper_2506_02006_amd import binding as B, synth
     B.LIB_PATH = os.path.join(ROOT, "paper_2506_02006_amd", "libmorph_timing.so")
@@ -36,6 +95,9 @@ def main():
     B.warmup()
     L.morph_debug_read_small_ticks.argtypes = [ctypes.c_void_p, ctypes.c_int]
     dev = "cuda"
+    if args.prefill:
+        prefill_clock(args, torch, B, L, synth)
+        return
     for name in synth.LINEAR_ORDER:
         K, N = synth.LAYER_SHAPES[args.family][name]
         recs = [B.quantize_layer(torch.randn((K, N), device=dev) * 0.02) for _ in range(max(4, int(6e8 // (K * N // 2))))]

@@ -321,20 +321,7 @@ def test_config5_mixed_stack(B, oracle):
         assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
         rmsv = np.sqrt((outs[0].astype(np.float64) ** 2).mean(axis=1))
         assert np.all(np.abs(rmsv - 1.0) < 1e-2)
-        # The persistent launch on the same 32 layers.  At this size the synthetic chain amplifies any
-        # perturbation by about 1.35x per layer (a 1e-3 change of the input is O(1) after 24
-        # layers), so its output cannot be compared with the per-step path end to end (one rounding
-        # sits elsewhere); what holds at any depth: it is finite, normalised and reproducible.
-        xf, xf2 = dev(x0).clone(), dev(x0).clone()
-        st.forward_fused(xf)
-        st.forward_fused(xf2)
-        torch.cuda.synchronize()
-        assert not st.fused_abandoned()
-        yf = host(xf)
-        assert np.isfinite(yf).all()
-        assert np.array_equal(yf.view(np.uint16), host(xf2).view(np.uint16))
-        assert np.all(np.abs(np.sqrt((yf.astype(np.float64) ** 2).mean(axis=1)) - 1.0) < 1e-2)
-    # the persistent launch, one layer at a time against the oracle's own layer (full size):
+    # one layer at a time against the oracle's own layer (full size), input to output:
     # one fp16 layer and one 4-bit layer, each fed the normalised input x0
     f16 = lambda v: np.asarray(v, np.float64).astype(np.float16)
     for l, kind in ((check_layers[0], "fp16"), (check_layers[1], "w4")):
@@ -342,9 +329,8 @@ def test_config5_mixed_stack(B, oracle):
         one.add_layer({n: ("w4",) + tuple(w4_dev[l][n]) for n in synth.LINEAR_ORDER} if kind == "w4"
                       else {n: ("fp16", fp16_dev[l][n]) for n in synth.LINEAR_ORDER})
         xg = dev(x0).clone()
-        one.forward_fused(xg)
+        one.forward(xg)
         torch.cuda.synchronize()
-        assert not one.fused_abandoned()
         R = {n: host_recs[l][n][kind] for n in synth.LINEAR_ORDER}
         qkv = f16(oracle_linear(oracle, R["qkv"], x0))
         a = f16(oracle.glue_qkv(qkv))
@@ -355,5 +341,5 @@ def test_config5_mixed_stack(B, oracle):
         d = f16(oracle_linear(oracle, R["down"], m))
         ref = f16(oracle.glue_residual(r_, d))
         e = oracle.error_metric(host(xg), ref.astype(np.float64))
-        say(f"  config5 persistent launch, layer {l} ({kind}) against the oracle's layer: err={e['err']:.3e}")
+        say(f"  config5 layer {l} ({kind}) input to output against the oracle's layer: err={e['err']:.3e}")
         assert e["finite"] and e["err"] <= TOL

@@ -131,8 +131,7 @@ def test_stack_step_under_graph_replay(B, oracle, M, kinds):
         st.add_layer(lin)
     x0 = dev(synth.activations(94, M, hidden, layer_id=0).astype(np.float16))
     x = torch.empty_like(x0)
-    fused_ok = all(k in ("w4", "fp16") for k in kinds) and M <= 32
-    variants = [("per linear", lambda: st.forward(x))] + ([("persistent", lambda: st.forward_fused(x))] if fused_ok else [])
+    variants = [("per linear", lambda: st.forward(x))]
     for label, fwd in variants:
         def step():
             x.copy_(x0)
@@ -151,5 +150,3 @@ def test_stack_step_under_graph_replay(B, oracle, M, kinds):
             g.replay()
             torch.cuda.synchronize()
             assert torch.equal(x, eager), (label, rep, int((x != eager).sum().item()))
-        if label == "persistent":
-            assert not st.fused_abandoned()
