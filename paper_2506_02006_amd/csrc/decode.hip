@@ -393,8 +393,9 @@ static DecodePlan plan_small(int M, int K, int N)
     pl.partial_bytes = S > 1 ? (size_t)pl.tiles * slices * S * nvec * 16 : 0;
     // A look is one trip to the L2, 0.15 .. 0.3 us; the others of a unit normally follow within a few of them.  A workgroup
     // that starts after another one of its unit has already finished (compute units held up by other work) cannot tell
-    // and waits the bound out before it recomputes: the bound is what such a launch costs, about 0.1 ms.
-    pl.polls = tuning_get(TUNE_DECODE_SCATTER) == 3 ? 0 : 512;    // 3: nobody looks, every workgroup recomputes what it needs (test hook)
+    // and waits the bound out before it recomputes: the bound is what such a launch costs, about 25 us (seen in
+    // about one launch in a thousand when the grid takes every compute unit of the chip).
+    pl.polls = tuning_get(TUNE_DECODE_SCATTER) == 3 ? 0 : 128;    // 3: nobody looks, every workgroup recomputes what it needs (test hook)
     pl.stream_loads = 1;
     pl.scatter = S > 1;
     return pl;
