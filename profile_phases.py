@@ -82,6 +82,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--M", default="1,16")
     ap.add_argument("--family", default=None)
+    ap.add_argument("--native", action="store_true", help="the codes in native order (morph_linear_w4a16_native, M <= 16)")
     ap.add_argument("--prefill", action="store_true", help="shader clock and barrier share inside the k loop of the prefill kernels")
     args = ap.parse_args()
     if args.family is None:
@@ -106,9 +107,14 @@ def main():
             y = torch.empty((M, N), device=dev, dtype=torch.float16)
             ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
 
+            nats = [B.repack_w4_native(r[0]) for r in recs] if args.native and M <= 16 else None
+
             def run():
-                for r in recs:
-                    B.linear_w4a16(x, r[0], r[1], r[2], ws, out=y)
+                for i, r in enumerate(recs):
+                    if nats is not None:
+                        B.linear_w4a16_native(x, nats[i], r[1], r[2], ws, out=y)
+                    else:
+                        B.linear_w4a16(x, r[0], r[1], r[2], ws, out=y)
             g = torch.cuda.CUDAGraph()
             s = torch.cuda.Stream()
             s.wait_stream(torch.cuda.current_stream())
@@ -131,7 +137,10 @@ def main():
             live = t[:, 1] != 0
             w = t[live][:, 1::2].astype(np.float64) * 0.01          # microseconds
             t0 = w[:, 0].min()
-            print(f"{args.family} {name} {K}x{N} M={M}: {int(live.sum())} workgroups", flush=True)
+            cyc = t[live][:, 0::2].astype(np.float64)
+            span = (w[:, 3] > w[:, 1]) & (w[:, 1] > 0)
+            mhz = ((cyc[span, 3] - cyc[span, 1]) / (w[span, 3] - w[span, 1])).mean() if span.any() else float("nan")
+            print(f"{args.family} {name} {K}x{N} M={M}: {int(live.sum())} workgroups; shader clock between the first loads and the end of the k loop {mhz:.0f} MHz", flush=True)
             for i, label in enumerate(LABELS):
                 v = w[:, i]
                 ok = v > 0
