@@ -64,11 +64,14 @@ struct SmallTail {
     int*      ctl;                               // kCtlInts per unit
     int       polls;                             // looks at the flags before a workgroup stops waiting
     int       nb;                                // M <= 16: groups of four rows that exist, ceil(M / 4)
-    int       tiles;                             // column tiles of 256
-    int       sl_shift;                          // 0: one slice of rows; 1: two slices of 32 rows, workgroups (tile, slice, split)
     int       far;                               // write the hand-over through to memory instead of leaving it in the L2
-    int       inv_s;                             // ceil(65536 / S): j / S = (j * inv_s) >> 16 for the j that occur
 };
+// What a workgroup needs to find its place travels as leading scalar kernel arguments (fourteen dwords with the
+// pointers: as many as are in registers when a wave starts); a field of the structure above costs a trip to
+// memory before the first load could be issued.  Packed two to a dword:
+//   ms = M | S << 16;  qr = groups per split | (splits that take one more) << 16;
+//   tiles_sl = column tiles of 256 | sl_shift << 16 (0: one slice of rows; 1: two slices of 32 rows, workgroups
+//   (tile, slice, split));  inv_s = ceil(65536 / S): j / S = (j * inv_s) >> 16 for the j that occur.
 
 template <bool BF>
 __device__ __forceinline__ f32x4 mfma_small(half8_t a, half8_t b, f32x4 c)
@@ -101,16 +104,17 @@ __device__ __forceinline__ void reload_fence() { asm volatile("" ::: "memory"); 
 // Tiles that do not exist (the last slot of an XCD when the tile count is no multiple of 8) have
 // tile >= tiles and leave at once.
 struct Place { int tile, slice, sp, unit; };
-__device__ __forceinline__ Place place_of(const SmallTail& t, int S)
+__device__ __forceinline__ Place place_of(int tiles_sl, int inv_s, int S)
 {
     const int L = blockIdx.x, xcd = L & 7, jj = L >> 3;
-    const int pair = (jj * t.inv_s) >> 16;
+    const int sl_shift = tiles_sl >> 16;
+    const int pair = (jj * inv_s) >> 16;
     Place p;
     p.sp = jj - pair * S;
-    const int slot = pair >> t.sl_shift;
-    p.slice = pair - (slot << t.sl_shift);
+    const int slot = pair >> sl_shift;
+    p.slice = pair - (slot << sl_shift);
     p.tile = slot * 8 + xcd;
-    p.unit = (p.tile << t.sl_shift) + p.slice;
+    p.unit = (p.tile << sl_shift) + p.slice;
     return p;
 }
 
@@ -255,9 +259,10 @@ struct SmallGroup {
 // piece, and a step takes four loads instead of eight.
 template <int RL, bool BF, bool NAT>
 __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
-    const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int M, int S,
-    int q_groups, int r_groups, SmallTail t)
+    const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
+    int tiles_sl, int inv_s, SmallTail t)
 {
+    const int M = ms & 0xFFFF, S = ms >> 16, q_groups = qr & 0xFFFF, r_groups = qr >> 16;
     // after the k loop: [wave][lane][column j of the lane, stored at j ^ (lane & 15)]
     __shared__ __align__(16) f32x4 yl[kSmWaves * 64 * 16];
     __shared__ uint32_t fresh_word;
@@ -266,14 +271,15 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, b = lane >> 4;
-    const Place p = place_of(t, S);
-    if (p.tile >= t.tiles) return;
+    const int tiles = tiles_sl & 0xFFFF;
+    const Place p = place_of(tiles_sl, inv_s, S);
+    if (p.tile >= tiles) return;
     const int n0 = p.tile * 256;
     const int NW = N >> 3;
 
     const uint32_t row_bytes = (uint32_t)NW * 4u;
     const uint32_t ksteps = (uint32_t)K >> 5;
-    const __amdgpu_buffer_rsrc_t rw = NAT ? make_rsrc(w, (uint32_t)t.tiles * ksteps * 4096u) : make_rsrc(w, (uint32_t)K * row_bytes);
+    const __amdgpu_buffer_rsrc_t rw = NAT ? make_rsrc(w, (uint32_t)tiles * ksteps * 4096u) : make_rsrc(w, (uint32_t)K * row_bytes);
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
     const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
@@ -482,9 +488,10 @@ struct MidGroup {
 
 template <bool BF>
 __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
-    const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int M_all, int S,
-    int q_groups, int r_groups, SmallTail t)
+    const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
+    int tiles_sl, int inv_s, SmallTail t)
 {
+    const int M_all = ms & 0xFFFF, S = ms >> 16, q_groups = qr & 0xFFFF, r_groups = qr >> 16;
     // During the k loop each wave keeps in its 16 KB two groups of x: 32 rows of 128 k, a row = 16 pieces
     // of 16 bytes, piece p stored at p ^ (row & 15) -- whole rows come from memory in whole cache
     // lines (a lane that fetched the 8 k of its own MFMA operand for every step would touch 16 lines
@@ -500,8 +507,9 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kh = wave >> 1, ch = wave & 1;
     const int c = lane & 15, b = lane >> 4;
-    const Place p = place_of(t, S);
-    if (p.tile >= t.tiles) return;
+    const int tiles = tiles_sl & 0xFFFF;
+    const Place p = place_of(tiles_sl, inv_s, S);
+    if (p.tile >= tiles) return;
     const int n0 = p.tile * 256;
     const int NW = N >> 3;
     // this workgroup's rows: a slice is 32 rows
@@ -700,11 +708,12 @@ hipError_t launch_small_with(Kernel kernel, int waves, const SmallArgs& a, hipSt
     const int G = a.K / kGroup;
     SmallTail t;
     t.y = a.y; t.slots = a.slots; t.ctl = a.ctl; t.polls = a.polls; t.nb = (a.M + 3) / 4;
-    t.tiles = a.tiles; t.far = a.far; t.inv_s = (65536 + a.S - 1) / a.S;
-    t.sl_shift = a.M > 32 ? 1 : 0;
-    const int grid = 8 * ((a.tiles + 7) / 8) * a.S << t.sl_shift;
+    t.far = a.far;
+    const int sl_shift = a.M > 32 ? 1 : 0;
+    const int grid = 8 * ((a.tiles + 7) / 8) * a.S << sl_shift;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(waves * 64), 0, st,
-                       (const uint32_t*)a.w, a.x, a.scales, (const uint32_t*)a.qzeros, a.K, a.N, a.M, a.S, G / a.S, G % a.S, t);
+                       (const uint32_t*)a.w, a.x, a.scales, (const uint32_t*)a.qzeros, a.K, a.N, a.M | (a.S << 16), (G / a.S) | ((G % a.S) << 16),
+                       a.tiles | (sl_shift << 16), (65536 + a.S - 1) / a.S, t);
     return hipGetLastError();
 }
 
@@ -728,7 +737,7 @@ MORPH_TICK_EXPORTS(small_ticks)
 
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
 {
-    if (a.M < 1 || a.M > 64 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1) return hipErrorInvalidValue;
+    if (a.M < 1 || a.M > 64 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1 || a.tiles > 65535 || a.K / kGroup > 65535) return hipErrorInvalidValue;
     if (a.S > 1 && a.tiles * (a.M > 32 ? 2 : 1) > 256) return hipErrorInvalidValue;     // flags for 256 (tile, slice) pairs
     return a.bf ? launch_small_m<true>(a, st) : launch_small_m<false>(a, st);
 }
