@@ -702,13 +702,20 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     if ((rc = morph_quantize_layer(w, MORPH_DTYPE_F16, q, s, z, kWK, kWN, 128, stream))) return rc;
     if ((rc = morph_dequantize_w4(q, s, z, f, MORPH_DTYPE_F32, kWK, kWN, 128, stream))) return rc;
     if ((rc = morph_dequantize_w4(q, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
-    const int ms[] = {1, 4, 17, 33, 49, kWM};            // one-row and several-row small kernels, both slice heights, the tiled kernels
+    const int ms[] = {1, 16, 17, 33, 49, kWM};           // the kernels for up to 4, up to 16 and up to 64 rows (one and two slices), the tiled kernels
     for (int m : ms) {
         if ((rc = morph_linear_fp16(x, w, y, m, kWK, kWN, ws, wsb, stream))) return rc;
         if ((rc = morph_linear_w4a16(x, q, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
         if ((rc = morph_linear_bf16(x, w, y, m, kWK, kWN, ws, wsb, stream))) return rc;
         if ((rc = morph_linear_w4a16_bf16(x, q, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
     }
+    // the native order of the 4-bit codes (16 KB, in the second half of the fp32 dummy matrix)
+    void* nat = reinterpret_cast<char*>(f) + 65536;
+    if ((rc = morph_repack_w4_native(q, nat, kWK, kWN, stream))) return rc;
+    if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 1, kWK, kWN, 128, ws, wsb, stream))) return rc;
+    if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 16, kWK, kWN, 128, ws, wsb, stream))) return rc;
+    if ((rc = morph_dequantize_w4_native(nat, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
+    if ((rc = morph_unpack_w4_native(nat, q, kWK, kWN, stream))) return rc;
     // the 8-bit variant: its codes (32 KB) go where the fp32 dummy matrix was
     int32_t* q8 = reinterpret_cast<int32_t*>(f);
     if ((rc = morph_quantize_layer_w8(w, MORPH_DTYPE_F16, q8, s, z, kWK, kWN, 128, stream))) return rc;
