@@ -407,7 +407,8 @@ DecodePlan plan_decode(int q, int M, int K, int N)
     const int small_rows = tuning_get(TUNE_SMALL) == 3 ? 16 : 64;       // 3: the register-tiled kernel only up to 16 rows
     if (q == 1 && M <= small_rows && tuning_get(TUNE_SMALL) != 2 && t != 16 && t != 32) {
         const DecodePlan ps = plan_small(M, K, N);
-        if (ps.partial_bytes <= kSlotBytes && (ps.S == 1 || ps.tiles * ps.slices <= 256)) return ps;
+        // (tile and group counts travel in 16 bits each)
+        if (ps.partial_bytes <= kSlotBytes && (ps.S == 1 || ps.tiles * ps.slices <= 256) && ps.tiles <= 65535 && K / kGroup <= 65535) return ps;
     }
     if (t == 16 || t == 32) return plan_rows(q, M, K, N, t);
     if (M <= 16) return plan_rows(q, M, K, N, 16);
