@@ -83,6 +83,27 @@ def test_linear_w4a16_validation(L):
     assert call(M=1, K=128 * 1024 * 64, N=1024) == 5
 
 
+def test_native_order_entry_points_validation(L):
+    """The native order of the 4-bit codes: sizes, argument checks, and what the decode entry point does not serve."""
+    L.morph_w4_native_bytes.restype = ctypes.c_size_t
+    assert L.morph_w4_native_bytes(128, 8) == 4 * 4096                 # one (padded) column tile, four k-steps
+    assert L.morph_w4_native_bytes(4096, 22016) == 86 * 128 * 4096
+    assert L.morph_w4_native_bytes(100, 8) == 0 and L.morph_w4_native_bytes(128, 12) == 0
+    assert L.morph_repack_w4_native(None, FAKE, 128, 8, None) == 1 and L.morph_repack_w4_native(FAKE, None, 128, 8, None) == 1
+    assert L.morph_repack_w4_native(FAKE, FAKE, 100, 8, None) == 2 and L.morph_repack_w4_native(FAKE + 4, FAKE, 128, 8, None) == 3
+    assert L.morph_unpack_w4_native(None, FAKE, 128, 8, None) == 1 and L.morph_unpack_w4_native(FAKE, FAKE, 128, 12, None) == 2
+    assert L.morph_dequantize_w4_native(FAKE, FAKE, FAKE, None, 0, 128, 8, 128, None) == 1
+    assert L.morph_dequantize_w4_native(FAKE, FAKE, FAKE, FAKE, 7, 128, 8, 128, None) == 2
+    f = L.morph_linear_w4a16_native
+    def call(x=FAKE, q=FAKE, s=FAKE, z=FAKE, y=FAKE, M=4, K=256, N=64, g=128, ws=None, wsb=0):
+        return f(x, q, s, z, y, M, K, N, g, ws, wsb, None)
+    assert call(x=None) == 1 and call(q=None) == 1 and call(y=None) == 1
+    assert call(M=0) == 2 and call(K=200) == 2 and call(g=64) == 2
+    assert call(q=FAKE + 8) == 3
+    assert call(M=17) == 5 and call(M=64) == 5                          # more than 16 rows: canonical records only
+    assert call(M=4, K=4096, N=4096) == 4                               # K is split: a workspace is needed
+
+
 def test_linear_w4a16_noalloc_validation(L):
     """The allocation-free variant: same argument checks, decode sizes only, sizes beyond its array refused."""
     f = L.morph_linear_w4a16_noalloc

@@ -91,10 +91,20 @@ def test_config2_llama7b_decode(B, oracle, linear):
     w16 = W.astype(np.float16)
     w16_dev = dev(w16)
     del W
+    # the headline runs on the codes in native order: the repack against the oracle's, bit for bit, at full size
+    nat_dev = B.repack_w4_native(rec_dev[0])
+    assert np.array_equal(host(nat_dev), oracle.repack_w4_native(rec[0]))
     for M in (1, 4, 16):
         x = synth.activations(2, M, K, tensor_id=M)
         run_w4(B, oracle, x, rec_dev, rec, f"config2/{linear}")
         run_fp16(B, oracle, x, w16_dev, w16, f"config2/{linear}")
+        # and the launch bench.py times: against the oracle, and the same bits as the canonical entry point
+        ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
+        yn = host(B.linear_w4a16_native(dev(x), nat_dev, rec_dev[1], rec_dev[2], ws))
+        r = oracle.error_metric(yn, oracle.linear_w4a16(x, *rec))
+        say(f"  config2/{linear} w4a16 native M={M}: err={r['err']:.3e}")
+        assert r["finite"] and r["err"] <= TOL, (linear, M, r)
+        assert np.array_equal(yn.view(np.uint16), host(B.linear_w4a16(dev(x), *rec_dev, ws)).view(np.uint16))
 
 
 @pytest.mark.parametrize("linear", synth.LINEAR_ORDER)
