@@ -115,9 +115,9 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
 /* ---- native storage order of the 4-bit codes ----
  * The paper (Section 4.3) has the quantized variants of a layer prepared ahead of time and kept in
  * pinned host memory; how their bytes are ordered is the implementation's business.  The canonical
- * record above is the interchange form; the decode kernel for at most 16 rows can also read the codes
- * in the order its lanes consume them, which makes every load of a wave one contiguous kilobyte and
- * halves the number of loads.  Scales and zero points stay as they are.
+ * record above is the interchange form; the decode kernels for at most 64 rows can also read the codes
+ * in the order their lanes consume them: 16-byte loads per lane, whole cache lines per wave (one
+ * contiguous kilobyte per load up to 16 rows), and a half or a quarter of the load instructions.  Scales and zero points stay as they are.
  *   native array: morph_w4_native_bytes(K, N) bytes = ceil(N / 256) * (K / 32) blocks of 4096 bytes, one
  *   per (column tile of 256, k-step of 32 rows), tiles outermost.  In a block, for b = 0..3, c = 0..15,
  *   h, p = 0..1, q = 0..3, r, e = 0..1: the byte at ((2 h + p) * 64 + 16 b + c) * 16 + 4 q + 2 r + e holds,
@@ -127,7 +127,7 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
  * morph_repack_w4_native / morph_unpack_w4_native convert between the two (device arrays, exact);
  * morph_quantize_layer_native = morph_quantize_layer into qweight_tmp (canonical size) followed by the
  * repack; morph_dequantize_w4_native is morph_dequantize_w4 on the native array (the same values);
- * morph_linear_w4a16_native is morph_linear_w4a16 on it for M <= 16 and fp16 activations (the same
+ * morph_linear_w4a16_native is morph_linear_w4a16 on it for M <= 64 and fp16 activations (the same
  * bits: the arithmetic and its order do not change), MORPH_ERR_UNSUPPORTED otherwise; workspace of
  * morph_workspace_bytes(MORPH_KIND_W4A16, M, K, N).  Arguments, alignment and errors as above. */
 size_t morph_w4_native_bytes(int K, int N);
@@ -151,8 +151,7 @@ int morph_linear_w4a16_native(const void* x, const void* native, const void* sca
  * Arguments, alignment, errors and exactness as for the 4-bit calls (N % 8 == 0 here too).
  * morph_linear_w8a16: y = x * dequant(W8), kind MORPH_KIND_W8A16 for morph_workspace_bytes(), the
  * layer descriptors of morph_stack_forward() and the layer records; the codes enter the matrix
- * cores as they are (decode) or are dequantized into the LDS tile (prefill).  The persistent stack
- * launch does not take 8-bit layers (UNSUPPORTED). */
+ * cores as they are (decode) or are dequantized into the LDS tile (prefill). */
 int morph_linear_w8a16(const void* x, const int32_t* qweight, const void* scales,
                        const int32_t* qzeros, void* y, int M, int K, int N, int group_size,
                        void* workspace, size_t workspace_bytes, void* stream);

@@ -281,7 +281,7 @@ def dequantize_w4_native(native, scales, qzeros, dtype=torch.float32, group_size
 
 
 def linear_w4a16_native(x, native, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:
-    """morph_linear_w4a16 on the native code array (M <= 16, fp16)."""
+    """morph_linear_w4a16 on the native code array (M <= 64, fp16)."""
     M, K = x.shape
     N = scales.shape[1]
     assert native.numel() == w4_native_bytes(K, N), (native.numel(), K, N)

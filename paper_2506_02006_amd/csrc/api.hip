@@ -360,9 +360,9 @@ int morph_linear_w4a16_native(const void* x, const void* native, const void* sca
 {
     if (group_size != MORPH_GROUP_SIZE) return (x && native && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
     if (int rc = validate_linear(MORPH_KIND_W4A16, x, native, scales, qzeros, y, M, K, N)) return rc;
-    if (M > 16 || morph_w4_native_bytes(K, N) >= k4G) return MORPH_ERR_UNSUPPORTED;
+    if (M > 64 || morph_w4_native_bytes(K, N) >= k4G) return MORPH_ERR_UNSUPPORTED;
     const DecodePlan pl = plan_decode(MORPH_KIND_W4A16, M, K, N);
-    if (!pl.small) return MORPH_ERR_UNSUPPORTED;         // only the kernel for at most 16 rows reads this order
+    if (!pl.small) return MORPH_ERR_UNSUPPORTED;         // only the kernels of decode_small.hip read this order
     SmallArgs s;
     s.x = x; s.w = native; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
     s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = 0; s.native = 1;

@@ -479,14 +479,18 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
 // staged loads need more than the 256 registers a wave would then have).
 // ------------------------------------------------------------------------------------------------
 struct MidStage {
-    uint32_t w[8];                               // row 8b + i of the k-step: one packed word = 8 columns
+    uint32_t w[8];                               // canonical codes: row 8b + i of the k-step, one packed word = 8 columns;
+                                                 // native codes: words q = 0..3 of the lane's loads p = 0 and p = 1
 };
 struct MidGroup {
     uint32_t zq;                                 // zero points of the lane's 8 columns
     u32x4    sc;                                 // their scales
 };
 
-template <bool BF>
+// NAT: the codes come in the native storage order.  The 8 columns of lane (c, b) here are column half
+// h = c & 1 of lane (8 ch + c / 2, b) of that order: its loads 2 h and 2 h + 1, 16 bytes each; a load
+// instruction of the wave then reads eight whole cache lines instead of touching sixteen halves.
+template <bool BF, bool NAT>
 __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
     const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
     int tiles_sl, int inv_s, SmallTail t)
@@ -517,7 +521,9 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
     const uint16_t* x = (const uint16_t*)x_all + (size_t)(32 * p.slice) * K;
 
     const uint32_t row_bytes = (uint32_t)NW * 4u;
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
+    const uint32_t ksteps = (uint32_t)K >> 5;
+    const __amdgpu_buffer_rsrc_t rw = NAT ? make_rsrc(w, (uint32_t)tiles * ksteps * 4096u) : make_rsrc(w, (uint32_t)K * row_bytes);
+    const uint32_t voff_n = (uint32_t)(c & 1) * 2048u + (uint32_t)(16 * b + 8 * ch + (c >> 1)) * 16u;   // native order: load 2 h of lane (8 ch + c / 2, b)
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
     const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
     const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
@@ -540,9 +546,17 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
     auto load_stage = [&](MidStage& sg, int ks) {
         const bool     dead = ks >= ks1;
         const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
-        const uint32_t vw   = voff_w | (dead ? kOut : 0u);
+        if constexpr (NAT) {
+            const uint32_t sn = dead ? 0u : ((uint32_t)p.tile * ksteps + (uint32_t)ks) * 4096u;
+            const uint32_t vn = voff_n | (dead ? kOut : 0u);
+            const u32x4 a0 = buf_load_u32x4<kAuxStream>(rw, vn, sn), a1 = buf_load_u32x4<kAuxStream>(rw, vn, sn + 1024u);
 #pragma unroll
-        for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+            for (int q = 0; q < 4; q++) { sg.w[q] = a0[q]; sg.w[4 + q] = a1[q]; }
+        } else {
+            const uint32_t vw = voff_w | (dead ? kOut : 0u);
+#pragma unroll
+            for (int i = 0; i < 8; i++) sg.w[i] = buf_load_u32<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+        }
     };
     auto load_group = [&](MidGroup& gr, int g) {
         const bool     dead = g >= gz;
@@ -640,9 +654,15 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
                     uint32_t pr[4], ph[4];
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
-                        const uint32_t r0 = sg.w[2 * q], r1 = sg.w[2 * q + 1];
-                        pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
-                              : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                        if constexpr (NAT) {
+                            // word q of load yb / 2: bytes (yb & 1) and 2 + (yb & 1) are rows 2 q and 2 q + 1
+                            const uint32_t wq = sg.w[4 * (yb >> 1) + q];
+                            pr[q] = (yb & 1) ? __builtin_amdgcn_perm(0u, wq, 0x0c030c01u) : (wq & 0x00FF00FFu);
+                        } else {
+                            const uint32_t r0 = sg.w[2 * q], r1 = sg.w[2 * q + 1];
+                            pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                                  : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                        }
                         ph[q] = pr[q] & 0x00F000F0u;
                     }
                     const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
@@ -724,11 +744,11 @@ hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
         if constexpr (BF) return hipErrorInvalidValue;
         else if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, false, true>, kSmWaves, a, st);
         else if (a.M <= 16) return launch_small_with(decode_small_kernel<4, false, true>, kSmWaves, a, st);
-        else return hipErrorInvalidValue;
+        else return launch_small_with(decode_mid_kernel<false, true>, kSmWaves, a, st);
     }
     if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, BF, false>, kSmWaves, a, st);
     if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF, false>, kSmWaves, a, st);
-    return launch_small_with(decode_mid_kernel<BF>, kSmWaves, a, st);      // beyond 32 rows: two slices
+    return launch_small_with(decode_mid_kernel<BF, false>, kSmWaves, a, st);      // beyond 32 rows: two slices
 }
 
 }  // namespace

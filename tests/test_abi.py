@@ -100,7 +100,7 @@ def test_native_order_entry_points_validation(L):
     assert call(x=None) == 1 and call(q=None) == 1 and call(y=None) == 1
     assert call(M=0) == 2 and call(K=200) == 2 and call(g=64) == 2
     assert call(q=FAKE + 8) == 3
-    assert call(M=17) == 5 and call(M=64) == 5                          # more than 16 rows: canonical records only
+    assert call(M=65) == 5 and call(M=2048) == 5                        # more than 64 rows: canonical records only
     assert call(M=4, K=4096, N=4096) == 4                               # K is split: a workspace is needed
 
 

@@ -77,7 +77,7 @@ def test_quantize_layer_native_is_quantize_then_repack(B, oracle):
 
 
 @pytest.mark.parametrize("split", [0, 1, 3])
-@pytest.mark.parametrize("M", [1, 2, 4, 5, 16])
+@pytest.mark.parametrize("M", [1, 2, 4, 5, 16, 17, 32, 33, 64])
 def test_decode_on_native_codes(B, oracle, M, split):
     """Several column tiles with a ragged last one, with and without a split along K."""
     B.set_tuning(B.TUNE_DECODE_SPLIT, split)
@@ -99,10 +99,11 @@ def test_decode_on_native_codes(B, oracle, M, split):
         B.set_tuning(B.TUNE_DECODE_SPLIT, 0)
 
 
-def test_identity_activations_on_native_codes(B, oracle):
+@pytest.mark.parametrize("M", [16, 48])
+def test_identity_activations_on_native_codes(B, oracle, M):
     """x = rows of the identity: y must be the fp16-rounded dequantized weight, bit for bit: pins the
-    order of rows, columns and nibbles through the kernel."""
-    K, N, M = 256, 520, 16
+    order of rows, columns and nibbles through both kernels that read this order."""
+    K, N = 256, 520
     W = synth.weights(77, K, N, layer_id=3)
     qw, sc, qz = oracle.quantize_w4(W)
     D16 = oracle.dequant_w4(qw, sc, qz, dtype=np.float16)
@@ -118,10 +119,10 @@ def test_identity_activations_on_native_codes(B, oracle):
 
 def test_native_rejects_what_it_does_not_serve(B):
     K, N = 256, 264
-    x = torch.zeros((17, K), dtype=torch.float16, device="cuda")
+    x = torch.zeros((65, K), dtype=torch.float16, device="cuda")
     nat = torch.zeros(B.w4_native_bytes(K, N), dtype=torch.uint8, device="cuda")
     sc = torch.zeros((K // 128, N), dtype=torch.float16, device="cuda")
     qz = torch.zeros((K // 128, N // 8), dtype=torch.int32, device="cuda")
     with pytest.raises(B.MorphError) as e:
         B.linear_w4a16_native(x, nat, sc, qz, None)
-    assert e.value.status == 5                            # MORPH_ERR_UNSUPPORTED: more than 16 rows
+    assert e.value.status == 5                            # MORPH_ERR_UNSUPPORTED: more than 64 rows
