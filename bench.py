@@ -239,13 +239,15 @@ def main():
                         B.linear_bf16(x, r, w, out=y)
                     elif kind == B.KIND_W4A16:
                         B.linear_w4a16(x, r[0], r[1], r[2], w, out=y)
+                    elif kind == B.KIND_W4A16_NATIVE:
+                        B.linear_w4a16_native(x, r[0], r[1], r[2], w, out=y)
                     elif kind == B.KIND_W8A16:
                         B.linear_w8a16(x, r[0], r[1], r[2], w, out=y)
                     else:
                         B.linear_fp16(x, r, w, out=y)
             g = graph_of(run)
             s = timed(lambda i: g.replay(), max(2, reps // len(recs)), 2) / (max(2, reps // len(recs)) * len(recs))
-            nbytes = (synth.w4_bytes(K, N, zeros=False) if kind == B.KIND_W4A16 else
+            nbytes = (synth.w4_bytes(K, N, zeros=False) if kind in (B.KIND_W4A16, B.KIND_W4A16_NATIVE) else
                       synth.w8_bytes(K, N, zeros=False) if kind == B.KIND_W8A16 else synth.fp16_bytes(K, N))
             return {"us": round(s * 1e6, 2), "GBps": round(nbytes / s / 1e9, 1),
                     "pct_hbm": round(nbytes / s / 1e9 / HBM_PEAK_GBS * 100, 1),
@@ -276,6 +278,9 @@ def main():
                 recs = cold_pool(B.KIND_W4A16, *shapes7[name])
                 for M in (1, 4, 16):
                     d7[f"w4a16/{name}/M{M}"] = per_linear(B.KIND_W4A16, "llama7b", name, M, recs, reps=2 * len(recs))
+                recs = [(B.repack_w4_native(r[0]), r[1], r[2]) for r in recs]       # the same codes in the native order
+                for M in (1, 4, 16):
+                    d7[f"w4a16_native/{name}/M{M}"] = per_linear(B.KIND_W4A16_NATIVE, "llama7b", name, M, recs, reps=2 * len(recs))
                 del recs
             for name in order:
                 recs = cold_pool(B.KIND_FP16, *shapes7[name])
@@ -383,6 +388,9 @@ def main():
                 recs = cold_pool(B.KIND_W4A16, *shapes8[name])
                 for M in (1, 8, 32, 64):
                     d8[f"w4a16/{name}/M{M}"] = per_linear(B.KIND_W4A16, "llama3_8b", name, M, recs, reps=2 * len(recs))
+                recs = [(B.repack_w4_native(r[0]), r[1], r[2]) for r in recs]
+                for M in (1, 8, 32, 64):
+                    d8[f"w4a16_native/{name}/M{M}"] = per_linear(B.KIND_W4A16_NATIVE, "llama3_8b", name, M, recs, reps=2 * len(recs))
                 del recs
             detail["config3_llama3_8b"] = d8
 
@@ -412,25 +420,33 @@ def main():
         M5, L5 = 32, (32 if "config5" in sections else 0)
         base16 = [{name: make_fp16(*shapes7[name]) for name in order} for _ in range(L5)]
         base4 = [{name: B.quantize_layer(base16[l][name]) for name in order} for l in range(L5)]
+        base4n = [{name: B.repack_w4_native(base4[l][name][0]) for name in order} for l in range(L5)]
         d5 = {}
         for k in ((0, 8, 16, 32) if L5 else ()):
             swapped = set(synth.swapped_layers(L5, k).tolist())
-            st = B.LayerStack(4096, 11008, M5)
-            for l in range(L5):
-                if l in swapped:
-                    st.add_layer({n: ("w4",) + tuple(base4[l][n]) for n in order})
-                else:
-                    st.add_layer({n: ("fp16", base16[l][n]) for n in order})
             x5 = rand_x(M5, 4096)
-            g5 = graph_of(lambda: st.forward(x5))
-            s = timed(lambda i: g5.replay(), 10, 2) / 10
             nbytes = sum((bytes_ws if l in swapped else sum(synth.fp16_bytes(*shapes7[n]) for n in order)) for l in range(L5))
-            d5[f"k{k}"] = {"ms": round(s * 1e3, 4), "GBps": round(nbytes / s / 1e9, 1),
-                           "pct_hbm": round(nbytes / s / 1e9 / HBM_PEAK_GBS * 100, 1), "weight_GB": round(nbytes / 1e9, 3)}
-            del g5, st
+            # the 4-bit layers as canonical records, then in the native code order (the same results)
+            for native in ((False, True) if k else (False,)):
+                st = B.LayerStack(4096, 11008, M5)
+                for l in range(L5):
+                    if l in swapped and native:
+                        st.add_layer({n: ("w4n", base4n[l][n]) + tuple(base4[l][n][1:]) for n in order})
+                    elif l in swapped:
+                        st.add_layer({n: ("w4",) + tuple(base4[l][n]) for n in order})
+                    else:
+                        st.add_layer({n: ("fp16", base16[l][n]) for n in order})
+                g5 = graph_of(lambda: st.forward(x5))
+                s = timed(lambda i: g5.replay(), 10, 2) / 10
+                if native:
+                    d5[f"k{k}"].update({"native_ms": round(s * 1e3, 4), "native_GBps": round(nbytes / s / 1e9, 1)})
+                else:
+                    d5[f"k{k}"] = {"ms": round(s * 1e3, 4), "GBps": round(nbytes / s / 1e9, 1),
+                                   "pct_hbm": round(nbytes / s / 1e9 / HBM_PEAK_GBS * 100, 1), "weight_GB": round(nbytes / 1e9, 3)}
+                del g5, st
         if d5:
             detail["config5_stack_M32"] = d5
-        del base16, base4
+        del base16, base4, base4n
 
         # ---- layers changing precision in place while the 32-layer stack decodes (M = 32) ----
         if "swap" in sections:

@@ -52,7 +52,8 @@ typedef enum {
     MORPH_ERR_DEVICE = 6       /* the HIP runtime reported an error at launch                    */
 } morph_status;
 
-enum { MORPH_KIND_FP16 = 0, MORPH_KIND_W4A16 = 1, MORPH_KIND_W8A16 = 2 };
+enum { MORPH_KIND_FP16 = 0, MORPH_KIND_W4A16 = 1, MORPH_KIND_W8A16 = 2,
+       MORPH_KIND_W4A16_NATIVE = 3   /* 4-bit codes in the native storage order, see below */ };
 enum { MORPH_DTYPE_F32 = 0, MORPH_DTYPE_F16 = 1, MORPH_DTYPE_BF16 = 2 };
 enum { MORPH_GROUP_SIZE = 128 };
 
@@ -129,7 +130,9 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
  * repack; morph_dequantize_w4_native is morph_dequantize_w4 on the native array (the same values);
  * morph_linear_w4a16_native is morph_linear_w4a16 on it for M <= 64 and fp16 activations (the same
  * bits: the arithmetic and its order do not change), MORPH_ERR_UNSUPPORTED otherwise; workspace of
- * morph_workspace_bytes(MORPH_KIND_W4A16, M, K, N).  Arguments, alignment and errors as above. */
+ * morph_workspace_bytes(MORPH_KIND_W4A16, M, K, N).  Arguments, alignment and errors as above.
+ * MORPH_KIND_W4A16_NATIVE names this form in the layer descriptors and layer records below (same
+ * limits: at most 64 rows, fp16 activations) and in morph_workspace_bytes (same answer as W4A16). */
 size_t morph_w4_native_bytes(int K, int N);
 int morph_repack_w4_native(const int32_t* qweight, void* native, int K, int N, void* stream);
 int morph_unpack_w4_native(const void* native, int32_t* qweight, int K, int N, void* stream);
@@ -213,12 +216,14 @@ int morph_glue_bf16(int op, const void* a, const void* b, void* out, int M, int 
  * scratch: device buffer of morph_stack_scratch_bytes() bytes (activations between steps).
  * If tap_layer is in [0, n_layers) the inputs and outputs of that layer's four linears are also
  * copied, in order (x, qkv, a, o, r, gu, m, d), to `tap` (device, morph_stack_tap_bytes() bytes),
- * for checking each linear against a reference on its actual input. */
+ * for checking each linear against a reference on its actual input.
+ * A layer of kind MORPH_KIND_W4A16_NATIVE is refused (UNSUPPORTED, before the first launch) by the
+ * bfloat16 variant and for shapes the decode kernels for at most 64 rows do not take. */
 typedef struct {
-    int         kind;     /* MORPH_KIND_FP16 or MORPH_KIND_W4A16 */
-    const void* w;        /* fp16 [K,N]  or  int32 qweight [K,N/8] */
-    const void* scales;   /* fp16 [K/128,N]   (W4A16 only) */
-    const void* qzeros;   /* int32 [K/128,N/8] (W4A16 only) */
+    int         kind;     /* MORPH_KIND_FP16, _W4A16, _W8A16 or _W4A16_NATIVE */
+    const void* w;        /* fp16 [K,N], int32 qweight [K,N/8] (W8: [K,N/4]), or the native code array */
+    const void* scales;   /* fp16 [K/128,N]   (quantized kinds only) */
+    const void* qzeros;   /* int32 [K/128,N/8], W8: [K/128,N/4] (quantized kinds only) */
 } morph_linear_desc;
 
 typedef struct {
@@ -248,7 +253,8 @@ int morph_stack_forward_bf16(const morph_layer_desc* layers /* host */, int n_la
  * the START of the slot, so that the layer keeps its address whatever its precision.
  * Record layout: the arrays of the four linears one after the other in the order qkv, o,
  * gate_up, down; for a linear of kind FP16 its [K,N] fp16 matrix, of kind W4A16 qweight
- * [K,N/8] int32, then scales [K/128,N] fp16, then qzeros [K/128,N/8] int32; every array starts on a
+ * [K,N/8] int32 (W8A16: [K,N/4]; W4A16_NATIVE: the native code array of morph_w4_native_bytes(K, N)
+ * bytes), then scales [K/128,N] fp16, then qzeros [K/128,N/8] int32 (W8A16: [K/128,N/4]); every array starts on a
  * multiple of 256 bytes (padding in between is never read).  hidden and inter as in the stack
  * calls (multiples of 128).
  *   morph_layer_record_bytes: size of a record, a multiple of 256; 0 for a kind or shape that does

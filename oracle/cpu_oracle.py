@@ -484,7 +484,8 @@ def glue_swiglu(gu: np.ndarray) -> np.ndarray:
 # layer owns one preallocated region of GPU memory, and a swap copies a variant to the START of
 # that region, so that the layer keeps its address.  A record is the layer's arrays one after the
 # other, linear by linear (qkv, o, gate_up, down); within a linear: the fp16 weight matrix, or
-# packed codes (4-bit: eight per word, 8-bit: four per word), then scales, then packed zeros.  Every array starts on a multiple of 256 bytes.
+# packed codes (4-bit: eight per word, 8-bit: four per word; kind "w4n": the 4-bit codes as the native
+# array of O12), then scales, then packed zeros.  Every array starts on a multiple of 256 bytes.
 
 RECORD_LINEARS = ("qkv", "o", "gate_up", "down")
 RECORD_ALIGN = 256
@@ -498,6 +499,8 @@ def _record_arrays(kind: str, K: int, N: int, G: int = 128):
     """(dtype, shape) of the arrays of one linear in a record, in order."""
     if kind == "fp16":
         return [(np.float16, (K, N))]
+    if kind == "w4n":
+        return [(np.uint8, (native_w4_bytes(K, N),)), (np.float16, (K // G, N)), (np.uint32, (K // G, N // 8))]
     per_word = {"w4": 8, "w8": 4}[kind]
     return [(np.uint32, (K, N // per_word)), (np.float16, (K // G, N)), (np.uint32, (K // G, N // per_word))]
 

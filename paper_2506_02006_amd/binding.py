@@ -11,7 +11,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmorph.so")
 
-KIND_FP16, KIND_W4A16, KIND_W8A16 = 0, 1, 2
+KIND_FP16, KIND_W4A16, KIND_W8A16, KIND_W4A16_NATIVE = 0, 1, 2, 3
 DTYPE_F32, DTYPE_F16, DTYPE_BF16 = 0, 1, 2
 _DTYPES = {torch.float32: DTYPE_F32, torch.float16: DTYPE_F16, torch.bfloat16: DTYPE_BF16}
 GROUP = 128
@@ -438,7 +438,7 @@ class LayerStack:
         self.dtype = dtype                 # format of the activations (and of the weights of "fp16" layers)
         self.hidden, self.inter, self.M = hidden, inter, M
         self.device = device
-        self.layers = []      # list of dict name -> ("fp16", w) | ("w4", qw, sc, qz)
+        self.layers = []      # list of dict name -> ("fp16", w) | ("w4", qw, sc, qz) | ("w8", qw, sc, qz) | ("w4n", native, sc, qz)
         self._desc = None
         self.scratch = torch.empty(int(lib().morph_stack_scratch_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
         self.tap = torch.empty(int(lib().morph_stack_tap_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
@@ -466,6 +466,12 @@ class LayerStack:
                 if rec[0] == "fp16":
                     assert rec[1].shape == (K, N)
                     d.kind, d.w, d.scales, d.qzeros = KIND_FP16, _dev(rec[1], self.dtype, name), None, None
+                elif rec[0] == "w4n":
+                    assert rec[1].numel() == w4_native_bytes(K, N)
+                    d.kind = KIND_W4A16_NATIVE
+                    d.w = _dev(rec[1], torch.uint8, name)
+                    d.scales = _dev(rec[2], torch.float16, name)
+                    d.qzeros = _dev(rec[3], torch.int32, name)
                 elif rec[0] == "w8":
                     assert rec[1].shape == (K, N // 4)
                     d.kind = KIND_W8A16
@@ -528,7 +534,8 @@ def layer_record_desc(kind: int, base_ptr: int, hidden: int, inter: int) -> Laye
 
 def layer_record_views(kind: int, buf: torch.Tensor, hidden: int, inter: int) -> dict:
     """The arrays of a record that starts at buf[0] (uint8 tensor, host or device) as tensor views:
-    name -> ("fp16", w) | ("w4", qweight, scales, qzeros).  Offsets come from the library."""
+    name -> ("fp16", w) | ("w4" or "w8", qweight, scales, qzeros) | ("w4n", native codes, scales, qzeros).
+    Offsets come from the library."""
     assert buf.dtype == torch.uint8 and buf.is_contiguous() and buf.numel() >= layer_record_bytes(kind, hidden, inter)
     base = buf.data_ptr()
     d = layer_record_desc(kind, base, hidden, inter)
@@ -542,6 +549,9 @@ def layer_record_views(kind: int, buf: torch.Tensor, hidden: int, inter: int) ->
             return buf[off:off + nb].view(dtype).view(rows, cols)
         if kind == KIND_FP16:
             out[name] = ("fp16", view(ld.w, torch.float16, K, N))
+        elif kind == KIND_W4A16_NATIVE:
+            out[name] = ("w4n", view(ld.w, torch.uint8, 1, w4_native_bytes(K, N))[0], view(ld.scales, torch.float16, K // 128, N),
+                         view(ld.qzeros, torch.int32, K // 128, N // 8))
         else:
             per_word, tag = (4, "w8") if kind == KIND_W8A16 else (8, "w4")
             out[name] = (tag, view(ld.w, torch.int32, K, N // per_word), view(ld.scales, torch.float16, K // 128, N),

@@ -70,14 +70,32 @@ int check_sizes(int kind, int M, int K, int N)
         if (k * n * 2 >= k4G) return MORPH_ERR_UNSUPPORTED;
     } else if (kind == MORPH_KIND_W8A16) {
         if (k * n >= k4G) return MORPH_ERR_UNSUPPORTED;
+    } else if (kind == MORPH_KIND_W4A16_NATIVE) {
+        if (morph_w4_native_bytes(K, N) >= k4G) return MORPH_ERR_UNSUPPORTED;
     } else {
         if (k * n / 2 >= k4G) return MORPH_ERR_UNSUPPORTED;
     }
     return MORPH_OK;
 }
 
+inline bool known_kind(int kind)
+{
+    return kind == MORPH_KIND_FP16 || kind == MORPH_KIND_W4A16 || kind == MORPH_KIND_W8A16 || kind == MORPH_KIND_W4A16_NATIVE;
+}
+// the planner and the workspace rules know the native code order as the 4-bit kind it is
+inline int plan_kind(int kind) { return kind == MORPH_KIND_W4A16_NATIVE ? MORPH_KIND_W4A16 : kind; }
+
+// The native code order is read by the kernels of decode_small.hip only: at most 64 rows, fp16
+// activations, a shape and tuning state for which the planner picks them.
+bool native_served(int M, int K, int N, int bf)
+{
+    if (bf || M > 64 || !takes_stream(MORPH_KIND_W4A16, M, K, N)) return false;
+    return plan_decode(MORPH_KIND_W4A16, M, K, N).small;
+}
+
 size_t workspace_need(int kind, int M, int K, int N)
 {
+    kind = plan_kind(kind);
     if (!takes_stream(kind, M, K, N)) {
         const PrefillPlan pp = plan_prefill(M, K, N);
         return pp.partial_bytes ? kScratchOffset + pp.partial_bytes : 0;
@@ -91,12 +109,15 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
                int M, int K, int N, void* workspace, size_t workspace_bytes, hipStream_t st, int bf = 0)
 {
     hipError_t e;
+    const int native = kind == MORPH_KIND_W4A16_NATIVE;
+    if (native && !native_served(M, K, N, bf)) return MORPH_ERR_UNSUPPORTED;
+    kind = plan_kind(kind);
     if (takes_stream(kind, M, K, N)) {
         const DecodePlan pl = plan_decode(kind, M, K, N);
         if (pl.small) {
             SmallArgs s;
             s.x = x; s.w = w; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
-            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf; s.native = 0;
+            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf; s.native = native;
             s.slots = nullptr; s.ctl = nullptr;
             if (pl.S > 1) {
                 if (!workspace || workspace_bytes < kScratchOffset) return MORPH_ERR_WORKSPACE;
@@ -359,21 +380,9 @@ int morph_linear_w4a16_native(const void* x, const void* native, const void* sca
                               size_t workspace_bytes, void* stream)
 {
     if (group_size != MORPH_GROUP_SIZE) return (x && native && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
-    if (int rc = validate_linear(MORPH_KIND_W4A16, x, native, scales, qzeros, y, M, K, N)) return rc;
-    if (M > 64 || morph_w4_native_bytes(K, N) >= k4G) return MORPH_ERR_UNSUPPORTED;
-    const DecodePlan pl = plan_decode(MORPH_KIND_W4A16, M, K, N);
-    if (!pl.small) return MORPH_ERR_UNSUPPORTED;         // only the kernels of decode_small.hip read this order
-    SmallArgs s;
-    s.x = x; s.w = native; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
-    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = 0; s.native = 1;
-    s.slots = nullptr; s.ctl = nullptr;
-    if (pl.S > 1) {
-        if (!workspace || workspace_bytes < kScratchOffset) return MORPH_ERR_WORKSPACE;
-        if (!aligned16(workspace)) return MORPH_ERR_ALIGN;
-        s.ctl   = reinterpret_cast<int*>(workspace) + kDepartBase;
-        s.slots = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(workspace) + kCounterBytes);
-    }
-    return launch_decode_small(s, (hipStream_t)stream) == hipSuccess ? MORPH_OK : MORPH_ERR_DEVICE;
+    if (int rc = validate_linear(MORPH_KIND_W4A16_NATIVE, x, native, scales, qzeros, y, M, K, N)) return rc;
+    return run_linear(MORPH_KIND_W4A16_NATIVE, x, native, scales, qzeros, y, M, K, N, workspace, workspace_bytes,
+                      (hipStream_t)stream);
 }
 
 int morph_quantize_layer_w8(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
@@ -390,7 +399,7 @@ int morph_dequantize_w8(const int32_t* qweight, const void* scales, const int32_
 
 size_t morph_workspace_bytes(int kind, int M, int K, int N)
 {
-    if (kind != MORPH_KIND_FP16 && kind != MORPH_KIND_W4A16 && kind != MORPH_KIND_W8A16) return 0;
+    if (!known_kind(kind)) return 0;
     if (check_shape(M, K, N) != MORPH_OK) return 0;
     return workspace_need(kind, M, K, N);
 }
@@ -486,7 +495,8 @@ static int stack_forward_any(const morph_layer_desc* layers, int n_layers, void*
         const Lin lins[4] = {{&layers[l].qkv, hidden, 3 * hidden}, {&layers[l].o, hidden, hidden},
                              {&layers[l].gate_up, hidden, 2 * inter}, {&layers[l].down, inter, hidden}};
         for (const Lin& li : lins) {
-            if (li.d->kind != MORPH_KIND_FP16 && li.d->kind != MORPH_KIND_W4A16 && li.d->kind != MORPH_KIND_W8A16) return MORPH_ERR_SHAPE;
+            if (!known_kind(li.d->kind)) return MORPH_ERR_SHAPE;
+            if (li.d->kind == MORPH_KIND_W4A16_NATIVE && !native_served(M, li.K, li.N, bf)) return MORPH_ERR_UNSUPPORTED;
             if (int rc = validate_linear(li.d->kind, x_io, li.d->w, li.d->scales, li.d->qzeros, scratch, M, li.K, li.N))
                 return rc;
             size_t nb = workspace_need(li.d->kind, M, li.K, li.N);
@@ -568,7 +578,7 @@ struct RecordLayout {
 RecordLayout record_layout(int kind, int hidden, int inter)
 {
     RecordLayout L{};
-    if (kind != MORPH_KIND_FP16 && kind != MORPH_KIND_W4A16 && kind != MORPH_KIND_W8A16) return L;
+    if (!known_kind(kind)) return L;
     if (hidden < MORPH_GROUP_SIZE || inter < MORPH_GROUP_SIZE || hidden % MORPH_GROUP_SIZE || inter % MORPH_GROUP_SIZE) return L;
     const size_t KN[4][2] = {{(size_t)hidden, 3 * (size_t)hidden}, {(size_t)hidden, (size_t)hidden},
                              {(size_t)hidden, 2 * (size_t)inter}, {(size_t)inter, (size_t)hidden}};
@@ -580,7 +590,7 @@ RecordLayout record_layout(int kind, int hidden, int inter)
             L.off[l][1] = L.off[l][2] = 0;
         } else {
             const size_t per_word = kind == MORPH_KIND_W8A16 ? 4 : 8;
-            L.off[l][0] = pos; pos += up256(K * (N / per_word) * 4);
+            L.off[l][0] = pos; pos += up256(kind == MORPH_KIND_W4A16_NATIVE ? morph_w4_native_bytes((int)K, (int)N) : K * (N / per_word) * 4);
             L.off[l][1] = pos; pos += up256(G * N * 2);
             L.off[l][2] = pos; pos += up256(G * (N / per_word) * 4);
         }

@@ -226,7 +226,8 @@ def test_layer_record_layout_agrees_with_oracle(L):
         lin16[name] = (W.astype(np.float16),)
         lin4[name] = O.quantize_w4(W)
     lin8 = {name: O.quantize_w8(synth.weights(92, *shapes[name], tensor_id=t)) for t, name in enumerate(O.RECORD_LINEARS)}
-    for kind, kname, lin in ((0, "fp16", lin16), (1, "w4", lin4), (2, "w8", lin8)):
+    lin4n = {name: (O.repack_w4_native(q),) + (s, z) for name, (q, s, z) in lin4.items()}
+    for kind, kname, lin in ((0, "fp16", lin16), (1, "w4", lin4), (2, "w8", lin8), (3, "w4n", lin4n)):
         rec = O.layer_record_pack(kname, lin, h, i)
         assert L.morph_layer_record_bytes(kind, h, i) == rec.size
         raw = np.zeros(rec.size + 256, np.uint8)
@@ -256,12 +257,13 @@ def test_layer_record_and_swap_validation(L):
     assert L.morph_layer_record_bytes(1, 4096, 11008) == 105140224
     n_w = 4096 * 12288 + 4096 * 4096 + 4096 * 22016 + 11008 * 4096
     assert L.morph_layer_record_bytes(2, 4096, 11008) == n_w + n_w // 128 * 2 + n_w // 128      # a byte per weight, scales, zeros
-    assert L.morph_layer_record_bytes(3, 4096, 11008) == 0 and L.morph_layer_record_bytes(1, 100, 128) == 0
+    assert L.morph_layer_record_bytes(3, 4096, 11008) == 105140224                             # native order: whole tiles here, the same size
+    assert L.morph_layer_record_bytes(4, 4096, 11008) == 0 and L.morph_layer_record_bytes(1, 100, 128) == 0
     assert L.morph_layer_record_bytes(1, 128, 0) == 0
     assert L.morph_layer_record_desc(1, None, 128, 128, ctypes.byref(d)) == 1
     assert L.morph_layer_record_desc(1, B256, 128, 128, None) == 1
     assert L.morph_layer_record_desc(1, B256 + 16, 128, 128, ctypes.byref(d)) == 3
-    assert L.morph_layer_record_desc(3, B256, 128, 128, ctypes.byref(d)) == 2
+    assert L.morph_layer_record_desc(4, B256, 128, 128, ctypes.byref(d)) == 2
     need = L.morph_layer_record_bytes(1, 128, 128)
     assert L.morph_layer_swap_async(None, need, B256, 1, 128, 128, None) == 1
     assert L.morph_layer_swap_async(B256, need, None, 1, 128, 128, None) == 1

@@ -303,6 +303,7 @@ def test_config5_mixed_stack(B, oracle):
         w4_dev.append(q)
     say(f"  config5: 32 layers built in {time.time() - t0:.1f} s")
     x0 = oracle.rms(synth.activations(5, M, hidden).astype(np.float64)).astype(np.float16)
+    nat_dev = [{n: B.repack_w4_native(w4_dev[l][n][0]) for n in synth.LINEAR_ORDER} for l in range(L)]
     for ki, k in enumerate((0, 8, 16, 32)):
         swapped = set(synth.swapped_layers(L, k).tolist())
         st = B.LayerStack(hidden, inter, M)
@@ -331,6 +332,18 @@ def test_config5_mixed_stack(B, oracle):
         assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
         rmsv = np.sqrt((outs[0].astype(np.float64) ** 2).mean(axis=1))
         assert np.all(np.abs(rmsv - 1.0) < 1e-2)
+        # the same stack with its 4-bit layers in the native code order: the same bytes out
+        if k:
+            stn = B.LayerStack(hidden, inter, M)
+            for l in range(L):
+                if l in swapped:
+                    stn.add_layer({n: ("w4n", nat_dev[l][n]) + tuple(w4_dev[l][n][1:]) for n in synth.LINEAR_ORDER})
+                else:
+                    stn.add_layer({n: ("fp16", fp16_dev[l][n]) for n in synth.LINEAR_ORDER})
+            xn = dev(x0).clone()
+            stn.forward(xn)
+            torch.cuda.synchronize()
+            assert np.array_equal(host(xn).view(np.uint16), outs[0].view(np.uint16)), k
     # one layer at a time against the oracle's own layer (full size), input to output:
     # one fp16 layer and one 4-bit layer, each fed the normalised input x0
     f16 = lambda v: np.asarray(v, np.float64).astype(np.float16)

@@ -126,3 +126,19 @@ def test_native_rejects_what_it_does_not_serve(B):
     with pytest.raises(B.MorphError) as e:
         B.linear_w4a16_native(x, nat, sc, qz, None)
     assert e.value.status == 5                            # MORPH_ERR_UNSUPPORTED: more than 64 rows
+
+
+def test_stack_refuses_native_layers_with_bfloat16_activations(B):
+    """Only the fp16 decode kernels read the native order: the bfloat16 stack says so before any launch."""
+    hidden, inter, M = 128, 256, 4
+    st = B.LayerStack(hidden, inter, M, dtype=torch.bfloat16)
+    layer = {}
+    for name, (K, N) in (("qkv", (hidden, 3 * hidden)), ("o", (hidden, hidden)), ("gate_up", (hidden, 2 * inter)), ("down", (inter, hidden))):
+        layer[name] = ("w4n", torch.zeros(B.w4_native_bytes(K, N), dtype=torch.uint8, device="cuda"),
+                       torch.zeros((K // 128, N), dtype=torch.float16, device="cuda"),
+                       torch.zeros((K // 128, N // 8), dtype=torch.int32, device="cuda"))
+    st.add_layer(layer)
+    x = torch.zeros((M, hidden), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.MorphError) as e:
+        st.forward(x)
+    assert e.value.status == 5

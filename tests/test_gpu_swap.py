@@ -24,7 +24,7 @@ from paper_2506_02006_amd import synth
 pytestmark = pytest.mark.gpu
 
 TOL = 5e-3
-KINDS = {"fp16": 0, "w4": 1, "w8": 2}
+KINDS = {"fp16": 0, "w4": 1, "w8": 2, "w4n": 3}          # w4n: the 4-bit codes in the native storage order
 
 
 @pytest.fixture(scope="module")
@@ -57,13 +57,14 @@ def make_layers(oracle, hidden, inter, n_layers, config_id):
     shapes = oracle.layer_shapes(hidden, inter)
     layers = []
     for l in range(n_layers):
-        v = {"fp16": {}, "w4": {}, "w8": {}}
+        v = {"fp16": {}, "w4": {}, "w8": {}, "w4n": {}}
         for t, name in enumerate(oracle.RECORD_LINEARS):
             K, N = shapes[name]
             W = synth.weights(config_id, K, N, layer_id=l, tensor_id=t)
             v["fp16"][name] = (W.astype(np.float16),)
             v["w4"][name] = oracle.quantize_w4(W)
             v["w8"][name] = oracle.quantize_w8(W)
+            v["w4n"][name] = (oracle.repack_w4_native(v["w4"][name][0]),) + tuple(v["w4"][name][1:])
         layers.append(v)
     return layers
 
@@ -71,7 +72,7 @@ def make_layers(oracle, hidden, inter, n_layers, config_id):
 def build_swap_stack(B, oracle, layers, hidden, inter, M, start_kind="fp16"):
     st = B.SwapStack(hidden, inter, M, len(layers))
     for l, v in enumerate(layers):
-        for kname in ("fp16", "w4", "w8"):
+        for kname in ("fp16", "w4", "w8", "w4n"):
             rec = st.new_host_record(KINDS[kname])
             rec.numpy()[:] = oracle.layer_record_pack(kname, v[kname], hidden, inter)
             st.set_host_record(l, KINDS[kname], rec)
@@ -211,15 +212,19 @@ def test_a_swap_every_step_without_host_synchronisation(B, oracle):
         kinds[l] = kname
 
 
-def test_swap_through_all_three_variants(B, oracle):
-    """fp16 -> 8-bit -> 4-bit -> fp16 on one layer (Section 4.3 lists INT8 next to INT4 among the
-    variants, and transitions between them), every state compared with a plain stack of that mix."""
+def test_swap_through_all_variants(B, oracle):
+    """fp16 -> 8-bit -> 4-bit -> 4-bit in the native code order -> fp16 on one layer (Section 4.3 lists
+    INT8 next to INT4 among the variants, and transitions between them), every state compared with a
+    plain stack of that mix; the two orders of the 4-bit codes give the same bits."""
     hidden, inter, n_layers, M = 256, 384, 4, 6
     layers = make_layers(oracle, hidden, inter, n_layers, 85)
     st = build_swap_stack(B, oracle, layers, hidden, inter, M)
     x0 = oracle.rms(synth.activations(85, M, hidden).astype(np.float64)).astype(np.float16)
     kinds = ["fp16"] * n_layers
-    for kname in ("w8", "w4", "fp16"):
+    w4_kinds = [k if l != 2 else "w4" for l, k in enumerate(kinds)]
+    assert same_bits(reference_step(B, layers, w4_kinds, hidden, inter, M, x0),
+                     reference_step(B, layers, [k.replace("w4", "w4n") for k in w4_kinds], hidden, inter, M, x0))
+    for kname in ("w8", "w4", "w4n", "fp16"):
         st.swap(2, KINDS[kname])
         x = dev(x0).clone()
         st.step(x)                                           # still the previous variant

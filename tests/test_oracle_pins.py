@@ -489,6 +489,12 @@ def test_p9_record_sizes_match_paper_and_arrays(oracle):
         raw += K * N // 2 + (K // 128) * N * 2 + (K // 128) * N // 2
     assert oracle.layer_record_bytes("w4", h, i) > raw      # the packed zeros of one group row are 64 .. 192 bytes
     assert oracle.layer_record_bytes("w4", h, i) % 256 == 0
+    # native code order: the same size when every N is a multiple of 256, whole padded tiles otherwise.
+    # hidden 128, inter 256 by hand (codes + scales + zeros, each rounded up to 256):
+    #   qkv 128x384: 2 tiles x 4 k-steps x 4096 + 768 + 256;  o 128x128: 16384 + 256 + 256;
+    #   gate_up 128x512: 32768 + 1024 + 256;  down 256x128: 8 k-steps x 4096 + 512 + 256
+    assert oracle.layer_record_bytes("w4n", 4096, 11008) == 105_140_224
+    assert oracle.layer_record_bytes("w4n", 128, 256) == 33792 + 16896 + 34048 + 33536
 
 
 def test_p9_record_round_trip_and_order(oracle):
@@ -516,6 +522,14 @@ def test_p9_record_round_trip_and_order(oracle):
     x = synth.activations(91, 3, h)
     back = oracle.layer_record_unpack("w4", rec, h, i)
     assert np.array_equal(oracle.linear_w4a16(x, *back["o"]), oracle.linear_w4a16(x, *w4["o"]))
+    # the native-order record holds the same codes: unpacking its code arrays gives the canonical ones back
+    w4n = {name: (oracle.repack_w4_native(w4[name][0]),) + tuple(w4[name][1:]) for name in oracle.RECORD_LINEARS}
+    recn = oracle.layer_record_pack("w4n", w4n, h, i)
+    assert recn.size == oracle.layer_record_bytes("w4n", h, i)
+    backn = oracle.layer_record_unpack("w4n", recn, h, i)
+    for name, (K, N) in oracle.layer_shapes(h, i).items():
+        assert np.array_equal(oracle.unpack_w4_native(backn[name][0], K, N), np.asarray(w4[name][0]).view(np.uint32))
+        assert np.array_equal(backn[name][1].view(np.uint16), w4[name][1].view(np.uint16))
 
 
 def test_p9_swap_in_place_keeps_the_address_and_the_rest(oracle):
