@@ -120,7 +120,7 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
  * in the order their lanes consume them: 16-byte loads per lane, whole cache lines per wave (one
  * contiguous kilobyte per load up to 16 rows), and a half or a quarter of the load instructions.  Scales and zero points stay as they are.
  *   native array: morph_w4_native_bytes(K, N) bytes = ceil(N / 256) * (K / 32) blocks of 4096 bytes, one
- *   per (column tile of 256, k-step of 32 rows), tiles outermost.  In a block, for b = 0..3, c = 0..15,
+ *   per (k-step of 32 rows, column tile of 256), k-steps outermost (block number = k-step * tiles + tile).  In a block, for b = 0..3, c = 0..15,
  *   h, p = 0..1, q = 0..3, r, e = 0..1: the byte at ((2 h + p) * 64 + 16 b + c) * 16 + 4 q + 2 r + e holds,
  *   for row 32 ks + 8 b + 2 q + r, the codes of columns 256 tile + 16 c + 8 h + 4 p + 2 e (low nibble) and
  *   the next one (high nibble), i.e. byte 2 p + e of canonical word 32 tile + 2 c + h of that row.  Columns

@@ -146,15 +146,17 @@ def dequant_w4(qw, sc, qz, G: int = 128, dtype=np.float32) -> np.ndarray:
 
 def native_w4_bytes(K: int, N: int) -> int:
     """O12.  Bytes of the native code array: column tiles of 256 (the last one padded), k-steps of 32
-    rows, 4096 bytes per (tile, k-step) block."""
+    rows, 4096 bytes per (k-step, tile) block."""
     return ((N + 255) // 256) * (K // 32) * 4096
 
 
-def native_w4_position(k, n, K: int):
+def native_w4_position(k, n, K: int, N: int):
     """O12.  Where the code of row k, column n sits in the native array: (byte offset, nibble), nibble 0
     = bits 3..0.  Works on integers and on numpy integer arrays alike.
 
-    A block = one column tile of 256 and one k-step of 32 rows, blocks in (tile, k-step) order.  Inside
+    A block = one column tile of 256 and one k-step of 32 rows, blocks in (k-step, tile) order: the
+    blocks of the ceil(N / 256) tiles of a k-step follow one another (what the workgroups of a launch
+    read at the same time then lies together instead of whole tiles apart).  Inside
     a block the decode kernel's lane (c, b), c = 0..15, b = 0..3, lane number 16 b + c, owns columns
     16 c .. 16 c + 15 of the tile and rows 8 b .. 8 b + 7 of the k-step: 64 bytes, fetched by four
     16-byte loads.  Load i = 2 h + p covers column half h (columns 8 h .. 8 h + 7 of the lane's 16) and
@@ -162,7 +164,7 @@ def native_w4_position(k, n, K: int):
     a load's 1024 bytes hold the 64 lanes' 16 bytes in lane order.  A lane's 16 bytes are four words,
     word q for rows 2 q, 2 q + 1 of its 8; a word's byte 2 r + e belongs to row 2 q + r and column
     pair 2 p + e; a byte holds the pair's even column in its low nibble, the odd one in its high."""
-    KS = K // 32
+    T = (N + 255) // 256
     tile, cn = n // 256, n % 256
     c, col = cn // 16, cn % 16
     h, pair, odd = col // 8, (col % 8) // 2, col % 2
@@ -170,7 +172,7 @@ def native_w4_position(k, n, K: int):
     ks, kr = k // 32, k % 32
     b, q, r = kr // 8, (kr % 8) // 2, kr % 2
     lane, i = 16 * b + c, 2 * h + p
-    byte = (((tile * KS + ks) * 4 + i) * 64 + lane) * 16 + 4 * q + 2 * r + e
+    byte = (((ks * T + tile) * 4 + i) * 64 + lane) * 16 + 4 * q + 2 * r + e
     return byte, odd
 
 
@@ -182,7 +184,7 @@ def repack_w4_native(qw: np.ndarray) -> np.ndarray:
     assert K % 32 == 0
     codes = unpack_w4(qw, N)
     kk, nn = np.meshgrid(np.arange(K, dtype=np.int64), np.arange(N, dtype=np.int64), indexing="ij")
-    byte, odd = native_w4_position(kk, nn, K)
+    byte, odd = native_w4_position(kk, nn, K, N)
     out = np.zeros(native_w4_bytes(K, N), np.uint8)
     low = odd == 0
     out[byte[low]] |= codes[low]                      # every byte is named once per nibble
@@ -195,7 +197,7 @@ def unpack_w4_native(native: np.ndarray, K: int, N: int) -> np.ndarray:
     native = _c(native, np.uint8)
     assert native.size == native_w4_bytes(K, N) and N % 8 == 0
     kk, nn = np.meshgrid(np.arange(K, dtype=np.int64), np.arange(N, dtype=np.int64), indexing="ij")
-    byte, odd = native_w4_position(kk, nn, K)
+    byte, odd = native_w4_position(kk, nn, K, N)
     codes = (native[byte] >> (4 * odd).astype(np.uint8)) & 0xF
     qw = np.zeros((K, N // 8), np.uint32)
     for j in range(8):

@@ -305,7 +305,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
         const uint32_t dm   = dead ? kOut : 0u;
         const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
         if constexpr (NAT) {
-            const uint32_t sn = dead ? 0u : ((uint32_t)p.tile * ksteps + (uint32_t)ks) * 4096u;
+            const uint32_t sn = dead ? 0u : ((uint32_t)ks * (uint32_t)tiles + (uint32_t)p.tile) * 4096u;
 #pragma unroll
             for (int i = 0; i < 4; i++) sg.w[i] = buf_load_u32x4<kAuxStream>(rw, ((uint32_t)lane * 16u) | dm, sn + (uint32_t)i * 1024u);
         } else {
@@ -547,7 +547,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
         const bool     dead = ks >= ks1;
         const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
         if constexpr (NAT) {
-            const uint32_t sn = dead ? 0u : ((uint32_t)p.tile * ksteps + (uint32_t)ks) * 4096u;
+            const uint32_t sn = dead ? 0u : ((uint32_t)ks * (uint32_t)tiles + (uint32_t)p.tile) * 4096u;
             const uint32_t vn = voff_n | (dead ? kOut : 0u);
             const u32x4 a0 = buf_load_u32x4<kAuxStream>(rw, vn, sn), a1 = buf_load_u32x4<kAuxStream>(rw, vn, sn + 1024u);
 #pragma unroll

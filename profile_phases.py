@@ -82,7 +82,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--M", default="1,16")
     ap.add_argument("--family", default=None)
-    ap.add_argument("--native", action="store_true", help="the codes in native order (morph_linear_w4a16_native, M <= 16)")
+    ap.add_argument("--native", action="store_true", help="the codes in native order (morph_linear_w4a16_native)")
     ap.add_argument("--prefill", action="store_true", help="shader clock and barrier share inside the k loop of the prefill kernels")
     args = ap.parse_args()
     if args.family is None:
@@ -107,7 +107,7 @@ def main():
             y = torch.empty((M, N), device=dev, dtype=torch.float16)
             ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
 
-            nats = [B.repack_w4_native(r[0]) for r in recs] if args.native and M <= 16 else None
+            nats = [B.repack_w4_native(r[0]) for r in recs] if args.native else None
 
             def run():
                 for i, r in enumerate(recs):

@@ -844,7 +844,7 @@ def _native_pins_hold(position, repack, unpack, nbytes):
     trip; size."""
     K, N = 128, 512
     for k, n, byte, nib in _native_golden():
-        b, o = position(k, n, K)
+        b, o = position(k, n, K, N)
         if (int(b), int(o)) != (byte, nib):
             return False
     if nbytes(K, N) != 2 * 4 * 4096 or nbytes(256, 264) != 2 * 8 * 4096:
@@ -859,7 +859,7 @@ def _native_pins_hold(position, repack, unpack, nbytes):
         nz = np.flatnonzero(nat)
         if nz.size != 1 or nat.size != nbytes(K, N):
             return False
-        block = (n // 256) * (K // 32) + k // 32
+        block = (k // 32) * ((N + 255) // 256) + n // 256
         if nz[0] // 4096 != block or int(nat[nz[0]]) not in (code, code << 4):
             return False
     # every code survives the round trip, ragged last tile included
@@ -883,8 +883,8 @@ def test_p13_native_code_order_pinned_by_hand_positions(oracle):
 def test_p13_native_pins_catch_planted_mistakes(oracle):
     """Plausible slips in the position formula (swapped roles, a forgotten factor) must fail the pins."""
     def variant(**swap):
-        def position(k, n, K):
-            KS = K // 32
+        def position(k, n, K, N):
+            KS, T = K // 32, (N + 255) // 256
             tile, cn = n // 256, n % 256
             c, col = cn // 16, cn % 16
             h, pair, odd = col // 8, (col % 8) // 2, col % 2
@@ -897,20 +897,20 @@ def test_p13_native_pins_catch_planted_mistakes(oracle):
                 q, r = kr % 4, (kr % 8) // 4
             lane = 16 * b + c if not swap.get("lane") else 4 * c + b
             i = 2 * h + p if not swap.get("load") else 2 * p + h
-            blk = tile * KS + ks if not swap.get("blk") else ks * ((512 + 255) // 256) + tile
+            blk = ks * T + tile if not swap.get("blk") else tile * KS + ks
             byte = ((blk * 4 + i) * 64 + lane) * 16 + 4 * q + (2 * r + e if not swap.get("re") else 2 * e + r)
             return byte, (odd if not swap.get("nib") else 1 - odd)
         def repack(qw):
             K, N = qw.shape[0], qw.shape[1] * 8
             codes = oracle.unpack_w4(qw, N)
             kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
-            byte, odd = position(kk, nn, K)
+            byte, odd = position(kk, nn, K, N)
             out = np.zeros(oracle.native_w4_bytes(K, N), np.uint8)
             np.bitwise_or.at(out, byte, (codes << (4 * odd)).astype(np.uint8))
             return out
         def unpack(nat, K, N):
             kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
-            byte, odd = position(kk, nn, K)
+            byte, odd = position(kk, nn, K, N)
             codes = (nat[byte] >> (4 * odd).astype(np.uint8)) & 0xF
             qw = np.zeros((K, N // 8), np.uint32)
             for j in range(8):
