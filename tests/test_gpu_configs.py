@@ -114,9 +114,18 @@ def test_config3_llama3_8b_heavy_tails(B, oracle, linear):
     rec = oracle.quantize_w4(W)
     rec_dev = tuple(dev(a) for a in rec)
     del W
+    nat_dev = B.repack_w4_native(rec_dev[0])
     for M in (1, 8, 32, 64):
         x = synth.activations(3, M, K, tensor_id=M)
         run_w4(B, oracle, x, rec_dev, rec, f"config3/{linear}")
+        # the same launch on the codes in native order (both kernels that read it, M = 64 in two slices of rows):
+        # against the oracle, and the same bits as the canonical entry point
+        ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
+        yn = host(B.linear_w4a16_native(dev(x), nat_dev, rec_dev[1], rec_dev[2], ws))
+        r = oracle.error_metric(yn, oracle.linear_w4a16(x, *rec))
+        say(f"  config3/{linear} w4a16 native M={M}: err={r['err']:.3e}")
+        assert r["finite"] and r["err"] <= TOL, (linear, M, r)
+        assert np.array_equal(yn.view(np.uint16), host(B.linear_w4a16(dev(x), *rec_dev, ws)).view(np.uint16))
 
 
 def sample_positions(rng, M, N):

@@ -59,9 +59,11 @@ def record(fn):
     return g
 
 
-def test_headline_step_under_graph_replay(B, oracle):
+@pytest.mark.parametrize("code_order", ["canonical", "native"])
+def test_headline_step_under_graph_replay(B, oracle, code_order):
     """The twelve launches of the benchmark step (four W4A16 linears of a 7B-shaped layer at M = 1, 4, 16,
-    one workspace shared by all of them) as one graph."""
+    one workspace shared by all of them) as one graph, on canonical records and on the native code order
+    (the form bench.py's headline runs on)."""
     shapes = synth.LAYER_SHAPES["llama7b"]
     order = synth.LINEAR_ORDER
     Ms = (1, 4, 16)
@@ -70,6 +72,7 @@ def test_headline_step_under_graph_replay(B, oracle):
         K, N = shapes[name]
         recs[name] = oracle.quantize_w4(synth.weights(93, K, N, tensor_id=synth._TENSOR_ID[name]))
         recs_d[name] = tuple(dev(r) for r in recs[name])
+    nats_d = {name: B.repack_w4_native(recs_d[name][0]) for name in order} if code_order == "native" else None
     xs_h = {(M, K): synth.activations(93, M, K, layer_id=M).astype(np.float16) for M in Ms for K in (4096, 11008)}
     xs = {k: dev(v) for k, v in xs_h.items()}
     ys = {(M, name): torch.zeros((M, shapes[name][1]), device="cuda", dtype=torch.float16) for M in Ms for name in order}
@@ -79,7 +82,10 @@ def test_headline_step_under_graph_replay(B, oracle):
         for M in Ms:
             for name in order:
                 K, N = shapes[name]
-                B.linear_w4a16(xs[(M, K)], *recs_d[name], ws, out=ys[(M, name)])
+                if nats_d is not None:
+                    B.linear_w4a16_native(xs[(M, K)], nats_d[name], recs_d[name][1], recs_d[name][2], ws, out=ys[(M, name)])
+                else:
+                    B.linear_w4a16(xs[(M, K)], *recs_d[name], ws, out=ys[(M, name)])
 
     step()
     torch.cuda.synchronize()
@@ -111,10 +117,10 @@ def test_headline_step_under_graph_replay(B, oracle):
     say(f"  headline step: {REPLAYS} replays equal to the eager step; worst error against the oracle {worst:.2e}")
 
 
-@pytest.mark.parametrize("M,kinds", [(32, ("w4", "fp16", "fp16", "w4")), (64, ("fp16", "w8", "w4"))])
+@pytest.mark.parametrize("M,kinds", [(32, ("w4", "fp16", "fp16", "w4")), (64, ("fp16", "w8", "w4")), (40, ("w4n", "fp16", "w4n"))])
 def test_stack_step_under_graph_replay(B, oracle, M, kinds):
-    """A mixed stack step (linears, glue, copies: kernel nodes only) as one graph, per-linear launches and
-    the persistent launch."""
+    """A mixed stack step (linears, glue, copies: kernel nodes only) as one graph; w4n = a 4-bit layer with its
+    codes in the native order."""
     hidden, inter = 1024, 2816
     st = B.LayerStack(hidden, inter, M)
     shapes = {"qkv": (hidden, 3 * hidden), "o": (hidden, hidden), "gate_up": (hidden, 2 * inter), "down": (inter, hidden)}
@@ -126,6 +132,9 @@ def test_stack_step_under_graph_replay(B, oracle, M, kinds):
                 lin[name] = ("fp16", dev(W.astype(np.float16)))
             elif kind == "w4":
                 lin[name] = ("w4",) + tuple(dev(r) for r in oracle.quantize_w4(W))
+            elif kind == "w4n":
+                q, sc, z = oracle.quantize_w4(W)
+                lin[name] = ("w4n", dev(oracle.repack_w4_native(q)), dev(sc), dev(z))
             else:
                 lin[name] = ("w8",) + tuple(dev(r) for r in oracle.quantize_w8(W))
         st.add_layer(lin)
