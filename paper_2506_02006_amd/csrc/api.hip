@@ -724,6 +724,7 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     if ((rc = morph_repack_w4_native(q, nat, kWK, kWN, stream))) return rc;
     if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 1, kWK, kWN, 128, ws, wsb, stream))) return rc;
     if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 16, kWK, kWN, 128, ws, wsb, stream))) return rc;
+    if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 33, kWK, kWN, 128, ws, wsb, stream))) return rc;   // the kernel for 17 to 64 rows
     if ((rc = morph_dequantize_w4_native(nat, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
     if ((rc = morph_unpack_w4_native(nat, q, kWK, kWN, stream))) return rc;
     // the 8-bit variant: its codes (32 KB) go where the fp32 dummy matrix was
