@@ -541,7 +541,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
 
     int      ga = 0, gz = 0, ks1 = 0;
     MidStage st[kRing];
-    MidGroup gcur, gnxt;
+    MidGroup gnxt;
     u32x4    xg[8];
     auto load_stage = [&](MidStage& sg, int ks) {
         const bool     dead = ks >= ks1;
@@ -615,23 +615,54 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
     };
 
     auto run_pass = [&](auto&& sink) {
-        // gacc[mt][2 yb]: sum of x * byte, gacc[mt][2 yb + 1]: sum of x * (byte & 0xF0), over the open group
-        f32x4 gacc[2][8], xs[2];
+        // Two sets of group sums: while the MFMAs of a group fill one set, the sums of the group before are
+        // folded out of the other, a quarter of them in each k-step, so that the fold's vector work runs
+        // beside the matrix core instead of after it (one wave has a SIMD to itself here: nothing else
+        // would fill the gap).
+        // gacc[set][mt][2 yb]: sum of x * byte, gacc[set][mt][2 yb + 1]: sum of x * (byte & 0xF0), over the set's group
+        f32x4 gacc[2][2][8], xs[2][2];
         float yr[2][8][4];                               // running results, column j of the lane, row 16 mt + 4 b + r
+        MidGroup gs[2];                                  // scales and zero points of the group a set holds
 #pragma unroll
         for (int mt = 0; mt < 2; mt++) {
 #pragma unroll
             for (int j = 0; j < 8; j++) {
-                gacc[mt][j] = zero4;
+                gacc[0][mt][j] = zero4;
+                gacc[1][mt][j] = zero4;
 #pragma unroll
                 for (int r = 0; r < 4; r++) yr[mt][j][r] = 0.f;
             }
-            xs[mt] = zero4;
+            xs[0][mt] = zero4;
+            xs[1][mt] = zero4;
         }
+        gs[0].zq = 0u; gs[0].sc = u32x4{0u, 0u, 0u, 0u};
+        gs[1] = gs[0];                                   // an empty set folds to nothing
+        // columns 2 yb, 2 yb + 1 of the lane: the sums of the set's group go into the running results
+        auto fold_pair = [&](auto setc, int yb) __attribute__((always_inline)) {
+            constexpr int P = decltype(setc)::value;
+            const uint32_t zw  = gs[P].zq;
+            const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;         // z of the even columns; 16 z of the odd ones
+            const uint32_t sw = gs[P].sc[yb];
+            const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+            const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+            const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
+            const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
+#pragma unroll
+            for (int mt = 0; mt < 2; mt++) {
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    const float d = gacc[P][mt][2 * yb][r] - gacc[P][mt][2 * yb + 1][r];
+                    yr[mt][2 * yb][r]     = __builtin_fmaf(-c_lo, xs[P][mt][r], __builtin_fmaf(s_lo, d, yr[mt][2 * yb][r]));
+                    yr[mt][2 * yb + 1][r] = __builtin_fmaf(-c_hi, xs[P][mt][r], __builtin_fmaf(s_hi, gacc[P][mt][2 * yb + 1][r], yr[mt][2 * yb + 1][r]));
+                }
+            }
+        };
         int xb = 0;                                      // the x buffer of the open group
         store_xgroup(0);
-        for (int g = ga; g < gz; g++) {
-            gcur = gnxt;
+        auto group = [&](auto setc, auto foldc, int g) __attribute__((always_inline)) {
+            constexpr int  P = decltype(setc)::value;
+            constexpr bool FOLD = decltype(foldc)::value;    // the other set holds a group (not so in a pass's first group)
+            gs[P] = gnxt;
 #pragma unroll
             for (int u = 0; u < kRing; u++) {
                 load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
@@ -647,7 +678,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
                     const half8_t xv = bit_cast<half8_t>(xl[xb * 512 + (16 * mt + c) * 16 + ((4 * u + b) ^ c)]);
                     if constexpr (BF) xa[mt] = bf16x8_up64(xv);
                     else xa[mt] = xv;
-                    xs[mt] = mfma_small<BF>(xa[mt], tiny, first ? zero4 : xs[mt]);
+                    xs[P][mt] = mfma_small<BF>(xa[mt], tiny, first ? zero4 : xs[P][mt]);
                 }
 #pragma unroll
                 for (int yb = 0; yb < 4; yb++) {
@@ -669,33 +700,40 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
                     const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
 #pragma unroll
                     for (int mt = 0; mt < 2; mt++) {
-                        gacc[mt][2 * yb]     = mfma_small<BF>(xa[mt], bbyte, first ? zero4 : gacc[mt][2 * yb]);
-                        gacc[mt][2 * yb + 1] = mfma_small<BF>(xa[mt], bhigh, first ? zero4 : gacc[mt][2 * yb + 1]);
+                        gacc[P][mt][2 * yb]     = mfma_small<BF>(xa[mt], bbyte, first ? zero4 : gacc[P][mt][2 * yb]);
+                        gacc[P][mt][2 * yb + 1] = mfma_small<BF>(xa[mt], bhigh, first ? zero4 : gacc[P][mt][2 * yb + 1]);
+                    }
+                }
+                if constexpr (FOLD) {
+                    fold_pair(std::integral_constant<int, 1 - P>{}, u);      // a quarter of the group before
+                    // one MFMA, then the vector instructions that fit beside it
+#pragma unroll
+                    for (int i = 0; i < 18; i++) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
             store_xgroup(xb ^ 1);                        // the next group's x, requested at the top of this one
             xb ^= 1;
-            // the group's sums go into the running results
-            const uint32_t zw  = gcur.zq;
-            const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;         // z of the even columns; 16 z of the odd ones
+        };
+        constexpr std::integral_constant<int, 0> set0{};
+        constexpr std::integral_constant<int, 1> set1{};
+        if (ga < gz) {
+            group(set0, std::false_type{}, ga);
+            int g = ga + 1;
+            for (; g + 1 < gz; g += 2) {
+                group(set1, std::true_type{}, g);
+                group(set0, std::true_type{}, g + 1);
+            }
+            if (g < gz) {                                // one more group: into set 1, and its sums are folded on their own
+                group(set1, std::true_type{}, g);
 #pragma unroll
-            for (int yb = 0; yb < 4; yb++) {
-                const uint32_t sw = gcur.sc[yb];
-                const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
-                const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
-                const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
-                const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
+                for (int yb = 0; yb < 4; yb++) fold_pair(set1, yb);
+            } else {
 #pragma unroll
-                for (int mt = 0; mt < 2; mt++) {
-#pragma unroll
-                    for (int r = 0; r < 4; r++) {
-                        const float d = gacc[mt][2 * yb][r] - gacc[mt][2 * yb + 1][r];
-                        yr[mt][2 * yb][r]     = __builtin_fmaf(-c_lo, xs[mt][r], __builtin_fmaf(s_lo, d, yr[mt][2 * yb][r]));
-                        yr[mt][2 * yb + 1][r] = __builtin_fmaf(-c_hi, xs[mt][r], __builtin_fmaf(s_hi, gacc[mt][2 * yb + 1][r], yr[mt][2 * yb + 1][r]));
-                    }
-                }
+                for (int yb = 0; yb < 4; yb++) fold_pair(set0, yb);
             }
         }
         // the powers of two come out; one tile of 16 rows at a time through LDS, summed over the two halves of K
