@@ -299,7 +299,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     // finish_over_splits for when it runs again.  begin_pass() fixes the range and requests its first loads.
     int      ga = 0, gz = 0, ks1 = 0;
     SmallStage st[kRing];
-    SmallGroup gcur, gnxt;
+    SmallGroup gnxt;
     auto load_stage = [&](SmallStage& sg, int ks) {
         const bool     dead = ks >= ks1;
         const uint32_t dm   = dead ? kOut : 0u;
@@ -372,18 +372,44 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
     };
 
     auto run_pass = [&](auto&& sink) {
-        // gacc[2 yb + 8 t]: sum of x * byte, gacc[.. + 1]: sum of x * (byte & 0xF0), over the open group
-        f32x4 gacc[16], xs;
+        // Two sets of group sums: while the MFMAs of a group fill one set, the sums of the group before are
+        // folded out of the other, a quarter of them in each k-step, so that the fold's vector work runs
+        // beside the matrix core instead of after it.
+        // gacc[set][2 yb + 8 t]: sum of x * byte, gacc[set][.. + 1]: sum of x * (byte & 0xF0), over the set's group
+        f32x4 gacc[2][16], xs[2];
         float yr[16][RL];                                // running results, column j of the lane, row 4 b + r
+        SmallGroup gs[2];                                // scales and zero points of the group a set holds
 #pragma unroll
         for (int j = 0; j < 16; j++) {
-            gacc[j] = zero4;
+            gacc[0][j] = zero4;
+            gacc[1][j] = zero4;
 #pragma unroll
             for (int r = 0; r < RL; r++) yr[j][r] = 0.f;
         }
-        xs = zero4;
-        for (int g = ga; g < gz; g++) {
-            gcur = gnxt;
+        xs[0] = zero4;
+        xs[1] = zero4;
+        // columns j0 = 8 t2 + 2 yb and j0 + 1 of the lane: the sums of the set's group go into the running results
+        auto fold_pair = [&](auto setc, int t2, int yb) __attribute__((always_inline)) {
+            constexpr int P = decltype(setc)::value;
+            const uint32_t zw  = gs[P].zq[t2];
+            const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;         // z of the even columns; 16 z of the odd ones
+            const uint32_t sw = gs[P].sc[t2][yb];
+            const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+            const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+            const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
+            const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
+            const int j0 = t2 * 8 + 2 * yb;
+#pragma unroll
+            for (int r = 0; r < RL; r++) {
+                const float d = gacc[P][j0][r] - gacc[P][j0 + 1][r];
+                yr[j0][r]     = __builtin_fmaf(-c_lo, xs[P][r], __builtin_fmaf(s_lo, d, yr[j0][r]));
+                yr[j0 + 1][r] = __builtin_fmaf(-c_hi, xs[P][r], __builtin_fmaf(s_hi, gacc[P][j0 + 1][r], yr[j0 + 1][r]));
+            }
+        };
+        auto group = [&](auto setc, auto foldc, int g) __attribute__((always_inline)) {
+            constexpr int  P = decltype(setc)::value;
+            constexpr bool FOLD = decltype(foldc)::value;    // the other set holds a group (not so in a pass's first group)
+            gs[P] = gnxt;
 #pragma unroll
             for (int u = 0; u < kRing; u++) {
                 load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
@@ -395,7 +421,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
                 if constexpr (BF) xa = bf16x8_up64(sg.a);
                 else xa = sg.a;
                 const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
-                xs = mfma_small<BF>(xa, tiny, first ? zero4 : xs);
+                xs[P] = mfma_small<BF>(xa, tiny, first ? zero4 : xs[P]);
 #pragma unroll
                 for (int t2 = 0; t2 < 2; t2++) {
 #pragma unroll
@@ -418,32 +444,38 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
                         const half8_t bbyte = bit_cast<half8_t>(u32x4{pr[0], pr[1], pr[2], pr[3]});
                         const half8_t bhigh = bit_cast<half8_t>(u32x4{ph[0], ph[1], ph[2], ph[3]});
                         const int j0 = t2 * 8 + 2 * yb;
-                        gacc[j0]     = mfma_small<BF>(xa, bbyte, first ? zero4 : gacc[j0]);
-                        gacc[j0 + 1] = mfma_small<BF>(xa, bhigh, first ? zero4 : gacc[j0 + 1]);
+                        gacc[P][j0]     = mfma_small<BF>(xa, bbyte, first ? zero4 : gacc[P][j0]);
+                        gacc[P][j0 + 1] = mfma_small<BF>(xa, bhigh, first ? zero4 : gacc[P][j0 + 1]);
                     }
+                }
+                if constexpr (FOLD) {                    // a quarter of the group before
+                    fold_pair(std::integral_constant<int, 1 - P>{}, u >> 1, 2 * (u & 1));
+                    fold_pair(std::integral_constant<int, 1 - P>{}, u >> 1, 2 * (u & 1) + 1);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // the group's sums go into the running results
+        };
+        auto fold_all = [&](auto setc) __attribute__((always_inline)) {
 #pragma unroll
             for (int t2 = 0; t2 < 2; t2++) {
-                const uint32_t zw  = gcur.zq[t2];
-                const uint32_t zlo = zw & 0x0F0F0F0Fu, zhi = zw & 0xF0F0F0F0u;     // z of the even columns; 16 z of the odd ones
 #pragma unroll
-                for (int yb = 0; yb < 4; yb++) {
-                    const uint32_t sw = gcur.sc[t2][yb];
-                    const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
-                    const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
-                    const float c_lo = s_lo * (float)((zlo >> (8 * yb)) & 0xFFu);
-                    const float c_hi = s_hi * (float)((zhi >> (8 * yb)) & 0xFFu);
-                    const int j0 = t2 * 8 + 2 * yb;
-#pragma unroll
-                    for (int r = 0; r < RL; r++) {
-                        const float d = gacc[j0][r] - gacc[j0 + 1][r];
-                        yr[j0][r]     = __builtin_fmaf(-c_lo, xs[r], __builtin_fmaf(s_lo, d, yr[j0][r]));
-                        yr[j0 + 1][r] = __builtin_fmaf(-c_hi, xs[r], __builtin_fmaf(s_hi, gacc[j0 + 1][r], yr[j0 + 1][r]));
-                    }
-                }
+                for (int yb = 0; yb < 4; yb++) fold_pair(setc, t2, yb);
+            }
+        };
+        constexpr std::integral_constant<int, 0> set0{};
+        constexpr std::integral_constant<int, 1> set1{};
+        if (ga < gz) {
+            group(set0, std::false_type{}, ga);
+            int g = ga + 1;
+            for (; g + 1 < gz; g += 2) {
+                group(set1, std::true_type{}, g);
+                group(set0, std::true_type{}, g + 1);
+            }
+            if (g < gz) {                                // one more group: into set 1, and its sums are folded on their own
+                group(set1, std::true_type{}, g);
+                fold_all(set1);
+            } else {
+                fold_all(set0);
             }
         }
         // the powers of two come out; every wave leaves its sums in LDS
@@ -705,13 +737,8 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
                     }
                 }
                 if constexpr (FOLD) {
-                    fold_pair(std::integral_constant<int, 1 - P>{}, u);      // a quarter of the group before
-                    // one MFMA, then the vector instructions that fit beside it
-#pragma unroll
-                    for (int i = 0; i < 18; i++) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
-                    }
+                    fold_pair(std::integral_constant<int, 1 - P>{}, u);      // a quarter of the group before (the compiler's own
+                                                                             // interleaving with the MFMAs measured as good as a forced one)
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
