@@ -27,7 +27,10 @@
 // few rows the loop is bound by the number of instructions the wave issues (measured: a vector
 // instruction every 4.5 clocks, an MFMA adds 8 and runs beside them): unpacking this way costs two
 // vector instructions per four weights and the fold five per result and group, against nine per
-// four weights for dequantizing them first.
+// four weights for dequantizing them first.  A fold that follows its group leaves the matrix core
+// idle meanwhile (measured in the 32-row kernel: 2045 clocks for a group's four k-steps, 1305 for its
+// fold), so there are two sets of group sums: the MFMAs of a group fill one while the group before is
+// folded out of the other, a quarter in each k-step.
 //
 // Two kernels:
 //   decode_small_kernel, M <= 16: a wave takes 256 columns (16 per lane, 8-byte loads) of all rows.
