@@ -58,7 +58,7 @@ def draw_shapes(seed, count):
     return out
 
 
-KINDS = ["fp16", "w4", "w8", "bf16", "w4_bf16", "w8_bf16"]
+KINDS = ["fp16", "w4", "w8", "bf16", "w4_bf16", "w8_bf16", "w4native"]   # w4native: the codes repacked by the ORACLE, M folded into 1..64
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -67,6 +67,8 @@ def test_random_shapes(B, oracle, kind):
     base = kind.split("_")[0]
     worst = 0.0
     for i, (M, K, N) in enumerate(draw_shapes(KINDS.index(kind), CASES_PER_KIND)):
+        if kind == "w4native":
+            M = 1 + (M - 1) % 64
         print(f"  {kind} case {i}: M={M} K={K} N={N}", flush=True)
         sys.stdout.flush()
         W = synth.weights(87, K, N, layer_id=i, dist="student_t5" if i % 3 == 0 else "normal")
@@ -77,7 +79,13 @@ def test_random_shapes(B, oracle, kind):
         else:
             xh = x32.astype(np.float16)
             xd = dev(xh)
-        if base in ("fp16", "bf16"):
+        if kind == "w4native":
+            rec = oracle.quantize_w4(W)
+            ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16_NATIVE, M, K, N))
+            nat = torch.from_numpy(oracle.repack_w4_native(rec[0])).cuda()
+            y = B.linear_w4a16_native(xd, nat, dev(rec[1]), dev(rec[2]), ws)
+            ref = oracle.linear_w4a16(xh, *rec)
+        elif base in ("fp16", "bf16"):
             ws = B.new_workspace(B.workspace_bytes(B.KIND_FP16, M, K, N))
             if bf:
                 wb = oracle.fp32_to_bf16(W)
