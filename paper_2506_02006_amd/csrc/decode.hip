@@ -363,7 +363,7 @@ DecodePlan plan_rows(int q, int M, int K, int N, int rows)
 // At most 16 rows of 4-bit weights: the kernel of decode_small.hip.  One workgroup per compute unit;
 // K is shared out over S <= 16 workgroups per column tile of 256 (one "share done" bit each in the
 // tile's counter), every workgroup keeping at least four k-steps, one per wave.
-static DecodePlan plan_small(int M, int K, int N)
+static DecodePlan plan_small(int q, int M, int K, int N)
 {
     DecodePlan pl{};
     pl.small  = 1;
@@ -379,7 +379,8 @@ static DecodePlan plan_small(int M, int K, int N)
     if (target <= 0) target = prefill_compute_units();
     const int slices = M > 32 ? 2 : 1;                   // slices of 32 rows, a workgroup each
     int S = target / (pl.tiles * slices);
-    const int most = M <= 16 ? T / 4 : (T / 8 > 0 ? T / 8 : 1);   // every workgroup keeps a quantization group; beyond 16 rows, each half of its waves one
+    // every workgroup keeps a quantization group; beyond 16 rows, and for dense weights, each half of its waves one
+    const int most = (M <= 16 && q == 1) ? T / 4 : (T / 8 > 0 ? T / 8 : 1);
     if (S > most) S = most;
     if (S > 16) S = 16;
     const int forced = tuning_get(TUNE_DECODE_SPLIT);
@@ -405,8 +406,8 @@ DecodePlan plan_decode(int q, int M, int K, int N)
 {
     const int t = tuning_get(TUNE_DECODE_SLICE);        // a forced slice height means the general streaming kernels
     const int small_rows = tuning_get(TUNE_SMALL) == 3 ? 16 : 64;       // 3: the register-tiled kernel only up to 16 rows
-    if (q == 1 && M <= small_rows && tuning_get(TUNE_SMALL) != 2 && t != 16 && t != 32) {
-        const DecodePlan ps = plan_small(M, K, N);
+    if ((q == 0 || q == 1) && M <= small_rows && tuning_get(TUNE_SMALL) != 2 && t != 16 && t != 32) {
+        const DecodePlan ps = plan_small(q, M, K, N);
         // (tile and group counts travel in 16 bits each)
         if (ps.partial_bytes <= kSlotBytes && (ps.S == 1 || ps.tiles * ps.slices <= 256) && ps.tiles <= 65535 && K / kGroup <= 65535) return ps;
     }

@@ -790,6 +790,162 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
     finish_over_splits(t, S, p, nvec, base, &fresh_word, run_pass, begin_pass, vec_store_y);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Dense weights (fp16, or bfloat16 with BF), M <= 64: the skeleton of decode_mid_kernel -- wave (kh, ch),
+// x through LDS, two slices of 32 rows beyond 32, the same vectors and the same hand-over -- around a
+// loop with nothing to unpack and nothing to fold.  A lane loads its 8 columns (16 bytes) of 8
+// consecutive rows, pairs the 16-bit values of rows 2 q, 2 q + 1 column by column (v_perm_b32: the MFMA
+// wants 8 consecutive k of one column), and the accumulators are the running results.  MT: tiles of 16
+// rows per slice (1: M <= 16).  A k-step is 8 KB per wave, three of them in flight.
+// ------------------------------------------------------------------------------------------------
+struct DenseStage {
+    u32x4 r[8];                                  // row 8 b + i of the k-step: the lane's 8 columns
+};
+
+template <int MT, bool BF>
+__global__ __launch_bounds__(kSmWaves * 64, 1) void decode_dense_kernel(
+    const uint32_t* w, const void* x_all, const void*, const uint32_t*, int K, int N, int ms, int qr,
+    int tiles_sl, int inv_s, SmallTail t)
+{
+    const int M_all = ms & 0xFFFF, S = ms >> 16, q_groups = qr & 0xFFFF, r_groups = qr >> 16;
+    // as in decode_mid_kernel: per wave two buffers of x (16 MT rows of 128 k, pieces XOR-swizzled by the row),
+    // afterwards the results of one tile of 16 rows at a time
+    __shared__ __align__(16) u32x4 sm[kSmWaves * 1024];
+    __shared__ uint32_t fresh_word;
+
+    MORPH_TICK(0);                                       // kernel entry
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kh = wave >> 1, ch = wave & 1;
+    const int c = lane & 15, b = lane >> 4;
+    const int tiles = tiles_sl & 0xFFFF;
+    const Place p = place_of(tiles_sl, inv_s, S);
+    if (p.tile >= tiles) return;
+    const int n0 = p.tile * 256;
+    constexpr int ROWS = 16 * MT;                        // rows of a slice
+    const int M = M_all - 32 * p.slice < ROWS ? M_all - 32 * p.slice : ROWS;
+    const uint16_t* x = (const uint16_t*)x_all + (size_t)(32 * p.slice) * K;
+
+    const uint32_t row_bytes = (uint32_t)N * 2u;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
+    const int  ncol   = n0 + 128 * ch + 8 * c;           // this lane's first column
+    const uint32_t kOut = 0xFFFFFFF0u;
+    const uint32_t voff_w = ncol < N ? (uint32_t)(8 * b) * row_bytes + (uint32_t)ncol * 2u : kOut;
+    // x of a whole group: load i takes rows 4 i + (lane >> 4), piece (lane & 15) of each; rows at or beyond M lie past the buffer
+    const uint32_t voff_x = ((uint32_t)b * (uint32_t)K + 8u * (uint32_t)c) * 2u;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    u32x4* const xl = sm + wave * 1024;
+
+    int        ga = 0, gz = 0, ks1 = 0;
+    DenseStage st[kRing];
+    u32x4      xg[4 * MT];
+    auto load_stage = [&](DenseStage& sg, int ks) {
+        const bool     dead = ks >= ks1;
+        const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
+        const uint32_t vw   = voff_w | (dead ? kOut : 0u);
+#pragma unroll
+        for (int i = 0; i < 8; i++) sg.r[i] = buf_load_u32x4<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+    };
+    auto load_xgroup = [&](int g) {
+        const bool     dead = g >= gz;
+        const uint32_t dm   = dead ? kOut : 0u;
+#pragma unroll
+        for (int i = 0; i < 4 * MT; i++)
+            xg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (voff_x + (uint32_t)i * 8u * (uint32_t)K) | dm, dead ? 0u : (uint32_t)g * 256u, 0);
+    };
+    auto store_xgroup = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4 * MT; i++) {
+            const int row = 4 * i + b;
+            xl[buf * 512 + row * 16 + ((c ^ row) & 15)] = xg[i];
+        }
+    };
+    auto begin_pass = [&](int split) {
+        // runs of 128 rows of k ("groups", as the quantized kernels count them) of the split, then of this wave's half
+        const int gb = split * q_groups + (split < r_groups ? split : r_groups);
+        const int ng = q_groups + (split < r_groups ? 1 : 0);
+        ga = gb + ((kh * ng) >> 1);
+        gz = gb + (((kh + 1) * ng) >> 1);
+        ks1 = 4 * gz;
+        load_xgroup(ga);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kAhead; i++) {
+            load_stage(st[i], 4 * ga + i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    begin_pass(p.sp);
+    const uint32_t base = flags_as_found(t, S, p, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MORPH_TICK(1);                                       // first loads issued
+
+    // A vector = four rows of one column; vector (mt, rq, col): column n0 + col, rows 16 mt + 4 rq ..;
+    // its number is id = 1024 mt + 256 rq + col.  With one tile of rows only the groups of four rows that exist are numbered.
+    const int nvec = MT == 2 ? 2048 : 256 * t.nb;
+    uint16_t* y = (uint16_t*)t.y + (size_t)(32 * p.slice) * N;
+    auto vec_store_y = [&](int id, f32x4 acc) {
+        const int col = n0 + (id & 255), row = 4 * (id >> 8);
+        if (col < N) {
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<BF>(acc[r]);
+        }
+    };
+
+    auto run_pass = [&](auto&& sink) {
+        f32x4 acc[MT][8];                                // column j of the lane, rows 16 mt + 4 b ..
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) acc[mt][j] = zero4;
+        }
+        int xb = 0;                                      // the x buffer of the open group
+        store_xgroup(0);
+        for (int g = ga; g < gz; g++) {
+#pragma unroll
+            for (int u = 0; u < kRing; u++) {
+                load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
+                if (u == 0) load_xgroup(g + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                const DenseStage& sg = st[u];
+                half8_t xa[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++) xa[mt] = bit_cast<half8_t>(xl[xb * 512 + (16 * mt + c) * 16 + ((4 * u + b) ^ c)]);
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    u32x4 bo;
+#pragma unroll
+                    for (int q = 0; q < 4; q++)          // rows 2 q and 2 q + 1, column j: low or high halves of word j / 2
+                        bo[q] = __builtin_amdgcn_perm(sg.r[2 * q + 1][j >> 1], sg.r[2 * q][j >> 1], (j & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+                    for (int mt = 0; mt < MT; mt++) acc[mt][j] = mfma_small<BF>(xa[mt], bit_cast<half8_t>(bo), acc[mt][j]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            store_xgroup(xb ^ 1);                        // the next group's x, requested at the top of this one
+            xb ^= 1;
+        }
+        // one tile of 16 rows at a time through LDS, summed over the two halves of K
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            __syncthreads();                             // every wave is done with its x, or with the tile before
+#pragma unroll
+            for (int j = 0; j < 8; j++) sm[kh * 1024 + b * 256 + ch * 128 + c * 8 + (j ^ (c & 7))] = bit_cast<u32x4>(acc[mt][j]);
+            __syncthreads();
+            const int live = MT == 2 ? 1024 : 256 * t.nb;
+            for (int lid = tid; lid < live; lid += kSmWaves * 64) {
+                const int pos = (lid & ~7) | ((lid ^ (lid >> 3)) & 7);      // column 8 c + j sits at j ^ (c & 7)
+                sink(mt * 1024 + lid, bit_cast<f32x4>(sm[pos]) + bit_cast<f32x4>(sm[1024 + pos]));
+            }
+        }
+    };
+
+    finish_over_splits(t, S, p, nvec, base, &fresh_word, run_pass, begin_pass, vec_store_y);
+}
+
 template <class Kernel>
 hipError_t launch_small_with(Kernel kernel, int waves, const SmallArgs& a, hipStream_t st)
 {
@@ -808,6 +964,10 @@ hipError_t launch_small_with(Kernel kernel, int waves, const SmallArgs& a, hipSt
 template <bool BF>
 hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
 {
+    if (a.dense) {
+        if (a.M <= 16) return launch_small_with(decode_dense_kernel<1, BF>, kSmWaves, a, st);
+        return launch_small_with(decode_dense_kernel<2, BF>, kSmWaves, a, st);
+    }
     if (a.native) {
         if constexpr (BF) return hipErrorInvalidValue;
         else if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, false, true>, kSmWaves, a, st);
@@ -827,6 +987,7 @@ hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
 {
     if (a.M < 1 || a.M > 64 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1 || a.tiles > 65535 || a.K / kGroup > 65535) return hipErrorInvalidValue;
     if (a.S > 1 && a.tiles * (a.M > 32 ? 2 : 1) > 256) return hipErrorInvalidValue;     // flags for 256 (tile, slice) pairs
+    if (a.dense && a.native) return hipErrorInvalidValue;
     return a.bf ? launch_small_m<true>(a, st) : launch_small_m<false>(a, st);
 }
 

@@ -73,7 +73,7 @@ hipError_t launch_decode(int q, const DecodeArgs& a, hipStream_t st);
 // ---- 4-bit weights, M <= 16 (decode_small.hip) ----
 struct SmallArgs {
     const void* x;         // fp16 / bfloat16 [M,K]
-    const void* w;         // uint32 [K,N/8], or the native array of the codes (native = 1)
+    const void* w;         // uint32 [K,N/8], the native array of the codes (native = 1), or the 16-bit matrix [K,N] (dense = 1)
     const void* scales;    // fp16 [K/128,N]
     const void* qzeros;    // uint32 [K/128,N/8]
     void*       y;         // fp16 / bfloat16 [M,N]
@@ -85,7 +85,8 @@ struct SmallArgs {
     int         polls;     // looks at the others' flags before a workgroup gives up
     int         far;       // hand-over always written through to memory, never left in an L2 (test hook)
     int         bf;
-    int         native;    // w is in the native storage order (M <= 16, fp16 only)
+    int         native;    // w is in the native storage order (fp16 activations only)
+    int         dense;     // w is a 16-bit matrix (fp16, or bfloat16 with bf): no scales, no zero points
 };
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st);
 

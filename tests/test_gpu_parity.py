@@ -274,10 +274,10 @@ def test_decode_either_slice_height(B, oracle, M, rows):
 
 @pytest.mark.parametrize("which", [0, 2, 3], ids=["auto", "general", "small-to-16"])
 @pytest.mark.parametrize("far", [0, 1], ids=["in-L2", "through-memory"])
-def test_decode_w4_register_tiled_kernel_or_general_ones(B, oracle, which, far):
-    """Up to 64 rows of 4-bit weights go to the register-tiled kernel (one or two tiles of 16 rows per
-    workgroup, two slices of 32 rows beyond 32), or, forced here, to the general streaming kernels; the
-    former hands its partial sums over inside one XCD's L2 or, forced here, through memory.  Row counts
+def test_decode_register_tiled_kernels_or_general_ones(B, oracle, which, far):
+    """Up to 64 rows, 4-bit and dense weights go to the register-tiled kernels (one or two tiles of 16 rows
+    per workgroup, two slices of 32 rows beyond 32), or, forced here, to the general streaming kernels; the
+    former hand their partial sums over inside one XCD's L2 or, forced here, through memory.  Row counts
     at and around every boundary (4-row groups, 16, 32, 48), with a ragged last column tile, with and
     without a split along K."""
     B.set_tuning(B.TUNE_SMALL, which)
@@ -286,6 +286,8 @@ def test_decode_w4_register_tiled_kernel_or_general_ones(B, oracle, which, far):
         for M in (1, 2, 5, 16, 17, 31, 32, 33, 47, 48, 49, 64):
             check_w4(B, oracle, M, 1792, 520, seed=M + which)
             check_w4(B, oracle, M, 256, 2824, seed=M + which + 1)
+            check_fp16(B, oracle, M, 1792, 520, seed=M + which + 2)
+            check_fp16(B, oracle, M, 256, 2824, seed=M + which + 3)
     finally:
         B.set_tuning(B.TUNE_SMALL, 0)
         B.set_tuning(B.TUNE_SMALL_FAR, 0)
