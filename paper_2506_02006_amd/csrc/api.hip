@@ -90,7 +90,7 @@ inline int plan_kind(int kind) { return kind == MORPH_KIND_W4A16_NATIVE ? MORPH_
 bool native_served(int M, int K, int N, int bf)
 {
     if (bf || M > 64 || !takes_stream(MORPH_KIND_W4A16, M, K, N)) return false;
-    return plan_decode(MORPH_KIND_W4A16, M, K, N).small;
+    return plan_decode(MORPH_KIND_W4A16, M, K, N, 1).small;
 }
 
 size_t workspace_need(int kind, int M, int K, int N)
@@ -113,11 +113,11 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
     if (native && !native_served(M, K, N, bf)) return MORPH_ERR_UNSUPPORTED;
     kind = plan_kind(kind);
     if (takes_stream(kind, M, K, N)) {
-        const DecodePlan pl = plan_decode(kind, M, K, N);
+        const DecodePlan pl = plan_decode(kind, M, K, N, native);
         if (pl.small) {
             SmallArgs s;
             s.x = x; s.w = w; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
-            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf; s.native = native; s.dense = kind == MORPH_KIND_FP16;
+            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf; s.native = native; s.dense = kind == MORPH_KIND_FP16; s.wide = pl.wide;
             s.slots = nullptr; s.ctl = nullptr;
             if (pl.S > 1) {
                 if (!workspace || workspace_bytes < kScratchOffset) return MORPH_ERR_WORKSPACE;
@@ -225,7 +225,7 @@ int morph_linear_w4a16_noalloc(const void* x, const int32_t* qweight, const void
     if (pl.S > 1 && (pl.partial_bytes > kNoAllocSlotBytes || pl.tiles > 256)) return MORPH_ERR_UNSUPPORTED;   // beyond the array
     SmallArgs s;
     s.x = x; s.w = qweight; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
-    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = 0; s.bf = 0; s.native = 0; s.dense = 0;
+    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = 0; s.bf = 0; s.native = 0; s.dense = 0; s.wide = 0;
     s.slots = nullptr; s.ctl = nullptr;
     if (pl.S > 1) {
         unsigned char* p = scratch_on_current_device();
@@ -724,7 +724,8 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     if ((rc = morph_repack_w4_native(q, nat, kWK, kWN, stream))) return rc;
     if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 1, kWK, kWN, 128, ws, wsb, stream))) return rc;
     if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 16, kWK, kWN, 128, ws, wsb, stream))) return rc;
-    if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 33, kWK, kWN, 128, ws, wsb, stream))) return rc;   // the kernel for 17 to 64 rows
+    if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 17, kWK, kWN, 128, ws, wsb, stream))) return rc;   // the eight-wave kernel for 17 to 32 rows
+    if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 33, kWK, kWN, 128, ws, wsb, stream))) return rc;   // the kernel for 33 to 64 rows
     if ((rc = morph_dequantize_w4_native(nat, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
     if ((rc = morph_unpack_w4_native(nat, q, kWK, kWN, stream))) return rc;
     // the 8-bit variant: its codes (32 KB) go where the fp32 dummy matrix was

@@ -363,7 +363,7 @@ DecodePlan plan_rows(int q, int M, int K, int N, int rows)
 // At most 16 rows of 4-bit weights: the kernel of decode_small.hip.  One workgroup per compute unit;
 // K is shared out over S <= 16 workgroups per column tile of 256 (one "share done" bit each in the
 // tile's counter), every workgroup keeping at least four k-steps, one per wave.
-static DecodePlan plan_small(int q, int M, int K, int N)
+static DecodePlan plan_small(int q, int M, int K, int N, int native)
 {
     DecodePlan pl{};
     pl.small  = 1;
@@ -377,7 +377,10 @@ static DecodePlan plan_small(int q, int M, int K, int N)
     // uses more than half the registers and the LDS of one).
     int target = tuning_get(TUNE_DECODE_WGS);
     if (target <= 0) target = prefill_compute_units();
-    const int slices = M > 32 ? 2 : 1;                   // slices of 32 rows, a workgroup each
+    // 17 to 32 rows on the native code order: the eight-wave kernel (decode_wide_kernel); beyond 32 rows slices
+    // of 32 rows, a workgroup each
+    const bool wide  = native && q == 1 && M > 16 && M <= 32 && tuning_get(TUNE_SMALL) != 4;
+    const int slices = M > 32 ? 2 : 1;
     int S = target / (pl.tiles * slices);
     // every workgroup keeps a quantization group; beyond 16 rows, and for dense weights, each half of its waves one
     const int most = (M <= 16 && q == 1) ? T / 4 : (T / 8 > 0 ? T / 8 : 1);
@@ -390,6 +393,7 @@ static DecodePlan plan_small(int q, int M, int K, int N)
     pl.S = S;
     // vectors of four rows per tile: up to 16 rows only the groups of four that exist, beyond whole tiles of 16 rows
     const size_t nvec = M <= 16 ? (size_t)256 * ((M + 3) / 4) : (size_t)2048;
+    pl.wide = wide;
     pl.slices = slices;
     pl.partial_bytes = S > 1 ? (size_t)pl.tiles * slices * S * nvec * 16 : 0;
     // A look is one trip to the L2, 0.15 .. 0.3 us; the others of a unit normally follow within a few of them.  A workgroup
@@ -402,12 +406,12 @@ static DecodePlan plan_small(int q, int M, int K, int N)
     return pl;
 }
 
-DecodePlan plan_decode(int q, int M, int K, int N)
+DecodePlan plan_decode(int q, int M, int K, int N, int native)
 {
     const int t = tuning_get(TUNE_DECODE_SLICE);        // a forced slice height means the general streaming kernels
     const int small_rows = tuning_get(TUNE_SMALL) == 3 ? 16 : 64;       // 3: the register-tiled kernel only up to 16 rows
     if ((q == 0 || q == 1) && M <= small_rows && tuning_get(TUNE_SMALL) != 2 && t != 16 && t != 32) {
-        const DecodePlan ps = plan_small(q, M, K, N);
+        const DecodePlan ps = plan_small(q, M, K, N, native);
         // (tile and group counts travel in 16 bits each)
         if (ps.partial_bytes <= kSlotBytes && (ps.S == 1 || ps.tiles * ps.slices <= 256) && ps.tiles <= 65535 && K / kGroup <= 65535) return ps;
     }

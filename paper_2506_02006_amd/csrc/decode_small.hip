@@ -32,7 +32,7 @@
 // fold), so there are two sets of group sums: the MFMAs of a group fill one while the group before is
 // folded out of the other, a quarter in each k-step.
 //
-// Two kernels:
+// Three kernels:
 //   decode_small_kernel, M <= 16: a wave takes 256 columns (16 per lane, 8-byte loads) of all rows.
 //     Up to four rows, row m is fed to the MFMA as its row 4 m, which comes out as the first of a
 //     lane's four accumulator components, and the fold touches only that one (RL = 1).
@@ -41,6 +41,7 @@
 //     of at most 32 rows, two waves side by side and two along K; beyond 32 rows two workgroups on
 //     the same XCD take a slice each and the second reading of the weights is served by that XCD's
 //     L2.  x reaches the waves through LDS, in whole cache lines.
+//   decode_wide_kernel, 17 <= M <= 32 on the native code order: eight waves, two to a SIMD, 64 columns each.
 #include <type_traits>
 
 #include "dev_common.h"
@@ -791,6 +792,234 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
+// 17 <= M <= 32 on the native code order: eight waves, two to a SIMD.  Wave (kh, cq) = (wave >> 2,
+// wave & 3) takes half kh of the workgroup's quantization groups and, of every lane's 16 columns in that
+// order, the four that its load cq holds: columns n0 + 16 c + 4 cq .. + 3 for c = 0 .. 15, all rows of
+// them.  A k-step is then one 16-byte load per lane -- one contiguous kilobyte per wave -- and group sums,
+// running results and staged loads of 32 rows x 64 columns fit in the 256 registers a wave has when two
+// share a SIMD, where one fills the issue slots the other leaves open (decode_mid_kernel: one wave per
+// SIMD, an instruction every seven clocks); a single set of group sums is enough then.  x of a group is
+// shared by the four waves of a kh through LDS (each fetches a quarter of the rows, in whole cache
+// lines); one workgroup barrier per group keeps the two buffers apart, so both halves of K walk the same
+// number of groups (the shorter one a dead group at its end).
+// RT: tiles of 16 rows.  With RT = 4 (all of 64 rows in one workgroup, every weight unpacked once) the
+// kernel needs all 256 registers and measured slower than two slices of decode_mid_kernel (8B shapes at
+// M = 64: 14.0 / 11.5 / 31.9 / 23.4 us against 13.1 / 9.8 / 29.5 / 18.3), so only RT = 2 is built.
+// ------------------------------------------------------------------------------------------------
+constexpr int kWideWaves = 8;
+struct WideGroup {
+    uint32_t zq;                                 // the packed word holding the zero points of the lane's 4 columns
+    u32x2    sc;                                 // their scales
+};
+
+template <int RT>
+__global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
+    const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
+    int tiles_sl, int inv_s, SmallTail t)
+{
+    const int M = ms & 0xFFFF, S = ms >> 16, q_groups = qr & 0xFFFF, r_groups = qr >> 16;
+    // During the k loop: [kh][buffer][row][piece] -- per half of K two groups of x, 16 RT rows of 128 k, a
+    // row = 16 pieces of 16 bytes, piece p stored at p ^ (row & 15) (see decode_mid_kernel).  After the
+    // loop the first 32 KB hold the results of one tile of 16 rows at a time:
+    // [kh][4-row group b][column of the tile: column 16 c + j stored at 16 c + (j ^ c)].
+    constexpr int kXBuf = RT * 256;                      // pieces per buffer
+    __shared__ __align__(16) u32x4 sm[4 * kXBuf];
+    static_assert(4 * kXBuf >= 2048, "the results of a tile of rows need 32 KB");
+    __shared__ uint32_t fresh_word;
+
+    MORPH_TICK(0);                                       // kernel entry
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kh = wave >> 2, cq = wave & 3;
+    const int c = lane & 15, b = lane >> 4;
+    const int tiles = tiles_sl & 0xFFFF;
+    const Place p = place_of(tiles_sl, inv_s, S);
+    if (p.tile >= tiles) return;
+    const int n0 = p.tile * 256;
+
+    const uint32_t zrow_bytes = (uint32_t)(N >> 3) * 4u;
+    const uint32_t ksteps = (uint32_t)K >> 5;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)tiles * ksteps * 4096u);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
+    const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * zrow_bytes);
+
+    const int  ncol   = n0 + 16 * c + 4 * cq;            // this lane's first column
+    const bool col_ok = ncol < N;
+    const uint32_t kOut = 0xFFFFFFF0u;
+    const uint32_t voff_w = (uint32_t)cq * 1024u + (uint32_t)lane * 16u;       // load cq of lane (c, b) of the native order
+    const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
+    const uint32_t voff_z = col_ok ? (uint32_t)(ncol >> 3) * 4u : kOut;
+    const uint32_t zsh    = 16u * (uint32_t)(cq & 1);                          // the lane's four nibbles in that word
+    // x of a whole group: load i takes row 16 i + 4 cq + b, piece c; rows at or beyond M lie past the buffer
+    const uint32_t voff_x = ((uint32_t)(4 * cq + b) * (uint32_t)K + 8u * (uint32_t)c) * 2u;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    u32x4* const xl = sm + kh * 2 * kXBuf;               // the two buffers of this half of K
+
+    int       ga = 0, gz = 0, ks1 = 0, nit = 0;
+    u32x4     st[kRing];
+    WideGroup gnxt;
+    u32x4     xg[RT];
+    auto load_stage = [&](u32x4& sg, int ks) {
+        const bool     dead = ks >= ks1;
+        const uint32_t sn   = dead ? 0u : ((uint32_t)ks * (uint32_t)tiles + (uint32_t)p.tile) * 4096u;
+        sg = buf_load_u32x4<kAuxStream>(rw, voff_w | (dead ? kOut : 0u), sn);
+    };
+    auto load_group = [&](WideGroup& gr, int g) {
+        const bool     dead = g >= gz;
+        const uint32_t gm   = dead ? kOut : 0u;
+        const uint32_t gg   = dead ? 0u : (uint32_t)g;
+        gr.zq = buf_load_u32(rz, voff_z | gm, gg * zrow_bytes);
+        gr.sc = buf_load_u32x2(rs, voff_s | gm, gg * (uint32_t)N * 2u);
+    };
+    auto load_xgroup = [&](int g) {
+        const bool     dead = g >= gz;
+        const uint32_t dm   = dead ? kOut : 0u;
+#pragma unroll
+        for (int i = 0; i < RT; i++)
+            xg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (voff_x + (uint32_t)i * 32u * (uint32_t)K) | dm, dead ? 0u : (uint32_t)g * 256u, 0);
+    };
+    auto store_xgroup = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < RT; i++) {
+            const int row = 16 * i + 4 * cq + b;
+            xl[buf * kXBuf + row * 16 + ((c ^ row) & 15)] = xg[i];
+        }
+    };
+    auto begin_pass = [&](int split) {
+        // quantization groups of the split, then of this wave's half: no division on the device
+        const int gb = split * q_groups + (split < r_groups ? split : r_groups);
+        const int ng = q_groups + (split < r_groups ? 1 : 0);
+        ga = gb + ((kh * ng) >> 1);
+        gz = gb + (((kh + 1) * ng) >> 1);
+        nit = ng - (ng >> 1);                            // groups of the longer half: what every wave walks
+        ks1 = 4 * gz;
+        load_group(gnxt, ga);
+        load_xgroup(ga);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kAhead; i++) {
+            load_stage(st[i], 4 * ga + i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    begin_pass(p.sp);
+    const uint32_t base = flags_as_found(t, S, p, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MORPH_TICK(1);                                       // first loads issued
+
+    // A vector = four rows of one column; vector (mt, rq, col): column n0 + col, rows 16 mt + 4 rq ..;
+    // its number is id = 1024 mt + 256 rq + col.
+    constexpr int nvec = 1024 * RT;
+    uint16_t* y = (uint16_t*)t.y;
+    auto vec_store_y = [&](int id, f32x4 acc) {
+        const int col = n0 + (id & 255), row = 4 * (id >> 8);
+        if (col < N) {
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<false>(acc[r]);
+        }
+    };
+
+    auto run_pass = [&](auto&& sink) {
+        // gacc[mt][2 yb]: sum of x * byte, gacc[mt][2 yb + 1]: sum of x * (byte & 0xF0) over the open group,
+        // byte column yb of the lane (columns 2 yb and 2 yb + 1)
+        f32x4 gacc[RT][4], xs[RT];
+        float yr[RT][4][4];                              // running results, column j of the lane, row 16 mt + 4 b + r
+#pragma unroll
+        for (int mt = 0; mt < RT; mt++) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                gacc[mt][j] = zero4;
+#pragma unroll
+                for (int r = 0; r < 4; r++) yr[mt][j][r] = 0.f;
+            }
+            xs[mt] = zero4;
+        }
+        store_xgroup(0);
+        __syncthreads();
+        int xb = 0;                                      // the x buffer of the open group
+        for (int it = 0; it < nit; it++) {
+            const int g = ga + it;
+            const WideGroup gs = gnxt;
+#pragma unroll
+            for (int u = 0; u < kRing; u++) {
+                load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
+                if (u == 0) load_xgroup(g + 1);          // issued before three stages of weights: a wait for it does not wait for them
+                if (u == 1) load_group(gnxt, g + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                const u32x4 sg = st[u];
+                const bool first = u == 0;
+                const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
+                // word q of the load: bytes 0 and 2 are rows 2 q and 2 q + 1 of byte column 0, bytes 1 and 3 of byte column 1
+                u32x4 b0, h0, b1, h1;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    b0[q] = sg[q] & 0x00FF00FFu;
+                    b1[q] = __builtin_amdgcn_perm(0u, sg[q], 0x0c030c01u);
+                    h0[q] = b0[q] & 0x00F000F0u;
+                    h1[q] = b1[q] & 0x00F000F0u;
+                }
+#pragma unroll
+                for (int mt = 0; mt < RT; mt++) {
+                    const half8_t xa = bit_cast<half8_t>(xl[xb * kXBuf + (16 * mt + c) * 16 + ((4 * u + b) ^ c)]);
+                    xs[mt]      = mfma_small<false>(xa, tiny, first ? zero4 : xs[mt]);
+                    gacc[mt][0] = mfma_small<false>(xa, bit_cast<half8_t>(b0), first ? zero4 : gacc[mt][0]);
+                    gacc[mt][1] = mfma_small<false>(xa, bit_cast<half8_t>(h0), first ? zero4 : gacc[mt][1]);
+                    gacc[mt][2] = mfma_small<false>(xa, bit_cast<half8_t>(b1), first ? zero4 : gacc[mt][2]);
+                    gacc[mt][3] = mfma_small<false>(xa, bit_cast<half8_t>(h1), first ? zero4 : gacc[mt][3]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // the group's sums go into the running results (a dead group has zero scales: nothing changes)
+            const uint32_t z16 = gs.zq >> zsh;
+#pragma unroll
+            for (int yb = 0; yb < 2; yb++) {
+                const uint32_t sw = gs.sc[yb];
+                const float s_lo = (float)bit_cast<half_t>((uint16_t)(sw & 0xFFFFu));
+                const float s_hi = (float)bit_cast<half_t>((uint16_t)(sw >> 16));
+                const float c_lo = s_lo * (float)((z16 >> (8 * yb)) & 0x0Fu);          // z of the even column
+                const float c_hi = s_hi * (float)((z16 >> (8 * yb)) & 0xF0u);          // 16 z of the odd one
+#pragma unroll
+                for (int mt = 0; mt < RT; mt++) {
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        const float d = gacc[mt][2 * yb][r] - gacc[mt][2 * yb + 1][r];
+                        yr[mt][2 * yb][r]     = __builtin_fmaf(-c_lo, xs[mt][r], __builtin_fmaf(s_lo, d, yr[mt][2 * yb][r]));
+                        yr[mt][2 * yb + 1][r] = __builtin_fmaf(-c_hi, xs[mt][r], __builtin_fmaf(s_hi, gacc[mt][2 * yb + 1][r], yr[mt][2 * yb + 1][r]));
+                    }
+                }
+            }
+            store_xgroup(xb ^ 1);                        // the next group's x, requested at the top of this one
+            xb ^= 1;
+            __syncthreads();                             // it is there for all four waves; the other buffer is free
+        }
+        // the powers of two come out; one tile of 16 rows at a time through LDS, summed over the two halves of K
+        constexpr float kEven = 0x1p24f;                 // low-nibble (even) columns
+        constexpr float kOdd  = 0x1p20f;                 // high-nibble (odd) columns: their sums carry a factor 16
+#pragma unroll
+        for (int mt = 0; mt < RT; mt++) {
+            __syncthreads();                             // every wave is done with the tile before
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                f32x4 v;
+#pragma unroll
+                for (int r = 0; r < 4; r++) v[r] = yr[mt][j][r] * ((j & 1) ? kOdd : kEven);
+                sm[kh * 1024 + b * 256 + 16 * c + ((4 * cq + j) ^ c)] = bit_cast<u32x4>(v);
+            }
+            __syncthreads();
+            for (int lid = tid; lid < 1024; lid += kWideWaves * 64) {
+                const int pos = (lid & ~15) | ((lid ^ (lid >> 4)) & 15);     // column 16 c + j sits at j ^ c
+                sink(mt * 1024 + lid, bit_cast<f32x4>(sm[pos]) + bit_cast<f32x4>(sm[1024 + pos]));
+            }
+        }
+    };
+
+    finish_over_splits(t, S, p, nvec, base, &fresh_word, run_pass, begin_pass, vec_store_y);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Dense weights (fp16, or bfloat16 with BF), M <= 64: the skeleton of decode_mid_kernel -- wave (kh, ch),
 // x through LDS, two slices of 32 rows beyond 32, the same vectors and the same hand-over -- around a
 // loop with nothing to unpack and nothing to fold.  A lane loads its 8 columns (16 bytes) of 8
@@ -972,7 +1201,8 @@ hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
         if constexpr (BF) return hipErrorInvalidValue;
         else if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, false, true>, kSmWaves, a, st);
         else if (a.M <= 16) return launch_small_with(decode_small_kernel<4, false, true>, kSmWaves, a, st);
-        else return launch_small_with(decode_mid_kernel<false, true>, kSmWaves, a, st);
+        else if (!a.wide)   return launch_small_with(decode_mid_kernel<false, true>, kSmWaves, a, st);
+        else return launch_small_with(decode_wide_kernel<2>, kWideWaves, a, st);
     }
     if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, BF, false>, kSmWaves, a, st);
     if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF, false>, kSmWaves, a, st);
@@ -986,6 +1216,7 @@ MORPH_TICK_EXPORTS(small_ticks)
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
 {
     if (a.M < 1 || a.M > 64 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1 || a.tiles > 65535 || a.K / kGroup > 65535) return hipErrorInvalidValue;
+    if (a.wide && (!a.native || a.bf || a.M <= 16 || a.M > 32)) return hipErrorInvalidValue;
     if (a.S > 1 && a.tiles * (a.M > 32 ? 2 : 1) > 256) return hipErrorInvalidValue;     // flags for 256 (tile, slice) pairs
     if (a.dense && a.native) return hipErrorInvalidValue;
     return a.bf ? launch_small_m<true>(a, st) : launch_small_m<false>(a, st);

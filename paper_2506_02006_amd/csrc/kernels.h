@@ -51,7 +51,8 @@ struct DecodePlan {
     int    stream_loads;       // load the weights non-temporally
     int    scatter;            // share the sum over the splits out among the workgroups of a tile
     int    polls;              // how many times a workgroup looks for the others before it gives up
-    int    small;              // the launch goes to the kernel for at most 16 rows of 4-bit weights (decode_small.hip)
+    int    small;              // the launch goes to the register-tiled kernels for at most 64 rows (decode_small.hip)
+    int    wide;               // ... to the eight-wave kernel for 17 to 32 rows on the native code order
 };
 // Workspace layout, the same for every kernel family so that one workspace serves any sequence of calls:
 //   [0, kCounterBytes)                 counters, zero between launches
@@ -67,7 +68,8 @@ constexpr int kPlainCounters = 16384;
 constexpr int kDepartBase    = 65536;
 constexpr int kSmallCtlInts  = 96;
 // q: 0 = fp16, 1 = 4-bit, 2 = 8-bit codes (the MORPH_KIND_* values)
-DecodePlan plan_decode(int q, int M, int K, int N);
+// native: the 4-bit codes are in the native storage order (q = 1 only)
+DecodePlan plan_decode(int q, int M, int K, int N, int native = 0);
 hipError_t launch_decode(int q, const DecodeArgs& a, hipStream_t st);
 
 // ---- 4-bit weights, M <= 16 (decode_small.hip) ----
@@ -87,6 +89,7 @@ struct SmallArgs {
     int         bf;
     int         native;    // w is in the native storage order (fp16 activations only)
     int         dense;     // w is a 16-bit matrix (fp16, or bfloat16 with bf): no scales, no zero points
+    int         wide;      // native order, 17 to 32 rows: the eight-wave kernel (DecodePlan::wide)
 };
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st);
 

@@ -99,7 +99,34 @@ def test_decode_on_native_codes(B, oracle, M, split):
         B.set_tuning(B.TUNE_DECODE_SPLIT, 0)
 
 
-@pytest.mark.parametrize("M", [16, 48])
+@pytest.mark.parametrize("M", [17, 24, 32])
+def test_both_kernels_for_17_to_32_rows_give_the_same_bits(B, oracle, M):
+    """17 to 32 rows on the native order go to the eight-wave kernel; tuning key 12 = 4 sends them to the
+    four-wave one.  Same arithmetic in the same order, a different share-out over waves: the same bits, with
+    and without a split along K, and either way within the oracle's tolerance."""
+    for (K, N, split) in ((1792, 520, 0), (1024, 2824, 1), (4096, 264, 5)):
+        W = synth.weights(78, K, N, layer_id=M)
+        x = synth.activations(78, M, K, layer_id=M + 1)
+        qw, sc, qz = oracle.quantize_w4(W)
+        nat = B.repack_w4_native(dev(qw))
+        ys = []
+        for key12 in (0, 4):
+            B.set_tuning(B.TUNE_DECODE_SPLIT, split)
+            B.set_tuning(B.TUNE_SMALL, key12)
+            try:
+                ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
+                ys.append(host(B.linear_w4a16_native(dev(x), nat, dev(sc), dev(qz), ws)))
+                torch.cuda.synchronize()
+            finally:
+                B.set_tuning(B.TUNE_SMALL, 0)
+                B.set_tuning(B.TUNE_DECODE_SPLIT, 0)
+        r = oracle.error_metric(ys[0], oracle.linear_w4a16(x, qw, sc, qz))
+        say(f"  native M={M} K={K} N={N} split={split}: err={r['err']:.3e}")
+        assert r["finite"] and r["err"] <= TOL, r
+        assert np.array_equal(ys[0].view(np.uint16), ys[1].view(np.uint16))
+
+
+@pytest.mark.parametrize("M", [16, 32, 48])
 def test_identity_activations_on_native_codes(B, oracle, M):
     """x = rows of the identity: y must be the fp16-rounded dequantized weight, bit for bit: pins the
     order of rows, columns and nibbles through both kernels that read this order."""
