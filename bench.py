@@ -158,7 +158,7 @@ def main():
     avg_launch_s = sec / (args.steps * launches_per_step)
     roofline = {
         "bound": "hbm",
-        "kernel": "decode_small_kernel<RL, false, true> (W4A16, M <= 16, codes in native order; RL = 1 up to 4 rows, else 4), mean over the 12 launches of a step",
+        "kernel": "W4A16 decode on the codes in native order, mean over the 12 launches of a step: decode_small_kernel<1, false, true> at M = 1 and 4 (8 launches), decode_wide_kernel<1> at M = 16 (4 launches)",
         "achieved": round(value, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
@@ -552,19 +552,41 @@ def main():
             for Mc in Ms:
                 xs_c[(Mc, K)] = synth.activations(2, Mc, K, tensor_id=Mc)
         t_total, b_total, reps = 0.0, 0, 0
+        per = {(Mc, name): [0.0, 0] for Mc in Ms for name in order}          # seconds, calls
         while t_total < 10.0 and reps < 64:
             for Mc in Ms:
                 for name in order:
                     K, N = shapes7[name]
                     t0 = time.perf_counter()
                     O.linear_w4a16(xs_c[(Mc, K)], *recs[name])
-                    t_total += time.perf_counter() - t0
+                    dt = time.perf_counter() - t0
+                    t_total += dt
+                    per[(Mc, name)][0] += dt
+                    per[(Mc, name)][1] += 1
                     b_total += synth.w4_bytes(K, N, zeros=False)
             reps += 1
-        result["cpu_baseline"] = {"value": round(b_total / t_total / 1e9, 4), "unit": "GB/s", "cores": O.num_threads(),
+        # per figure: mean seconds per call, GFLOP/s (2 M K N) and GB/s of codes + scales, next to the GPU figures of `detail`
+        figures = {}
+        for (Mc, name), (sec, n) in per.items():
+            K, N = shapes7[name]
+            figures[f"w4a16/{name}/M{Mc}"] = {"s": round(sec / n, 5), "GFLOPs": round(2.0 * Mc * K * N * n / sec / 1e9, 2),
+                                              "GBps": round(synth.w4_bytes(K, N, zeros=False) * n / sec / 1e9, 3)}
+        # configuration 1 (one 4096 x 4096 W4A16 linear, one row) on a single thread
+        threads = O.num_threads()
+        K1, N1 = shapes7["o"]
+        O.set_num_threads(1)
+        try:
+            t0 = time.perf_counter()
+            O.linear_w4a16(xs_c[(1, K1)], *recs["o"])
+            t_single = time.perf_counter() - t0
+        finally:
+            O.set_num_threads(threads)
+        result["cpu_baseline"] = {"value": round(b_total / t_total / 1e9, 4), "unit": "GB/s", "cores": threads,
                                   "kind": "oracle",
                                   "sample": f"{reps} repetitions of the bench step (llama7b layer, 4 linears, W4A16, "
-                                            f"M in {{1,4,16}}) on one layer's weights, fp64 oracle, {t_total:.1f} s"}
+                                            f"M in {{1,4,16}}) on one layer's weights, fp64 oracle, {t_total:.1f} s",
+                                  "figures": figures,
+                                  "config1_single_thread_s": round(t_single, 4)}
     print(json.dumps(result))
 
 

@@ -377,13 +377,13 @@ static DecodePlan plan_small(int q, int M, int K, int N, int native)
     // uses more than half the registers and the LDS of one).
     int target = tuning_get(TUNE_DECODE_WGS);
     if (target <= 0) target = prefill_compute_units();
-    // 17 to 32 rows on the native code order: the eight-wave kernel (decode_wide_kernel); beyond 32 rows slices
+    // 9 to 32 rows on the native code order: the eight-wave kernel (decode_wide_kernel); beyond 32 rows slices
     // of 32 rows, a workgroup each
-    const bool wide  = native && q == 1 && M > 16 && M <= 32 && tuning_get(TUNE_SMALL) != 4;
+    const bool wide  = native && q == 1 && M > 8 && M <= 32 && tuning_get(TUNE_SMALL) != 4;
     const int slices = M > 32 ? 2 : 1;
     int S = target / (pl.tiles * slices);
     // every workgroup keeps a quantization group; beyond 16 rows, and for dense weights, each half of its waves one
-    const int most = (M <= 16 && q == 1) ? T / 4 : (T / 8 > 0 ? T / 8 : 1);
+    const int most = (M <= 16 && q == 1 && !wide) ? T / 4 : (T / 8 > 0 ? T / 8 : 1);
     if (S > most) S = most;
     if (S > 16) S = 16;
     const int forced = tuning_get(TUNE_DECODE_SPLIT);

@@ -41,7 +41,7 @@
 //     of at most 32 rows, two waves side by side and two along K; beyond 32 rows two workgroups on
 //     the same XCD take a slice each and the second reading of the weights is served by that XCD's
 //     L2.  x reaches the waves through LDS, in whole cache lines.
-//   decode_wide_kernel, 17 <= M <= 32 on the native code order: eight waves, two to a SIMD, 64 columns each.
+//   decode_wide_kernel, 9 <= M <= 32 on the native code order: eight waves, two to a SIMD, 64 columns each.
 #include <type_traits>
 
 #include "dev_common.h"
@@ -792,7 +792,7 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// 17 <= M <= 32 on the native code order: eight waves, two to a SIMD.  Wave (kh, cq) = (wave >> 2,
+// 9 <= M <= 32 on the native code order: eight waves, two to a SIMD.  Wave (kh, cq) = (wave >> 2,
 // wave & 3) takes half kh of the workgroup's quantization groups and, of every lane's 16 columns in that
 // order, the four that its load cq holds: columns n0 + 16 c + 4 cq .. + 3 for c = 0 .. 15, all rows of
 // them.  A k-step is then one 16-byte load per lane -- one contiguous kilobyte per wave -- and group sums,
@@ -802,9 +802,14 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
 // shared by the four waves of a kh through LDS (each fetches a quarter of the rows, in whole cache
 // lines); one workgroup barrier per group keeps the two buffers apart, so both halves of K walk the same
 // number of groups (the shorter one a dead group at its end).
-// RT: tiles of 16 rows.  With RT = 4 (all of 64 rows in one workgroup, every weight unpacked once) the
-// kernel needs all 256 registers and measured slower than two slices of decode_mid_kernel (8B shapes at
-// M = 64: 14.0 / 11.5 / 31.9 / 23.4 us against 13.1 / 9.8 / 29.5 / 18.3), so only RT = 2 is built.
+// RT: tiles of 16 rows (1: M <= 16, 2: M <= 32).  With RT = 4 (all of 64 rows in one workgroup, every weight
+// unpacked once) the kernel needs all 256 registers and measured slower than two slices of
+// decode_mid_kernel (8B shapes at M = 64: 14.0 / 11.5 / 31.9 / 23.4 us against 13.1 / 9.8 / 29.5 / 18.3), so it is
+// not built.  Below nine rows decode_small_kernel is as fast or faster (its fold touches only the rows
+// that exist up to four of them, and a wave has four kilobytes per k-step in flight instead of one).
+// A ring of eight stages (seven k-steps ahead) measured slower than four at either RT, and so did
+// loads that write to LDS directly (buffer_load ... lds) sixteen deep: what bounds this loop is the
+// instructions a SIMD issues, not the bytes it has in flight.
 // ------------------------------------------------------------------------------------------------
 constexpr int kWideWaves = 8;
 struct WideGroup {
@@ -823,8 +828,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
     // loop the first 32 KB hold the results of one tile of 16 rows at a time:
     // [kh][4-row group b][column of the tile: column 16 c + j stored at 16 c + (j ^ c)].
     constexpr int kXBuf = RT * 256;                      // pieces per buffer
-    __shared__ __align__(16) u32x4 sm[4 * kXBuf];
-    static_assert(4 * kXBuf >= 2048, "the results of a tile of rows need 32 KB");
+    __shared__ __align__(16) u32x4 sm[4 * kXBuf > 2048 ? 4 * kXBuf : 2048];   // the results of a tile of rows need 32 KB
     __shared__ uint32_t fresh_word;
 
     MORPH_TICK(0);                                       // kernel entry
@@ -910,8 +914,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
     MORPH_TICK(1);                                       // first loads issued
 
     // A vector = four rows of one column; vector (mt, rq, col): column n0 + col, rows 16 mt + 4 rq ..;
-    // its number is id = 1024 mt + 256 rq + col.
-    constexpr int nvec = 1024 * RT;
+    // its number is id = 1024 mt + 256 rq + col.  With one tile of rows only the groups of four rows that exist are numbered.
+    const int nvec = RT == 1 ? 256 * t.nb : 1024 * RT;
     uint16_t* y = (uint16_t*)t.y;
     auto vec_store_y = [&](int id, f32x4 acc) {
         const int col = n0 + (id & 255), row = 4 * (id >> 8);
@@ -1009,7 +1013,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
                 sm[kh * 1024 + b * 256 + 16 * c + ((4 * cq + j) ^ c)] = bit_cast<u32x4>(v);
             }
             __syncthreads();
-            for (int lid = tid; lid < 1024; lid += kWideWaves * 64) {
+            const int live = RT == 1 ? 256 * t.nb : 1024;
+            for (int lid = tid; lid < live; lid += kWideWaves * 64) {
                 const int pos = (lid & ~15) | ((lid ^ (lid >> 4)) & 15);     // column 16 c + j sits at j ^ c
                 sink(mt * 1024 + lid, bit_cast<f32x4>(sm[pos]) + bit_cast<f32x4>(sm[1024 + pos]));
             }
@@ -1199,6 +1204,7 @@ hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
     }
     if (a.native) {
         if constexpr (BF) return hipErrorInvalidValue;
+        else if (a.wide && a.M <= 16) return launch_small_with(decode_wide_kernel<1>, kWideWaves, a, st);
         else if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, false, true>, kSmWaves, a, st);
         else if (a.M <= 16) return launch_small_with(decode_small_kernel<4, false, true>, kSmWaves, a, st);
         else if (!a.wide)   return launch_small_with(decode_mid_kernel<false, true>, kSmWaves, a, st);
@@ -1216,7 +1222,7 @@ MORPH_TICK_EXPORTS(small_ticks)
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
 {
     if (a.M < 1 || a.M > 64 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1 || a.tiles > 65535 || a.K / kGroup > 65535) return hipErrorInvalidValue;
-    if (a.wide && (!a.native || a.bf || a.M <= 16 || a.M > 32)) return hipErrorInvalidValue;
+    if (a.wide && (!a.native || a.bf || a.M > 32)) return hipErrorInvalidValue;
     if (a.S > 1 && a.tiles * (a.M > 32 ? 2 : 1) > 256) return hipErrorInvalidValue;     // flags for 256 (tile, slice) pairs
     if (a.dense && a.native) return hipErrorInvalidValue;
     return a.bf ? launch_small_m<true>(a, st) : launch_small_m<false>(a, st);
