@@ -129,7 +129,7 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
  * morph_quantize_layer_native = morph_quantize_layer into qweight_tmp (canonical size) followed by the
  * repack; morph_dequantize_w4_native is morph_dequantize_w4 on the native array (the same values);
  * morph_linear_w4a16_native is morph_linear_w4a16 on it for M <= 64 and fp16 activations (the same
- * bits: the arithmetic and its order do not change -- except from 9 to 16 rows, where this order has a
+ * bits: the arithmetic and its order do not change -- except up to 16 rows where this order goes to a
  * kernel of its own that shares the sum over K out differently: the same products, fp32 sums rounded in
  * another order), MORPH_ERR_UNSUPPORTED otherwise; workspace of
  * morph_workspace_bytes(MORPH_KIND_W4A16, M, K, N).  Arguments, alignment and errors as above.

@@ -377,19 +377,28 @@ static DecodePlan plan_small(int q, int M, int K, int N, int native)
     // uses more than half the registers and the LDS of one).
     int target = tuning_get(TUNE_DECODE_WGS);
     if (target <= 0) target = prefill_compute_units();
-    // 9 to 32 rows on the native code order: the eight-wave kernel (decode_wide_kernel); beyond 32 rows slices
-    // of 32 rows, a workgroup each
-    const bool wide  = native && q == 1 && M > 8 && M <= 32 && tuning_get(TUNE_SMALL) != 4;
-    const int slices = M > 32 ? 2 : 1;
-    int S = target / (pl.tiles * slices);
-    // every workgroup keeps a quantization group; beyond 16 rows, and for dense weights, each half of its waves one
-    const int most = (M <= 16 && q == 1 && !wide) ? T / 4 : (T / 8 > 0 ? T / 8 : 1);
-    if (S > most) S = most;
-    if (S > 16) S = 16;
-    const int forced = tuning_get(TUNE_DECODE_SPLIT);
-    if (forced > 0) S = forced > 16 ? 16 : forced;
-    if (S > T / 4) S = T / 4;
-    if (S < 1) S = 1;
+    const int slices = M > 32 ? 2 : 1;                   // beyond 32 rows slices of 32 rows, a workgroup each
+    // `most`: every workgroup keeps a quantization group (decode_small_kernel), or each half of its waves one
+    auto split_for = [&](int most) {
+        int S = target / (pl.tiles * slices);
+        if (S > most) S = most;
+        if (S > 16) S = 16;
+        const int forced = tuning_get(TUNE_DECODE_SPLIT);
+        if (forced > 0) S = forced > 16 ? 16 : forced;
+        if (S > T / 4) S = T / 4;
+        return S < 1 ? 1 : S;
+    };
+    const int halves = T / 8 > 0 ? T / 8 : 1;
+    int S = split_for((M <= 16 && q == 1) ? T / 4 : halves);
+    // The native code order has the eight-wave kernel (decode_wide_kernel) from 9 to 32 rows, and below nine rows where a
+    // workgroup is left with few groups to walk, which eight waves share out better than four (measured on the 7B shapes
+    // at M = 1 and 4: o-proj, 2 groups per workgroup, 5.7 -> 5.4 us, down, 5.4 groups, 8.1 -> 7.7; qkv, 6.4 groups, 8.0 -> 8.4,
+    // gate_up, 16 groups, 11.1 -> 12.4).
+    bool wide = false;
+    if (native && q == 1 && M <= 32 && tuning_get(TUNE_SMALL) != 4) {
+        wide = M > 8 || (T / 4) <= 6 * S;
+        if (wide) S = split_for(halves);
+    }
     pl.S = S;
     // vectors of four rows per tile: up to 16 rows only the groups of four that exist, beyond whole tiles of 16 rows
     const size_t nvec = M <= 16 ? (size_t)256 * ((M + 3) / 4) : (size_t)2048;

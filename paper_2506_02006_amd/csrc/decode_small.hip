@@ -41,7 +41,7 @@
 //     of at most 32 rows, two waves side by side and two along K; beyond 32 rows two workgroups on
 //     the same XCD take a slice each and the second reading of the weights is served by that XCD's
 //     L2.  x reaches the waves through LDS, in whole cache lines.
-//   decode_wide_kernel, 9 <= M <= 32 on the native code order: eight waves, two to a SIMD, 64 columns each.
+//   decode_wide_kernel, M <= 32 on the native code order: eight waves, two to a SIMD, 64 columns each.
 #include <type_traits>
 
 #include "dev_common.h"
@@ -792,7 +792,8 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// 9 <= M <= 32 on the native code order: eight waves, two to a SIMD.  Wave (kh, cq) = (wave >> 2,
+// M <= 32 on the native code order (always from 9 rows, below where the planner finds few groups per
+// workgroup): eight waves, two to a SIMD.  Wave (kh, cq) = (wave >> 2,
 // wave & 3) takes half kh of the workgroup's quantization groups and, of every lane's 16 columns in that
 // order, the four that its load cq holds: columns n0 + 16 c + 4 cq .. + 3 for c = 0 .. 15, all rows of
 // them.  A k-step is then one 16-byte load per lane -- one contiguous kilobyte per wave -- and group sums,
@@ -802,11 +803,12 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
 // shared by the four waves of a kh through LDS (each fetches a quarter of the rows, in whole cache
 // lines); one workgroup barrier per group keeps the two buffers apart, so both halves of K walk the same
 // number of groups (the shorter one a dead group at its end).
-// RT: tiles of 16 rows (1: M <= 16, 2: M <= 32).  With RT = 4 (all of 64 rows in one workgroup, every weight
+// RT: tiles of 16 rows (1: M <= 16, 2: M <= 32); RL as in decode_small_kernel.  With RT = 4 (all of 64 rows in one workgroup, every weight
 // unpacked once) the kernel needs all 256 registers and measured slower than two slices of
 // decode_mid_kernel (8B shapes at M = 64: 14.0 / 11.5 / 31.9 / 23.4 us against 13.1 / 9.8 / 29.5 / 18.3), so it is
-// not built.  Below nine rows decode_small_kernel is as fast or faster (its fold touches only the rows
-// that exist up to four of them, and a wave has four kilobytes per k-step in flight instead of one).
+// not built.  Below nine rows decode_small_kernel is faster where a workgroup walks many groups (a wave
+// has four kilobytes per k-step in flight instead of one), this kernel where it walks few (eight waves
+// share two or five groups out better than four).
 // A ring of eight stages (seven k-steps ahead) measured slower than four at either RT, and so did
 // loads that write to LDS directly (buffer_load ... lds) sixteen deep: what bounds this loop is the
 // instructions a SIMD issues, not the bytes it has in flight.
@@ -817,11 +819,12 @@ struct WideGroup {
     u32x2    sc;                                 // their scales
 };
 
-template <int RT>
+template <int RT, int RL>
 __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
     const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
     int tiles_sl, int inv_s, SmallTail t)
 {
+    static_assert(RL == 4 || (RL == 1 && RT == 1), "RL = 1: at most four rows, one tile");
     const int M = ms & 0xFFFF, S = ms >> 16, q_groups = qr & 0xFFFF, r_groups = qr >> 16;
     // During the k loop: [kh][buffer][row][piece] -- per half of K two groups of x, 16 RT rows of 128 k, a
     // row = 16 pieces of 16 bytes, piece p stored at p ^ (row & 15) (see decode_mid_kernel).  After the
@@ -855,8 +858,11 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
     const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
     const uint32_t voff_z = col_ok ? (uint32_t)(ncol >> 3) * 4u : kOut;
     const uint32_t zsh    = 16u * (uint32_t)(cq & 1);                          // the lane's four nibbles in that word
-    // x of a whole group: load i takes row 16 i + 4 cq + b, piece c; rows at or beyond M lie past the buffer
-    const uint32_t voff_x = ((uint32_t)(4 * cq + b) * (uint32_t)K + 8u * (uint32_t)c) * 2u;
+    // x of a whole group: load i takes row 16 i + 4 cq + b, piece c; rows at or beyond M lie past the buffer.
+    // RL = 1: x row m is the MFMA's row 4 m (it comes out as the first accumulator component of lane (c, m)), the
+    // other rows are zero
+    const uint32_t voff_x = RL == 1 ? (b ? kOut : ((uint32_t)cq * (uint32_t)K + 8u * (uint32_t)c) * 2u)
+                                    : ((uint32_t)(4 * cq + b) * (uint32_t)K + 8u * (uint32_t)c) * 2u;
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
     u32x4* const xl = sm + kh * 2 * kXBuf;               // the two buffers of this half of K
 
@@ -930,14 +936,14 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
         // gacc[mt][2 yb]: sum of x * byte, gacc[mt][2 yb + 1]: sum of x * (byte & 0xF0) over the open group,
         // byte column yb of the lane (columns 2 yb and 2 yb + 1)
         f32x4 gacc[RT][4], xs[RT];
-        float yr[RT][4][4];                              // running results, column j of the lane, row 16 mt + 4 b + r
+        float yr[RT][4][RL];                             // running results, column j of the lane, row 16 mt + 4 b + r (RL = 1: row b)
 #pragma unroll
         for (int mt = 0; mt < RT; mt++) {
 #pragma unroll
             for (int j = 0; j < 4; j++) {
                 gacc[mt][j] = zero4;
 #pragma unroll
-                for (int r = 0; r < 4; r++) yr[mt][j][r] = 0.f;
+                for (int r = 0; r < RL; r++) yr[mt][j][r] = 0.f;
             }
             xs[mt] = zero4;
         }
@@ -988,7 +994,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
 #pragma unroll
                 for (int mt = 0; mt < RT; mt++) {
 #pragma unroll
-                    for (int r = 0; r < 4; r++) {
+                    for (int r = 0; r < RL; r++) {
                         const float d = gacc[mt][2 * yb][r] - gacc[mt][2 * yb + 1][r];
                         yr[mt][2 * yb][r]     = __builtin_fmaf(-c_lo, xs[mt][r], __builtin_fmaf(s_lo, d, yr[mt][2 * yb][r]));
                         yr[mt][2 * yb + 1][r] = __builtin_fmaf(-c_hi, xs[mt][r], __builtin_fmaf(s_hi, gacc[mt][2 * yb + 1][r], yr[mt][2 * yb + 1][r]));
@@ -1005,12 +1011,19 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
 #pragma unroll
         for (int mt = 0; mt < RT; mt++) {
             __syncthreads();                             // every wave is done with the tile before
+            if constexpr (RL == 1) {
+                // lane (c, b) holds row b of its columns: the four lanes of a column make up its vector
+                float* const sf = reinterpret_cast<float*>(sm);
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                f32x4 v;
+                for (int j = 0; j < 4; j++) sf[(kh * 1024 + 16 * c + ((4 * cq + j) ^ c)) * 4 + b] = yr[mt][j][0] * ((j & 1) ? kOdd : kEven);
+            } else {
 #pragma unroll
-                for (int r = 0; r < 4; r++) v[r] = yr[mt][j][r] * ((j & 1) ? kOdd : kEven);
-                sm[kh * 1024 + b * 256 + 16 * c + ((4 * cq + j) ^ c)] = bit_cast<u32x4>(v);
+                for (int j = 0; j < 4; j++) {
+                    f32x4 v;
+#pragma unroll
+                    for (int r = 0; r < 4; r++) v[r] = yr[mt][j][r] * ((j & 1) ? kOdd : kEven);
+                    sm[kh * 1024 + b * 256 + 16 * c + ((4 * cq + j) ^ c)] = bit_cast<u32x4>(v);
+                }
             }
             __syncthreads();
             const int live = RT == 1 ? 256 * t.nb : 1024;
@@ -1204,11 +1217,12 @@ hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
     }
     if (a.native) {
         if constexpr (BF) return hipErrorInvalidValue;
-        else if (a.wide && a.M <= 16) return launch_small_with(decode_wide_kernel<1>, kWideWaves, a, st);
+        else if (a.wide && a.M <= 4)  return launch_small_with(decode_wide_kernel<1, 1>, kWideWaves, a, st);
+        else if (a.wide && a.M <= 16) return launch_small_with(decode_wide_kernel<1, 4>, kWideWaves, a, st);
         else if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, false, true>, kSmWaves, a, st);
         else if (a.M <= 16) return launch_small_with(decode_small_kernel<4, false, true>, kSmWaves, a, st);
         else if (!a.wide)   return launch_small_with(decode_mid_kernel<false, true>, kSmWaves, a, st);
-        else return launch_small_with(decode_wide_kernel<2>, kWideWaves, a, st);
+        else return launch_small_with(decode_wide_kernel<2, 4>, kWideWaves, a, st);
     }
     if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, BF, false>, kSmWaves, a, st);
     if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF, false>, kSmWaves, a, st);

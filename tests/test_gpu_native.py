@@ -94,7 +94,7 @@ def test_decode_on_native_codes(B, oracle, M, split):
             r = oracle.error_metric(host(y), oracle.linear_w4a16(x, qw, sc, qz))
             say(f"  native M={M} K={K} N={N} split={split}: err={r['err']:.3e}")
             assert r["finite"] and r["err"] <= TOL, r
-            if 9 <= M <= 16:                              # the eight-wave kernel shares K out differently; the four-wave one gives the canonical bits
+            if M <= 16:                                   # the eight-wave kernel shares K out differently; the four-wave one gives the canonical bits
                 B.set_tuning(B.TUNE_SMALL, 4)
                 try:
                     y = B.linear_w4a16_native(dev(x), nat, dev(sc), dev(qz), ws)
@@ -106,10 +106,10 @@ def test_decode_on_native_codes(B, oracle, M, split):
         B.set_tuning(B.TUNE_DECODE_SPLIT, 0)
 
 
-@pytest.mark.parametrize("M", [9, 13, 16, 17, 24, 32])
-def test_both_kernels_for_9_to_32_rows(B, oracle, M):
-    """9 to 32 rows on the native order go to the eight-wave kernel; tuning key 12 = 4 sends them to the
-    four-wave ones.  Either way within the oracle's tolerance, with and without a split along K; from 17
+@pytest.mark.parametrize("M", [1, 3, 4, 5, 8, 9, 13, 16, 17, 24, 32])
+def test_both_kernels_up_to_32_rows(B, oracle, M):
+    """9 to 32 rows on the native order go to the eight-wave kernel, and so do fewer rows where a workgroup has few
+    groups of K to walk (the three shapes here); tuning key 12 = 4 sends them to the four-wave ones.  Either way within the oracle's tolerance, with and without a split along K; from 17
     rows on both halve a workgroup's K range the same way and give the same bits."""
     for (K, N, split) in ((1792, 520, 0), (1024, 2824, 1), (4096, 264, 5)):
         W = synth.weights(78, K, N, layer_id=M)
