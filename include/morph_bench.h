@@ -38,8 +38,8 @@ extern "C" {
  * 11 = prefill: who stages the tiles into LDS (1 = half the waves the weight tile and half the x tile,
  * 2 = every wave an equal share of both; quantized kinds only).
  * 12 = the register-tiled kernel for at most 64 rows of 4-bit weights (2 = never: the general streaming kernels
- *      take them; 3 = only up to 16 rows; 4 = up to 32 rows on the native code order always through the four-wave kernels,
- *      never the eight-wave one).
+ *      take them; 3 = only up to 16 rows; 4 = the native code order always through the four-wave kernels,
+ *      never the eight-wave one; 5 = always through the eight-wave one).
  * 13 = that kernel's hand-over: 1 = written through to memory instead of kept in one XCD's L2.
  * A change alters morph_workspace_bytes(); size the workspace after setting. */
 int morph_set_tuning(int key, int value);

@@ -395,8 +395,8 @@ static DecodePlan plan_small(int q, int M, int K, int N, int native)
     // at M = 1 and 4: o-proj, 2 groups per workgroup, 5.7 -> 5.4 us, down, 5.4 groups, 8.1 -> 7.7; qkv, 6.4 groups, 8.0 -> 8.4,
     // gate_up, 16 groups, 11.1 -> 12.4).
     bool wide = false;
-    if (native && q == 1 && M <= 32 && tuning_get(TUNE_SMALL) != 4) {
-        wide = M > 8 || (T / 4) <= 6 * S;
+    if (native && q == 1 && tuning_get(TUNE_SMALL) != 4) {
+        wide = M > 8 || (T / 4) <= 6 * S || tuning_get(TUNE_SMALL) == 5;
         if (wide) S = split_for(halves);
     }
     pl.S = S;

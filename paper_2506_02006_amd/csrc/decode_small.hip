@@ -41,7 +41,8 @@
 //     of at most 32 rows, two waves side by side and two along K; beyond 32 rows two workgroups on
 //     the same XCD take a slice each and the second reading of the weights is served by that XCD's
 //     L2.  x reaches the waves through LDS, in whole cache lines.
-//   decode_wide_kernel, M <= 32 on the native code order: eight waves, two to a SIMD, 64 columns each.
+//   decode_wide_kernel, the native code order from 9 rows on (and below where K is cut short): eight waves, two to
+//     a SIMD, 64 columns each, slices of 32 rows.
 #include <type_traits>
 
 #include "dev_common.h"
@@ -792,8 +793,8 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_mid_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// M <= 32 on the native code order (always from 9 rows, below where the planner finds few groups per
-// workgroup): eight waves, two to a SIMD.  Wave (kh, cq) = (wave >> 2,
+// The native code order at 9 rows or more (beyond 32 in two slices of 32 rows, as decode_mid_kernel), and
+// below 9 where the planner finds few groups per workgroup: eight waves, two to a SIMD.  Wave (kh, cq) = (wave >> 2,
 // wave & 3) takes half kh of the workgroup's quantization groups and, of every lane's 16 columns in that
 // order, the four that its load cq holds: columns n0 + 16 c + 4 cq .. + 3 for c = 0 .. 15, all rows of
 // them.  A k-step is then one 16-byte load per lane -- one contiguous kilobyte per wave -- and group sums,
@@ -821,11 +822,11 @@ struct WideGroup {
 
 template <int RT, int RL>
 __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
-    const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
+    const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
     int tiles_sl, int inv_s, SmallTail t)
 {
     static_assert(RL == 4 || (RL == 1 && RT == 1), "RL = 1: at most four rows, one tile");
-    const int M = ms & 0xFFFF, S = ms >> 16, q_groups = qr & 0xFFFF, r_groups = qr >> 16;
+    const int M_all = ms & 0xFFFF, S = ms >> 16, q_groups = qr & 0xFFFF, r_groups = qr >> 16;
     // During the k loop: [kh][buffer][row][piece] -- per half of K two groups of x, 16 RT rows of 128 k, a
     // row = 16 pieces of 16 bytes, piece p stored at p ^ (row & 15) (see decode_mid_kernel).  After the
     // loop the first 32 KB hold the results of one tile of 16 rows at a time:
@@ -843,6 +844,9 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
     const Place p = place_of(tiles_sl, inv_s, S);
     if (p.tile >= tiles) return;
     const int n0 = p.tile * 256;
+    // this workgroup's rows: beyond 32 rows two workgroups on the same XCD take a slice of 32 rows each (see decode_mid_kernel)
+    const int M = M_all - 32 * p.slice < 16 * RT ? M_all - 32 * p.slice : 16 * RT;
+    const uint16_t* x = (const uint16_t*)x_all + (size_t)(32 * p.slice) * K;
 
     const uint32_t zrow_bytes = (uint32_t)(N >> 3) * 4u;
     const uint32_t ksteps = (uint32_t)K >> 5;
@@ -922,7 +926,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
     // A vector = four rows of one column; vector (mt, rq, col): column n0 + col, rows 16 mt + 4 rq ..;
     // its number is id = 1024 mt + 256 rq + col.  With one tile of rows only the groups of four rows that exist are numbered.
     const int nvec = RT == 1 ? 256 * t.nb : 1024 * RT;
-    uint16_t* y = (uint16_t*)t.y;
+    uint16_t* y = (uint16_t*)t.y + (size_t)(32 * p.slice) * N;
     auto vec_store_y = [&](int id, f32x4 acc) {
         const int col = n0 + (id & 255), row = 4 * (id >> 8);
         if (col < N) {
@@ -1236,7 +1240,7 @@ MORPH_TICK_EXPORTS(small_ticks)
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
 {
     if (a.M < 1 || a.M > 64 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1 || a.tiles > 65535 || a.K / kGroup > 65535) return hipErrorInvalidValue;
-    if (a.wide && (!a.native || a.bf || a.M > 32)) return hipErrorInvalidValue;
+    if (a.wide && (!a.native || a.bf)) return hipErrorInvalidValue;
     if (a.S > 1 && a.tiles * (a.M > 32 ? 2 : 1) > 256) return hipErrorInvalidValue;     // flags for 256 (tile, slice) pairs
     if (a.dense && a.native) return hipErrorInvalidValue;
     return a.bf ? launch_small_m<true>(a, st) : launch_small_m<false>(a, st);

@@ -52,7 +52,7 @@ struct DecodePlan {
     int    scatter;            // share the sum over the splits out among the workgroups of a tile
     int    polls;              // how many times a workgroup looks for the others before it gives up
     int    small;              // the launch goes to the register-tiled kernels for at most 64 rows (decode_small.hip)
-    int    wide;               // ... to the eight-wave kernel for up to 32 rows on the native code order
+    int    wide;               // ... to the eight-wave kernel on the native code order
 };
 // Workspace layout, the same for every kernel family so that one workspace serves any sequence of calls:
 //   [0, kCounterBytes)                 counters, zero between launches
@@ -89,7 +89,7 @@ struct SmallArgs {
     int         bf;
     int         native;    // w is in the native storage order (fp16 activations only)
     int         dense;     // w is a 16-bit matrix (fp16, or bfloat16 with bf): no scales, no zero points
-    int         wide;      // native order, up to 32 rows: the eight-wave kernel (DecodePlan::wide)
+    int         wide;      // native order: the eight-wave kernel (DecodePlan::wide)
 };
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st);
 
