@@ -49,11 +49,12 @@ def main():
     ap.add_argument("--command", default="")
     ap.add_argument("--note", default="")
     ap.add_argument("--min-launches", type=int, default=3, help="leave out (kernel, grid) rows with fewer launches (warm-up on dummies)")
-    ap.add_argument("--mean-of", default="", help="kernel name prefix: print its launch-weighted mean traffic and duration")
+    ap.add_argument("--mean-of", default="", help="kernel name prefix, or several separated by '|': print the launch-weighted mean traffic and duration over them")
     ap.add_argument("--mean-has", default="", help="with --mean-of: the kernel name must also contain this (a template argument list)")
     ap.add_argument("--counters", help="results db of a further --pmc run")
     ap.add_argument("--like", default="prefill_kernel", help="kernel name substring for --counters")
     a = ap.parse_args()
+    prefixes = tuple(x for x in a.mean_of.split("|") if x)
     if a.command:
         print("command:")
         for line in a.command.split(";"):
@@ -87,7 +88,7 @@ def main():
             wm = w[k][1] * w_scale * 1024 / 1e6
             print(f"{k[0][:58]:58s} {str(k[1]) + 'x' + str(k[2]):>14s} {f[k][0]:6d} {fm:10.3f} {wm:10.3f} {fm + wm:10.3f}")
         if a.mean_of:
-            ks = [k for k in f if k in w and k[0].startswith(a.mean_of) and a.mean_has in k[0] and f[k][0] >= 10]
+            ks = [k for k in f if k in w and k[0].startswith(prefixes) and a.mean_has in k[0] and f[k][0] >= 10]
             n = sum(f[k][0] for k in ks)
             tot = sum(f[k][0] * (f[k][1] * f_scale + w[k][1] * w_scale) * 1024 for k in ks)
             print(f"\nlaunch-weighted mean over {a.mean_of} {a.mean_has} (rows with n >= 10):")
@@ -117,7 +118,7 @@ def main():
                 tf = 512.0 * mops[1] / (dur[k] * 1e-6) / 1e12
                 print(f"    -> {512.0 * mops[1]:.4e} MFMA flop in {dur[k]:.1f} us = {tf:.1f} TFLOP/s = {tf / 2500.0 * 100:.1f} % of 2.5 PFLOP/s dense fp16")
     if a.mean_of and a.trace:
-        rows = [r for r in trace_rows(a.trace) if short(r[0]).startswith(a.mean_of) and a.mean_has in short(r[0]) and r[3] >= 10]
+        rows = [r for r in trace_rows(a.trace) if short(r[0]).startswith(prefixes) and a.mean_has in short(r[0]) and r[3] >= 10]
         n = sum(r[3] for r in rows)
         print(f"duration_us_per_launch_mean: {sum(r[3] * r[4] for r in rows) / n:.3f}   ({n} launches)")
 
