@@ -128,13 +128,14 @@ int morph_dequantize_w4(const int32_t* qweight, const void* scales, const int32_
  * morph_repack_w4_native / morph_unpack_w4_native convert between the two (device arrays, exact);
  * morph_quantize_layer_native = morph_quantize_layer into qweight_tmp (canonical size) followed by the
  * repack; morph_dequantize_w4_native is morph_dequantize_w4 on the native array (the same values);
- * morph_linear_w4a16_native is morph_linear_w4a16 on it for M <= 64 and fp16 activations (the same
+ * morph_linear_w4a16_native is morph_linear_w4a16 on it for M <= 64, and morph_linear_w4a16_native_bf16 is
+ * morph_linear_w4a16_bf16 (x and y bfloat16, see below) on it (the same
  * bits: the arithmetic and its order do not change -- except up to 16 rows where this order goes to a
  * kernel of its own that shares the sum over K out differently: the same products, fp32 sums rounded in
  * another order), MORPH_ERR_UNSUPPORTED otherwise; workspace of
  * morph_workspace_bytes(MORPH_KIND_W4A16, M, K, N).  Arguments, alignment and errors as above.
  * MORPH_KIND_W4A16_NATIVE names this form in the layer descriptors and layer records below (same
- * limits: at most 64 rows, fp16 activations) and in morph_workspace_bytes (same answer as W4A16). */
+ * limit: at most 64 rows) and in morph_workspace_bytes (same answer as W4A16). */
 size_t morph_w4_native_bytes(int K, int N);
 int morph_repack_w4_native(const int32_t* qweight, void* native, int K, int N, void* stream);
 int morph_unpack_w4_native(const void* native, int32_t* qweight, int K, int N, void* stream);
@@ -145,6 +146,9 @@ int morph_dequantize_w4_native(const void* native, const void* scales, const int
 int morph_linear_w4a16_native(const void* x, const void* native, const void* scales, const int32_t* qzeros,
                               void* y, int M, int K, int N, int group_size, void* workspace,
                               size_t workspace_bytes, void* stream);
+int morph_linear_w4a16_native_bf16(const void* x, const void* native, const void* scales, const int32_t* qzeros,
+                                   void* y, int M, int K, int N, int group_size, void* workspace,
+                                   size_t workspace_bytes, void* stream);
 
 /* ---- the 8-bit weight-only variant (Section 4.3 lists INT8 next to INT4 among the variants of
  * a layer; Appendix C: FP16, W8 and W4 are preloaded) ----
@@ -219,8 +223,8 @@ int morph_glue_bf16(int op, const void* a, const void* b, void* out, int M, int 
  * If tap_layer is in [0, n_layers) the inputs and outputs of that layer's four linears are also
  * copied, in order (x, qkv, a, o, r, gu, m, d), to `tap` (device, morph_stack_tap_bytes() bytes),
  * for checking each linear against a reference on its actual input.
- * A layer of kind MORPH_KIND_W4A16_NATIVE is refused (UNSUPPORTED, before the first launch) by the
- * bfloat16 variant and for shapes the decode kernels for at most 64 rows do not take. */
+ * A layer of kind MORPH_KIND_W4A16_NATIVE is refused (UNSUPPORTED, before the first launch) for
+ * shapes the decode kernels for at most 64 rows do not take. */
 typedef struct {
     int         kind;     /* MORPH_KIND_FP16, _W4A16, _W8A16 or _W4A16_NATIVE */
     const void* w;        /* fp16 [K,N], int32 qweight [K,N/8] (W8: [K,N/4]), or the native code array */

@@ -37,7 +37,7 @@ EXPORTS = [
     "morph_glue_bf16", "morph_stack_forward_bf16",
     "morph_linear_w4a16_noalloc", "morph_noalloc_scratch_bytes",
     "morph_w4_native_bytes", "morph_repack_w4_native", "morph_unpack_w4_native", "morph_quantize_layer_native",
-    "morph_dequantize_w4_native", "morph_linear_w4a16_native",
+    "morph_dequantize_w4_native", "morph_linear_w4a16_native", "morph_linear_w4a16_native_bf16",
 ]
 
 
@@ -80,6 +80,7 @@ def lib() -> ctypes.CDLL:
     L.morph_quantize_layer_native.argtypes = [vp, i, vp, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w4_native.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_linear_w4a16_native.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.morph_linear_w4a16_native_bf16.argtypes = L.morph_linear_w4a16_native.argtypes
     L.morph_quantize_layer.argtypes = [vp, i, vp, vp, vp, i, i, i, vp]
     L.morph_dequantize_w4.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     L.morph_linear_w8a16.argtypes = L.morph_linear_w4a16.argtypes
@@ -291,6 +292,20 @@ def linear_w4a16_native(x, native, scales, qzeros, ws=None, out=None, group_size
                                            _dev(scales, torch.float16, "scales"), _dev(qzeros, torch.int32, "qzeros"),
                                            _dev(y, torch.float16, "y"), M, K, N, group_size, wp, wb, _stream()),
            "morph_linear_w4a16_native")
+    return y
+
+
+def linear_w4a16_native_bf16(x, native, scales, qzeros, ws=None, out=None, group_size: int = GROUP) -> torch.Tensor:
+    """morph_linear_w4a16_bf16 on the native code array (M <= 64; x and y bfloat16)."""
+    M, K = x.shape
+    N = scales.shape[1]
+    assert native.numel() == w4_native_bytes(K, N), (native.numel(), K, N)
+    y = out if out is not None else torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    wp, wb = _ws_args(ws)
+    _check(lib().morph_linear_w4a16_native_bf16(_dev(x, torch.bfloat16, "x"), _dev(native, torch.uint8, "native"),
+                                                _dev(scales, torch.float16, "scales"), _dev(qzeros, torch.int32, "qzeros"),
+                                                _dev(y, torch.bfloat16, "y"), M, K, N, group_size, wp, wb, _stream()),
+           "morph_linear_w4a16_native_bf16")
     return y
 
 

@@ -85,11 +85,11 @@ inline bool known_kind(int kind)
 // the planner and the workspace rules know the native code order as the 4-bit kind it is
 inline int plan_kind(int kind) { return kind == MORPH_KIND_W4A16_NATIVE ? MORPH_KIND_W4A16 : kind; }
 
-// The native code order is read by the kernels of decode_small.hip only: at most 64 rows, fp16
-// activations, a shape and tuning state for which the planner picks them.
-bool native_served(int M, int K, int N, int bf)
+// The native code order is read by the kernels of decode_small.hip only: at most 64 rows, a shape
+// and tuning state for which the planner picks them.
+bool native_served(int M, int K, int N, int)
 {
-    if (bf || M > 64 || !takes_stream(MORPH_KIND_W4A16, M, K, N)) return false;
+    if (M > 64 || !takes_stream(MORPH_KIND_W4A16, M, K, N)) return false;
     return plan_decode(MORPH_KIND_W4A16, M, K, N, 1).small;
 }
 
@@ -383,6 +383,16 @@ int morph_linear_w4a16_native(const void* x, const void* native, const void* sca
     if (int rc = validate_linear(MORPH_KIND_W4A16_NATIVE, x, native, scales, qzeros, y, M, K, N)) return rc;
     return run_linear(MORPH_KIND_W4A16_NATIVE, x, native, scales, qzeros, y, M, K, N, workspace, workspace_bytes,
                       (hipStream_t)stream);
+}
+
+int morph_linear_w4a16_native_bf16(const void* x, const void* native, const void* scales, const int32_t* qzeros,
+                                   void* y, int M, int K, int N, int group_size, void* workspace,
+                                   size_t workspace_bytes, void* stream)
+{
+    if (group_size != MORPH_GROUP_SIZE) return (x && native && scales && qzeros && y) ? MORPH_ERR_SHAPE : MORPH_ERR_NULL;
+    if (int rc = validate_linear(MORPH_KIND_W4A16_NATIVE, x, native, scales, qzeros, y, M, K, N)) return rc;
+    return run_linear(MORPH_KIND_W4A16_NATIVE, x, native, scales, qzeros, y, M, K, N, workspace, workspace_bytes,
+                      (hipStream_t)stream, 1);
 }
 
 int morph_quantize_layer_w8(const void* w, int w_dtype, int32_t* qweight, void* scales, int32_t* qzeros,
@@ -726,6 +736,7 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 16, kWK, kWN, 128, ws, wsb, stream))) return rc;
     if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 17, kWK, kWN, 128, ws, wsb, stream))) return rc;   // the eight-wave kernel for 17 to 32 rows
     if ((rc = morph_linear_w4a16_native(x, nat, s, z, y, 33, kWK, kWN, 128, ws, wsb, stream))) return rc;   // the kernel for 33 to 64 rows
+    for (int m : {1, 16, 17}) if ((rc = morph_linear_w4a16_native_bf16(x, nat, s, z, y, m, kWK, kWN, 128, ws, wsb, stream))) return rc;
     if ((rc = morph_dequantize_w4_native(nat, s, z, w, MORPH_DTYPE_F16, kWK, kWN, 128, stream))) return rc;
     if ((rc = morph_unpack_w4_native(nat, q, kWK, kWN, stream))) return rc;
     // the 8-bit variant: its codes (32 KB) go where the fp32 dummy matrix was

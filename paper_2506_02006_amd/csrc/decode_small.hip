@@ -820,7 +820,7 @@ struct WideGroup {
     u32x2    sc;                                 // their scales
 };
 
-template <int RT, int RL>
+template <int RT, int RL, bool BF>
 __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
     const uint32_t* w, const void* x_all, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
     int tiles_sl, int inv_s, SmallTail t)
@@ -893,11 +893,13 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
         for (int i = 0; i < RT; i++)
             xg[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (voff_x + (uint32_t)i * 32u * (uint32_t)K) | dm, dead ? 0u : (uint32_t)g * 256u, 0);
     };
+    // (bfloat16 x is scaled by 2^64 here, once for the four waves that read it: see bf16x8_up64)
     auto store_xgroup = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < RT; i++) {
             const int row = 16 * i + 4 * cq + b;
-            xl[buf * kXBuf + row * 16 + ((c ^ row) & 15)] = xg[i];
+            if constexpr (BF) xl[buf * kXBuf + row * 16 + ((c ^ row) & 15)] = bit_cast<u32x4>(bf16x8_up64(bit_cast<half8_t>(xg[i])));
+            else xl[buf * kXBuf + row * 16 + ((c ^ row) & 15)] = xg[i];
         }
     };
     auto begin_pass = [&](int split) {
@@ -932,7 +934,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
         if (col < N) {
 #pragma unroll
             for (int r = 0; r < 4; r++)
-                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<false>(acc[r]);
+                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<BF>(acc[r]);
         }
     };
 
@@ -978,11 +980,11 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
 #pragma unroll
                 for (int mt = 0; mt < RT; mt++) {
                     const half8_t xa = bit_cast<half8_t>(xl[xb * kXBuf + (16 * mt + c) * 16 + ((4 * u + b) ^ c)]);
-                    xs[mt]      = mfma_small<false>(xa, tiny, first ? zero4 : xs[mt]);
-                    gacc[mt][0] = mfma_small<false>(xa, bit_cast<half8_t>(b0), first ? zero4 : gacc[mt][0]);
-                    gacc[mt][1] = mfma_small<false>(xa, bit_cast<half8_t>(h0), first ? zero4 : gacc[mt][1]);
-                    gacc[mt][2] = mfma_small<false>(xa, bit_cast<half8_t>(b1), first ? zero4 : gacc[mt][2]);
-                    gacc[mt][3] = mfma_small<false>(xa, bit_cast<half8_t>(h1), first ? zero4 : gacc[mt][3]);
+                    xs[mt]      = mfma_small<BF>(xa, tiny, first ? zero4 : xs[mt]);
+                    gacc[mt][0] = mfma_small<BF>(xa, bit_cast<half8_t>(b0), first ? zero4 : gacc[mt][0]);
+                    gacc[mt][1] = mfma_small<BF>(xa, bit_cast<half8_t>(h0), first ? zero4 : gacc[mt][1]);
+                    gacc[mt][2] = mfma_small<BF>(xa, bit_cast<half8_t>(b1), first ? zero4 : gacc[mt][2]);
+                    gacc[mt][3] = mfma_small<BF>(xa, bit_cast<half8_t>(h1), first ? zero4 : gacc[mt][3]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -1010,8 +1012,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void decode_wide_kernel(
             __syncthreads();                             // it is there for all four waves; the other buffer is free
         }
         // the powers of two come out; one tile of 16 rows at a time through LDS, summed over the two halves of K
-        constexpr float kEven = 0x1p24f;                 // low-nibble (even) columns
-        constexpr float kOdd  = 0x1p20f;                 // high-nibble (odd) columns: their sums carry a factor 16
+        constexpr float kEven = BF ? 0x1p69f : 0x1p24f;                 // low-nibble (even) columns
+        constexpr float kOdd  = BF ? 0x1p65f : 0x1p20f;                 // high-nibble (odd) columns: their sums carry a factor 16
 #pragma unroll
         for (int mt = 0; mt < RT; mt++) {
             __syncthreads();                             // every wave is done with the tile before
@@ -1220,13 +1222,12 @@ hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
         return launch_small_with(decode_dense_kernel<2, BF>, kSmWaves, a, st);
     }
     if (a.native) {
-        if constexpr (BF) return hipErrorInvalidValue;
-        else if (a.wide && a.M <= 4)  return launch_small_with(decode_wide_kernel<1, 1>, kWideWaves, a, st);
-        else if (a.wide && a.M <= 16) return launch_small_with(decode_wide_kernel<1, 4>, kWideWaves, a, st);
-        else if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, false, true>, kSmWaves, a, st);
-        else if (a.M <= 16) return launch_small_with(decode_small_kernel<4, false, true>, kSmWaves, a, st);
-        else if (!a.wide)   return launch_small_with(decode_mid_kernel<false, true>, kSmWaves, a, st);
-        else return launch_small_with(decode_wide_kernel<2, 4>, kWideWaves, a, st);
+        if (a.wide && a.M <= 4)  return launch_small_with(decode_wide_kernel<1, 1, BF>, kWideWaves, a, st);
+        if (a.wide && a.M <= 16) return launch_small_with(decode_wide_kernel<1, 4, BF>, kWideWaves, a, st);
+        if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, BF, true>, kSmWaves, a, st);
+        if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF, true>, kSmWaves, a, st);
+        if (!a.wide)   return launch_small_with(decode_mid_kernel<BF, true>, kSmWaves, a, st);
+        return launch_small_with(decode_wide_kernel<2, 4, BF>, kWideWaves, a, st);
     }
     if (a.M <= 4)  return launch_small_with(decode_small_kernel<1, BF, false>, kSmWaves, a, st);
     if (a.M <= 16) return launch_small_with(decode_small_kernel<4, BF, false>, kSmWaves, a, st);
@@ -1240,7 +1241,7 @@ MORPH_TICK_EXPORTS(small_ticks)
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
 {
     if (a.M < 1 || a.M > 64 || a.S < 1 || a.S > 16 || a.S > a.K / kGroup || a.tiles < 1 || a.tiles > 65535 || a.K / kGroup > 65535) return hipErrorInvalidValue;
-    if (a.wide && (!a.native || a.bf)) return hipErrorInvalidValue;
+    if (a.wide && !a.native) return hipErrorInvalidValue;
     if (a.S > 1 && a.tiles * (a.M > 32 ? 2 : 1) > 256) return hipErrorInvalidValue;     // flags for 256 (tile, slice) pairs
     if (a.dense && a.native) return hipErrorInvalidValue;
     return a.bf ? launch_small_m<true>(a, st) : launch_small_m<false>(a, st);

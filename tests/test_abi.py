@@ -94,14 +94,14 @@ def test_native_order_entry_points_validation(L):
     assert L.morph_unpack_w4_native(None, FAKE, 128, 8, None) == 1 and L.morph_unpack_w4_native(FAKE, FAKE, 128, 12, None) == 2
     assert L.morph_dequantize_w4_native(FAKE, FAKE, FAKE, None, 0, 128, 8, 128, None) == 1
     assert L.morph_dequantize_w4_native(FAKE, FAKE, FAKE, FAKE, 7, 128, 8, 128, None) == 2
-    f = L.morph_linear_w4a16_native
-    def call(x=FAKE, q=FAKE, s=FAKE, z=FAKE, y=FAKE, M=4, K=256, N=64, g=128, ws=None, wsb=0):
-        return f(x, q, s, z, y, M, K, N, g, ws, wsb, None)
-    assert call(x=None) == 1 and call(q=None) == 1 and call(y=None) == 1
-    assert call(M=0) == 2 and call(K=200) == 2 and call(g=64) == 2
-    assert call(q=FAKE + 8) == 3
-    assert call(M=65) == 5 and call(M=2048) == 5                        # more than 64 rows: canonical records only
-    assert call(M=4, K=4096, N=4096) == 4                               # K is split: a workspace is needed
+    for f in (L.morph_linear_w4a16_native, L.morph_linear_w4a16_native_bf16):
+        def call(x=FAKE, q=FAKE, s=FAKE, z=FAKE, y=FAKE, M=4, K=256, N=64, g=128, ws=None, wsb=0):
+            return f(x, q, s, z, y, M, K, N, g, ws, wsb, None)
+        assert call(x=None) == 1 and call(q=None) == 1 and call(y=None) == 1
+        assert call(M=0) == 2 and call(K=200) == 2 and call(g=64) == 2
+        assert call(q=FAKE + 8) == 3
+        assert call(M=65) == 5 and call(M=2048) == 5                    # more than 64 rows: canonical records only
+        assert call(M=4, K=4096, N=4096) == 4                           # K is split: a workspace is needed
 
 
 def test_linear_w4a16_noalloc_validation(L):

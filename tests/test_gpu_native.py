@@ -165,17 +165,66 @@ def test_native_rejects_what_it_does_not_serve(B):
     assert e.value.status == 5                            # MORPH_ERR_UNSUPPORTED: more than 64 rows
 
 
-def test_stack_refuses_native_layers_with_bfloat16_activations(B):
-    """Only the fp16 decode kernels read the native order: the bfloat16 stack says so before any launch."""
-    hidden, inter, M = 128, 256, 4
-    st = B.LayerStack(hidden, inter, M, dtype=torch.bfloat16)
-    layer = {}
-    for name, (K, N) in (("qkv", (hidden, 3 * hidden)), ("o", (hidden, hidden)), ("gate_up", (hidden, 2 * inter)), ("down", (inter, hidden))):
-        layer[name] = ("w4n", torch.zeros(B.w4_native_bytes(K, N), dtype=torch.uint8, device="cuda"),
-                       torch.zeros((K // 128, N), dtype=torch.float16, device="cuda"),
-                       torch.zeros((K // 128, N // 8), dtype=torch.int32, device="cuda"))
-    st.add_layer(layer)
-    x = torch.zeros((M, hidden), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(B.MorphError) as e:
-        st.forward(x)
-    assert e.value.status == 5
+def dev_bf(bits):
+    """uint16 bit patterns -> bfloat16 tensor on the GPU (same bits)."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def host_bf(t):
+    return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+TOL_BF = 1e-2                                             # bfloat16 outputs: 8 bits of mantissa
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 128, 8), (1, 4096, 4096), (3, 384, 264), (4, 4096, 520), (8, 256, 2048), (12, 1792, 520),
+                                   (16, 1024, 1032), (17, 512, 1024), (32, 11008, 512), (33, 640, 776), (49, 1280, 264), (64, 768, 1288)])
+def test_bfloat16_activations_on_native_codes(B, oracle, M, K, N):
+    """morph_linear_w4a16_native_bf16 against the oracle's bfloat16 linear, and against the canonical bfloat16 entry
+    point: the same bits wherever both share K out the same way (beyond 16 rows, and up to 16 through the four-wave
+    kernels that tuning key 12 = 4 selects)."""
+    W = synth.weights(79, K, N, layer_id=M)
+    xb = oracle.fp32_to_bf16(synth.activations(79, M, K, layer_id=M + 2).astype(np.float32))
+    qw, sc, qz = oracle.quantize_w4(W)
+    nat = B.repack_w4_native(dev(qw))
+    ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
+    y = host_bf(B.linear_w4a16_native_bf16(dev_bf(xb), nat, dev(sc), dev(qz), ws))
+    torch.cuda.synchronize()
+    r = oracle.error_metric(oracle.bf16_to_fp32(y).astype(np.float64), oracle.linear_q_bf16(4, xb, qw, sc, qz))
+    say(f"  native bf16 M={M} K={K} N={N}: err={r['err']:.3e}")
+    assert r["finite"] and r["err"] <= TOL_BF, r
+    if M <= 16:
+        B.set_tuning(B.TUNE_SMALL, 4)
+        try:
+            y = host_bf(B.linear_w4a16_native_bf16(dev_bf(xb), nat, dev(sc), dev(qz), ws))
+            torch.cuda.synchronize()
+        finally:
+            B.set_tuning(B.TUNE_SMALL, 0)
+    y_canon = host_bf(B.linear_w4a16_bf16(dev_bf(xb), dev(qw), dev(sc), dev(qz), ws))
+    assert np.array_equal(y, y_canon)
+
+
+@pytest.mark.parametrize("M", [4, 32])
+def test_bfloat16_stack_takes_native_layers(B, oracle, M):
+    """A bfloat16 stack with its 4-bit layers in the native order: the same bytes out as with canonical records
+    (M = 32: the eight-wave kernel halves K as the four-wave one does; M = 4: the four-wave kernels on both sides)."""
+    hidden, inter = 256, 512
+    outs = []
+    B.set_tuning(B.TUNE_SMALL, 4 if M <= 16 else 0)
+    try:
+        for order in ("w4", "w4n"):
+            st = B.LayerStack(hidden, inter, M, dtype=torch.bfloat16)
+            for l in range(2):
+                layer = {}
+                for name, (K, N) in (("qkv", (hidden, 3 * hidden)), ("o", (hidden, hidden)), ("gate_up", (hidden, 2 * inter)), ("down", (inter, hidden))):
+                    qw, sc, qz = oracle.quantize_w4(synth.weights(80, K, N, layer_id=l, tensor_id=synth._TENSOR_ID[name]))
+                    codes = dev(qw) if order == "w4" else B.repack_w4_native(dev(qw))
+                    layer[name] = (order, codes, dev(sc), dev(qz))
+                st.add_layer(layer)
+            x = dev_bf(oracle.fp32_to_bf16(synth.activations(80, M, hidden, layer_id=7).astype(np.float32))).clone()
+            outs.append(host_bf(st.forward(x)))
+            torch.cuda.synchronize()
+    finally:
+        B.set_tuning(B.TUNE_SMALL, 0)
+    assert np.all(np.isfinite(oracle.bf16_to_fp32(outs[0])))
+    assert np.array_equal(outs[0], outs[1])
