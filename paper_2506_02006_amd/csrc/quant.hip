@@ -6,6 +6,19 @@
 
 namespace morph {
 
+// rintf(v / s) with the division correctly rounded (what the format prescribes), without dividing: t = v * r,
+// r within an ulp of 1 / s, lies within 3e-7 |t| of the quotient and of its rounded value, so all three
+// round to the same integer unless t comes within a hair of a half-integer -- there, and for |t| so large
+// that every float is an integer (far beyond the clamp that follows), the division is carried out.
+__device__ __forceinline__ int quotient_rint(float v, float s, float r)
+{
+    const float t = v * r;
+    const float n = rintf(t);
+    const float d = __builtin_fabsf(t - n);               // distance to the nearest integer, at most 0.5
+    if (__builtin_expect(0.5f - d < 1e-4f * __builtin_fmaxf(1.0f, __builtin_fabsf(t)), 0)) return (int)rintf(__fdiv_rn(v, s));
+    return (int)n;                                        // (infinite t: the conversion saturates, as that of the quotient would)
+}
+
 // One workgroup owns one 128-row group of kQC consecutive columns.  The tile is read from memory
 // once, in 256-byte (fp32) or 128-byte (fp16) runs per row, and parked in LDS as fp32; the
 // column ranges, the scales and zero points and finally the codes are all computed from there.
@@ -113,10 +126,10 @@ __global__ __launch_bounds__(256) void quantize_kernel(const WT* __restrict__ w,
     {
         constexpr int WPR = kQC / 8;                        // 8-column units per row of the tile
         const int cw = tid & (WPR - 1);
-        float sf[8];
+        float sf[8], rf[8];
         int   z[8];
 #pragma unroll
-        for (int j = 0; j < 8; j++) { sf[j] = sfl[8 * cw + j]; z[j] = zl[8 * cw + j]; }
+        for (int j = 0; j < 8; j++) { sf[j] = sfl[8 * cw + j]; rf[j] = __builtin_amdgcn_rcpf(sf[j]); z[j] = zl[8 * cw + j]; }
         if (n0 + 8 * cw < N) {
 #pragma unroll 4
             for (int i = 0; i < kGroup * WPR / 256; i++) {
@@ -127,7 +140,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const WT* __restrict__ w,
                 uint32_t word[8 / CPW] = {};
 #pragma unroll
                 for (int j = 0; j < 8; j++) {
-                    int q = (int)rintf(__fdiv_rn(v[j], sf[j])) + z[j];
+                    int q = quotient_rint(v[j], sf[j], rf[j]) + z[j];
                     q     = q < 0 ? 0 : (q > kLevels ? kLevels : q);
                     word[j / CPW] |= (uint32_t)q << (BITS * (j % CPW));
                 }
