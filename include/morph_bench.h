@@ -57,6 +57,15 @@ int morph_copy(const void* src, void* dst, size_t bytes, void* stream);
  *   morph_probe_mfma: every wave issues iters x 4 independent 32x32x16 fp16 MFMAs on registers;
  *     *flop (host, may be NULL) receives the flop of the launch: flop over the launch time is the rate
  *     the matrix cores sustain with nothing else in the way (1 <= iters <= 2^24). */
+/* How a launch of at most 64 rows would be laid out on the device (host only, launches nothing):
+ * plan[0] = 1 when the register-tiled kernels of decode_small.hip take it (else the rest is 0), plan[1] =
+ * column tiles of 256, plan[2] = workgroups sharing the K range of a tile, plan[3] = slices of rows,
+ * plan[4] = 1 for the eight-wave kernel.  kind as in morph.h (MORPH_KIND_W4A16_NATIVE for the native code
+ * order).  The workgroups of a tile wait for each other, so the layout must fit the device at once:
+ * tiles * splits * slices workgroups on its compute units, and ceil(tiles / 8) * splits * slices on the
+ * compute units of one XCD (the tests check this over a sweep of shapes). */
+int morph_plan_decode(int kind, int M, int K, int N, int* plan);
+
 size_t morph_probe_out_bytes(void);
 int morph_probe_read(const void* src, size_t bytes, void* out, size_t out_bytes, void* stream);
 int morph_probe_mfma(int iters, void* out, size_t out_bytes, double* flop, void* stream);

@@ -38,6 +38,7 @@ EXPORTS = [
     "morph_linear_w4a16_noalloc", "morph_noalloc_scratch_bytes",
     "morph_w4_native_bytes", "morph_repack_w4_native", "morph_unpack_w4_native", "morph_quantize_layer_native",
     "morph_dequantize_w4_native", "morph_linear_w4a16_native", "morph_linear_w4a16_native_bf16",
+    "morph_plan_decode",
 ]
 
 

@@ -761,6 +761,20 @@ int morph_warmup(void* dummy, size_t dummy_bytes, void* stream)
     return MORPH_OK;
 }
 
+int morph_plan_decode(int kind, int M, int K, int N, int* plan)
+{
+    if (!plan) return MORPH_ERR_NULL;
+    if (!known_kind(kind)) return MORPH_ERR_SHAPE;
+    if (int rc = check_shape(M, K, N)) return rc;
+    for (int i = 0; i < 5; i++) plan[i] = 0;
+    const int native = kind == MORPH_KIND_W4A16_NATIVE;
+    if (M > 64 || !takes_stream(plan_kind(kind), M, K, N)) return MORPH_OK;
+    const DecodePlan pl = plan_decode(plan_kind(kind), M, K, N, native);
+    if (!pl.small) return MORPH_OK;
+    plan[0] = 1; plan[1] = pl.tiles; plan[2] = pl.S; plan[3] = pl.slices; plan[4] = pl.wide;
+    return MORPH_OK;
+}
+
 const char* morph_status_string(int status)
 {
     switch (status) {

@@ -381,6 +381,12 @@ static DecodePlan plan_small(int q, int M, int K, int N, int native)
     // `most`: every workgroup keeps a quantization group (decode_small_kernel), or each half of its waves one
     auto split_for = [&](int most) {
         int S = target / (pl.tiles * slices);
+        // ... and never more on one XCD than it has compute units: the workgroups of a tile share an XCD, tile t goes to
+        // XCD t % 8, so an XCD runs ceil(tiles / 8) tiles (20 tiles of a 5120-wide matrix: 3, not 2.5 -- with 12 splits
+        // that made 36 workgroups for 32 compute units, and the four that had to wait for a free one found the others
+        // gone, waited the bound out and recomputed everything: 49 us instead of 7)
+        const int per_xcd = (target / 8) / (((pl.tiles + 7) / 8) * slices);
+        if (S > per_xcd) S = per_xcd;
         if (S > most) S = most;
         if (S > 16) S = 16;
         const int forced = tuning_get(TUNE_DECODE_SPLIT);

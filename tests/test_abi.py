@@ -280,3 +280,27 @@ def test_cosine_rows_validation(L, fname):
     assert f(FAKE, FAKE, FAKE, None, 0, 64, None) == 2 and f(FAKE, FAKE, FAKE, None, 4, 60, None) == 2
     assert f(FAKE + 8, FAKE, FAKE, None, 4, 64, None) == 3 and f(FAKE, FAKE, FAKE + 2, None, 4, 64, None) == 3
     assert f(FAKE, FAKE, FAKE, FAKE + 1, 4, 64, None) == 3
+
+
+def test_decode_layout_fits_the_device_at_once(L):
+    """The workgroups that share a column tile wait for each other, and tile t runs on XCD t % 8: whatever the shape,
+    the planner's layout must fit the 256 compute units at once and, XCD by XCD, the 32 of each -- 20 tiles (a
+    5120-wide matrix) are three per XCD, not two and a half.  (A layout that does not fit still gives the right
+    result, six to eight times slower: measured 49 us instead of 7 on a 5120 x 5120 matrix before this was checked.)"""
+    plan = (ctypes.c_int * 5)()
+    assert L.morph_plan_decode(1, 1, 4096, 4096, None) == 1
+    seen = 0
+    for kind in (0, 1, 3):                                  # fp16, W4A16, W4A16 in native order
+        for M in (1, 4, 8, 16, 17, 32, 33, 64):
+            for K in (128, 1024, 4096, 5120, 11008, 14336):
+                for N in list(range(8, 8200, 248)) + [4096, 5120, 6144, 12288, 13824, 15360, 22016, 27648, 28672]:
+                    assert L.morph_plan_decode(kind, M, K, N, plan) == 0, (kind, M, K, N)
+                    small, tiles, S, slices, wide = list(plan)
+                    if not small:
+                        continue
+                    seen += 1
+                    assert tiles == (N + 255) // 256 and S >= 1 and slices == (2 if M > 32 else 1)
+                    if S > 1:
+                        assert tiles * S * slices <= 256, (kind, M, K, N, list(plan))
+                        assert ((tiles + 7) // 8) * S * slices <= 32, (kind, M, K, N, list(plan))
+    assert seen > 3000
