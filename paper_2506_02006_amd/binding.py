@@ -575,6 +575,36 @@ def layer_record_views(kind: int, buf: torch.Tensor, hidden: int, inter: int) ->
     return out
 
 
+def _stream_beside(compute, device="cuda", tries: int = 4):
+    """A new stream (default priority) whose host-to-device copies run beside the kernels of `compute`.
+    The runtime deals streams out over a few hardware queues, and a copy stream that lands on the compute
+    stream's queue runs its copies behind the kernels queued there instead of beside them (a swap then costs
+    its whole copy time in decode time).  Which queue a stream got cannot be asked, so each candidate is tried:
+    a few milliseconds of kernels on `compute`, a small copy on the candidate, and the candidate is taken if its
+    copy is done while the kernels are still running.  Falls back to the last candidate."""
+    src = torch.empty(64 << 20, dtype=torch.uint8, device=device)
+    dst = torch.empty_like(src)
+    small_h = torch.empty(1 << 20, dtype=torch.uint8, pin_memory=True)
+    small_d = torch.empty(1 << 20, dtype=torch.uint8, device=device)
+    cand = None
+    for _ in range(tries):
+        cand = torch.cuda.Stream(device=device)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(compute):
+            for _ in range(40):
+                _check(lib().morph_copy(src.data_ptr(), dst.data_ptr(), src.numel(), compute.cuda_stream), "morph_copy")
+            done = torch.cuda.Event()
+            done.record(compute)
+        with torch.cuda.stream(cand):
+            small_d.copy_(small_h, non_blocking=True)
+        cand.synchronize()
+        beside = not done.query()
+        torch.cuda.synchronize()
+        if beside:
+            break
+    return cand
+
+
 class SwapStack:
     """A stack of layers that live in fixed device slots and change precision in place while the
     stack keeps decoding: every layer has a slot sized for its fp16 record and pinned host records
@@ -591,7 +621,7 @@ class SwapStack:
         self.kinds = [None] * n_layers
         self.host = [dict() for _ in range(n_layers)]          # kind -> pinned uint8 tensor (may be shared between layers)
         self.desc = (LayerDesc * n_layers)()
-        self.copy_stream = torch.cuda.Stream(device=device)     # default priority
+        self.copy_stream = _stream_beside(torch.cuda.current_stream(), device)   # default priority
         self.scratch = torch.empty(int(lib().morph_stack_scratch_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
         self.tap = torch.empty(int(lib().morph_stack_tap_bytes(M, hidden, inter)), dtype=torch.uint8, device=device)
         need = 0
