@@ -451,17 +451,18 @@ def main():
         # ---- layers changing precision in place while the 32-layer stack decodes (M = 32) ----
         if "swap" in sections:
             Ls, h7, i7 = 32, 4096, 11008
+            KW4 = B.KIND_W4A16_NATIVE                       # the 4-bit records hold their codes in the native order (the faster decode)
             sst = B.SwapStack(h7, i7, M5, Ls)
             # two distinct layers' records in pinned host memory, shared by the layers in turn
             host_recs = []
             for j in range(2):
                 lay16 = {name: make_fp16(*shapes7[name]) for name in order}
                 recs = {}
-                for kind in (B.KIND_FP16, B.KIND_W4A16):
+                for kind in (B.KIND_FP16, KW4):
                     rec = sst.new_host_record(kind)
                     views = B.layer_record_views(kind, rec, h7, i7)
                     for name in order:
-                        src = (lay16[name],) if kind == B.KIND_FP16 else B.quantize_layer(lay16[name])
+                        src = (lay16[name],) if kind == B.KIND_FP16 else B.quantize_layer_native(lay16[name])
                         for dst, a in zip(views[name][1:], src):
                             dst.copy_(a)
                     recs[kind] = rec
@@ -469,11 +470,11 @@ def main():
                 del lay16
             torch.cuda.synchronize()
             for l in range(Ls):
-                for kind in (B.KIND_FP16, B.KIND_W4A16):
+                for kind in (B.KIND_FP16, KW4):
                     sst.set_host_record(l, kind, host_recs[l % 2][kind])
                 sst.load(l, B.KIND_FP16)
             xs5 = rand_x(M5, h7)
-            rec_bytes = {kind: B.layer_record_bytes(kind, h7, i7) for kind in (B.KIND_FP16, B.KIND_W4A16)}
+            rec_bytes = {kind: B.layer_record_bytes(kind, h7, i7) for kind in (B.KIND_FP16, KW4)}
 
             def copy_alone(kind, layer):
                 # the copy by itself, nothing else running (layer is left in `kind`)
@@ -488,7 +489,7 @@ def main():
                 sst._adopt(layer, kind)
                 return e0.elapsed_time(e1)
 
-            ms_w4 = min(copy_alone(B.KIND_W4A16, 31) for _ in range(3))
+            ms_w4 = min(copy_alone(KW4, 31) for _ in range(3))
             ms_16 = min(copy_alone(B.KIND_FP16, 31) for _ in range(3))
             # steps without a swap (all fp16, launched eagerly as the swapping path has to be)
             quiet = timed(lambda i: sst.step(xs5), 16, 3) / 16
@@ -498,7 +499,7 @@ def main():
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for l in range(Ls - 1, -1, -1):
-                sst.swap(l, B.KIND_W4A16)
+                sst.swap(l, KW4)
                 sst.step(xs5, timing=True)
             sst.step(xs5)                                 # adopts the last one
             e1.record()
@@ -522,9 +523,10 @@ def main():
             # step t is t layers in W4, so the no-copy cost is the mean of the two quiet figures
             expect_ms = 33 * 0.5 * (quiet + quiet4) * 1e3
             detail["swap_llama7b_M32"] = {
-                "w4_record_MB": round(rec_bytes[B.KIND_W4A16] / 1e6, 1), "fp16_record_MB": round(rec_bytes[B.KIND_FP16] / 1e6, 1),
+                "w4_code_order": "native",
+                "w4_record_MB": round(rec_bytes[KW4] / 1e6, 1), "fp16_record_MB": round(rec_bytes[B.KIND_FP16] / 1e6, 1),
                 "copy_alone_ms": {"w4": round(ms_w4, 3), "fp16": round(ms_16, 3)},
-                "copy_alone_GBps": {"w4": round(rec_bytes[B.KIND_W4A16] / ms_w4 / 1e6, 1),
+                "copy_alone_GBps": {"w4": round(rec_bytes[KW4] / ms_w4 / 1e6, 1),
                                     "fp16": round(rec_bytes[B.KIND_FP16] / ms_16 / 1e6, 1)},
                 "copy_under_decode_ms": {"w4_mean": round(sum(under) / len(under), 3), "w4_max": round(max(under), 3)},
                 "step_ms_all_fp16_eager": round(quiet * 1e3, 4), "step_ms_all_w4_eager": round(quiet4 * 1e3, 4),
