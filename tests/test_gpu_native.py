@@ -165,6 +165,35 @@ def test_native_rejects_what_it_does_not_serve(B):
     assert e.value.status == 5                            # MORPH_ERR_UNSUPPORTED: more than 64 rows
 
 
+@pytest.mark.parametrize("how", ["nobody_waits", "through_memory"])
+@pytest.mark.parametrize("M", [1, 4, 8, 12, 16, 24, 32, 48, 64])
+def test_hand_over_paths_on_native_codes(B, oracle, how, M):
+    """The kernels that read the native order share the hand-over of the others: with the bound of the wait set to
+    zero from the host every workgroup works out the other splits of its share itself (the k loop entered a second
+    time), and with tuning key 13 the partial sums travel through memory instead of one XCD's L2.  Either way the
+    same bits as the ordinary launch, and within the oracle's tolerance."""
+    for (K, N) in ((1792, 520), (4096, 264), (2048, 1288)):
+        W = synth.weights(81, K, N, layer_id=M)
+        x = synth.activations(81, M, K, layer_id=M + 3)
+        qw, sc, qz = oracle.quantize_w4(W)
+        nat = B.repack_w4_native(dev(qw))
+        ws = B.new_workspace(B.workspace_bytes(B.KIND_W4A16, M, K, N))
+        y0 = host(B.linear_w4a16_native(dev(x), nat, dev(sc), dev(qz), ws))
+        torch.cuda.synchronize()
+        key, val = (B.TUNE_DECODE_SCATTER, 3) if how == "nobody_waits" else (B.TUNE_SMALL_FAR, 1)
+        B.set_tuning(key, val)
+        try:
+            y1 = host(B.linear_w4a16_native(dev(x), nat, dev(sc), dev(qz), ws))
+            y2 = host(B.linear_w4a16_native(dev(x), nat, dev(sc), dev(qz), ws))      # and again on the same workspace
+            torch.cuda.synchronize()
+        finally:
+            B.set_tuning(key, 0)
+        r = oracle.error_metric(y1, oracle.linear_w4a16(x, qw, sc, qz))
+        say(f"  native {how} M={M} K={K} N={N}: err={r['err']:.3e}")
+        assert r["finite"] and r["err"] <= TOL, r
+        assert np.array_equal(y0.view(np.uint16), y1.view(np.uint16)) and np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+
+
 def dev_bf(bits):
     """uint16 bit patterns -> bfloat16 tensor on the GPU (same bits)."""
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
