@@ -158,7 +158,7 @@ def main():
     avg_launch_s = sec / (args.steps * launches_per_step)
     roofline = {
         "bound": "hbm",
-        "kernel": "W4A16 decode on the codes in native order, mean over the 12 launches of a step: decode_small_kernel<1, false, true> (qkv, gate_up at M = 1 and 4), decode_wide_kernel<1, 1> (o, down at M = 1 and 4), decode_wide_kernel<1, 4> (M = 16)",
+        "kernel": "W4A16 decode on the codes in native order, mean over the 12 launches of a step: decode_small_kernel<1, false, true> (qkv, gate_up at M = 1 and 4), decode_wide_kernel<1, 1, false> (o, down at M = 1 and 4), decode_wide_kernel<1, 4, false> (M = 16)",
         "achieved": round(value, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
