@@ -393,6 +393,17 @@ def main():
                     d8[f"w4a16_native/{name}/M{M}"] = per_linear(B.KIND_W4A16_NATIVE, "llama3_8b", name, M, recs, reps=2 * len(recs))
                 del recs
             detail["config3_llama3_8b"] = d8
+            # the 13B shapes at decode sizes too (configuration 4 itself is the prefill chunk below): 5120-wide matrices
+            # are 20 column tiles, three to an XCD, which the planner has to count with
+            shapes13d = synth.LAYER_SHAPES["llama13b"]
+            d13d = {}
+            for name in order:
+                recs = cold_pool(B.KIND_W4A16, *shapes13d[name])
+                recs = [(B.repack_w4_native(r[0]), r[1], r[2]) for r in recs]
+                for M in (1, 16):
+                    d13d[f"w4a16_native/{name}/M{M}"] = per_linear(B.KIND_W4A16_NATIVE, "llama13b", name, M, recs, reps=2 * len(recs))
+                del recs
+            detail["decode_llama13b"] = d13d
 
         # ---- config 4: 13B prefill chunk ----
         shapes13 = synth.LAYER_SHAPES["llama13b"]
