@@ -55,7 +55,7 @@ def bits_of(t):
 
 SHAPES = [("o7", 4096, 4096), ("down7", 11008, 4096), ("o13", 5120, 5120)]
 ROWS = [1, 4, 16, 32, 48, 64, 200, 256, 512, 1024]
-KINDS = ["w4", "fp16", "w8", "w4_bf16", "bf16"]
+KINDS = ["w4", "fp16", "w8", "w4_bf16", "bf16", "w4n", "w4n_bf16"]      # w4n: the 4-bit codes in the native order (at most 64 rows)
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -65,18 +65,21 @@ def test_same_bits_on_every_call(B, oracle, kind, shape):
     bf = kind.endswith("bf16")
     base = kind.split("_")[0]
     W = synth.weights(91, K, N, layer_id=SHAPES.index(shape))
-    rows = ROWS if kind in ("w4", "fp16") else [4, 32, 64, 256, 512]
+    rows = ROWS if kind in ("w4", "fp16") else [1, 4, 8, 16, 32, 48, 64] if base == "w4n" else [4, 32, 64, 256, 512]
     if base in ("fp16", "bf16"):
         wq = oracle.fp32_to_bf16(W) if bf else W.astype(np.float16)
         wd = (dev_bf(wq) if bf else dev(wq),)
         k = B.KIND_FP16
     else:
-        bits = 4 if base == "w4" else 8
+        bits = 4 if base in ("w4", "w4n") else 8
         rec = oracle.quantize_w4(W) if bits == 4 else oracle.quantize_w8(W)
         wd = tuple(dev(r) for r in rec)
+        if base == "w4n":
+            wd = (B.repack_w4_native(wd[0]),) + wd[1:]
         k = B.KIND_W4A16 if bits == 4 else B.KIND_W8A16
     fn = {("fp16", False): B.linear_fp16, ("bf16", True): B.linear_bf16, ("w4", False): B.linear_w4a16,
-          ("w4", True): B.linear_w4a16_bf16, ("w8", False): B.linear_w8a16, ("w8", True): B.linear_w8a16_bf16}[(base, bf)]
+          ("w4", True): B.linear_w4a16_bf16, ("w8", False): B.linear_w8a16, ("w8", True): B.linear_w8a16_bf16,
+          ("w4n", False): B.linear_w4a16_native, ("w4n", True): B.linear_w4a16_native_bf16}[(base, bf)]
     filler_src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     filler_dst = torch.empty_like(filler_src)
     for M in rows:
