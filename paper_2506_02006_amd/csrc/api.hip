@@ -117,7 +117,7 @@ int run_linear(int kind, const void* x, const void* w, const void* scales, const
         if (pl.small) {
             SmallArgs s;
             s.x = x; s.w = w; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
-            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf; s.native = native; s.dense = kind == MORPH_KIND_FP16; s.wide = pl.wide;
+            s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = tuning_get(TUNE_SMALL_DEPTH) == 1; s.bf = bf; s.native = native; s.dense = kind == MORPH_KIND_FP16; s.wide = pl.wide; s.w8 = kind == MORPH_KIND_W8A16;
             s.slots = nullptr; s.ctl = nullptr;
             if (pl.S > 1) {
                 if (!workspace || workspace_bytes < kScratchOffset) return MORPH_ERR_WORKSPACE;
@@ -225,7 +225,7 @@ int morph_linear_w4a16_noalloc(const void* x, const int32_t* qweight, const void
     if (pl.S > 1 && (pl.partial_bytes > kNoAllocSlotBytes || pl.tiles > 256)) return MORPH_ERR_UNSUPPORTED;   // beyond the array
     SmallArgs s;
     s.x = x; s.w = qweight; s.scales = scales; s.qzeros = qzeros; s.y = y; s.M = M; s.K = K; s.N = N;
-    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = 0; s.bf = 0; s.native = 0; s.dense = 0; s.wide = 0;
+    s.S = pl.S; s.tiles = pl.tiles; s.polls = pl.polls; s.far = 0; s.bf = 0; s.native = 0; s.dense = 0; s.wide = 0; s.w8 = 0;
     s.slots = nullptr; s.ctl = nullptr;
     if (pl.S > 1) {
         unsigned char* p = scratch_on_current_device();

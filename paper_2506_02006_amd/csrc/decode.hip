@@ -369,8 +369,8 @@ static DecodePlan plan_small(int q, int M, int K, int N, int native)
     pl.small  = 1;
     pl.rows   = 16;
     pl.slices = 1;
-    pl.tile_n = 256;
-    pl.tiles  = (N + 255) / 256;
+    pl.tile_n = q == 2 ? 128 : 256;                      // 8-bit codes: a wave's 8 bytes per row are 8 columns
+    pl.tiles  = (N + pl.tile_n - 1) / pl.tile_n;
     const int T = K / 32;
     // Never more workgroups than compute units: the workgroups of a tile wait for each other's partial
     // sums, which is quick only while all of them run at the same time (one per compute unit: the kernel
@@ -395,7 +395,7 @@ static DecodePlan plan_small(int q, int M, int K, int N, int native)
         return S < 1 ? 1 : S;
     };
     const int halves = T / 8 > 0 ? T / 8 : 1;
-    int S = split_for((M <= 16 && q == 1) ? T / 4 : halves);
+    int S = split_for((M <= 16 && q != 0) ? T / 4 : halves);
     // The native code order has the eight-wave kernel (decode_wide_kernel) from 9 to 32 rows, and below nine rows where a
     // workgroup is left with few groups to walk, which eight waves share out better than four (measured on the 7B shapes
     // at M = 1 and 4: o-proj, 2 groups per workgroup, 5.7 -> 5.4 us, down, 5.4 groups, 8.1 -> 7.7; qkv, 6.4 groups, 8.0 -> 8.4,
@@ -407,7 +407,7 @@ static DecodePlan plan_small(int q, int M, int K, int N, int native)
     }
     pl.S = S;
     // vectors of four rows per tile: up to 16 rows only the groups of four that exist, beyond whole tiles of 16 rows
-    const size_t nvec = M <= 16 ? (size_t)256 * ((M + 3) / 4) : (size_t)2048;
+    const size_t nvec = M <= 16 ? (size_t)pl.tile_n * ((M + 3) / 4) : (size_t)2048;
     pl.wide = wide;
     pl.slices = slices;
     pl.partial_bytes = S > 1 ? (size_t)pl.tiles * slices * S * nvec * 16 : 0;
@@ -425,7 +425,7 @@ DecodePlan plan_decode(int q, int M, int K, int N, int native)
 {
     const int t = tuning_get(TUNE_DECODE_SLICE);        // a forced slice height means the general streaming kernels
     const int small_rows = tuning_get(TUNE_SMALL) == 3 ? 16 : 64;       // 3: the register-tiled kernel only up to 16 rows
-    if ((q == 0 || q == 1) && M <= small_rows && tuning_get(TUNE_SMALL) != 2 && t != 16 && t != 32) {
+    if ((q == 0 || q == 1 || (q == 2 && M <= 16)) && M <= small_rows && tuning_get(TUNE_SMALL) != 2 && t != 16 && t != 32) {
         const DecodePlan ps = plan_small(q, M, K, N, native);
         // (tile and group counts travel in 16 bits each)
         if (ps.partial_bytes <= kSlotBytes && (ps.S == 1 || ps.tiles * ps.slices <= 256) && ps.tiles <= 65535 && K / kGroup <= 65535) return ps;

@@ -508,6 +508,195 @@ __global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
+// 8-bit codes, M <= 16: the skeleton of decode_small_kernel on the canonical record of the 8-bit
+// variant (four codes per word along N).  A lane keeps 8 columns = two words per row, a wave 128
+// columns (the tile), and loads the same 8 bytes from 8 consecutive rows; the byte of rows 2 q and
+// 2 q + 1 paired in one word IS the B operand (the code times 2^-24, or 2^-133 read as bfloat16): one
+// MFMA per column and k-step, one more for the row sums of x, and per group
+//     Y += s * acc - (s * z) * xsum,
+// the power of two taken out at the end.  One set of group sums: the fold is two instructions per
+// result and group.  Same division of K over workgroups and waves, same hand-over.  (A variant with 16
+// columns per lane, 16-byte loads and tiles of 256 measured the same on the large matrices and 7 to 10 %
+// slower on the 4096-wide ones: half the tiles, twice the splits.)
+// ------------------------------------------------------------------------------------------------
+struct Small8Group {
+    u32x2 zq;                                    // zero points of the lane's 8 columns, a byte each
+    u32x4 sc;                                    // their scales
+};
+
+template <int RL, bool BF>
+__global__ __launch_bounds__(kSmWaves * 64, 1) void decode_small8_kernel(
+    const uint32_t* w, const void* x, const void* scales, const uint32_t* qzeros, int K, int N, int ms, int qr,
+    int tiles_sl, int inv_s, SmallTail t)
+{
+    const int M = ms & 0xFFFF, S = ms >> 16, q_groups = qr & 0xFFFF, r_groups = qr >> 16;
+    // after the k loop: [wave][lane][column j of the lane, stored at j ^ (lane & 7)]
+    __shared__ __align__(16) f32x4 yl[kSmWaves * 64 * 8];
+    __shared__ uint32_t fresh_word;
+
+    MORPH_TICK(0);                                       // kernel entry
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, b = lane >> 4;
+    const int tiles = tiles_sl & 0xFFFF;
+    const Place p = place_of(tiles_sl, inv_s, S);
+    if (p.tile >= tiles) return;
+    const int n0 = p.tile * 128;
+
+    const uint32_t row_bytes = (uint32_t)N;              // a byte per code
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(w, (uint32_t)K * row_bytes);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)M * (uint32_t)K * 2u);
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(scales, (uint32_t)(K / kGroup) * (uint32_t)N * 2u);
+    const __amdgpu_buffer_rsrc_t rz = make_rsrc(qzeros, (uint32_t)(K / kGroup) * row_bytes);
+
+    const int  ncol   = n0 + 8 * c;                      // this lane's first column
+    const bool col_ok = ncol < N;
+    const uint32_t kOut = 0xFFFFFFF0u;
+    const uint32_t voff_w = col_ok ? (uint32_t)(8 * b) * row_bytes + (uint32_t)ncol : kOut;
+    const uint32_t voff_s = col_ok ? (uint32_t)ncol * 2u : kOut;
+    const uint32_t voff_z = col_ok ? (uint32_t)ncol : kOut;
+    // the x row this lane feeds to the MFMA as its row c; rows at or beyond M lie past the buffer
+    const uint32_t voff_a = RL == 1 ? ((c & 3) ? kOut : ((uint32_t)(c >> 2) * (uint32_t)K + 8u * b) * 2u)
+                                    : ((uint32_t)c * (uint32_t)K + 8u * b) * 2u;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+    int         ga = 0, gz = 0, ks1 = 0;
+    SmallStage  st[kRing];
+    Small8Group gnxt;
+    auto load_stage = [&](SmallStage& sg, int ks) {
+        const bool     dead = ks >= ks1;
+        const uint32_t so   = dead ? 0u : (uint32_t)ks * 32u * row_bytes;
+        const uint32_t vw   = voff_w | (dead ? kOut : 0u);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {                    // row 8 b + i of the k-step: words (2 i, 2 i + 1) of the stage
+            const u32x2 v = buf_load_u32x2<kAuxStream>(rw, vw, so + (uint32_t)i * row_bytes);
+            sg.w[i >> 1][2 * (i & 1)] = v[0];
+            sg.w[i >> 1][2 * (i & 1) + 1] = v[1];
+        }
+        sg.a = bit_cast<half8_t>(__builtin_amdgcn_raw_buffer_load_b128(rx, voff_a | (dead ? kOut : 0u), dead ? 0u : (uint32_t)ks * 64u, 0));
+    };
+    auto load_group = [&](Small8Group& gr, int g) {
+        const bool     dead = g >= gz;
+        const uint32_t gm   = dead ? kOut : 0u;
+        const uint32_t gg   = dead ? 0u : (uint32_t)g;
+        gr.zq = buf_load_u32x2(rz, voff_z | gm, gg * row_bytes);
+        gr.sc = buf_load_u32x4(rs, voff_s | gm, gg * (uint32_t)N * 2u);
+    };
+    auto begin_pass = [&](int split) {
+        const int gb = split * q_groups + (split < r_groups ? split : r_groups);
+        const int ng = q_groups + (split < r_groups ? 1 : 0);
+        ga = gb + ((wave * ng) >> 2);
+        gz = gb + (((wave + 1) * ng) >> 2);
+        ks1 = 4 * gz;
+        load_group(gnxt, ga);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kAhead; i++) {
+            load_stage(st[i], 4 * ga + i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    begin_pass(p.sp);
+    const uint32_t base = flags_as_found(t, S, p, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    MORPH_TICK(1);                                       // first loads issued
+
+    // A vector = four rows of one column.  Vector (ln, j): column n0 + 8 (ln & 15) + j, rows 4 (ln >> 4) ..;
+    // its number is id = 8 ln + j, so that 128 consecutive numbers are the tile's 128 columns.
+    const int nvec = 128 * t.nb;
+    auto vec_sum = [&](int id) {                         // over the waves in the order of their k ranges
+        const int ln = id >> 3, j = (id ^ ln) & 7;
+        f32x4 a = yl[ln * 8 + j];
+#pragma unroll
+        for (int q = 1; q < kSmWaves; q++) a += yl[(q * 64 + ln) * 8 + j];
+        return a;
+    };
+    uint16_t* y = (uint16_t*)t.y;
+    auto vec_store_y = [&](int id, f32x4 acc) {
+        const int ln = id >> 3, j = id & 7;
+        const int col = n0 + 8 * (ln & 15) + j, row = 4 * (ln >> 4);
+        if (col < N) {
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (row + r < M) y[(size_t)(row + r) * N + col] = narrow16<BF>(acc[r]);
+        }
+    };
+
+    auto run_pass = [&](auto&& sink) {
+        f32x4 gacc[8], xs = zero4;                       // sums over the open group: x * code of column j; row sums of x
+        float yr[8][RL];                                 // running results, column j of the lane, row 4 b + r (RL = 1: row b)
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            gacc[j] = zero4;
+#pragma unroll
+            for (int r = 0; r < RL; r++) yr[j][r] = 0.f;
+        }
+        for (int g = ga; g < gz; g++) {
+            const Small8Group gs = gnxt;
+#pragma unroll
+            for (int u = 0; u < kRing; u++) {
+                load_stage(st[(u + kAhead) % kRing], 4 * g + u + kAhead);
+                if (u == 1) load_group(gnxt, g + 1);     // arrives well before the next group ends
+                __builtin_amdgcn_sched_barrier(0);
+                const SmallStage& sg = st[u];
+                const bool first = u == 0;
+                half8_t xa;
+                if constexpr (BF) xa = bf16x8_up64(sg.a);
+                else xa = sg.a;
+                const half8_t tiny = bit_cast<half8_t>(u32x4{0x00010001u, 0x00010001u, 0x00010001u, 0x00010001u});   // the smallest subnormal, eight times
+                xs = mfma_small<BF>(xa, tiny, first ? zero4 : xs);
+#pragma unroll
+                for (int t2 = 0; t2 < 2; t2++) {
+#pragma unroll
+                    for (int yb = 0; yb < 4; yb++) {
+                        u32x4 pr;
+#pragma unroll
+                        for (int q = 0; q < 4; q++) {    // rows 2 q and 2 q + 1 sit in words (t2) and (2 + t2) of stage vector q
+                            const uint32_t r0 = sg.w[q][t2], r1 = sg.w[q][2 + t2];
+                            pr[q] = yb == 0 ? pair_bytes<0>(r0, r1) : yb == 1 ? pair_bytes<1>(r0, r1)
+                                  : yb == 2 ? pair_bytes<2>(r0, r1) : pair_bytes<3>(r0, r1);
+                        }
+                        const int j = 4 * t2 + yb;
+                        gacc[j] = mfma_small<BF>(xa, bit_cast<half8_t>(pr), first ? zero4 : gacc[j]);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // the group's sums go into the running results
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint32_t sw = gs.sc[j >> 1];
+                const float sj = (float)bit_cast<half_t>((uint16_t)((j & 1) ? sw >> 16 : sw & 0xFFFFu));
+                const float cj = sj * (float)((gs.zq[j >> 2] >> (8 * (j & 3))) & 0xFFu);
+#pragma unroll
+                for (int r = 0; r < RL; r++)
+                    yr[j][r] = __builtin_fmaf(-cj, xs[r], __builtin_fmaf(sj, gacc[j][r], yr[j][r]));
+            }
+        }
+        constexpr float kOut2 = BF ? 0x1p69f : 0x1p24f;  // the codes' weight comes out
+        if constexpr (RL == 1) {
+            // lane (c, b) holds row b of column j: the four lanes of a column make up its vector
+            float* const yf = reinterpret_cast<float*>(yl);
+#pragma unroll
+            for (int j = 0; j < 8; j++) yf[((wave * 64 + c) * 8 + (j ^ (c & 7))) * 4 + b] = yr[j][0] * kOut2;
+        } else if (b < t.nb) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                f32x4 v;
+#pragma unroll
+                for (int r = 0; r < RL; r++) v[r] = yr[j][r] * kOut2;
+                yl[(wave * 64 + lane) * 8 + (j ^ (c & 7))] = v;
+            }
+        }
+        __syncthreads();
+        for (int id = tid; id < nvec; id += kSmWaves * 64) sink(id, vec_sum(id));
+    };
+
+    finish_over_splits(t, S, p, nvec, base, &fresh_word, run_pass, begin_pass, vec_store_y);
+}
+
+// ------------------------------------------------------------------------------------------------
 // 17 <= M <= 64, in slices of at most 32 rows = two MFMA tiles.  Wave (kh, ch) = (wave >> 1, wave & 1)
 // takes half kh of the workgroup's quantization groups and columns n0 + 128 ch ..; lane (c, b) the 8
 // columns 8 c .. of those = one packed word per row.  With this many rows the loop is bound by the
@@ -1217,6 +1406,10 @@ hipError_t launch_small_with(Kernel kernel, int waves, const SmallArgs& a, hipSt
 template <bool BF>
 hipError_t launch_small_m(const SmallArgs& a, hipStream_t st)
 {
+    if (a.w8) {
+        if (a.M <= 4) return launch_small_with(decode_small8_kernel<1, BF>, kSmWaves, a, st);
+        return launch_small_with(decode_small8_kernel<4, BF>, kSmWaves, a, st);
+    }
     if (a.dense) {
         if (a.M <= 16) return launch_small_with(decode_dense_kernel<1, BF>, kSmWaves, a, st);
         return launch_small_with(decode_dense_kernel<2, BF>, kSmWaves, a, st);
@@ -1244,6 +1437,7 @@ hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st)
     if (a.wide && !a.native) return hipErrorInvalidValue;
     if (a.S > 1 && a.tiles * (a.M > 32 ? 2 : 1) > 256) return hipErrorInvalidValue;     // flags for 256 (tile, slice) pairs
     if (a.dense && a.native) return hipErrorInvalidValue;
+    if (a.w8 && (a.dense || a.native || a.wide || a.M > 16)) return hipErrorInvalidValue;
     return a.bf ? launch_small_m<true>(a, st) : launch_small_m<false>(a, st);
 }
 

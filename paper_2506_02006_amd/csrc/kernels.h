@@ -90,6 +90,7 @@ struct SmallArgs {
     int         native;    // w is in the native storage order (fp16 activations only)
     int         dense;     // w is a 16-bit matrix (fp16, or bfloat16 with bf): no scales, no zero points
     int         wide;      // native order: the eight-wave kernel (DecodePlan::wide)
+    int         w8;        // w is the 8-bit record's code array (uint32 [K,N/4], zero points a byte each): at most 16 rows, column tiles of 128
 };
 hipError_t launch_decode_small(const SmallArgs& a, hipStream_t st);
 
